@@ -1,0 +1,318 @@
+"""Pins for the CPU oracles (NumPy and plain C).  CPU only.
+
+Each test ties the oracle to something that is not the oracle: a library
+routine (dense attention, sort, argpartition), a closed form, brute force on
+tiny inputs or an invariant of the definition.
+"""
+import itertools
+import math
+import os
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import c_oracle
+from oracle import topk_attention_ref as ref
+from paper_2502_06766_amd import workloads as wl
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+
+
+def _rand(Hq, Hkv, N, d, seed, dtype=wl.F32):
+    g = np.random.default_rng(seed)
+    q = g.standard_normal((Hq, d)).astype(np.float32)
+    K = g.standard_normal((Hkv, N, d)).astype(np.float32)
+    V = g.standard_normal((Hkv, N, d)).astype(np.float32)
+    qs, Ks, Vs = wl.quantize(q, dtype), wl.quantize(K, dtype), wl.quantize(V, dtype)
+    return (qs, Ks, Vs), (wl.widen(qs, dtype), wl.widen(Ks, dtype), wl.widen(Vs, dtype))
+
+
+def _dense_library(q, K, V):
+    """Eq. 1 through torch's scaled_dot_product_attention (float64, CPU), with the
+    library's own GQA convention (query head h -> KV head h // G)."""
+    Hq, d = q.shape
+    Hkv = K.shape[0]
+    G = Hq // Hkv
+    qt = torch.from_numpy(q)[None, :, None, :]
+    Kt = torch.from_numpy(K).repeat_interleave(G, dim=0)[None]
+    Vt = torch.from_numpy(V).repeat_interleave(G, dim=0)[None]
+    o = torch.nn.functional.scaled_dot_product_attention(qt, Kt, Vt)
+    return o[0, :, 0, :].numpy()
+
+
+# ---------------------------------------------------------------- k = N is Eq. 1
+@pytest.mark.parametrize("Hq,Hkv,N,d", [(1, 1, 37, 8), (4, 2, 129, 16), (8, 2, 300, 64)])
+def test_k_equals_n_is_dense_attention_numpy(Hq, Hkv, N, d):
+    _, (q, K, V) = _rand(Hq, Hkv, N, d, 1)
+    out, idx, vals, lse = ref.topk_attention(q, K, V, N)
+    np.testing.assert_allclose(out, _dense_library(q, K, V), rtol=1e-12, atol=1e-13)
+    for h in range(Hq):
+        assert sorted(idx[h].tolist()) == list(range(N))
+    # lse against the library's logsumexp
+    G = Hq // Hkv
+    for h in range(Hq):
+        z = torch.from_numpy(K[h // G] @ q[h]) / math.sqrt(d)
+        assert abs(lse[h] - float(torch.logsumexp(z, 0))) < 1e-12
+
+
+@pytest.mark.parametrize("dtype", [wl.F32, wl.F16, wl.BF16])
+def test_k_equals_n_is_dense_attention_c(dtype):
+    (qs, Ks, Vs), (q, K, V) = _rand(8, 2, 257, 32, 2, dtype)
+    out, idx, vals, lse = c_oracle.topk_attention(qs, Ks, Vs, dtype, 257)
+    np.testing.assert_allclose(out, _dense_library(q, K, V), rtol=1e-12, atol=1e-13)
+    # k > N pads and changes nothing else
+    out2, idx2, vals2, _ = c_oracle.topk_attention(qs, Ks, Vs, dtype, 300)
+    np.testing.assert_allclose(out2, out, rtol=0, atol=0)
+    assert (idx2[:, 257:] == -1).all() and np.isneginf(vals2[:, 257:]).all()
+    assert (idx2[:, :257] == idx).all()
+
+
+# ---------------------------------------------------------------- closed form
+def test_closed_form_log_scores():
+    """d = 4 so sqrt(d) = 2; q = (2,0,0,0) and key i = (ln(i+1),0,0,0) give scaled
+    scores ln(i+1), i.e. softmax weights proportional to i+1.  With N = 5, k = 3
+    the selected positions are {4,3,2} with weights 5/12, 4/12, 3/12 and
+    lse = ln 12; vals are the raw scores 2 ln(i+1)."""
+    N, d, k = 5, 4, 3
+    q = np.array([[2.0, 0, 0, 0]])
+    K = np.zeros((1, N, d))
+    K[0, :, 0] = np.log(np.arange(1, N + 1))
+    V = np.arange(N * d, dtype=np.float64).reshape(1, N, d) ** 1.5
+    want = (5 * V[0, 4] + 4 * V[0, 3] + 3 * V[0, 2]) / 12.0
+    out, idx, vals, lse = ref.topk_attention(q, K, V, k)
+    np.testing.assert_allclose(out[0], want, rtol=1e-13)
+    assert idx[0].tolist() == [4, 3, 2]
+    np.testing.assert_allclose(vals[0], 2 * np.log([5, 4, 3]), rtol=1e-14)
+    assert abs(lse[0] - math.log(12.0)) < 1e-13
+    # same case through the C oracle (fp32 storage: compare against the rounded inputs)
+    qs, Ks, Vs = (a.astype(np.float32) for a in (q, K, V))
+    out_c, idx_c, vals_c, lse_c = c_oracle.topk_attention(qs, Ks, Vs, wl.F32, k)
+    w = np.exp(Ks[0, [4, 3, 2], 0].astype(np.float64))   # exp(ln(i+1)) up to fp32 rounding
+    want_c = (w[:, None] * Vs[0, [4, 3, 2]].astype(np.float64)).sum(0) / w.sum()
+    np.testing.assert_allclose(out_c[0], want_c, rtol=1e-13)
+    assert idx_c[0].tolist() == [4, 3, 2]
+    assert abs(lse_c[0] - math.log(12.0)) < 1e-6
+
+
+# ---------------------------------------------------------------- brute force
+@pytest.mark.parametrize("seed", range(6))
+def test_bruteforce_subsets_tiny(seed):
+    """For tie-free scores the top-k set is the unique k-subset with the largest
+    score sum; the output is the explicit softmax-weighted sum over it."""
+    g = np.random.default_rng(seed)
+    N, d, k = int(g.integers(5, 12)), 4, int(g.integers(1, 5))
+    (qs, Ks, Vs), (q, K, V) = _rand(2, 1, N, d, 100 + seed)
+    S = [[sum(q[h, c] * K[0, i, c] for c in range(d)) for i in range(N)] for h in range(2)]
+    out, idx, vals, lse = ref.topk_attention(q, K, V, k)
+    out_c, idx_c, vals_c, _ = c_oracle.topk_attention(qs, Ks, Vs, wl.F32, k)
+    for h in range(2):
+        best = max(itertools.combinations(range(N), k), key=lambda I: sum(S[h][i] for i in I))
+        assert set(idx[h].tolist()) == set(best)
+        assert set(idx_c[h].tolist()) == set(best)
+        mx = max(S[h][i] for i in best)
+        w = {i: math.exp((S[h][i] - mx) / math.sqrt(d)) for i in best}
+        Z = sum(w.values())
+        want = [sum(w[i] / Z * V[0, i, c] for i in best) for c in range(d)]
+        np.testing.assert_allclose(out[h], want, rtol=1e-12, atol=1e-14)
+        np.testing.assert_allclose(out_c[h], want, rtol=1e-12, atol=1e-14)
+        np.testing.assert_allclose(sorted(vals[h]), sorted(S[h][i] for i in best), rtol=1e-13)
+
+
+# ---------------------------------------------------------------- library selection
+@pytest.mark.parametrize("N,k", [(1000, 1), (1000, 17), (5000, 500), (4096, 4096)])
+def test_selection_matches_library_partition(N, k):
+    (qs, Ks, Vs), (q, K, V) = _rand(4, 2, N, 16, 7)
+    S = ref.scores(q, K)
+    _, idx, vals, _ = ref.topk_attention(q, K, V, k)
+    _, idx_c, vals_c, _ = c_oracle.topk_attention(qs, Ks, Vs, wl.F32, k)
+    for h in range(4):
+        part = np.argpartition(-S[h], k - 1)[:k] if k < N else np.arange(N)
+        assert set(idx[h].tolist()) == set(part.tolist())
+        assert set(idx_c[h].tolist()) == set(part.tolist())
+        np.testing.assert_array_equal(vals[h], np.sort(S[h])[::-1][:k])
+        np.testing.assert_allclose(vals_c[h], vals[h], rtol=1e-13, atol=1e-13)
+        rest = np.setdiff1d(np.arange(N), idx[h])
+        if rest.size:
+            assert vals[h].min() >= S[h][rest].max()
+        # vals are the raw dot products of the selected keys (unscaled)
+        np.testing.assert_allclose(vals[h], K[h // 2][idx[h]] @ q[h], rtol=1e-13)
+
+
+def test_scores_orientation_and_gqa_mapping():
+    """scores[h, i] = q_h . K[h // G, i]: check against an explicit einsum per KV
+    head with distinct caches per head (catches transposed or mis-grouped heads)."""
+    (qs, Ks, _), (q, K, _) = _rand(6, 3, 50, 8, 3)
+    want = np.einsum("hgd,hnd->hgn", q.reshape(3, 2, 8), K).reshape(6, 50)
+    np.testing.assert_allclose(ref.scores(q, K), want, rtol=1e-13)
+    np.testing.assert_allclose(c_oracle.scores(qs, Ks, wl.F32), want, rtol=1e-13)
+
+
+# ---------------------------------------------------------------- special cases
+def test_k1_returns_argmax_value_row():
+    (qs, Ks, Vs), (q, K, V) = _rand(4, 2, 333, 16, 11)
+    out, idx, _, lse = ref.topk_attention(q, K, V, 1)
+    out_c, idx_c, _, _ = c_oracle.topk_attention(qs, Ks, Vs, wl.F32, 1)
+    for h in range(4):
+        i = int(np.argmax(K[h // 2] @ q[h]))
+        assert idx[h, 0] == i and idx_c[h, 0] == i
+        np.testing.assert_array_equal(out[h], V[h // 2, i])
+        np.testing.assert_array_equal(out_c[h], V[h // 2, i])
+        assert abs(lse[h] - (K[h // 2, i] @ q[h]) / 4.0) < 1e-13
+
+
+def test_identical_keys_tie_rule_and_mean():
+    """All scores equal: lowest positions win and the output is their mean."""
+    N, d, k = 40, 8, 7
+    g = np.random.default_rng(5)
+    q = g.standard_normal((1, d))
+    K = np.tile(g.standard_normal((1, 1, d)), (1, N, 1))
+    V = g.standard_normal((1, N, d))
+    out, idx, _, _ = ref.topk_attention(q, K, V, k)
+    assert idx[0].tolist() == list(range(k))
+    np.testing.assert_allclose(out[0], V[0, :k].mean(0), rtol=1e-13)
+    f = lambda a: a.astype(np.float32)
+    out_c, idx_c, _, _ = c_oracle.topk_attention(f(q), f(K), f(V), wl.F32, k)
+    assert idx_c[0].tolist() == list(range(k))
+    np.testing.assert_allclose(out_c[0], f(V)[0, :k].astype(np.float64).mean(0), rtol=1e-13)
+
+
+def test_duplicate_key_pairs_tie_rule():
+    """Key j+N/2 duplicates key j: when only one of a pair fits, the lower position wins."""
+    (_, _, _), (q, K, V) = _rand(1, 1, 64, 8, 21)
+    K[0, 32:] = K[0, :32]
+    for k in (1, 3, 9):
+        _, idx, _, _ = ref.topk_attention(q, K, V, k)
+        order = np.argsort(-(K[0, :32] @ q[0]), kind="stable")
+        want = []
+        for j in order:
+            want += [int(j), int(j) + 32]
+        assert idx[0].tolist() == want[:k]
+
+
+def test_score_shift_and_query_scale_invariance():
+    (_, _, _), (q, K, V) = _rand(2, 1, 400, 16, 31)
+    out, idx, vals, _ = ref.topk_attention(q[:1], K, V, 25)
+    # adding c q/|q|^2 to every key shifts every score by c: same set, same output
+    c = 3.25
+    K2 = K + c * q[0] / (q[0] @ q[0])
+    out2, idx2, vals2, _ = ref.topk_attention(q[:1], K2, V, 25)
+    assert idx2[0].tolist() == idx[0].tolist()
+    np.testing.assert_allclose(vals2[0], vals[0] + c, rtol=1e-12)
+    np.testing.assert_allclose(out2, out, rtol=1e-10)
+    # scaling the query by a > 0 keeps the selected set (the metric is the raw dot product)
+    _, idx3, vals3, _ = ref.topk_attention(2.5 * q[:1], K, V, 25)
+    assert idx3[0].tolist() == idx[0].tolist()
+    np.testing.assert_allclose(vals3[0], 2.5 * vals[0], rtol=1e-13)
+
+
+def test_permutation_invariance():
+    (_, _, _), (q, K, V) = _rand(4, 2, 500, 16, 41)
+    out, idx, _, _ = ref.topk_attention(q, K, V, 33)
+    perm = np.random.default_rng(0).permutation(500)     # new position j holds old row perm[j]
+    out_p, idx_p, _, _ = ref.topk_attention(q, K[:, perm], V[:, perm], 33)
+    np.testing.assert_allclose(out_p, out, rtol=1e-11, atol=1e-13)
+    for h in range(4):
+        assert set(perm[idx_p[h]].tolist()) == set(idx[h].tolist())
+
+
+def test_planted_dominant_keys_are_selected():
+    w = wl.C1
+    q, K, V = wl.make_cache(w, seed=0)
+    q, K, V = q.astype(np.float64), K.astype(np.float64), V.astype(np.float64)
+    S = ref.scores(q, K)[0]
+    g = np.random.default_rng(9)
+    planted = g.choice(w.n_tokens, size=5, replace=False)
+    # rescale each planted row so its score is 1.5x the largest other score
+    top_other = np.delete(S, planted).max()
+    for p in planted:
+        K[0, p] = q[0] * (1.5 * top_other / (q[0] @ q[0]))
+    _, idx, _, _ = ref.topk_attention(q, K, V, 5)
+    assert set(idx[0].tolist()) == set(planted.tolist())
+    _, idx, _, _ = ref.topk_attention(q, K, V, 64)
+    assert set(planted.tolist()) <= set(idx[0].tolist())
+
+
+def test_weights_sum_to_one_and_convex_hull():
+    (_, _, _), (q, K, V) = _rand(2, 2, 300, 8, 51)
+    out, idx, vals, lse = ref.topk_attention(q, K, V, 20)
+    for h in range(2):
+        rows = V[h][idx[h]]
+        assert (out[h] <= rows.max(0) + 1e-12).all() and (out[h] >= rows.min(0) - 1e-12).all()
+        p = np.exp(vals[h] / math.sqrt(8) - lse[h])
+        assert abs(p.sum() - 1.0) < 1e-12
+        np.testing.assert_allclose(out[h], p @ rows, rtol=1e-12)
+
+
+def test_truncation_error_bound():
+    """|out_topk - out_dense|_inf <= 2 (1 - m) max|V| with m the dense mass captured."""
+    w = wl.C5.scaled(8192, k=164, n_layers=1)
+    qs, Ks, Vs = wl.make_quantized(w, seed=3)
+    q, K, V = (wl.widen(a, w.dtype) for a in (qs, Ks, Vs))
+    out, idx, _, _ = ref.topk_attention(q, K, V, w.k)
+    dense = _dense_library(q, K, V)
+    S = ref.scores(q, K)
+    masses = []
+    for h in range(w.n_q_heads):
+        m = ref.captured_mass(S[h], idx[h], w.head_dim)
+        masses.append(m)
+        bound = 2 * (1 - m) * np.abs(V[h // w.group]).max()
+        assert np.abs(out[h] - dense[h]).max() <= bound + 1e-12
+    # the score-shaped recipe concentrates ~95 % of the dense mass on the top 2 %
+    assert 0.85 < float(np.mean(masses)) < 0.99
+    ent = np.mean([ref.attention_entropy(S[h], w.head_dim) for h in range(w.n_q_heads)])
+    assert ent < math.log(w.n_tokens)
+
+
+def test_entropy_uniform_is_log_n():
+    assert abs(ref.attention_entropy(np.full(1000, 0.37), 64) - math.log(1000)) < 1e-12
+    assert ref.attention_entropy(np.array([0.0, 1000.0, 0.0]), 1) < 1e-12
+
+
+# ---------------------------------------------------------------- C vs NumPy, dtypes
+@pytest.mark.parametrize("dtype", [wl.F32, wl.F16, wl.BF16])
+@pytest.mark.parametrize("Hq,Hkv,N,d,k", [(4, 1, 700, 64, 50), (8, 2, 1025, 128, 128), (2, 2, 64, 8, 64)])
+def test_c_oracle_matches_numpy_oracle(dtype, Hq, Hkv, N, d, k):
+    (qs, Ks, Vs), (q, K, V) = _rand(Hq, Hkv, N, d, 61, dtype)
+    out, idx, vals, lse = ref.topk_attention(q, K, V, k)
+    out_c, idx_c, vals_c, lse_c = c_oracle.topk_attention(qs, Ks, Vs, dtype, k)
+    np.testing.assert_array_equal(idx_c, idx)
+    np.testing.assert_allclose(vals_c, vals, rtol=1e-13, atol=1e-13)
+    np.testing.assert_allclose(out_c, out, rtol=1e-11, atol=1e-13)
+    np.testing.assert_allclose(lse_c, lse, rtol=1e-13)
+    np.testing.assert_allclose(c_oracle.scores(qs, Ks, dtype), ref.scores(q, K), rtol=1e-13, atol=1e-13)
+
+
+@pytest.mark.parametrize("dtype", [wl.F16, wl.BF16])
+def test_c_oracle_widens_every_16bit_pattern_exactly(dtype):
+    """q = [1], one key per finite 16-bit pattern: scores must be the stored values."""
+    bits = np.arange(65536, dtype=np.uint16)
+    if dtype == wl.F16:
+        vals = bits.view(np.float16).astype(np.float64)
+        K = bits.view(np.float16)[None, :, None]
+        q = np.array([[1.0]], dtype=np.float16)
+    else:
+        vals = torch.from_numpy(bits.view(np.int16)).view(torch.bfloat16).to(torch.float64).numpy()
+        K = bits[None, :, None]
+        q = wl.to_bf16_bits(np.array([[1.0]], dtype=np.float32))
+    S = c_oracle.scores(q, np.ascontiguousarray(K), dtype)[0]
+    fin = np.isfinite(vals)
+    np.testing.assert_array_equal(S[fin], vals[fin])
+
+
+def test_bf16_rounding_matches_library():
+    x = np.random.default_rng(0).standard_normal(100000).astype(np.float32) * 37.0
+    lib = torch.from_numpy(x).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)
+    np.testing.assert_array_equal(wl.to_bf16_bits(x), lib)
+    np.testing.assert_array_equal(wl.bf16_bits_to_f32(lib),
+                                  torch.from_numpy(x).to(torch.bfloat16).to(torch.float32).numpy())
+
+
+# ---------------------------------------------------------------- sizes the paper prints
+def test_kv_cache_sizes_printed_in_paper():
+    for line in open(os.path.join(GOLDEN, "kv_cache_sizes.txt")):
+        if line.startswith("#") or not line.strip():
+            continue
+        n, hidden, layers, bpe, gb = line.split()
+        got = wl.kv_cache_bytes(int(n), int(hidden), int(layers), int(bpe)) / 1e9
+        assert abs(got - float(gb)) / float(gb) < 0.03, (line, got)
