@@ -1,0 +1,147 @@
+/*
+ * topk_attn.h -- C ABI of the MI355X (gfx950) top-k attention decode library.
+ *
+ * The library implements one operator: the per-step "top-k attention" decode of
+ * arXiv 2502.06766 (Methodology, "Top-k Attention: Accelerating Decoding", and
+ * Algorithm 1 "Top-k KV Cache Decoding") in its exact-search form, with the whole
+ * KV cache resident in GPU memory.  For every query head it
+ *   1. scores the query against all N cached keys of its KV head with the raw dot
+ *      product (the paper's search metric; S = q K^T of Eq. 1),
+ *   2. finds the k largest scores `vals` and their positions `I`
+ *      (Algorithm 1's  vals, I <- knn_search(q, K_index[l], k)),
+ *   3. returns Softmax(vals / sqrt(head_dim)) . V[I]  (Algorithm 1's attention
+ *      step over the retrieved rows).
+ * With grouped-query attention, query head h reads KV head h / (n_q_heads /
+ * n_kv_heads); every query head selects its own k positions.
+ *
+ * All pointers named "device" are GPU addresses on the configured device; the
+ * library never allocates or frees device memory, never synchronises the device
+ * in append/decode, and never touches host copies of the cache.  Calls on one
+ * handle must not overlap in time (no internal locking).  Every function returns
+ * a TOPK_ATTN_* code; argument errors are detected on the host before anything
+ * is enqueued and leave the handle unchanged.
+ */
+#ifndef TOPK_ATTN_H
+#define TOPK_ATTN_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct topk_attn topk_attn_t; /* opaque, host memory owned by the library */
+
+enum {
+    TOPK_ATTN_OK = 0,
+    TOPK_ATTN_EINVAL = 1,       /* null pointer, index out of range, k < 1, empty cache ... */
+    TOPK_ATTN_ECAPACITY = 2,    /* append would exceed max_tokens */
+    TOPK_ATTN_EUNSUPPORTED = 3, /* head_dim / dtype / head grouping the kernels do not cover */
+    TOPK_ATTN_EDEVICE = 4,      /* a HIP call failed */
+    TOPK_ATTN_ENOMEM = 5        /* host allocation failed, or a caller buffer is too small */
+};
+
+enum { TOPK_ATTN_F32 = 0, TOPK_ATTN_F16 = 1, TOPK_ATTN_BF16 = 2 }; /* element type of q, K, V */
+
+/* Which selection pipeline decode uses (see topk_attn_set_path). */
+enum {
+    TOPK_ATTN_PATH_AUTO = 0,    /* filtered scan when the shape allows it, else full */
+    TOPK_ATTN_PATH_FULL = 1,    /* always materialise all N scores and radix-select over them */
+    TOPK_ATTN_PATH_FILTER = 2   /* sampled-threshold scan whenever its candidate list fits the
+                                   workspace, also for short caches (the full path still redoes
+                                   heads whose candidate list under- or overflows) */
+};
+
+typedef struct {
+    uint32_t struct_size;   /* sizeof(topk_attn_config), for ABI versioning */
+    int32_t n_layers;       /* L: independent caches, one per transformer layer */
+    int32_t n_seqs;         /* B: sequences decoded together in one call */
+    int32_t n_q_heads;      /* Hq */
+    int32_t n_kv_heads;     /* Hkv, must divide Hq; Hq/Hkv <= 16 */
+    int32_t head_dim;       /* d in {32, 64, 128, 256} */
+    int64_t max_tokens;     /* capacity N_cap per (layer, sequence) */
+    int32_t max_k;          /* largest k decode will be called with; sizes the workspace */
+    int32_t dtype;          /* TOPK_ATTN_F32 / F16 / BF16 for q, K and V alike */
+    int32_t device;         /* HIP device ordinal */
+    int32_t reserved;
+    void* kv_storage;       /* device, >= topk_attn_kv_bytes(), 256-byte aligned, caller-owned */
+    size_t kv_bytes;
+    void* workspace;        /* device, >= topk_attn_workspace_bytes(), 256-byte aligned, caller-owned */
+    size_t workspace_bytes;
+} topk_attn_config;
+
+/* Bytes of cache storage for the configuration: K then V, each laid out
+ * [layer][seq][kv_head][max_tokens][head_dim] in `dtype` (2 L B Hkv N_cap d e bytes;
+ * the paper's 2NDL cache of the Introduction with D = Hkv*d).  0 on invalid config. */
+size_t topk_attn_kv_bytes(const topk_attn_config* cfg);
+
+/* Bytes of scratch the kernels need (score buffer, candidate lists, partial sums,
+ * per-sequence lengths).  0 on invalid config. */
+size_t topk_attn_workspace_bytes(const topk_attn_config* cfg);
+
+/* Build a handle over caller-owned storage (Algorithm 1's build_index for the exact
+ * "list" index: the head-major key array itself is the index).  Zeroes the lengths
+ * (synchronously).  The storage must stay valid until topk_attn_destroy. */
+int topk_attn_create(const topk_attn_config* cfg, topk_attn_t** out);
+
+/* Append n_new tokens to the cache of (layer, seq): Algorithm 1's concat of the new
+ * k, v (and, with a large n_new, the bulk import of a prefilled cache).
+ * k_new / v_new: device, element (t, h, c) at  base[t*token_stride + h*head_stride + c],
+ * strides in elements (token-major [n_new, Hkv, d]: token_stride = Hkv*d, head_stride = d;
+ * head-major [Hkv, n_new, d]: token_stride = d, head_stride = n_new*d).  Rows must be
+ * 16-byte aligned.  The data is copied on `hip_stream` (a hipStream_t, may be NULL for
+ * the default stream); the source may be reused once the stream has passed the call.
+ * Errors: EINVAL (null, range, n_new < 0, misaligned), ECAPACITY. n_new == 0 is a no-op. */
+int topk_attn_append_kv(topk_attn_t* h, int layer, int seq, const void* k_new, const void* v_new,
+                        int64_t n_new, int64_t token_stride, int64_t head_stride, void* hip_stream);
+
+/* One decode step of `layer` for all B sequences: steps 1-3 above over all tokens
+ * currently cached for (layer, b).  k_eff = min(k, N_b).
+ *   q     device [B, Hq, d] in the cache dtype
+ *   out   device [B, Hq, d] fp32
+ *   idx   device [B, Hq, k] int32 or NULL: selected positions, in no particular order;
+ *         slots >= k_eff hold -1
+ *   vals  device [B, Hq, k] fp32 or NULL: raw (unscaled) scores q.K[idx]; slots >= k_eff
+ *         hold -inf
+ *   lse   device [B, Hq] fp32 or NULL: log-sum-exp of vals/sqrt(d) over the selection
+ *         (lets a caller merge with attention over further keys, e.g. a recent window)
+ * Ties between equal scores go to the lower position.  Scores are accumulated in fp32.
+ * Asynchronous on `hip_stream`.  Errors: EINVAL (null h/q/out, layer range, k < 1,
+ * k > max_k, a sequence with no tokens), EDEVICE. */
+int topk_attn_decode(topk_attn_t* h, int layer, const void* q, int k, float* out, int32_t* idx,
+                     float* vals, float* lse, void* hip_stream);
+
+/* Debug/measurement: write the full fp32 score matrix S = q K^T of `layer`
+ * to scores [B, Hq, max_tokens] (device); entries beyond a sequence's length are
+ * left untouched. */
+int topk_attn_scores(topk_attn_t* h, int layer, const void* q, float* scores, void* hip_stream);
+
+/* Tokens currently cached for (layer, seq); -1 on bad arguments. */
+int64_t topk_attn_length(const topk_attn_t* h, int layer, int seq);
+
+/* Forget the tokens of (layer, seq) (length := 0); enqueued on hip_stream. */
+int topk_attn_reset(topk_attn_t* h, int layer, int seq, void* hip_stream);
+
+/* Choose the selection pipeline (TOPK_ATTN_PATH_*); default AUTO. */
+int topk_attn_set_path(topk_attn_t* h, int path);
+
+/* After the stream has been synchronised by the caller: number of (sequence, head)
+ * pairs of the last decode whose filtered candidate list was unusable and were
+ * recomputed by the full path.  Copies a few bytes device->host (synchronous). */
+int topk_attn_last_fallbacks(topk_attn_t* h, int* n_heads);
+
+/* Measurement aid: stream `bytes` (multiple of 16) from `src` (device) with 128-bit
+ * loads and write one checksum word per workgroup to `sink` (device, >= 64 KiB).
+ * Gives the read-bandwidth ceiling the key scan is compared against. */
+int topk_attn_read_probe(const void* src, size_t bytes, void* sink, void* hip_stream);
+
+const char* topk_attn_strerror(int code);
+
+/* Frees the host handle only. */
+int topk_attn_destroy(topk_attn_t* h);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* TOPK_ATTN_H */

@@ -1,0 +1,352 @@
+// Host side of libtopk_attn: handle, argument checks, workspace layout, launches.
+#include <hip/hip_runtime.h>
+#include <math.h>
+#include <stdlib.h>
+#include <string.h>
+
+#include <new>
+#include <vector>
+
+#include "../../include/topk_attn.h"
+#include "device_utils.h"
+#include "internal.h"
+
+using namespace tka;
+
+namespace {
+
+constexpr size_t kAlign = 256;
+inline size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
+inline int elem_bytes(int dtype) { return dtype == TOPK_ATTN_F32 ? 4 : 2; }
+
+struct WsLayout {
+    size_t len, thr, samp, cand_cnt, flags, hmax, fallback, cand, scores, sel_idx, sel_val, part_acc, part_l, total;
+    int cand_cap, n_chunk_cap;
+};
+
+bool config_ok(const topk_attn_config* c, int* why) {
+    *why = TOPK_ATTN_EINVAL;
+    if (!c || c->struct_size != sizeof(topk_attn_config)) return false;
+    if (c->n_layers < 1 || c->n_seqs < 1 || c->n_q_heads < 1 || c->n_kv_heads < 1) return false;
+    if (c->max_tokens < 1 || c->max_k < 1 || c->device < 0) return false;
+    if (c->max_tokens > (int64_t)0x7FFFFF00) return false;   // positions are int32
+    if (c->n_seqs > 65535 || c->n_kv_heads > 65535) return false;
+    *why = TOPK_ATTN_EUNSUPPORTED;
+    if (c->dtype != TOPK_ATTN_F32 && c->dtype != TOPK_ATTN_F16 && c->dtype != TOPK_ATTN_BF16) return false;
+    if (c->head_dim != 32 && c->head_dim != 64 && c->head_dim != 128 && c->head_dim != 256) return false;
+    if (c->n_q_heads % c->n_kv_heads) return false;
+    if (c->n_q_heads / c->n_kv_heads > 16) return false;
+    *why = TOPK_ATTN_OK;
+    return true;
+}
+
+size_t kv_half_bytes(const topk_attn_config* c) {
+    return align_up((size_t)c->n_layers * c->n_seqs * c->n_kv_heads * (size_t)c->max_tokens * c->head_dim *
+                    elem_bytes(c->dtype));
+}
+
+WsLayout ws_layout(const topk_attn_config* c) {
+    WsLayout w;
+    const size_t BH = (size_t)c->n_seqs * c->n_q_heads;
+    const int64_t max_k = c->max_k < c->max_tokens ? c->max_k : c->max_tokens;
+    w.cand_cap = (int)(4 * max_k + 16384);
+    w.n_chunk_cap = (int)((max_k + kGatherRows - 1) / kGatherRows);
+    size_t o = 0;
+    auto take = [&](size_t bytes) { size_t at = o; o = align_up(o + bytes); return at; };
+    w.len = take((size_t)c->n_layers * c->n_seqs * sizeof(int32_t));
+    w.thr = take(BH * sizeof(float));
+    w.samp = take(BH * kSampMax * sizeof(float));
+    w.cand_cnt = take(BH * sizeof(uint32_t));
+    w.flags = take(BH * sizeof(uint32_t));
+    w.hmax = take(BH * sizeof(float));
+    w.fallback = take(sizeof(uint32_t));
+    w.cand = take(BH * (size_t)w.cand_cap * sizeof(uint64_t));
+    w.scores = take(BH * (size_t)c->max_tokens * sizeof(float));
+    w.sel_idx = take(BH * (size_t)c->max_k * sizeof(int32_t));   // stride is the requested k, up to max_k
+    w.sel_val = take(BH * (size_t)c->max_k * sizeof(float));
+    w.part_acc = take(BH * (size_t)w.n_chunk_cap * c->head_dim * sizeof(float));
+    w.part_l = take(BH * (size_t)w.n_chunk_cap * sizeof(float));
+    w.total = o;
+    return w;
+}
+
+__global__ void append_kernel(const char* __restrict__ ksrc, const char* __restrict__ vsrc, char* __restrict__ kdst,
+                              char* __restrict__ vdst, int64_t n_new, int Hkv, int chunks_per_row,
+                              int64_t token_stride_b, int64_t head_stride_b, int64_t dst_head_stride_b,
+                              int32_t* len_slot, int32_t new_len) {
+    const int64_t total = n_new * Hkv * chunks_per_row;
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < total;
+         i += (int64_t)gridDim.x * blockDim.x) {
+        const int c = (int)(i % chunks_per_row);
+        const int64_t th = i / chunks_per_row;
+        const int h = (int)(th % Hkv);
+        const int64_t t = th / Hkv;
+        const int64_t so = t * token_stride_b + h * head_stride_b + (int64_t)c * 16;
+        const int64_t d_o = h * dst_head_stride_b + (t * chunks_per_row + c) * 16;
+        *reinterpret_cast<u32x4*>(kdst + d_o) = *reinterpret_cast<const u32x4*>(ksrc + so);
+        *reinterpret_cast<u32x4*>(vdst + d_o) = *reinterpret_cast<const u32x4*>(vsrc + so);
+    }
+    if (blockIdx.x == 0 && threadIdx.x == 0) *len_slot = new_len;
+}
+
+__global__ void set_len_kernel(int32_t* len_slot, int32_t v) { *len_slot = v; }
+
+__global__ void __launch_bounds__(256) read_probe_kernel(const u32x4* __restrict__ src, size_t n_vec, uint32_t* sink) {
+    uint32_t acc = 0;
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    for (; i + 3 * stride < n_vec; i += 4 * stride) {
+        const u32x4 a = src[i], b = src[i + stride], c = src[i + 2 * stride], d = src[i + 3 * stride];
+        acc ^= a.x ^ a.y ^ a.z ^ a.w ^ b.x ^ b.y ^ b.z ^ b.w ^ c.x ^ c.y ^ c.z ^ c.w ^ d.x ^ d.y ^ d.z ^ d.w;
+    }
+    for (; i < n_vec; i += stride) {
+        const u32x4 a = src[i];
+        acc ^= a.x ^ a.y ^ a.z ^ a.w;
+    }
+    for (int o = 32; o > 0; o >>= 1) acc ^= __shfl_xor(acc, o, 64);
+    if ((threadIdx.x & 63) == 0) atomicXor(&sink[blockIdx.x & 16383], acc);
+}
+
+}  // namespace
+
+struct topk_attn {
+    topk_attn_config cfg;
+    WsLayout ws;
+    size_t kv_half;
+    std::vector<int64_t> len;   // host mirror of the device lengths, [L][B]
+    int path;
+    bool last_fast;
+};
+
+extern "C" {
+
+size_t topk_attn_kv_bytes(const topk_attn_config* cfg) {
+    int why;
+    if (!config_ok(cfg, &why)) return 0;
+    return 2 * kv_half_bytes(cfg);
+}
+
+size_t topk_attn_workspace_bytes(const topk_attn_config* cfg) {
+    int why;
+    if (!config_ok(cfg, &why)) return 0;
+    return ws_layout(cfg).total;
+}
+
+int topk_attn_create(const topk_attn_config* cfg, topk_attn_t** out) {
+    if (!out) return TOPK_ATTN_EINVAL;
+    *out = nullptr;
+    int why;
+    if (!config_ok(cfg, &why)) return why;
+    if (!cfg->kv_storage || !cfg->workspace) return TOPK_ATTN_EINVAL;
+    if (((uintptr_t)cfg->kv_storage | (uintptr_t)cfg->workspace) & (kAlign - 1)) return TOPK_ATTN_EINVAL;
+    WsLayout w = ws_layout(cfg);
+    if (cfg->kv_bytes < 2 * kv_half_bytes(cfg) || cfg->workspace_bytes < w.total) return TOPK_ATTN_ENOMEM;
+    topk_attn* h = new (std::nothrow) topk_attn;
+    if (!h) return TOPK_ATTN_ENOMEM;
+    h->cfg = *cfg;
+    h->ws = w;
+    h->kv_half = kv_half_bytes(cfg);
+    h->len.assign((size_t)cfg->n_layers * cfg->n_seqs, 0);
+    h->path = TOPK_ATTN_PATH_AUTO;
+    h->last_fast = false;
+    if (hipSetDevice(cfg->device) != hipSuccess) { delete h; return TOPK_ATTN_EDEVICE; }
+    // lengths and the small per-head control words start at zero
+    if (hipMemset(cfg->workspace, 0, w.cand) != hipSuccess || hipDeviceSynchronize() != hipSuccess) {
+        delete h;
+        return TOPK_ATTN_EDEVICE;
+    }
+    *out = h;
+    return TOPK_ATTN_OK;
+}
+
+int topk_attn_destroy(topk_attn_t* h) {
+    if (!h) return TOPK_ATTN_EINVAL;
+    delete h;
+    return TOPK_ATTN_OK;
+}
+
+int64_t topk_attn_length(const topk_attn_t* h, int layer, int seq) {
+    if (!h || layer < 0 || layer >= h->cfg.n_layers || seq < 0 || seq >= h->cfg.n_seqs) return -1;
+    return h->len[(size_t)layer * h->cfg.n_seqs + seq];
+}
+
+int topk_attn_set_path(topk_attn_t* h, int path) {
+    if (!h || path < TOPK_ATTN_PATH_AUTO || path > TOPK_ATTN_PATH_FILTER) return TOPK_ATTN_EINVAL;
+    h->path = path;
+    return TOPK_ATTN_OK;
+}
+
+int topk_attn_reset(topk_attn_t* h, int layer, int seq, void* hip_stream) {
+    if (!h || layer < 0 || layer >= h->cfg.n_layers || seq < 0 || seq >= h->cfg.n_seqs) return TOPK_ATTN_EINVAL;
+    const size_t slot = (size_t)layer * h->cfg.n_seqs + seq;
+    int32_t* len_dev = reinterpret_cast<int32_t*>(static_cast<char*>(h->cfg.workspace) + h->ws.len) + slot;
+    hipLaunchKernelGGL(set_len_kernel, dim3(1), dim3(1), 0, (hipStream_t)hip_stream, len_dev, 0);
+    if (hipGetLastError() != hipSuccess) return TOPK_ATTN_EDEVICE;
+    h->len[slot] = 0;
+    return TOPK_ATTN_OK;
+}
+
+int topk_attn_append_kv(topk_attn_t* h, int layer, int seq, const void* k_new, const void* v_new, int64_t n_new,
+                        int64_t token_stride, int64_t head_stride, void* hip_stream) {
+    if (!h || layer < 0 || layer >= h->cfg.n_layers || seq < 0 || seq >= h->cfg.n_seqs) return TOPK_ATTN_EINVAL;
+    if (n_new < 0) return TOPK_ATTN_EINVAL;
+    if (n_new == 0) return TOPK_ATTN_OK;
+    if (!k_new || !v_new) return TOPK_ATTN_EINVAL;
+    const topk_attn_config& c = h->cfg;
+    const int e = elem_bytes(c.dtype);
+    if (token_stride < 0 || head_stride < 0) return TOPK_ATTN_EINVAL;
+    if (((uintptr_t)k_new | (uintptr_t)v_new) & 15) return TOPK_ATTN_EINVAL;
+    if (((token_stride * e) | (head_stride * e)) & 15) return TOPK_ATTN_EINVAL;
+    const size_t slot = (size_t)layer * c.n_seqs + seq;
+    const int64_t cur = h->len[slot];
+    if (cur + n_new > c.max_tokens) return TOPK_ATTN_ECAPACITY;
+
+    const int64_t row_b = (int64_t)c.head_dim * e;
+    const int64_t head_b = c.max_tokens * row_b;
+    const int64_t off = ((int64_t)slot * c.n_kv_heads) * head_b + cur * row_b;
+    char* kdst = static_cast<char*>(c.kv_storage) + off;
+    char* vdst = static_cast<char*>(c.kv_storage) + h->kv_half + off;
+    int32_t* len_dev = reinterpret_cast<int32_t*>(static_cast<char*>(c.workspace) + h->ws.len) + slot;
+    const int chunks = (int)(row_b / 16);
+    const int64_t total = n_new * c.n_kv_heads * chunks;
+    int64_t blocks = (total + 255) / 256;
+    if (blocks > 65536) blocks = 65536;
+    hipLaunchKernelGGL(append_kernel, dim3((unsigned)blocks), dim3(256), 0, (hipStream_t)hip_stream,
+                       static_cast<const char*>(k_new), static_cast<const char*>(v_new), kdst, vdst, n_new,
+                       c.n_kv_heads, chunks, token_stride * e, head_stride * e, head_b, len_dev,
+                       (int32_t)(cur + n_new));
+    if (hipGetLastError() != hipSuccess) return TOPK_ATTN_EDEVICE;
+    h->len[slot] = cur + n_new;
+    return TOPK_ATTN_OK;
+}
+
+static void fill_call(topk_attn_t* h, int layer, const void* q, int k, Shape* s, Bufs* b) {
+    const topk_attn_config& c = h->cfg;
+    const int e = elem_bytes(c.dtype);
+    s->B = c.n_seqs; s->Hq = c.n_q_heads; s->Hkv = c.n_kv_heads; s->G = c.n_q_heads / c.n_kv_heads;
+    s->D = c.head_dim; s->dtype = c.dtype; s->k = k; s->max_k = c.max_k;
+    s->cand_cap = h->ws.cand_cap; s->samp_cap = kSampMax; s->n_chunk_cap = h->ws.n_chunk_cap;
+    s->Ncap = c.max_tokens;
+    char* ws = static_cast<char*>(c.workspace);
+    const size_t layer_b = (size_t)c.n_seqs * c.n_kv_heads * (size_t)c.max_tokens * c.head_dim * e;
+    b->K = static_cast<char*>(c.kv_storage) + (size_t)layer * layer_b;
+    b->V = static_cast<char*>(c.kv_storage) + h->kv_half + (size_t)layer * layer_b;
+    b->q = q;
+    b->len = reinterpret_cast<int32_t*>(ws + h->ws.len) + (size_t)layer * c.n_seqs;
+    b->thr = reinterpret_cast<float*>(ws + h->ws.thr);
+    b->samp = reinterpret_cast<float*>(ws + h->ws.samp);
+    b->cand_cnt = reinterpret_cast<uint32_t*>(ws + h->ws.cand_cnt);
+    b->flags = reinterpret_cast<uint32_t*>(ws + h->ws.flags);
+    b->hmax = reinterpret_cast<float*>(ws + h->ws.hmax);
+    b->cand = reinterpret_cast<uint64_t*>(ws + h->ws.cand);
+    b->scores = reinterpret_cast<float*>(ws + h->ws.scores);
+    b->sel_idx = reinterpret_cast<int32_t*>(ws + h->ws.sel_idx);
+    b->sel_val = reinterpret_cast<float*>(ws + h->ws.sel_val);
+    b->part_acc = reinterpret_cast<float*>(ws + h->ws.part_acc);
+    b->part_l = reinterpret_cast<float*>(ws + h->ws.part_l);
+    b->out = nullptr; b->lse = nullptr;
+    b->fallback_total = reinterpret_cast<uint32_t*>(ws + h->ws.fallback);
+}
+
+static int lengths_of(const topk_attn_t* h, int layer, int64_t* nmin, int64_t* nmax) {
+    const int B = h->cfg.n_seqs;
+    int64_t lo = INT64_MAX, hi = 0;
+    for (int b = 0; b < B; ++b) {
+        const int64_t n = h->len[(size_t)layer * B + b];
+        lo = n < lo ? n : lo;
+        hi = n > hi ? n : hi;
+    }
+    *nmin = lo; *nmax = hi;
+    return lo >= 1 ? TOPK_ATTN_OK : TOPK_ATTN_EINVAL;
+}
+
+int topk_attn_decode(topk_attn_t* h, int layer, const void* q, int k, float* out, int32_t* idx, float* vals,
+                     float* lse, void* hip_stream) {
+    if (!h || !q || !out) return TOPK_ATTN_EINVAL;
+    if (layer < 0 || layer >= h->cfg.n_layers) return TOPK_ATTN_EINVAL;
+    if (k < 1 || k > h->cfg.max_k) return TOPK_ATTN_EINVAL;
+    if ((uintptr_t)q & 15) return TOPK_ATTN_EINVAL;
+    int64_t nmin, nmax;
+    if (lengths_of(h, layer, &nmin, &nmax) != TOPK_ATTN_OK) return TOPK_ATTN_EINVAL;
+    hipStream_t st = (hipStream_t)hip_stream;
+    Shape s; Bufs b;
+    fill_call(h, layer, q, k, &s, &b);
+    b.out = out; b.lse = lse;
+    if (idx) b.sel_idx = idx;
+    if (vals) b.sel_val = vals;
+
+    bool fast = false;
+    if (h->path != TOPK_ATTN_PATH_FULL && scan_mfma_supported(s)) {
+        fast = true;
+        for (int i = 0; i < s.B && fast; ++i) {
+            const int64_t n = h->len[(size_t)layer * s.B + i];
+            const int ke = k < n ? k : (int)n;
+            fast = plan_is_fast(make_plan(n, ke), n, s.cand_cap, h->path == TOPK_ATTN_PATH_FILTER);
+        }
+    }
+    hipError_t e = hipSuccess;
+    if (fast) {
+        e = launch_scan_sample(s, b, nmax, st);
+        if (e == hipSuccess) e = launch_threshold(s, b, st);
+        if (e == hipSuccess) e = launch_scan_filter(s, b, nmax, st);
+        if (e == hipSuccess) e = launch_select_candidates(s, b, st);
+        if (e == hipSuccess) e = launch_scan_full(s, b, nmax, true, b.scores, st);
+        if (e == hipSuccess) e = launch_select_full(s, b, true, st);
+    } else {
+        e = launch_scan_full(s, b, nmax, false, b.scores, st);
+        if (e == hipSuccess) e = launch_select_full(s, b, false, st);
+    }
+    if (e == hipSuccess) e = launch_gather(s, b, st);
+    h->last_fast = fast;
+    return e == hipSuccess ? TOPK_ATTN_OK : TOPK_ATTN_EDEVICE;
+}
+
+int topk_attn_scores(topk_attn_t* h, int layer, const void* q, float* scores, void* hip_stream) {
+    if (!h || !q || !scores) return TOPK_ATTN_EINVAL;
+    if (layer < 0 || layer >= h->cfg.n_layers) return TOPK_ATTN_EINVAL;
+    if ((uintptr_t)q & 15) return TOPK_ATTN_EINVAL;
+    int64_t nmin, nmax;
+    if (lengths_of(h, layer, &nmin, &nmax) != TOPK_ATTN_OK) return TOPK_ATTN_EINVAL;
+    Shape s; Bufs b;
+    fill_call(h, layer, q, 1, &s, &b);
+    hipError_t e = launch_scan_full(s, b, nmax, false, scores, (hipStream_t)hip_stream);
+    return e == hipSuccess ? TOPK_ATTN_OK : TOPK_ATTN_EDEVICE;
+}
+
+int topk_attn_last_fallbacks(topk_attn_t* h, int* n_heads) {
+    if (!h || !n_heads) return TOPK_ATTN_EINVAL;
+    *n_heads = 0;
+    if (!h->last_fast) return TOPK_ATTN_OK;
+    uint32_t v = 0;
+    if (hipMemcpy(&v, static_cast<char*>(h->cfg.workspace) + h->ws.fallback, sizeof v, hipMemcpyDeviceToHost) !=
+        hipSuccess)
+        return TOPK_ATTN_EDEVICE;
+    *n_heads = (int)v;
+    return TOPK_ATTN_OK;
+}
+
+int topk_attn_read_probe(const void* src, size_t bytes, void* sink, void* hip_stream) {
+    if (!src || !sink || bytes == 0 || (bytes & 15) || ((uintptr_t)src & 15)) return TOPK_ATTN_EINVAL;
+    const size_t n_vec = bytes / 16;
+    size_t blocks = (n_vec + 256 * 4 - 1) / (256 * 4);
+    if (blocks > 16384) blocks = 16384;
+    if (const char* e = getenv("TOPK_ATTN_PROBE_BLOCKS")) blocks = (size_t)atoi(e);
+    if (blocks < 1) blocks = 1;
+    hipLaunchKernelGGL(read_probe_kernel, dim3((unsigned)blocks), dim3(256), 0, (hipStream_t)hip_stream,
+                       static_cast<const u32x4*>(src), n_vec, static_cast<uint32_t*>(sink));
+    return hipGetLastError() == hipSuccess ? TOPK_ATTN_OK : TOPK_ATTN_EDEVICE;
+}
+
+const char* topk_attn_strerror(int code) {
+    switch (code) {
+        case TOPK_ATTN_OK: return "ok";
+        case TOPK_ATTN_EINVAL: return "invalid argument";
+        case TOPK_ATTN_ECAPACITY: return "cache capacity exceeded";
+        case TOPK_ATTN_EUNSUPPORTED: return "unsupported configuration";
+        case TOPK_ATTN_EDEVICE: return "HIP error";
+        case TOPK_ATTN_ENOMEM: return "out of memory or buffer too small";
+        default: return "unknown error";
+    }
+}
+
+}  // extern "C"

@@ -1,0 +1,108 @@
+// Internal declarations shared by the translation units of libtopk_attn (gfx950 only).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace tka {
+
+enum { DT_F32 = 0, DT_F16 = 1, DT_BF16 = 2 };
+
+constexpr int kWave = 64;
+constexpr int kSelThreads = 1024;   // workgroup size of the selection kernels
+constexpr int kGatherRows = 256;    // value rows handled by one gather workgroup
+constexpr int kSampMax = 16384;     // most sample scores per head in the threshold estimate
+constexpr int kSampMin = 1024;
+constexpr int kFilterMinN = 16384;  // below this the full path is used
+
+// Geometry of one decode call, passed by value to every kernel.
+struct Shape {
+    int B, Hq, Hkv, G, D, dtype;
+    int k;            // requested k (k_eff = min(k, len[b]) per sequence)
+    int max_k;
+    int cand_cap;     // entries per (b, head) candidate list
+    int samp_cap;     // entries per (b, head) sample-score row
+    int n_chunk_cap;  // partial-sum slots per (b, head)
+    int64_t Ncap;     // row capacity per (layer, seq, kv head)
+};
+
+// Device pointers of one decode call.
+struct Bufs {
+    const void* K;          // this layer's keys  [B][Hkv][Ncap][D]
+    const void* V;          // this layer's values
+    const void* q;          // [B][Hq][D]
+    const int32_t* len;     // [B] tokens cached per sequence (this layer)
+    float* thr;             // [B*Hq] candidate threshold
+    float* samp;            // [B*Hq][samp_cap]
+    uint32_t* cand_cnt;     // [B*Hq]
+    uint32_t* flags;        // [B*Hq] 1 = candidate list unusable, use the full path
+    float* hmax;            // [B*Hq] largest selected score
+    uint64_t* cand;         // [B*Hq][cand_cap] (score bits << 32 | position)
+    float* scores;          // [B*Hq][Ncap] full score buffer
+    int32_t* sel_idx;       // [B*Hq][k]
+    float* sel_val;         // [B*Hq][k]
+    float* part_acc;        // [B*Hq][n_chunk_cap][D]
+    float* part_l;          // [B*Hq][n_chunk_cap]
+    float* out;             // [B*Hq][D]
+    float* lse;             // [B*Hq] or null
+    uint32_t* fallback_total; // [1]
+};
+
+// Sampling plan for the threshold estimate of one sequence (same code on host and device).
+struct Plan {
+    int n_samp;      // sample keys per KV head (multiple of 64)
+    int stride;      // one sample per `stride` consecutive positions
+    int rank;        // threshold = rank-th largest sample score
+    int64_t c_hi;    // candidates expected at most (z-sigma above the mean)
+};
+
+__host__ __device__ inline Plan make_plan(int64_t N, int k_eff) {
+    Plan p;
+    int64_t ns = N / 64;
+    if (ns > kSampMax) ns = kSampMax;
+    if (ns < kSampMin) ns = kSampMin;
+    if (ns > N) ns = N;
+    ns &= ~int64_t(63);
+    if (ns < 64) ns = 64;
+    p.n_samp = (int)ns;
+    p.stride = (int)(N / ns);
+    if (p.stride < 1) p.stride = 1;
+    // With r0 samples expected above the true k-th score, take the rank r solving
+    // r - z sqrt(r) = r0 so that the threshold is below the k-th score unless a
+    // z-sigma event happens; the candidate list then holds about N r / n_samp entries.
+    const double z = 6.0;
+    double r0 = (double)k_eff * (double)ns / (double)N;
+    double sr = 0.5 * (z + sqrt(z * z + 4.0 * r0));
+    double r = sr * sr;
+    p.rank = (int)r + 2;
+    p.c_hi = (int64_t)((double)N * (r + z * sr + 2.0) / (double)ns) + 64;
+    return p;
+}
+
+// The filtered scan needs the candidate list to fit; unless forced it is also skipped
+// for short caches and for selections too dense to be worth filtering.
+__host__ __device__ inline bool plan_is_fast(const Plan& p, int64_t N, int cand_cap, bool force) {
+    if (N < 256 || p.rank > p.n_samp || p.c_hi > cand_cap) return false;
+    return force || (N >= kFilterMinN && p.c_hi * 4 <= N);
+}
+
+// Position of sample s: one jittered position inside each stride-long stratum.
+__host__ __device__ inline int64_t sample_pos(int s, int stride) {
+    uint32_t h = (uint32_t)s * 2654435761u;
+    h ^= h >> 15; h *= 2246822519u; h ^= h >> 13;
+    return (int64_t)s * stride + (int64_t)(h % (uint32_t)stride);
+}
+
+// Launch wrappers (each returns the hipError_t of the launch).
+hipError_t launch_scan_sample(const Shape& s, const Bufs& b, int64_t Nmax, hipStream_t st);
+hipError_t launch_scan_filter(const Shape& s, const Bufs& b, int64_t Nmax, hipStream_t st);
+hipError_t launch_scan_full(const Shape& s, const Bufs& b, int64_t Nmax, bool only_flagged, float* dst,
+                            hipStream_t st);
+bool scan_mfma_supported(const Shape& s);
+
+hipError_t launch_threshold(const Shape& s, const Bufs& b, hipStream_t st);
+hipError_t launch_select_candidates(const Shape& s, const Bufs& b, hipStream_t st);
+hipError_t launch_select_full(const Shape& s, const Bufs& b, bool only_flagged, hipStream_t st);
+
+hipError_t launch_gather(const Shape& s, const Bufs& b, hipStream_t st);
+
+}  // namespace tka

@@ -1,0 +1,327 @@
+// Key-scoring scan: S[h, i] = q_h . K[g(h), i] over the cached keys of one layer
+// (the score matrix S = q K^T of Eq. 1 of arXiv 2502.06766, raw dot products as used by
+// the paper's k-nearest-neighbour search under the dot-product metric).
+//
+// 16-bit caches use v_mfma_f32_16x16x32_{f16,bf16}: one wave scores a tile of 64
+// consecutive keys against the (up to 4) query heads that share the KV head, fp32
+// accumulate.  Operand B is loaded straight from the row-major key rows in its MFMA
+// register layout (lane (j, n) holds 8 consecutive channels of key n), operand A holds the
+// query block replicated in every group of four rows, so that after four accumulators
+// (one per 16-key sub-tile) lane l owns the scores of key l for all heads of the group.
+//
+// Three uses of the same tile routine:
+//   sample : score a strided, jittered sample of positions (threshold estimate)
+//   filter : score every key, keep (score, position) pairs >= a per-head threshold in a
+//            per-wave LDS list, flushed to the head's global candidate list
+//   full   : score every key and store the fp32 scores
+// Other dtypes / head groupings go through a plain FMA kernel (full only).
+#include "device_utils.h"
+#include "internal.h"
+
+namespace tka {
+
+template <int DT> struct Mfma;
+template <> struct Mfma<DT_F16> {
+    using v8 = f16x8;
+    static __device__ __forceinline__ f32x4 mac(v8 a, v8 b, f32x4 c) {
+        return __builtin_amdgcn_mfma_f32_16x16x32_f16(a, b, c, 0, 0, 0);
+    }
+};
+template <> struct Mfma<DT_BF16> {
+    using v8 = bf16x8;
+    static __device__ __forceinline__ f32x4 mac(v8 a, v8 b, f32x4 c) {
+        return __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, c, 0, 0, 0);
+    }
+};
+
+enum { MODE_SAMPLE = 0, MODE_FILTER = 1, MODE_FULL = 2 };
+constexpr int kScanWaves = 4;     // waves per scan workgroup
+constexpr int kCandLds = 128;     // per-wave, per-head LDS candidate slots
+
+// Query block of the group in operand-A layout: lane (j, m) holds channels
+// 32 s + 8 j .. +7 of head m % 4 (zero for heads the group does not have).
+template <int DT, int D>
+__device__ __forceinline__ void load_query_a(const void* q, int64_t head0, int G,
+                                             typename Mfma<DT>::v8 (&qa)[D / 32]) {
+    using v8 = typename Mfma<DT>::v8;
+    const int lane = lane_id();
+    const int j = lane >> 4, r = lane & 3;
+    const v8* p = reinterpret_cast<const v8*>(static_cast<const char*>(q) + (head0 + (r < G ? r : 0)) * D * 2) + j;
+#pragma unroll
+    for (int s = 0; s < D / 32; ++s) {
+        v8 v = p[4 * s];
+        if (r >= G) v = v8{};
+        qa[s] = v;
+    }
+}
+
+// Scores of 64 keys: lane l gets res[r] = q_{head0 + r} . K[row(l)], rows given per
+// 16-key sub-tile by rowfn(slot).
+template <int DT, int D, class RowFn>
+__device__ __forceinline__ f32x4 tile_scores(const char* Kh, RowFn rowfn,
+                                             const typename Mfma<DT>::v8 (&qa)[D / 32]) {
+    using v8 = typename Mfma<DT>::v8;
+    constexpr int KS = D / 32;
+    const int lane = lane_id();
+    const int j = lane >> 4, n = lane & 15;
+    v8 b[4][KS];
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+        const int64_t row = rowfn(16 * g + n);
+        const v8* p = reinterpret_cast<const v8*>(Kh + row * (D * 2)) + j;
+#pragma unroll
+        for (int s = 0; s < KS; ++s) b[g][s] = p[4 * s];
+    }
+    f32x4 c[4];
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+        c[g] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int s = 0; s < KS; ++s) c[g] = Mfma<DT>::mac(qa[s], b[g][s], c[g]);
+    }
+    // rows 4 jj .. 4 jj + 3 of every accumulator hold heads 0..3; lane group jj keeps sub-tile jj
+    f32x4 res;
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+        const float lo = (j & 1) ? c[1][r] : c[0][r];
+        const float hi = (j & 1) ? c[3][r] : c[2][r];
+        res[r] = (j & 2) ? hi : lo;
+    }
+    return res;
+}
+
+__device__ __forceinline__ void flush_candidates(uint64_t* seg, int cnt, uint32_t* gcnt, uint64_t* gcand,
+                                                 int cap) {
+    wave_sync();
+    const int lane = lane_id();
+    uint32_t base = 0;
+    if (lane == 0) base = atomicAdd(gcnt, (uint32_t)cnt);
+    base = wave_first_u32(base);
+    for (int i = lane; i < cnt; i += kWave) {
+        if (base + (uint32_t)i < (uint32_t)cap) gcand[base + i] = seg[i];
+    }
+    wave_sync();
+}
+
+// Keep the keys of one head whose score reaches the head's threshold.
+__device__ __forceinline__ void filter_head(float score, float thr, int& cnt, bool valid, int64_t item,
+                                            uint64_t* seg, uint32_t* gcnt, uint64_t* gcand, int cap) {
+    const float sc = score + 0.0f;
+    const bool pass = valid && sc >= thr;
+    const uint64_t m = __ballot(pass);
+    if (m) {
+        const int add = __popcll(m);
+        if (cnt + add > kCandLds) {
+            flush_candidates(seg, cnt, gcnt, gcand, cap);
+            cnt = 0;
+        }
+        if (pass) seg[cnt + mask_rank(m)] = ((uint64_t)__float_as_uint(sc) << 32) | (uint64_t)(uint32_t)item;
+        cnt += add;
+    }
+}
+
+template <int DT, int D, int MODE>
+__global__ void __launch_bounds__(kScanWaves* kWave)
+scan_mfma_kernel(Shape sh, Bufs bf, int tiles_per_wave, int only_flagged, float* dst) {
+    using v8 = typename Mfma<DT>::v8;
+    const int b = blockIdx.z, kvh = blockIdx.y;
+    const int G = sh.G;
+    const int64_t head0 = (int64_t)b * sh.Hq + (int64_t)kvh * G;
+    const int lane = lane_id();
+    const int wave = threadIdx.x >> 6;
+    const int64_t N = bf.len[b];
+
+    if (MODE == MODE_FULL && only_flagged) {
+        uint32_t any = 0;
+        for (int r = 0; r < G; ++r) any |= bf.flags[head0 + r];
+        if (!any) return;
+    }
+
+    int64_t n_items = N;   // keys (or samples) this (b, kv head) has
+    int stride = 1;
+    if (MODE == MODE_SAMPLE) {
+        Plan pl = make_plan(N, sh.k < N ? sh.k : (int)N);
+        n_items = pl.n_samp;
+        stride = pl.stride;
+    }
+    const int64_t tile0 = (int64_t)blockIdx.x * tiles_per_wave * kScanWaves;
+    if (tile0 * 64 >= n_items) return;
+
+    v8 qa[D / 32];
+    load_query_a<DT, D>(bf.q, head0, G, qa);
+    const char* Kh = static_cast<const char*>(bf.K) + ((int64_t)b * sh.Hkv + kvh) * sh.Ncap * (D * 2);
+
+    __shared__ uint64_t cand_lds[MODE == MODE_FILTER ? kScanWaves * 4 * kCandLds : 1];
+    uint64_t* const seg0 = cand_lds + (MODE == MODE_FILTER ? wave * 4 * kCandLds : 0);
+    uint32_t* const gcnt0 = bf.cand_cnt + head0;
+    const int cap = sh.cand_cap;
+    uint64_t* const gcand0 = bf.cand + head0 * (int64_t)cap;
+    float thr0 = 0.f, thr1 = 0.f, thr2 = 0.f, thr3 = 0.f;
+    int cnt0 = 0, cnt1 = 0, cnt2 = 0, cnt3 = 0;
+    if (MODE == MODE_FILTER) {
+        thr0 = bf.thr[head0];
+        if (1 < G) thr1 = bf.thr[head0 + 1];
+        if (2 < G) thr2 = bf.thr[head0 + 2];
+        if (3 < G) thr3 = bf.thr[head0 + 3];
+    }
+
+    for (int it = 0; it < tiles_per_wave; ++it) {
+        const int64_t tile = tile0 + (int64_t)it * kScanWaves + wave;
+        const int64_t item0 = tile * 64;
+        if (item0 >= n_items) break;   // wave-uniform
+        f32x4 res;
+        if (MODE == MODE_SAMPLE) {
+            res = tile_scores<DT, D>(Kh, [&](int slot) {
+                int64_t s = item0 + slot;
+                if (s > n_items - 1) s = n_items - 1;
+                int64_t p = sample_pos((int)s, stride);
+                return p < N ? p : N - 1;
+            }, qa);
+        } else {
+            res = tile_scores<DT, D>(Kh, [&](int slot) {
+                int64_t p = item0 + slot;
+                return p < N ? p : N - 1;
+            }, qa);
+        }
+        const int64_t item = item0 + lane;
+        const bool valid = item < n_items;
+        if (MODE == MODE_SAMPLE) {
+#pragma unroll
+            for (int r = 0; r < 4; ++r)
+                if (r < G && valid) bf.samp[(head0 + r) * sh.samp_cap + item] = res[r];
+        } else if (MODE == MODE_FULL) {
+#pragma unroll
+            for (int r = 0; r < 4; ++r)
+                if (r < G && valid) dst[(head0 + r) * sh.Ncap + item] = res[r];
+        } else {
+            if (0 < G) filter_head(res[0], thr0, cnt0, valid, item, seg0 + 0 * kCandLds, gcnt0 + 0, gcand0 + 0 * (int64_t)cap, cap);
+            if (1 < G) filter_head(res[1], thr1, cnt1, valid, item, seg0 + 1 * kCandLds, gcnt0 + 1, gcand0 + 1 * (int64_t)cap, cap);
+            if (2 < G) filter_head(res[2], thr2, cnt2, valid, item, seg0 + 2 * kCandLds, gcnt0 + 2, gcand0 + 2 * (int64_t)cap, cap);
+            if (3 < G) filter_head(res[3], thr3, cnt3, valid, item, seg0 + 3 * kCandLds, gcnt0 + 3, gcand0 + 3 * (int64_t)cap, cap);
+        }
+    }
+    if (MODE == MODE_FILTER) {
+        if (cnt0 > 0) flush_candidates(seg0, cnt0, gcnt0, gcand0, cap);
+        if (cnt1 > 0) flush_candidates(seg0 + kCandLds, cnt1, gcnt0 + 1, gcand0 + (int64_t)cap, cap);
+        if (cnt2 > 0) flush_candidates(seg0 + 2 * kCandLds, cnt2, gcnt0 + 2, gcand0 + 2 * (int64_t)cap, cap);
+        if (cnt3 > 0) flush_candidates(seg0 + 3 * kCandLds, cnt3, gcnt0 + 3, gcand0 + 3 * (int64_t)cap, cap);
+    }
+}
+
+// Plain FMA scoring for every shape the MFMA kernel does not take (fp32 caches, other
+// head groupings): a row of D elements is spread over D*e/16 lanes, 16 bytes each.
+template <int DT>
+__global__ void __launch_bounds__(256)
+scan_generic_kernel(Shape sh, Bufs bf, int rows_per_block, int only_flagged, float* dst) {
+    constexpr int EPL = Elem<DT>::kPerLoad;
+    const int b = blockIdx.z, kvh = blockIdx.y;
+    const int G = sh.G, D = sh.D;
+    const int64_t head0 = (int64_t)b * sh.Hq + (int64_t)kvh * G;
+    const int64_t N = bf.len[b];
+    if (only_flagged) {
+        uint32_t any = 0;
+        for (int r = 0; r < G; ++r) any |= bf.flags[head0 + r];
+        if (!any) return;
+    }
+    const int64_t row_begin = (int64_t)blockIdx.x * rows_per_block;
+    if (row_begin >= N) return;
+
+    __shared__ float q_lds[16 * 256];
+    for (int i = threadIdx.x; i < G * D; i += blockDim.x) {
+        const char* qp = static_cast<const char*>(bf.q) + (head0 * D + i) * Elem<DT>::kBytes;
+        float v;
+        if (DT == DT_F32) v = *reinterpret_cast<const float*>(qp);
+        else if (DT == DT_F16) v = (float)*reinterpret_cast<const _Float16*>(qp);
+        else v = __uint_as_float((uint32_t)*reinterpret_cast<const uint16_t*>(qp) << 16);
+        q_lds[i] = v;
+    }
+    __syncthreads();
+
+    const int lpr = D / EPL;              // lanes per row (power of two, <= 64)
+    const int rows_per_pass = blockDim.x / lpr;
+    const int slot = threadIdx.x / lpr, chunk = threadIdx.x % lpr;
+    const char* Kh = static_cast<const char*>(bf.K) +
+                     ((int64_t)b * sh.Hkv + kvh) * sh.Ncap * D * Elem<DT>::kBytes;
+    int64_t row_end = row_begin + rows_per_block;
+    if (row_end > N) row_end = N;
+    for (int64_t base = row_begin; base < row_end; base += rows_per_pass) {
+        const int64_t row = base + slot;
+        const bool valid = row < row_end;
+        const int64_t lrow = valid ? row : row_end - 1;
+        const u32x4 raw = *reinterpret_cast<const u32x4*>(Kh + (lrow * D + chunk * EPL) * Elem<DT>::kBytes);
+        float kf[EPL];
+        Elem<DT>::widen(raw, kf);
+        for (int r = 0; r < G; ++r) {
+            const float* qr = q_lds + r * D + chunk * EPL;
+            float acc = 0.f;
+#pragma unroll
+            for (int e = 0; e < EPL; ++e) acc = fmaf(kf[e], qr[e], acc);
+            for (int m = 1; m < lpr; m <<= 1) acc += wave_xor(acc, m);
+            if (valid && chunk == 0) dst[(head0 + r) * sh.Ncap + row] = acc;
+        }
+    }
+}
+
+bool scan_mfma_supported(const Shape& s) {
+    return (s.dtype == DT_F16 || s.dtype == DT_BF16) && (s.D == 64 || s.D == 128) && s.G >= 1 && s.G <= 4;
+}
+
+static int tiles_per_wave_for(int64_t n_items, int B, int Hkv) {
+    // aim at ~16 workgroups per CU over the whole grid, at least 1 tile and at most 32 per wave
+    const int64_t tiles = (n_items + 63) / 64;
+    const int64_t want_wgs = 4096 / ((int64_t)B * Hkv > 0 ? (int64_t)B * Hkv : 1);
+    int64_t tpw = tiles / (kScanWaves * (want_wgs > 0 ? want_wgs : 1));
+    if (const char* e = getenv("TOPK_ATTN_TILES_PER_WAVE")) tpw = atoi(e);
+    if (tpw < 1) tpw = 1;
+    if (tpw > 64) tpw = 64;
+    return (int)tpw;
+}
+
+template <int MODE>
+static hipError_t launch_mfma(const Shape& s, const Bufs& b, int64_t n_items, bool only_flagged, float* dst,
+                              hipStream_t st) {
+    const int tpw = tiles_per_wave_for(n_items, s.B, s.Hkv);
+    const int64_t tiles = (n_items + 63) / 64;
+    const int64_t per_wg = (int64_t)tpw * kScanWaves;
+    dim3 grid((unsigned)((tiles + per_wg - 1) / per_wg), (unsigned)s.Hkv, (unsigned)s.B);
+    dim3 block(kScanWaves * kWave);
+    const int of = only_flagged ? 1 : 0;
+#define TKA_LAUNCH(DT_, D_) \
+    hipLaunchKernelGGL((scan_mfma_kernel<DT_, D_, MODE>), grid, block, 0, st, s, b, tpw, of, dst)
+    if (s.dtype == DT_F16 && s.D == 128) TKA_LAUNCH(DT_F16, 128);
+    else if (s.dtype == DT_F16 && s.D == 64) TKA_LAUNCH(DT_F16, 64);
+    else if (s.dtype == DT_BF16 && s.D == 128) TKA_LAUNCH(DT_BF16, 128);
+    else if (s.dtype == DT_BF16 && s.D == 64) TKA_LAUNCH(DT_BF16, 64);
+    else return hipErrorInvalidValue;
+#undef TKA_LAUNCH
+    return hipGetLastError();
+}
+
+hipError_t launch_scan_sample(const Shape& s, const Bufs& b, int64_t Nmax, hipStream_t st) {
+    Plan pl = make_plan(Nmax, s.k);
+    return launch_mfma<MODE_SAMPLE>(s, b, pl.n_samp, false, nullptr, st);
+}
+
+hipError_t launch_scan_filter(const Shape& s, const Bufs& b, int64_t Nmax, hipStream_t st) {
+    return launch_mfma<MODE_FILTER>(s, b, Nmax, false, nullptr, st);
+}
+
+hipError_t launch_scan_full(const Shape& s, const Bufs& b, int64_t Nmax, bool only_flagged, float* dst,
+                            hipStream_t st) {
+    if (scan_mfma_supported(s)) return launch_mfma<MODE_FULL>(s, b, Nmax, only_flagged, dst, st);
+    const int epl = s.dtype == DT_F32 ? 4 : 8;
+    const int lpr = s.D / epl;
+    const int rows_per_pass = 256 / lpr;
+    int64_t rows_per_block = (int64_t)rows_per_pass * 16;
+    dim3 grid((unsigned)((Nmax + rows_per_block - 1) / rows_per_block), (unsigned)s.Hkv, (unsigned)s.B);
+    const int of = only_flagged ? 1 : 0;
+    if (s.dtype == DT_F32)
+        hipLaunchKernelGGL((scan_generic_kernel<DT_F32>), grid, dim3(256), 0, st, s, b, (int)rows_per_block, of, dst);
+    else if (s.dtype == DT_F16)
+        hipLaunchKernelGGL((scan_generic_kernel<DT_F16>), grid, dim3(256), 0, st, s, b, (int)rows_per_block, of, dst);
+    else
+        hipLaunchKernelGGL((scan_generic_kernel<DT_BF16>), grid, dim3(256), 0, st, s, b, (int)rows_per_block, of, dst);
+    return hipGetLastError();
+}
+
+}  // namespace tka

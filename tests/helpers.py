@@ -1,0 +1,104 @@
+"""Shared test helpers: margin enforcement (uses the oracle), upload, parity checks."""
+from __future__ import annotations
+
+import numpy as np
+
+from oracle import c_oracle
+from paper_2502_06766_amd import workloads as wl
+
+U32 = 2.0 ** -24   # unit roundoff of fp32
+
+
+def abs_storage(x: np.ndarray, dtype: int) -> np.ndarray:
+    if dtype == wl.BF16:
+        return x & np.uint16(0x7FFF)
+    return np.abs(x)
+
+
+def scale_rows_storage(K: np.ndarray, dtype: int, g: int, rows: np.ndarray, factor: float) -> None:
+    """K[g, rows] *= factor, re-rounded to the storage dtype (in place)."""
+    if dtype == wl.BF16:
+        f = wl.bf16_bits_to_f32(K[g, rows]) * np.float32(factor)
+        K[g, rows] = wl.to_bf16_bits(f)
+    else:
+        K[g, rows] = (K[g, rows].astype(np.float32) * np.float32(factor)).astype(K.dtype)
+
+
+def score_margin(q, K, dtype) -> np.ndarray:
+    """delta_h = 8 d u max_i sum_c |q_c K_ic|: four times the worst-case gap two fp32
+    dot products of length d can be off by (each is within d u sum|q_c K_ic| of exact)."""
+    d = q.shape[1]
+    A = c_oracle.scores(abs_storage(q, dtype), abs_storage(K, dtype), dtype)
+    return 8.0 * d * U32 * A.max(axis=1)
+
+
+def enforce_margin(q, K, dtype, k, max_rounds=40):
+    """Nudge keys (scale the row by 1 - 2^-6) until, for every head, no unselected
+    score lies within delta_h below the k-th largest score.  Uses only oracle scores.
+    Returns (K, delta [Hq], rounds).  K is modified in place."""
+    Hq, d = q.shape
+    Hkv, N, _ = K.shape
+    G = Hq // Hkv
+    delta = score_margin(q, K, dtype)
+    if k >= N:
+        return K, delta, 0
+    for rnd in range(max_rounds):
+        S = c_oracle.scores(q, K, dtype)
+        dirty = False
+        for h in range(Hq):
+            s = S[h]
+            part = np.partition(s, N - k)          # part[N-k] is the k-th largest
+            s_k = part[N - k]
+            below = part[:N - k]
+            if below.max() > s_k - delta[h]:
+                # unselected keys inside the band (ties with s_k at higher positions included)
+                cand = np.nonzero(s > s_k - delta[h])[0]      # the k selected plus the band
+                order = cand[np.lexsort((cand, -s[cand]))]
+                viol = order[k:]
+                scale_rows_storage(K, dtype, h // G, viol, 1.0 - 2.0 ** -6)
+                dirty = True
+        if not dirty:
+            return K, delta, rnd
+    raise AssertionError("margin enforcement did not converge")
+
+
+def to_torch(x: np.ndarray, dtype: int, device):
+    import torch
+    if dtype == wl.BF16:
+        return torch.from_numpy(x.view(np.int16)).to(device).view(torch.bfloat16)
+    return torch.from_numpy(x).to(device)
+
+
+def check_against_oracle(out, idx, vals, lse, ref, delta, k_eff, tol, vmax, label=""):
+    """out/idx/vals/lse: numpy arrays from the GPU for one sequence ([Hq, ...]);
+    ref = (out, idx, vals, lse) from the oracle."""
+    r_out, r_idx, r_vals, r_lse = ref
+    Hq = r_out.shape[0]
+    for h in range(Hq):
+        got = np.sort(idx[h, :k_eff].astype(np.int64))
+        want = np.sort(r_idx[h, :k_eff])
+        if not np.array_equal(got, want):
+            miss = np.setdiff1d(want, got).size
+            raise AssertionError(f"{label} head {h}: index set differs ({miss} of {k_eff} missing)")
+        if idx.shape[1] > k_eff:
+            assert (idx[h, k_eff:] == -1).all(), f"{label} head {h}: idx padding"
+            assert np.isneginf(vals[h, k_eff:]).all(), f"{label} head {h}: vals padding"
+        gv = np.sort(vals[h, :k_eff].astype(np.float64))[::-1]
+        dv = np.abs(gv - r_vals[h, :k_eff]).max()
+        assert dv <= delta[h] / 8 + 1e-30, f"{label} head {h}: vals off by {dv} (allowed {delta[h] / 8})"
+        # vals must belong to the indices they are reported with
+        o = np.argsort(idx[h, :k_eff], kind="stable")
+        ro = np.argsort(r_idx[h, :k_eff], kind="stable")
+        dv2 = np.abs(vals[h, :k_eff][o].astype(np.float64) - r_vals[h, :k_eff][ro]).max()
+        assert dv2 <= delta[h] / 8 + 1e-30, f"{label} head {h}: vals not aligned with idx ({dv2})"
+        scale = max(np.abs(r_out[h]).max(), 1e-6 * vmax)
+        err = np.abs(out[h].astype(np.float64) - r_out[h]).max() / scale
+        assert err <= tol, f"{label} head {h}: out rel err {err:.3e} > {tol}"
+        if lse is not None:
+            assert abs(lse[h] - r_lse[h]) <= 1e-4 * max(1.0, abs(r_lse[h])), \
+                f"{label} head {h}: lse {lse[h]} vs {r_lse[h]}"
+
+
+def out_tolerance(dtype: int) -> float:
+    """2e-3 relative for 16-bit K/V with fp32 accumulate, 1e-5 for fp32."""
+    return 1e-5 if dtype == wl.F32 else 2e-3

@@ -1,0 +1,91 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports every
+symbol the header declares, sizes caches as the paper's 2NDL formula says, and rejects
+bad configurations before touching a device."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2502_06766_amd import topk_attn as ta
+from paper_2502_06766_amd import workloads as wl
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def header_functions():
+    text = open(os.path.join(ROOT, "include", "topk_attn.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(topk_attn_[a-z_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    L = ta.lib()
+    names = header_functions()
+    assert len(names) >= 10
+    for n in names:
+        assert hasattr(L, n), f"{n} declared in topk_attn.h but not exported"
+    assert sorted(ta.EXPORTS) == names
+
+
+def test_config_struct_matches_header_size():
+    # uint32 + 5*int32 + int64 + 4*int32 + 2*(ptr + size_t) = 24 + 8 + 16 + 32
+    assert ctypes.sizeof(ta.Config) == 80
+
+
+def test_kv_bytes_is_2ndl():
+    # Llama-3-8B-like layer shapes with GQA: 2 * L * B * Hkv * Ncap * d * e
+    cfg = ta.make_config(32, 1, 32, 8, 128, 524288, 8192, ta.F16)
+    assert ta.topk_attn_kv_bytes(cfg) == 2 * 32 * 8 * 524288 * 128 * 2
+    # the paper's own example ignores GQA: hidden 4096 = 32 heads of 128, N = 100k, 16 bit
+    cfg = ta.make_config(32, 1, 32, 32, 128, 100000, 1000, ta.BF16)
+    got = ta.topk_attn_kv_bytes(cfg)
+    assert abs(got - wl.kv_cache_bytes(100000, 4096, 32, 2)) <= 2 * 256
+    assert abs(got / 1e9 - 52) < 1.0
+    assert ta.topk_attn_workspace_bytes(cfg) > 0
+
+
+@pytest.mark.parametrize("kw,code", [
+    (dict(head_dim=96), ta.EUNSUPPORTED),
+    (dict(dtype=7), ta.EUNSUPPORTED),
+    (dict(n_q_heads=30), ta.EUNSUPPORTED),          # 30 % 8 != 0
+    (dict(n_q_heads=8 * 32), ta.EUNSUPPORTED),       # group of 32 > 16
+    (dict(n_layers=0), ta.EINVAL),
+    (dict(max_k=0), ta.EINVAL),
+    (dict(max_tokens=1 << 31), ta.EINVAL),
+])
+def test_bad_config_rejected_without_device(kw, code):
+    base = dict(n_layers=1, n_seqs=1, n_q_heads=32, n_kv_heads=8, head_dim=128, max_tokens=4096, max_k=64,
+                dtype=ta.F16)
+    base.update(kw)
+    cfg = ta.make_config(**base)
+    assert ta.topk_attn_kv_bytes(cfg) == 0
+    assert ta.topk_attn_workspace_bytes(cfg) == 0
+    h = ctypes.c_void_p()
+    assert ta.lib().topk_attn_create(ctypes.byref(cfg), ctypes.byref(h)) == code
+    assert not h.value
+
+
+def test_create_rejects_null_storage_and_wrong_struct_size():
+    cfg = ta.make_config(1, 1, 4, 2, 64, 128, 8, ta.F32)
+    h = ctypes.c_void_p()
+    assert ta.lib().topk_attn_create(ctypes.byref(cfg), ctypes.byref(h)) == ta.EINVAL   # null storage
+    cfg.struct_size = 12
+    assert ta.lib().topk_attn_create(ctypes.byref(cfg), ctypes.byref(h)) == ta.EINVAL
+    assert ta.lib().topk_attn_create(ctypes.byref(cfg), None) == ta.EINVAL
+
+
+def test_null_handle_calls_fail_cleanly():
+    L = ta.lib()
+    assert L.topk_attn_decode(None, 0, None, 1, None, None, None, None, None) == ta.EINVAL
+    assert L.topk_attn_append_kv(None, 0, 0, None, None, 1, 1, 1, None) == ta.EINVAL
+    assert L.topk_attn_length(None, 0, 0) == -1
+    assert L.topk_attn_destroy(None) == ta.EINVAL
+    assert L.topk_attn_set_path(None, 0) == ta.EINVAL
+    assert L.topk_attn_read_probe(None, 16, None, None) == ta.EINVAL
+
+
+def test_strerror():
+    assert ta.topk_attn_strerror(ta.OK) == "ok"
+    assert "capacity" in ta.topk_attn_strerror(ta.ECAPACITY)
+    assert ta.topk_attn_strerror(99) == "unknown error"

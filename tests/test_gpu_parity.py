@@ -1,0 +1,241 @@
+"""GPU parity: the HIP path (through the C ABI) against the CPU oracle, element by element.
+
+Bars: selected index sets identical (inputs are given a score margin at the k-th
+boundary, or are integer valued so both sides are exact); vals within delta/8 of the
+double-precision scores (delta = 8 d u max sum|q_c K_c|); out within 2e-3 (16-bit)
+or 1e-5 (fp32) of max|out_ref| per head.
+"""
+import numpy as np
+import pytest
+import torch
+
+import helpers as H
+from oracle import c_oracle
+from paper_2502_06766_amd import topk_attn as ta
+from paper_2502_06766_amd import workloads as wl
+
+pytestmark = pytest.mark.gpu
+DEV = torch.device("cuda", 0) if torch.cuda.is_available() else None
+
+
+def run_case(q, K, V, dtype, k, path=ta.PATH_AUTO, max_tokens=None, chunks=1, label="", expect_fallbacks=None,
+             exact_inputs=False):
+    """One sequence, one layer.  q [Hq,d], K,V [Hkv,N,d] storage arrays (already margin-safe)."""
+    Hq, d = q.shape
+    Hkv, N, _ = K.shape
+    delta = H.score_margin(q, K, dtype)
+    if exact_inputs:
+        delta = np.full(Hq, 1e-30)
+    ref = c_oracle.topk_attention(q, K, V, dtype, k)
+    cache = ta.TopkAttnCache(1, 1, Hq, Hkv, d, max_tokens or N, k, dtype)
+    try:
+        cache.set_path(path)
+        Kd, Vd = H.to_torch(K, dtype, DEV), H.to_torch(V, dtype, DEV)
+        # bulk import in `chunks` head-major pieces, exercising append at non-zero offsets
+        bounds = np.linspace(0, N, chunks + 1).astype(int)
+        for a, b in zip(bounds[:-1], bounds[1:]):
+            if b > a:
+                cache.append(0, 0, Kd[:, a:b].contiguous(), Vd[:, a:b].contiguous(), head_major=True)
+        assert cache.length(0, 0) == N
+        qd = H.to_torch(q, dtype, DEV)[None].contiguous()
+        out, idx, vals, lse = cache.decode(0, qd, k)
+        torch.cuda.synchronize()
+        fb = cache.last_fallbacks()
+        k_eff = min(k, N)
+        vmax = float(np.abs(wl.widen(V, dtype)).max())
+        H.check_against_oracle(out[0].cpu().numpy(), idx[0].cpu().numpy(), vals[0].cpu().numpy(),
+                               lse[0].cpu().numpy(), ref, delta, k_eff, H.out_tolerance(dtype), vmax, label)
+        if expect_fallbacks is not None:
+            assert fb == expect_fallbacks, f"{label}: {fb} heads fell back"
+        # second call without idx/vals/lse outputs must give the same attention output
+        out2, _, _, _ = cache.decode(0, qd, k, want_idx=False, want_vals=False, want_lse=False)
+        torch.cuda.synchronize()
+        np.testing.assert_allclose(out2.cpu().numpy(), out.cpu().numpy(), rtol=1e-5, atol=1e-6)
+        return fb
+    finally:
+        cache.close()
+
+
+def rand_case(Hq, Hkv, N, d, dtype, k, seed):
+    g = np.random.default_rng(seed)
+    q = wl.quantize(g.standard_normal((Hq, d)).astype(np.float32), dtype)
+    K = wl.quantize(g.standard_normal((Hkv, N, d)).astype(np.float32), dtype)
+    V = wl.quantize(g.standard_normal((Hkv, N, d)).astype(np.float32), dtype)
+    K, _, _ = H.enforce_margin(q, K, dtype, k)
+    return q, K, V
+
+
+# ------------------------------------------------------------------ config 1
+@pytest.mark.parametrize("seed", [0, 1, 2])
+def test_c1_single_head_fp32(seed):
+    w = wl.C1
+    q, K, V = wl.make_quantized(w, seed)
+    K, _, _ = H.enforce_margin(q, K, w.dtype, w.k)
+    run_case(q, K, V, w.dtype, w.k, label=f"c1 seed {seed}")
+
+
+# ------------------------------------------------------------------ general path sweeps
+@pytest.mark.parametrize("dtype", [wl.F32, wl.F16, wl.BF16])
+@pytest.mark.parametrize("Hq,Hkv,N,d,k", [
+    (1, 1, 1, 32, 1),          # one cached token
+    (2, 1, 63, 64, 5),         # below one tile
+    (4, 1, 65, 128, 65),       # k = N, one key past a tile
+    (4, 2, 1000, 64, 1),       # k = 1
+    (8, 2, 4097, 128, 130),    # ragged tail, several workgroups
+    (6, 2, 777, 256, 40),      # G = 3, d = 256
+    (16, 1, 300, 32, 300),     # G = 16 (plain FMA scorer), k = N
+    (5, 5, 2049, 64, 700),     # G = 1, large k/N
+])
+def test_general_path_sweep(dtype, Hq, Hkv, N, d, k):
+    q, K, V = rand_case(Hq, Hkv, N, d, dtype, k, seed=N + k)
+    run_case(q, K, V, dtype, k, path=ta.PATH_FULL, chunks=3, label=f"full N={N} k={k}")
+
+
+def test_k_larger_than_n_pads():
+    q, K, V = rand_case(4, 2, 50, 64, wl.F16, 50, seed=5)
+    run_case(q, K, V, wl.F16, 80, path=ta.PATH_FULL, label="k>N")
+
+
+# ------------------------------------------------------------------ filtered scan path
+@pytest.mark.parametrize("dtype,Hq,Hkv,N,d,k", [
+    (wl.F16, 8, 2, 20001, 128, 300),
+    (wl.BF16, 8, 2, 65536 + 17, 128, 1024),
+    (wl.F16, 4, 2, 40000, 64, 64),       # G = 2, d = 64
+    (wl.BF16, 3, 3, 33333, 128, 500),    # G = 1
+    (wl.F16, 12, 4, 70001, 128, 1),      # G = 3, k = 1
+])
+def test_filter_path_sweep(dtype, Hq, Hkv, N, d, k):
+    q, K, V = rand_case(Hq, Hkv, N, d, dtype, k, seed=N + k)
+    run_case(q, K, V, dtype, k, path=ta.PATH_AUTO, chunks=2, label=f"filter N={N} k={k}", expect_fallbacks=0)
+
+
+def test_filter_path_clustered_scores():
+    """High scores concentrated in the most recent positions (local attention): the
+    position-uniform sample must still bracket the k-th score."""
+    g = np.random.default_rng(3)
+    Hq, Hkv, N, d, k = 8, 2, 60000, 128, 900
+    q = g.standard_normal((Hq, d)).astype(np.float32)
+    K = g.standard_normal((Hkv, N, d)).astype(np.float32)
+    V = g.standard_normal((Hkv, N, d)).astype(np.float32)
+    for h in range(Hq):
+        K[h // 4, N - 1500:N] += 0.08 * q[h]
+    q, K, V = (wl.quantize(a, wl.F16) for a in (q, K, V))
+    K, _, _ = H.enforce_margin(q, K, wl.F16, k)
+    run_case(q, K, V, wl.F16, k, label="clustered")
+
+
+# ------------------------------------------------------------------ ties (integer-valued, exact on both sides)
+@pytest.mark.parametrize("path,N,k", [(ta.PATH_FULL, 3000, 257), (ta.PATH_FILTER, 50000, 999),
+                                       (ta.PATH_FULL, 512, 100)])
+@pytest.mark.parametrize("dtype", [wl.F16, wl.F32])
+def test_ties_lower_position_wins(path, N, k, dtype):
+    """Small-integer q and K make every dot product exact in fp32, so scores tie
+    massively and both sides must resolve them identically (lower position first)."""
+    g = np.random.default_rng(N + k)
+    Hq, Hkv, d = 4, 2, 64
+    q = wl.quantize(g.integers(-3, 4, (Hq, d)).astype(np.float32), dtype)
+    K = wl.quantize(g.integers(-3, 4, (Hkv, N, d)).astype(np.float32), dtype)
+    V = wl.quantize(g.standard_normal((Hkv, N, d)).astype(np.float32), dtype)
+    if path == ta.PATH_FILTER and dtype == wl.F32:
+        pytest.skip("filtered scan covers 16-bit caches only")
+    run_case(q, K, V, dtype, k, path=path, label="ties", exact_inputs=True)
+
+
+def test_all_keys_identical():
+    """Every score equal: positions 0..k-1 win and out is their mean (both paths)."""
+    g = np.random.default_rng(0)
+    Hq, Hkv, N, d, k = 4, 1, 30000, 128, 77
+    q = wl.quantize(g.integers(-2, 3, (Hq, d)).astype(np.float32), wl.BF16)
+    K = np.tile(wl.quantize(g.integers(-2, 3, (Hkv, 1, d)).astype(np.float32), wl.BF16), (1, N, 1))
+    V = wl.quantize(g.standard_normal((Hkv, N, d)).astype(np.float32), wl.BF16)
+    fb = run_case(q, K, V, wl.BF16, k, path=ta.PATH_FILTER, label="identical", exact_inputs=True)
+    assert fb == Hq     # every head's candidate list overflows and is redone by the full path
+
+
+# ------------------------------------------------------------------ debug score dump
+@pytest.mark.parametrize("dtype,G,d", [(wl.F16, 4, 128), (wl.BF16, 2, 64), (wl.F32, 4, 64), (wl.F16, 8, 128)])
+def test_scores_within_fp32_bound(dtype, G, d):
+    g = np.random.default_rng(7)
+    Hkv, N = 2, 5000
+    Hq = Hkv * G
+    q = wl.quantize(g.standard_normal((Hq, d)).astype(np.float32), dtype)
+    K = wl.quantize(g.standard_normal((Hkv, N, d)).astype(np.float32), dtype)
+    S = c_oracle.scores(q, K, dtype)
+    bound = d * H.U32 * c_oracle.scores(H.abs_storage(q, dtype), H.abs_storage(K, dtype), dtype)
+    cache = ta.TopkAttnCache(1, 1, Hq, Hkv, d, N + 100, 8, dtype)
+    try:
+        Kd = H.to_torch(K, dtype, DEV)
+        cache.append(0, 0, Kd.permute(1, 0, 2).contiguous(), Kd.permute(1, 0, 2).contiguous())  # token-major
+        got = cache.scores(0, H.to_torch(q, dtype, DEV)[None].contiguous())[0, :, :N].cpu().numpy()
+        assert (np.abs(got - S) <= bound + 1e-30).all()
+    finally:
+        cache.close()
+
+
+# ------------------------------------------------------------------ batches, layers, incremental append
+def test_batch_ragged_lengths_and_layers():
+    """B = 3 sequences of different length, 2 layers, token-by-token appends after a bulk import."""
+    dtype, Hq, Hkv, d, k = wl.BF16, 8, 2, 128, 200
+    lens = [30000, 17001, 150]
+    cache = ta.TopkAttnCache(2, 3, Hq, Hkv, d, 30010, k, dtype)
+    g = np.random.default_rng(11)
+    try:
+        data = {}
+        for layer in range(2):
+            for b, n in enumerate(lens):
+                q, K, V = rand_case(Hq, Hkv, n + 3, d, dtype, k, seed=100 * layer + b)
+                data[(layer, b)] = (q, K, V)
+                Kd, Vd = H.to_torch(K, dtype, DEV), H.to_torch(V, dtype, DEV)
+                cache.append(layer, b, Kd[:, :n].contiguous(), Vd[:, :n].contiguous(), head_major=True)
+                for t in range(n, n + 3):     # decode-time appends, token-major [1, Hkv, d]
+                    cache.append(layer, b, Kd[:, t:t + 1].permute(1, 0, 2).contiguous(),
+                                 Vd[:, t:t + 1].permute(1, 0, 2).contiguous())
+        for layer in range(2):
+            qd = torch.stack([H.to_torch(data[(layer, b)][0], dtype, DEV) for b in range(3)]).contiguous()
+            out, idx, vals, lse = cache.decode(layer, qd, k)
+            torch.cuda.synchronize()
+            for b, n in enumerate(lens):
+                q, K, V = data[(layer, b)]
+                ref = c_oracle.topk_attention(q, K, V, dtype, k)
+                delta = H.score_margin(q, K, dtype)
+                H.check_against_oracle(out[b].cpu().numpy(), idx[b].cpu().numpy(), vals[b].cpu().numpy(),
+                                       lse[b].cpu().numpy(), ref, delta, min(k, n + 3), 2e-3,
+                                       float(np.abs(wl.widen(V, dtype)).max()), f"layer {layer} seq {b}")
+    finally:
+        cache.close()
+
+
+def test_repeatable_index_sets():
+    """Two runs of the same decode give identical index sets and vals (no dependence on
+    the order in which waves append candidates)."""
+    w = wl.C2.scaled(50000)
+    q, K, V = wl.make_quantized(w, 4)
+    cache = ta.TopkAttnCache(1, 1, w.n_q_heads, w.n_kv_heads, w.head_dim, w.n_tokens, w.k, w.dtype)
+    try:
+        cache.append(0, 0, H.to_torch(K, w.dtype, DEV), H.to_torch(V, w.dtype, DEV), head_major=True)
+        qd = H.to_torch(q, w.dtype, DEV)[None].contiguous()
+        res = []
+        for _ in range(2):
+            out, idx, vals, _ = cache.decode(0, qd, w.k)
+            torch.cuda.synchronize()
+            o = torch.argsort(idx[0], dim=1)
+            res.append((torch.gather(idx[0], 1, o).cpu().numpy(), torch.gather(vals[0], 1, o).cpu().numpy()))
+        np.testing.assert_array_equal(res[0][0], res[1][0])
+        np.testing.assert_array_equal(res[0][1], res[1][1])
+    finally:
+        cache.close()
+
+
+# ------------------------------------------------------------------ benchmark configurations
+def test_c2_llama_layer_128k_bf16():
+    w = wl.C2
+    q, K, V = wl.make_quantized(w, 0)
+    K, _, _ = H.enforce_margin(q, K, w.dtype, w.k)
+    run_case(q, K, V, w.dtype, w.k, label="c2", expect_fallbacks=0)
+
+
+def test_c3_llama_layer_1m_fp16():
+    w = wl.C3
+    q, K, V = wl.make_quantized(w, 0)
+    K, _, _ = H.enforce_margin(q, K, w.dtype, w.k)
+    run_case(q, K, V, w.dtype, w.k, label="c3", expect_fallbacks=0)
