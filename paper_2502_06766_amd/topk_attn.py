@@ -57,6 +57,9 @@ def lib() -> ctypes.CDLL:
             raise RuntimeError(
                 f"{LIB_PATH} is missing: build it with `python -m paper_2502_06766_amd.build` "
                 "(hipcc, gfx950); there is no fallback path")
+        # PyTorch ships the HIP runtime that owns the tensors handed to the library; load it
+        # first so that the library binds to that same runtime instead of a second copy.
+        import torch  # noqa: F401
         L = ctypes.CDLL(LIB_PATH)
         vp, i32, i64, sz = ctypes.c_void_p, ctypes.c_int, ctypes.c_int64, ctypes.c_size_t
         cfgp = ctypes.POINTER(Config)
