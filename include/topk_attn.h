@@ -131,6 +131,15 @@ int topk_attn_set_path(topk_attn_t* h, int path);
  * recomputed by the full path.  Copies a few bytes device->host (synchronous). */
 int topk_attn_last_fallbacks(topk_attn_t* h, int* n_heads);
 
+/* Measurement aid: when enabled, every decode records a HIP event on its stream just
+ * before and just after the key-scan kernel (up to 512 decodes between two reads).
+ * Enabling creates the events (host resources only) and clears earlier records. */
+int topk_attn_set_scan_timing(topk_attn_t* h, int enable);
+
+/* After the caller has synchronised the stream: total milliseconds between the event
+ * pairs recorded since the last read and the number of pairs; clears the records. */
+int topk_attn_scan_time(topk_attn_t* h, double* total_ms, int* n_calls);
+
 /* Measurement aid: stream `bytes` (multiple of 16) from `src` (device) with 128-bit
  * loads and write one checksum word per workgroup to `sink` (device, >= 64 KiB).
  * Gives the read-bandwidth ceiling the key scan is compared against. */

@@ -20,7 +20,7 @@ inline size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
 inline int elem_bytes(int dtype) { return dtype == TOPK_ATTN_F32 ? 4 : 2; }
 
 struct WsLayout {
-    size_t len, thr, samp, cand_cnt, flags, hmax, fallback, cand, scores, sel_idx, sel_val, part_acc, part_l, total;
+    size_t len, thr, samp, seg_cnt, flags, hmax, fallback, cand, cand_flat, scores, sel_idx, sel_val, part_acc, part_l, total;
     int cand_cap, n_chunk_cap;
 };
 
@@ -56,11 +56,12 @@ WsLayout ws_layout(const topk_attn_config* c) {
     w.len = take((size_t)c->n_layers * c->n_seqs * sizeof(int32_t));
     w.thr = take(BH * sizeof(float));
     w.samp = take(BH * kSampMax * sizeof(float));
-    w.cand_cnt = take(BH * sizeof(uint32_t));
+    w.seg_cnt = take(BH * kMaxSeg * sizeof(uint32_t));
     w.flags = take(BH * sizeof(uint32_t));
     w.hmax = take(BH * sizeof(float));
     w.fallback = take(sizeof(uint32_t));
     w.cand = take(BH * (size_t)w.cand_cap * sizeof(uint64_t));
+    w.cand_flat = take(BH * (size_t)w.cand_cap * sizeof(uint64_t));
     w.scores = take(BH * (size_t)c->max_tokens * sizeof(float));
     w.sel_idx = take(BH * (size_t)c->max_k * sizeof(int32_t));   // stride is the requested k, up to max_k
     w.sel_val = take(BH * (size_t)c->max_k * sizeof(float));
@@ -109,6 +110,8 @@ __global__ void __launch_bounds__(256) read_probe_kernel(const u32x4* __restrict
 
 }  // namespace
 
+constexpr int kTimingSlots = 512;
+
 struct topk_attn {
     topk_attn_config cfg;
     WsLayout ws;
@@ -116,6 +119,11 @@ struct topk_attn {
     std::vector<int64_t> len;   // host mirror of the device lengths, [L][B]
     int path;
     bool last_fast;
+    int n_cu;                   // compute units of the device
+    // optional event pairs around the key scan of each decode (measurement only)
+    bool timing;
+    std::vector<hipEvent_t> ev;  // 2 * kTimingSlots once enabled
+    int ev_used;
 };
 
 extern "C" {
@@ -149,7 +157,12 @@ int topk_attn_create(const topk_attn_config* cfg, topk_attn_t** out) {
     h->len.assign((size_t)cfg->n_layers * cfg->n_seqs, 0);
     h->path = TOPK_ATTN_PATH_AUTO;
     h->last_fast = false;
+    h->timing = false;
+    h->ev_used = 0;
     if (hipSetDevice(cfg->device) != hipSuccess) { delete h; return TOPK_ATTN_EDEVICE; }
+    hipDeviceProp_t prop;
+    if (hipGetDeviceProperties(&prop, cfg->device) != hipSuccess) { delete h; return TOPK_ATTN_EDEVICE; }
+    h->n_cu = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
     // lengths and the small per-head control words start at zero
     if (hipMemset(cfg->workspace, 0, w.cand) != hipSuccess || hipDeviceSynchronize() != hipSuccess) {
         delete h;
@@ -161,6 +174,7 @@ int topk_attn_create(const topk_attn_config* cfg, topk_attn_t** out) {
 
 int topk_attn_destroy(topk_attn_t* h) {
     if (!h) return TOPK_ATTN_EINVAL;
+    for (hipEvent_t e : h->ev) (void)hipEventDestroy(e);
     delete h;
     return TOPK_ATTN_OK;
 }
@@ -225,7 +239,7 @@ static void fill_call(topk_attn_t* h, int layer, const void* q, int k, Shape* s,
     const int e = elem_bytes(c.dtype);
     s->B = c.n_seqs; s->Hq = c.n_q_heads; s->Hkv = c.n_kv_heads; s->G = c.n_q_heads / c.n_kv_heads;
     s->D = c.head_dim; s->dtype = c.dtype; s->k = k; s->max_k = c.max_k;
-    s->cand_cap = h->ws.cand_cap; s->samp_cap = kSampMax; s->n_chunk_cap = h->ws.n_chunk_cap;
+    s->cand_cap = h->ws.cand_cap; s->n_seg = 4; s->seg_cap = h->ws.cand_cap / 4; s->samp_cap = kSampMax; s->n_chunk_cap = h->ws.n_chunk_cap;
     s->Ncap = c.max_tokens;
     char* ws = static_cast<char*>(c.workspace);
     const size_t layer_b = (size_t)c.n_seqs * c.n_kv_heads * (size_t)c.max_tokens * c.head_dim * e;
@@ -235,10 +249,11 @@ static void fill_call(topk_attn_t* h, int layer, const void* q, int k, Shape* s,
     b->len = reinterpret_cast<int32_t*>(ws + h->ws.len) + (size_t)layer * c.n_seqs;
     b->thr = reinterpret_cast<float*>(ws + h->ws.thr);
     b->samp = reinterpret_cast<float*>(ws + h->ws.samp);
-    b->cand_cnt = reinterpret_cast<uint32_t*>(ws + h->ws.cand_cnt);
+    b->seg_cnt = reinterpret_cast<uint32_t*>(ws + h->ws.seg_cnt);
     b->flags = reinterpret_cast<uint32_t*>(ws + h->ws.flags);
     b->hmax = reinterpret_cast<float*>(ws + h->ws.hmax);
     b->cand = reinterpret_cast<uint64_t*>(ws + h->ws.cand);
+    b->cand_flat = reinterpret_cast<uint64_t*>(ws + h->ws.cand_flat);
     b->scores = reinterpret_cast<float*>(ws + h->ws.scores);
     b->sel_idx = reinterpret_cast<int32_t*>(ws + h->ws.sel_idx);
     b->sel_val = reinterpret_cast<float*>(ws + h->ws.sel_val);
@@ -246,6 +261,33 @@ static void fill_call(topk_attn_t* h, int layer, const void* q, int k, Shape* s,
     b->part_l = reinterpret_cast<float*>(ws + h->ws.part_l);
     b->out = nullptr; b->lse = nullptr;
     b->fallback_total = reinterpret_cast<uint32_t*>(ws + h->ws.fallback);
+}
+
+// Split of each head's candidate list into per-wave segments for the filtered scan:
+// about two 4-wave workgroups per compute unit over the whole grid, no more waves than
+// key tiles, and segments large enough for their share of the expected candidates plus
+// eight standard deviations.  False if no split fits (the caller takes the full path).
+static bool choose_segments(const topk_attn_t* h, const Shape& s, int64_t nmax, int64_t c_hi, int* n_seg,
+                            int* seg_cap) {
+    int64_t target_wgs = 2 * (int64_t)h->n_cu;
+    if (const char* e = getenv("TOPK_ATTN_SCAN_WGS")) target_wgs = atoll(e);
+    int64_t P = target_wgs / ((int64_t)s.B * s.Hkv);
+    const int64_t tiles = (nmax + 63) / 64;
+    if (P * 4 > tiles) P = tiles / 4;
+    if (P * 4 > kMaxSeg) P = kMaxSeg / 4;
+    if (P < 1) P = 1;
+    for (; P >= 1; P /= 2) {
+        const int64_t ns = P * 4;
+        const int64_t cap = s.cand_cap / ns;
+        const double mean = (double)c_hi / (double)ns;
+        if ((double)cap >= mean + 8.0 * sqrt(mean) + 32.0) {
+            *n_seg = (int)ns;
+            *seg_cap = (int)cap;
+            return true;
+        }
+        if (P == 1) break;
+    }
+    return false;
 }
 
 static int lengths_of(const topk_attn_t* h, int layer, int64_t* nmin, int64_t* nmax) {
@@ -278,22 +320,33 @@ int topk_attn_decode(topk_attn_t* h, int layer, const void* q, int k, float* out
     bool fast = false;
     if (h->path != TOPK_ATTN_PATH_FULL && scan_mfma_supported(s)) {
         fast = true;
+        int64_t c_hi = 0;
         for (int i = 0; i < s.B && fast; ++i) {
             const int64_t n = h->len[(size_t)layer * s.B + i];
             const int ke = k < n ? k : (int)n;
-            fast = plan_is_fast(make_plan(n, ke), n, s.cand_cap, h->path == TOPK_ATTN_PATH_FILTER);
+            const Plan pl = make_plan(n, ke);
+            fast = plan_is_fast(pl, n, s.cand_cap, h->path == TOPK_ATTN_PATH_FILTER);
+            c_hi = pl.c_hi > c_hi ? pl.c_hi : c_hi;
         }
+        if (fast) fast = choose_segments(h, s, nmax, c_hi, &s.n_seg, &s.seg_cap);
     }
     hipError_t e = hipSuccess;
+    const bool timed = h->timing && h->ev_used < kTimingSlots;
     if (fast) {
         e = launch_scan_sample(s, b, nmax, st);
         if (e == hipSuccess) e = launch_threshold(s, b, st);
+        if (e == hipSuccess && timed) e = hipEventRecord(h->ev[2 * h->ev_used], st);
         if (e == hipSuccess) e = launch_scan_filter(s, b, nmax, st);
+        if (e == hipSuccess && timed) e = hipEventRecord(h->ev[2 * h->ev_used + 1], st);
+        if (e == hipSuccess && timed) h->ev_used++;
         if (e == hipSuccess) e = launch_select_candidates(s, b, st);
         if (e == hipSuccess) e = launch_scan_full(s, b, nmax, true, b.scores, st);
         if (e == hipSuccess) e = launch_select_full(s, b, true, st);
     } else {
-        e = launch_scan_full(s, b, nmax, false, b.scores, st);
+        if (timed) e = hipEventRecord(h->ev[2 * h->ev_used], st);
+        if (e == hipSuccess) e = launch_scan_full(s, b, nmax, false, b.scores, st);
+        if (e == hipSuccess && timed) e = hipEventRecord(h->ev[2 * h->ev_used + 1], st);
+        if (e == hipSuccess && timed) h->ev_used++;
         if (e == hipSuccess) e = launch_select_full(s, b, false, st);
     }
     if (e == hipSuccess) e = launch_gather(s, b, st);
@@ -322,6 +375,37 @@ int topk_attn_last_fallbacks(topk_attn_t* h, int* n_heads) {
         hipSuccess)
         return TOPK_ATTN_EDEVICE;
     *n_heads = (int)v;
+    return TOPK_ATTN_OK;
+}
+
+int topk_attn_set_scan_timing(topk_attn_t* h, int enable) {
+    if (!h) return TOPK_ATTN_EINVAL;
+    if (enable && h->ev.empty()) {
+        h->ev.resize(2 * kTimingSlots);
+        for (size_t i = 0; i < h->ev.size(); ++i) {
+            if (hipEventCreate(&h->ev[i]) != hipSuccess) {
+                for (size_t j = 0; j < i; ++j) (void)hipEventDestroy(h->ev[j]);
+                h->ev.clear();
+                return TOPK_ATTN_EDEVICE;
+            }
+        }
+    }
+    h->timing = enable != 0;
+    h->ev_used = 0;
+    return TOPK_ATTN_OK;
+}
+
+int topk_attn_scan_time(topk_attn_t* h, double* total_ms, int* n_calls) {
+    if (!h || !total_ms || !n_calls) return TOPK_ATTN_EINVAL;
+    double sum = 0.0;
+    for (int i = 0; i < h->ev_used; ++i) {
+        float ms = 0.f;
+        if (hipEventElapsedTime(&ms, h->ev[2 * i], h->ev[2 * i + 1]) != hipSuccess) return TOPK_ATTN_EDEVICE;
+        sum += ms;
+    }
+    *total_ms = sum;
+    *n_calls = h->ev_used;
+    h->ev_used = 0;
     return TOPK_ATTN_OK;
 }
 

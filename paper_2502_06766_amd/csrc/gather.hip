@@ -73,15 +73,27 @@ __global__ void __launch_bounds__(256) gather_combine_kernel(Shape sh, Bufs bf, 
     const int64_t N = bf.len[b];
     const int k_eff = sh.k < N ? sh.k : (int)N;
     const int nch = (k_eff + kGatherRows - 1) / kGatherRows;
+    // 256 / D threads share an output element, each adds every (256 / D)-th partial
+    const int parts = 256 / D, e = threadIdx.x % D, part = threadIdx.x / D;
+    __shared__ float red[256];
+    __shared__ float lred[256];
+    const float* pa = bf.part_acc + bh * sh.n_chunk_cap * (int64_t)D + e;
+    float a = 0.f;
+#pragma unroll 8
+    for (int ch = part; ch < nch; ch += parts) a += pa[(int64_t)ch * D];
     float l = 0.f;
-    for (int ch = 0; ch < nch; ++ch) l += bf.part_l[bh * sh.n_chunk_cap + ch];
-    const float inv = 1.0f / l;
-    for (int t = threadIdx.x; t < D; t += blockDim.x) {
-        float a = 0.f;
-        for (int ch = 0; ch < nch; ++ch) a += bf.part_acc[(bh * sh.n_chunk_cap + ch) * D + t];
-        bf.out[bh * D + t] = a * inv;
+    for (int ch = threadIdx.x; ch < nch; ch += 256) l += bf.part_l[bh * sh.n_chunk_cap + ch];
+    red[threadIdx.x] = a;
+    lred[threadIdx.x] = l;
+    __syncthreads();
+    if (threadIdx.x < D) {
+        float lt = 0.f;
+        for (int i = 0; i < 256; ++i) lt += lred[i];      // fixed order
+        float at = 0.f;
+        for (int p = 0; p < parts; ++p) at += red[p * D + e];
+        bf.out[bh * D + e] = at / lt;
+        if (threadIdx.x == 0 && bf.lse) bf.lse[bh] = bf.hmax[bh] * scale + logf(lt);
     }
-    if (threadIdx.x == 0 && bf.lse) bf.lse[bh] = bf.hmax[bh] * scale + logf(l);
 }
 
 hipError_t launch_gather(const Shape& s, const Bufs& b, hipStream_t st) {

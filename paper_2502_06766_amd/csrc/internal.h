@@ -13,6 +13,7 @@ constexpr int kGatherRows = 256;    // value rows handled by one gather workgrou
 constexpr int kSampMax = 16384;     // most sample scores per head in the threshold estimate
 constexpr int kSampMin = 1024;
 constexpr int kFilterMinN = 16384;  // below this the full path is used
+constexpr int kMaxSeg = 1024;       // most candidate segments per head
 
 // Geometry of one decode call, passed by value to every kernel.
 struct Shape {
@@ -20,6 +21,8 @@ struct Shape {
     int k;            // requested k (k_eff = min(k, len[b]) per sequence)
     int max_k;
     int cand_cap;     // entries per (b, head) candidate list
+    int n_seg;        // segments the candidate list is split in (one per scanning wave)
+    int seg_cap;      // entries per segment (n_seg * seg_cap <= cand_cap)
     int samp_cap;     // entries per (b, head) sample-score row
     int n_chunk_cap;  // partial-sum slots per (b, head)
     int64_t Ncap;     // row capacity per (layer, seq, kv head)
@@ -33,10 +36,11 @@ struct Bufs {
     const int32_t* len;     // [B] tokens cached per sequence (this layer)
     float* thr;             // [B*Hq] candidate threshold
     float* samp;            // [B*Hq][samp_cap]
-    uint32_t* cand_cnt;     // [B*Hq]
+    uint32_t* seg_cnt;      // [B*Hq][n_seg] candidates each scanning wave found (may exceed seg_cap)
     uint32_t* flags;        // [B*Hq] 1 = candidate list unusable, use the full path
     float* hmax;            // [B*Hq] largest selected score
-    uint64_t* cand;         // [B*Hq][cand_cap] (score bits << 32 | position)
+    uint64_t* cand;         // [B*Hq][cand_cap] (score bits << 32 | position), n_seg segments
+    uint64_t* cand_flat;    // [B*Hq][cand_cap] the segments packed back to back
     float* scores;          // [B*Hq][Ncap] full score buffer
     int32_t* sel_idx;       // [B*Hq][k]
     float* sel_val;         // [B*Hq][k]

@@ -11,8 +11,9 @@
 //
 // Three uses of the same tile routine:
 //   sample : score a strided, jittered sample of positions (threshold estimate)
-//   filter : score every key, keep (score, position) pairs >= a per-head threshold in a
-//            per-wave LDS list, flushed to the head's global candidate list
+//   filter : score every key, keep (score, position) pairs >= a per-head threshold; every
+//            wave appends to a private segment of the head's candidate list (plain stores,
+//            no atomics, so the list order is fixed by the launch geometry alone)
 //   full   : score every key and store the fp32 scores
 // Other dtypes / head groupings go through a plain FMA kernel (full only).
 #include "device_utils.h"
@@ -34,9 +35,12 @@ template <> struct Mfma<DT_BF16> {
     }
 };
 
+#ifndef TKA_SCAN_PIPELINE
+#define TKA_SCAN_PIPELINE 1   // 1: loads of tile t+1 overlap the MFMAs of tile t within a wave
+#endif
+
 enum { MODE_SAMPLE = 0, MODE_FILTER = 1, MODE_FULL = 2 };
 constexpr int kScanWaves = 4;     // waves per scan workgroup
-constexpr int kCandLds = 128;     // per-wave, per-head LDS candidate slots
 
 // Query block of the group in operand-A layout: lane (j, m) holds channels
 // 32 s + 8 j .. +7 of head m % 4 (zero for heads the group does not have).
@@ -55,16 +59,15 @@ __device__ __forceinline__ void load_query_a(const void* q, int64_t head0, int G
     }
 }
 
-// Scores of 64 keys: lane l gets res[r] = q_{head0 + r} . K[row(l)], rows given per
-// 16-key sub-tile by rowfn(slot).
+// Operand B of a 64-key tile: for each 16-key sub-tile g, lane (j, n) loads the 16-byte
+// chunks 4 s + j (s = 0 .. D/32-1) of the row rowfn(16 g + n).  All loads are issued
+// before anything consumes them.
 template <int DT, int D, class RowFn>
-__device__ __forceinline__ f32x4 tile_scores(const char* Kh, RowFn rowfn,
-                                             const typename Mfma<DT>::v8 (&qa)[D / 32]) {
+__device__ __forceinline__ void tile_load(const char* Kh, RowFn rowfn, typename Mfma<DT>::v8 (&b)[4][D / 32]) {
     using v8 = typename Mfma<DT>::v8;
     constexpr int KS = D / 32;
     const int lane = lane_id();
     const int j = lane >> 4, n = lane & 15;
-    v8 b[4][KS];
 #pragma unroll
     for (int g = 0; g < 4; ++g) {
         const int64_t row = rowfn(16 * g + n);
@@ -72,6 +75,14 @@ __device__ __forceinline__ f32x4 tile_scores(const char* Kh, RowFn rowfn,
 #pragma unroll
         for (int s = 0; s < KS; ++s) b[g][s] = p[4 * s];
     }
+}
+
+// Scores of the tile: lane l gets res[r] = q_{head0 + r} . K[row(l)].
+template <int DT, int D>
+__device__ __forceinline__ f32x4 tile_mac(const typename Mfma<DT>::v8 (&b)[4][D / 32],
+                                          const typename Mfma<DT>::v8 (&qa)[D / 32]) {
+    constexpr int KS = D / 32;
+    const int j = lane_id() >> 4;
     f32x4 c[4];
 #pragma unroll
     for (int g = 0; g < 4; ++g) {
@@ -90,33 +101,17 @@ __device__ __forceinline__ f32x4 tile_scores(const char* Kh, RowFn rowfn,
     return res;
 }
 
-__device__ __forceinline__ void flush_candidates(uint64_t* seg, int cnt, uint32_t* gcnt, uint64_t* gcand,
-                                                 int cap) {
-    wave_sync();
-    const int lane = lane_id();
-    uint32_t base = 0;
-    if (lane == 0) base = atomicAdd(gcnt, (uint32_t)cnt);
-    base = wave_first_u32(base);
-    for (int i = lane; i < cnt; i += kWave) {
-        if (base + (uint32_t)i < (uint32_t)cap) gcand[base + i] = seg[i];
-    }
-    wave_sync();
-}
-
-// Keep the keys of one head whose score reaches the head's threshold.
+// Keep the keys of one head whose score reaches the head's threshold: lanes that pass
+// append (score bits, position) to the wave's segment of the head's candidate list.
 __device__ __forceinline__ void filter_head(float score, float thr, int& cnt, bool valid, int64_t item,
-                                            uint64_t* seg, uint32_t* gcnt, uint64_t* gcand, int cap) {
+                                            uint64_t* seg, int seg_cap) {
     const float sc = score + 0.0f;
     const bool pass = valid && sc >= thr;
     const uint64_t m = __ballot(pass);
     if (m) {
-        const int add = __popcll(m);
-        if (cnt + add > kCandLds) {
-            flush_candidates(seg, cnt, gcnt, gcand, cap);
-            cnt = 0;
-        }
-        if (pass) seg[cnt + mask_rank(m)] = ((uint64_t)__float_as_uint(sc) << 32) | (uint64_t)(uint32_t)item;
-        cnt += add;
+        const int slot = cnt + mask_rank(m);
+        if (pass && slot < seg_cap) seg[slot] = ((uint64_t)__float_as_uint(sc) << 32) | (uint64_t)(uint32_t)item;
+        cnt += __popcll(m);   // keeps counting past the capacity: the selection sees the overflow
     }
 }
 
@@ -144,18 +139,33 @@ scan_mfma_kernel(Shape sh, Bufs bf, int tiles_per_wave, int only_flagged, float*
         n_items = pl.n_samp;
         stride = pl.stride;
     }
-    const int64_t tile0 = (int64_t)blockIdx.x * tiles_per_wave * kScanWaves;
-    if (tile0 * 64 >= n_items) return;
+    // tiles of this wave.  sample/full: a workgroup owns a contiguous run of tiles and its
+    // waves take them round-robin.  filter: wave-segment sid = 4 blockIdx.x + wave takes the
+    // tiles sid, sid + n_seg, ... so that any clustering of high scores along the sequence
+    // spreads evenly over the segments.
+    const int64_t n_tiles_all = (n_items + 63) / 64;
+    int64_t tile, tile_end, tile_step;
+    if (MODE == MODE_FILTER) {
+        tile = (int64_t)blockIdx.x * kScanWaves + wave;
+        tile_step = (int64_t)gridDim.x * kScanWaves;
+        tile_end = n_tiles_all;
+    } else {
+        const int64_t tile0 = (int64_t)blockIdx.x * tiles_per_wave * kScanWaves;
+        if (tile0 >= n_tiles_all) return;   // whole workgroup past the end
+        tile = tile0 + wave;
+        tile_step = kScanWaves;
+        tile_end = tile0 + (int64_t)tiles_per_wave * kScanWaves;
+        if (tile_end > n_tiles_all) tile_end = n_tiles_all;
+    }
 
     v8 qa[D / 32];
     load_query_a<DT, D>(bf.q, head0, G, qa);
     const char* Kh = static_cast<const char*>(bf.K) + ((int64_t)b * sh.Hkv + kvh) * sh.Ncap * (D * 2);
 
-    __shared__ uint64_t cand_lds[MODE == MODE_FILTER ? kScanWaves * 4 * kCandLds : 1];
-    uint64_t* const seg0 = cand_lds + (MODE == MODE_FILTER ? wave * 4 * kCandLds : 0);
-    uint32_t* const gcnt0 = bf.cand_cnt + head0;
-    const int cap = sh.cand_cap;
-    uint64_t* const gcand0 = bf.cand + head0 * (int64_t)cap;
+    // filter: this wave's segment in each head's candidate list
+    const int seg_cap = sh.seg_cap;
+    const int sid = (int)blockIdx.x * kScanWaves + wave;
+    uint64_t* const seg0 = bf.cand + head0 * (int64_t)sh.cand_cap + (int64_t)sid * seg_cap;
     float thr0 = 0.f, thr1 = 0.f, thr2 = 0.f, thr3 = 0.f;
     int cnt0 = 0, cnt1 = 0, cnt2 = 0, cnt3 = 0;
     if (MODE == MODE_FILTER) {
@@ -165,24 +175,16 @@ scan_mfma_kernel(Shape sh, Bufs bf, int tiles_per_wave, int only_flagged, float*
         if (3 < G) thr3 = bf.thr[head0 + 3];
     }
 
-    for (int it = 0; it < tiles_per_wave; ++it) {
-        const int64_t tile = tile0 + (int64_t)it * kScanWaves + wave;
-        const int64_t item0 = tile * 64;
-        if (item0 >= n_items) break;   // wave-uniform
-        f32x4 res;
+    // row of tile slot `slot` for the tile starting at item `item0`
+    auto row_of = [&](int64_t item0, int slot) -> int64_t {
+        int64_t p = item0 + slot;
         if (MODE == MODE_SAMPLE) {
-            res = tile_scores<DT, D>(Kh, [&](int slot) {
-                int64_t s = item0 + slot;
-                if (s > n_items - 1) s = n_items - 1;
-                int64_t p = sample_pos((int)s, stride);
-                return p < N ? p : N - 1;
-            }, qa);
-        } else {
-            res = tile_scores<DT, D>(Kh, [&](int slot) {
-                int64_t p = item0 + slot;
-                return p < N ? p : N - 1;
-            }, qa);
+            if (p > n_items - 1) p = n_items - 1;
+            p = sample_pos((int)p, stride);
         }
+        return p < N ? p : N - 1;
+    };
+    auto consume = [&](const f32x4& res, int64_t item0) {
         const int64_t item = item0 + lane;
         const bool valid = item < n_items;
         if (MODE == MODE_SAMPLE) {
@@ -194,17 +196,43 @@ scan_mfma_kernel(Shape sh, Bufs bf, int tiles_per_wave, int only_flagged, float*
             for (int r = 0; r < 4; ++r)
                 if (r < G && valid) dst[(head0 + r) * sh.Ncap + item] = res[r];
         } else {
-            if (0 < G) filter_head(res[0], thr0, cnt0, valid, item, seg0 + 0 * kCandLds, gcnt0 + 0, gcand0 + 0 * (int64_t)cap, cap);
-            if (1 < G) filter_head(res[1], thr1, cnt1, valid, item, seg0 + 1 * kCandLds, gcnt0 + 1, gcand0 + 1 * (int64_t)cap, cap);
-            if (2 < G) filter_head(res[2], thr2, cnt2, valid, item, seg0 + 2 * kCandLds, gcnt0 + 2, gcand0 + 2 * (int64_t)cap, cap);
-            if (3 < G) filter_head(res[3], thr3, cnt3, valid, item, seg0 + 3 * kCandLds, gcnt0 + 3, gcand0 + 3 * (int64_t)cap, cap);
+            if (0 < G) filter_head(res[0], thr0, cnt0, valid, item, seg0 + 0 * (int64_t)sh.cand_cap, seg_cap);
+            if (1 < G) filter_head(res[1], thr1, cnt1, valid, item, seg0 + 1 * (int64_t)sh.cand_cap, seg_cap);
+            if (2 < G) filter_head(res[2], thr2, cnt2, valid, item, seg0 + 2 * (int64_t)sh.cand_cap, seg_cap);
+            if (3 < G) filter_head(res[3], thr3, cnt3, valid, item, seg0 + 3 * (int64_t)sh.cand_cap, seg_cap);
         }
+    };
+
+    // the next tile's loads are in flight while the current one is multiplied and filtered
+#if TKA_SCAN_PIPELINE
+    v8 ba[4][D / 32], bb[4][D / 32];
+    if (tile < tile_end) tile_load<DT, D>(Kh, [&](int slot) { return row_of(tile * 64, slot); }, ba);
+    while (tile < tile_end) {
+        const int64_t t1 = tile + tile_step;
+        if (t1 < tile_end) tile_load<DT, D>(Kh, [&](int slot) { return row_of(t1 * 64, slot); }, bb);
+        __builtin_amdgcn_sched_barrier(0);
+        consume(tile_mac<DT, D>(ba, qa), tile * 64);
+        if (t1 >= tile_end) break;
+        const int64_t t2 = t1 + tile_step;
+        if (t2 < tile_end) tile_load<DT, D>(Kh, [&](int slot) { return row_of(t2 * 64, slot); }, ba);
+        __builtin_amdgcn_sched_barrier(0);
+        consume(tile_mac<DT, D>(bb, qa), t1 * 64);
+        tile = t2;
     }
-    if (MODE == MODE_FILTER) {
-        if (cnt0 > 0) flush_candidates(seg0, cnt0, gcnt0, gcand0, cap);
-        if (cnt1 > 0) flush_candidates(seg0 + kCandLds, cnt1, gcnt0 + 1, gcand0 + (int64_t)cap, cap);
-        if (cnt2 > 0) flush_candidates(seg0 + 2 * kCandLds, cnt2, gcnt0 + 2, gcand0 + 2 * (int64_t)cap, cap);
-        if (cnt3 > 0) flush_candidates(seg0 + 3 * kCandLds, cnt3, gcnt0 + 3, gcand0 + 3 * (int64_t)cap, cap);
+#else
+    for (; tile < tile_end; tile += tile_step) {
+        v8 ba[4][D / 32];
+        tile_load<DT, D>(Kh, [&](int slot) { return row_of(tile * 64, slot); }, ba);
+        __builtin_amdgcn_sched_barrier(0);
+        consume(tile_mac<DT, D>(ba, qa), tile * 64);
+    }
+#endif
+    if (MODE == MODE_FILTER && lane == 0) {
+        uint32_t* sc = bf.seg_cnt + head0 * (int64_t)sh.n_seg + sid;
+        sc[0] = (uint32_t)cnt0;
+        if (1 < G) sc[sh.n_seg] = (uint32_t)cnt1;
+        if (2 < G) sc[2 * (int64_t)sh.n_seg] = (uint32_t)cnt2;
+        if (3 < G) sc[3 * (int64_t)sh.n_seg] = (uint32_t)cnt3;
     }
 }
 
@@ -303,7 +331,19 @@ hipError_t launch_scan_sample(const Shape& s, const Bufs& b, int64_t Nmax, hipSt
 }
 
 hipError_t launch_scan_filter(const Shape& s, const Bufs& b, int64_t Nmax, hipStream_t st) {
-    return launch_mfma<MODE_FILTER>(s, b, Nmax, false, nullptr, st);
+    (void)Nmax;
+    // one wave per candidate segment: n_seg / 4 workgroups per KV head
+    dim3 grid((unsigned)(s.n_seg / kScanWaves), (unsigned)s.Hkv, (unsigned)s.B);
+    dim3 block(kScanWaves * kWave);
+#define TKA_LAUNCH(DT_, D_) \
+    hipLaunchKernelGGL((scan_mfma_kernel<DT_, D_, MODE_FILTER>), grid, block, 0, st, s, b, 0, 0, (float*)nullptr)
+    if (s.dtype == DT_F16 && s.D == 128) TKA_LAUNCH(DT_F16, 128);
+    else if (s.dtype == DT_F16 && s.D == 64) TKA_LAUNCH(DT_F16, 64);
+    else if (s.dtype == DT_BF16 && s.D == 128) TKA_LAUNCH(DT_BF16, 128);
+    else if (s.dtype == DT_BF16 && s.D == 64) TKA_LAUNCH(DT_BF16, 64);
+    else return hipErrorInvalidValue;
+#undef TKA_LAUNCH
+    return hipGetLastError();
 }
 
 hipError_t launch_scan_full(const Shape& s, const Bufs& b, int64_t Nmax, bool only_flagged, float* dst,

@@ -12,7 +12,8 @@ import os
 from typing import Optional
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libtopk_attn.so")
+# TOPK_ATTN_LIB selects another build of the same library (A/B measurements)
+LIB_PATH = os.environ.get("TOPK_ATTN_LIB") or os.path.join(_HERE, "libtopk_attn.so")
 
 OK, EINVAL, ECAPACITY, EUNSUPPORTED, EDEVICE, ENOMEM = range(6)
 F32, F16, BF16 = 0, 1, 2
@@ -21,7 +22,7 @@ PATH_AUTO, PATH_FULL, PATH_FILTER = 0, 1, 2
 EXPORTS = [
     "topk_attn_kv_bytes", "topk_attn_workspace_bytes", "topk_attn_create", "topk_attn_append_kv",
     "topk_attn_decode", "topk_attn_scores", "topk_attn_length", "topk_attn_reset", "topk_attn_set_path",
-    "topk_attn_last_fallbacks", "topk_attn_read_probe", "topk_attn_strerror", "topk_attn_destroy",
+    "topk_attn_last_fallbacks", "topk_attn_set_scan_timing", "topk_attn_scan_time", "topk_attn_read_probe", "topk_attn_strerror", "topk_attn_destroy",
 ]
 
 
@@ -83,6 +84,10 @@ def lib() -> ctypes.CDLL:
         L.topk_attn_set_path.restype = i32
         L.topk_attn_last_fallbacks.argtypes = [vp, ctypes.POINTER(i32)]
         L.topk_attn_last_fallbacks.restype = i32
+        L.topk_attn_set_scan_timing.argtypes = [vp, i32]
+        L.topk_attn_set_scan_timing.restype = i32
+        L.topk_attn_scan_time.argtypes = [vp, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(i32)]
+        L.topk_attn_scan_time.restype = i32
         L.topk_attn_read_probe.argtypes = [vp, sz, vp, vp]
         L.topk_attn_read_probe.restype = i32
         L.topk_attn_strerror.argtypes = [i32]
@@ -163,6 +168,17 @@ def topk_attn_last_fallbacks(h) -> int:
     n = ctypes.c_int(0)
     _check(lib().topk_attn_last_fallbacks(h, ctypes.byref(n)), "topk_attn_last_fallbacks")
     return n.value
+
+
+def topk_attn_set_scan_timing(h, enable: bool):
+    _check(lib().topk_attn_set_scan_timing(h, 1 if enable else 0), "topk_attn_set_scan_timing")
+
+
+def topk_attn_scan_time(h):
+    """(total_ms, n_calls) of the key-scan kernel since the last read; sync the stream first."""
+    ms, n = ctypes.c_double(0.0), ctypes.c_int(0)
+    _check(lib().topk_attn_scan_time(h, ctypes.byref(ms), ctypes.byref(n)), "topk_attn_scan_time")
+    return ms.value, n.value
 
 
 def topk_attn_read_probe(src_ptr, nbytes, sink_ptr, stream=0):
