@@ -20,7 +20,7 @@ inline size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
 inline int elem_bytes(int dtype) { return dtype == TOPK_ATTN_F32 ? 4 : 2; }
 
 struct WsLayout {
-    size_t len, thr, samp, seg_cnt, flags, hmax, fallback, cand, cand_flat, scores, sel_idx, sel_val, part_acc, part_l, total;
+    size_t len, thr, samp, seg_cnt, flags, hmax, fallback, cand, scores, sel_idx, sel_val, part_acc, part_l, total;
     int cand_cap, n_chunk_cap;
 };
 
@@ -61,7 +61,6 @@ WsLayout ws_layout(const topk_attn_config* c) {
     w.hmax = take(BH * sizeof(float));
     w.fallback = take(sizeof(uint32_t));
     w.cand = take(BH * (size_t)w.cand_cap * sizeof(uint64_t));
-    w.cand_flat = take(BH * (size_t)w.cand_cap * sizeof(uint64_t));
     w.scores = take(BH * (size_t)c->max_tokens * sizeof(float));
     w.sel_idx = take(BH * (size_t)c->max_k * sizeof(int32_t));   // stride is the requested k, up to max_k
     w.sel_val = take(BH * (size_t)c->max_k * sizeof(float));
@@ -253,7 +252,6 @@ static void fill_call(topk_attn_t* h, int layer, const void* q, int k, Shape* s,
     b->flags = reinterpret_cast<uint32_t*>(ws + h->ws.flags);
     b->hmax = reinterpret_cast<float*>(ws + h->ws.hmax);
     b->cand = reinterpret_cast<uint64_t*>(ws + h->ws.cand);
-    b->cand_flat = reinterpret_cast<uint64_t*>(ws + h->ws.cand_flat);
     b->scores = reinterpret_cast<float*>(ws + h->ws.scores);
     b->sel_idx = reinterpret_cast<int32_t*>(ws + h->ws.sel_idx);
     b->sel_val = reinterpret_cast<float*>(ws + h->ws.sel_val);
@@ -276,6 +274,7 @@ static bool choose_segments(const topk_attn_t* h, const Shape& s, int64_t nmax, 
     if (P * 4 > tiles) P = tiles / 4;
     if (P * 4 > kMaxSeg) P = kMaxSeg / 4;
     if (P < 1) P = 1;
+    while (P & (P - 1)) P &= P - 1;          // power of two: the selection indexes segments by mask
     for (; P >= 1; P /= 2) {
         const int64_t ns = P * 4;
         const int64_t cap = s.cand_cap / ns;

@@ -8,7 +8,10 @@ namespace tka {
 enum { DT_F32 = 0, DT_F16 = 1, DT_BF16 = 2 };
 
 constexpr int kWave = 64;
-constexpr int kSelThreads = 1024;   // workgroup size of the selection kernels
+#ifndef TKA_SEL_THREADS
+#define TKA_SEL_THREADS 1024
+#endif
+constexpr int kSelThreads = TKA_SEL_THREADS;   // workgroup size of the selection kernels
 constexpr int kGatherRows = 256;    // value rows handled by one gather workgroup
 constexpr int kSampMax = 16384;     // most sample scores per head in the threshold estimate
 constexpr int kSampMin = 1024;
@@ -21,7 +24,7 @@ struct Shape {
     int k;            // requested k (k_eff = min(k, len[b]) per sequence)
     int max_k;
     int cand_cap;     // entries per (b, head) candidate list
-    int n_seg;        // segments the candidate list is split in (one per scanning wave)
+    int n_seg;        // segments the candidate list is split in (one per scanning wave), power of 2
     int seg_cap;      // entries per segment (n_seg * seg_cap <= cand_cap)
     int samp_cap;     // entries per (b, head) sample-score row
     int n_chunk_cap;  // partial-sum slots per (b, head)
@@ -39,8 +42,8 @@ struct Bufs {
     uint32_t* seg_cnt;      // [B*Hq][n_seg] candidates each scanning wave found (may exceed seg_cap)
     uint32_t* flags;        // [B*Hq] 1 = candidate list unusable, use the full path
     float* hmax;            // [B*Hq] largest selected score
-    uint64_t* cand;         // [B*Hq][cand_cap] (score bits << 32 | position), n_seg segments
-    uint64_t* cand_flat;    // [B*Hq][cand_cap] the segments packed back to back
+    uint64_t* cand;         // [B*Hq][cand_cap] (score bits << 32 | position); entry e of segment g
+                            // at [e * n_seg + g]
     float* scores;          // [B*Hq][Ncap] full score buffer
     int32_t* sel_idx;       // [B*Hq][k]
     float* sel_val;         // [B*Hq][k]

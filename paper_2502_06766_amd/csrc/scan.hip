@@ -101,17 +101,40 @@ __device__ __forceinline__ f32x4 tile_mac(const typename Mfma<DT>::v8 (&b)[4][D 
     return res;
 }
 
-// Keep the keys of one head whose score reaches the head's threshold: lanes that pass
-// append (score bits, position) to the wave's segment of the head's candidate list.
-__device__ __forceinline__ void filter_head(float score, float thr, int& cnt, bool valid, int64_t item,
-                                            uint64_t* seg, int seg_cap) {
+constexpr int kStage = 128;   // LDS staging slots per (wave, head)
+
+// Candidates of one (wave, head): staged in LDS, appended to the wave's private segment
+// of the head's global list in bursts.  Global stores in the tile loop would sit between
+// the key loads in the wave's in-order memory queue and stall the prefetch.
+struct CandStage {
+    uint64_t* lds;      // kStage slots
+    uint64_t* seg;      // this wave's entry 0 in the head's interleaved list (entry e at seg[e * n_seg])
+    int n_lds;          // staged entries (wave-uniform)
+    int n_glob;         // entries already appended, may run past seg_cap (overflow is detected later)
+};
+
+__device__ __forceinline__ void stage_flush(CandStage& c, int seg_cap, int n_seg) {
+    wave_sync();
+    for (int i = lane_id(); i < c.n_lds; i += kWave) {
+        const int slot = c.n_glob + i;
+        if (slot < seg_cap) c.seg[(int64_t)slot * n_seg] = c.lds[i];
+    }
+    wave_sync();
+    c.n_glob += c.n_lds;
+    c.n_lds = 0;
+}
+
+// Keep the keys of one head whose score reaches the head's threshold.
+__device__ __forceinline__ void filter_head(float score, float thr, CandStage& c, bool valid, int64_t item,
+                                            int seg_cap, int n_seg) {
     const float sc = score + 0.0f;
     const bool pass = valid && sc >= thr;
     const uint64_t m = __ballot(pass);
     if (m) {
-        const int slot = cnt + mask_rank(m);
-        if (pass && slot < seg_cap) seg[slot] = ((uint64_t)__float_as_uint(sc) << 32) | (uint64_t)(uint32_t)item;
-        cnt += __popcll(m);   // keeps counting past the capacity: the selection sees the overflow
+        const int add = __popcll(m);
+        if (c.n_lds + add > kStage) stage_flush(c, seg_cap, n_seg);
+        if (pass) c.lds[c.n_lds + mask_rank(m)] = ((uint64_t)__float_as_uint(sc) << 32) | (uint64_t)(uint32_t)item;
+        c.n_lds += add;
     }
 }
 
@@ -123,7 +146,7 @@ scan_mfma_kernel(Shape sh, Bufs bf, int tiles_per_wave, int only_flagged, float*
     const int G = sh.G;
     const int64_t head0 = (int64_t)b * sh.Hq + (int64_t)kvh * G;
     const int lane = lane_id();
-    const int wave = threadIdx.x >> 6;
+    const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));   // wave-uniform
     const int64_t N = bf.len[b];
 
     if (MODE == MODE_FULL && only_flagged) {
@@ -165,9 +188,13 @@ scan_mfma_kernel(Shape sh, Bufs bf, int tiles_per_wave, int only_flagged, float*
     // filter: this wave's segment in each head's candidate list
     const int seg_cap = sh.seg_cap;
     const int sid = (int)blockIdx.x * kScanWaves + wave;
-    uint64_t* const seg0 = bf.cand + head0 * (int64_t)sh.cand_cap + (int64_t)sid * seg_cap;
+    uint64_t* const seg0 = bf.cand + head0 * (int64_t)sh.cand_cap + sid;
+    __shared__ uint64_t stage_lds[MODE == MODE_FILTER ? kScanWaves * 4 * kStage : 1];
+    uint64_t* const st0 = stage_lds + (MODE == MODE_FILTER ? wave * 4 * kStage : 0);
+    CandStage cs0{st0, seg0, 0, 0}, cs1{st0 + kStage, seg0 + (int64_t)sh.cand_cap, 0, 0},
+        cs2{st0 + 2 * kStage, seg0 + 2 * (int64_t)sh.cand_cap, 0, 0},
+        cs3{st0 + 3 * kStage, seg0 + 3 * (int64_t)sh.cand_cap, 0, 0};
     float thr0 = 0.f, thr1 = 0.f, thr2 = 0.f, thr3 = 0.f;
-    int cnt0 = 0, cnt1 = 0, cnt2 = 0, cnt3 = 0;
     if (MODE == MODE_FILTER) {
         thr0 = bf.thr[head0];
         if (1 < G) thr1 = bf.thr[head0 + 1];
@@ -196,28 +223,35 @@ scan_mfma_kernel(Shape sh, Bufs bf, int tiles_per_wave, int only_flagged, float*
             for (int r = 0; r < 4; ++r)
                 if (r < G && valid) dst[(head0 + r) * sh.Ncap + item] = res[r];
         } else {
-            if (0 < G) filter_head(res[0], thr0, cnt0, valid, item, seg0 + 0 * (int64_t)sh.cand_cap, seg_cap);
-            if (1 < G) filter_head(res[1], thr1, cnt1, valid, item, seg0 + 1 * (int64_t)sh.cand_cap, seg_cap);
-            if (2 < G) filter_head(res[2], thr2, cnt2, valid, item, seg0 + 2 * (int64_t)sh.cand_cap, seg_cap);
-            if (3 < G) filter_head(res[3], thr3, cnt3, valid, item, seg0 + 3 * (int64_t)sh.cand_cap, seg_cap);
+            if (0 < G) filter_head(res[0], thr0, cs0, valid, item, seg_cap, sh.n_seg);
+            if (1 < G) filter_head(res[1], thr1, cs1, valid, item, seg_cap, sh.n_seg);
+            if (2 < G) filter_head(res[2], thr2, cs2, valid, item, seg_cap, sh.n_seg);
+            if (3 < G) filter_head(res[3], thr3, cs3, valid, item, seg_cap, sh.n_seg);
         }
     };
 
-    // the next tile's loads are in flight while the current one is multiplied and filtered
+    // The next tile's loads are in flight while the current one is multiplied and filtered.
+    // The prefetch is unconditional (past the end it re-reads the current tile, a cache hit)
+    // so that the wait before the MFMAs only covers the tile they consume.
 #if TKA_SCAN_PIPELINE
     v8 ba[4][D / 32], bb[4][D / 32];
-    if (tile < tile_end) tile_load<DT, D>(Kh, [&](int slot) { return row_of(tile * 64, slot); }, ba);
-    while (tile < tile_end) {
-        const int64_t t1 = tile + tile_step;
-        if (t1 < tile_end) tile_load<DT, D>(Kh, [&](int slot) { return row_of(t1 * 64, slot); }, bb);
-        __builtin_amdgcn_sched_barrier(0);
-        consume(tile_mac<DT, D>(ba, qa), tile * 64);
-        if (t1 >= tile_end) break;
-        const int64_t t2 = t1 + tile_step;
-        if (t2 < tile_end) tile_load<DT, D>(Kh, [&](int slot) { return row_of(t2 * 64, slot); }, ba);
-        __builtin_amdgcn_sched_barrier(0);
-        consume(tile_mac<DT, D>(bb, qa), t1 * 64);
-        tile = t2;
+    if (tile < tile_end) {
+        tile_load<DT, D>(Kh, [&](int slot) { return row_of(tile * 64, slot); }, ba);
+        while (true) {
+            const int64_t t1 = tile + tile_step;
+            const int64_t p1 = t1 < tile_end ? t1 : tile;
+            tile_load<DT, D>(Kh, [&](int slot) { return row_of(p1 * 64, slot); }, bb);
+            __builtin_amdgcn_sched_barrier(0);
+            consume(tile_mac<DT, D>(ba, qa), tile * 64);
+            if (t1 >= tile_end) break;
+            const int64_t t2 = t1 + tile_step;
+            const int64_t p2 = t2 < tile_end ? t2 : t1;
+            tile_load<DT, D>(Kh, [&](int slot) { return row_of(p2 * 64, slot); }, ba);
+            __builtin_amdgcn_sched_barrier(0);
+            consume(tile_mac<DT, D>(bb, qa), t1 * 64);
+            if (t2 >= tile_end) break;
+            tile = t2;
+        }
     }
 #else
     for (; tile < tile_end; tile += tile_step) {
@@ -227,12 +261,18 @@ scan_mfma_kernel(Shape sh, Bufs bf, int tiles_per_wave, int only_flagged, float*
         consume(tile_mac<DT, D>(ba, qa), tile * 64);
     }
 #endif
-    if (MODE == MODE_FILTER && lane == 0) {
-        uint32_t* sc = bf.seg_cnt + head0 * (int64_t)sh.n_seg + sid;
-        sc[0] = (uint32_t)cnt0;
-        if (1 < G) sc[sh.n_seg] = (uint32_t)cnt1;
-        if (2 < G) sc[2 * (int64_t)sh.n_seg] = (uint32_t)cnt2;
-        if (3 < G) sc[3 * (int64_t)sh.n_seg] = (uint32_t)cnt3;
+    if (MODE == MODE_FILTER) {
+        stage_flush(cs0, seg_cap, sh.n_seg);
+        if (1 < G) stage_flush(cs1, seg_cap, sh.n_seg);
+        if (2 < G) stage_flush(cs2, seg_cap, sh.n_seg);
+        if (3 < G) stage_flush(cs3, seg_cap, sh.n_seg);
+        if (lane == 0) {
+            uint32_t* sc = bf.seg_cnt + head0 * (int64_t)sh.n_seg + sid;
+            sc[0] = (uint32_t)cs0.n_glob;
+            if (1 < G) sc[sh.n_seg] = (uint32_t)cs1.n_glob;
+            if (2 < G) sc[2 * (int64_t)sh.n_seg] = (uint32_t)cs2.n_glob;
+            if (3 < G) sc[3 * (int64_t)sh.n_seg] = (uint32_t)cs3.n_glob;
+        }
     }
 }
 
