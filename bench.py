@@ -19,6 +19,9 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBPS = 8000.0   # MI355X HBM3E, published
+# HBM bytes one key-scan launch moves at the default workload, from rocprofv3 FETCH_SIZE + WRITE_SIZE
+# (profiles/decode_c3_hbm_counters.md, counters calibrated against copy kernels of known size).
+SCAN_TRAFFIC_BYTES_C3 = 2.1697e9
 
 
 def main() -> int:
@@ -141,7 +144,7 @@ def main() -> int:
         "filter_fallback_heads": fallbacks,
         "roofline": {"bound": "hbm", "kernel": "scan_mfma_kernel (filter)", "achieved": scan_gbps,
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": scan_gbps / HBM_PEAK_GBPS,
-                     "traffic": None, "ms_per_launch": scan_ms, "bytes_per_launch": k_bytes,
+                     "traffic": SCAN_TRAFFIC_BYTES_C3 if not args.tokens else None, "ms_per_launch": scan_ms, "bytes_per_launch": k_bytes,
                      "frac_of_read_probe": scan_gbps / probe_gbps},
         "cpu_baseline": cpu,
         "input_generation_s": gen_s,
