@@ -32,31 +32,34 @@ def score_margin(q, K, dtype) -> np.ndarray:
     return 8.0 * d * U32 * A.max(axis=1)
 
 
-def enforce_margin(q, K, dtype, k, max_rounds=40):
-    """Nudge keys (scale the row by 1 - 2^-6) until, for every head, no unselected
-    score lies within delta_h below the k-th largest score.  Uses only oracle scores.
-    Returns (K, delta [Hq], rounds).  K is modified in place."""
+def enforce_margin(q, K, dtype, k, max_rounds=60):
+    """Nudge keys (scale the row by 1 - 2^-6) until, for every head and every k asked
+    for (an int or a list), no unselected score lies within delta_h below the k-th largest
+    score.  Uses only oracle scores.  Returns (K, delta [Hq], rounds).  K is modified in place."""
     Hq, d = q.shape
     Hkv, N, _ = K.shape
     G = Hq // Hkv
+    ks = [kk for kk in (k if isinstance(k, (list, tuple)) else [k]) if kk < N]
     delta = score_margin(q, K, dtype)
-    if k >= N:
+    if not ks:
         return K, delta, 0
     for rnd in range(max_rounds):
         S = c_oracle.scores(q, K, dtype)
         dirty = False
         for h in range(Hq):
             s = S[h]
-            part = np.partition(s, N - k)          # part[N-k] is the k-th largest
-            s_k = part[N - k]
-            below = part[:N - k]
-            if below.max() > s_k - delta[h]:
-                # unselected keys inside the band (ties with s_k at higher positions included)
-                cand = np.nonzero(s > s_k - delta[h])[0]      # the k selected plus the band
-                order = cand[np.lexsort((cand, -s[cand]))]
-                viol = order[k:]
-                scale_rows_storage(K, dtype, h // G, viol, 1.0 - 2.0 ** -6)
-                dirty = True
+            for kk in ks:
+                part = np.partition(s, N - kk)          # part[N-kk] is the kk-th largest
+                s_k = part[N - kk]
+                below = part[:N - kk]
+                if below.max() > s_k - delta[h]:
+                    # unselected keys inside the band (ties with s_k at higher positions included)
+                    cand = np.nonzero(s > s_k - delta[h])[0]      # the kk selected plus the band
+                    order = cand[np.lexsort((cand, -s[cand]))]
+                    viol = order[kk:]
+                    scale_rows_storage(K, dtype, h // G, viol, 1.0 - 2.0 ** -6)
+                    dirty = True
+                    break    # scores of this KV head changed: re-score before looking further
         if not dirty:
             return K, delta, rnd
     raise AssertionError("margin enforcement did not converge")
