@@ -298,6 +298,9 @@ __global__ void __launch_bounds__(kSelThreads) select_candidates_kernel(Shape sh
     const int64_t N = bf.len[b];
     const int k_eff = sh.k < N ? sh.k : (int)N;
 
+#if defined(TKA_SEL_STOP) && TKA_SEL_STOP == 0
+    return;
+#endif
     // segment lengths: total, longest
     uint32_t sum = 0, mxl = 0;
     for (int g = tid; g < sh.n_seg; g += kSelThreads) {
@@ -328,6 +331,12 @@ __global__ void __launch_bounds__(kSelThreads) select_candidates_kernel(Shape sh
     }
     const SrcSeg src{bf.cand + bh * (int64_t)sh.cand_cap, sm.seg_len, sh.n_seg, (int)max_len};
     const Items<32768 / kSelThreads, SrcSeg> items(src);
+#if defined(TKA_SEL_STOP) && TKA_SEL_STOP == 1
+    { uint64_t x = 0; items.for_each([&](uint64_t c) { x ^= c; }); if (x == 12345) bf.hmax[bh] = 1.f; return; }
+#endif
+#if defined(TKA_SEL_STOP) && TKA_SEL_STOP == 2
+    { uint64_t km; uint64_t T0 = wg_select_kth(items, (int64_t)total, (int64_t)total, sm, &km); if (T0 == 12345) bf.hmax[bh] = 1.f; return; }
+#endif
     uint64_t kmax;
     const uint64_t T = wg_select_kth(items, (int64_t)total, (int64_t)k_eff, sm, &kmax);
     wg_emit(items, T, k_eff, sh.k, bf.sel_idx + bh * sh.k, bf.sel_val + bh * sh.k, sm);
