@@ -76,14 +76,18 @@ struct Items {
             bool ok[B];
 #pragma unroll
             for (int u = 0; u < B; ++u) {
-                const int64_t i = (int64_t)(j0 + u) * kSelThreads + threadIdx.x;
-                ok[u] = src.valid(i);
-                r[u] = *src.where(ok[u] ? i : 0);
+                if (j0 + u < CPT) {          // CPT need not be a multiple of the batch
+                    const int64_t i = (int64_t)(j0 + u) * kSelThreads + threadIdx.x;
+                    ok[u] = src.valid(i);
+                    r[u] = *src.where(ok[u] ? i : 0);
+                }
             }
 #pragma unroll
             for (int u = 0; u < B; ++u) {
-                const int64_t i = (int64_t)(j0 + u) * kSelThreads + threadIdx.x;
-                kc[j0 + u] = ok[u] ? src.key(r[u], i) : 0ull;
+                if (j0 + u < CPT) {
+                    const int64_t i = (int64_t)(j0 + u) * kSelThreads + threadIdx.x;
+                    kc[j0 + u] = ok[u] ? src.key(r[u], i) : 0ull;
+                }
             }
         }
     }
@@ -163,7 +167,7 @@ __device__ uint64_t wg_select_kth(const It& items, int64_t n, int64_t k, SelShar
     if (wave == 0) {
         mx = lane < kSelWaves ? sm.red_max[lane] : 0ull;
         mn = lane < kSelWaves ? sm.red_min[lane] : ~0ull;
-        for (int o = kSelWaves / 2; o > 0; o >>= 1) {
+        for (int o = 32; o > 0; o >>= 1) {
             const uint64_t a = __shfl_xor(mx, o, kWave), b = __shfl_xor(mn, o, kWave);
             mx = a > mx ? a : mx;
             mn = b < mn ? b : mn;
@@ -180,13 +184,7 @@ __device__ uint64_t wg_select_kth(const It& items, int64_t n, int64_t k, SelShar
     int rb = 64 - __clzll((long long)(mx ^ mn));   // mx != mn: keys are unique and n >= 3 here
     uint64_t prefix = rb >= 64 ? 0ull : (mx >> rb) << rb;
     int64_t k_rem = k;
-#if defined(TKA_SEL_STOP) && TKA_SEL_STOP >= 10
-    int dbg_pass = 0;
-#endif
     while (rb > 0) {
-#if defined(TKA_SEL_STOP) && TKA_SEL_STOP >= 10
-        if (dbg_pass++ >= TKA_SEL_STOP - 10) break;
-#endif
         const int w = rb < kDigitBits ? rb : kDigitBits;
         const int shift = rb - w;
         const uint32_t dmask = (1u << w) - 1u;
@@ -277,7 +275,7 @@ __global__ void __launch_bounds__(kSelThreads) threshold_kernel(Shape sh, Bufs b
     const int k_eff = sh.k < N ? sh.k : (int)N;
     const Plan pl = make_plan(N, k_eff);
     const SrcDense src{bf.samp + bh * sh.samp_cap, (int64_t)pl.n_samp};
-    const Items<kSampMax / kSelThreads, SrcDense> items(src);
+    const Items<(kSampMax + kSelThreads - 1) / kSelThreads, SrcDense> items(src);
     uint64_t kmax;
     const int rank = pl.rank < pl.n_samp ? pl.rank : pl.n_samp;
     const uint64_t T = wg_select_kth(items, (int64_t)pl.n_samp, (int64_t)rank, sm, &kmax);
@@ -298,9 +296,6 @@ __global__ void __launch_bounds__(kSelThreads) select_candidates_kernel(Shape sh
     const int64_t N = bf.len[b];
     const int k_eff = sh.k < N ? sh.k : (int)N;
 
-#if defined(TKA_SEL_STOP) && TKA_SEL_STOP == 0
-    return;
-#endif
     // segment lengths: total, longest
     uint32_t sum = 0, mxl = 0;
     for (int g = tid; g < sh.n_seg; g += kSelThreads) {
@@ -330,13 +325,7 @@ __global__ void __launch_bounds__(kSelThreads) select_candidates_kernel(Shape sh
         return;
     }
     const SrcSeg src{bf.cand + bh * (int64_t)sh.cand_cap, sm.seg_len, sh.n_seg, (int)max_len};
-    const Items<32768 / kSelThreads, SrcSeg> items(src);
-#if defined(TKA_SEL_STOP) && TKA_SEL_STOP == 1
-    { uint64_t x = 0; items.for_each([&](uint64_t c) { x ^= c; }); if (x == 12345) bf.hmax[bh] = 1.f; return; }
-#endif
-#if defined(TKA_SEL_STOP) && TKA_SEL_STOP == 2
-    { uint64_t km; uint64_t T0 = wg_select_kth(items, (int64_t)total, (int64_t)total, sm, &km); if (T0 == 12345) bf.hmax[bh] = 1.f; return; }
-#endif
+    const Items<(32768 + kSelThreads - 1) / kSelThreads, SrcSeg> items(src);
     uint64_t kmax;
     const uint64_t T = wg_select_kth(items, (int64_t)total, (int64_t)k_eff, sm, &kmax);
     wg_emit(items, T, k_eff, sh.k, bf.sel_idx + bh * sh.k, bf.sel_val + bh * sh.k, sm);
@@ -352,7 +341,7 @@ __global__ void __launch_bounds__(kSelThreads) select_full_kernel(Shape sh, Bufs
     const int64_t N = bf.len[b];
     const int k_eff = sh.k < N ? sh.k : (int)N;
     const SrcDense src{bf.scores + bh * sh.Ncap, N};
-    const Items<8192 / kSelThreads, SrcDense> items(src);
+    const Items<(8192 + kSelThreads - 1) / kSelThreads, SrcDense> items(src);
     uint64_t kmax;
     const uint64_t T = wg_select_kth(items, N, (int64_t)k_eff, sm, &kmax);
     wg_emit(items, T, k_eff, sh.k, bf.sel_idx + bh * sh.k, bf.sel_val + bh * sh.k, sm);
