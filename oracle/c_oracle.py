@@ -38,6 +38,9 @@ def _load():
         lib.oracle_topk_attention.argtypes = [vp, vp, vp, i32, i32, i32, i32, i64, i64,
                                               vp, vp, vp, vp]
         lib.oracle_topk_attention.restype = i32
+        lib.oracle_topk_attention_window.argtypes = [vp, vp, vp, i32, i32, i32, i32, i64, i64, i64,
+                                                     vp, vp, vp, vp]
+        lib.oracle_topk_attention_window.restype = i32
         lib.oracle_num_threads.restype = i32
         _lib = lib
     return _lib
@@ -81,4 +84,22 @@ def topk_attention(q: np.ndarray, K: np.ndarray, V: np.ndarray, dtype: int, k: i
                                        vals.ctypes.data, lse.ctypes.data)
     if rc:
         raise RuntimeError(f"oracle_topk_attention failed rc={rc}")
+    return out, idx, vals, lse
+
+
+def topk_attention_window(q: np.ndarray, K: np.ndarray, V: np.ndarray, dtype: int, k: int, window: int):
+    """Like topk_attention, with the last `window` tokens always attended and the search
+    restricted to the older prefix (one softmax over both parts)."""
+    q, K, V = _check(q, dtype), _check(K, dtype), _check(V, dtype)
+    Hq, d = q.shape
+    Hkv, N, _ = K.shape
+    out = np.empty((Hq, d), dtype=np.float64)
+    idx = np.empty((Hq, k), dtype=np.int64)
+    vals = np.empty((Hq, k), dtype=np.float64)
+    lse = np.empty((Hq,), dtype=np.float64)
+    rc = _load().oracle_topk_attention_window(q.ctypes.data, K.ctypes.data, V.ctypes.data, dtype,
+                                              Hq, Hkv, d, N, k, window, out.ctypes.data, idx.ctypes.data,
+                                              vals.ctypes.data, lse.ctypes.data)
+    if rc:
+        raise RuntimeError(f"oracle_topk_attention_window failed rc={rc}")
     return out, idx, vals, lse

@@ -21,7 +21,10 @@ design notes):
 Pins: every function here is pinned by tests/test_oracle_pins.py (k = N equals
 library dense attention, brute-force subset enumeration on tiny N, k = 1,
 all-equal scores, score-shift invariance, permutation invariance, planted
-dominant keys, truncation-error bound).  No function is "parity unpinned".
+dominant keys, truncation-error bound; for the window variant: window 0 equals the
+plain step, full coverage equals library dense attention, brute force on tiny N, and
+the log-sum-exp merge of a top-k prefix with library attention over the window).
+No function is "parity unpinned".
 """
 from __future__ import annotations
 
@@ -102,6 +105,43 @@ def topk_attention(q, K, V, k: int):
         idx[h, :ke] = I
         vals[h, :ke] = v
         out[h], lse[h] = attend_selected(v, V[h // G][I], d)
+    return out, idx, vals, lse
+
+
+def topk_attention_window(q, K, V, k: int, window: int):
+    """Decode step with the recent-token window of Algorithm 1: the last `window`
+    cached tokens play the role of K_gen / V_gen (always attended), the k-nearest-
+    neighbour search runs over the older prefix only, and one softmax spans the
+    retrieved scores and the window scores together (the reading taken for the
+    algorithm's window line, whose printed form lacks the value factor).
+
+    Returns out [Hq, d], idx [Hq, k] (search result over the prefix, -1 padded),
+    vals [Hq, k] (-inf padded), lse [Hq] (over retrieved + window scores).
+    """
+    q = np.asarray(q, dtype=np.float64)
+    K = np.asarray(K, dtype=np.float64)
+    V = np.asarray(V, dtype=np.float64)
+    Hq, d = q.shape
+    Hkv, N, _ = K.shape
+    G = Hq // Hkv
+    if k < 1 or N < 1 or window < 0:
+        raise ValueError("k, N must be >= 1 and window >= 0")
+    W = min(int(window), N)
+    P = N - W                               # the search runs over positions [0, P)
+    S = scores(q, K)
+    out = np.zeros((Hq, d))
+    idx = np.full((Hq, k), -1, dtype=np.int64)
+    vals = np.full((Hq, k), -np.inf)
+    lse = np.zeros(Hq)
+    for h in range(Hq):
+        if P > 0:
+            I, v = select_topk(S[h, :P], k)
+        else:
+            I, v = np.zeros(0, dtype=np.int64), np.zeros(0)
+        idx[h, :I.shape[0]] = I
+        vals[h, :I.shape[0]] = v
+        rows = np.concatenate([I, np.arange(P, N)])          # retrieved positions, then the window
+        out[h], lse[h] = attend_selected(S[h, rows], V[h // G][rows], d)
     return out, idx, vals, lse
 
 

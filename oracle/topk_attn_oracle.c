@@ -151,6 +151,10 @@ int oracle_scores(const void* q, const void* K, int dtype, int Hq, int Hkv, int 
     return fail ? 2 : 0;
 }
 
+static int topk_window_impl(const void* q, const void* K, const void* V, int dtype, int Hq, int Hkv, int d,
+                            int64_t N, int64_t k, int64_t window, double* out, int64_t* idx, double* vals,
+                            double* lse);
+
 /*
  * One decode step for one (layer, sequence).
  * q [Hq, d], K, V [Hkv, N, d] in `dtype`.
@@ -161,11 +165,33 @@ int oracle_scores(const void* q, const void* K, int dtype, int Hq, int Hkv, int 
 int oracle_topk_attention(const void* q, const void* K, const void* V, int dtype,
                           int Hq, int Hkv, int d, int64_t N, int64_t k,
                           double* out, int64_t* idx, double* vals, double* lse) {
+    return topk_window_impl(q, K, V, dtype, Hq, Hkv, d, N, k, 0, out, idx, vals, lse);
+}
+
+/*
+ * Decode step with the recent-token window of Algorithm 1: the last `window` cached
+ * tokens (the algorithm's K_gen / V_gen) are always attended, the search runs over the
+ * older prefix [0, N - window) only, and one softmax spans retrieved and window scores.
+ * idx / vals report the search result over the prefix; lse covers both parts.
+ */
+int oracle_topk_attention_window(const void* q, const void* K, const void* V, int dtype,
+                                 int Hq, int Hkv, int d, int64_t N, int64_t k, int64_t window,
+                                 double* out, int64_t* idx, double* vals, double* lse) {
+    if (window < 0) return 1;
+    return topk_window_impl(q, K, V, dtype, Hq, Hkv, d, N, k, window, out, idx, vals, lse);
+}
+
+static int topk_window_impl(const void* q, const void* K, const void* V, int dtype, int Hq, int Hkv, int d,
+                            int64_t N, int64_t k, int64_t window, double* out, int64_t* idx, double* vals,
+                            double* lse) {
     if (!q || !K || !V || !out || Hq < 1 || Hkv < 1 || d < 1 || N < 1 || k < 1 || Hq % Hkv)
         return 1;
     if (dtype < 0 || dtype > 2) return 1;
     int G = Hq / Hkv;
-    int64_t k_eff = k < N ? k : N;
+    int64_t W = window < N ? window : N;
+    int64_t P = N - W;                           /* the search runs over positions [0, P) */
+    int64_t k_eff = k < P ? k : P;
+    int64_t n_att = k_eff + W;                   /* rows the softmax spans */
     double inv_sqrt_d = 1.0 / sqrt((double)d);
 
     /* 1. scores: raw dot product of each query with every cached key */
@@ -179,8 +205,8 @@ int oracle_topk_attention(const void* q, const void* K, const void* V, int dtype
     int fail = 0;
 #pragma omp parallel for schedule(dynamic, 1)
     for (int h = 0; h < Hq; ++h) {
-        pair_t* p = (pair_t*)malloc(sizeof(pair_t) * (size_t)N);
-        double* w = (double*)malloc(sizeof(double) * (size_t)k_eff);
+        pair_t* p = (pair_t*)malloc(sizeof(pair_t) * (size_t)(N > 0 ? N : 1));
+        double* w = (double*)malloc(sizeof(double) * (size_t)n_att);
         double* vd = (double*)malloc(sizeof(double) * (size_t)d);
         if (!p || !w || !vd) {
 #pragma omp atomic write
@@ -192,19 +218,23 @@ int oracle_topk_attention(const void* q, const void* K, const void* V, int dtype
             p[i].s = S[(int64_t)h * N + i];
             p[i].i = i;
         }
-        /* 2. exact search: full sort of all N pairs, keep the first k_eff */
-        qsort(p, (size_t)N, sizeof(pair_t), cmp_pair);
-        /* 3. softmax over the k_eff retrieved scores, scaled by 1/sqrt(d) */
-        double m = p[0].s * inv_sqrt_d;          /* sorted: the first is the largest */
+        /* 2. exact search: full sort of the P prefix pairs, keep the first k_eff;
+              the W window pairs p[P..N) follow them unsorted */
+        qsort(p, (size_t)P, sizeof(pair_t), cmp_pair);
+        if (k_eff < P) memmove(p + k_eff, p + P, sizeof(pair_t) * (size_t)W);
+        /* 3. softmax over the retrieved and the window scores, scaled by 1/sqrt(d) */
+        double m = -INFINITY;
+        for (int64_t j = 0; j < n_att; ++j)
+            if (p[j].s * inv_sqrt_d > m) m = p[j].s * inv_sqrt_d;
         double Z = 0.0;
-        for (int64_t j = 0; j < k_eff; ++j) {
+        for (int64_t j = 0; j < n_att; ++j) {
             w[j] = exp(p[j].s * inv_sqrt_d - m);
             Z += w[j];
         }
-        /* 4. weighted sum of the retrieved value rows */
+        /* 4. weighted sum of the attended value rows */
         double* o = out + (int64_t)h * d;
         for (int c = 0; c < d; ++c) o[c] = 0.0;
-        for (int64_t j = 0; j < k_eff; ++j) {
+        for (int64_t j = 0; j < n_att; ++j) {
             widen_row(V, dtype, tab, ((int64_t)(h / G) * N + p[j].i) * d, d, vd);
             double pj = w[j] / Z;
             for (int c = 0; c < d; ++c) o[c] += pj * vd[c];

@@ -316,3 +316,75 @@ def test_kv_cache_sizes_printed_in_paper():
         n, hidden, layers, bpe, gb = line.split()
         got = wl.kv_cache_bytes(int(n), int(hidden), int(layers), int(bpe)) / 1e9
         assert abs(got - float(gb)) / float(gb) < 0.03, (line, got)
+
+
+# ---------------------------------------------------------------- recent-token window (Algorithm 1's K_gen / V_gen)
+def test_window_zero_is_plain_topk():
+    (qs, Ks, Vs), (q, K, V) = _rand(4, 2, 200, 16, 71)
+    a = ref.topk_attention(q, K, V, 17)
+    b = ref.topk_attention_window(q, K, V, 17, 0)
+    c = c_oracle.topk_attention_window(qs, Ks, Vs, wl.F32, 17, 0)
+    for x, y, z in zip(a, b, c):
+        np.testing.assert_array_equal(x, y)
+        np.testing.assert_allclose(z, x, rtol=1e-12, atol=1e-13)
+
+
+@pytest.mark.parametrize("N,k,W", [(60, 50, 10), (60, 100, 7), (33, 5, 33), (33, 5, 80)])
+def test_window_covering_everything_is_dense_attention(N, k, W):
+    """k >= N - W (or W >= N): every cached token is attended, so the result is Eq. 1."""
+    (qs, Ks, Vs), (q, K, V) = _rand(4, 2, N, 8, 72)
+    dense = _dense_library(q, K, V)
+    out, idx, vals, lse = ref.topk_attention_window(q, K, V, k, W)
+    out_c, idx_c, _, lse_c = c_oracle.topk_attention_window(qs, Ks, Vs, wl.F32, k, W)
+    np.testing.assert_allclose(out, dense, rtol=1e-12, atol=1e-13)
+    np.testing.assert_allclose(out_c, dense, rtol=1e-12, atol=1e-13)
+    P = max(0, N - W)
+    for h in range(4):
+        assert sorted(i for i in idx[h].tolist() if i >= 0) == list(range(min(k, P)))
+        assert (idx[h][min(k, P):] == -1).all()
+        z = torch.from_numpy(K[h // 2] @ q[h]) / math.sqrt(8)
+        assert abs(lse[h] - float(torch.logsumexp(z, 0))) < 1e-12
+        assert abs(lse_c[h] - lse[h]) < 1e-12
+    np.testing.assert_array_equal(idx_c, idx)
+
+
+@pytest.mark.parametrize("seed", range(4))
+def test_window_bruteforce_tiny(seed):
+    g = np.random.default_rng(seed)
+    N, d = int(g.integers(8, 13)), 4
+    W, k = int(g.integers(1, 4)), int(g.integers(1, 4))
+    (qs, Ks, Vs), (q, K, V) = _rand(1, 1, N, d, 200 + seed)
+    P = N - W
+    S = [sum(q[0, c] * K[0, i, c] for c in range(d)) for i in range(N)]
+    best = max(itertools.combinations(range(P), k), key=lambda I: sum(S[i] for i in I))
+    att = list(best) + list(range(P, N))
+    mx = max(S[i] for i in att)
+    w = {i: math.exp((S[i] - mx) / math.sqrt(d)) for i in att}
+    Z = sum(w.values())
+    want = [sum(w[i] / Z * V[0, i, c] for i in att) for c in range(d)]
+    for out, idx, vals, lse in (ref.topk_attention_window(q, K, V, k, W),
+                                c_oracle.topk_attention_window(qs, Ks, Vs, wl.F32, k, W)):
+        assert set(idx[0].tolist()) == set(best)
+        np.testing.assert_allclose(out[0], want, rtol=1e-12, atol=1e-14)
+        assert abs(lse[0] - (mx / math.sqrt(d) + math.log(Z))) < 1e-12
+
+
+def test_window_is_lse_merge_of_topk_prefix_and_dense_window():
+    """out = (e^la out_a + e^lb out_b) / (e^la + e^lb) with a = top-k attention over the
+    prefix alone and b = dense attention (library) over the window alone."""
+    (qs, Ks, Vs), (q, K, V) = _rand(6, 3, 500, 16, 73)
+    k, W = 40, 37
+    P = 500 - W
+    out_a, idx_a, vals_a, lse_a = ref.topk_attention(q, K[:, :P], V[:, :P], k)
+    out_b = _dense_library(q, K[:, P:], V[:, P:])
+    out, idx, vals, lse = ref.topk_attention_window(q, K, V, k, W)
+    out_c, idx_c, vals_c, lse_c = c_oracle.topk_attention_window(qs, Ks, Vs, wl.F32, k, W)
+    np.testing.assert_array_equal(idx, idx_a)
+    np.testing.assert_array_equal(idx_c, idx_a)
+    for h in range(6):
+        lb = float(torch.logsumexp(torch.from_numpy(K[h // 2, P:] @ q[h]) / 4.0, 0))
+        wa, wb = math.exp(lse_a[h] - lse[h]), math.exp(lb - lse[h])
+        assert abs(wa + wb - 1.0) < 1e-12
+        np.testing.assert_allclose(out[h], wa * out_a[h] + wb * out_b[h], rtol=1e-11, atol=1e-13)
+        np.testing.assert_allclose(out_c[h], out[h], rtol=1e-11, atol=1e-13)
+        assert abs(lse_c[h] - lse[h]) < 1e-12
