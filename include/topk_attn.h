@@ -64,7 +64,7 @@ typedef struct {
     int32_t max_k;          /* largest k decode will be called with; sizes the workspace */
     int32_t dtype;          /* TOPK_ATTN_F32 / F16 / BF16 for q, K and V alike */
     int32_t device;         /* HIP device ordinal */
-    int32_t reserved;
+    int32_t max_window;     /* largest `window` topk_attn_decode_window will be called with (0 if unused) */
     void* kv_storage;       /* device, >= topk_attn_kv_bytes(), 256-byte aligned, caller-owned */
     size_t kv_bytes;
     void* workspace;        /* device, >= topk_attn_workspace_bytes(), 256-byte aligned, caller-owned */
@@ -111,6 +111,16 @@ int topk_attn_append_kv(topk_attn_t* h, int layer, int seq, const void* k_new, c
  * k > max_k, a sequence with no tokens), EDEVICE. */
 int topk_attn_decode(topk_attn_t* h, int layer, const void* q, int k, float* out, int32_t* idx,
                      float* vals, float* lse, void* hip_stream);
+
+/* Decode step with the recent-token window of Algorithm 1 (its K_gen / V_gen, "resembles
+ * windowed attention"): for each sequence the last min(window, N_b) cached tokens are always
+ * attended, the k-nearest-neighbour search runs over the older prefix only
+ * (k_eff = min(k, N_b - window)), and one softmax spans the retrieved and the window scores
+ * (the algorithm's window line is read as a joint softmax over both parts applied to
+ * [V[I]; V_gen]).  idx / vals report the search result over the prefix; lse covers both parts.
+ * window == 0 is topk_attn_decode.  Extra error: EINVAL if window < 0 or > max_window. */
+int topk_attn_decode_window(topk_attn_t* h, int layer, const void* q, int k, int window, float* out,
+                            int32_t* idx, float* vals, float* lse, void* hip_stream);
 
 /* Debug/measurement: write the full fp32 score matrix S = q K^T of `layer`
  * to scores [B, Hq, max_tokens] (device); entries beyond a sequence's length are

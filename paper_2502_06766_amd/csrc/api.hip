@@ -20,7 +20,7 @@ inline size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
 inline int elem_bytes(int dtype) { return dtype == TOPK_ATTN_F32 ? 4 : 2; }
 
 struct WsLayout {
-    size_t len, thr, samp, seg_cnt, flags, hmax, fallback, cand, scores, sel_idx, sel_val, part_acc, part_l, total;
+    size_t len, thr, samp, seg_cnt, flags, hmax, fallback, cand, scores, sel_idx, sel_val, part_acc, part_l, part_m, total;
     int cand_cap, n_chunk_cap;
 };
 
@@ -28,7 +28,7 @@ bool config_ok(const topk_attn_config* c, int* why) {
     *why = TOPK_ATTN_EINVAL;
     if (!c || c->struct_size != sizeof(topk_attn_config)) return false;
     if (c->n_layers < 1 || c->n_seqs < 1 || c->n_q_heads < 1 || c->n_kv_heads < 1) return false;
-    if (c->max_tokens < 1 || c->max_k < 1 || c->device < 0) return false;
+    if (c->max_tokens < 1 || c->max_k < 1 || c->device < 0 || c->max_window < 0) return false;
     if (c->max_tokens > (int64_t)0x7FFFFF00) return false;   // positions are int32
     if (c->n_seqs > 65535 || c->n_kv_heads > 65535) return false;
     *why = TOPK_ATTN_EUNSUPPORTED;
@@ -50,7 +50,8 @@ WsLayout ws_layout(const topk_attn_config* c) {
     const size_t BH = (size_t)c->n_seqs * c->n_q_heads;
     const int64_t max_k = c->max_k < c->max_tokens ? c->max_k : c->max_tokens;
     w.cand_cap = (int)(4 * max_k + 16384);
-    w.n_chunk_cap = (int)((max_k + kGatherRows - 1) / kGatherRows);
+    const int64_t max_w = c->max_window < c->max_tokens ? c->max_window : c->max_tokens;
+    w.n_chunk_cap = (int)((c->max_k + kGatherRows - 1) / kGatherRows + (max_w + kGatherRows - 1) / kGatherRows);
     size_t o = 0;
     auto take = [&](size_t bytes) { size_t at = o; o = align_up(o + bytes); return at; };
     w.len = take((size_t)c->n_layers * c->n_seqs * sizeof(int32_t));
@@ -66,6 +67,7 @@ WsLayout ws_layout(const topk_attn_config* c) {
     w.sel_val = take(BH * (size_t)c->max_k * sizeof(float));
     w.part_acc = take(BH * (size_t)w.n_chunk_cap * c->head_dim * sizeof(float));
     w.part_l = take(BH * (size_t)w.n_chunk_cap * sizeof(float));
+    w.part_m = take(BH * (size_t)w.n_chunk_cap * sizeof(float));
     w.total = o;
     return w;
 }
@@ -237,7 +239,7 @@ static void fill_call(topk_attn_t* h, int layer, const void* q, int k, Shape* s,
     const topk_attn_config& c = h->cfg;
     const int e = elem_bytes(c.dtype);
     s->B = c.n_seqs; s->Hq = c.n_q_heads; s->Hkv = c.n_kv_heads; s->G = c.n_q_heads / c.n_kv_heads;
-    s->D = c.head_dim; s->dtype = c.dtype; s->k = k; s->max_k = c.max_k;
+    s->D = c.head_dim; s->dtype = c.dtype; s->k = k; s->window = 0; s->max_k = c.max_k;
     s->cand_cap = h->ws.cand_cap; s->n_seg = 4; s->seg_cap = h->ws.cand_cap / 4; s->samp_cap = kSampMax; s->n_chunk_cap = h->ws.n_chunk_cap;
     s->Ncap = c.max_tokens;
     char* ws = static_cast<char*>(c.workspace);
@@ -257,6 +259,7 @@ static void fill_call(topk_attn_t* h, int layer, const void* q, int k, Shape* s,
     b->sel_val = reinterpret_cast<float*>(ws + h->ws.sel_val);
     b->part_acc = reinterpret_cast<float*>(ws + h->ws.part_acc);
     b->part_l = reinterpret_cast<float*>(ws + h->ws.part_l);
+    b->part_m = reinterpret_cast<float*>(ws + h->ws.part_m);
     b->out = nullptr; b->lse = nullptr;
     b->fallback_total = reinterpret_cast<uint32_t*>(ws + h->ws.fallback);
 }
@@ -289,39 +292,46 @@ static bool choose_segments(const topk_attn_t* h, const Shape& s, int64_t nmax, 
     return false;
 }
 
-static int lengths_of(const topk_attn_t* h, int layer, int64_t* nmin, int64_t* nmax) {
+// Shortest and longest searched prefix over the sequences of a layer; EINVAL if a sequence is empty.
+static int lengths_of(const topk_attn_t* h, int layer, int window, int64_t* nmin, int64_t* nmax) {
     const int B = h->cfg.n_seqs;
     int64_t lo = INT64_MAX, hi = 0;
     for (int b = 0; b < B; ++b) {
         const int64_t n = h->len[(size_t)layer * B + b];
-        lo = n < lo ? n : lo;
-        hi = n > hi ? n : hi;
+        if (n < 1) return TOPK_ATTN_EINVAL;
+        const int64_t p = prefix_len(n, window);
+        lo = p < lo ? p : lo;
+        hi = p > hi ? p : hi;
     }
     *nmin = lo; *nmax = hi;
-    return lo >= 1 ? TOPK_ATTN_OK : TOPK_ATTN_EINVAL;
+    return TOPK_ATTN_OK;
 }
 
-int topk_attn_decode(topk_attn_t* h, int layer, const void* q, int k, float* out, int32_t* idx, float* vals,
-                     float* lse, void* hip_stream) {
+static int decode_impl(topk_attn_t* h, int layer, const void* q, int k, int window, float* out, int32_t* idx,
+                       float* vals, float* lse, void* hip_stream) {
     if (!h || !q || !out) return TOPK_ATTN_EINVAL;
     if (layer < 0 || layer >= h->cfg.n_layers) return TOPK_ATTN_EINVAL;
     if (k < 1 || k > h->cfg.max_k) return TOPK_ATTN_EINVAL;
+    if (window < 0 || window > h->cfg.max_window) return TOPK_ATTN_EINVAL;
+    if (window > h->cfg.max_tokens) window = (int)h->cfg.max_tokens;   // same result: no sequence is longer
     if ((uintptr_t)q & 15) return TOPK_ATTN_EINVAL;
-    int64_t nmin, nmax;
-    if (lengths_of(h, layer, &nmin, &nmax) != TOPK_ATTN_OK) return TOPK_ATTN_EINVAL;
+    int64_t nmin, nmax;     // searched prefix lengths
+    if (lengths_of(h, layer, window, &nmin, &nmax) != TOPK_ATTN_OK) return TOPK_ATTN_EINVAL;
     hipStream_t st = (hipStream_t)hip_stream;
     Shape s; Bufs b;
     fill_call(h, layer, q, k, &s, &b);
+    s.window = window;
     b.out = out; b.lse = lse;
     if (idx) b.sel_idx = idx;
     if (vals) b.sel_val = vals;
 
     bool fast = false;
-    if (h->path != TOPK_ATTN_PATH_FULL && scan_mfma_supported(s)) {
+    if (h->path != TOPK_ATTN_PATH_FULL && scan_mfma_supported(s) && nmax > 0) {
         fast = true;
         int64_t c_hi = 0;
         for (int i = 0; i < s.B && fast; ++i) {
-            const int64_t n = h->len[(size_t)layer * s.B + i];
+            const int64_t n = prefix_len(h->len[(size_t)layer * s.B + i], window);
+            if (n == 0) continue;            // this sequence lies entirely inside its window
             const int ke = k < n ? k : (int)n;
             const Plan pl = make_plan(n, ke);
             fast = plan_is_fast(pl, n, s.cand_cap, h->path == TOPK_ATTN_PATH_FILTER);
@@ -342,15 +352,27 @@ int topk_attn_decode(topk_attn_t* h, int layer, const void* q, int k, float* out
         if (e == hipSuccess) e = launch_scan_full(s, b, nmax, true, b.scores, st);
         if (e == hipSuccess) e = launch_select_full(s, b, true, st);
     } else {
-        if (timed) e = hipEventRecord(h->ev[2 * h->ev_used], st);
-        if (e == hipSuccess) e = launch_scan_full(s, b, nmax, false, b.scores, st);
-        if (e == hipSuccess && timed) e = hipEventRecord(h->ev[2 * h->ev_used + 1], st);
-        if (e == hipSuccess && timed) h->ev_used++;
-        if (e == hipSuccess) e = launch_select_full(s, b, false, st);
+        if (nmax > 0) {
+            if (timed) e = hipEventRecord(h->ev[2 * h->ev_used], st);
+            if (e == hipSuccess) e = launch_scan_full(s, b, nmax, false, b.scores, st);
+            if (e == hipSuccess && timed) e = hipEventRecord(h->ev[2 * h->ev_used + 1], st);
+            if (e == hipSuccess && timed) h->ev_used++;
+        }
+        if (e == hipSuccess) e = launch_select_full(s, b, false, st);   // with nothing to search it only pads
     }
     if (e == hipSuccess) e = launch_gather(s, b, st);
     h->last_fast = fast;
     return e == hipSuccess ? TOPK_ATTN_OK : TOPK_ATTN_EDEVICE;
+}
+
+int topk_attn_decode(topk_attn_t* h, int layer, const void* q, int k, float* out, int32_t* idx, float* vals,
+                     float* lse, void* hip_stream) {
+    return decode_impl(h, layer, q, k, 0, out, idx, vals, lse, hip_stream);
+}
+
+int topk_attn_decode_window(topk_attn_t* h, int layer, const void* q, int k, int window, float* out, int32_t* idx,
+                            float* vals, float* lse, void* hip_stream) {
+    return decode_impl(h, layer, q, k, window, out, idx, vals, lse, hip_stream);
 }
 
 int topk_attn_scores(topk_attn_t* h, int layer, const void* q, float* scores, void* hip_stream) {
@@ -358,7 +380,7 @@ int topk_attn_scores(topk_attn_t* h, int layer, const void* q, float* scores, vo
     if (layer < 0 || layer >= h->cfg.n_layers) return TOPK_ATTN_EINVAL;
     if ((uintptr_t)q & 15) return TOPK_ATTN_EINVAL;
     int64_t nmin, nmax;
-    if (lengths_of(h, layer, &nmin, &nmax) != TOPK_ATTN_OK) return TOPK_ATTN_EINVAL;
+    if (lengths_of(h, layer, 0, &nmin, &nmax) != TOPK_ATTN_OK) return TOPK_ATTN_EINVAL;
     Shape s; Bufs b;
     fill_call(h, layer, q, 1, &s, &b);
     hipError_t e = launch_scan_full(s, b, nmax, false, scores, (hipStream_t)hip_stream);

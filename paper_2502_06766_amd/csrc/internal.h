@@ -21,7 +21,8 @@ constexpr int kMaxSeg = 1024;       // most candidate segments per head
 // Geometry of one decode call, passed by value to every kernel.
 struct Shape {
     int B, Hq, Hkv, G, D, dtype;
-    int k;            // requested k (k_eff = min(k, len[b]) per sequence)
+    int k;            // requested k (k_eff = min(k, searched prefix of sequence b))
+    int window;       // most recent tokens that are always attended and excluded from the search
     int max_k;
     int cand_cap;     // entries per (b, head) candidate list
     int n_seg;        // segments the candidate list is split in (one per scanning wave), power of 2
@@ -49,10 +50,16 @@ struct Bufs {
     float* sel_val;         // [B*Hq][k]
     float* part_acc;        // [B*Hq][n_chunk_cap][D]
     float* part_l;          // [B*Hq][n_chunk_cap]
+    float* part_m;          // [B*Hq][n_chunk_cap] score the partial's weights are relative to
     float* out;             // [B*Hq][D]
     float* lse;             // [B*Hq] or null
     uint32_t* fallback_total; // [1]
 };
+
+// Tokens of a sequence the search runs over: everything but the always-attended window.
+__host__ __device__ inline int64_t prefix_len(int64_t n_tokens, int window) {
+    return n_tokens - (window < n_tokens ? (int64_t)window : n_tokens);
+}
 
 // Sampling plan for the threshold estimate of one sequence (same code on host and device).
 struct Plan {

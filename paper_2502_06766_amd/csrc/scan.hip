@@ -147,7 +147,7 @@ scan_mfma_kernel(Shape sh, Bufs bf, int tiles_per_wave, int only_flagged, float*
     const int64_t head0 = (int64_t)b * sh.Hq + (int64_t)kvh * G;
     const int lane = lane_id();
     const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));   // wave-uniform
-    const int64_t N = bf.len[b];
+    const int64_t N = prefix_len(bf.len[b], sh.window);
 
     if (MODE == MODE_FULL && only_flagged) {
         uint32_t any = 0;
@@ -158,6 +158,7 @@ scan_mfma_kernel(Shape sh, Bufs bf, int tiles_per_wave, int only_flagged, float*
     int64_t n_items = N;   // keys (or samples) this (b, kv head) has
     int stride = 1;
     if (MODE == MODE_SAMPLE) {
+        if (N == 0) return;          // nothing to search: the whole sequence is inside the window
         Plan pl = make_plan(N, sh.k < N ? sh.k : (int)N);
         n_items = pl.n_samp;
         stride = pl.stride;
@@ -285,7 +286,7 @@ scan_generic_kernel(Shape sh, Bufs bf, int rows_per_block, int only_flagged, flo
     const int b = blockIdx.z, kvh = blockIdx.y;
     const int G = sh.G, D = sh.D;
     const int64_t head0 = (int64_t)b * sh.Hq + (int64_t)kvh * G;
-    const int64_t N = bf.len[b];
+    const int64_t N = prefix_len(bf.len[b], sh.window);
     if (only_flagged) {
         uint32_t any = 0;
         for (int r = 0; r < G; ++r) any |= bf.flags[head0 + r];

@@ -234,6 +234,14 @@ __device__ uint64_t wg_select_kth(const It& items, int64_t n, int64_t k, SelShar
     return prefix;
 }
 
+// Slots the selection does not fill: position -1, score -inf.
+__device__ __forceinline__ void pad_outputs(int k_eff, int k, int32_t* idx, float* vals) {
+    for (int j = k_eff + (int)threadIdx.x; j < k; j += kSelThreads) {
+        idx[j] = -1;
+        vals[j] = -INFINITY;
+    }
+}
+
 // Write the items with key >= T (exactly k_eff of them) to idx/vals and pad up to k.
 // Order: wave-major, then slot, then lane -- fixed, and each store instruction of a wave
 // writes one contiguous run.
@@ -259,10 +267,7 @@ __device__ void wg_emit(const It& items, uint64_t T, int k_eff, int k, int32_t* 
         }
         run += (uint32_t)__popcll(m);
     });
-    for (int j = k_eff + (int)threadIdx.x; j < k; j += kSelThreads) {
-        idx[j] = -1;
-        vals[j] = -INFINITY;
-    }
+    pad_outputs(k_eff, k, idx, vals);
 }
 
 // Threshold estimate: the rank-th largest of the sample scores of each head; also clears
@@ -271,8 +276,16 @@ __global__ void __launch_bounds__(kSelThreads) threshold_kernel(Shape sh, Bufs b
     __shared__ SelShared sm;
     const int b = blockIdx.y, h = blockIdx.x;
     const int64_t bh = (int64_t)b * sh.Hq + h;
-    const int64_t N = bf.len[b];
+    const int64_t N = prefix_len(bf.len[b], sh.window);
     const int k_eff = sh.k < N ? sh.k : (int)N;
+    if (N == 0) {                    // nothing to search for this sequence
+        if (threadIdx.x == 0) {
+            bf.thr[bh] = INFINITY;
+            bf.flags[bh] = 0;
+            if (bh == 0) *bf.fallback_total = 0;
+        }
+        return;
+    }
     const Plan pl = make_plan(N, k_eff);
     const SrcDense src{bf.samp + bh * sh.samp_cap, (int64_t)pl.n_samp};
     const Items<(kSampMax + kSelThreads - 1) / kSelThreads, SrcDense> items(src);
@@ -293,9 +306,14 @@ __global__ void __launch_bounds__(kSelThreads) select_candidates_kernel(Shape sh
     const int b = blockIdx.y, h = blockIdx.x;
     const int tid = threadIdx.x, lane = lane_id(), wave = tid >> 6;
     const int64_t bh = (int64_t)b * sh.Hq + h;
-    const int64_t N = bf.len[b];
+    const int64_t N = prefix_len(bf.len[b], sh.window);
     const int k_eff = sh.k < N ? sh.k : (int)N;
 
+    if (k_eff == 0) {                // nothing to search: only padding to write
+        pad_outputs(0, sh.k, bf.sel_idx + bh * sh.k, bf.sel_val + bh * sh.k);
+        if (tid == 0) bf.hmax[bh] = -INFINITY;
+        return;
+    }
     // segment lengths: total, longest
     uint32_t sum = 0, mxl = 0;
     for (int g = tid; g < sh.n_seg; g += kSelThreads) {
@@ -338,8 +356,13 @@ __global__ void __launch_bounds__(kSelThreads) select_full_kernel(Shape sh, Bufs
     const int b = blockIdx.y, h = blockIdx.x;
     const int64_t bh = (int64_t)b * sh.Hq + h;
     if (only_flagged && !bf.flags[bh]) return;
-    const int64_t N = bf.len[b];
+    const int64_t N = prefix_len(bf.len[b], sh.window);
     const int k_eff = sh.k < N ? sh.k : (int)N;
+    if (k_eff == 0) {
+        pad_outputs(0, sh.k, bf.sel_idx + bh * sh.k, bf.sel_val + bh * sh.k);
+        if (threadIdx.x == 0) bf.hmax[bh] = -INFINITY;
+        return;
+    }
     const SrcDense src{bf.scores + bh * sh.Ncap, N};
     const Items<(8192 + kSelThreads - 1) / kSelThreads, SrcDense> items(src);
     uint64_t kmax;

@@ -86,14 +86,15 @@ def check_against_oracle(out, idx, vals, lse, ref, delta, k_eff, tol, vmax, labe
         if idx.shape[1] > k_eff:
             assert (idx[h, k_eff:] == -1).all(), f"{label} head {h}: idx padding"
             assert np.isneginf(vals[h, k_eff:]).all(), f"{label} head {h}: vals padding"
-        gv = np.sort(vals[h, :k_eff].astype(np.float64))[::-1]
-        dv = np.abs(gv - r_vals[h, :k_eff]).max()
-        assert dv <= delta[h] / 8 + 1e-30, f"{label} head {h}: vals off by {dv} (allowed {delta[h] / 8})"
-        # vals must belong to the indices they are reported with
-        o = np.argsort(idx[h, :k_eff], kind="stable")
-        ro = np.argsort(r_idx[h, :k_eff], kind="stable")
-        dv2 = np.abs(vals[h, :k_eff][o].astype(np.float64) - r_vals[h, :k_eff][ro]).max()
-        assert dv2 <= delta[h] / 8 + 1e-30, f"{label} head {h}: vals not aligned with idx ({dv2})"
+        if k_eff > 0:
+            gv = np.sort(vals[h, :k_eff].astype(np.float64))[::-1]
+            dv = np.abs(gv - r_vals[h, :k_eff]).max()
+            assert dv <= delta[h] / 8 + 1e-30, f"{label} head {h}: vals off by {dv} (allowed {delta[h] / 8})"
+            # vals must belong to the indices they are reported with
+            o = np.argsort(idx[h, :k_eff], kind="stable")
+            ro = np.argsort(r_idx[h, :k_eff], kind="stable")
+            dv2 = np.abs(vals[h, :k_eff][o].astype(np.float64) - r_vals[h, :k_eff][ro]).max()
+            assert dv2 <= delta[h] / 8 + 1e-30, f"{label} head {h}: vals not aligned with idx ({dv2})"
         scale = max(np.abs(r_out[h]).max(), 1e-6 * vmax)
         err = np.abs(out[h].astype(np.float64) - r_out[h]).max() / scale
         assert err <= tol, f"{label} head {h}: out rel err {err:.3e} > {tol}"

@@ -359,3 +359,88 @@ def test_error_codes_on_a_live_handle():
         torch.cuda.synchronize()
     finally:
         cache.close()
+
+
+# ------------------------------------------------------------------ recent-token window (Algorithm 1's K_gen / V_gen)
+def run_window_case(q, K, V, dtype, k, window, path=ta.PATH_AUTO, label=""):
+    Hq, d = q.shape
+    Hkv, N, _ = K.shape
+    P = max(0, N - window)
+    delta = H.score_margin(q, K, dtype)
+    ref = c_oracle.topk_attention_window(q, K, V, dtype, k, window)
+    cache = ta.TopkAttnCache(1, 1, Hq, Hkv, d, N, k, dtype, max_window=max(window, 1))
+    try:
+        cache.set_path(path)
+        cache.append(0, 0, H.to_torch(K, dtype, DEV), H.to_torch(V, dtype, DEV), head_major=True)
+        qd = H.to_torch(q, dtype, DEV)[None].contiguous()
+        out, idx, vals, lse = cache.decode(0, qd, k, window=window)
+        torch.cuda.synchronize()
+        H.check_against_oracle(out[0].cpu().numpy(), idx[0].cpu().numpy(), vals[0].cpu().numpy(),
+                               lse[0].cpu().numpy(), ref, delta, min(k, P), H.out_tolerance(dtype),
+                               float(np.abs(wl.widen(V, dtype)).max()), label)
+    finally:
+        cache.close()
+
+
+@pytest.mark.parametrize("dtype,Hq,Hkv,N,d,k,window,path", [
+    (wl.F16, 8, 2, 30000, 128, 400, 1000, ta.PATH_AUTO),     # filtered scan + 4 window chunks
+    (wl.BF16, 8, 2, 30000, 128, 400, 77, ta.PATH_AUTO),      # window smaller than a chunk
+    (wl.F32, 4, 2, 3000, 64, 50, 300, ta.PATH_AUTO),         # fp32, general path
+    (wl.F16, 4, 1, 500, 64, 20, 499, ta.PATH_FULL),          # one searched token
+    (wl.F16, 4, 1, 500, 64, 20, 500, ta.PATH_FULL),          # window covers the whole cache
+    (wl.BF16, 6, 2, 700, 256, 900, 100, ta.PATH_FULL),       # k beyond the searched prefix
+    (wl.F16, 16, 1, 2000, 32, 64, 513, ta.PATH_FULL),        # G = 16, d = 32
+])
+def test_window_decode(dtype, Hq, Hkv, N, d, k, window, path):
+    g = np.random.default_rng(N + k + window)
+    q = wl.quantize(g.standard_normal((Hq, d)).astype(np.float32), dtype)
+    K = wl.quantize(g.standard_normal((Hkv, N, d)).astype(np.float32), dtype)
+    V = wl.quantize(g.standard_normal((Hkv, N, d)).astype(np.float32), dtype)
+    P = max(0, N - window)
+    if 0 < k < P:    # margin at the k-th boundary of the searched prefix only
+        Kp = np.ascontiguousarray(K[:, :P])
+        Kp, _, _ = H.enforce_margin(q, Kp, dtype, k)
+        K[:, :P] = Kp
+    run_window_case(q, K, V, dtype, k, window, path, label=f"window N={N} k={k} W={window}")
+
+
+def test_window_ragged_batch_and_limits():
+    """Three sequences, one shorter than the window; window 0 equals the plain call;
+    a window beyond max_window is rejected."""
+    dtype, Hq, Hkv, d, k, W = wl.BF16, 8, 2, 128, 100, 600
+    lens = [20000, 400, 5000]
+    cache = ta.TopkAttnCache(1, 3, Hq, Hkv, d, 20000, k, dtype, max_window=W)
+    try:
+        data = []
+        for b, n in enumerate(lens):
+            g = np.random.default_rng(900 + b)
+            q = wl.quantize(g.standard_normal((Hq, d)).astype(np.float32), dtype)
+            K = wl.quantize(g.standard_normal((Hkv, n, d)).astype(np.float32), dtype)
+            V = wl.quantize(g.standard_normal((Hkv, n, d)).astype(np.float32), dtype)
+            P = max(0, n - W)
+            if k < P:
+                Kp = np.ascontiguousarray(K[:, :P])
+                Kp, _, _ = H.enforce_margin(q, Kp, dtype, k)
+                K[:, :P] = Kp
+            data.append((q, K, V))
+            cache.append(0, b, H.to_torch(K, dtype, DEV), H.to_torch(V, dtype, DEV), head_major=True)
+        qd = torch.stack([H.to_torch(x[0], dtype, DEV) for x in data]).contiguous()
+        out, idx, vals, lse = cache.decode(0, qd, k, window=W)
+        torch.cuda.synchronize()
+        for b, n in enumerate(lens):
+            q, K, V = data[b]
+            ref = c_oracle.topk_attention_window(q, K, V, dtype, k, W)
+            H.check_against_oracle(out[b].cpu().numpy(), idx[b].cpu().numpy(), vals[b].cpu().numpy(),
+                                   lse[b].cpu().numpy(), ref, H.score_margin(q, K, dtype), min(k, max(0, n - W)),
+                                   2e-3, float(np.abs(wl.widen(V, dtype)).max()), f"ragged window seq {b}")
+        o = torch.empty_like(out)
+        L = ta.lib()
+        st = torch.cuda.current_stream().cuda_stream
+        assert L.topk_attn_decode_window(cache.h, 0, qd.data_ptr(), k, W + 1, o.data_ptr(), None, None, None, st) == ta.EINVAL
+        assert L.topk_attn_decode_window(cache.h, 0, qd.data_ptr(), k, -1, o.data_ptr(), None, None, None, st) == ta.EINVAL
+        out0, idx0, _, _ = cache.decode(0, qd, k)
+        assert L.topk_attn_decode_window(cache.h, 0, qd.data_ptr(), k, 0, o.data_ptr(), None, None, None, st) == ta.OK
+        torch.cuda.synchronize()
+        assert torch.equal(o, out0)
+    finally:
+        cache.close()
