@@ -122,6 +122,16 @@ int topk_attn_decode(topk_attn_t* h, int layer, const void* q, int k, float* out
 int topk_attn_decode_window(topk_attn_t* h, int layer, const void* q, int k, int window, float* out,
                             int32_t* idx, float* vals, float* lse, void* hip_stream);
 
+/* Host-only helper for the paper's layer-wise settings of k ("Layer-Wise Settings for k":
+ * a fixed total budget sum_l k_l, spent either uniformly or increasing linearly from the
+ * first to the last layer).  Writes k_out[0 .. n_layers) with sum exactly total_k and
+ * k_l proportional (before rounding) to 1 + (last_over_first - 1) * l / (n_layers - 1);
+ * last_over_first == 1 gives the uniform split.  Rounding: floor, then the remainder goes
+ * one each to the layers with the largest fractional parts (later layer first on ties).
+ * Errors: EINVAL if k_out is NULL, n_layers < 1, total_k < n_layers (every layer needs
+ * k >= 1), last_over_first <= 0 or not finite, or a k_l would not fit in int32. */
+int topk_attn_k_schedule(int64_t total_k, int n_layers, double last_over_first, int32_t* k_out);
+
 /* Debug/measurement: write the full fp32 score matrix S = q K^T of `layer`
  * to scores [B, Hq, max_tokens] (device); entries beyond a sequence's length are
  * left untouched. */

@@ -162,3 +162,31 @@ def captured_mass(s: np.ndarray, I: np.ndarray, d: int) -> float:
     z = z - z.max()
     a = np.exp(z)
     return float(a[I].sum() / a.sum())
+
+
+def k_schedule(total_k: int, n_layers: int, last_over_first: float = 1.0):
+    """Layer-wise k of the paper's "Layer-Wise Settings for k": a fixed total budget
+    sum_l k_l, uniform (ratio 1) or increasing linearly from the first to the last layer.
+    Exact rational shares total_k * w_l / sum(w), w_l = 1 + (ratio - 1) l / (L - 1), rounded
+    by largest remainder (later layer first on ties), every layer at least 1."""
+    from fractions import Fraction
+    L = n_layers
+    r = Fraction(last_over_first).limit_denominator(1 << 20)
+    w = [Fraction(1) if L == 1 else 1 + (r - 1) * Fraction(l, L - 1) for l in range(L)]
+    tot = sum(w)
+    exact = [total_k * x / tot for x in w]
+    k = [max(1, int(e)) for e in exact]          # int() floors positive fractions
+    order = sorted(range(L), key=lambda l: (exact[l] - k[l], l), reverse=True)
+    rem = total_k - sum(k)
+    i = 0
+    while rem > 0:
+        k[order[i % L]] += 1
+        rem -= 1
+        i += 1
+    i = L - 1
+    while rem < 0:
+        if k[order[i % L]] > 1:
+            k[order[i % L]] -= 1
+            rem += 1
+        i -= 1
+    return k

@@ -4,7 +4,10 @@
 #include <stdlib.h>
 #include <string.h>
 
+#include <algorithm>
+#include <cmath>
 #include <new>
+#include <utility>
 #include <vector>
 
 #include "../../include/topk_attn.h"
@@ -373,6 +376,42 @@ int topk_attn_decode(topk_attn_t* h, int layer, const void* q, int k, float* out
 int topk_attn_decode_window(topk_attn_t* h, int layer, const void* q, int k, int window, float* out, int32_t* idx,
                             float* vals, float* lse, void* hip_stream) {
     return decode_impl(h, layer, q, k, window, out, idx, vals, lse, hip_stream);
+}
+
+int topk_attn_k_schedule(int64_t total_k, int n_layers, double last_over_first, int32_t* k_out) {
+    if (!k_out || n_layers < 1 || total_k < n_layers) return TOPK_ATTN_EINVAL;
+    if (!(last_over_first > 0.0) || !std::isfinite(last_over_first)) return TOPK_ATTN_EINVAL;
+    std::vector<double> w((size_t)n_layers);
+    double wsum = 0.0;
+    for (int l = 0; l < n_layers; ++l) {
+        w[l] = n_layers == 1 ? 1.0 : 1.0 + (last_over_first - 1.0) * (double)l / (double)(n_layers - 1);
+        wsum += w[l];
+    }
+    std::vector<int64_t> k((size_t)n_layers);
+    std::vector<std::pair<double, int>> frac((size_t)n_layers);
+    int64_t used = 0;
+    for (int l = 0; l < n_layers; ++l) {
+        const double exact = (double)total_k * w[l] / wsum;
+        int64_t fl = (int64_t)floor(exact);
+        if (fl < 1) fl = 1;                       // every layer attends to at least one key
+        k[l] = fl;
+        used += fl;
+        frac[l] = {exact - (double)fl, l};
+    }
+    // hand out (or, after the >= 1 clamp, take back) the remainder by fractional part
+    std::sort(frac.begin(), frac.end(), [](const std::pair<double, int>& a, const std::pair<double, int>& b) {
+        return a.first != b.first ? a.first > b.first : a.second > b.second;
+    });
+    int64_t rem = total_k - used;
+    for (int i = 0; rem > 0; i = (i + 1) % n_layers, --rem) k[frac[i].second] += 1;
+    for (int i = n_layers - 1; rem < 0; i = (i + n_layers - 1) % n_layers) {
+        if (k[frac[i].second] > 1) { k[frac[i].second] -= 1; ++rem; }
+    }
+    for (int l = 0; l < n_layers; ++l) {
+        if (k[l] > INT32_MAX) return TOPK_ATTN_EINVAL;
+        k_out[l] = (int32_t)k[l];
+    }
+    return TOPK_ATTN_OK;
 }
 
 int topk_attn_scores(topk_attn_t* h, int layer, const void* q, float* scores, void* hip_stream) {

@@ -21,7 +21,7 @@ PATH_AUTO, PATH_FULL, PATH_FILTER = 0, 1, 2
 
 EXPORTS = [
     "topk_attn_kv_bytes", "topk_attn_workspace_bytes", "topk_attn_create", "topk_attn_append_kv",
-    "topk_attn_decode", "topk_attn_decode_window", "topk_attn_scores", "topk_attn_length", "topk_attn_reset", "topk_attn_set_path",
+    "topk_attn_decode", "topk_attn_decode_window", "topk_attn_k_schedule", "topk_attn_scores", "topk_attn_length", "topk_attn_reset", "topk_attn_set_path",
     "topk_attn_last_fallbacks", "topk_attn_set_scan_timing", "topk_attn_scan_time", "topk_attn_read_probe", "topk_attn_strerror", "topk_attn_destroy",
 ]
 
@@ -76,6 +76,8 @@ def lib() -> ctypes.CDLL:
         L.topk_attn_decode.restype = i32
         L.topk_attn_decode_window.argtypes = [vp, i32, vp, i32, i32, vp, vp, vp, vp, vp]
         L.topk_attn_decode_window.restype = i32
+        L.topk_attn_k_schedule.argtypes = [i64, i32, ctypes.c_double, ctypes.POINTER(ctypes.c_int32)]
+        L.topk_attn_k_schedule.restype = i32
         L.topk_attn_scores.argtypes = [vp, i32, vp, vp, vp]
         L.topk_attn_scores.restype = i32
         L.topk_attn_length.argtypes = [vp, i32, i32]
@@ -153,6 +155,13 @@ def topk_attn_decode(h, layer, q_ptr, k, out_ptr, idx_ptr=0, vals_ptr=0, lse_ptr
 def topk_attn_decode_window(h, layer, q_ptr, k, window, out_ptr, idx_ptr=0, vals_ptr=0, lse_ptr=0, stream=0):
     _check(lib().topk_attn_decode_window(h, layer, q_ptr, k, window, out_ptr, idx_ptr or None, vals_ptr or None,
                                          lse_ptr or None, stream), "topk_attn_decode_window")
+
+
+def topk_attn_k_schedule(total_k: int, n_layers: int, last_over_first: float = 1.0):
+    """Per-layer k with a fixed total budget (host only); returns a list of n_layers ints."""
+    buf = (ctypes.c_int32 * max(1, n_layers))()
+    _check(lib().topk_attn_k_schedule(total_k, n_layers, last_over_first, buf), "topk_attn_k_schedule")
+    return list(buf)[:n_layers]
 
 
 def topk_attn_scores(h, layer, q_ptr, scores_ptr, stream=0):

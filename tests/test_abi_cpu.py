@@ -5,6 +5,7 @@ import ctypes
 import os
 import re
 
+import numpy as np
 import pytest
 
 from paper_2502_06766_amd import topk_attn as ta
@@ -89,3 +90,34 @@ def test_strerror():
     assert ta.topk_attn_strerror(ta.OK) == "ok"
     assert "capacity" in ta.topk_attn_strerror(ta.ECAPACITY)
     assert ta.topk_attn_strerror(99) == "unknown error"
+
+
+# ---------------------------------------------------------------- layer-wise k schedule (host only)
+def test_k_schedule_closed_forms_and_invariants():
+    from oracle import topk_attention_ref as ref
+    # uniform: equal shares, remainder spread one each
+    assert ta.topk_attn_k_schedule(32 * 8192, 32, 1.0) == [8192] * 32
+    ks = ta.topk_attn_k_schedule(100, 8, 1.0)
+    assert sum(ks) == 100 and max(ks) - min(ks) == 1
+    # two layers, ratio 3: shares 1/4 and 3/4
+    assert ta.topk_attn_k_schedule(4000, 2, 3.0) == [1000, 3000]
+    # arithmetic progression when it divides: L = 5, ratio 3 -> weights 1, 1.5, 2, 2.5, 3 (sum 10)
+    assert ta.topk_attn_k_schedule(1000, 5, 3.0) == [100, 150, 200, 250, 300]
+    for total, L, r in [(262144, 32, 4.0), (1000, 7, 2.5), (33, 32, 8.0), (5000, 3, 0.5), (77, 1, 9.0)]:
+        ks = ta.topk_attn_k_schedule(total, L, r)
+        assert sum(ks) == total and min(ks) >= 1 and len(ks) == L
+        assert ks == ref.k_schedule(total, L, r)
+        d = np.diff(ks)
+        if total >= 8 * L:      # linear up to rounding: second differences within +-2
+            assert (np.abs(np.diff(d)) <= 2).all()
+            assert (d >= -1).all() if r >= 1 else (d <= 1).all()
+
+
+def test_k_schedule_rejects_bad_arguments():
+    buf = (ctypes.c_int32 * 4)()
+    L = ta.lib()
+    assert L.topk_attn_k_schedule(3, 4, 1.0, buf) == ta.EINVAL          # fewer keys than layers
+    assert L.topk_attn_k_schedule(100, 0, 1.0, buf) == ta.EINVAL
+    assert L.topk_attn_k_schedule(100, 4, 0.0, buf) == ta.EINVAL
+    assert L.topk_attn_k_schedule(100, 4, float("nan"), buf) == ta.EINVAL
+    assert L.topk_attn_k_schedule(100, 4, 1.0, None) == ta.EINVAL

@@ -444,3 +444,24 @@ def test_window_ragged_batch_and_limits():
         assert torch.equal(o, out0)
     finally:
         cache.close()
+
+
+def test_layerwise_k_schedule_decode():
+    """Per-layer k from the fixed-budget linear schedule (the paper's layer-wise setting),
+    one decode per layer with its own k."""
+    dtype, L, Hq, Hkv, d, N = wl.F16, 4, 8, 2, 128, 24000
+    ks = ta.topk_attn_k_schedule(4 * 400, L, 3.0)
+    assert sum(ks) == 1600 and ks[0] < ks[-1]
+    cache = ta.TopkAttnCache(L, 1, Hq, Hkv, d, N, max(ks), dtype)
+    try:
+        for l in range(L):
+            q, K, V = rand_case(Hq, Hkv, N, d, dtype, ks[l], seed=40 + l)
+            cache.append(l, 0, H.to_torch(K, dtype, DEV), H.to_torch(V, dtype, DEV), head_major=True)
+            out, idx, vals, lse = cache.decode(l, H.to_torch(q, dtype, DEV)[None].contiguous(), ks[l])
+            torch.cuda.synchronize()
+            ref = c_oracle.topk_attention(q, K, V, dtype, ks[l])
+            H.check_against_oracle(out[0].cpu().numpy(), idx[0].cpu().numpy(), vals[0].cpu().numpy(),
+                                   lse[0].cpu().numpy(), ref, H.score_margin(q, K, dtype), ks[l], 2e-3,
+                                   float(np.abs(wl.widen(V, dtype)).max()), f"layer {l} k={ks[l]}")
+    finally:
+        cache.close()
