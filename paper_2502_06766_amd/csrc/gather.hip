@@ -150,48 +150,89 @@ __global__ void __launch_bounds__(256) window_partial_kernel(Shape sh, Bufs bf, 
                          [&](int j) { return exp2f((sm.sc[j - j0] - m) * scale_log2e); }, m, slot0 + chunk_id, sm);
 }
 
+constexpr int kCombineSlots = 1024;   // partial slots whose rescale factors are staged in LDS
+
+// Without a window every partial of a head is relative to the same score (the head's
+// largest selected one): plain sums, one round of loads.
+__global__ void __launch_bounds__(256) gather_sum_kernel(Shape sh, Bufs bf, float scale) {
+    const int h = blockIdx.x, b = blockIdx.y;
+    const int64_t bh = (int64_t)b * sh.Hq + h;
+    const int D = sh.D;
+    const int tid = threadIdx.x, lane = lane_id(), wave = tid >> 6;
+    const int64_t N = bf.len[b];
+    const int k_eff = sh.k < N ? sh.k : (int)N;
+    const int nch = (k_eff + kGatherRows - 1) / kGatherRows;
+    __shared__ float red[256];
+    __shared__ float wred[4];
+    const int parts = 256 / D, e = tid % D, part = tid / D;
+    const float* pa = bf.part_acc + bh * sh.n_chunk_cap * (int64_t)D + e;
+    float a = 0.f;
+#pragma unroll 8
+    for (int ch = part; ch < nch; ch += parts) a += pa[(int64_t)ch * D];
+    float l = 0.f;
+    for (int ch = tid; ch < nch; ch += 256) l += bf.part_l[bh * sh.n_chunk_cap + ch];
+    for (int o = 32; o > 0; o >>= 1) l += wave_xor(l, o);      // fixed tree: same result every run
+    if (lane == 0) wred[wave] = l;
+    red[tid] = a;
+    __syncthreads();
+    if (tid < D) {
+        const float lt = (wred[0] + wred[1]) + (wred[2] + wred[3]);
+        float at = 0.f;
+        for (int p = 0; p < parts; ++p) at += red[p * D + e];
+        bf.out[bh * D + e] = at / lt;
+        if (tid == 0 && bf.lse) bf.lse[bh] = bf.hmax[bh] * scale + logf(lt);
+    }
+}
+
+// With a window the partials carry their own reference scores: log-sum-exp merge.
 __global__ void __launch_bounds__(256) gather_combine_kernel(Shape sh, Bufs bf, float scale, float scale_log2e,
                                                              int n_slots) {
     const int h = blockIdx.x, b = blockIdx.y;
     const int64_t bh = (int64_t)b * sh.Hq + h;
     const int D = sh.D;
+    const int tid = threadIdx.x, lane = lane_id(), wave = tid >> 6;
     __shared__ float red[256];
-    __shared__ float lred[256];
-    __shared__ float mred[256];
+    __shared__ float fac[kCombineSlots];
+    __shared__ float wred[4];
     const float* pl = bf.part_l + bh * sh.n_chunk_cap;
     const float* pm = bf.part_m + bh * sh.n_chunk_cap;
     // reference score of the merged softmax: the largest one any non-empty partial used
     float M = -INFINITY;
-    for (int s = threadIdx.x; s < n_slots; s += 256)
+    for (int s = tid; s < n_slots; s += 256)
         if (pl[s] > 0.f) M = fmaxf(M, pm[s]);
-    mred[threadIdx.x] = M;
+    for (int o = 32; o > 0; o >>= 1) M = fmaxf(M, wave_xor(M, o));
+    if (lane == 0) wred[wave] = M;
     __syncthreads();
-    M = -INFINITY;
-    for (int i = 0; i < 256; ++i) M = fmaxf(M, mred[i]);
+    M = fmaxf(fmaxf(wred[0], wred[1]), fmaxf(wred[2], wred[3]));
+    __syncthreads();
+    // per-slot rescale factor 2^((m_s - M) scale log2e) (0 for an empty slot) and the weight total
+    float l = 0.f;
+    for (int s = tid; s < n_slots; s += 256) {
+        const float ls = pl[s];
+        const float f = ls > 0.f ? exp2f((pm[s] - M) * scale_log2e) : 0.f;
+        if (s < kCombineSlots) fac[s] = f;
+        l = fmaf(ls, f, l);
+    }
+    for (int o = 32; o > 0; o >>= 1) l += wave_xor(l, o);      // fixed tree: same result every run
+    if (lane == 0) wred[wave] = l;
+    __syncthreads();
+    const float lt = (wred[0] + wred[1]) + (wred[2] + wred[3]);
     // 256 / D threads share an output element, each adds every (256 / D)-th partial
-    const int parts = 256 / D, e = threadIdx.x % D, part = threadIdx.x / D;
+    const int parts = 256 / D, e = tid % D, part = tid / D;
     const float* pa = bf.part_acc + bh * sh.n_chunk_cap * (int64_t)D + e;
     float a = 0.f;
-#pragma unroll 4
+#pragma unroll 8
     for (int s = part; s < n_slots; s += parts) {
-        const float l = pl[s];
-        if (l > 0.f) a = fmaf(pa[(int64_t)s * D], exp2f((pm[s] - M) * scale_log2e), a);
+        const float f = s < kCombineSlots ? fac[s] : (pl[s] > 0.f ? exp2f((pm[s] - M) * scale_log2e) : 0.f);
+        if (f > 0.f) a = fmaf(pa[(int64_t)s * D], f, a);
     }
-    float l = 0.f;
-    for (int s = threadIdx.x; s < n_slots; s += 256) {
-        const float ls = pl[s];
-        if (ls > 0.f) l = fmaf(ls, exp2f((pm[s] - M) * scale_log2e), l);
-    }
-    red[threadIdx.x] = a;
-    lred[threadIdx.x] = l;
+    red[tid] = a;
     __syncthreads();
-    if (threadIdx.x < D) {
-        float lt = 0.f;
-        for (int i = 0; i < 256; ++i) lt += lred[i];      // fixed order
+    if (tid < D) {
         float at = 0.f;
         for (int p = 0; p < parts; ++p) at += red[p * D + e];
         bf.out[bh * D + e] = at / lt;
-        if (threadIdx.x == 0 && bf.lse) bf.lse[bh] = M * scale + logf(lt);
+        if (tid == 0 && bf.lse) bf.lse[bh] = M * scale + logf(lt);
     }
 }
 
@@ -220,8 +261,11 @@ hipError_t launch_gather(const Shape& s, const Bufs& b, hipStream_t st) {
         e = hipGetLastError();
         if (e != hipSuccess) return e;
     }
-    hipLaunchKernelGGL(gather_combine_kernel, dim3(s.Hq, s.B), dim3(256), 0, st, s, b, scale, scale_log2e,
-                       nch + nwin);
+    if (nwin > 0)
+        hipLaunchKernelGGL(gather_combine_kernel, dim3(s.Hq, s.B), dim3(256), 0, st, s, b, scale, scale_log2e,
+                           nch + nwin);
+    else
+        hipLaunchKernelGGL(gather_sum_kernel, dim3(s.Hq, s.B), dim3(256), 0, st, s, b, scale);
     return hipGetLastError();
 }
 

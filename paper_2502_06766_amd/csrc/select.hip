@@ -1,12 +1,15 @@
 // Exact top-k selection (the result of the paper's knn_search: the k largest scores
-// `vals` and their positions `I`), by radix select on unique 64-bit keys
-// (order-preserving image of the fp32 score, then inverted position), so that equal
-// scores resolve to the lower position and the selected set never depends on the order
-// in which candidates were produced.  One workgroup per (sequence, head).
+// `vals` and their positions `I`), by radix select.  Scores are compared through an
+// order-preserving 32-bit image of the fp32 value; when the k-th score is shared by more
+// items than fit, a second radix select over the (unique) inverted positions of those
+// items picks the lowest positions, so equal scores resolve to the lower position and the
+// selected set never depends on the order in which candidates were produced.
+// One workgroup per (sequence, head).
 //
-// The first CPT * kSelThreads items of a head are held in registers for all passes; anything
-// beyond is re-read from memory in batches of independent loads.  Output order is fixed
-// (thread-major), so repeated calls return bit-identical results.
+// The first CPT * kSelThreads items of a head keep their score key in registers for all
+// passes (and, for candidate lists, their position in LDS); anything beyond is re-read
+// from memory in batches of independent loads.  Output order is fixed (wave-major), so
+// repeated calls return bit-identical results.
 #include "device_utils.h"
 #include "internal.h"
 
@@ -19,34 +22,45 @@ constexpr int kSelWaves = kSelThreads / kWave;
 constexpr int kDigitBits = TKA_DIGIT_BITS;     // radix digit width
 constexpr int kBins = 1 << kDigitBits;
 constexpr int kBinsPerLane = kBins / kWave;
+constexpr int kCandSlots = 32768;              // candidate slots kept on chip per head
 
 struct SelShared {
     uint32_t hist[kBins];
-    uint64_t red_max[kSelWaves];
-    uint64_t red_min[kSelWaves];
-    uint64_t bc_max, bc_min;
+    uint32_t red_max[kSelWaves];
+    uint32_t red_min[kSelWaves];
+    uint32_t bc_max, bc_min;
     uint32_t bin, above, cb;
     uint32_t wave_tot[kSelWaves];
-    uint32_t scan_total;
     uint32_t seg_len[kMaxSeg];
 };
 
-// Sources of (score, position) items, split into "is there an item in slot i", "where is
-// it" and "turn the loaded word into a key", so that a batch of independent loads can be
-// issued before any of them is consumed.  Key 0 never occurs for a real item (its low
-// word would have to be 0xFFFFFFFF - position = 0) and marks an empty slot.
-struct SrcDense {            // scores[i], position i, i < n
+// Order-preserving key of a score (-0 counts as +0).  0 would need the bit pattern of a
+// NaN, so 0 marks "no item"; inverted positions 0xFFFFFFFF - p are >= 2^31 and never 0.
+__device__ __forceinline__ uint32_t score_key(float s) { return ord_from_bits(__float_as_uint(s + 0.0f)); }
+__device__ __forceinline__ float key_score(uint32_t o) { return __uint_as_float(bits_from_ord(o)); }
+
+// ---------------------------------------------------------------------------------------
+// Sources: slot i of a head either holds an item (score, position) or is empty.
+// ---------------------------------------------------------------------------------------
+struct SrcDense {            // scores[i] at position i, i < n
     const float* s;
     int64_t n;
     typedef float raw_t;
     __device__ __forceinline__ int64_t slots() const { return n; }
     __device__ __forceinline__ bool valid(int64_t i) const { return i < n; }
     __device__ __forceinline__ const float* where(int64_t i) const { return s + i; }
-    __device__ __forceinline__ uint64_t key(float r, int64_t i) const { return composite(r, (uint32_t)i); }
+    __device__ __forceinline__ uint32_t key(float r) const { return score_key(r); }
+    __device__ __forceinline__ uint32_t ipos(float, int64_t i) const { return 0xFFFFFFFFu - (uint32_t)i; }
+    // the position of a cached slot is implied by the slot
+    __device__ __forceinline__ void stash(int, float) const {}
+    __device__ __forceinline__ uint32_t cached_ipos(int j) const {
+        return 0xFFFFFFFFu - (uint32_t)(j * kSelThreads + (int)threadIdx.x);
+    }
 };
 struct SrcSeg {              // candidate list of n_seg interleaved segments: entry e of segment g
     const uint64_t* segs;    // sits in slot e * n_seg + g; entries are (score bits << 32 | position)
     const uint32_t* seg_len; // LDS: entries per segment
+    uint32_t* pos_lds;       // LDS: inverted positions of the cached slots, [slot j][thread]
     int n_seg;               // power of two
     int max_len;             // longest segment
     typedef uint64_t raw_t;
@@ -55,21 +69,27 @@ struct SrcSeg {              // candidate list of n_seg interleaved segments: en
         return i < slots() && (uint32_t)(i / n_seg) < seg_len[i & (n_seg - 1)];
     }
     __device__ __forceinline__ const uint64_t* where(int64_t i) const { return segs + i; }
-    __device__ __forceinline__ uint64_t key(uint64_t e, int64_t) const {
-        return composite(__uint_as_float((uint32_t)(e >> 32)), (uint32_t)e);
+    __device__ __forceinline__ uint32_t key(uint64_t e) const {
+        return score_key(__uint_as_float((uint32_t)(e >> 32)));
     }
+    __device__ __forceinline__ uint32_t ipos(uint64_t e, int64_t) const { return 0xFFFFFFFFu - (uint32_t)e; }
+    __device__ __forceinline__ void stash(int j, uint64_t e) const {
+        pos_lds[j * kSelThreads + (int)threadIdx.x] = 0xFFFFFFFFu - (uint32_t)e;
+    }
+    __device__ __forceinline__ uint32_t cached_ipos(int j) const { return pos_lds[j * kSelThreads + (int)threadIdx.x]; }
 };
 
-// The items of one head as seen by one thread: register slot j holds slot
-// j * kSelThreads + tid of the source, later slots are streamed.  Every lane of a wave visits the
-// same slots in the same order (with a per-lane "present" flag), so callers may use
-// wave-wide ballots inside the visitor.
+// The items of one head as seen by one thread: register slot j holds the score key of
+// source slot j * kSelThreads + tid, later slots are streamed.  Every lane of a wave
+// visits the same slots in the same order (with a per-lane "present" flag), so visitors
+// may use wave-wide ballots.
 template <int CPT, class Src>
 struct Items {
-    uint64_t kc[CPT > 0 ? CPT : 1];
-    const Src& src;
+    uint32_t kc[CPT > 0 ? CPT : 1];
+    const Src src;      // by value: keeps the LDS pointers inside visible to the compiler as LDS
     __device__ __forceinline__ Items(const Src& s) : src(s) {
-        constexpr int B = CPT < 8 ? (CPT > 0 ? CPT : 1) : 8;     // independent loads per batch
+        constexpr int BMAX = 16;                                   // independent loads per batch
+        constexpr int B = CPT < BMAX ? (CPT > 0 ? CPT : 1) : BMAX;
 #pragma unroll
         for (int j0 = 0; j0 < CPT; j0 += B) {
             typename Src::raw_t r[B];
@@ -85,17 +105,17 @@ struct Items {
 #pragma unroll
             for (int u = 0; u < B; ++u) {
                 if (j0 + u < CPT) {
-                    const int64_t i = (int64_t)(j0 + u) * kSelThreads + threadIdx.x;
-                    kc[j0 + u] = ok[u] ? src.key(r[u], i) : 0ull;
+                    kc[j0 + u] = ok[u] ? src.key(r[u]) : 0u;
+                    if (ok[u]) src.stash(j0 + u, r[u]);
                 }
             }
         }
     }
-    // f(key, present) for every slot, all lanes in lock step
+    // f(score key, inverted position, present) for every slot, all lanes in lock step
     template <class F>
-    __device__ __forceinline__ void for_each_sync(F f) const {
+    __device__ __forceinline__ void visit(F f) const {
 #pragma unroll
-        for (int j = 0; j < CPT; ++j) f(kc[j], kc[j] != 0ull);
+        for (int j = 0; j < CPT; ++j) f(kc[j], src.cached_ipos(j), kc[j] != 0u);
         constexpr int U = 8;
         const int64_t n_slots = src.slots();
         for (int64_t base = (int64_t)CPT * kSelThreads; base < n_slots; base += (int64_t)U * kSelThreads) {
@@ -110,65 +130,47 @@ struct Items {
 #pragma unroll
             for (int u = 0; u < U; ++u) {
                 const int64_t i = base + (int64_t)u * kSelThreads + threadIdx.x;
-                f(ok[u] ? src.key(r[u], i) : 0ull, ok[u]);
+                f(ok[u] ? src.key(r[u]) : 0u, src.ipos(r[u], i), ok[u]);
             }
         }
     }
-    template <class F>
-    __device__ __forceinline__ void for_each(F f) const {
-        for_each_sync([&](uint64_t c, bool present) { if (present) f(c); });
-    }
 };
 
-// exclusive prefix sum of one value per thread over the workgroup; *total gets the sum
-__device__ __forceinline__ uint32_t wg_exclusive_scan(uint32_t v, SelShared& sm, uint32_t* total) {
-    const int lane = lane_id(), wave = threadIdx.x >> 6;
-    uint32_t incl = v;
-    for (int o = 1; o < kWave; o <<= 1) {
-        const uint32_t t = __shfl_up(incl, o, kWave);
-        if (lane >= o) incl += t;
-    }
-    __syncthreads();                      // protects wave_tot against a previous use
-    if (lane == kWave - 1) sm.wave_tot[wave] = incl;
-    __syncthreads();
-    if (wave == 0) {
-        uint32_t w = lane < kSelWaves ? sm.wave_tot[lane] : 0u;
-        uint32_t wi = w;
-        for (int o = 1; o < kSelWaves; o <<= 1) {
-            const uint32_t t = __shfl_up(wi, o, kWave);
-            if (lane >= o) wi += t;
-        }
-        if (lane < kSelWaves) sm.wave_tot[lane] = wi - w;
-        if (lane == kSelWaves - 1) sm.scan_total = wi;
-    }
-    __syncthreads();
-    *total = sm.scan_total;
-    return sm.wave_tot[wave] + incl - v;
-}
+// Result of a radix select of the k largest among a multiset of 32-bit keys: the wanted
+// keys are all keys > T plus `need` of the `have` keys in the threshold class.  The class
+// is "key == T" when `exact`; otherwise the select stopped early because the whole last
+// bin was wanted (need == have) and the wanted keys are simply all keys >= T.
+struct Sel32 {
+    uint32_t T, kmax, need, have;
+    bool exact;
+};
 
-// Returns T such that exactly k of the n items have key >= T (1 <= k <= n).
-// *kmax receives the largest key.  All threads of the workgroup must call it.
-template <class It>
-__device__ uint64_t wg_select_kth(const It& items, int64_t n, int64_t k, SelShared& sm, uint64_t* kmax) {
+// `keys(f)` must call f(key, present) for every slot, slot-synchronously.
+// 1 <= k <= number of present keys.  All threads of the workgroup must call it.
+template <class Keys>
+__device__ __forceinline__ Sel32 wg_select32(Keys keys, int64_t k, SelShared& sm) {
     const int tid = threadIdx.x, lane = lane_id(), wave = tid >> 6;
-    uint64_t mx = 0, mn = ~0ull;
-    items.for_each([&](uint64_t c) {
-        mx = c > mx ? c : mx;
-        mn = c < mn ? c : mn;
+    uint32_t mx = 0u, mn = ~0u;
+    keys([&](uint32_t c, bool present) {
+        if (present) {
+            mx = c > mx ? c : mx;
+            mn = c < mn ? c : mn;
+        }
     });
     for (int o = 32; o > 0; o >>= 1) {
-        const uint64_t a = __shfl_xor(mx, o, kWave), b = __shfl_xor(mn, o, kWave);
+        const uint32_t a = __shfl_xor(mx, o, kWave), b = __shfl_xor(mn, o, kWave);
         mx = a > mx ? a : mx;
         mn = b < mn ? b : mn;
     }
+    __syncthreads();                  // the shared scratch may still be read by a previous select
     if (lane == 0) { sm.red_max[wave] = mx; sm.red_min[wave] = mn; }
     for (int i = tid; i < kBins; i += kSelThreads) sm.hist[i] = 0;
     __syncthreads();
     if (wave == 0) {
-        mx = lane < kSelWaves ? sm.red_max[lane] : 0ull;
-        mn = lane < kSelWaves ? sm.red_min[lane] : ~0ull;
+        mx = lane < kSelWaves ? sm.red_max[lane] : 0u;
+        mn = lane < kSelWaves ? sm.red_min[lane] : ~0u;
         for (int o = 32; o > 0; o >>= 1) {
-            const uint64_t a = __shfl_xor(mx, o, kWave), b = __shfl_xor(mn, o, kWave);
+            const uint32_t a = __shfl_xor(mx, o, kWave), b = __shfl_xor(mn, o, kWave);
             mx = a > mx ? a : mx;
             mn = b < mn ? b : mn;
         }
@@ -176,29 +178,39 @@ __device__ uint64_t wg_select_kth(const It& items, int64_t n, int64_t k, SelShar
     }
     __syncthreads();
     mx = sm.bc_max; mn = sm.bc_min;
-    *kmax = mx;
-    if (k >= n) return mn;
-    if (k == 1) return mx;
-
-    // bits above `rb` are common to every remaining item and fixed in `prefix`
-    int rb = 64 - __clzll((long long)(mx ^ mn));   // mx != mn: keys are unique and n >= 3 here
-    uint64_t prefix = rb >= 64 ? 0ull : (mx >> rb) << rb;
+    Sel32 res;
+    res.kmax = mx;
+    if (mx == mn) {                   // one distinct key: the class is everything
+        uint32_t cnt = 0;
+        keys([&](uint32_t, bool present) { cnt += (uint32_t)__popcll(__ballot(present)); });
+        __syncthreads();
+        if (lane == 0) sm.wave_tot[wave] = cnt;
+        __syncthreads();
+        uint32_t total = 0;
+        for (int w = 0; w < kSelWaves; ++w) total += sm.wave_tot[w];
+        res.T = mx; res.need = (uint32_t)k; res.have = total; res.exact = true;
+        return res;
+    }
+    // bits above `rb` are common to every remaining key and fixed in `prefix`
+    int rb = 32 - __clz((int)(mx ^ mn));
+    uint32_t prefix = rb >= 32 ? 0u : (mx >> rb) << rb;
     int64_t k_rem = k;
-    while (rb > 0) {
+    uint32_t cb = 0;
+    while (true) {
         const int w = rb < kDigitBits ? rb : kDigitBits;
         const int shift = rb - w;
         const uint32_t dmask = (1u << w) - 1u;
-        const uint64_t want = rb >= 64 ? 0ull : (prefix >> rb);
-        const int rbs = rb >= 64 ? 63 : rb;          // shift amount that is always defined
-        const bool all = rb >= 64;
-        items.for_each([&](uint64_t c) {
-            if (all || (c >> rbs) == want) atomicAdd(&sm.hist[(uint32_t)(c >> shift) & dmask], 1u);
+        const uint32_t want = rb >= 32 ? 0u : (prefix >> rb);
+        const int rbs = rb >= 32 ? 31 : rb;          // a shift amount that is always defined
+        const bool all = rb >= 32;
+        keys([&](uint32_t c, bool present) {
+            if (present && (all || (c >> rbs) == want)) atomicAdd(&sm.hist[(c >> shift) & dmask], 1u);
         });
         __syncthreads();
         if (wave == 0) {
             // digits in descending order: position p = kBinsPerLane * lane + i <-> bin kBins-1-p
             uint32_t local = 0;
-#pragma unroll 8
+#pragma unroll
             for (int i = 0; i < kBinsPerLane; ++i)   // rotated start: lanes hit different LDS banks
                 local += sm.hist[kBins - 1 - (kBinsPerLane * lane + ((i + lane) & (kBinsPerLane - 1)))];
             uint32_t incl = local;
@@ -221,17 +233,22 @@ __device__ uint64_t wg_select_kth(const It& items, int64_t n, int64_t k, SelShar
             }
         }
         __syncthreads();
-        const uint32_t bin = sm.bin, above = sm.above, cb = sm.cb;
+        const uint32_t bin = sm.bin, above = sm.above;
+        cb = sm.cb;
         __syncthreads();
         for (int i = tid; i < kBins; i += kSelThreads) sm.hist[i] = 0;
-        prefix |= (uint64_t)bin << shift;
+        prefix |= bin << shift;
         k_rem -= above;
         rb = shift;
-        if ((int64_t)cb == k_rem) break;   // the whole bin is selected
+        if ((int64_t)cb == k_rem || rb == 0) break;   // the whole bin is wanted, or all bits are fixed
         __syncthreads();
     }
     __syncthreads();
-    return prefix;
+    res.T = prefix;
+    res.need = (uint32_t)k_rem;
+    res.have = cb;
+    res.exact = rb == 0;
+    return res;
 }
 
 // Slots the selection does not fill: position -1, score -inf.
@@ -242,36 +259,53 @@ __device__ __forceinline__ void pad_outputs(int k_eff, int k, int32_t* idx, floa
     }
 }
 
-// Write the items with key >= T (exactly k_eff of them) to idx/vals and pad up to k.
-// Order: wave-major, then slot, then lane -- fixed, and each store instruction of a wave
-// writes one contiguous run.
+// Exact top-k_eff of the items: select on the score keys, break a tie at the k-th score
+// by position, write idx/vals (wave-major, then slot, then lane: fixed, and every store
+// instruction of a wave writes one contiguous run) and pad up to k.  Returns the largest key.
 template <class It>
-__device__ void wg_emit(const It& items, uint64_t T, int k_eff, int k, int32_t* idx, float* vals, SelShared& sm) {
+__device__ __forceinline__ uint32_t wg_topk_emit(const It& items, int k_eff, int k, int32_t* idx, float* vals, SelShared& sm) {
     const int lane = lane_id(), wave = threadIdx.x >> 6;
+    const Sel32 s = wg_select32([&](auto f) { items.visit([&](uint32_t c, uint32_t, bool p) { f(c, p); }); },
+                                (int64_t)k_eff, sm);
+    const bool ties = s.need < s.have;    // (uniform) more items share the k-th score than fit
+    uint32_t T2 = 0u;                     // then: inverted-position threshold inside the class key == T
+    if (ties) {
+        // positions are unique, so this select always ends with need == have: ipos >= T2 is exact
+        const Sel32 t = wg_select32(
+            [&](auto f) { items.visit([&](uint32_t c, uint32_t ip, bool p) { f(ip, p && c == s.T); }); },
+            (int64_t)s.need, sm);
+        T2 = t.T;
+    }
+    auto wanted = [&](uint32_t c, uint32_t ip, bool present) {
+        return present && (c > s.T || (c == s.T && (!ties || ip >= T2)));
+    };
     uint32_t wave_total = 0;
-    items.for_each_sync([&](uint64_t c, bool present) { wave_total += (uint32_t)__popcll(__ballot(present && c >= T)); });
+    items.visit([&](uint32_t c, uint32_t ip, bool p) {
+        wave_total += (uint32_t)__popcll(__ballot(wanted(c, ip, p)));
+    });
     __syncthreads();
     if (lane == 0) sm.wave_tot[wave] = wave_total;
     __syncthreads();
     uint32_t run = 0;
     for (int w = 0; w < wave; ++w) run += sm.wave_tot[w];
-    items.for_each_sync([&](uint64_t c, bool present) {
-        const bool sel = present && c >= T;
+    items.visit([&](uint32_t c, uint32_t ip, bool p) {
+        const bool sel = wanted(c, ip, p);
         const uint64_t m = __ballot(sel);
         if (sel) {
             const uint32_t slot = run + (uint32_t)mask_rank(m);
             if (slot < (uint32_t)k_eff) {     // always true; guards the output buffer
-                idx[slot] = (int32_t)composite_pos(c);
-                vals[slot] = composite_score(c);
+                idx[slot] = (int32_t)(0xFFFFFFFFu - ip);
+                vals[slot] = key_score(c);
             }
         }
         run += (uint32_t)__popcll(m);
     });
     pad_outputs(k_eff, k, idx, vals);
+    return s.kmax;
 }
 
-// Threshold estimate: the rank-th largest of the sample scores of each head; also clears
-// the head's fallback flag for the scan that follows.
+// Threshold estimate: the rank-th largest of the sample scores of each head (any value
+// with `rank` samples at or above it serves); also clears the head's fallback flag.
 __global__ void __launch_bounds__(kSelThreads) threshold_kernel(Shape sh, Bufs bf) {
     __shared__ SelShared sm;
     const int b = blockIdx.y, h = blockIdx.x;
@@ -289,11 +323,11 @@ __global__ void __launch_bounds__(kSelThreads) threshold_kernel(Shape sh, Bufs b
     const Plan pl = make_plan(N, k_eff);
     const SrcDense src{bf.samp + bh * sh.samp_cap, (int64_t)pl.n_samp};
     const Items<(kSampMax + kSelThreads - 1) / kSelThreads, SrcDense> items(src);
-    uint64_t kmax;
     const int rank = pl.rank < pl.n_samp ? pl.rank : pl.n_samp;
-    const uint64_t T = wg_select_kth(items, (int64_t)pl.n_samp, (int64_t)rank, sm, &kmax);
+    const Sel32 s = wg_select32([&](auto f) { items.visit([&](uint32_t c, uint32_t, bool p) { f(c, p); }); },
+                                (int64_t)rank, sm);
     if (threadIdx.x == 0) {
-        bf.thr[bh] = composite_score(T);
+        bf.thr[bh] = key_score(s.T);
         bf.flags[bh] = 0;
         if (bh == 0) *bf.fallback_total = 0;
     }
@@ -303,6 +337,7 @@ __global__ void __launch_bounds__(kSelThreads) threshold_kernel(Shape sh, Bufs b
 // per-wave segments.
 __global__ void __launch_bounds__(kSelThreads) select_candidates_kernel(Shape sh, Bufs bf) {
     __shared__ SelShared sm;
+    __shared__ uint32_t pos_lds[kCandSlots];
     const int b = blockIdx.y, h = blockIdx.x;
     const int tid = threadIdx.x, lane = lane_id(), wave = tid >> 6;
     const int64_t bh = (int64_t)b * sh.Hq + h;
@@ -332,7 +367,7 @@ __global__ void __launch_bounds__(kSelThreads) select_candidates_kernel(Shape sh
     uint32_t total = 0, max_len = 0;
     for (int w = 0; w < kSelWaves; ++w) {
         total += sm.wave_tot[w];
-        max_len = (uint32_t)sm.red_max[w] > max_len ? (uint32_t)sm.red_max[w] : max_len;
+        max_len = sm.red_max[w] > max_len ? sm.red_max[w] : max_len;
     }
     __syncthreads();
     if (max_len > (uint32_t)sh.seg_cap || total < (uint32_t)k_eff) {   // uniform: a segment overflowed, or
@@ -342,12 +377,10 @@ __global__ void __launch_bounds__(kSelThreads) select_candidates_kernel(Shape sh
         }
         return;
     }
-    const SrcSeg src{bf.cand + bh * (int64_t)sh.cand_cap, sm.seg_len, sh.n_seg, (int)max_len};
-    const Items<(32768 + kSelThreads - 1) / kSelThreads, SrcSeg> items(src);
-    uint64_t kmax;
-    const uint64_t T = wg_select_kth(items, (int64_t)total, (int64_t)k_eff, sm, &kmax);
-    wg_emit(items, T, k_eff, sh.k, bf.sel_idx + bh * sh.k, bf.sel_val + bh * sh.k, sm);
-    if (tid == 0) bf.hmax[bh] = composite_score(kmax);
+    const SrcSeg src{bf.cand + bh * (int64_t)sh.cand_cap, sm.seg_len, pos_lds, sh.n_seg, (int)max_len};
+    const Items<kCandSlots / kSelThreads, SrcSeg> items(src);
+    const uint32_t kmax = wg_topk_emit(items, k_eff, sh.k, bf.sel_idx + bh * sh.k, bf.sel_val + bh * sh.k, sm);
+    if (tid == 0) bf.hmax[bh] = key_score(kmax);
 }
 
 // Exact selection over the full score row (general path, and heads the filter gave up on).
@@ -365,10 +398,8 @@ __global__ void __launch_bounds__(kSelThreads) select_full_kernel(Shape sh, Bufs
     }
     const SrcDense src{bf.scores + bh * sh.Ncap, N};
     const Items<(8192 + kSelThreads - 1) / kSelThreads, SrcDense> items(src);
-    uint64_t kmax;
-    const uint64_t T = wg_select_kth(items, N, (int64_t)k_eff, sm, &kmax);
-    wg_emit(items, T, k_eff, sh.k, bf.sel_idx + bh * sh.k, bf.sel_val + bh * sh.k, sm);
-    if (threadIdx.x == 0) bf.hmax[bh] = composite_score(kmax);
+    const uint32_t kmax = wg_topk_emit(items, k_eff, sh.k, bf.sel_idx + bh * sh.k, bf.sel_val + bh * sh.k, sm);
+    if (threadIdx.x == 0) bf.hmax[bh] = key_score(kmax);
 }
 
 hipError_t launch_threshold(const Shape& s, const Bufs& b, hipStream_t st) {
