@@ -352,12 +352,11 @@ static int decode_impl(topk_attn_t* h, int layer, const void* q, int k, int wind
         if (e == hipSuccess && timed) e = hipEventRecord(h->ev[2 * h->ev_used + 1], st);
         if (e == hipSuccess && timed) h->ev_used++;
         if (e == hipSuccess) e = launch_select_candidates(s, b, st);
-        if (e == hipSuccess) e = launch_scan_full(s, b, nmax, true, b.scores, st);
-        if (e == hipSuccess) e = launch_select_full(s, b, true, st);
+        if (e == hipSuccess) e = launch_select_full(s, b, true, st);   // redoes flagged heads only, else exits at once
     } else {
         if (nmax > 0) {
             if (timed) e = hipEventRecord(h->ev[2 * h->ev_used], st);
-            if (e == hipSuccess) e = launch_scan_full(s, b, nmax, false, b.scores, st);
+            if (e == hipSuccess) e = launch_scan_full(s, b, nmax, b.scores, st);
             if (e == hipSuccess && timed) e = hipEventRecord(h->ev[2 * h->ev_used + 1], st);
             if (e == hipSuccess && timed) h->ev_used++;
         }
@@ -422,7 +421,7 @@ int topk_attn_scores(topk_attn_t* h, int layer, const void* q, float* scores, vo
     if (lengths_of(h, layer, 0, &nmin, &nmax) != TOPK_ATTN_OK) return TOPK_ATTN_EINVAL;
     Shape s; Bufs b;
     fill_call(h, layer, q, 1, &s, &b);
-    hipError_t e = launch_scan_full(s, b, nmax, false, scores, (hipStream_t)hip_stream);
+    hipError_t e = launch_scan_full(s, b, nmax, scores, (hipStream_t)hip_stream);
     return e == hipSuccess ? TOPK_ATTN_OK : TOPK_ATTN_EDEVICE;
 }
 

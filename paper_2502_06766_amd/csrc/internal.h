@@ -109,13 +109,12 @@ __host__ __device__ inline int64_t sample_pos(int s, int stride) {
 // Launch wrappers (each returns the hipError_t of the launch).
 hipError_t launch_scan_sample(const Shape& s, const Bufs& b, int64_t Nmax, hipStream_t st);
 hipError_t launch_scan_filter(const Shape& s, const Bufs& b, int64_t Nmax, hipStream_t st);
-hipError_t launch_scan_full(const Shape& s, const Bufs& b, int64_t Nmax, bool only_flagged, float* dst,
-                            hipStream_t st);
+hipError_t launch_scan_full(const Shape& s, const Bufs& b, int64_t Nmax, float* dst, hipStream_t st);
 bool scan_mfma_supported(const Shape& s);
 
 hipError_t launch_threshold(const Shape& s, const Bufs& b, hipStream_t st);
 hipError_t launch_select_candidates(const Shape& s, const Bufs& b, hipStream_t st);
-hipError_t launch_select_full(const Shape& s, const Bufs& b, bool only_flagged, hipStream_t st);
+hipError_t launch_select_full(const Shape& s, const Bufs& b, bool redo_flagged, hipStream_t st);
 
 hipError_t launch_gather(const Shape& s, const Bufs& b, hipStream_t st);
 

@@ -140,7 +140,7 @@ __device__ __forceinline__ void filter_head(float score, float thr, CandStage& c
 
 template <int DT, int D, int MODE>
 __global__ void __launch_bounds__(kScanWaves* kWave)
-scan_mfma_kernel(Shape sh, Bufs bf, int tiles_per_wave, int only_flagged, float* dst) {
+scan_mfma_kernel(Shape sh, Bufs bf, int tiles_per_wave, float* dst) {
     using v8 = typename Mfma<DT>::v8;
     const int b = blockIdx.z, kvh = blockIdx.y;
     const int G = sh.G;
@@ -148,12 +148,6 @@ scan_mfma_kernel(Shape sh, Bufs bf, int tiles_per_wave, int only_flagged, float*
     const int lane = lane_id();
     const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));   // wave-uniform
     const int64_t N = prefix_len(bf.len[b], sh.window);
-
-    if (MODE == MODE_FULL && only_flagged) {
-        uint32_t any = 0;
-        for (int r = 0; r < G; ++r) any |= bf.flags[head0 + r];
-        if (!any) return;
-    }
 
     int64_t n_items = N;   // keys (or samples) this (b, kv head) has
     int stride = 1;
@@ -281,17 +275,12 @@ scan_mfma_kernel(Shape sh, Bufs bf, int tiles_per_wave, int only_flagged, float*
 // head groupings): a row of D elements is spread over D*e/16 lanes, 16 bytes each.
 template <int DT>
 __global__ void __launch_bounds__(256)
-scan_generic_kernel(Shape sh, Bufs bf, int rows_per_block, int only_flagged, float* dst) {
+scan_generic_kernel(Shape sh, Bufs bf, int rows_per_block, float* dst) {
     constexpr int EPL = Elem<DT>::kPerLoad;
     const int b = blockIdx.z, kvh = blockIdx.y;
     const int G = sh.G, D = sh.D;
     const int64_t head0 = (int64_t)b * sh.Hq + (int64_t)kvh * G;
     const int64_t N = prefix_len(bf.len[b], sh.window);
-    if (only_flagged) {
-        uint32_t any = 0;
-        for (int r = 0; r < G; ++r) any |= bf.flags[head0 + r];
-        if (!any) return;
-    }
     const int64_t row_begin = (int64_t)blockIdx.x * rows_per_block;
     if (row_begin >= N) return;
 
@@ -347,16 +336,14 @@ static int tiles_per_wave_for(int64_t n_items, int B, int Hkv) {
 }
 
 template <int MODE>
-static hipError_t launch_mfma(const Shape& s, const Bufs& b, int64_t n_items, bool only_flagged, float* dst,
-                              hipStream_t st) {
+static hipError_t launch_mfma(const Shape& s, const Bufs& b, int64_t n_items, float* dst, hipStream_t st) {
     const int tpw = tiles_per_wave_for(n_items, s.B, s.Hkv);
     const int64_t tiles = (n_items + 63) / 64;
     const int64_t per_wg = (int64_t)tpw * kScanWaves;
     dim3 grid((unsigned)((tiles + per_wg - 1) / per_wg), (unsigned)s.Hkv, (unsigned)s.B);
     dim3 block(kScanWaves * kWave);
-    const int of = only_flagged ? 1 : 0;
 #define TKA_LAUNCH(DT_, D_) \
-    hipLaunchKernelGGL((scan_mfma_kernel<DT_, D_, MODE>), grid, block, 0, st, s, b, tpw, of, dst)
+    hipLaunchKernelGGL((scan_mfma_kernel<DT_, D_, MODE>), grid, block, 0, st, s, b, tpw, dst)
     if (s.dtype == DT_F16 && s.D == 128) TKA_LAUNCH(DT_F16, 128);
     else if (s.dtype == DT_F16 && s.D == 64) TKA_LAUNCH(DT_F16, 64);
     else if (s.dtype == DT_BF16 && s.D == 128) TKA_LAUNCH(DT_BF16, 128);
@@ -368,7 +355,7 @@ static hipError_t launch_mfma(const Shape& s, const Bufs& b, int64_t n_items, bo
 
 hipError_t launch_scan_sample(const Shape& s, const Bufs& b, int64_t Nmax, hipStream_t st) {
     Plan pl = make_plan(Nmax, s.k);
-    return launch_mfma<MODE_SAMPLE>(s, b, pl.n_samp, false, nullptr, st);
+    return launch_mfma<MODE_SAMPLE>(s, b, pl.n_samp, nullptr, st);
 }
 
 hipError_t launch_scan_filter(const Shape& s, const Bufs& b, int64_t Nmax, hipStream_t st) {
@@ -377,7 +364,7 @@ hipError_t launch_scan_filter(const Shape& s, const Bufs& b, int64_t Nmax, hipSt
     dim3 grid((unsigned)(s.n_seg / kScanWaves), (unsigned)s.Hkv, (unsigned)s.B);
     dim3 block(kScanWaves * kWave);
 #define TKA_LAUNCH(DT_, D_) \
-    hipLaunchKernelGGL((scan_mfma_kernel<DT_, D_, MODE_FILTER>), grid, block, 0, st, s, b, 0, 0, (float*)nullptr)
+    hipLaunchKernelGGL((scan_mfma_kernel<DT_, D_, MODE_FILTER>), grid, block, 0, st, s, b, 0, (float*)nullptr)
     if (s.dtype == DT_F16 && s.D == 128) TKA_LAUNCH(DT_F16, 128);
     else if (s.dtype == DT_F16 && s.D == 64) TKA_LAUNCH(DT_F16, 64);
     else if (s.dtype == DT_BF16 && s.D == 128) TKA_LAUNCH(DT_BF16, 128);
@@ -387,21 +374,19 @@ hipError_t launch_scan_filter(const Shape& s, const Bufs& b, int64_t Nmax, hipSt
     return hipGetLastError();
 }
 
-hipError_t launch_scan_full(const Shape& s, const Bufs& b, int64_t Nmax, bool only_flagged, float* dst,
-                            hipStream_t st) {
-    if (scan_mfma_supported(s)) return launch_mfma<MODE_FULL>(s, b, Nmax, only_flagged, dst, st);
+hipError_t launch_scan_full(const Shape& s, const Bufs& b, int64_t Nmax, float* dst, hipStream_t st) {
+    if (scan_mfma_supported(s)) return launch_mfma<MODE_FULL>(s, b, Nmax, dst, st);
     const int epl = s.dtype == DT_F32 ? 4 : 8;
     const int lpr = s.D / epl;
     const int rows_per_pass = 256 / lpr;
     int64_t rows_per_block = (int64_t)rows_per_pass * 16;
     dim3 grid((unsigned)((Nmax + rows_per_block - 1) / rows_per_block), (unsigned)s.Hkv, (unsigned)s.B);
-    const int of = only_flagged ? 1 : 0;
     if (s.dtype == DT_F32)
-        hipLaunchKernelGGL((scan_generic_kernel<DT_F32>), grid, dim3(256), 0, st, s, b, (int)rows_per_block, of, dst);
+        hipLaunchKernelGGL((scan_generic_kernel<DT_F32>), grid, dim3(256), 0, st, s, b, (int)rows_per_block, dst);
     else if (s.dtype == DT_F16)
-        hipLaunchKernelGGL((scan_generic_kernel<DT_F16>), grid, dim3(256), 0, st, s, b, (int)rows_per_block, of, dst);
+        hipLaunchKernelGGL((scan_generic_kernel<DT_F16>), grid, dim3(256), 0, st, s, b, (int)rows_per_block, dst);
     else
-        hipLaunchKernelGGL((scan_generic_kernel<DT_BF16>), grid, dim3(256), 0, st, s, b, (int)rows_per_block, of, dst);
+        hipLaunchKernelGGL((scan_generic_kernel<DT_BF16>), grid, dim3(256), 0, st, s, b, (int)rows_per_block, dst);
     return hipGetLastError();
 }
 

@@ -32,6 +32,7 @@ struct SelShared {
     uint32_t bin, above, cb;
     uint32_t wave_tot[kSelWaves];
     uint32_t seg_len[kMaxSeg];
+    float qrow[256];
 };
 
 // Order-preserving key of a score (-0 counts as +0).  0 would need the bit pattern of a
@@ -304,6 +305,43 @@ __device__ __forceinline__ uint32_t wg_topk_emit(const It& items, int k_eff, int
     return s.kmax;
 }
 
+// Scores of all N keys against one query head, computed by this workgroup alone with plain
+// FMAs (rows of D elements spread over D*e/16 lanes).  Only used to redo a head whose
+// candidate list turned out unusable, so speed does not matter.
+template <int DT>
+__device__ void wg_score_head(const Shape& sh, const Bufs& bf, int b, int h, int64_t N, float* dst, SelShared& sm) {
+    constexpr int EPL = Elem<DT>::kPerLoad;
+    const int D = sh.D;
+    const int64_t bh = (int64_t)b * sh.Hq + h;
+    for (int i = threadIdx.x; i < D; i += kSelThreads) {
+        const char* qp = static_cast<const char*>(bf.q) + (bh * D + i) * Elem<DT>::kBytes;
+        float v;
+        if (DT == DT_F32) v = *reinterpret_cast<const float*>(qp);
+        else if (DT == DT_F16) v = (float)*reinterpret_cast<const _Float16*>(qp);
+        else v = __uint_as_float((uint32_t)*reinterpret_cast<const uint16_t*>(qp) << 16);
+        sm.qrow[i] = v;
+    }
+    __syncthreads();
+    const int lpr = D / EPL, rows_per_pass = kSelThreads / lpr;
+    const int rs = threadIdx.x / lpr, chunk = threadIdx.x % lpr;
+    const char* Kh = static_cast<const char*>(bf.K) +
+                     ((int64_t)b * sh.Hkv + h / sh.G) * sh.Ncap * D * Elem<DT>::kBytes;
+    for (int64_t base = 0; base < N; base += rows_per_pass) {
+        const int64_t row = base + rs;
+        const bool valid = row < N;
+        const u32x4 raw =
+            *reinterpret_cast<const u32x4*>(Kh + ((valid ? row : N - 1) * D + chunk * EPL) * Elem<DT>::kBytes);
+        float kf[EPL];
+        Elem<DT>::widen(raw, kf);
+        float acc = 0.f;
+#pragma unroll
+        for (int e = 0; e < EPL; ++e) acc = fmaf(kf[e], sm.qrow[chunk * EPL + e], acc);
+        for (int m = 1; m < lpr; m <<= 1) acc += wave_xor(acc, m);
+        if (valid && chunk == 0) dst[row] = acc;
+    }
+    __syncthreads();   // the scores are read back by other threads of this workgroup
+}
+
 // Threshold estimate: the rank-th largest of the sample scores of each head (any value
 // with `rank` samples at or above it serves); also clears the head's fallback flag.
 __global__ void __launch_bounds__(kSelThreads) threshold_kernel(Shape sh, Bufs bf) {
@@ -383,18 +421,26 @@ __global__ void __launch_bounds__(kSelThreads) select_candidates_kernel(Shape sh
     if (tid == 0) bf.hmax[bh] = key_score(kmax);
 }
 
-// Exact selection over the full score row (general path, and heads the filter gave up on).
-__global__ void __launch_bounds__(kSelThreads) select_full_kernel(Shape sh, Bufs bf, int only_flagged) {
+// Exact selection over the full score row.  General path: the scores are already in the
+// score buffer.  After a filtered scan (`redo_flagged`): only the heads whose candidate
+// list was unusable run, and each rescores its whole head itself first -- slow, rare, exact.
+__global__ void __launch_bounds__(kSelThreads) select_full_kernel(Shape sh, Bufs bf, int redo_flagged) {
     __shared__ SelShared sm;
     const int b = blockIdx.y, h = blockIdx.x;
     const int64_t bh = (int64_t)b * sh.Hq + h;
-    if (only_flagged && !bf.flags[bh]) return;
+    if (redo_flagged && !bf.flags[bh]) return;
     const int64_t N = prefix_len(bf.len[b], sh.window);
     const int k_eff = sh.k < N ? sh.k : (int)N;
     if (k_eff == 0) {
         pad_outputs(0, sh.k, bf.sel_idx + bh * sh.k, bf.sel_val + bh * sh.k);
         if (threadIdx.x == 0) bf.hmax[bh] = -INFINITY;
         return;
+    }
+    if (redo_flagged) {
+        float* row = bf.scores + bh * sh.Ncap;
+        if (sh.dtype == DT_F16) wg_score_head<DT_F16>(sh, bf, b, h, N, row, sm);
+        else if (sh.dtype == DT_BF16) wg_score_head<DT_BF16>(sh, bf, b, h, N, row, sm);
+        else wg_score_head<DT_F32>(sh, bf, b, h, N, row, sm);
     }
     const SrcDense src{bf.scores + bh * sh.Ncap, N};
     const Items<(8192 + kSelThreads - 1) / kSelThreads, SrcDense> items(src);
@@ -410,8 +456,8 @@ hipError_t launch_select_candidates(const Shape& s, const Bufs& b, hipStream_t s
     hipLaunchKernelGGL(select_candidates_kernel, dim3(s.Hq, s.B), dim3(kSelThreads), 0, st, s, b);
     return hipGetLastError();
 }
-hipError_t launch_select_full(const Shape& s, const Bufs& b, bool only_flagged, hipStream_t st) {
-    hipLaunchKernelGGL(select_full_kernel, dim3(s.Hq, s.B), dim3(kSelThreads), 0, st, s, b, only_flagged ? 1 : 0);
+hipError_t launch_select_full(const Shape& s, const Bufs& b, bool redo_flagged, hipStream_t st) {
+    hipLaunchKernelGGL(select_full_kernel, dim3(s.Hq, s.B), dim3(kSelThreads), 0, st, s, b, redo_flagged ? 1 : 0);
     return hipGetLastError();
 }
 
