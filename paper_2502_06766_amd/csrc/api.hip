@@ -23,7 +23,7 @@ inline size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
 inline int elem_bytes(int dtype) { return dtype == TOPK_ATTN_F32 ? 4 : 2; }
 
 struct WsLayout {
-    size_t len, thr, samp, seg_cnt, flags, hmax, fallback, cand, scores, sel_idx, sel_val, part_acc, part_l, part_m, total;
+    size_t len, thr, samp, seg_cnt, seg_max, flags, hmax, fallback, cand, scores, sel_idx, sel_val, part_acc, part_l, part_m, total;
     int cand_cap, n_chunk_cap;
 };
 
@@ -61,6 +61,7 @@ WsLayout ws_layout(const topk_attn_config* c) {
     w.thr = take(BH * sizeof(float));
     w.samp = take(BH * kSampMax * sizeof(float));
     w.seg_cnt = take(BH * kMaxSeg * sizeof(uint32_t));
+    w.seg_max = take(BH * kMaxSeg * sizeof(float));
     w.flags = take(BH * sizeof(uint32_t));
     w.hmax = take(BH * sizeof(float));
     w.fallback = take(sizeof(uint32_t));
@@ -254,6 +255,7 @@ static void fill_call(topk_attn_t* h, int layer, const void* q, int k, Shape* s,
     b->thr = reinterpret_cast<float*>(ws + h->ws.thr);
     b->samp = reinterpret_cast<float*>(ws + h->ws.samp);
     b->seg_cnt = reinterpret_cast<uint32_t*>(ws + h->ws.seg_cnt);
+    b->seg_max = reinterpret_cast<float*>(ws + h->ws.seg_max);
     b->flags = reinterpret_cast<uint32_t*>(ws + h->ws.flags);
     b->hmax = reinterpret_cast<float*>(ws + h->ws.hmax);
     b->cand = reinterpret_cast<uint64_t*>(ws + h->ws.cand);

@@ -41,6 +41,7 @@ struct Bufs {
     float* thr;             // [B*Hq] candidate threshold
     float* samp;            // [B*Hq][samp_cap]
     uint32_t* seg_cnt;      // [B*Hq][n_seg] candidates each scanning wave found (may exceed seg_cap)
+    float* seg_max;         // [B*Hq][n_seg] largest score each scanning wave saw (-inf if it saw none)
     uint32_t* flags;        // [B*Hq] 1 = candidate list unusable, use the full path
     float* hmax;            // [B*Hq] largest selected score
     uint64_t* cand;         // [B*Hq][cand_cap] (score bits << 32 | position); entry e of segment g

@@ -190,6 +190,7 @@ scan_mfma_kernel(Shape sh, Bufs bf, int tiles_per_wave, float* dst) {
         cs2{st0 + 2 * kStage, seg0 + 2 * (int64_t)sh.cand_cap, 0, 0},
         cs3{st0 + 3 * kStage, seg0 + 3 * (int64_t)sh.cand_cap, 0, 0};
     float thr0 = 0.f, thr1 = 0.f, thr2 = 0.f, thr3 = 0.f;
+    float top0 = -INFINITY, top1 = -INFINITY, top2 = -INFINITY, top3 = -INFINITY;   // largest score seen per head
     if (MODE == MODE_FILTER) {
         thr0 = bf.thr[head0];
         if (1 < G) thr1 = bf.thr[head0 + 1];
@@ -218,6 +219,10 @@ scan_mfma_kernel(Shape sh, Bufs bf, int tiles_per_wave, float* dst) {
             for (int r = 0; r < 4; ++r)
                 if (r < G && valid) dst[(head0 + r) * sh.Ncap + item] = res[r];
         } else {
+            if (valid) {
+                top0 = fmaxf(top0, res[0]); top1 = fmaxf(top1, res[1]);
+                top2 = fmaxf(top2, res[2]); top3 = fmaxf(top3, res[3]);
+            }
             if (0 < G) filter_head(res[0], thr0, cs0, valid, item, seg_cap, sh.n_seg);
             if (1 < G) filter_head(res[1], thr1, cs1, valid, item, seg_cap, sh.n_seg);
             if (2 < G) filter_head(res[2], thr2, cs2, valid, item, seg_cap, sh.n_seg);
@@ -261,12 +266,18 @@ scan_mfma_kernel(Shape sh, Bufs bf, int tiles_per_wave, float* dst) {
         if (1 < G) stage_flush(cs1, seg_cap, sh.n_seg);
         if (2 < G) stage_flush(cs2, seg_cap, sh.n_seg);
         if (3 < G) stage_flush(cs3, seg_cap, sh.n_seg);
+        for (int o = 32; o > 0; o >>= 1) {
+            top0 = fmaxf(top0, wave_xor(top0, o)); top1 = fmaxf(top1, wave_xor(top1, o));
+            top2 = fmaxf(top2, wave_xor(top2, o)); top3 = fmaxf(top3, wave_xor(top3, o));
+        }
         if (lane == 0) {
             uint32_t* sc = bf.seg_cnt + head0 * (int64_t)sh.n_seg + sid;
+            float* sx = bf.seg_max + head0 * (int64_t)sh.n_seg + sid;
             sc[0] = (uint32_t)cs0.n_glob;
-            if (1 < G) sc[sh.n_seg] = (uint32_t)cs1.n_glob;
-            if (2 < G) sc[2 * (int64_t)sh.n_seg] = (uint32_t)cs2.n_glob;
-            if (3 < G) sc[3 * (int64_t)sh.n_seg] = (uint32_t)cs3.n_glob;
+            sx[0] = top0;
+            if (1 < G) { sc[sh.n_seg] = (uint32_t)cs1.n_glob; sx[sh.n_seg] = top1; }
+            if (2 < G) { sc[2 * (int64_t)sh.n_seg] = (uint32_t)cs2.n_glob; sx[2 * (int64_t)sh.n_seg] = top2; }
+            if (3 < G) { sc[3 * (int64_t)sh.n_seg] = (uint32_t)cs3.n_glob; sx[3 * (int64_t)sh.n_seg] = top3; }
         }
     }
 }

@@ -62,12 +62,12 @@ struct SrcSeg {              // candidate list of n_seg interleaved segments: en
     const uint64_t* segs;    // sits in slot e * n_seg + g; entries are (score bits << 32 | position)
     const uint32_t* seg_len; // LDS: entries per segment
     uint32_t* pos_lds;       // LDS: inverted positions of the cached slots, [slot j][thread]
-    int n_seg;               // power of two
+    int log2_n_seg;          // n_seg is a power of two
     int max_len;             // longest segment
     typedef uint64_t raw_t;
-    __device__ __forceinline__ int64_t slots() const { return (int64_t)n_seg * max_len; }
+    __device__ __forceinline__ int64_t slots() const { return (int64_t)max_len << log2_n_seg; }
     __device__ __forceinline__ bool valid(int64_t i) const {
-        return i < slots() && (uint32_t)(i / n_seg) < seg_len[i & (n_seg - 1)];
+        return i < slots() && (uint32_t)(i >> log2_n_seg) < seg_len[i & ((1 << log2_n_seg) - 1)];
     }
     __device__ __forceinline__ const uint64_t* where(int64_t i) const { return segs + i; }
     __device__ __forceinline__ uint32_t key(uint64_t e) const {
@@ -148,37 +148,47 @@ struct Sel32 {
 
 // `keys(f)` must call f(key, present) for every slot, slot-synchronously.
 // 1 <= k <= number of present keys.  All threads of the workgroup must call it.
+// With `bounded`, the caller already knows the largest key `hi` and a lower bound `lo` of
+// all keys, and the pass that would find them is skipped.  `max_passes` > 0 stops the
+// refinement early: the result then has need <= have and T is only a lower bound of the
+// k-th key (for callers that can live with a few extra keys at or above T).
 template <class Keys>
-__device__ __forceinline__ Sel32 wg_select32(Keys keys, int64_t k, SelShared& sm) {
+__device__ __forceinline__ Sel32 wg_select32(Keys keys, int64_t k, SelShared& sm, bool bounded = false,
+                                             uint32_t lo = 0u, uint32_t hi = 0u, int max_passes = 0) {
     const int tid = threadIdx.x, lane = lane_id(), wave = tid >> 6;
-    uint32_t mx = 0u, mn = ~0u;
-    keys([&](uint32_t c, bool present) {
-        if (present) {
-            mx = c > mx ? c : mx;
-            mn = c < mn ? c : mn;
-        }
-    });
-    for (int o = 32; o > 0; o >>= 1) {
-        const uint32_t a = __shfl_xor(mx, o, kWave), b = __shfl_xor(mn, o, kWave);
-        mx = a > mx ? a : mx;
-        mn = b < mn ? b : mn;
-    }
-    __syncthreads();                  // the shared scratch may still be read by a previous select
-    if (lane == 0) { sm.red_max[wave] = mx; sm.red_min[wave] = mn; }
-    for (int i = tid; i < kBins; i += kSelThreads) sm.hist[i] = 0;
-    __syncthreads();
-    if (wave == 0) {
-        mx = lane < kSelWaves ? sm.red_max[lane] : 0u;
-        mn = lane < kSelWaves ? sm.red_min[lane] : ~0u;
+    uint32_t mx = hi, mn = lo;
+    if (!bounded) {
+        mx = 0u; mn = ~0u;
+        keys([&](uint32_t c, bool present) {
+            if (present) {
+                mx = c > mx ? c : mx;
+                mn = c < mn ? c : mn;
+            }
+        });
         for (int o = 32; o > 0; o >>= 1) {
             const uint32_t a = __shfl_xor(mx, o, kWave), b = __shfl_xor(mn, o, kWave);
             mx = a > mx ? a : mx;
             mn = b < mn ? b : mn;
         }
-        if (lane == 0) { sm.bc_max = mx; sm.bc_min = mn; }
     }
+    __syncthreads();                  // the shared scratch may still be read by a previous select
+    if (!bounded && lane == 0) { sm.red_max[wave] = mx; sm.red_min[wave] = mn; }
+    for (int i = tid; i < kBins; i += kSelThreads) sm.hist[i] = 0;
     __syncthreads();
-    mx = sm.bc_max; mn = sm.bc_min;
+    if (!bounded) {
+        if (wave == 0) {
+            mx = lane < kSelWaves ? sm.red_max[lane] : 0u;
+            mn = lane < kSelWaves ? sm.red_min[lane] : ~0u;
+            for (int o = 32; o > 0; o >>= 1) {
+                const uint32_t a = __shfl_xor(mx, o, kWave), b = __shfl_xor(mn, o, kWave);
+                mx = a > mx ? a : mx;
+                mn = b < mn ? b : mn;
+            }
+            if (lane == 0) { sm.bc_max = mx; sm.bc_min = mn; }
+        }
+        __syncthreads();
+        mx = sm.bc_max; mn = sm.bc_min;
+    }
     Sel32 res;
     res.kmax = mx;
     if (mx == mn) {                   // one distinct key: the class is everything
@@ -197,6 +207,7 @@ __device__ __forceinline__ Sel32 wg_select32(Keys keys, int64_t k, SelShared& sm
     uint32_t prefix = rb >= 32 ? 0u : (mx >> rb) << rb;
     int64_t k_rem = k;
     uint32_t cb = 0;
+    int passes = 0;
     while (true) {
         const int w = rb < kDigitBits ? rb : kDigitBits;
         const int shift = rb - w;
@@ -241,14 +252,16 @@ __device__ __forceinline__ Sel32 wg_select32(Keys keys, int64_t k, SelShared& sm
         prefix |= bin << shift;
         k_rem -= above;
         rb = shift;
+        ++passes;
         if ((int64_t)cb == k_rem || rb == 0) break;   // the whole bin is wanted, or all bits are fixed
+        if (passes == max_passes) break;              // good enough for the caller: everything >= prefix
         __syncthreads();
     }
     __syncthreads();
     res.T = prefix;
     res.need = (uint32_t)k_rem;
     res.have = cb;
-    res.exact = rb == 0;
+    res.exact = rb == 0;          // false also after an early stop: T = prefix <= the k-th key
     return res;
 }
 
@@ -264,10 +277,12 @@ __device__ __forceinline__ void pad_outputs(int k_eff, int k, int32_t* idx, floa
 // by position, write idx/vals (wave-major, then slot, then lane: fixed, and every store
 // instruction of a wave writes one contiguous run) and pad up to k.  Returns the largest key.
 template <class It>
-__device__ __forceinline__ uint32_t wg_topk_emit(const It& items, int k_eff, int k, int32_t* idx, float* vals, SelShared& sm) {
+__device__ __forceinline__ uint32_t wg_topk_emit(const It& items, int k_eff, int k, int32_t* idx, float* vals,
+                                                 SelShared& sm, bool bounded = false, uint32_t lo = 0u,
+                                                 uint32_t hi = 0u) {
     const int lane = lane_id(), wave = threadIdx.x >> 6;
     const Sel32 s = wg_select32([&](auto f) { items.visit([&](uint32_t c, uint32_t, bool p) { f(c, p); }); },
-                                (int64_t)k_eff, sm);
+                                (int64_t)k_eff, sm, bounded, lo, hi);
     const bool ties = s.need < s.have;    // (uniform) more items share the k-th score than fit
     uint32_t T2 = 0u;                     // then: inverted-position threshold inside the class key == T
     if (ties) {
@@ -362,8 +377,10 @@ __global__ void __launch_bounds__(kSelThreads) threshold_kernel(Shape sh, Bufs b
     const SrcDense src{bf.samp + bh * sh.samp_cap, (int64_t)pl.n_samp};
     const Items<(kSampMax + kSelThreads - 1) / kSelThreads, SrcDense> items(src);
     const int rank = pl.rank < pl.n_samp ? pl.rank : pl.n_samp;
+    // two digits (18 bits from the first bit in which the samples differ) are plenty: stopping
+    // there lowers the threshold by at most the last bin's width, a handful of extra samples
     const Sel32 s = wg_select32([&](auto f) { items.visit([&](uint32_t c, uint32_t, bool p) { f(c, p); }); },
-                                (int64_t)rank, sm);
+                                (int64_t)rank, sm, false, 0u, 0u, 2);
     if (threadIdx.x == 0) {
         bf.thr[bh] = key_score(s.T);
         bf.flags[bh] = 0;
@@ -388,24 +405,29 @@ __global__ void __launch_bounds__(kSelThreads) select_candidates_kernel(Shape sh
         return;
     }
     // segment lengths: total, longest
-    uint32_t sum = 0, mxl = 0;
+    uint32_t sum = 0, mxl = 0, kmx = 0;      // kmx: largest score key any scanning wave saw
     for (int g = tid; g < sh.n_seg; g += kSelThreads) {
         const uint32_t c = bf.seg_cnt[bh * sh.n_seg + g];
         sm.seg_len[g] = c;
         sum += c;
         mxl = c > mxl ? c : mxl;
+        const uint32_t km = score_key(bf.seg_max[bh * sh.n_seg + g]);
+        kmx = km > kmx ? km : kmx;
     }
     for (int o = 32; o > 0; o >>= 1) {
         sum += __shfl_xor(sum, o, kWave);
-        const uint32_t t = __shfl_xor(mxl, o, kWave);
+        const uint32_t t = __shfl_xor(mxl, o, kWave), u = __shfl_xor(kmx, o, kWave);
         mxl = t > mxl ? t : mxl;
+        kmx = u > kmx ? u : kmx;
     }
-    if (lane == 0) { sm.wave_tot[wave] = sum; sm.red_max[wave] = mxl; }
+    if (lane == 0) { sm.wave_tot[wave] = sum; sm.red_max[wave] = mxl; sm.red_min[wave] = kmx; }
     __syncthreads();
     uint32_t total = 0, max_len = 0;
+    kmx = 0;
     for (int w = 0; w < kSelWaves; ++w) {
         total += sm.wave_tot[w];
         max_len = sm.red_max[w] > max_len ? sm.red_max[w] : max_len;
+        kmx = sm.red_min[w] > kmx ? sm.red_min[w] : kmx;
     }
     __syncthreads();
     if (max_len > (uint32_t)sh.seg_cap || total < (uint32_t)k_eff) {   // uniform: a segment overflowed, or
@@ -415,9 +437,11 @@ __global__ void __launch_bounds__(kSelThreads) select_candidates_kernel(Shape sh
         }
         return;
     }
-    const SrcSeg src{bf.cand + bh * (int64_t)sh.cand_cap, sm.seg_len, pos_lds, sh.n_seg, (int)max_len};
+    const SrcSeg src{bf.cand + bh * (int64_t)sh.cand_cap, sm.seg_len, pos_lds, 31 - __clz(sh.n_seg), (int)max_len};
     const Items<kCandSlots / kSelThreads, SrcSeg> items(src);
-    const uint32_t kmax = wg_topk_emit(items, k_eff, sh.k, bf.sel_idx + bh * sh.k, bf.sel_val + bh * sh.k, sm);
+    // every candidate is >= the head's threshold and the scan reported the largest score
+    const uint32_t kmax = wg_topk_emit(items, k_eff, sh.k, bf.sel_idx + bh * sh.k, bf.sel_val + bh * sh.k, sm, true,
+                                       score_key(bf.thr[bh]), kmx);
     if (tid == 0) bf.hmax[bh] = key_score(kmax);
 }
 
