@@ -65,6 +65,9 @@ typedef struct {
     int32_t dtype;          /* TOPK_ATTN_F32 / F16 / BF16 for q, K and V alike */
     int32_t device;         /* HIP device ordinal */
     int32_t max_window;     /* largest `window` topk_attn_decode_window will be called with (0 if unused) */
+    int32_t max_queries;    /* largest n_queries topk_attn_decode_multi will be called with (0 or 1 if
+                               unused); the workspace grows in proportion */
+    int32_t reserved;       /* must be 0 */
     void* kv_storage;       /* device, >= topk_attn_kv_bytes(), 256-byte aligned, caller-owned */
     size_t kv_bytes;
     void* workspace;        /* device, >= topk_attn_workspace_bytes(), 256-byte aligned, caller-owned */
@@ -121,6 +124,24 @@ int topk_attn_decode(topk_attn_t* h, int layer, const void* q, int k, float* out
  * window == 0 is topk_attn_decode.  Extra error: EINVAL if window < 0 or > max_window. */
 int topk_attn_decode_window(topk_attn_t* h, int layer, const void* q, int k, int window, float* out,
                             int32_t* idx, float* vals, float* lse, void* hip_stream);
+
+/* Several queries per sequence against the cache in one pass over the keys (a chunk of M
+ * consecutive queries, as in building the cache chunk by chunk -- the paper's "top-k at
+ * cache construction time" of the section on million-token cache generation -- or in
+ * verifying drafted tokens): each of the M queries of a sequence gets its own exact
+ * top-k search, softmax and weighted value sum, exactly as if topk_attn_decode_window had
+ * been called once per query, but the keys are read once per block of up to 16
+ * (query, head) rows of a KV head instead of once per query.
+ *   q     device [B, M, Hq, d];  out [B, M, Hq, d];  idx / vals [B, M, Hq, k];  lse [B, M, Hq]
+ *   causal != 0: the M queries are the last M cached tokens' queries, query m attends only
+ *         to the first N_b - (M - 1 - m) tokens (its own token and everything before it);
+ *         the window and k_eff are taken relative to that visible length.
+ *   causal == 0: every query sees all N_b tokens.
+ * n_queries == 1 is topk_attn_decode_window.  Extra errors: EINVAL if n_queries < 1,
+ * n_queries > max(1, max_queries), or (causal) a sequence holds fewer than n_queries tokens. */
+int topk_attn_decode_multi(topk_attn_t* h, int layer, const void* q, int n_queries, int causal, int k,
+                           int window, float* out, int32_t* idx, float* vals, float* lse,
+                           void* hip_stream);
 
 /* Host-only helper for the paper's layer-wise settings of k ("Layer-Wise Settings for k":
  * a fixed total budget sum_l k_l, spent either uniformly or increasing linearly from the

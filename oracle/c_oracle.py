@@ -41,6 +41,9 @@ def _load():
         lib.oracle_topk_attention_window.argtypes = [vp, vp, vp, i32, i32, i32, i32, i64, i64, i64,
                                                      vp, vp, vp, vp]
         lib.oracle_topk_attention_window.restype = i32
+        lib.oracle_topk_attention_multi.argtypes = [vp, vp, vp, i32, i32, i32, i32, i32, i64, i32, i64, i64,
+                                                    vp, vp, vp, vp]
+        lib.oracle_topk_attention_multi.restype = i32
         lib.oracle_num_threads.restype = i32
         _lib = lib
     return _lib
@@ -102,4 +105,23 @@ def topk_attention_window(q: np.ndarray, K: np.ndarray, V: np.ndarray, dtype: in
                                               vals.ctypes.data, lse.ctypes.data)
     if rc:
         raise RuntimeError(f"oracle_topk_attention_window failed rc={rc}")
+    return out, idx, vals, lse
+
+
+def topk_attention_multi(q: np.ndarray, K: np.ndarray, V: np.ndarray, dtype: int, k: int, causal: bool,
+                         window: int = 0):
+    """q [M,Hq,d]: M queries against one cache, each an independent decode step; with `causal`
+    query m sees the first N - (M - 1 - m) tokens.  Returns out [M,Hq,d], idx, vals [M,Hq,k], lse [M,Hq]."""
+    q, K, V = _check(q, dtype), _check(K, dtype), _check(V, dtype)
+    M, Hq, d = q.shape
+    Hkv, N, _ = K.shape
+    out = np.empty((M, Hq, d), dtype=np.float64)
+    idx = np.empty((M, Hq, k), dtype=np.int64)
+    vals = np.empty((M, Hq, k), dtype=np.float64)
+    lse = np.empty((M, Hq), dtype=np.float64)
+    rc = _load().oracle_topk_attention_multi(q.ctypes.data, K.ctypes.data, V.ctypes.data, dtype, M, Hq, Hkv, d,
+                                             N, 1 if causal else 0, k, window, out.ctypes.data,
+                                             idx.ctypes.data, vals.ctypes.data, lse.ctypes.data)
+    if rc:
+        raise RuntimeError(f"oracle_topk_attention_multi failed rc={rc}")
     return out, idx, vals, lse

@@ -23,7 +23,9 @@ library dense attention, brute-force subset enumeration on tiny N, k = 1,
 all-equal scores, score-shift invariance, permutation invariance, planted
 dominant keys, truncation-error bound; for the window variant: window 0 equals the
 plain step, full coverage equals library dense attention, brute force on tiny N, and
-the log-sum-exp merge of a top-k prefix with library attention over the window).
+the log-sum-exp merge of a top-k prefix with library attention over the window;
+for the multi-query variant: k >= N with a causal chunk equals library causal dense
+attention, the last causal query equals the plain step, and brute force on tiny N).
 No function is "parity unpinned".
 """
 from __future__ import annotations
@@ -143,6 +145,30 @@ def topk_attention_window(q, K, V, k: int, window: int):
         rows = np.concatenate([I, np.arange(P, N)])          # retrieved positions, then the window
         out[h], lse[h] = attend_selected(S[h, rows], V[h // G][rows], d)
     return out, idx, vals, lse
+
+
+def topk_attention_multi(q, K, V, k: int, causal: bool, window: int = 0):
+    """A chunk of M queries against one cache, each an independent decode step (the
+    multi-query use of top-k attention: the paper notes that top-k can also serve while
+    the cache is built, in the section on generating million-token caches).
+
+    q [M, Hq, d].  With `causal` the queries are those of the last M cached tokens and
+    query m sees the first N - (M - 1 - m) tokens only (itself and everything before);
+    otherwise all queries see all N.  Returns out [M, Hq, d], idx, vals [M, Hq, k],
+    lse [M, Hq]: row m is topk_attention_window on the visible part of the cache.
+    """
+    q = np.asarray(q, dtype=np.float64)
+    K = np.asarray(K, dtype=np.float64)
+    V = np.asarray(V, dtype=np.float64)
+    M = q.shape[0]
+    N = K.shape[1]
+    res = []
+    for m in range(M):
+        n_vis = N - (M - 1 - m) if causal else N
+        if n_vis < 1:
+            raise ValueError("a causal chunk needs at least M cached tokens")
+        res.append(topk_attention_window(q[m], K[:, :n_vis], V[:, :n_vis], k, window))
+    return tuple(np.stack([r[i] for r in res]) for i in range(4))
 
 
 def attention_entropy(s: np.ndarray, d: int) -> float:

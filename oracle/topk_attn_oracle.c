@@ -99,13 +99,13 @@ int oracle_num_threads(void) {
 
 /* scores of all query heads against keys [i0, i1) of every KV head */
 static void score_block(const void* q, const void* K, int dtype, const double* tab,
-                        int Hq, int Hkv, int d, int64_t N, int64_t i0, int64_t i1,
+                        int Hq, int Hkv, int d, int64_t N, int64_t rows, int64_t i0, int64_t i1,
                         int g, double* S, double* qd, double* kd) {
     int G = Hq / Hkv;
     for (int j = 0; j < G; ++j)
         widen_row(q, dtype, tab, (int64_t)(g * G + j) * d, d, qd + (size_t)j * d);
     for (int64_t i = i0; i < i1; ++i) {
-        widen_row(K, dtype, tab, ((int64_t)g * N + i) * d, d, kd);
+        widen_row(K, dtype, tab, ((int64_t)g * rows + i) * d, d, kd);
         for (int j = 0; j < G; ++j) {
             const double* qh = qd + (size_t)j * d;
             double acc = 0.0;
@@ -120,9 +120,18 @@ static void score_block(const void* q, const void* K, int dtype, const double* t
  * scored against KV head h / G.
  * q [Hq, d], K [Hkv, N, d] in `dtype`; S [Hq, N] double.
  */
+static int scores_impl(const void* q, const void* K, int dtype, int Hq, int Hkv, int d,
+                       int64_t N, int64_t rows, double* S);
+
 int oracle_scores(const void* q, const void* K, int dtype, int Hq, int Hkv, int d,
                   int64_t N, double* S) {
-    if (!q || !K || !S || Hq < 1 || Hkv < 1 || d < 1 || N < 0 || Hq % Hkv) return 1;
+    return scores_impl(q, K, dtype, Hq, Hkv, d, N, N, S);
+}
+
+/* The same with the first N of `rows` stored rows per KV head scored (K [Hkv, rows, d]). */
+static int scores_impl(const void* q, const void* K, int dtype, int Hq, int Hkv, int d,
+                       int64_t N, int64_t rows, double* S) {
+    if (!q || !K || !S || Hq < 1 || Hkv < 1 || d < 1 || N < 0 || rows < N || Hq % Hkv) return 1;
     if (dtype < 0 || dtype > 2) return 1;
     double* tab = build_table(dtype);
     if (dtype != ORACLE_F32 && !tab) return 2;
@@ -143,7 +152,7 @@ int oracle_scores(const void* q, const void* K, int dtype, int Hq, int Hkv, int 
             for (int64_t b = 0; b < nblk; ++b) {
                 if (!qd || !kd) continue;
                 int64_t i0 = b * blk, i1 = i0 + blk < N ? i0 + blk : N;
-                score_block(q, K, dtype, tab, Hq, Hkv, d, N, i0, i1, g, S, qd, kd);
+                score_block(q, K, dtype, tab, Hq, Hkv, d, N, rows, i0, i1, g, S, qd, kd);
             }
         free(qd); free(kd);
     }
@@ -152,8 +161,8 @@ int oracle_scores(const void* q, const void* K, int dtype, int Hq, int Hkv, int 
 }
 
 static int topk_window_impl(const void* q, const void* K, const void* V, int dtype, int Hq, int Hkv, int d,
-                            int64_t N, int64_t k, int64_t window, double* out, int64_t* idx, double* vals,
-                            double* lse);
+                            int64_t N, int64_t rows, int64_t k, int64_t window, double* out, int64_t* idx,
+                            double* vals, double* lse);
 
 /*
  * One decode step for one (layer, sequence).
@@ -165,7 +174,7 @@ static int topk_window_impl(const void* q, const void* K, const void* V, int dty
 int oracle_topk_attention(const void* q, const void* K, const void* V, int dtype,
                           int Hq, int Hkv, int d, int64_t N, int64_t k,
                           double* out, int64_t* idx, double* vals, double* lse) {
-    return topk_window_impl(q, K, V, dtype, Hq, Hkv, d, N, k, 0, out, idx, vals, lse);
+    return topk_window_impl(q, K, V, dtype, Hq, Hkv, d, N, N, k, 0, out, idx, vals, lse);
 }
 
 /*
@@ -178,12 +187,35 @@ int oracle_topk_attention_window(const void* q, const void* K, const void* V, in
                                  int Hq, int Hkv, int d, int64_t N, int64_t k, int64_t window,
                                  double* out, int64_t* idx, double* vals, double* lse) {
     if (window < 0) return 1;
-    return topk_window_impl(q, K, V, dtype, Hq, Hkv, d, N, k, window, out, idx, vals, lse);
+    return topk_window_impl(q, K, V, dtype, Hq, Hkv, d, N, N, k, window, out, idx, vals, lse);
+}
+
+/*
+ * A chunk of M queries against one cache (the multi-query use of top-k attention: the
+ * paper's remark that top-k can also serve while the cache is being built).  Each query
+ * is an independent decode step as above; with `causal` the queries belong to the last M
+ * cached tokens and query m sees only the first N - (M - 1 - m) of them, without it every
+ * query sees all N.  q [M, Hq, d]; K, V [Hkv, N, d]; out [M, Hq, d]; idx, vals [M, Hq, k];
+ * lse [M, Hq].
+ */
+int oracle_topk_attention_multi(const void* q, const void* K, const void* V, int dtype, int M,
+                                int Hq, int Hkv, int d, int64_t N, int causal, int64_t k, int64_t window,
+                                double* out, int64_t* idx, double* vals, double* lse) {
+    if (M < 1 || window < 0 || !q || dtype < 0 || dtype > 2) return 1;
+    size_t esize = dtype == ORACLE_F32 ? 4 : 2;
+    for (int m = 0; m < M; ++m) {
+        int64_t n_vis = causal ? N - (M - 1 - m) : N;
+        int rc = topk_window_impl((const char*)q + (size_t)m * Hq * d * esize, K, V, dtype, Hq, Hkv, d, n_vis, N,
+                                  k, window, out + (size_t)m * Hq * d, idx ? idx + (size_t)m * Hq * k : NULL,
+                                  vals ? vals + (size_t)m * Hq * k : NULL, lse ? lse + (size_t)m * Hq : NULL);
+        if (rc) return rc;
+    }
+    return 0;
 }
 
 static int topk_window_impl(const void* q, const void* K, const void* V, int dtype, int Hq, int Hkv, int d,
-                            int64_t N, int64_t k, int64_t window, double* out, int64_t* idx, double* vals,
-                            double* lse) {
+                            int64_t N, int64_t rows, int64_t k, int64_t window, double* out, int64_t* idx,
+                            double* vals, double* lse) {
     if (!q || !K || !V || !out || Hq < 1 || Hkv < 1 || d < 1 || N < 1 || k < 1 || Hq % Hkv)
         return 1;
     if (dtype < 0 || dtype > 2) return 1;
@@ -197,7 +229,7 @@ static int topk_window_impl(const void* q, const void* K, const void* V, int dty
     /* 1. scores: raw dot product of each query with every cached key */
     double* S = (double*)malloc(sizeof(double) * (size_t)Hq * (size_t)N);
     if (!S) return 2;
-    int rc = oracle_scores(q, K, dtype, Hq, Hkv, d, N, S);
+    int rc = scores_impl(q, K, dtype, Hq, Hkv, d, N, rows, S);
     if (rc) { free(S); return rc; }
 
     double* tab = build_table(dtype);
@@ -235,7 +267,7 @@ static int topk_window_impl(const void* q, const void* K, const void* V, int dty
         double* o = out + (int64_t)h * d;
         for (int c = 0; c < d; ++c) o[c] = 0.0;
         for (int64_t j = 0; j < n_att; ++j) {
-            widen_row(V, dtype, tab, ((int64_t)(h / G) * N + p[j].i) * d, d, vd);
+            widen_row(V, dtype, tab, ((int64_t)(h / G) * rows + p[j].i) * d, d, vd);
             double pj = w[j] / Z;
             for (int c = 0; c < d; ++c) o[c] += pj * vd[c];
         }

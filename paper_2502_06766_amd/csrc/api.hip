@@ -32,6 +32,8 @@ bool config_ok(const topk_attn_config* c, int* why) {
     if (!c || c->struct_size != sizeof(topk_attn_config)) return false;
     if (c->n_layers < 1 || c->n_seqs < 1 || c->n_q_heads < 1 || c->n_kv_heads < 1) return false;
     if (c->max_tokens < 1 || c->max_k < 1 || c->device < 0 || c->max_window < 0) return false;
+    if (c->max_queries < 0 || c->max_queries > 4096 || c->reserved != 0) return false;
+    if ((int64_t)c->n_seqs * (c->max_queries > 1 ? c->max_queries : 1) > 65535) return false;   // a grid dimension
     if (c->max_tokens > (int64_t)0x7FFFFF00) return false;   // positions are int32
     if (c->n_seqs > 65535 || c->n_kv_heads > 65535) return false;
     *why = TOPK_ATTN_EUNSUPPORTED;
@@ -50,7 +52,7 @@ size_t kv_half_bytes(const topk_attn_config* c) {
 
 WsLayout ws_layout(const topk_attn_config* c) {
     WsLayout w;
-    const size_t BH = (size_t)c->n_seqs * c->n_q_heads;
+    const size_t BH = (size_t)c->n_seqs * (c->max_queries > 1 ? c->max_queries : 1) * c->n_q_heads;
     const int64_t max_k = c->max_k < c->max_tokens ? c->max_k : c->max_tokens;
     w.cand_cap = (int)(4 * max_k + 16384);
     const int64_t max_w = c->max_window < c->max_tokens ? c->max_window : c->max_tokens;
@@ -239,10 +241,13 @@ int topk_attn_append_kv(topk_attn_t* h, int layer, int seq, const void* k_new, c
     return TOPK_ATTN_OK;
 }
 
-static void fill_call(topk_attn_t* h, int layer, const void* q, int k, Shape* s, Bufs* b) {
+static void fill_call(topk_attn_t* h, int layer, const void* q, int k, int n_queries, Shape* s, Bufs* b) {
     const topk_attn_config& c = h->cfg;
     const int e = elem_bytes(c.dtype);
-    s->B = c.n_seqs; s->Hq = c.n_q_heads; s->Hkv = c.n_kv_heads; s->G = c.n_q_heads / c.n_kv_heads;
+    s->Bc = c.n_seqs; s->M = n_queries; s->causal = 0; s->B = c.n_seqs * n_queries;
+    s->Hq = c.n_q_heads; s->Hkv = c.n_kv_heads; s->G = c.n_q_heads / c.n_kv_heads;
+    s->q_per_blk = 16 / s->G < n_queries ? 16 / s->G : n_queries;     // G <= 16
+    s->n_qblk = (n_queries + s->q_per_blk - 1) / s->q_per_blk;
     s->D = c.head_dim; s->dtype = c.dtype; s->k = k; s->window = 0; s->max_k = c.max_k;
     s->cand_cap = h->ws.cand_cap; s->n_seg = 4; s->seg_cap = h->ws.cand_cap / 4; s->samp_cap = kSampMax; s->n_chunk_cap = h->ws.n_chunk_cap;
     s->Ncap = c.max_tokens;
@@ -277,7 +282,7 @@ static bool choose_segments(const topk_attn_t* h, const Shape& s, int64_t nmax, 
                             int* seg_cap) {
     int64_t target_wgs = 2 * (int64_t)h->n_cu;
     if (const char* e = getenv("TOPK_ATTN_SCAN_WGS")) target_wgs = atoll(e);
-    int64_t P = target_wgs / ((int64_t)s.B * s.Hkv);
+    int64_t P = target_wgs / ((int64_t)scan_grid_z(s) * s.Hkv);
     const int64_t tiles = (nmax + 63) / 64;
     if (P * 4 > tiles) P = tiles / 4;
     if (P * 4 > kMaxSeg) P = kMaxSeg / 4;
@@ -298,12 +303,13 @@ static bool choose_segments(const topk_attn_t* h, const Shape& s, int64_t nmax, 
 }
 
 // Shortest and longest searched prefix over the sequences of a layer; EINVAL if a sequence is empty.
-static int lengths_of(const topk_attn_t* h, int layer, int window, int64_t* nmin, int64_t* nmax) {
+static int lengths_of(const topk_attn_t* h, int layer, int window, int64_t min_tokens, int64_t* nmin,
+                      int64_t* nmax) {
     const int B = h->cfg.n_seqs;
     int64_t lo = INT64_MAX, hi = 0;
     for (int b = 0; b < B; ++b) {
         const int64_t n = h->len[(size_t)layer * B + b];
-        if (n < 1) return TOPK_ATTN_EINVAL;
+        if (n < min_tokens) return TOPK_ATTN_EINVAL;
         const int64_t p = prefix_len(n, window);
         lo = p < lo ? p : lo;
         hi = p > hi ? p : hi;
@@ -312,20 +318,24 @@ static int lengths_of(const topk_attn_t* h, int layer, int window, int64_t* nmin
     return TOPK_ATTN_OK;
 }
 
-static int decode_impl(topk_attn_t* h, int layer, const void* q, int k, int window, float* out, int32_t* idx,
-                       float* vals, float* lse, void* hip_stream) {
+static int decode_impl(topk_attn_t* h, int layer, const void* q, int n_queries, int causal, int k, int window,
+                       float* out, int32_t* idx, float* vals, float* lse, void* hip_stream) {
     if (!h || !q || !out) return TOPK_ATTN_EINVAL;
     if (layer < 0 || layer >= h->cfg.n_layers) return TOPK_ATTN_EINVAL;
     if (k < 1 || k > h->cfg.max_k) return TOPK_ATTN_EINVAL;
     if (window < 0 || window > h->cfg.max_window) return TOPK_ATTN_EINVAL;
+    if (n_queries < 1 || n_queries > (h->cfg.max_queries > 1 ? h->cfg.max_queries : 1)) return TOPK_ATTN_EINVAL;
     if (window > h->cfg.max_tokens) window = (int)h->cfg.max_tokens;   // same result: no sequence is longer
     if ((uintptr_t)q & 15) return TOPK_ATTN_EINVAL;
-    int64_t nmin, nmax;     // searched prefix lengths
-    if (lengths_of(h, layer, window, &nmin, &nmax) != TOPK_ATTN_OK) return TOPK_ATTN_EINVAL;
+    // the plans below are made for the longest searched prefix of each sequence (its last
+    // query's); the earlier queries of a causal chunk search up to n_queries - 1 keys fewer
+    int64_t nmin, nmax;
+    if (lengths_of(h, layer, window, causal ? n_queries : 1, &nmin, &nmax) != TOPK_ATTN_OK) return TOPK_ATTN_EINVAL;
     hipStream_t st = (hipStream_t)hip_stream;
     Shape s; Bufs b;
-    fill_call(h, layer, q, k, &s, &b);
+    fill_call(h, layer, q, k, n_queries, &s, &b);
     s.window = window;
+    s.causal = causal ? 1 : 0;
     b.out = out; b.lse = lse;
     if (idx) b.sel_idx = idx;
     if (vals) b.sel_val = vals;
@@ -334,8 +344,8 @@ static int decode_impl(topk_attn_t* h, int layer, const void* q, int k, int wind
     if (h->path != TOPK_ATTN_PATH_FULL && scan_mfma_supported(s) && nmax > 0) {
         fast = true;
         int64_t c_hi = 0;
-        for (int i = 0; i < s.B && fast; ++i) {
-            const int64_t n = prefix_len(h->len[(size_t)layer * s.B + i], window);
+        for (int i = 0; i < s.Bc && fast; ++i) {
+            const int64_t n = prefix_len(h->len[(size_t)layer * s.Bc + i], window);
             if (n == 0) continue;            // this sequence lies entirely inside its window
             const int ke = k < n ? k : (int)n;
             const Plan pl = make_plan(n, ke);
@@ -371,12 +381,17 @@ static int decode_impl(topk_attn_t* h, int layer, const void* q, int k, int wind
 
 int topk_attn_decode(topk_attn_t* h, int layer, const void* q, int k, float* out, int32_t* idx, float* vals,
                      float* lse, void* hip_stream) {
-    return decode_impl(h, layer, q, k, 0, out, idx, vals, lse, hip_stream);
+    return decode_impl(h, layer, q, 1, 0, k, 0, out, idx, vals, lse, hip_stream);
 }
 
 int topk_attn_decode_window(topk_attn_t* h, int layer, const void* q, int k, int window, float* out, int32_t* idx,
                             float* vals, float* lse, void* hip_stream) {
-    return decode_impl(h, layer, q, k, window, out, idx, vals, lse, hip_stream);
+    return decode_impl(h, layer, q, 1, 0, k, window, out, idx, vals, lse, hip_stream);
+}
+
+int topk_attn_decode_multi(topk_attn_t* h, int layer, const void* q, int n_queries, int causal, int k, int window,
+                           float* out, int32_t* idx, float* vals, float* lse, void* hip_stream) {
+    return decode_impl(h, layer, q, n_queries, causal, k, window, out, idx, vals, lse, hip_stream);
 }
 
 int topk_attn_k_schedule(int64_t total_k, int n_layers, double last_over_first, int32_t* k_out) {
@@ -420,9 +435,9 @@ int topk_attn_scores(topk_attn_t* h, int layer, const void* q, float* scores, vo
     if (layer < 0 || layer >= h->cfg.n_layers) return TOPK_ATTN_EINVAL;
     if ((uintptr_t)q & 15) return TOPK_ATTN_EINVAL;
     int64_t nmin, nmax;
-    if (lengths_of(h, layer, 0, &nmin, &nmax) != TOPK_ATTN_OK) return TOPK_ATTN_EINVAL;
+    if (lengths_of(h, layer, 0, 1, &nmin, &nmax) != TOPK_ATTN_OK) return TOPK_ATTN_EINVAL;
     Shape s; Bufs b;
-    fill_call(h, layer, q, 1, &s, &b);
+    fill_call(h, layer, q, 1, 1, &s, &b);
     hipError_t e = launch_scan_full(s, b, nmax, scores, (hipStream_t)hip_stream);
     return e == hipSuccess ? TOPK_ATTN_OK : TOPK_ATTN_EDEVICE;
 }

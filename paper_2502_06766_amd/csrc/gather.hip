@@ -80,13 +80,13 @@ __global__ void __launch_bounds__(256) gather_partial_kernel(Shape sh, Bufs bf, 
     __shared__ GatherShared sm;
     const int chunk_id = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
     const int64_t bh = (int64_t)b * sh.Hq + h;
-    const int64_t P = prefix_len(bf.len[b], sh.window);
+    const int64_t P = prefix_len(visible_len(sh, bf, b), sh.window);
     const int k_eff = sh.k < P ? sh.k : (int)P;
     const int j0 = chunk_id * kGatherRows;
     if (j0 >= k_eff) { mark_empty(sh, bf, bh, chunk_id); return; }
     const int j1 = j0 + kGatherRows < k_eff ? j0 + kGatherRows : k_eff;
     const char* Vh = static_cast<const char*>(bf.V) +
-                     ((int64_t)b * sh.Hkv + h / sh.G) * sh.Ncap * sh.D * Elem<DT>::kBytes;
+                     ((int64_t)cache_seq(sh, b) * sh.Hkv + h / sh.G) * sh.Ncap * sh.D * Elem<DT>::kBytes;
     const int32_t* idx = bf.sel_idx + bh * sh.k;
     const float* val = bf.sel_val + bh * sh.k;
     const float m = bf.hmax[bh];
@@ -103,13 +103,13 @@ __global__ void __launch_bounds__(256) window_partial_kernel(Shape sh, Bufs bf, 
     const int chunk_id = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
     const int64_t bh = (int64_t)b * sh.Hq + h;
     const int D = sh.D;
-    const int64_t N = bf.len[b];
+    const int64_t N = visible_len(sh, bf, b);
     const int64_t P = prefix_len(N, sh.window);
     const int W = (int)(N - P);
     const int j0 = chunk_id * kGatherRows;
     if (j0 >= W) { mark_empty(sh, bf, bh, slot0 + chunk_id); return; }
     const int j1 = j0 + kGatherRows < W ? j0 + kGatherRows : W;
-    const int64_t head_off = ((int64_t)b * sh.Hkv + h / sh.G) * sh.Ncap * D * Elem<DT>::kBytes;
+    const int64_t head_off = ((int64_t)cache_seq(sh, b) * sh.Hkv + h / sh.G) * sh.Ncap * D * Elem<DT>::kBytes;
     const char* Kh = static_cast<const char*>(bf.K) + head_off;
     const char* Vh = static_cast<const char*>(bf.V) + head_off;
 
@@ -159,7 +159,7 @@ __global__ void __launch_bounds__(256) gather_sum_kernel(Shape sh, Bufs bf, floa
     const int64_t bh = (int64_t)b * sh.Hq + h;
     const int D = sh.D;
     const int tid = threadIdx.x, lane = lane_id(), wave = tid >> 6;
-    const int64_t N = bf.len[b];
+    const int64_t N = visible_len(sh, bf, b);
     const int k_eff = sh.k < N ? sh.k : (int)N;
     const int nch = (k_eff + kGatherRows - 1) / kGatherRows;
     __shared__ float red[256];

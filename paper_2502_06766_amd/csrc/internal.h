@@ -20,7 +20,13 @@ constexpr int kMaxSeg = 1024;       // most candidate segments per head
 
 // Geometry of one decode call, passed by value to every kernel.
 struct Shape {
-    int B, Hq, Hkv, G, D, dtype;
+    int B;            // sequences of the call: B = Bc * M, sequence b is query b % M of cache sequence b / M
+    int Hq, Hkv, G, D, dtype;
+    int Bc;           // cache sequences
+    int M;            // queries per cache sequence in this call (1 for plain decode)
+    int causal;       // query m of M sees only the first len - (M - 1 - m) tokens
+    int q_per_blk;    // row-tile scan: queries per block of <= 16 (query, head) rows
+    int n_qblk;       // row-tile scan: blocks per cache sequence
     int k;            // requested k (k_eff = min(k, searched prefix of sequence b))
     int window;       // most recent tokens that are always attended and excluded from the search
     int max_k;
@@ -37,7 +43,7 @@ struct Bufs {
     const void* K;          // this layer's keys  [B][Hkv][Ncap][D]
     const void* V;          // this layer's values
     const void* q;          // [B][Hq][D]
-    const int32_t* len;     // [B] tokens cached per sequence (this layer)
+    const int32_t* len;     // [Bc] tokens cached per cache sequence (this layer)
     float* thr;             // [B*Hq] candidate threshold
     float* samp;            // [B*Hq][samp_cap]
     uint32_t* seg_cnt;      // [B*Hq][n_seg] candidates each scanning wave found (may exceed seg_cap)
@@ -56,6 +62,20 @@ struct Bufs {
     float* lse;             // [B*Hq] or null
     uint32_t* fallback_total; // [1]
 };
+
+// The MFMA scan has two kernels: one query and at most four heads per KV head go through
+// the grouped kernel (grid z = sequences), everything else through the row-tile kernel
+// (grid z = cache sequences x row blocks).
+inline bool scan_row_tiles(const Shape& s) { return s.M > 1 || s.G > 4; }
+inline int scan_grid_z(const Shape& s) { return scan_row_tiles(s) ? s.Bc * s.n_qblk : s.B; }
+
+// Cache sequence behind sequence b of the call, and the tokens of it that b may attend to.
+__device__ inline int cache_seq(const Shape& sh, int b) { return sh.M == 1 ? b : b / sh.M; }
+__device__ inline int64_t visible_len(const Shape& sh, const Bufs& bf, int b) {
+    if (sh.M == 1) return bf.len[b];
+    const int c = b / sh.M;
+    return (int64_t)bf.len[c] - (sh.causal ? sh.M - 1 - (b - c * sh.M) : 0);
+}
 
 // Tokens of a sequence the search runs over: everything but the always-attended window.
 __host__ __device__ inline int64_t prefix_len(int64_t n_tokens, int window) {

@@ -282,6 +282,225 @@ scan_mfma_kernel(Shape sh, Bufs bf, int tiles_per_wave, float* dst) {
     }
 }
 
+// ---------------------------------------------------------------------------------------
+// Row-tile variant: up to 16 (query, head) rows against one KV head in a single pass over
+// its keys -- head groups of 5..16, and several queries per sequence (a chunk of M
+// queries, the cache-construction use the paper mentions for top-k attention).  Operand A
+// holds 16 distinct rows, so the four accumulators of a 64-key tile give lane (j, n) the
+// scores of rows 4 j + i (i = 0..3) for keys n, 16 + n, 32 + n, 48 + n: the same 16 MFMAs
+// per tile as the grouped kernel, four times the rows.  Per-row state lives in the 16
+// lanes that own the row.
+// ---------------------------------------------------------------------------------------
+constexpr int kStageRow = 64;   // LDS staging slots per (wave, row); >= the 64 entries one step can add
+
+template <int DT, int D, int MODE>
+__global__ void __launch_bounds__(kScanWaves* kWave)
+scan_rows_kernel(Shape sh, Bufs bf, int tiles_per_wave, float* dst) {
+    using v8 = typename Mfma<DT>::v8;
+    constexpr int KS = D / 32;
+    const int G = sh.G, M = sh.M;
+    const int bc = (int)blockIdx.z / sh.n_qblk, blk = (int)blockIdx.z % sh.n_qblk;   // cache sequence, row block
+    const int kvh = blockIdx.y;
+    const int m0 = blk * sh.q_per_blk;                                // first query of the block
+    const int mq = sh.q_per_blk < M - m0 ? sh.q_per_blk : M - m0;     // its queries
+    const int R = mq * G;                                             // its rows, <= 16
+    const int lane = lane_id();
+    const int j = lane >> 4, n = lane & 15;
+    const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+    const int64_t Nc = bf.len[bc];
+    const int64_t N = prefix_len(Nc, sh.window);      // longest searched prefix of the sequence's queries
+
+    // row rr of the block is head kvh * G + rr % G of query m0 + rr / G
+    auto head_of = [&](int rr) -> int64_t {
+        return ((int64_t)bc * M + m0 + rr / G) * sh.Hq + (int64_t)kvh * G + rr % G;
+    };
+    auto prefix_of = [&](int rr) -> int {   // keys row rr searches (0 for rows the block does not have)
+        if (rr >= R) return 0;
+        const int m = m0 + rr / G;
+        return (int)prefix_len(Nc - (sh.causal ? M - 1 - m : 0), sh.window);
+    };
+
+    int64_t n_items = N;
+    int stride = 1;
+    if (MODE == MODE_SAMPLE) {
+        if (N == 0) return;
+        Plan pl = make_plan(N, sh.k < N ? sh.k : (int)N);
+        n_items = pl.n_samp;
+        stride = pl.stride;
+    }
+    const int64_t n_tiles_all = (n_items + 63) / 64;
+    int64_t tile, tile_end, tile_step;
+    if (MODE == MODE_FILTER) {
+        tile = (int64_t)blockIdx.x * kScanWaves + wave;
+        tile_step = (int64_t)gridDim.x * kScanWaves;
+        tile_end = n_tiles_all;
+    } else {
+        const int64_t tile0 = (int64_t)blockIdx.x * tiles_per_wave * kScanWaves;
+        if (tile0 >= n_tiles_all) return;
+        tile = tile0 + wave;
+        tile_step = kScanWaves;
+        tile_end = tile0 + (int64_t)tiles_per_wave * kScanWaves;
+        if (tile_end > n_tiles_all) tile_end = n_tiles_all;
+    }
+
+    // operand A: lane (j, m) holds channels 32 s + 8 j .. +7 of row m
+    v8 qa[KS];
+    {
+        const v8* p = reinterpret_cast<const v8*>(static_cast<const char*>(bf.q) + head_of(n < R ? n : 0) * (D * 2)) + j;
+#pragma unroll
+        for (int s = 0; s < KS; ++s) {
+            v8 v = p[4 * s];
+            if (n >= R) v = v8{};
+            qa[s] = v;
+        }
+    }
+    const char* Kh = static_cast<const char*>(bf.K) + ((int64_t)bc * sh.Hkv + kvh) * sh.Ncap * (D * 2);
+
+    // the four rows 4 j + i this lane owns
+    int64_t vh[4];
+    int P[4];
+    float thr[4], top[4];
+    int nl[4], ng[4];       // staged / already appended candidates (uniform over the 16 lanes of the row)
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int rr = 4 * j + i;
+        vh[i] = head_of(rr < R ? rr : 0);
+        P[i] = prefix_of(rr);
+        thr[i] = (MODE == MODE_FILTER && rr < R) ? bf.thr[vh[i]] : INFINITY;
+        top[i] = -INFINITY;
+        nl[i] = 0;
+        ng[i] = 0;
+    }
+    const int seg_cap = sh.seg_cap, n_seg = sh.n_seg;
+    const int sid = (int)blockIdx.x * kScanWaves + wave;
+    __shared__ uint64_t stage_lds[MODE == MODE_FILTER ? kScanWaves * 16 * kStageRow : 1];
+    uint64_t* const st0 = stage_lds + (MODE == MODE_FILTER ? wave * 16 * kStageRow : 0);
+
+    // append the staged candidates of rows 4 j' + i (all j') to their segments
+    auto flush = [&](int i, int& nl_i, int& ng_i, int64_t vh_i) {
+        wave_sync();
+        uint64_t* seg = bf.cand + vh_i * (int64_t)sh.cand_cap + sid;
+        const uint64_t* src = st0 + (4 * j + i) * kStageRow;
+        for (int e = n; e < nl_i; e += 16) {
+            const int slot = ng_i + e;
+            if (slot < seg_cap) seg[(int64_t)slot * n_seg] = src[e];
+        }
+        wave_sync();
+        ng_i += nl_i;
+        nl_i = 0;
+    };
+
+    auto row_of = [&](int64_t item0, int slot) -> int64_t {
+        int64_t p = item0 + slot;
+        if (MODE == MODE_SAMPLE) {
+            if (p > n_items - 1) p = n_items - 1;
+            p = sample_pos((int)p, stride);
+        }
+        return p < N ? p : N - 1;
+    };
+    auto consume = [&](const f32x4 (&c)[4], int64_t item0) {
+        if (MODE == MODE_SAMPLE) {
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                const int64_t item = item0 + 16 * g + n;
+                if (item < n_items) {
+                    const int64_t pos = sample_pos((int)item, stride);
+#pragma unroll
+                    for (int i = 0; i < 4; ++i)   // a sample past the row's own prefix does not count
+                        if (4 * j + i < R) bf.samp[vh[i] * sh.samp_cap + item] = pos < P[i] ? c[g][i] : -INFINITY;
+                }
+            }
+        } else if (MODE == MODE_FULL) {
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                const int64_t item = item0 + 16 * g + n;
+#pragma unroll
+                for (int i = 0; i < 4; ++i)
+                    if (item < P[i]) dst[vh[i] * sh.Ncap + item] = c[g][i];
+            }
+        } else {
+            const uint32_t below = (1u << n) - 1u;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                float sc[4];
+                bool ps[4];
+                uint64_t mg[4], any = 0;
+#pragma unroll
+                for (int g = 0; g < 4; ++g) {
+                    sc[g] = c[g][i] + 0.0f;
+                    const bool valid = item0 + 16 * g + n < P[i];
+                    if (valid) top[i] = fmaxf(top[i], sc[g]);
+                    ps[g] = valid && sc[g] >= thr[i];
+                    mg[g] = __ballot(ps[g]);
+                    any |= mg[g];
+                }
+                if (any) {
+                    uint32_t gm[4];
+                    int add = 0;
+#pragma unroll
+                    for (int g = 0; g < 4; ++g) {
+                        gm[g] = (uint32_t)(mg[g] >> (16 * j)) & 0xFFFFu;
+                        add += __popc(gm[g]);
+                    }
+                    if (__ballot(nl[i] + add > kStageRow)) flush(i, nl[i], ng[i], vh[i]);
+                    uint64_t* row_st = st0 + (4 * j + i) * kStageRow;
+                    int off = nl[i];
+#pragma unroll
+                    for (int g = 0; g < 4; ++g) {
+                        if (ps[g])
+                            row_st[off + __popc(gm[g] & below)] =
+                                ((uint64_t)__float_as_uint(sc[g]) << 32) | (uint64_t)(uint32_t)(item0 + 16 * g + n);
+                        off += __popc(gm[g]);
+                    }
+                    nl[i] = off;
+                }
+            }
+        }
+    };
+    auto mac = [&](const v8 (&b)[4][KS], f32x4 (&c)[4]) {
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+            c[g] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int s = 0; s < KS; ++s) c[g] = Mfma<DT>::mac(qa[s], b[g][s], c[g]);
+        }
+    };
+
+    v8 ba[4][KS], bb[4][KS];
+    if (tile < tile_end) {
+        tile_load<DT, D>(Kh, [&](int slot) { return row_of(tile * 64, slot); }, ba);
+        while (true) {
+            f32x4 c[4];
+            const int64_t t1 = tile + tile_step;
+            const int64_t p1 = t1 < tile_end ? t1 : tile;
+            tile_load<DT, D>(Kh, [&](int slot) { return row_of(p1 * 64, slot); }, bb);
+            __builtin_amdgcn_sched_barrier(0);
+            mac(ba, c);
+            consume(c, tile * 64);
+            if (t1 >= tile_end) break;
+            const int64_t t2 = t1 + tile_step;
+            const int64_t p2 = t2 < tile_end ? t2 : t1;
+            tile_load<DT, D>(Kh, [&](int slot) { return row_of(p2 * 64, slot); }, ba);
+            __builtin_amdgcn_sched_barrier(0);
+            mac(bb, c);
+            consume(c, t1 * 64);
+            if (t2 >= tile_end) break;
+            tile = t2;
+        }
+    }
+    if (MODE == MODE_FILTER) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            flush(i, nl[i], ng[i], vh[i]);
+            for (int o = 8; o > 0; o >>= 1) top[i] = fmaxf(top[i], wave_xor(top[i], o));
+            if (n == 0 && 4 * j + i < R) {
+                bf.seg_cnt[vh[i] * (int64_t)n_seg + sid] = (uint32_t)ng[i];
+                bf.seg_max[vh[i] * (int64_t)n_seg + sid] = top[i];
+            }
+        }
+    }
+}
+
 // Plain FMA scoring for every shape the MFMA kernel does not take (fp32 caches, other
 // head groupings): a row of D elements is spread over D*e/16 lanes, 16 bytes each.
 template <int DT>
@@ -291,7 +510,7 @@ scan_generic_kernel(Shape sh, Bufs bf, int rows_per_block, float* dst) {
     const int b = blockIdx.z, kvh = blockIdx.y;
     const int G = sh.G, D = sh.D;
     const int64_t head0 = (int64_t)b * sh.Hq + (int64_t)kvh * G;
-    const int64_t N = prefix_len(bf.len[b], sh.window);
+    const int64_t N = prefix_len(visible_len(sh, bf, b), sh.window);
     const int64_t row_begin = (int64_t)blockIdx.x * rows_per_block;
     if (row_begin >= N) return;
 
@@ -310,7 +529,7 @@ scan_generic_kernel(Shape sh, Bufs bf, int rows_per_block, float* dst) {
     const int rows_per_pass = blockDim.x / lpr;
     const int slot = threadIdx.x / lpr, chunk = threadIdx.x % lpr;
     const char* Kh = static_cast<const char*>(bf.K) +
-                     ((int64_t)b * sh.Hkv + kvh) * sh.Ncap * D * Elem<DT>::kBytes;
+                     ((int64_t)cache_seq(sh, b) * sh.Hkv + kvh) * sh.Ncap * D * Elem<DT>::kBytes;
     int64_t row_end = row_begin + rows_per_block;
     if (row_end > N) row_end = N;
     for (int64_t base = row_begin; base < row_end; base += rows_per_pass) {
@@ -332,7 +551,7 @@ scan_generic_kernel(Shape sh, Bufs bf, int rows_per_block, float* dst) {
 }
 
 bool scan_mfma_supported(const Shape& s) {
-    return (s.dtype == DT_F16 || s.dtype == DT_BF16) && (s.D == 64 || s.D == 128) && s.G >= 1 && s.G <= 4;
+    return (s.dtype == DT_F16 || s.dtype == DT_BF16) && (s.D == 64 || s.D == 128) && s.G >= 1 && s.G <= 16;
 }
 
 static int tiles_per_wave_for(int64_t n_items, int B, int Hkv) {
@@ -348,13 +567,17 @@ static int tiles_per_wave_for(int64_t n_items, int B, int Hkv) {
 
 template <int MODE>
 static hipError_t launch_mfma(const Shape& s, const Bufs& b, int64_t n_items, float* dst, hipStream_t st) {
-    const int tpw = tiles_per_wave_for(n_items, s.B, s.Hkv);
+    const bool rows = scan_row_tiles(s);
+    const int tpw = tiles_per_wave_for(n_items, scan_grid_z(s), s.Hkv);
     const int64_t tiles = (n_items + 63) / 64;
     const int64_t per_wg = (int64_t)tpw * kScanWaves;
-    dim3 grid((unsigned)((tiles + per_wg - 1) / per_wg), (unsigned)s.Hkv, (unsigned)s.B);
+    dim3 grid((unsigned)((tiles + per_wg - 1) / per_wg), (unsigned)s.Hkv, (unsigned)(scan_grid_z(s)));
     dim3 block(kScanWaves * kWave);
-#define TKA_LAUNCH(DT_, D_) \
-    hipLaunchKernelGGL((scan_mfma_kernel<DT_, D_, MODE>), grid, block, 0, st, s, b, tpw, dst)
+#define TKA_LAUNCH(DT_, D_)                                                                                 \
+    do {                                                                                                    \
+        if (rows) hipLaunchKernelGGL((scan_rows_kernel<DT_, D_, MODE>), grid, block, 0, st, s, b, tpw, dst); \
+        else hipLaunchKernelGGL((scan_mfma_kernel<DT_, D_, MODE>), grid, block, 0, st, s, b, tpw, dst);     \
+    } while (0)
     if (s.dtype == DT_F16 && s.D == 128) TKA_LAUNCH(DT_F16, 128);
     else if (s.dtype == DT_F16 && s.D == 64) TKA_LAUNCH(DT_F16, 64);
     else if (s.dtype == DT_BF16 && s.D == 128) TKA_LAUNCH(DT_BF16, 128);
@@ -372,10 +595,18 @@ hipError_t launch_scan_sample(const Shape& s, const Bufs& b, int64_t Nmax, hipSt
 hipError_t launch_scan_filter(const Shape& s, const Bufs& b, int64_t Nmax, hipStream_t st) {
     (void)Nmax;
     // one wave per candidate segment: n_seg / 4 workgroups per KV head
-    dim3 grid((unsigned)(s.n_seg / kScanWaves), (unsigned)s.Hkv, (unsigned)s.B);
+    const bool rows = scan_row_tiles(s);
+    dim3 grid((unsigned)(s.n_seg / kScanWaves), (unsigned)s.Hkv, (unsigned)(scan_grid_z(s)));
     dim3 block(kScanWaves * kWave);
-#define TKA_LAUNCH(DT_, D_) \
-    hipLaunchKernelGGL((scan_mfma_kernel<DT_, D_, MODE_FILTER>), grid, block, 0, st, s, b, 0, (float*)nullptr)
+#define TKA_LAUNCH(DT_, D_)                                                                                  \
+    do {                                                                                                     \
+        if (rows)                                                                                            \
+            hipLaunchKernelGGL((scan_rows_kernel<DT_, D_, MODE_FILTER>), grid, block, 0, st, s, b, 0,        \
+                               (float*)nullptr);                                                             \
+        else                                                                                                 \
+            hipLaunchKernelGGL((scan_mfma_kernel<DT_, D_, MODE_FILTER>), grid, block, 0, st, s, b, 0,        \
+                               (float*)nullptr);                                                             \
+    } while (0)
     if (s.dtype == DT_F16 && s.D == 128) TKA_LAUNCH(DT_F16, 128);
     else if (s.dtype == DT_F16 && s.D == 64) TKA_LAUNCH(DT_F16, 64);
     else if (s.dtype == DT_BF16 && s.D == 128) TKA_LAUNCH(DT_BF16, 128);

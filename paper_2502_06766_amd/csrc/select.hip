@@ -340,7 +340,7 @@ __device__ void wg_score_head(const Shape& sh, const Bufs& bf, int b, int h, int
     const int lpr = D / EPL, rows_per_pass = kSelThreads / lpr;
     const int rs = threadIdx.x / lpr, chunk = threadIdx.x % lpr;
     const char* Kh = static_cast<const char*>(bf.K) +
-                     ((int64_t)b * sh.Hkv + h / sh.G) * sh.Ncap * D * Elem<DT>::kBytes;
+                     ((int64_t)cache_seq(sh, b) * sh.Hkv + h / sh.G) * sh.Ncap * D * Elem<DT>::kBytes;
     for (int64_t base = 0; base < N; base += rows_per_pass) {
         const int64_t row = base + rs;
         const bool valid = row < N;
@@ -363,9 +363,7 @@ __global__ void __launch_bounds__(kSelThreads) threshold_kernel(Shape sh, Bufs b
     __shared__ SelShared sm;
     const int b = blockIdx.y, h = blockIdx.x;
     const int64_t bh = (int64_t)b * sh.Hq + h;
-    const int64_t N = prefix_len(bf.len[b], sh.window);
-    const int k_eff = sh.k < N ? sh.k : (int)N;
-    if (N == 0) {                    // nothing to search for this sequence
+    if (prefix_len(visible_len(sh, bf, b), sh.window) == 0) {   // nothing to search for this sequence
         if (threadIdx.x == 0) {
             bf.thr[bh] = INFINITY;
             bf.flags[bh] = 0;
@@ -373,7 +371,9 @@ __global__ void __launch_bounds__(kSelThreads) threshold_kernel(Shape sh, Bufs b
         }
         return;
     }
-    const Plan pl = make_plan(N, k_eff);
+    // the sample was drawn by the plan of the cache sequence (shared by all its queries)
+    const int64_t N = prefix_len(bf.len[cache_seq(sh, b)], sh.window);
+    const Plan pl = make_plan(N, sh.k < N ? sh.k : (int)N);
     const SrcDense src{bf.samp + bh * sh.samp_cap, (int64_t)pl.n_samp};
     const Items<(kSampMax + kSelThreads - 1) / kSelThreads, SrcDense> items(src);
     const int rank = pl.rank < pl.n_samp ? pl.rank : pl.n_samp;
@@ -396,7 +396,7 @@ __global__ void __launch_bounds__(kSelThreads) select_candidates_kernel(Shape sh
     const int b = blockIdx.y, h = blockIdx.x;
     const int tid = threadIdx.x, lane = lane_id(), wave = tid >> 6;
     const int64_t bh = (int64_t)b * sh.Hq + h;
-    const int64_t N = prefix_len(bf.len[b], sh.window);
+    const int64_t N = prefix_len(visible_len(sh, bf, b), sh.window);
     const int k_eff = sh.k < N ? sh.k : (int)N;
 
     if (k_eff == 0) {                // nothing to search: only padding to write
@@ -453,7 +453,7 @@ __global__ void __launch_bounds__(kSelThreads) select_full_kernel(Shape sh, Bufs
     const int b = blockIdx.y, h = blockIdx.x;
     const int64_t bh = (int64_t)b * sh.Hq + h;
     if (redo_flagged && !bf.flags[bh]) return;
-    const int64_t N = prefix_len(bf.len[b], sh.window);
+    const int64_t N = prefix_len(visible_len(sh, bf, b), sh.window);
     const int k_eff = sh.k < N ? sh.k : (int)N;
     if (k_eff == 0) {
         pad_outputs(0, sh.k, bf.sel_idx + bh * sh.k, bf.sel_val + bh * sh.k);

@@ -21,7 +21,7 @@ PATH_AUTO, PATH_FULL, PATH_FILTER = 0, 1, 2
 
 EXPORTS = [
     "topk_attn_kv_bytes", "topk_attn_workspace_bytes", "topk_attn_create", "topk_attn_append_kv",
-    "topk_attn_decode", "topk_attn_decode_window", "topk_attn_k_schedule", "topk_attn_scores", "topk_attn_length", "topk_attn_reset", "topk_attn_set_path",
+    "topk_attn_decode", "topk_attn_decode_window", "topk_attn_decode_multi", "topk_attn_k_schedule", "topk_attn_scores", "topk_attn_length", "topk_attn_reset", "topk_attn_set_path",
     "topk_attn_last_fallbacks", "topk_attn_set_scan_timing", "topk_attn_scan_time", "topk_attn_read_probe", "topk_attn_strerror", "topk_attn_destroy",
 ]
 
@@ -40,6 +40,8 @@ class Config(ctypes.Structure):
         ("dtype", ctypes.c_int32),
         ("device", ctypes.c_int32),
         ("max_window", ctypes.c_int32),
+        ("max_queries", ctypes.c_int32),
+        ("reserved", ctypes.c_int32),
         ("kv_storage", ctypes.c_void_p),
         ("kv_bytes", ctypes.c_size_t),
         ("workspace", ctypes.c_void_p),
@@ -76,6 +78,8 @@ def lib() -> ctypes.CDLL:
         L.topk_attn_decode.restype = i32
         L.topk_attn_decode_window.argtypes = [vp, i32, vp, i32, i32, vp, vp, vp, vp, vp]
         L.topk_attn_decode_window.restype = i32
+        L.topk_attn_decode_multi.argtypes = [vp, i32, vp, i32, i32, i32, i32, vp, vp, vp, vp, vp]
+        L.topk_attn_decode_multi.restype = i32
         L.topk_attn_k_schedule.argtypes = [i64, i32, ctypes.c_double, ctypes.POINTER(ctypes.c_int32)]
         L.topk_attn_k_schedule.restype = i32
         L.topk_attn_scores.argtypes = [vp, i32, vp, vp, vp]
@@ -114,9 +118,10 @@ def _check(code: int, where: str) -> None:
 
 
 def make_config(n_layers, n_seqs, n_q_heads, n_kv_heads, head_dim, max_tokens, max_k, dtype, device=0,
-                kv_storage=0, kv_bytes=0, workspace=0, workspace_bytes=0, max_window=0) -> Config:
+                kv_storage=0, kv_bytes=0, workspace=0, workspace_bytes=0, max_window=0, max_queries=0) -> Config:
     return Config(ctypes.sizeof(Config), n_layers, n_seqs, n_q_heads, n_kv_heads, head_dim, max_tokens,
-                  max_k, dtype, device, max_window, kv_storage, kv_bytes, workspace, workspace_bytes)
+                  max_k, dtype, device, max_window, max_queries, 0, kv_storage, kv_bytes, workspace,
+                  workspace_bytes)
 
 
 def topk_attn_strerror(code: int) -> str:
@@ -155,6 +160,13 @@ def topk_attn_decode(h, layer, q_ptr, k, out_ptr, idx_ptr=0, vals_ptr=0, lse_ptr
 def topk_attn_decode_window(h, layer, q_ptr, k, window, out_ptr, idx_ptr=0, vals_ptr=0, lse_ptr=0, stream=0):
     _check(lib().topk_attn_decode_window(h, layer, q_ptr, k, window, out_ptr, idx_ptr or None, vals_ptr or None,
                                          lse_ptr or None, stream), "topk_attn_decode_window")
+
+
+def topk_attn_decode_multi(h, layer, q_ptr, n_queries, causal, k, window, out_ptr, idx_ptr=0, vals_ptr=0, lse_ptr=0,
+                           stream=0):
+    _check(lib().topk_attn_decode_multi(h, layer, q_ptr, n_queries, 1 if causal else 0, k, window, out_ptr,
+                                        idx_ptr or None, vals_ptr or None, lse_ptr or None, stream),
+           "topk_attn_decode_multi")
 
 
 def topk_attn_k_schedule(total_k: int, n_layers: int, last_over_first: float = 1.0):
@@ -208,14 +220,14 @@ class TopkAttnCache:
     """Allocates kv_storage/workspace as torch tensors and wraps the handle."""
 
     def __init__(self, n_layers, n_seqs, n_q_heads, n_kv_heads, head_dim, max_tokens, max_k, dtype, device=0,
-                 max_window=0):
+                 max_window=0, max_queries=0):
         import torch
         self.torch = torch
         self.shape = (n_layers, n_seqs, n_q_heads, n_kv_heads, head_dim, max_tokens, max_k, dtype)
         self.dtype = dtype
         self.device = torch.device("cuda", device)
         cfg = make_config(n_layers, n_seqs, n_q_heads, n_kv_heads, head_dim, max_tokens, max_k, dtype, device,
-                          max_window=max_window)
+                          max_window=max_window, max_queries=max_queries)
         kvb, wsb = topk_attn_kv_bytes(cfg), topk_attn_workspace_bytes(cfg)
         if kvb == 0 or wsb == 0:
             h = ctypes.c_void_p()
@@ -263,6 +275,20 @@ class TopkAttnCache:
             topk_attn_decode_window(self.h, layer, q.data_ptr(), k, window, *args)
         else:
             topk_attn_decode(self.h, layer, q.data_ptr(), k, *args)
+        return out, idx, vals, lse
+
+    def decode_multi(self, layer, q, k, causal=True, window=0, want_idx=True, want_vals=True, want_lse=True):
+        """q [B, M, Hq, d] device tensor -> (out [B, M, Hq, d], idx, vals [B, M, Hq, k], lse [B, M, Hq])."""
+        t = self.torch
+        B, M, Hq, d = q.shape
+        assert q.is_cuda and q.is_contiguous() and q.dtype == self.torch_dtype()
+        out = t.empty((B, M, Hq, d), dtype=t.float32, device=self.device)
+        idx = t.empty((B, M, Hq, k), dtype=t.int32, device=self.device) if want_idx else None
+        vals = t.empty((B, M, Hq, k), dtype=t.float32, device=self.device) if want_vals else None
+        lse = t.empty((B, M, Hq), dtype=t.float32, device=self.device) if want_lse else None
+        topk_attn_decode_multi(self.h, layer, q.data_ptr(), M, causal, k, window, out.data_ptr(),
+                               idx.data_ptr() if want_idx else 0, vals.data_ptr() if want_vals else 0,
+                               lse.data_ptr() if want_lse else 0, self._stream())
         return out, idx, vals, lse
 
     def scores(self, layer, q):

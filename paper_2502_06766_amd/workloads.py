@@ -212,6 +212,26 @@ def make_quantized(w: Workload, seed: int, layer: int = 0, seq: int = 0, threads
     return quantize(q, w.dtype), quantize(K, w.dtype), quantize(V, w.dtype)
 
 
+def make_query_chunk(q: np.ndarray, dtype: int, n_queries: int, seed: int, rho: float = 0.8) -> np.ndarray:
+    """A chunk of consecutive queries [M, Hq, d] (storage dtype) whose last row is the
+    given query block q [Hq, d] (storage dtype): neighbouring tokens ask for similar
+    things, so row m is q mixed with fresh noise of the same per-head norm, with
+    correlation rho ** (M - 1 - m) to q."""
+    qf = bf16_bits_to_f32(q) if dtype == BF16 else q.astype(np.float32)
+    Hq, d = qf.shape
+    g = _rng(seed, 0x51C0FFEE, n_queries, 0x7FFE0000)
+    norm = np.linalg.norm(qf, axis=1, keepdims=True)
+    rows = []
+    for m in range(n_queries):
+        c = rho ** (n_queries - 1 - m)
+        noise = g.standard_normal((Hq, d), dtype=np.float32)
+        noise *= norm / np.maximum(np.linalg.norm(noise, axis=1, keepdims=True), 1e-20)
+        rows.append(qf if m == n_queries - 1 else (c * qf + np.sqrt(1.0 - c * c) * noise).astype(np.float32))
+    out = quantize(np.stack(rows), dtype)
+    out[n_queries - 1] = q
+    return out
+
+
 def kv_cache_bytes(n_tokens: int, hidden: int, n_layers: int, bytes_per_el: int) -> int:
     """Size of a dense KV cache: two tensors of n_tokens x hidden per layer."""
     return 2 * n_tokens * hidden * n_layers * bytes_per_el

@@ -32,37 +32,77 @@ def score_margin(q, K, dtype) -> np.ndarray:
     return 8.0 * d * U32 * A.max(axis=1)
 
 
-def enforce_margin(q, K, dtype, k, max_rounds=60):
-    """Nudge keys (scale the row by 1 - 2^-6) until, for every head and every k asked
+def enforce_margin(q, K, dtype, k, max_rounds=60, prefix=None, shrink=2.0 ** -6):
+    """Nudge keys (scale the row by 1 - shrink) until, for every head and every k asked
     for (an int or a list), no unselected score lies within delta_h below the k-th largest
-    score.  Uses only oracle scores.  Returns (K, delta [Hq], rounds).  K is modified in place."""
+    score.  `prefix[h]` (default N) is the number of leading keys head h searches.  Uses only
+    oracle scores.  Returns (K, delta [Hq], rounds).  K is modified in place.
+
+    A nudged key moves in every head that shares its KV head; when it drops out of another
+    head's selection that head's boundary moves to a score whose neighbourhood has not been
+    cleared yet.  With many rows per KV head and a large N use a smaller `shrink` (still
+    several ulps of the storage dtype) so that such crossings stay rare and the rounds converge."""
     Hq, d = q.shape
     Hkv, N, _ = K.shape
     G = Hq // Hkv
-    ks = [kk for kk in (k if isinstance(k, (list, tuple)) else [k]) if kk < N]
+    P = np.full(Hq, N, dtype=np.int64) if prefix is None else np.asarray(prefix, dtype=np.int64)
+    ks = list(k) if isinstance(k, (list, tuple)) else [k]
     delta = score_margin(q, K, dtype)
-    if not ks:
+    if all(kk >= P.max() for kk in ks):
         return K, delta, 0
     for rnd in range(max_rounds):
         S = c_oracle.scores(q, K, dtype)
         dirty = False
         for h in range(Hq):
-            s = S[h]
+            n = int(P[h])
+            s = S[h, :n]
             for kk in ks:
-                part = np.partition(s, N - kk)          # part[N-kk] is the kk-th largest
-                s_k = part[N - kk]
-                below = part[:N - kk]
+                if kk >= n:
+                    continue
+                part = np.partition(s, n - kk)          # part[n-kk] is the kk-th largest
+                s_k = part[n - kk]
+                below = part[:n - kk]
                 if below.max() > s_k - delta[h]:
                     # unselected keys inside the band (ties with s_k at higher positions included)
                     cand = np.nonzero(s > s_k - delta[h])[0]      # the kk selected plus the band
                     order = cand[np.lexsort((cand, -s[cand]))]
                     viol = order[kk:]
-                    scale_rows_storage(K, dtype, h // G, viol, 1.0 - 2.0 ** -6)
+                    scale_rows_storage(K, dtype, h // G, viol, 1.0 - shrink)
                     dirty = True
                     break    # scores of this KV head changed: re-score before looking further
         if not dirty:
             return K, delta, rnd
     raise AssertionError("margin enforcement did not converge")
+
+
+def rows_by_kv_head(q, Hkv):
+    """q [M, Hq, d] -> [Hkv * M * G, d] with all (query, head) rows of a KV head adjacent
+    (row kvh * M * G + m * G + g is head kvh * G + g of query m), so that the single-query
+    helpers apply with a head group of M * G."""
+    M, Hq, d = q.shape
+    G = Hq // Hkv
+    return np.ascontiguousarray(q.reshape(M, Hkv, G, d).transpose(1, 0, 2, 3).reshape(Hkv * M * G, d))
+
+
+def multi_prefix(M, Hq, Hkv, N, causal, window):
+    """Searched prefix length of every row of rows_by_kv_head."""
+    G = Hq // Hkv
+    P = np.empty((Hkv, M, G), dtype=np.int64)
+    for m in range(M):
+        n_vis = N - (M - 1 - m) if causal else N
+        P[:, m, :] = n_vis - min(window, n_vis)
+    return P.reshape(-1)
+
+
+def enforce_margin_multi(q, K, dtype, k, causal, window=0, shrink=2.0 ** -6):
+    """Margin enforcement for a chunk of queries q [M, Hq, d]; returns (K, delta [M, Hq])."""
+    M, Hq, d = q.shape
+    Hkv, N, _ = K.shape
+    G = Hq // Hkv
+    q2 = rows_by_kv_head(q, Hkv)
+    K, delta2, _ = enforce_margin(q2, K, dtype, k, prefix=multi_prefix(M, Hq, Hkv, N, causal, window), shrink=shrink)
+    delta = delta2.reshape(Hkv, M, G).transpose(1, 0, 2).reshape(M, Hq)
+    return K, delta
 
 
 def to_torch(x: np.ndarray, dtype: int, device):

@@ -30,8 +30,8 @@ def test_library_exports_every_declared_symbol():
 
 
 def test_config_struct_matches_header_size():
-    # uint32 + 5*int32 + int64 + 4*int32 + 2*(ptr + size_t) = 24 + 8 + 16 + 32
-    assert ctypes.sizeof(ta.Config) == 80
+    # uint32 + 5*int32 + int64 + 6*int32 + 2*(ptr + size_t) = 24 + 8 + 24 + 32
+    assert ctypes.sizeof(ta.Config) == 88
 
 
 def test_kv_bytes_is_2ndl():
@@ -54,6 +54,9 @@ def test_kv_bytes_is_2ndl():
     (dict(n_layers=0), ta.EINVAL),
     (dict(max_k=0), ta.EINVAL),
     (dict(max_tokens=1 << 31), ta.EINVAL),
+    (dict(max_queries=-1), ta.EINVAL),
+    (dict(max_queries=5000), ta.EINVAL),
+    (dict(n_seqs=4096, max_queries=16), ta.EINVAL),  # sequences x queries is a grid dimension
 ])
 def test_bad_config_rejected_without_device(kw, code):
     base = dict(n_layers=1, n_seqs=1, n_q_heads=32, n_kv_heads=8, head_dim=128, max_tokens=4096, max_k=64,
@@ -65,6 +68,17 @@ def test_bad_config_rejected_without_device(kw, code):
     h = ctypes.c_void_p()
     assert ta.lib().topk_attn_create(ctypes.byref(cfg), ctypes.byref(h)) == code
     assert not h.value
+
+
+def test_workspace_grows_with_max_queries():
+    one = ta.topk_attn_workspace_bytes(ta.make_config(1, 2, 32, 8, 128, 65536, 1024, ta.F16))
+    same = ta.topk_attn_workspace_bytes(ta.make_config(1, 2, 32, 8, 128, 65536, 1024, ta.F16, max_queries=1))
+    four = ta.topk_attn_workspace_bytes(ta.make_config(1, 2, 32, 8, 128, 65536, 1024, ta.F16, max_queries=4))
+    assert same == one
+    assert 3.9 * one < four <= 4 * one
+    cfg = ta.make_config(1, 1, 4, 2, 64, 128, 8, ta.F32)
+    cfg.reserved = 1
+    assert ta.topk_attn_workspace_bytes(cfg) == 0
 
 
 def test_create_rejects_null_storage_and_wrong_struct_size():
@@ -79,6 +93,7 @@ def test_create_rejects_null_storage_and_wrong_struct_size():
 def test_null_handle_calls_fail_cleanly():
     L = ta.lib()
     assert L.topk_attn_decode(None, 0, None, 1, None, None, None, None, None) == ta.EINVAL
+    assert L.topk_attn_decode_multi(None, 0, None, 2, 1, 1, 0, None, None, None, None, None) == ta.EINVAL
     assert L.topk_attn_append_kv(None, 0, 0, None, None, 1, 1, 1, None) == ta.EINVAL
     assert L.topk_attn_length(None, 0, 0) == -1
     assert L.topk_attn_destroy(None) == ta.EINVAL

@@ -388,3 +388,84 @@ def test_window_is_lse_merge_of_topk_prefix_and_dense_window():
         np.testing.assert_allclose(out[h], wa * out_a[h] + wb * out_b[h], rtol=1e-11, atol=1e-13)
         np.testing.assert_allclose(out_c[h], out[h], rtol=1e-11, atol=1e-13)
         assert abs(lse_c[h] - lse[h]) < 1e-12
+
+
+# ---------------------------------------------------------------- several queries per cache
+def _rand_multi(M, Hq, Hkv, N, d, seed, dtype=wl.F32):
+    g = np.random.default_rng(seed)
+    q = g.standard_normal((M, Hq, d)).astype(np.float32)
+    K = g.standard_normal((Hkv, N, d)).astype(np.float32)
+    V = g.standard_normal((Hkv, N, d)).astype(np.float32)
+    qs, Ks, Vs = wl.quantize(q, dtype), wl.quantize(K, dtype), wl.quantize(V, dtype)
+    return (qs, Ks, Vs), (wl.widen(qs, dtype), wl.widen(Ks, dtype), wl.widen(Vs, dtype))
+
+
+@pytest.mark.parametrize("dtype", [wl.F32, wl.F16])
+def test_multi_causal_with_k_at_least_n_is_library_causal_attention(dtype):
+    """With k >= N every visible key is selected, so a causal chunk of M queries is the
+    last M rows of causal dense attention (library routine with a boolean mask)."""
+    M, Hq, Hkv, N, d = 5, 4, 2, 70, 16
+    (qs, Ks, Vs), (q, K, V) = _rand_multi(M, Hq, Hkv, N, d, 310, dtype)
+    G = Hq // Hkv
+    qt = torch.from_numpy(q).permute(1, 0, 2)[None]                         # [1, Hq, M, d]
+    Kt = torch.from_numpy(K).repeat_interleave(G, dim=0)[None]
+    Vt = torch.from_numpy(V).repeat_interleave(G, dim=0)[None]
+    pos = torch.arange(N)[None, :]
+    mask = pos <= (N - M + torch.arange(M))[:, None]                        # query m sees tokens 0 .. N-M+m
+    want = torch.nn.functional.scaled_dot_product_attention(qt, Kt, Vt, attn_mask=mask)[0].permute(1, 0, 2).numpy()
+    for out, idx, vals, lse in (ref.topk_attention_multi(q, K, V, N, True),
+                                c_oracle.topk_attention_multi(qs, Ks, Vs, dtype, N, True)):
+        np.testing.assert_allclose(out, want, rtol=1e-11, atol=1e-13)
+        for m in range(M):
+            n_vis = N - (M - 1 - m)
+            for h in range(Hq):
+                assert sorted(i for i in idx[m, h].tolist() if i >= 0) == list(range(n_vis))
+                assert (idx[m, h] == -1).sum() == N - n_vis
+
+
+def test_multi_rows_are_single_query_steps():
+    """Non-causal: row m is the plain step for query m.  Causal: the last query sees the
+    whole cache (plain step), the first one a cache M - 1 tokens shorter."""
+    M, Hq, Hkv, N, d, k = 3, 6, 2, 200, 8, 17
+    (qs, Ks, Vs), (q, K, V) = _rand_multi(M, Hq, Hkv, N, d, 311)
+    for fn_multi, fn_one, args in ((lambda c: ref.topk_attention_multi(q, K, V, k, c),
+                                    lambda m, n: ref.topk_attention(q[m], K[:, :n], V[:, :n], k), None),
+                                   (lambda c: c_oracle.topk_attention_multi(qs, Ks, Vs, wl.F32, k, c),
+                                    lambda m, n: c_oracle.topk_attention(
+                                        qs[m], np.ascontiguousarray(Ks[:, :n]), np.ascontiguousarray(Vs[:, :n]),
+                                        wl.F32, k), None)):
+        out, idx, vals, lse = fn_multi(False)
+        for m in range(M):
+            o1, i1, v1, l1 = fn_one(m, N)
+            np.testing.assert_array_equal(idx[m], i1)
+            np.testing.assert_allclose(out[m], o1, rtol=1e-13, atol=0)
+        out, idx, vals, lse = fn_multi(True)
+        for m in (0, M - 1):
+            o1, i1, v1, l1 = fn_one(m, N - (M - 1 - m))
+            np.testing.assert_array_equal(idx[m], i1)
+            np.testing.assert_allclose(out[m], o1, rtol=1e-13, atol=0)
+            np.testing.assert_allclose(lse[m], l1, rtol=1e-13, atol=0)
+        assert idx[0].max() <= N - M        # the first query never sees the last M - 1 tokens
+
+
+@pytest.mark.parametrize("seed", range(3))
+def test_multi_bruteforce_tiny(seed):
+    g = np.random.default_rng(900 + seed)
+    N, d, M = int(g.integers(9, 13)), 4, 3
+    k, W = int(g.integers(1, 4)), int(g.integers(0, 3))
+    (qs, Ks, Vs), (q, K, V) = _rand_multi(M, 1, 1, N, d, 320 + seed)
+    res = (ref.topk_attention_multi(q, K, V, k, True, W), c_oracle.topk_attention_multi(qs, Ks, Vs, wl.F32, k, True, W))
+    for m in range(M):
+        n_vis = N - (M - 1 - m)
+        P = n_vis - W
+        S = [sum(q[m, 0, c] * K[0, i, c] for c in range(d)) for i in range(n_vis)]
+        best = max(itertools.combinations(range(P), k), key=lambda I: sum(S[i] for i in I))
+        att = list(best) + list(range(P, n_vis))
+        mx = max(S[i] for i in att)
+        w = {i: math.exp((S[i] - mx) / math.sqrt(d)) for i in att}
+        Z = sum(w.values())
+        want = [sum(w[i] / Z * V[0, i, c] for i in att) for c in range(d)]
+        for out, idx, vals, lse in res:
+            assert set(idx[m, 0].tolist()) == set(best)
+            np.testing.assert_allclose(out[m, 0], want, rtol=1e-12, atol=1e-14)
+            assert abs(lse[m, 0] - (mx / math.sqrt(d) + math.log(Z))) < 1e-12
