@@ -31,6 +31,8 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=6)
     ap.add_argument("--layers", type=int, default=4, help="distinct resident layers the steps rotate over")
     ap.add_argument("--tokens", type=int, default=0, help="override N (debug only; invalidates the metric)")
+    ap.add_argument("--queries", type=int, default=1,
+                    help="queries per step (a causal chunk through topk_attn_decode_multi); 1 is the metric's workload")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--seed", type=int, default=0)
     args = ap.parse_args()
@@ -56,7 +58,8 @@ def main() -> int:
     q, K, V = wl.make_quantized(w, args.seed, threads=16)
     gen_s = time.time() - t0
 
-    cache = ta.TopkAttnCache(L, 1, Hq, Hkv, d, N, k, w.dtype)
+    M = max(1, args.queries)
+    cache = ta.TopkAttnCache(L, 1, Hq, Hkv, d, N, k, w.dtype, max_queries=M)
     Kd, Vd = torch.from_numpy(K).to(dev), torch.from_numpy(V).to(dev)
     for layer in range(L):
         if layer == 0:
@@ -65,14 +68,20 @@ def main() -> int:
             sh = 7919 * layer
             cache.append(layer, 0, torch.roll(Kd, sh, 1), torch.roll(Vd, sh, 1), head_major=True)
     del Kd, Vd
+    if M > 1:
+        q = wl.make_query_chunk(q, w.dtype, M, args.seed)
     qd = torch.from_numpy(q).to(dev)[None].contiguous()
-    out = torch.empty((1, Hq, d), dtype=torch.float32, device=dev)
-    idx = torch.empty((1, Hq, k), dtype=torch.int32, device=dev)
+    out = torch.empty((1, M, Hq, d), dtype=torch.float32, device=dev)
+    idx = torch.empty((1, M, Hq, k), dtype=torch.int32, device=dev)
     stream = torch.cuda.current_stream(dev).cuda_stream
     torch.cuda.synchronize()
 
     def step(i):
-        ta.topk_attn_decode(cache.h, i % L, qd.data_ptr(), k, out.data_ptr(), idx.data_ptr(), 0, 0, stream)
+        if M == 1:
+            ta.topk_attn_decode(cache.h, i % L, qd.data_ptr(), k, out.data_ptr(), idx.data_ptr(), 0, 0, stream)
+        else:
+            ta.topk_attn_decode_multi(cache.h, i % L, qd.data_ptr(), M, True, k, 0, out.data_ptr(), idx.data_ptr(),
+                                      0, 0, stream)
 
     for i in range(args.warmup):
         step(i)
@@ -108,12 +117,13 @@ def main() -> int:
     probe_gbps = k_bytes / (min(probe_ms[L:]) * 1e-3) / 1e9
 
     e = 2
-    alg_bytes = Hkv * N * d * e + Hq * k * d * e + Hq * d * (e + 4) + Hq * k * 4
+    alg_bytes = Hkv * N * d * e + M * (Hq * k * d * e + Hq * d * (e + 4) + Hq * k * 4)
     keys_per_s = Hkv * N / (ms_per_step * 1e-3)
-    scan_gbps = k_bytes / (scan_ms * 1e-3) / 1e9
+    n_qblk = 1 if M == 1 else -(-M // (16 // (Hq // Hkv)))     # passes over the keys: one per block of 16 rows
+    scan_gbps = k_bytes * n_qblk / (scan_ms * 1e-3) / 1e9
 
     cpu = None
-    if not args.no_cpu_baseline:
+    if not args.no_cpu_baseline and M == 1:
         from oracle import c_oracle
         t0 = time.perf_counter()
         c_oracle.topk_attention(q, K, V, w.dtype, k)
@@ -135,16 +145,17 @@ def main() -> int:
         "dtype": "f16",
         "data": "synthetic",
         "config": {"workload": w.name, "n_q_heads": Hq, "n_kv_heads": Hkv, "head_dim": d, "n_tokens": N,
-                   "k": k, "layers_rotated": L, "n_seqs": 1},
-        "scores_per_sec": Hq * N / (ms_per_step * 1e-3),
+                   "k": k, "layers_rotated": L, "n_seqs": 1, "queries_per_step": M},
+        "scores_per_sec": M * Hq * N / (ms_per_step * 1e-3),
         "step_hbm_gbps": alg_bytes / (ms_per_step * 1e-3) / 1e9,
         "step_pct_of_hbm_peak": 100.0 * alg_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBPS,
         "step_ms_gpu_events": ev0.elapsed_time(ev1) / args.steps,
         "read_probe_gbps": probe_gbps,
         "filter_fallback_heads": fallbacks,
-        "roofline": {"bound": "hbm", "kernel": "scan_mfma_kernel (filter)", "achieved": scan_gbps,
+        "roofline": {"bound": "hbm", "kernel": "scan_mfma_kernel (filter)" if M == 1 else "scan_rows_kernel (filter)", "achieved": scan_gbps,
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": scan_gbps / HBM_PEAK_GBPS,
-                     "traffic": SCAN_TRAFFIC_BYTES_C3 if not args.tokens else None, "ms_per_launch": scan_ms, "bytes_per_launch": k_bytes,
+                     "traffic": SCAN_TRAFFIC_BYTES_C3 if not args.tokens and M == 1 else None, "ms_per_launch": scan_ms,
+                     "bytes_per_launch": k_bytes * n_qblk,
                      "frac_of_read_probe": scan_gbps / probe_gbps},
         "cpu_baseline": cpu,
         "input_generation_s": gen_s,

@@ -153,6 +153,23 @@ int topk_attn_decode_multi(topk_attn_t* h, int layer, const void* q, int n_queri
  * k >= 1), last_over_first <= 0 or not finite, or a k_l would not fit in int32. */
 int topk_attn_k_schedule(int64_t total_k, int n_layers, double last_over_first, int32_t* k_out);
 
+/* Decode steps of n_layers consecutive layers [layer0, layer0 + n_layers) with a per-layer k
+ * (e.g. from topk_attn_k_schedule), enqueued back to back on `hip_stream`: the same work as
+ * n_layers calls of topk_attn_decode_window, one per layer, each with its own query block.
+ * (In a transformer layer l+1's query depends on layer l's output; this entry point serves
+ * callers that have all queries at hand, such as replaying recorded queries or measuring
+ * a whole-model decode step.)
+ *   q     device [n_layers, B, Hq, d];  out device [n_layers, B, Hq, d] fp32
+ *   k     host   [n_layers] int32, each in [1, max_k]
+ *   idx / vals  device or NULL: ragged concatenation, layer l's [B, Hq, k[l]] block starts
+ *         at element B * Hq * (k[0] + ... + k[l-1])
+ *   lse   device [n_layers, B, Hq] or NULL
+ * Errors as topk_attn_decode_window for any layer; nothing is enqueued unless all layers
+ * pass the checks. */
+int topk_attn_decode_layers(topk_attn_t* h, int layer0, int n_layers, const void* q, const int32_t* k,
+                            int window, float* out, int32_t* idx, float* vals, float* lse,
+                            void* hip_stream);
+
 /* Debug/measurement: write the full fp32 score matrix S = q K^T of `layer`
  * to scores [B, Hq, max_tokens] (device); entries beyond a sequence's length are
  * left untouched. */

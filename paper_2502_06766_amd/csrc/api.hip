@@ -394,6 +394,29 @@ int topk_attn_decode_multi(topk_attn_t* h, int layer, const void* q, int n_queri
     return decode_impl(h, layer, q, n_queries, causal, k, window, out, idx, vals, lse, hip_stream);
 }
 
+int topk_attn_decode_layers(topk_attn_t* h, int layer0, int n_layers, const void* q, const int32_t* k, int window,
+                            float* out, int32_t* idx, float* vals, float* lse, void* hip_stream) {
+    if (!h || !q || !out || !k) return TOPK_ATTN_EINVAL;
+    if (n_layers < 1 || layer0 < 0 || layer0 > h->cfg.n_layers - n_layers) return TOPK_ATTN_EINVAL;
+    if (window < 0 || window > h->cfg.max_window || ((uintptr_t)q & 15)) return TOPK_ATTN_EINVAL;
+    for (int l = 0; l < n_layers; ++l) {
+        if (k[l] < 1 || k[l] > h->cfg.max_k) return TOPK_ATTN_EINVAL;
+        for (int b = 0; b < h->cfg.n_seqs; ++b)
+            if (h->len[(size_t)(layer0 + l) * h->cfg.n_seqs + b] < 1) return TOPK_ATTN_EINVAL;
+    }
+    const size_t BH = (size_t)h->cfg.n_seqs * h->cfg.n_q_heads;
+    const size_t q_step = BH * h->cfg.head_dim * elem_bytes(h->cfg.dtype);
+    size_t sel_off = 0;
+    for (int l = 0; l < n_layers; ++l) {
+        const int rc = decode_impl(h, layer0 + l, static_cast<const char*>(q) + l * q_step, 1, 0, k[l], window,
+                                   out + l * BH * h->cfg.head_dim, idx ? idx + sel_off : nullptr,
+                                   vals ? vals + sel_off : nullptr, lse ? lse + l * BH : nullptr, hip_stream);
+        if (rc != TOPK_ATTN_OK) return rc;
+        sel_off += BH * (size_t)k[l];
+    }
+    return TOPK_ATTN_OK;
+}
+
 int topk_attn_k_schedule(int64_t total_k, int n_layers, double last_over_first, int32_t* k_out) {
     if (!k_out || n_layers < 1 || total_k < n_layers) return TOPK_ATTN_EINVAL;
     if (!(last_over_first > 0.0) || !std::isfinite(last_over_first)) return TOPK_ATTN_EINVAL;

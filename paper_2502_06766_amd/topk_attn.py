@@ -21,7 +21,7 @@ PATH_AUTO, PATH_FULL, PATH_FILTER = 0, 1, 2
 
 EXPORTS = [
     "topk_attn_kv_bytes", "topk_attn_workspace_bytes", "topk_attn_create", "topk_attn_append_kv",
-    "topk_attn_decode", "topk_attn_decode_window", "topk_attn_decode_multi", "topk_attn_k_schedule", "topk_attn_scores", "topk_attn_length", "topk_attn_reset", "topk_attn_set_path",
+    "topk_attn_decode", "topk_attn_decode_window", "topk_attn_decode_multi", "topk_attn_decode_layers", "topk_attn_k_schedule", "topk_attn_scores", "topk_attn_length", "topk_attn_reset", "topk_attn_set_path",
     "topk_attn_last_fallbacks", "topk_attn_set_scan_timing", "topk_attn_scan_time", "topk_attn_read_probe", "topk_attn_strerror", "topk_attn_destroy",
 ]
 
@@ -80,6 +80,8 @@ def lib() -> ctypes.CDLL:
         L.topk_attn_decode_window.restype = i32
         L.topk_attn_decode_multi.argtypes = [vp, i32, vp, i32, i32, i32, i32, vp, vp, vp, vp, vp]
         L.topk_attn_decode_multi.restype = i32
+        L.topk_attn_decode_layers.argtypes = [vp, i32, i32, vp, ctypes.POINTER(ctypes.c_int32), i32, vp, vp, vp, vp, vp]
+        L.topk_attn_decode_layers.restype = i32
         L.topk_attn_k_schedule.argtypes = [i64, i32, ctypes.c_double, ctypes.POINTER(ctypes.c_int32)]
         L.topk_attn_k_schedule.restype = i32
         L.topk_attn_scores.argtypes = [vp, i32, vp, vp, vp]
@@ -167,6 +169,13 @@ def topk_attn_decode_multi(h, layer, q_ptr, n_queries, causal, k, window, out_pt
     _check(lib().topk_attn_decode_multi(h, layer, q_ptr, n_queries, 1 if causal else 0, k, window, out_ptr,
                                         idx_ptr or None, vals_ptr or None, lse_ptr or None, stream),
            "topk_attn_decode_multi")
+
+
+def topk_attn_decode_layers(h, layer0, ks, q_ptr, window, out_ptr, idx_ptr=0, vals_ptr=0, lse_ptr=0, stream=0):
+    """ks: per-layer k (sequence of ints) for layers layer0 .. layer0 + len(ks) - 1."""
+    arr = (ctypes.c_int32 * max(1, len(ks)))(*ks)
+    _check(lib().topk_attn_decode_layers(h, layer0, len(ks), q_ptr, arr, window, out_ptr, idx_ptr or None,
+                                         vals_ptr or None, lse_ptr or None, stream), "topk_attn_decode_layers")
 
 
 def topk_attn_k_schedule(total_k: int, n_layers: int, last_over_first: float = 1.0):

@@ -5,6 +5,8 @@ boundary, or are integer valued so both sides are exact); vals within delta/8 of
 double-precision scores (delta = 8 d u max sum|q_c K_c|); out within 2e-3 (16-bit)
 or 1e-5 (fp32) of max|out_ref| per head.
 """
+import ctypes
+
 import numpy as np
 import pytest
 import torch
@@ -454,14 +456,40 @@ def test_layerwise_k_schedule_decode():
     assert sum(ks) == 1600 and ks[0] < ks[-1]
     cache = ta.TopkAttnCache(L, 1, Hq, Hkv, d, N, max(ks), dtype)
     try:
+        per_layer, queries = [], []
         for l in range(L):
             q, K, V = rand_case(Hq, Hkv, N, d, dtype, ks[l], seed=40 + l)
             cache.append(l, 0, H.to_torch(K, dtype, DEV), H.to_torch(V, dtype, DEV), head_major=True)
-            out, idx, vals, lse = cache.decode(l, H.to_torch(q, dtype, DEV)[None].contiguous(), ks[l])
+            queries.append(H.to_torch(q, dtype, DEV)[None].contiguous())
+            out, idx, vals, lse = cache.decode(l, queries[-1], ks[l])
             torch.cuda.synchronize()
+            per_layer.append((out, idx, vals, lse))
             ref = c_oracle.topk_attention(q, K, V, dtype, ks[l])
             H.check_against_oracle(out[0].cpu().numpy(), idx[0].cpu().numpy(), vals[0].cpu().numpy(),
                                    lse[0].cpu().numpy(), ref, H.score_margin(q, K, dtype), ks[l], 2e-3,
                                    float(np.abs(wl.widen(V, dtype)).max()), f"layer {l} k={ks[l]}")
+        # all layers in one call: ragged idx / vals blocks, bit-identical to the per-layer calls
+        qd = torch.stack(queries).contiguous()                                  # [L, 1, Hq, d]
+        out_all = torch.empty((L, 1, Hq, d), dtype=torch.float32, device=DEV)
+        idx_all = torch.empty((Hq * sum(ks),), dtype=torch.int32, device=DEV)
+        vals_all = torch.empty((Hq * sum(ks),), dtype=torch.float32, device=DEV)
+        lse_all = torch.empty((L, 1, Hq), dtype=torch.float32, device=DEV)
+        st = torch.cuda.current_stream().cuda_stream
+        ta.topk_attn_decode_layers(cache.h, 0, ks, qd.data_ptr(), 0, out_all.data_ptr(), idx_all.data_ptr(),
+                                   vals_all.data_ptr(), lse_all.data_ptr(), st)
+        torch.cuda.synchronize()
+        off = 0
+        for l in range(L):
+            out, idx, vals, lse = per_layer[l]
+            n = Hq * ks[l]
+            assert torch.equal(out_all[l], out) and torch.equal(lse_all[l], lse)
+            assert torch.equal(idx_all[off:off + n].view(1, Hq, ks[l]), idx)
+            assert torch.equal(vals_all[off:off + n].view(1, Hq, ks[l]), vals)
+            off += n
+        bad = (ctypes.c_int32 * L)(*([ks[0]] * (L - 1) + [max(ks) + 1]))
+        assert ta.lib().topk_attn_decode_layers(cache.h, 0, L, qd.data_ptr(), bad, 0, out_all.data_ptr(), None, None,
+                                                None, st) == ta.EINVAL
+        assert ta.lib().topk_attn_decode_layers(cache.h, 1, L, qd.data_ptr(), bad, 0, out_all.data_ptr(), None, None,
+                                                None, st) == ta.EINVAL
     finally:
         cache.close()

@@ -469,3 +469,89 @@ def test_multi_bruteforce_tiny(seed):
             assert set(idx[m, 0].tolist()) == set(best)
             np.testing.assert_allclose(out[m, 0], want, rtol=1e-12, atol=1e-14)
             assert abs(lse[m, 0] - (mx / math.sqrt(d) + math.log(Z))) < 1e-12
+
+
+# ---------------------------------------------------------------- compressed (int8) key index
+from oracle import int8_index_ref as i8  # noqa: E402
+
+
+def test_int8_codes_reconstruct_within_half_a_step():
+    g = np.random.default_rng(400)
+    x = (g.standard_normal((300, 128)) * g.uniform(0.01, 30.0, (300, 1))).astype(np.float32)
+    x[7] = 0.0                                   # an all-zero row
+    x[8, 5] = 1e-30                              # a row whose largest element is tiny
+    codes, scale = i8.quantize_rows_int8(x)
+    assert codes.dtype == np.int8 and scale.dtype == np.float32
+    assert np.abs(codes.astype(np.int32)).max() <= 127
+    err = np.abs(x.astype(np.float64) - codes.astype(np.float64) * scale[:, None].astype(np.float64))
+    assert (err <= 0.5 * scale[:, None].astype(np.float64) * (1 + 1e-5) + 1e-45).all()
+    # the largest element of every non-zero row is coded +-127, a zero row is all zeros with scale 0
+    for r in range(300):
+        j = np.abs(x[r]).argmax()
+        if x[r, j] != 0:
+            assert abs(int(codes[r, j])) == 127 and np.sign(codes[r, j]) == np.sign(x[r, j])
+    assert (codes[7] == 0).all() and scale[7] == 0
+    # odd symmetry and monotonicity within a row
+    c2, s2 = i8.quantize_rows_int8(-x)
+    assert np.array_equal(c2, -codes) and np.array_equal(s2, scale)
+    o = np.argsort(x[3])
+    assert (np.diff(codes[3][o].astype(np.int32)) >= 0).all()
+
+
+def test_int8_codes_agree_with_library_quantiser():
+    """torch.quantize_per_tensor with the same scale rounds x * (1/scale) instead of
+    x * (127/amax): the two products differ by an ulp at most, so codes may differ only at
+    rounding ties, and then by one."""
+    g = np.random.default_rng(401)
+    x = g.standard_normal((64, 128)).astype(np.float32) * 3
+    codes, scale = i8.quantize_rows_int8(x)
+    differ = 0
+    for r in range(64):
+        t = torch.quantize_per_tensor(torch.from_numpy(x[r]), float(scale[r]), 0, torch.qint8).int_repr().numpy()
+        d = np.abs(t.astype(np.int32) - codes[r].astype(np.int32))
+        assert d.max() <= 1
+        differ += int((d != 0).sum())
+    assert differ <= 64 * 128 // 200
+
+
+def test_int8_approx_scores_closed_form_error_bound_and_orientation():
+    g = np.random.default_rng(402)
+    Hq, Hkv, N, d = 6, 3, 500, 64
+    q = g.standard_normal((Hq, d)).astype(np.float32)
+    K = g.standard_normal((Hkv, N, d)).astype(np.float32)
+    K[1] *= 7.0                                   # a KV head on another scale: catches a wrong head mapping
+    A = i8.approx_scores_int8(q, K)
+    S = ref.scores(q, K)
+    _, sq = i8.quantize_rows_int8(q)
+    _, sK = i8.quantize_rows_int8(K)
+    for h in range(Hq):
+        g_ = h // 2
+        # |q.K - q~.K~| <= |q|_1 sK/2 + |K|_1 sq/2 + d sq sK / 4
+        bound = (np.abs(q[h]).sum() * sK[g_] / 2 + np.abs(K[g_]).sum(axis=1) * sq[h] / 2 + d * sq[h] * sK[g_] / 4)
+        assert (np.abs(A[h] - S[h]) <= bound * (1 + 1e-4)).all()
+        # and in practice far tighter: quantisation noise is a few percent of the score spread
+        assert np.abs(A[h] - S[h]).std() < 0.05 * S[h].std()
+    # integer-valued inputs with amax = 127 are coded exactly: approximate == exact
+    qi = g.integers(-127, 128, (2, 32)).astype(np.float32); qi[:, 0] = 127
+    Ki = g.integers(-127, 128, (1, 40, 32)).astype(np.float32); Ki[:, :, 1] = -127
+    np.testing.assert_array_equal(i8.approx_scores_int8(qi, Ki).astype(np.float64), ref.scores(qi, Ki))
+
+
+def test_rerank_with_all_candidates_is_the_exact_step_and_recall_grows():
+    (qs, Ks, Vs), (q, K, V) = _rand(4, 2, 3000, 32, 403)
+    k = 100
+    exact = ref.topk_attention(q, K, V, k)
+    full = i8.rerank_topk(qs, Ks, Vs, k, 3000)
+    np.testing.assert_array_equal(np.sort(full[1], axis=1), np.sort(exact[1], axis=1))
+    np.testing.assert_allclose(full[0], exact[0], rtol=1e-12, atol=1e-14)
+    prev = 0.0
+    for c in (100, 120, 160, 300):
+        got = i8.rerank_topk(qs, Ks, Vs, k, c)
+        rec = np.mean([i8.recall_at_k(got[1][h], exact[1][h]) for h in range(4)])
+        assert rec >= prev - 1e-12
+        prev = rec
+        # whatever was returned carries its exact score
+        for h in range(4):
+            np.testing.assert_allclose(got[2][h], (K[h // 2][got[1][h]] @ q[h]), rtol=1e-12)
+    assert prev == 1.0            # 3x over-fetch recovers everything at this noise level
+    assert i8.recall_at_k(np.array([1, 2, -1]), np.array([2, 3, -1, -1])) == 0.5
