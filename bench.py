@@ -33,6 +33,8 @@ def main() -> int:
     ap.add_argument("--tokens", type=int, default=0, help="override N (debug only; invalidates the metric)")
     ap.add_argument("--queries", type=int, default=1,
                     help="queries per step (a causal chunk through topk_attn_decode_multi); 1 is the metric's workload")
+    ap.add_argument("--index", action="store_true",
+                    help="approximate search through the int8 key index (exact refinement); not the metric's workload")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--seed", type=int, default=0)
     args = ap.parse_args()
@@ -59,7 +61,10 @@ def main() -> int:
     gen_s = time.time() - t0
 
     M = max(1, args.queries)
-    cache = ta.TopkAttnCache(L, 1, Hq, Hkv, d, N, k, w.dtype, max_queries=M)
+    cache = ta.TopkAttnCache(L, 1, Hq, Hkv, d, N, k, w.dtype, max_queries=M,
+                             index_kind=ta.INDEX_INT8 if args.index else ta.INDEX_NONE)
+    if args.index:
+        cache.set_path(ta.PATH_INDEX)
     Kd, Vd = torch.from_numpy(K).to(dev), torch.from_numpy(V).to(dev)
     for layer in range(L):
         if layer == 0:
@@ -120,10 +125,13 @@ def main() -> int:
     alg_bytes = Hkv * N * d * e + M * (Hq * k * d * e + Hq * d * (e + 4) + Hq * k * 4)
     keys_per_s = Hkv * N / (ms_per_step * 1e-3)
     n_qblk = 1 if M == 1 else -(-M // (16 // (Hq // Hkv)))     # passes over the keys: one per block of 16 rows
-    scan_gbps = k_bytes * n_qblk / (scan_ms * 1e-3) / 1e9
+    scan_bytes = k_bytes * n_qblk
+    if args.index and M == 1:
+        scan_bytes = Hkv * N * (d + 4)                          # int8 codes and one fp32 scale per key
+    scan_gbps = scan_bytes / (scan_ms * 1e-3) / 1e9
 
     cpu = None
-    if not args.no_cpu_baseline and M == 1:
+    if not args.no_cpu_baseline and M == 1 and not args.index:
         from oracle import c_oracle
         t0 = time.perf_counter()
         c_oracle.topk_attention(q, K, V, w.dtype, k)
@@ -145,17 +153,18 @@ def main() -> int:
         "dtype": "f16",
         "data": "synthetic",
         "config": {"workload": w.name, "n_q_heads": Hq, "n_kv_heads": Hkv, "head_dim": d, "n_tokens": N,
-                   "k": k, "layers_rotated": L, "n_seqs": 1, "queries_per_step": M},
+                   "k": k, "layers_rotated": L, "n_seqs": 1, "queries_per_step": M,
+                   "search": "int8 index + exact refinement" if args.index else "exact"},
         "scores_per_sec": M * Hq * N / (ms_per_step * 1e-3),
         "step_hbm_gbps": alg_bytes / (ms_per_step * 1e-3) / 1e9,
         "step_pct_of_hbm_peak": 100.0 * alg_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBPS,
         "step_ms_gpu_events": ev0.elapsed_time(ev1) / args.steps,
         "read_probe_gbps": probe_gbps,
         "filter_fallback_heads": fallbacks,
-        "roofline": {"bound": "hbm", "kernel": "scan_mfma_kernel (filter)" if M == 1 else "scan_rows_kernel (filter)", "achieved": scan_gbps,
+        "roofline": {"bound": "hbm", "kernel": ("scan8_kernel (filter)" if args.index else "scan_mfma_kernel (filter)") if M == 1 else "scan_rows_kernel (filter)", "achieved": scan_gbps,
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": scan_gbps / HBM_PEAK_GBPS,
-                     "traffic": SCAN_TRAFFIC_BYTES_C3 if not args.tokens and M == 1 else None, "ms_per_launch": scan_ms,
-                     "bytes_per_launch": k_bytes * n_qblk,
+                     "traffic": SCAN_TRAFFIC_BYTES_C3 if not args.tokens and M == 1 and not args.index else None, "ms_per_launch": scan_ms,
+                     "bytes_per_launch": scan_bytes,
                      "frac_of_read_probe": scan_gbps / probe_gbps},
         "cpu_baseline": cpu,
         "input_generation_s": gen_s,

@@ -48,9 +48,23 @@ enum { TOPK_ATTN_F32 = 0, TOPK_ATTN_F16 = 1, TOPK_ATTN_BF16 = 2 }; /* element ty
 enum {
     TOPK_ATTN_PATH_AUTO = 0,    /* filtered scan when the shape allows it, else full */
     TOPK_ATTN_PATH_FULL = 1,    /* always materialise all N scores and radix-select over them */
-    TOPK_ATTN_PATH_FILTER = 2   /* sampled-threshold scan whenever its candidate list fits the
+    TOPK_ATTN_PATH_FILTER = 2,  /* sampled-threshold scan whenever its candidate list fits the
                                    workspace, also for short caches (the full path still redoes
                                    heads whose candidate list under- or overflows) */
+    TOPK_ATTN_PATH_INDEX = 3    /* approximate search over the int8 key index with exact refinement
+                                   (needs index_kind = TOPK_ATTN_INDEX_INT8); where the filtered scan
+                                   does not apply (short caches, dense k, several queries) the exact
+                                   path runs instead */
+};
+
+/* Search index kept beside the keys (Algorithm 1's build_index; the paper leaves the kind of
+ * index open, from a plain list to approximate structures). */
+enum {
+    TOPK_ATTN_INDEX_NONE = 0,   /* the key array itself: exact search */
+    TOPK_ATTN_INDEX_INT8 = 1    /* plus a compressed copy of every key row: int8 codes
+                                   rint(x * 127 / amax) and one fp32 scale amax / 127 per row
+                                   (amax = largest magnitude of the row; rows below 2^-100 are coded
+                                   as zero).  16-bit dtypes, head_dim 64 or 128, Hq/Hkv <= 4. */
 };
 
 typedef struct {
@@ -67,7 +81,7 @@ typedef struct {
     int32_t max_window;     /* largest `window` topk_attn_decode_window will be called with (0 if unused) */
     int32_t max_queries;    /* largest n_queries topk_attn_decode_multi will be called with (0 or 1 if
                                unused); the workspace grows in proportion */
-    int32_t reserved;       /* must be 0 */
+    int32_t index_kind;     /* TOPK_ATTN_INDEX_*; the index lives in kv_storage after K and V */
     void* kv_storage;       /* device, >= topk_attn_kv_bytes(), 256-byte aligned, caller-owned */
     size_t kv_bytes;
     void* workspace;        /* device, >= topk_attn_workspace_bytes(), 256-byte aligned, caller-owned */
@@ -76,7 +90,10 @@ typedef struct {
 
 /* Bytes of cache storage for the configuration: K then V, each laid out
  * [layer][seq][kv_head][max_tokens][head_dim] in `dtype` (2 L B Hkv N_cap d e bytes;
- * the paper's 2NDL cache of the Introduction with D = Hkv*d).  0 on invalid config. */
+ * the paper's 2NDL cache of the Introduction with D = Hkv*d), each rounded up to 256 bytes.
+ * With TOPK_ATTN_INDEX_INT8 the codes [layer][seq][kv_head][max_tokens][head_dim] int8 and
+ * then the scales [layer][seq][kv_head][max_tokens] fp32 follow (each rounded up to 256
+ * bytes).  0 on invalid config. */
 size_t topk_attn_kv_bytes(const topk_attn_config* cfg);
 
 /* Bytes of scratch the kernels need (score buffer, candidate lists, partial sums,
@@ -181,7 +198,13 @@ int64_t topk_attn_length(const topk_attn_t* h, int layer, int seq);
 /* Forget the tokens of (layer, seq) (length := 0); enqueued on hip_stream. */
 int topk_attn_reset(topk_attn_t* h, int layer, int seq, void* hip_stream);
 
-/* Choose the selection pipeline (TOPK_ATTN_PATH_*); default AUTO. */
+/* Choose the selection pipeline (TOPK_ATTN_PATH_*); default AUTO.  EINVAL for an unknown
+ * value, or TOPK_ATTN_PATH_INDEX on a handle without an index.  With TOPK_ATTN_PATH_INDEX
+ * the result of decode is approximate: a key whose coded score falls below the candidate
+ * threshold is missed even if its exact score belongs to the k largest (recall@k against
+ * the exact path is the figure of merit); positions returned always carry their exact
+ * scores, and the softmax runs over exactly those.  topk_attn_scores then dumps the
+ * approximate scores  float(codes(q) . codes(K_i)) * (scale_q * scale_i). */
 int topk_attn_set_path(topk_attn_t* h, int path);
 
 /* After the stream has been synchronised by the caller: number of (sequence, head)

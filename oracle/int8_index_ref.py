@@ -10,7 +10,8 @@ final top-k (approximate search, exact refinement).  The paper fixes none of the
 details; the definitions below are this build's and are listed with its other readings.
 
   code_c  = rint(x_c * (127 / amax))    (fp32 multiply, round half to even), amax = max_c |x_c|
-  scale   = amax / 127                  (fp32); an all-zero row has codes 0 and scale 0
+  scale   = amax / 127                  (fp32); a row with amax < 2^-100 (all zeros included) has
+                                        codes 0 and scale 0, which keeps 127 / amax finite
   s~(q,K_i) = float(sum_c codeq_c * codeK_ic) * (scale_q * scale_Ki)     (all fp32)
 
 Encoding and integer work are bit-exact contracts; the search result is judged by
@@ -34,11 +35,12 @@ def quantize_rows_int8(x: np.ndarray):
     """x [..., d] (values exactly representable in fp32) -> (codes int8 [..., d], scale fp32 [...])."""
     x = np.asarray(x, dtype=np.float32)
     amax = np.abs(x).max(axis=-1)
-    with np.errstate(divide="ignore"):
-        inv = np.where(amax > 0, np.float32(127.0) / amax, np.float32(0.0)).astype(np.float32)
+    live = amax >= np.float32(2.0 ** -100)
+    safe = np.where(live, amax, np.float32(1.0))
+    inv = np.where(live, np.float32(127.0) / safe, np.float32(0.0)).astype(np.float32)
     v = (x * inv[..., None]).astype(np.float32)
     codes = np.rint(v).astype(np.int8)               # round half to even, |v| <= 127
-    scale = (amax / np.float32(127.0)).astype(np.float32)
+    scale = np.where(live, amax / np.float32(127.0), np.float32(0.0)).astype(np.float32)
     return codes, scale
 
 

@@ -23,7 +23,7 @@ inline size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
 inline int elem_bytes(int dtype) { return dtype == TOPK_ATTN_F32 ? 4 : 2; }
 
 struct WsLayout {
-    size_t len, thr, samp, seg_cnt, seg_max, flags, hmax, fallback, cand, scores, sel_idx, sel_val, part_acc, part_l, part_m, total;
+    size_t len, thr, samp, seg_cnt, seg_max, flags, hmax, fallback, qscale, q8, cand, scores, sel_idx, sel_val, part_acc, part_l, part_m, total;
     int cand_cap, n_chunk_cap;
 };
 
@@ -32,7 +32,8 @@ bool config_ok(const topk_attn_config* c, int* why) {
     if (!c || c->struct_size != sizeof(topk_attn_config)) return false;
     if (c->n_layers < 1 || c->n_seqs < 1 || c->n_q_heads < 1 || c->n_kv_heads < 1) return false;
     if (c->max_tokens < 1 || c->max_k < 1 || c->device < 0 || c->max_window < 0) return false;
-    if (c->max_queries < 0 || c->max_queries > 4096 || c->reserved != 0) return false;
+    if (c->max_queries < 0 || c->max_queries > 4096) return false;
+    if (c->index_kind != TOPK_ATTN_INDEX_NONE && c->index_kind != TOPK_ATTN_INDEX_INT8) return false;
     if ((int64_t)c->n_seqs * (c->max_queries > 1 ? c->max_queries : 1) > 65535) return false;   // a grid dimension
     if (c->max_tokens > (int64_t)0x7FFFFF00) return false;   // positions are int32
     if (c->n_seqs > 65535 || c->n_kv_heads > 65535) return false;
@@ -41,6 +42,9 @@ bool config_ok(const topk_attn_config* c, int* why) {
     if (c->head_dim != 32 && c->head_dim != 64 && c->head_dim != 128 && c->head_dim != 256) return false;
     if (c->n_q_heads % c->n_kv_heads) return false;
     if (c->n_q_heads / c->n_kv_heads > 16) return false;
+    if (c->index_kind == TOPK_ATTN_INDEX_INT8 &&
+        !index8_supported(c->dtype, c->head_dim, c->n_q_heads / c->n_kv_heads))
+        return false;
     *why = TOPK_ATTN_OK;
     return true;
 }
@@ -48,6 +52,19 @@ bool config_ok(const topk_attn_config* c, int* why) {
 size_t kv_half_bytes(const topk_attn_config* c) {
     return align_up((size_t)c->n_layers * c->n_seqs * c->n_kv_heads * (size_t)c->max_tokens * c->head_dim *
                     elem_bytes(c->dtype));
+}
+
+// int8 index behind K and V: codes, then scales
+size_t index_codes_bytes(const topk_attn_config* c) {
+    if (c->index_kind != TOPK_ATTN_INDEX_INT8) return 0;
+    return align_up((size_t)c->n_layers * c->n_seqs * c->n_kv_heads * (size_t)c->max_tokens * c->head_dim);
+}
+size_t index_scales_bytes(const topk_attn_config* c) {
+    if (c->index_kind != TOPK_ATTN_INDEX_INT8) return 0;
+    return align_up((size_t)c->n_layers * c->n_seqs * c->n_kv_heads * (size_t)c->max_tokens * sizeof(float));
+}
+size_t kv_total_bytes(const topk_attn_config* c) {
+    return 2 * kv_half_bytes(c) + index_codes_bytes(c) + index_scales_bytes(c);
 }
 
 WsLayout ws_layout(const topk_attn_config* c) {
@@ -67,6 +84,8 @@ WsLayout ws_layout(const topk_attn_config* c) {
     w.flags = take(BH * sizeof(uint32_t));
     w.hmax = take(BH * sizeof(float));
     w.fallback = take(sizeof(uint32_t));
+    w.qscale = take(BH * sizeof(float));
+    w.q8 = take(BH * (size_t)c->head_dim);
     w.cand = take(BH * (size_t)w.cand_cap * sizeof(uint64_t));
     w.scores = take(BH * (size_t)c->max_tokens * sizeof(float));
     w.sel_idx = take(BH * (size_t)c->max_k * sizeof(int32_t));   // stride is the requested k, up to max_k
@@ -138,7 +157,7 @@ extern "C" {
 size_t topk_attn_kv_bytes(const topk_attn_config* cfg) {
     int why;
     if (!config_ok(cfg, &why)) return 0;
-    return 2 * kv_half_bytes(cfg);
+    return kv_total_bytes(cfg);
 }
 
 size_t topk_attn_workspace_bytes(const topk_attn_config* cfg) {
@@ -155,7 +174,7 @@ int topk_attn_create(const topk_attn_config* cfg, topk_attn_t** out) {
     if (!cfg->kv_storage || !cfg->workspace) return TOPK_ATTN_EINVAL;
     if (((uintptr_t)cfg->kv_storage | (uintptr_t)cfg->workspace) & (kAlign - 1)) return TOPK_ATTN_EINVAL;
     WsLayout w = ws_layout(cfg);
-    if (cfg->kv_bytes < 2 * kv_half_bytes(cfg) || cfg->workspace_bytes < w.total) return TOPK_ATTN_ENOMEM;
+    if (cfg->kv_bytes < kv_total_bytes(cfg) || cfg->workspace_bytes < w.total) return TOPK_ATTN_ENOMEM;
     topk_attn* h = new (std::nothrow) topk_attn;
     if (!h) return TOPK_ATTN_ENOMEM;
     h->cfg = *cfg;
@@ -192,7 +211,8 @@ int64_t topk_attn_length(const topk_attn_t* h, int layer, int seq) {
 }
 
 int topk_attn_set_path(topk_attn_t* h, int path) {
-    if (!h || path < TOPK_ATTN_PATH_AUTO || path > TOPK_ATTN_PATH_FILTER) return TOPK_ATTN_EINVAL;
+    if (!h || path < TOPK_ATTN_PATH_AUTO || path > TOPK_ATTN_PATH_INDEX) return TOPK_ATTN_EINVAL;
+    if (path == TOPK_ATTN_PATH_INDEX && h->cfg.index_kind != TOPK_ATTN_INDEX_INT8) return TOPK_ATTN_EINVAL;
     h->path = path;
     return TOPK_ATTN_OK;
 }
@@ -237,6 +257,15 @@ int topk_attn_append_kv(topk_attn_t* h, int layer, int seq, const void* k_new, c
                        c.n_kv_heads, chunks, token_stride * e, head_stride * e, head_b, len_dev,
                        (int32_t)(cur + n_new));
     if (hipGetLastError() != hipSuccess) return TOPK_ATTN_EDEVICE;
+    if (c.index_kind == TOPK_ATTN_INDEX_INT8) {   // code the rows just written (stream order: after the copy)
+        char* base = static_cast<char*>(c.kv_storage) + 2 * h->kv_half;
+        const int64_t row0 = (int64_t)slot * c.n_kv_heads * c.max_tokens + cur;
+        int8_t* codes = reinterpret_cast<int8_t*>(base) + row0 * c.head_dim;
+        float* scales = reinterpret_cast<float*>(base + index_codes_bytes(&c)) + row0;
+        if (launch_quantize_rows(c.dtype, c.head_dim, kdst, n_new, head_b, c.n_kv_heads, codes, scales, c.max_tokens,
+                                 (hipStream_t)hip_stream) != hipSuccess)
+            return TOPK_ATTN_EDEVICE;
+    }
     h->len[slot] = cur + n_new;
     return TOPK_ATTN_OK;
 }
@@ -251,11 +280,21 @@ static void fill_call(topk_attn_t* h, int layer, const void* q, int k, int n_que
     s->D = c.head_dim; s->dtype = c.dtype; s->k = k; s->window = 0; s->max_k = c.max_k;
     s->cand_cap = h->ws.cand_cap; s->n_seg = 4; s->seg_cap = h->ws.cand_cap / 4; s->samp_cap = kSampMax; s->n_chunk_cap = h->ws.n_chunk_cap;
     s->Ncap = c.max_tokens;
+    s->indexed = 0;
     char* ws = static_cast<char*>(c.workspace);
     const size_t layer_b = (size_t)c.n_seqs * c.n_kv_heads * (size_t)c.max_tokens * c.head_dim * e;
     b->K = static_cast<char*>(c.kv_storage) + (size_t)layer * layer_b;
     b->V = static_cast<char*>(c.kv_storage) + h->kv_half + (size_t)layer * layer_b;
     b->q = q;
+    b->K8 = nullptr; b->Kscale = nullptr;
+    if (c.index_kind == TOPK_ATTN_INDEX_INT8) {
+        const char* base = static_cast<const char*>(c.kv_storage) + 2 * h->kv_half;
+        const size_t layer_rows = (size_t)layer * c.n_seqs * c.n_kv_heads * (size_t)c.max_tokens;
+        b->K8 = reinterpret_cast<const int8_t*>(base) + layer_rows * c.head_dim;
+        b->Kscale = reinterpret_cast<const float*>(base + index_codes_bytes(&c)) + layer_rows;
+    }
+    b->q8 = reinterpret_cast<int8_t*>(ws + h->ws.q8);
+    b->qscale = reinterpret_cast<float*>(ws + h->ws.qscale);
     b->len = reinterpret_cast<int32_t*>(ws + h->ws.len) + (size_t)layer * c.n_seqs;
     b->thr = reinterpret_cast<float*>(ws + h->ws.thr);
     b->samp = reinterpret_cast<float*>(ws + h->ws.samp);
@@ -340,6 +379,9 @@ static int decode_impl(topk_attn_t* h, int layer, const void* q, int n_queries, 
     if (idx) b.sel_idx = idx;
     if (vals) b.sel_val = vals;
 
+    // the int8 index serves one query per sequence with the grouped scan layout
+    const bool want_index = h->path == TOPK_ATTN_PATH_INDEX && n_queries == 1 && s.G <= 4;
+    s.indexed = want_index ? 1 : 0;
     bool fast = false;
     if (h->path != TOPK_ATTN_PATH_FULL && scan_mfma_supported(s) && nmax > 0) {
         fast = true;
@@ -348,15 +390,27 @@ static int decode_impl(topk_attn_t* h, int layer, const void* q, int n_queries, 
             const int64_t n = prefix_len(h->len[(size_t)layer * s.Bc + i], window);
             if (n == 0) continue;            // this sequence lies entirely inside its window
             const int ke = k < n ? k : (int)n;
-            const Plan pl = make_plan(n, ke);
+            const Plan pl = make_plan(n, ke, s.indexed);
             fast = plan_is_fast(pl, n, s.cand_cap, h->path == TOPK_ATTN_PATH_FILTER);
             c_hi = pl.c_hi > c_hi ? pl.c_hi : c_hi;
         }
         if (fast) fast = choose_segments(h, s, nmax, c_hi, &s.n_seg, &s.seg_cap);
     }
+    if (!fast) s.indexed = 0;      // no filtered scan: exact path
     hipError_t e = hipSuccess;
     const bool timed = h->timing && h->ev_used < kTimingSlots;
-    if (fast) {
+    if (fast && s.indexed) {
+        e = launch_quantize_rows(s.dtype, s.D, q, (int64_t)s.B * s.Hq, 0, 1, b.q8, b.qscale, 0, st);
+        if (e == hipSuccess) e = launch_scan8_sample(s, b, nmax, st);
+        if (e == hipSuccess) e = launch_threshold(s, b, st);
+        if (e == hipSuccess && timed) e = hipEventRecord(h->ev[2 * h->ev_used], st);
+        if (e == hipSuccess) e = launch_scan8_filter(s, b, st);
+        if (e == hipSuccess && timed) e = hipEventRecord(h->ev[2 * h->ev_used + 1], st);
+        if (e == hipSuccess && timed) h->ev_used++;
+        if (e == hipSuccess) e = launch_rerank(s, b, st);
+        if (e == hipSuccess) e = launch_select_candidates(s, b, st);
+        if (e == hipSuccess) e = launch_select_full(s, b, true, st);
+    } else if (fast) {
         e = launch_scan_sample(s, b, nmax, st);
         if (e == hipSuccess) e = launch_threshold(s, b, st);
         if (e == hipSuccess && timed) e = hipEventRecord(h->ev[2 * h->ev_used], st);
@@ -461,7 +515,13 @@ int topk_attn_scores(topk_attn_t* h, int layer, const void* q, float* scores, vo
     if (lengths_of(h, layer, 0, 1, &nmin, &nmax) != TOPK_ATTN_OK) return TOPK_ATTN_EINVAL;
     Shape s; Bufs b;
     fill_call(h, layer, q, 1, 1, &s, &b);
-    hipError_t e = launch_scan_full(s, b, nmax, scores, (hipStream_t)hip_stream);
+    hipError_t e;
+    if (h->path == TOPK_ATTN_PATH_INDEX && s.G <= 4) {   // approximate scores from the codes
+        e = launch_quantize_rows(s.dtype, s.D, q, (int64_t)s.B * s.Hq, 0, 1, b.q8, b.qscale, 0, (hipStream_t)hip_stream);
+        if (e == hipSuccess) e = launch_scan8_full(s, b, nmax, scores, (hipStream_t)hip_stream);
+    } else {
+        e = launch_scan_full(s, b, nmax, scores, (hipStream_t)hip_stream);
+    }
     return e == hipSuccess ? TOPK_ATTN_OK : TOPK_ATTN_EDEVICE;
 }
 

@@ -27,6 +27,7 @@ struct Shape {
     int causal;       // query m of M sees only the first len - (M - 1 - m) tokens
     int q_per_blk;    // row-tile scan: queries per block of <= 16 (query, head) rows
     int n_qblk;       // row-tile scan: blocks per cache sequence
+    int indexed;      // the scan reads the int8 key index; candidates are re-scored exactly afterwards
     int k;            // requested k (k_eff = min(k, searched prefix of sequence b))
     int window;       // most recent tokens that are always attended and excluded from the search
     int max_k;
@@ -43,6 +44,10 @@ struct Bufs {
     const void* K;          // this layer's keys  [B][Hkv][Ncap][D]
     const void* V;          // this layer's values
     const void* q;          // [B][Hq][D]
+    const int8_t* K8;       // this layer's int8 key codes [Bc][Hkv][Ncap][D] (compressed index), or null
+    const float* Kscale;    // this layer's per-row code scales [Bc][Hkv][Ncap]
+    int8_t* q8;             // [B*Hq][D] query codes of this call
+    float* qscale;          // [B*Hq]
     const int32_t* len;     // [Bc] tokens cached per cache sequence (this layer)
     float* thr;             // [B*Hq] candidate threshold
     float* samp;            // [B*Hq][samp_cap]
@@ -90,7 +95,9 @@ struct Plan {
     int64_t c_hi;    // candidates expected at most (z-sigma above the mean)
 };
 
-__host__ __device__ inline Plan make_plan(int64_t N, int k_eff) {
+// `indexed`: the sample scores are approximate (int8 index); a quarter more samples are
+// expected above the threshold so that coding noise at the k-th score stays inside the list.
+__host__ __device__ inline Plan make_plan(int64_t N, int k_eff, int indexed = 0) {
     Plan p;
     int64_t ns = N / 64;
     if (ns > kSampMax) ns = kSampMax;
@@ -106,6 +113,7 @@ __host__ __device__ inline Plan make_plan(int64_t N, int k_eff) {
     // z-sigma event happens; the candidate list then holds about N r / n_samp entries.
     const double z = 6.0;
     double r0 = (double)k_eff * (double)ns / (double)N;
+    if (indexed) r0 = 1.25 * r0 + 4.0;
     double sr = 0.5 * (z + sqrt(z * z + 4.0 * r0));
     double r = sr * sr;
     p.rank = (int)r + 2;
@@ -138,5 +146,14 @@ hipError_t launch_select_candidates(const Shape& s, const Bufs& b, hipStream_t s
 hipError_t launch_select_full(const Shape& s, const Bufs& b, bool redo_flagged, hipStream_t st);
 
 hipError_t launch_gather(const Shape& s, const Bufs& b, hipStream_t st);
+
+// int8 key index
+bool index8_supported(int dtype, int D, int G);
+hipError_t launch_quantize_rows(int dtype, int D, const void* src, int64_t rows_per_head, int64_t src_head_stride_bytes,
+                                int n_heads, int8_t* dst, float* scale, int64_t dst_head_stride_rows, hipStream_t st);
+hipError_t launch_scan8_sample(const Shape& s, const Bufs& b, int64_t Nmax, hipStream_t st);
+hipError_t launch_scan8_filter(const Shape& s, const Bufs& b, hipStream_t st);
+hipError_t launch_scan8_full(const Shape& s, const Bufs& b, int64_t Nmax, float* dst, hipStream_t st);
+hipError_t launch_rerank(const Shape& s, const Bufs& b, hipStream_t st);
 
 }  // namespace tka

@@ -373,7 +373,7 @@ __global__ void __launch_bounds__(kSelThreads) threshold_kernel(Shape sh, Bufs b
     }
     // the sample was drawn by the plan of the cache sequence (shared by all its queries)
     const int64_t N = prefix_len(bf.len[cache_seq(sh, b)], sh.window);
-    const Plan pl = make_plan(N, sh.k < N ? sh.k : (int)N);
+    const Plan pl = make_plan(N, sh.k < N ? sh.k : (int)N, sh.indexed);
     const SrcDense src{bf.samp + bh * sh.samp_cap, (int64_t)pl.n_samp};
     const Items<(kSampMax + kSelThreads - 1) / kSelThreads, SrcDense> items(src);
     const int rank = pl.rank < pl.n_samp ? pl.rank : pl.n_samp;
@@ -439,9 +439,10 @@ __global__ void __launch_bounds__(kSelThreads) select_candidates_kernel(Shape sh
     }
     const SrcSeg src{bf.cand + bh * (int64_t)sh.cand_cap, sm.seg_len, pos_lds, 31 - __clz(sh.n_seg), (int)max_len};
     const Items<kCandSlots / kSelThreads, SrcSeg> items(src);
-    // every candidate is >= the head's threshold and the scan reported the largest score
-    const uint32_t kmax = wg_topk_emit(items, k_eff, sh.k, bf.sel_idx + bh * sh.k, bf.sel_val + bh * sh.k, sm, true,
-                                       score_key(bf.thr[bh]), kmx);
+    // every candidate is >= the head's threshold and the scan reported the largest score; not so
+    // after an index scan, whose candidates were re-scored since
+    const uint32_t kmax = wg_topk_emit(items, k_eff, sh.k, bf.sel_idx + bh * sh.k, bf.sel_val + bh * sh.k, sm,
+                                       !sh.indexed, score_key(bf.thr[bh]), kmx);
     if (tid == 0) bf.hmax[bh] = key_score(kmax);
 }
 

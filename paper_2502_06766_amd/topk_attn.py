@@ -17,7 +17,8 @@ LIB_PATH = os.environ.get("TOPK_ATTN_LIB") or os.path.join(_HERE, "libtopk_attn.
 
 OK, EINVAL, ECAPACITY, EUNSUPPORTED, EDEVICE, ENOMEM = range(6)
 F32, F16, BF16 = 0, 1, 2
-PATH_AUTO, PATH_FULL, PATH_FILTER = 0, 1, 2
+PATH_AUTO, PATH_FULL, PATH_FILTER, PATH_INDEX = 0, 1, 2, 3
+INDEX_NONE, INDEX_INT8 = 0, 1
 
 EXPORTS = [
     "topk_attn_kv_bytes", "topk_attn_workspace_bytes", "topk_attn_create", "topk_attn_append_kv",
@@ -41,7 +42,7 @@ class Config(ctypes.Structure):
         ("device", ctypes.c_int32),
         ("max_window", ctypes.c_int32),
         ("max_queries", ctypes.c_int32),
-        ("reserved", ctypes.c_int32),
+        ("index_kind", ctypes.c_int32),
         ("kv_storage", ctypes.c_void_p),
         ("kv_bytes", ctypes.c_size_t),
         ("workspace", ctypes.c_void_p),
@@ -120,9 +121,10 @@ def _check(code: int, where: str) -> None:
 
 
 def make_config(n_layers, n_seqs, n_q_heads, n_kv_heads, head_dim, max_tokens, max_k, dtype, device=0,
-                kv_storage=0, kv_bytes=0, workspace=0, workspace_bytes=0, max_window=0, max_queries=0) -> Config:
+                kv_storage=0, kv_bytes=0, workspace=0, workspace_bytes=0, max_window=0, max_queries=0,
+                index_kind=0) -> Config:
     return Config(ctypes.sizeof(Config), n_layers, n_seqs, n_q_heads, n_kv_heads, head_dim, max_tokens,
-                  max_k, dtype, device, max_window, max_queries, 0, kv_storage, kv_bytes, workspace,
+                  max_k, dtype, device, max_window, max_queries, index_kind, kv_storage, kv_bytes, workspace,
                   workspace_bytes)
 
 
@@ -229,14 +231,14 @@ class TopkAttnCache:
     """Allocates kv_storage/workspace as torch tensors and wraps the handle."""
 
     def __init__(self, n_layers, n_seqs, n_q_heads, n_kv_heads, head_dim, max_tokens, max_k, dtype, device=0,
-                 max_window=0, max_queries=0):
+                 max_window=0, max_queries=0, index_kind=0):
         import torch
         self.torch = torch
         self.shape = (n_layers, n_seqs, n_q_heads, n_kv_heads, head_dim, max_tokens, max_k, dtype)
         self.dtype = dtype
         self.device = torch.device("cuda", device)
         cfg = make_config(n_layers, n_seqs, n_q_heads, n_kv_heads, head_dim, max_tokens, max_k, dtype, device,
-                          max_window=max_window, max_queries=max_queries)
+                          max_window=max_window, max_queries=max_queries, index_kind=index_kind)
         kvb, wsb = topk_attn_kv_bytes(cfg), topk_attn_workspace_bytes(cfg)
         if kvb == 0 or wsb == 0:
             h = ctypes.c_void_p()

@@ -77,8 +77,24 @@ def test_workspace_grows_with_max_queries():
     assert same == one
     assert 3.9 * one < four <= 4 * one
     cfg = ta.make_config(1, 1, 4, 2, 64, 128, 8, ta.F32)
-    cfg.reserved = 1
+    cfg.index_kind = 7
     assert ta.topk_attn_workspace_bytes(cfg) == 0
+
+
+def test_int8_index_storage_and_supported_shapes():
+    base = dict(n_layers=2, n_seqs=3, n_q_heads=8, n_kv_heads=2, head_dim=128, max_tokens=1000, max_k=64)
+    plain = ta.topk_attn_kv_bytes(ta.make_config(dtype=ta.F16, **base))
+    with_index = ta.topk_attn_kv_bytes(ta.make_config(dtype=ta.F16, index_kind=ta.INDEX_INT8, **base))
+    rows = 2 * 3 * 2 * 1000
+    up = lambda x: (x + 255) // 256 * 256
+    assert plain == 2 * up(rows * 128 * 2)
+    assert with_index == plain + up(rows * 128) + up(rows * 4)        # codes, then one fp32 scale per row
+    # fp32 caches, head_dim 256 and head groups above 4 have no int8 index
+    for kw in (dict(dtype=ta.F32), dict(dtype=ta.F16, head_dim=256), dict(dtype=ta.F16, n_q_heads=16)):
+        cfg = ta.make_config(**{**base, **kw, "index_kind": ta.INDEX_INT8})
+        assert ta.topk_attn_kv_bytes(cfg) == 0
+        h = ctypes.c_void_p()
+        assert ta.lib().topk_attn_create(ctypes.byref(cfg), ctypes.byref(h)) == ta.EUNSUPPORTED
 
 
 def test_create_rejects_null_storage_and_wrong_struct_size():

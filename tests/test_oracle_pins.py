@@ -479,18 +479,22 @@ def test_int8_codes_reconstruct_within_half_a_step():
     g = np.random.default_rng(400)
     x = (g.standard_normal((300, 128)) * g.uniform(0.01, 30.0, (300, 1))).astype(np.float32)
     x[7] = 0.0                                   # an all-zero row
-    x[8, 5] = 1e-30                              # a row whose largest element is tiny
+    x[8] = 0.0
+    x[8, 5] = 1e-29                              # a row whose largest element is tiny but above the floor
+    x[9] = 1e-38                                 # a row below the coding floor of 2^-100: coded as zero
     codes, scale = i8.quantize_rows_int8(x)
     assert codes.dtype == np.int8 and scale.dtype == np.float32
     assert np.abs(codes.astype(np.int32)).max() <= 127
     err = np.abs(x.astype(np.float64) - codes.astype(np.float64) * scale[:, None].astype(np.float64))
-    assert (err <= 0.5 * scale[:, None].astype(np.float64) * (1 + 1e-5) + 1e-45).all()
+    assert (err <= 0.5 * scale[:, None].astype(np.float64) * (1 + 1e-5) + 2.0 ** -100).all()   # floor: rows coded as zero
     # the largest element of every non-zero row is coded +-127, a zero row is all zeros with scale 0
     for r in range(300):
         j = np.abs(x[r]).argmax()
-        if x[r, j] != 0:
+        if abs(x[r, j]) >= 2.0 ** -100:
             assert abs(int(codes[r, j])) == 127 and np.sign(codes[r, j]) == np.sign(x[r, j])
     assert (codes[7] == 0).all() and scale[7] == 0
+    assert (codes[9] == 0).all() and scale[9] == 0
+    assert codes[8, 5] == 127 and (np.delete(codes[8], 5) == 0).all() and scale[8] > 0
     # odd symmetry and monotonicity within a row
     c2, s2 = i8.quantize_rows_int8(-x)
     assert np.array_equal(c2, -codes) and np.array_equal(s2, scale)
