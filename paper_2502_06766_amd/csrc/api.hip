@@ -117,6 +117,12 @@ __global__ void append_kernel(const char* __restrict__ ksrc, const char* __restr
 }
 
 __global__ void set_len_kernel(int32_t* len_slot, int32_t v) { *len_slot = v; }
+#ifdef TKA_DEBUG_NO_CAND
+__global__ void debug_raise_thr_kernel(float* thr, int n) {
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) thr[i] = INFINITY;
+}
+#endif
 
 __global__ void __launch_bounds__(256) read_probe_kernel(const u32x4* __restrict__ src, size_t n_vec, uint32_t* sink) {
     uint32_t acc = 0;
@@ -278,7 +284,7 @@ static void fill_call(topk_attn_t* h, int layer, const void* q, int k, int n_que
     s->q_per_blk = 16 / s->G < n_queries ? 16 / s->G : n_queries;     // G <= 16
     s->n_qblk = (n_queries + s->q_per_blk - 1) / s->q_per_blk;
     s->D = c.head_dim; s->dtype = c.dtype; s->k = k; s->window = 0; s->max_k = c.max_k;
-    s->cand_cap = h->ws.cand_cap; s->n_seg = 4; s->seg_cap = h->ws.cand_cap / 4; s->samp_cap = kSampMax; s->n_chunk_cap = h->ws.n_chunk_cap;
+    s->cand_cap = h->ws.cand_cap; s->n_seg = 4; s->seg_cap = (h->ws.cand_cap / 4) & ~(kCandChunk - 1); s->samp_cap = kSampMax; s->n_chunk_cap = h->ws.n_chunk_cap;
     s->Ncap = c.max_tokens;
     s->indexed = 0;
     char* ws = static_cast<char*>(c.workspace);
@@ -329,7 +335,7 @@ static bool choose_segments(const topk_attn_t* h, const Shape& s, int64_t nmax, 
     while (P & (P - 1)) P &= P - 1;          // power of two: the selection indexes segments by mask
     for (; P >= 1; P /= 2) {
         const int64_t ns = P * 4;
-        const int64_t cap = s.cand_cap / ns;
+        const int64_t cap = (s.cand_cap / ns) & ~(int64_t)(kCandChunk - 1);
         const double mean = (double)c_hi / (double)ns;
         if ((double)cap >= mean + 8.0 * sqrt(mean) + 32.0) {
             *n_seg = (int)ns;
@@ -413,6 +419,9 @@ static int decode_impl(topk_attn_t* h, int layer, const void* q, int n_queries, 
     } else if (fast) {
         e = launch_scan_sample(s, b, nmax, st);
         if (e == hipSuccess) e = launch_threshold(s, b, st);
+#ifdef TKA_DEBUG_NO_CAND
+        hipLaunchKernelGGL(debug_raise_thr_kernel, dim3((s.B * s.Hq + 255) / 256), dim3(256), 0, st, b.thr, s.B * s.Hq);
+#endif
         if (e == hipSuccess && timed) e = hipEventRecord(h->ev[2 * h->ev_used], st);
         if (e == hipSuccess) e = launch_scan_filter(s, b, nmax, st);
         if (e == hipSuccess && timed) e = hipEventRecord(h->ev[2 * h->ev_used + 1], st);

@@ -143,19 +143,31 @@ __device__ __forceinline__ i32x4 tile_mac8(const i32x4 (&b)[4][D / 64], const i3
 
 struct CandStage8 {
     uint64_t* lds;
-    uint64_t* seg;
+    uint64_t* list;     // the head's candidate list
+    int sid;            // this wave's segment
     int n_lds, n_glob;
 };
 
-__device__ __forceinline__ void stage_flush8(CandStage8& c, int seg_cap, int n_seg) {
+// Appends the staged entries up to the last whole run of kCandChunk (all of them when
+// `final`): whole 128-byte lines; the remainder moves to the front of the stage.
+__device__ __forceinline__ void stage_flush8(CandStage8& c, int seg_cap, int n_seg, bool final = false) {
+    static_assert(kCandChunk <= kWave && kStage >= kWave + kCandChunk, "stage too small for an aligned flush");
     wave_sync();
-    for (int i = lane_id(); i < c.n_lds; i += kWave) {
+    const int total = c.n_glob + c.n_lds;
+    const int f = (final ? total : (total & ~(kCandChunk - 1))) - c.n_glob;
+    for (int i = lane_id(); i < f; i += kWave) {
         const int slot = c.n_glob + i;
-        if (slot < seg_cap) c.seg[(int64_t)slot * n_seg] = c.lds[i];
+        if (slot < seg_cap) c.list[cand_slot(slot, c.sid, n_seg)] = c.lds[i];
+    }
+    const int r = f > 0 ? c.n_lds - f : c.n_lds;
+    if (f > 0) {
+        const uint64_t keep = lane_id() < r ? c.lds[f + lane_id()] : 0;
+        wave_sync();
+        if (lane_id() < r) c.lds[lane_id()] = keep;
+        c.n_glob += f;
     }
     wave_sync();
-    c.n_glob += c.n_lds;
-    c.n_lds = 0;
+    c.n_lds = r;
 }
 
 __device__ __forceinline__ void filter_head8(float score, float thr, CandStage8& c, bool valid, int64_t item,
@@ -225,12 +237,12 @@ scan8_kernel(Shape sh, Bufs bf, int tiles_per_wave, float* dst) {
 
     const int seg_cap = sh.seg_cap;
     const int sid = (int)blockIdx.x * kScanWaves + wave;
-    uint64_t* const seg0 = bf.cand + head0 * (int64_t)sh.cand_cap + sid;
+    uint64_t* const list0 = bf.cand + head0 * (int64_t)sh.cand_cap;
     __shared__ uint64_t stage_lds[MODE == MODE_FILTER ? kScanWaves * 4 * kStage : 1];
     uint64_t* const st0 = stage_lds + (MODE == MODE_FILTER ? wave * 4 * kStage : 0);
-    CandStage8 cs0{st0, seg0, 0, 0}, cs1{st0 + kStage, seg0 + (int64_t)sh.cand_cap, 0, 0},
-        cs2{st0 + 2 * kStage, seg0 + 2 * (int64_t)sh.cand_cap, 0, 0},
-        cs3{st0 + 3 * kStage, seg0 + 3 * (int64_t)sh.cand_cap, 0, 0};
+    CandStage8 cs0{st0, list0, sid, 0, 0}, cs1{st0 + kStage, list0 + (int64_t)sh.cand_cap, sid, 0, 0},
+        cs2{st0 + 2 * kStage, list0 + 2 * (int64_t)sh.cand_cap, sid, 0, 0},
+        cs3{st0 + 3 * kStage, list0 + 3 * (int64_t)sh.cand_cap, sid, 0, 0};
     float thr0 = 0.f, thr1 = 0.f, thr2 = 0.f, thr3 = 0.f;
     if (MODE == MODE_FILTER) {
         thr0 = bf.thr[head0];
@@ -290,10 +302,10 @@ scan8_kernel(Shape sh, Bufs bf, int tiles_per_wave, float* dst) {
         }
     }
     if (MODE == MODE_FILTER) {
-        stage_flush8(cs0, seg_cap, sh.n_seg);
-        if (1 < G) stage_flush8(cs1, seg_cap, sh.n_seg);
-        if (2 < G) stage_flush8(cs2, seg_cap, sh.n_seg);
-        if (3 < G) stage_flush8(cs3, seg_cap, sh.n_seg);
+        stage_flush8(cs0, seg_cap, sh.n_seg, true);
+        if (1 < G) stage_flush8(cs1, seg_cap, sh.n_seg, true);
+        if (2 < G) stage_flush8(cs2, seg_cap, sh.n_seg, true);
+        if (3 < G) stage_flush8(cs3, seg_cap, sh.n_seg, true);
         if (lane == 0) {
             uint32_t* sc = bf.seg_cnt + head0 * (int64_t)sh.n_seg + sid;
             sc[0] = (uint32_t)cs0.n_glob;
@@ -343,8 +355,8 @@ hipError_t launch_scan8_full(const Shape& s, const Bufs& b, int64_t Nmax, float*
 
 // ---------------------------------------------------------------------------------------
 // Exact refinement: the score of every candidate the index scan kept is replaced by the
-// fp32 dot product of the query with the 16-bit key row.  Slot s of a head's interleaved
-// list is entry s / n_seg of segment s % n_seg; a workgroup takes 256 consecutive slots,
+// fp32 dot product of the query with the 16-bit key row.  A workgroup takes 256 consecutive
+// slots of a head's candidate list,
 // D / 8 lanes per candidate.
 // ---------------------------------------------------------------------------------------
 template <int DT>
@@ -361,9 +373,9 @@ __global__ void __launch_bounds__(256) rerank_kernel(Shape sh, Bufs bf) {
     const int64_t slot0 = (int64_t)blockIdx.x * 256;
     const uint32_t* cnt = bf.seg_cnt + bh * sh.n_seg;
     auto valid_slot = [&](int64_t s) {
-        uint32_t have = cnt[s & (sh.n_seg - 1)];
+        uint32_t have = cnt[cand_slot_segment(s, log2_seg)];
         if (have > (uint32_t)sh.seg_cap) have = (uint32_t)sh.seg_cap;
-        return (uint32_t)(s >> log2_seg) < have;
+        return (uint32_t)cand_slot_entry(s, log2_seg) < have;
     };
     // most blocks lie beyond the filled part of the list
     if (!__syncthreads_or(valid_slot(slot0 + threadIdx.x) ? 1 : 0)) return;

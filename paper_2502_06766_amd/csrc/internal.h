@@ -33,7 +33,7 @@ struct Shape {
     int max_k;
     int cand_cap;     // entries per (b, head) candidate list
     int n_seg;        // segments the candidate list is split in (one per scanning wave), power of 2
-    int seg_cap;      // entries per segment (n_seg * seg_cap <= cand_cap)
+    int seg_cap;      // entries per segment (n_seg * seg_cap <= cand_cap), a multiple of kCandChunk
     int samp_cap;     // entries per (b, head) sample-score row
     int n_chunk_cap;  // partial-sum slots per (b, head)
     int64_t Ncap;     // row capacity per (layer, seq, kv head)
@@ -56,7 +56,7 @@ struct Bufs {
     uint32_t* flags;        // [B*Hq] 1 = candidate list unusable, use the full path
     float* hmax;            // [B*Hq] largest selected score
     uint64_t* cand;         // [B*Hq][cand_cap] (score bits << 32 | position); entry e of segment g
-                            // at [e * n_seg + g]
+                            // at [cand_slot(e, g, n_seg)]
     float* scores;          // [B*Hq][Ncap] full score buffer
     int32_t* sel_idx;       // [B*Hq][k]
     float* sel_val;         // [B*Hq][k]
@@ -80,6 +80,27 @@ __device__ inline int64_t visible_len(const Shape& sh, const Bufs& bf, int b) {
     if (sh.M == 1) return bf.len[b];
     const int c = b / sh.M;
     return (int64_t)bf.len[c] - (sh.causal ? sh.M - 1 - (b - c * sh.M) : 0);
+}
+
+// Candidate list of one head: n_seg segments (one per scanning wave).  Runs of kCandChunk
+// consecutive entries of a segment are contiguous (a wave's flush writes whole 128-byte
+// pieces), and the runs of the segments interleave, so that the filled part of the list is
+// dense at its start whatever the fill of the single segments.
+#ifndef TKA_CAND_CHUNK_LOG2
+#define TKA_CAND_CHUNK_LOG2 4
+#endif
+constexpr int kCandChunkLog2 = TKA_CAND_CHUNK_LOG2;
+constexpr int kCandChunk = 1 << kCandChunkLog2;
+// slot of entry e of segment g
+__host__ __device__ inline int64_t cand_slot(int64_t e, int g, int n_seg) {
+    return ((((e >> kCandChunkLog2) * n_seg) + g) << kCandChunkLog2) | (e & (kCandChunk - 1));
+}
+// segment and entry of slot i (n_seg = 1 << log2_n_seg)
+__host__ __device__ inline int cand_slot_segment(int64_t i, int log2_n_seg) {
+    return (int)((i >> kCandChunkLog2) & ((1 << log2_n_seg) - 1));
+}
+__host__ __device__ inline int64_t cand_slot_entry(int64_t i, int log2_n_seg) {
+    return (((i >> kCandChunkLog2) >> log2_n_seg) << kCandChunkLog2) | (i & (kCandChunk - 1));
 }
 
 // Tokens of a sequence the search runs over: everything but the always-attended window.

@@ -36,7 +36,10 @@ template <> struct Mfma<DT_BF16> {
 };
 
 #ifndef TKA_SCAN_PIPELINE
-#define TKA_SCAN_PIPELINE 1   // 1: loads of tile t+1 overlap the MFMAs of tile t within a wave
+#define TKA_SCAN_PIPELINE 1   // 1: loads of tile t+1 are issued before the MFMAs of tile t; 0: no prefetch
+#endif
+#ifndef TKA_SCAN_SADDR
+#define TKA_SCAN_SADDR 1      // 1: whole tiles are addressed as wave-uniform base + per-lane 32-bit offset
 #endif
 
 enum { MODE_SAMPLE = 0, MODE_FILTER = 1, MODE_FULL = 2 };
@@ -77,6 +80,65 @@ __device__ __forceinline__ void tile_load(const char* Kh, RowFn rowfn, typename 
     }
 }
 
+// The same for a tile whose 64 rows all exist, through buffer loads: the tile's address
+// (wave-uniform) sits in a scalar buffer descriptor, the 16-row sub-tile is a scalar offset
+// and lane_off = (n * D + 8 j) * 2 the lane's loop-invariant byte offset, so the loop holds
+// no per-lane address arithmetic at all.  (With per-lane 64-bit addresses the compiler
+// builds them in registers of the buffer it is about to refill and then waits for every
+// outstanding load before it may overwrite them, which serialises every other prefetch.)
+template <int DT, int D>
+__device__ __forceinline__ void tile_load_full(const char* tile_base, uint32_t lane_off,
+                                               typename Mfma<DT>::v8 (&b)[4][D / 32]) {
+    using v8 = typename Mfma<DT>::v8;
+    constexpr int KS = D / 32;
+    // raw buffer (stride 0), 64 * D * 2 bytes long, 32-bit data format
+    const __amdgpu_buffer_rsrc_t rsrc =
+        __builtin_amdgcn_make_buffer_rsrc(const_cast<char*>(tile_base), 0, 64 * D * 2, 0x00020000);
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+#pragma unroll
+        for (int s = 0; s < KS; ++s) {
+            const u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(rsrc, (int)lane_off + 64 * s, g * 16 * D * 2, 0);
+            b[g][s] = __builtin_bit_cast(v8, v);
+        }
+    }
+}
+
+// A wave's walk over the tiles tile, tile + step, ... < end with two register buffers: the
+// next tile's loads are in flight while the current one is multiplied and filtered.  The
+// prefetch is unconditional (past the end it re-reads a tile the wave already had, a cache
+// hit) so that the wait before the MFMAs only covers the tile they consume.  Returns the
+// first tile of the sequence at or past `end`.
+template <class Buf, class Load, class Use>
+__device__ __forceinline__ int64_t walk_tiles(int64_t tile, int64_t end, int64_t step, Buf& ba, Buf& bb, Load load,
+                                              Use use) {
+#if TKA_SCAN_PIPELINE
+    if (tile < end) {
+        load(ba, tile);
+        while (true) {
+            const int64_t t1 = tile + step;
+            load(bb, t1 < end ? t1 : tile);
+            __builtin_amdgcn_sched_barrier(0);
+            use(ba, tile);
+            if (t1 >= end) { tile = t1; break; }
+            const int64_t t2 = t1 + step;
+            load(ba, t2 < end ? t2 : t1);
+            __builtin_amdgcn_sched_barrier(0);
+            use(bb, t1);
+            if (t2 >= end) { tile = t2; break; }
+            tile = t2;
+        }
+    }
+#else
+    for (; tile < end; tile += step) {
+        load(ba, tile);
+        __builtin_amdgcn_sched_barrier(0);
+        use(ba, tile);
+    }
+#endif
+    return tile;
+}
+
 // Scores of the tile: lane l gets res[r] = q_{head0 + r} . K[row(l)].
 template <int DT, int D>
 __device__ __forceinline__ f32x4 tile_mac(const typename Mfma<DT>::v8 (&b)[4][D / 32],
@@ -108,20 +170,33 @@ constexpr int kStage = 128;   // LDS staging slots per (wave, head)
 // the key loads in the wave's in-order memory queue and stall the prefetch.
 struct CandStage {
     uint64_t* lds;      // kStage slots
-    uint64_t* seg;      // this wave's entry 0 in the head's interleaved list (entry e at seg[e * n_seg])
+    uint64_t* list;     // the head's candidate list (entry e of this wave at list[cand_slot(e, sid, n_seg)])
+    int sid;            // this wave's segment
     int n_lds;          // staged entries (wave-uniform)
     int n_glob;         // entries already appended, may run past seg_cap (overflow is detected later)
 };
 
-__device__ __forceinline__ void stage_flush(CandStage& c, int seg_cap, int n_seg) {
+// Appends the staged entries up to the last whole run of kCandChunk (all of them when
+// `final`), so that every store but the last covers whole 128-byte lines; the remainder
+// (fewer than kCandChunk entries) moves to the front of the stage.
+__device__ __forceinline__ void stage_flush(CandStage& c, int seg_cap, int n_seg, bool final = false) {
+    static_assert(kCandChunk <= kWave && kStage >= kWave + kCandChunk, "stage too small for an aligned flush");
     wave_sync();
-    for (int i = lane_id(); i < c.n_lds; i += kWave) {
+    const int total = c.n_glob + c.n_lds;
+    const int f = (final ? total : (total & ~(kCandChunk - 1))) - c.n_glob;     // entries to append now
+    for (int i = lane_id(); i < f; i += kWave) {
         const int slot = c.n_glob + i;
-        if (slot < seg_cap) c.seg[(int64_t)slot * n_seg] = c.lds[i];
+        if (slot < seg_cap) c.list[cand_slot(slot, c.sid, n_seg)] = c.lds[i];
+    }
+    const int r = f > 0 ? c.n_lds - f : c.n_lds;
+    if (f > 0) {
+        const uint64_t keep = lane_id() < r ? c.lds[f + lane_id()] : 0;
+        wave_sync();
+        if (lane_id() < r) c.lds[lane_id()] = keep;
+        c.n_glob += f;
     }
     wave_sync();
-    c.n_glob += c.n_lds;
-    c.n_lds = 0;
+    c.n_lds = r;
 }
 
 // Keep the keys of one head whose score reaches the head's threshold.
@@ -183,12 +258,12 @@ scan_mfma_kernel(Shape sh, Bufs bf, int tiles_per_wave, float* dst) {
     // filter: this wave's segment in each head's candidate list
     const int seg_cap = sh.seg_cap;
     const int sid = (int)blockIdx.x * kScanWaves + wave;
-    uint64_t* const seg0 = bf.cand + head0 * (int64_t)sh.cand_cap + sid;
+    uint64_t* const list0 = bf.cand + head0 * (int64_t)sh.cand_cap;
     __shared__ uint64_t stage_lds[MODE == MODE_FILTER ? kScanWaves * 4 * kStage : 1];
     uint64_t* const st0 = stage_lds + (MODE == MODE_FILTER ? wave * 4 * kStage : 0);
-    CandStage cs0{st0, seg0, 0, 0}, cs1{st0 + kStage, seg0 + (int64_t)sh.cand_cap, 0, 0},
-        cs2{st0 + 2 * kStage, seg0 + 2 * (int64_t)sh.cand_cap, 0, 0},
-        cs3{st0 + 3 * kStage, seg0 + 3 * (int64_t)sh.cand_cap, 0, 0};
+    CandStage cs0{st0, list0, sid, 0, 0}, cs1{st0 + kStage, list0 + (int64_t)sh.cand_cap, sid, 0, 0},
+        cs2{st0 + 2 * kStage, list0 + 2 * (int64_t)sh.cand_cap, sid, 0, 0},
+        cs3{st0 + 3 * kStage, list0 + 3 * (int64_t)sh.cand_cap, sid, 0, 0};
     float thr0 = 0.f, thr1 = 0.f, thr2 = 0.f, thr3 = 0.f;
     float top0 = -INFINITY, top1 = -INFINITY, top2 = -INFINITY, top3 = -INFINITY;   // largest score seen per head
     if (MODE == MODE_FILTER) {
@@ -230,42 +305,27 @@ scan_mfma_kernel(Shape sh, Bufs bf, int tiles_per_wave, float* dst) {
         }
     };
 
-    // The next tile's loads are in flight while the current one is multiplied and filtered.
-    // The prefetch is unconditional (past the end it re-reads the current tile, a cache hit)
-    // so that the wait before the MFMAs only covers the tile they consume.
-#if TKA_SCAN_PIPELINE
-    v8 ba[4][D / 32], bb[4][D / 32];
-    if (tile < tile_end) {
-        tile_load<DT, D>(Kh, [&](int slot) { return row_of(tile * 64, slot); }, ba);
-        while (true) {
-            const int64_t t1 = tile + tile_step;
-            const int64_t p1 = t1 < tile_end ? t1 : tile;
-            tile_load<DT, D>(Kh, [&](int slot) { return row_of(p1 * 64, slot); }, bb);
-            __builtin_amdgcn_sched_barrier(0);
-            consume(tile_mac<DT, D>(ba, qa), tile * 64);
-            if (t1 >= tile_end) break;
-            const int64_t t2 = t1 + tile_step;
-            const int64_t p2 = t2 < tile_end ? t2 : t1;
-            tile_load<DT, D>(Kh, [&](int slot) { return row_of(p2 * 64, slot); }, ba);
-            __builtin_amdgcn_sched_barrier(0);
-            consume(tile_mac<DT, D>(bb, qa), t1 * 64);
-            if (t2 >= tile_end) break;
-            tile = t2;
+    struct TileB { v8 b[4][D / 32]; } ba, bb;
+    auto load_rows = [&](TileB& t, int64_t ti) { tile_load<DT, D>(Kh, [&](int slot) { return row_of(ti * 64, slot); }, t.b); };
+    auto use = [&](TileB& t, int64_t ti) { consume(tile_mac<DT, D>(t.b, qa), ti * 64); };
+    if (MODE == MODE_SAMPLE || !TKA_SCAN_SADDR) {
+        walk_tiles(tile, tile_end, tile_step, ba, bb, load_rows, use);
+    } else {
+        // whole tiles first, then the one tile (if any) that the end of the cache cuts short
+        const int64_t n_whole = N / 64;
+        const uint32_t lane_off = (uint32_t)(((lane & 15) * D + (lane >> 4) * 8) * 2);
+        tile = walk_tiles(tile, tile_end < n_whole ? tile_end : n_whole, tile_step, ba, bb,
+                          [&](TileB& t, int64_t ti) { tile_load_full<DT, D>(Kh + ti * (64 * D * 2), lane_off, t.b); }, use);
+        for (; tile < tile_end; tile += tile_step) {
+            load_rows(ba, tile);
+            use(ba, tile);
         }
     }
-#else
-    for (; tile < tile_end; tile += tile_step) {
-        v8 ba[4][D / 32];
-        tile_load<DT, D>(Kh, [&](int slot) { return row_of(tile * 64, slot); }, ba);
-        __builtin_amdgcn_sched_barrier(0);
-        consume(tile_mac<DT, D>(ba, qa), tile * 64);
-    }
-#endif
     if (MODE == MODE_FILTER) {
-        stage_flush(cs0, seg_cap, sh.n_seg);
-        if (1 < G) stage_flush(cs1, seg_cap, sh.n_seg);
-        if (2 < G) stage_flush(cs2, seg_cap, sh.n_seg);
-        if (3 < G) stage_flush(cs3, seg_cap, sh.n_seg);
+        stage_flush(cs0, seg_cap, sh.n_seg, true);
+        if (1 < G) stage_flush(cs1, seg_cap, sh.n_seg, true);
+        if (2 < G) stage_flush(cs2, seg_cap, sh.n_seg, true);
+        if (3 < G) stage_flush(cs3, seg_cap, sh.n_seg, true);
         for (int o = 32; o > 0; o >>= 1) {
             top0 = fmaxf(top0, wave_xor(top0, o)); top1 = fmaxf(top1, wave_xor(top1, o));
             top2 = fmaxf(top2, wave_xor(top2, o)); top3 = fmaxf(top3, wave_xor(top3, o));
@@ -291,10 +351,20 @@ scan_mfma_kernel(Shape sh, Bufs bf, int tiles_per_wave, float* dst) {
 // per tile as the grouped kernel, four times the rows.  Per-row state lives in the 16
 // lanes that own the row.
 // ---------------------------------------------------------------------------------------
-constexpr int kStageRow = 64;   // LDS staging slots per (wave, row); >= the 64 entries one step can add
+#ifndef TKA_STAGE_ROW
+#define TKA_STAGE_ROW 128
+#endif
+// LDS staging slots per (wave, row): the 64 entries one step can add on top of the remainder
+// (fewer than kCandChunk entries) an aligned flush leaves behind
+constexpr int kStageRow = TKA_STAGE_ROW;
+static_assert(kCandChunk <= 16 && kStageRow >= 64 + kCandChunk, "row stage too small for an aligned flush");
 
+#ifndef TKA_ROWS_WAVES_PER_SIMD
+#define TKA_ROWS_WAVES_PER_SIMD 2
+#endif
 template <int DT, int D, int MODE>
 __global__ void __launch_bounds__(kScanWaves* kWave)
+__attribute__((amdgpu_waves_per_eu(TKA_ROWS_WAVES_PER_SIMD, TKA_ROWS_WAVES_PER_SIMD)))
 scan_rows_kernel(Shape sh, Bufs bf, int tiles_per_wave, float* dst) {
     using v8 = typename Mfma<DT>::v8;
     constexpr int KS = D / 32;
@@ -376,18 +446,26 @@ scan_rows_kernel(Shape sh, Bufs bf, int tiles_per_wave, float* dst) {
     __shared__ uint64_t stage_lds[MODE == MODE_FILTER ? kScanWaves * 16 * kStageRow : 1];
     uint64_t* const st0 = stage_lds + (MODE == MODE_FILTER ? wave * 16 * kStageRow : 0);
 
-    // append the staged candidates of rows 4 j' + i (all j') to their segments
-    auto flush = [&](int i, int& nl_i, int& ng_i, int64_t vh_i) {
+    // append the staged candidates of rows 4 j' + i (all j') to their segments, up to the last
+    // whole run of kCandChunk entries unless `final` (see stage_flush)
+    auto flush = [&](int i, int& nl_i, int& ng_i, int64_t vh_i, bool final) {
         wave_sync();
-        uint64_t* seg = bf.cand + vh_i * (int64_t)sh.cand_cap + sid;
-        const uint64_t* src = st0 + (4 * j + i) * kStageRow;
-        for (int e = n; e < nl_i; e += 16) {
+        uint64_t* list = bf.cand + vh_i * (int64_t)sh.cand_cap;
+        uint64_t* src = st0 + (4 * j + i) * kStageRow;
+        const int total = ng_i + nl_i;
+        const int f = (final ? total : (total & ~(kCandChunk - 1))) - ng_i;
+        for (int e = n; e < f; e += 16) {
             const int slot = ng_i + e;
-            if (slot < seg_cap) seg[(int64_t)slot * n_seg] = src[e];
+            if (slot < seg_cap) list[cand_slot(slot, sid, n_seg)] = src[e];
         }
+        const int r = f > 0 ? nl_i - f : nl_i;          // < kCandChunk <= 16 after a flush
+        const bool mv = f > 0 && n < r;
+        const uint64_t keep = mv ? src[f + n] : 0;
         wave_sync();
-        ng_i += nl_i;
-        nl_i = 0;
+        if (mv) src[n] = keep;
+        wave_sync();
+        if (f > 0) ng_i += f;
+        nl_i = r;
     };
 
     auto row_of = [&](int64_t item0, int slot) -> int64_t {
@@ -442,7 +520,7 @@ scan_rows_kernel(Shape sh, Bufs bf, int tiles_per_wave, float* dst) {
                         gm[g] = (uint32_t)(mg[g] >> (16 * j)) & 0xFFFFu;
                         add += __popc(gm[g]);
                     }
-                    if (__ballot(nl[i] + add > kStageRow)) flush(i, nl[i], ng[i], vh[i]);
+                    if (__ballot(nl[i] + add > kStageRow)) flush(i, nl[i], ng[i], vh[i], false);
                     uint64_t* row_st = st0 + (4 * j + i) * kStageRow;
                     int off = nl[i];
 #pragma unroll
@@ -466,32 +544,29 @@ scan_rows_kernel(Shape sh, Bufs bf, int tiles_per_wave, float* dst) {
         }
     };
 
-    v8 ba[4][KS], bb[4][KS];
-    if (tile < tile_end) {
-        tile_load<DT, D>(Kh, [&](int slot) { return row_of(tile * 64, slot); }, ba);
-        while (true) {
-            f32x4 c[4];
-            const int64_t t1 = tile + tile_step;
-            const int64_t p1 = t1 < tile_end ? t1 : tile;
-            tile_load<DT, D>(Kh, [&](int slot) { return row_of(p1 * 64, slot); }, bb);
-            __builtin_amdgcn_sched_barrier(0);
-            mac(ba, c);
-            consume(c, tile * 64);
-            if (t1 >= tile_end) break;
-            const int64_t t2 = t1 + tile_step;
-            const int64_t p2 = t2 < tile_end ? t2 : t1;
-            tile_load<DT, D>(Kh, [&](int slot) { return row_of(p2 * 64, slot); }, ba);
-            __builtin_amdgcn_sched_barrier(0);
-            mac(bb, c);
-            consume(c, t1 * 64);
-            if (t2 >= tile_end) break;
-            tile = t2;
+    struct TileB { v8 b[4][KS]; } ba, bb;
+    auto load_rows = [&](TileB& t, int64_t ti) { tile_load<DT, D>(Kh, [&](int slot) { return row_of(ti * 64, slot); }, t.b); };
+    auto use = [&](TileB& t, int64_t ti) {
+        f32x4 c[4];
+        mac(t.b, c);
+        consume(c, ti * 64);
+    };
+    if (MODE == MODE_SAMPLE || !TKA_SCAN_SADDR) {
+        walk_tiles(tile, tile_end, tile_step, ba, bb, load_rows, use);
+    } else {
+        const int64_t n_whole = N / 64;
+        const uint32_t lane_off = (uint32_t)((n * D + j * 8) * 2);
+        tile = walk_tiles(tile, tile_end < n_whole ? tile_end : n_whole, tile_step, ba, bb,
+                          [&](TileB& t, int64_t ti) { tile_load_full<DT, D>(Kh + ti * (64 * D * 2), lane_off, t.b); }, use);
+        for (; tile < tile_end; tile += tile_step) {
+            load_rows(ba, tile);
+            use(ba, tile);
         }
     }
     if (MODE == MODE_FILTER) {
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-            flush(i, nl[i], ng[i], vh[i]);
+            flush(i, nl[i], ng[i], vh[i], true);
             for (int o = 8; o > 0; o >>= 1) top[i] = fmaxf(top[i], wave_xor(top[i], o));
             if (n == 0 && 4 * j + i < R) {
                 bf.seg_cnt[vh[i] * (int64_t)n_seg + sid] = (uint32_t)ng[i];

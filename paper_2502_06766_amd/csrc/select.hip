@@ -59,15 +59,17 @@ struct SrcDense {            // scores[i] at position i, i < n
     }
 };
 struct SrcSeg {              // candidate list of n_seg interleaved segments: entry e of segment g
-    const uint64_t* segs;    // sits in slot e * n_seg + g; entries are (score bits << 32 | position)
+    const uint64_t* segs;    // sits in slot cand_slot(e, g, n_seg); entries are (score bits << 32 | position)
     const uint32_t* seg_len; // LDS: entries per segment
     uint32_t* pos_lds;       // LDS: inverted positions of the cached slots, [slot j][thread]
     int log2_n_seg;          // n_seg is a power of two
     int max_len;             // longest segment
     typedef uint64_t raw_t;
-    __device__ __forceinline__ int64_t slots() const { return (int64_t)max_len << log2_n_seg; }
+    __device__ __forceinline__ int64_t slots() const {
+        return (int64_t)((max_len + kCandChunk - 1) & ~(kCandChunk - 1)) << log2_n_seg;
+    }
     __device__ __forceinline__ bool valid(int64_t i) const {
-        return i < slots() && (uint32_t)(i >> log2_n_seg) < seg_len[i & ((1 << log2_n_seg) - 1)];
+        return i < slots() && (uint32_t)cand_slot_entry(i, log2_n_seg) < seg_len[cand_slot_segment(i, log2_n_seg)];
     }
     __device__ __forceinline__ const uint64_t* where(int64_t i) const { return segs + i; }
     __device__ __forceinline__ uint32_t key(uint64_t e) const {
