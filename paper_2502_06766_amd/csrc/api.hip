@@ -117,12 +117,6 @@ __global__ void append_kernel(const char* __restrict__ ksrc, const char* __restr
 }
 
 __global__ void set_len_kernel(int32_t* len_slot, int32_t v) { *len_slot = v; }
-#ifdef TKA_DEBUG_NO_CAND
-__global__ void debug_raise_thr_kernel(float* thr, int n) {
-    const int i = blockIdx.x * blockDim.x + threadIdx.x;
-    if (i < n) thr[i] = INFINITY;
-}
-#endif
 
 __global__ void __launch_bounds__(256) read_probe_kernel(const u32x4* __restrict__ src, size_t n_vec, uint32_t* sink) {
     uint32_t acc = 0;
@@ -419,9 +413,6 @@ static int decode_impl(topk_attn_t* h, int layer, const void* q, int n_queries, 
     } else if (fast) {
         e = launch_scan_sample(s, b, nmax, st);
         if (e == hipSuccess) e = launch_threshold(s, b, st);
-#ifdef TKA_DEBUG_NO_CAND
-        hipLaunchKernelGGL(debug_raise_thr_kernel, dim3((s.B * s.Hq + 255) / 256), dim3(256), 0, st, b.thr, s.B * s.Hq);
-#endif
         if (e == hipSuccess && timed) e = hipEventRecord(h->ev[2 * h->ev_used], st);
         if (e == hipSuccess) e = launch_scan_filter(s, b, nmax, st);
         if (e == hipSuccess && timed) e = hipEventRecord(h->ev[2 * h->ev_used + 1], st);

@@ -20,22 +20,6 @@ __device__ __forceinline__ uint32_t ord_from_bits(uint32_t u) {
 __device__ __forceinline__ uint32_t bits_from_ord(uint32_t o) {
     return o ^ ((o >> 31) ? 0x80000000u : 0xFFFFFFFFu);
 }
-// Unique 64-bit selection key: larger score first, then lower position.
-__device__ __forceinline__ uint64_t composite(float score, uint32_t pos) {
-    float s = score + 0.0f;
-    return ((uint64_t)ord_from_bits(__float_as_uint(s)) << 32) | (uint64_t)(0xFFFFFFFFu - pos);
-}
-__device__ __forceinline__ float composite_score(uint64_t c) {
-    return __uint_as_float(bits_from_ord((uint32_t)(c >> 32)));
-}
-__device__ __forceinline__ uint32_t composite_pos(uint64_t c) {
-    return 0xFFFFFFFFu - (uint32_t)c;
-}
-
-__device__ __forceinline__ uint32_t wave_first_u32(uint32_t v) {
-    return (uint32_t)__builtin_amdgcn_readfirstlane((int)v);
-}
-
 // Orders this wave's LDS/global accesses as seen by its own lanes.
 __device__ __forceinline__ void wave_sync() {
     __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");

@@ -222,3 +222,76 @@ def test_c3_index_decode_1m_fp16():
     K, _, _ = H.enforce_margin(q, K, w.dtype, w.k)
     rec = run_index_case(q, K, V, w.dtype, w.k, label="c3 index")
     assert min(rec) == 1.0
+
+
+def test_index_layer_schedule_in_one_call():
+    """Three layers with their own k through topk_attn_decode_layers under the index path:
+    each layer judged against the exact oracle, and bit-identical to separate calls."""
+    dtype, L, Hq, Hkv, d, N = wl.F16, 3, 8, 2, 128, 30000
+    ks = ta.topk_attn_k_schedule(900, L, 2.0)
+    cache = ta.TopkAttnCache(L, 1, Hq, Hkv, d, N, max(ks), dtype, index_kind=ta.INDEX_INT8)
+    try:
+        cache.set_path(ta.PATH_INDEX)
+        data, queries, single = [], [], []
+        for l in range(L):
+            q, K, V = rand_case(Hq, Hkv, N, d, dtype, ks[l], seed=600 + l)
+            data.append((q, K, V))
+            cache.append(l, 0, H.to_torch(K, dtype, DEV), H.to_torch(V, dtype, DEV), head_major=True)
+            queries.append(H.to_torch(q, dtype, DEV)[None].contiguous())
+            single.append(cache.decode(l, queries[-1], ks[l]))
+        qd = torch.stack(queries).contiguous()
+        out = torch.empty((L, 1, Hq, d), dtype=torch.float32, device=DEV)
+        idx = torch.empty((Hq * sum(ks),), dtype=torch.int32, device=DEV)
+        vals = torch.empty((Hq * sum(ks),), dtype=torch.float32, device=DEV)
+        lse = torch.empty((L, 1, Hq), dtype=torch.float32, device=DEV)
+        ta.topk_attn_decode_layers(cache.h, 0, ks, qd.data_ptr(), 0, out.data_ptr(), idx.data_ptr(), vals.data_ptr(),
+                                   lse.data_ptr(), torch.cuda.current_stream().cuda_stream)
+        torch.cuda.synchronize()
+        off = 0
+        for l in range(L):
+            n = Hq * ks[l]
+            q, K, V = data[l]
+            res = (out[l, 0].cpu().numpy(), idx[off:off + n].view(Hq, ks[l]).cpu().numpy(),
+                   vals[off:off + n].view(Hq, ks[l]).cpu().numpy(), lse[l, 0].cpu().numpy())
+            check_index_result(res, q, K, V, dtype, ks[l], 0, f"index layer {l} k={ks[l]}")
+            assert torch.equal(out[l], single[l][0]) and torch.equal(idx[off:off + n].view(1, Hq, ks[l]), single[l][1])
+            off += n
+    finally:
+        cache.close()
+
+
+def test_c4_batched_index_decode():
+    """Config 4 at full size (16 sequences x 262144 tokens, bf16) through the int8 index, k = 1024;
+    two sequences are checked against the exact oracle, all of them for self-consistency
+    with the exact path of the library."""
+    w = wl.C4
+    B, Hq, Hkv, d, N, k = w.n_seqs, w.n_q_heads, w.n_kv_heads, w.head_dim, w.n_tokens, 1024
+    sampled = [0, 15]
+    cache = ta.TopkAttnCache(1, B, Hq, Hkv, d, N, k, w.dtype, index_kind=ta.INDEX_INT8)
+    try:
+        host, qs = {}, []
+        for b in range(B):
+            q, K, V = wl.make_quantized(w, seed=3, seq=b, threads=16)
+            if b in sampled:
+                K, _, _ = H.enforce_margin(q, K, w.dtype, k)
+                host[b] = (q, K, V)
+            cache.append(0, b, H.to_torch(K, w.dtype, DEV), H.to_torch(V, w.dtype, DEV), head_major=True)
+            qs.append(H.to_torch(q, w.dtype, DEV))
+        qd = torch.stack(qs).contiguous()
+        exact = cache.decode(0, qd, k)
+        cache.set_path(ta.PATH_INDEX)
+        approx = cache.decode(0, qd, k)
+        torch.cuda.synchronize()
+        assert cache.last_fallbacks() == 0
+        for b in sampled:
+            q, K, V = host[b]
+            check_index_result(tuple(t[b].cpu().numpy() for t in approx), q, K, V, w.dtype, k, 0, f"c4 index seq {b}")
+        # every sequence: at least 99.9 % of the exact path's positions, per head
+        se, sa = torch.sort(exact[1], dim=-1).values, torch.sort(approx[1], dim=-1).values
+        same = (se == sa).all(dim=-1)
+        for b, h in (~same).nonzero().tolist():
+            rec = i8.recall_at_k(approx[1][b, h].cpu().numpy(), exact[1][b, h].cpu().numpy())
+            assert rec >= 0.999, (b, h, rec)
+        np.testing.assert_allclose(approx[0].cpu().numpy(), exact[0].cpu().numpy(), rtol=0, atol=5e-3 * float(exact[0].abs().max()))
+    finally:
+        cache.close()

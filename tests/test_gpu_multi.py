@@ -179,3 +179,25 @@ def test_c3_chunk_of_four_queries_1m_fp16():
     q = wl.make_query_chunk(q0, w.dtype, M, 11)
     K, delta = H.enforce_margin_multi(q, K, w.dtype, w.k, True, 0, shrink=2.0 ** -9)   # 16 rows per KV head
     run_multi_case(q, K, V, delta, w.dtype, w.k, True, 0, ta.PATH_AUTO, label="c3 x4", expect_fallbacks=0)
+
+
+def test_multi_batched_wide_groups_ragged():
+    """Three sequences of different length, head groups of 8, three queries each (row blocks
+    of two and one query), causal with a window."""
+    dtype, M, Hq, Hkv, d, k, W = wl.F16, 3, 16, 2, 64, 120, 50
+    lens = [22000, 300, 19001]          # the middle one takes the exact general path with the others
+    cache = ta.TopkAttnCache(1, 3, Hq, Hkv, d, max(lens), k, dtype, max_window=W, max_queries=M)
+    try:
+        data = []
+        for b, n in enumerate(lens):
+            q, K, V, delta = make_multi(M, Hq, Hkv, n, d, dtype, k, True, W, seed=80 + b)
+            data.append((q, K, V, delta))
+            cache.append(0, b, H.to_torch(K, dtype, DEV), H.to_torch(V, dtype, DEV), head_major=True)
+        qd = torch.stack([H.to_torch(x[0], dtype, DEV) for x in data]).contiguous()
+        res = cache.decode_multi(0, qd, k, causal=True, window=W)
+        torch.cuda.synchronize()
+        for b in range(3):
+            q, K, V, delta = data[b]
+            check_multi(tuple(t[b].cpu().numpy() for t in res), q, K, V, dtype, k, True, W, delta, f"wide ragged seq {b}")
+    finally:
+        cache.close()
