@@ -15,7 +15,7 @@ constexpr int kSelThreads = TKA_SEL_THREADS;   // workgroup size of the selectio
 constexpr int kGatherRows = 256;    // value rows handled by one gather workgroup
 constexpr int kSampMax = 16384;     // most sample scores per head in the threshold estimate
 constexpr int kSampMin = 1024;
-constexpr int kFilterMinN = 16384;  // below this the full path is used
+constexpr int kFilterMinN = 32768;  // below this the full path is faster (measured crossover)
 constexpr int kMaxSeg = 1024;       // most candidate segments per head
 
 // Geometry of one decode call, passed by value to every kernel.

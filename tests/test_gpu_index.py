@@ -137,7 +137,7 @@ def run_index_case(q, K, V, dtype, k, window=0, label="", expect_fallbacks=0):
     (wl.F16, 4, 2, 50000, 64, 64, 0),          # G = 2, d = 64
     (wl.BF16, 3, 3, 33333, 128, 500, 0),       # G = 1
     (wl.F16, 12, 4, 70001, 128, 1, 0),         # G = 3, k = 1
-    (wl.F16, 8, 2, 30000, 128, 400, 1000),     # with the recent-token window
+    (wl.F16, 8, 2, 40000, 128, 400, 1000),     # with the recent-token window
 ])
 def test_index_decode_recall(dtype, Hq, Hkv, N, d, k, window):
     g = np.random.default_rng(N + k)
@@ -184,7 +184,7 @@ def test_index_short_cache_and_dense_k_use_the_exact_path():
 
 def test_index_ragged_batch_path_switch_and_errors():
     dtype, Hq, Hkv, d, k = wl.BF16, 8, 2, 128, 150
-    lens = [30000, 21001, 18000]
+    lens = [40000, 34001, 33000]
     cache = ta.TopkAttnCache(1, 3, Hq, Hkv, d, max(lens), k, dtype, index_kind=ta.INDEX_INT8, max_queries=2)
     plain = ta.TopkAttnCache(1, 1, Hq, Hkv, d, 64, 8, dtype)
     try:
@@ -227,7 +227,7 @@ def test_c3_index_decode_1m_fp16():
 def test_index_layer_schedule_in_one_call():
     """Three layers with their own k through topk_attn_decode_layers under the index path:
     each layer judged against the exact oracle, and bit-identical to separate calls."""
-    dtype, L, Hq, Hkv, d, N = wl.F16, 3, 8, 2, 128, 30000
+    dtype, L, Hq, Hkv, d, N = wl.F16, 3, 8, 2, 128, 36000
     ks = ta.topk_attn_k_schedule(900, L, 2.0)
     cache = ta.TopkAttnCache(L, 1, Hq, Hkv, d, N, max(ks), dtype, index_kind=ta.INDEX_INT8)
     try:

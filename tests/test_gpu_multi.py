@@ -20,7 +20,7 @@ DEV = torch.device("cuda", 0) if torch.cuda.is_available() else None
 @pytest.mark.parametrize("dtype,Hq,Hkv,N,d,k,path", [
     (wl.F16, 16, 2, 40000, 128, 300, ta.PATH_AUTO),      # G = 8
     (wl.BF16, 16, 1, 33001, 64, 500, ta.PATH_AUTO),      # G = 16: a full row tile
-    (wl.F16, 10, 2, 20001, 128, 64, ta.PATH_AUTO),       # G = 5: rows 5..15 of the tile unused
+    (wl.F16, 10, 2, 36001, 128, 64, ta.PATH_AUTO),       # G = 5: rows 5..15 of the tile unused
     (wl.BF16, 24, 2, 70001, 128, 1, ta.PATH_AUTO),       # G = 12, k = 1
     (wl.F16, 14, 2, 4097, 64, 130, ta.PATH_FULL),        # G = 7, all scores stored
     (wl.F16, 16, 2, 3000, 128, 200, ta.PATH_FILTER),     # short cache forced through the filter
@@ -75,16 +75,16 @@ def run_multi_case(q, K, V, delta, dtype, k, causal, window=0, path=ta.PATH_AUTO
 
 
 @pytest.mark.parametrize("dtype,M,Hq,Hkv,N,d,k,causal,window,path", [
-    (wl.F16, 4, 8, 2, 30000, 128, 300, True, 0, ta.PATH_AUTO),      # 4 queries x 4 heads: one full row tile
+    (wl.F16, 4, 8, 2, 36000, 128, 300, True, 0, ta.PATH_AUTO),      # 4 queries x 4 heads: one full row tile
     (wl.BF16, 3, 8, 2, 50001, 64, 1000, False, 0, ta.PATH_AUTO),    # 12 rows, every query sees everything
-    (wl.F16, 7, 8, 2, 25000, 128, 200, True, 100, ta.PATH_AUTO),    # two row blocks (4 + 3 queries), window
-    (wl.F16, 5, 16, 2, 20000, 128, 128, True, 0, ta.PATH_AUTO),     # G = 8: blocks of 2, 2, 1 queries
-    (wl.BF16, 2, 16, 1, 20000, 64, 77, True, 0, ta.PATH_AUTO),      # G = 16: one query per block
+    (wl.F16, 7, 8, 2, 35000, 128, 200, True, 100, ta.PATH_AUTO),    # two row blocks (4 + 3 queries), window
+    (wl.F16, 5, 16, 2, 34000, 128, 128, True, 0, ta.PATH_AUTO),     # G = 8: blocks of 2, 2, 1 queries
+    (wl.BF16, 2, 16, 1, 33000, 64, 77, True, 0, ta.PATH_AUTO),      # G = 16: one query per block
     (wl.F16, 6, 6, 2, 18000, 128, 90, True, 0, ta.PATH_FILTER),     # G = 3: blocks of 5 and 1 queries
     (wl.F16, 4, 4, 1, 700, 128, 60, True, 0, ta.PATH_FULL),         # all scores stored, row-tile kernel
     (wl.F32, 3, 4, 2, 3000, 64, 50, True, 0, ta.PATH_AUTO),         # fp32: plain-FMA scorer per query
-    (wl.F16, 16, 2, 2, 20000, 128, 150, True, 0, ta.PATH_AUTO),     # MQA-like: 16 queries x 1 head
-    (wl.F16, 33, 4, 1, 17000, 64, 100, True, 16, ta.PATH_AUTO),     # 9 row blocks, the last with one query
+    (wl.F16, 16, 2, 2, 34000, 128, 150, True, 0, ta.PATH_AUTO),     # MQA-like: 16 queries x 1 head
+    (wl.F16, 33, 4, 1, 33500, 64, 100, True, 16, ta.PATH_AUTO),     # 9 row blocks, the last with one query
 ])
 def test_multi_query_decode(dtype, M, Hq, Hkv, N, d, k, causal, window, path):
     q, K, V, delta = make_multi(M, Hq, Hkv, N, d, dtype, k, causal, window, seed=N + k + M)
@@ -108,7 +108,7 @@ def test_multi_batch_ragged_and_single_query_equivalence():
     must also be what a plain decode of a cache truncated to its visible length returns
     (bit for bit in idx order-insensitive form), and n_queries = 1 is the plain decode."""
     dtype, M, Hq, Hkv, d, k = wl.BF16, 3, 8, 2, 128, 200
-    lens = [26000, 17003]
+    lens = [36000, 33003]
     cache = ta.TopkAttnCache(1, 2, Hq, Hkv, d, max(lens), k, dtype, max_queries=M)
     try:
         data = []
@@ -185,7 +185,7 @@ def test_multi_batched_wide_groups_ragged():
     """Three sequences of different length, head groups of 8, three queries each (row blocks
     of two and one query), causal with a window."""
     dtype, M, Hq, Hkv, d, k, W = wl.F16, 3, 16, 2, 64, 120, 50
-    lens = [22000, 300, 19001]          # the middle one takes the exact general path with the others
+    lens = [34000, 300, 33001]          # the middle one takes the exact general path with the others
     cache = ta.TopkAttnCache(1, 3, Hq, Hkv, d, max(lens), k, dtype, max_window=W, max_queries=M)
     try:
         data = []

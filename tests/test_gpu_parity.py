@@ -100,7 +100,7 @@ def test_k_larger_than_n_pads():
 
 # ------------------------------------------------------------------ filtered scan path
 @pytest.mark.parametrize("dtype,Hq,Hkv,N,d,k", [
-    (wl.F16, 8, 2, 20001, 128, 300),
+    (wl.F16, 8, 2, 40001, 128, 300),
     (wl.BF16, 8, 2, 65536 + 17, 128, 1024),
     (wl.F16, 4, 2, 40000, 64, 64),       # G = 2, d = 64
     (wl.BF16, 3, 3, 33333, 128, 500),    # G = 1
@@ -178,8 +178,8 @@ def test_scores_within_fp32_bound(dtype, G, d):
 def test_batch_ragged_lengths_and_layers():
     """B = 3 sequences of different length, 2 layers, token-by-token appends after a bulk import."""
     dtype, Hq, Hkv, d, k = wl.BF16, 8, 2, 128, 200
-    lens = [30000, 17001, 150]
-    cache = ta.TopkAttnCache(2, 3, Hq, Hkv, d, 30010, k, dtype)
+    lens = [40000, 33001, 150]
+    cache = ta.TopkAttnCache(2, 3, Hq, Hkv, d, 40010, k, dtype)
     g = np.random.default_rng(11)
     try:
         data = {}
@@ -385,8 +385,8 @@ def run_window_case(q, K, V, dtype, k, window, path=ta.PATH_AUTO, label=""):
 
 
 @pytest.mark.parametrize("dtype,Hq,Hkv,N,d,k,window,path", [
-    (wl.F16, 8, 2, 30000, 128, 400, 1000, ta.PATH_AUTO),     # filtered scan + 4 window chunks
-    (wl.BF16, 8, 2, 30000, 128, 400, 77, ta.PATH_AUTO),      # window smaller than a chunk
+    (wl.F16, 8, 2, 40000, 128, 400, 1000, ta.PATH_AUTO),     # filtered scan + 4 window chunks
+    (wl.BF16, 8, 2, 40000, 128, 400, 77, ta.PATH_AUTO),      # window smaller than a chunk
     (wl.F32, 4, 2, 3000, 64, 50, 300, ta.PATH_AUTO),         # fp32, general path
     (wl.F16, 4, 1, 500, 64, 20, 499, ta.PATH_FULL),          # one searched token
     (wl.F16, 4, 1, 500, 64, 20, 500, ta.PATH_FULL),          # window covers the whole cache
@@ -410,8 +410,8 @@ def test_window_ragged_batch_and_limits():
     """Three sequences, one shorter than the window; window 0 equals the plain call;
     a window beyond max_window is rejected."""
     dtype, Hq, Hkv, d, k, W = wl.BF16, 8, 2, 128, 100, 600
-    lens = [20000, 400, 5000]
-    cache = ta.TopkAttnCache(1, 3, Hq, Hkv, d, 20000, k, dtype, max_window=W)
+    lens = [36000, 400, 5000]
+    cache = ta.TopkAttnCache(1, 3, Hq, Hkv, d, 36000, k, dtype, max_window=W)
     try:
         data = []
         for b, n in enumerate(lens):
@@ -451,7 +451,7 @@ def test_window_ragged_batch_and_limits():
 def test_layerwise_k_schedule_decode():
     """Per-layer k from the fixed-budget linear schedule (the paper's layer-wise setting),
     one decode per layer with its own k."""
-    dtype, L, Hq, Hkv, d, N = wl.F16, 4, 8, 2, 128, 24000
+    dtype, L, Hq, Hkv, d, N = wl.F16, 4, 8, 2, 128, 36000
     ks = ta.topk_attn_k_schedule(4 * 400, L, 3.0)
     assert sum(ks) == 1600 and ks[0] < ks[-1]
     cache = ta.TopkAttnCache(L, 1, Hq, Hkv, d, N, max(ks), dtype)
