@@ -493,3 +493,47 @@ def test_layerwise_k_schedule_decode():
                                                 None, st) == ta.EINVAL
     finally:
         cache.close()
+
+
+def test_decode_under_graph_capture_replays():
+    """A decode step captured in a HIP graph (the library enqueues kernels only: no memsets, no
+    allocation, no synchronisation) replays with eager work in between and gives the eager
+    result every time, also after the query buffer has been overwritten in place."""
+    dtype, Hq, Hkv, d, N, k = wl.F16, 8, 2, 128, 40000, 300
+    cases = [rand_case(Hq, Hkv, N, d, dtype, k, seed=700)]
+    q2 = wl.quantize(np.random.default_rng(701).standard_normal((Hq, d)).astype(np.float32), dtype)
+    K2, _, _ = H.enforce_margin(q2, cases[0][1].copy(), dtype, k)      # margins for both queries on one cache
+    K2, _, _ = H.enforce_margin(cases[0][0], K2, dtype, k)
+    K2, _, _ = H.enforce_margin(q2, K2, dtype, k)
+    q1, _, V = cases[0]
+    cache = ta.TopkAttnCache(1, 1, Hq, Hkv, d, N, k, dtype)
+    try:
+        cache.append(0, 0, H.to_torch(K2, dtype, DEV), H.to_torch(V, dtype, DEV), head_major=True)
+        qd = H.to_torch(q1, dtype, DEV)[None].contiguous()
+        out = torch.empty((1, Hq, d), dtype=torch.float32, device=DEV)
+        idx = torch.empty((1, Hq, k), dtype=torch.int32, device=DEV)
+        vals = torch.empty((1, Hq, k), dtype=torch.float32, device=DEV)
+        lse = torch.empty((1, Hq), dtype=torch.float32, device=DEV)
+        s = torch.cuda.Stream()
+        with torch.cuda.stream(s):
+            args = (cache.h, 0, qd.data_ptr(), k, out.data_ptr(), idx.data_ptr(), vals.data_ptr(), lse.data_ptr())
+            ta.topk_attn_decode(*args, s.cuda_stream)          # warm-up outside the capture
+            s.synchronize()
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g, stream=s):
+                ta.topk_attn_decode(*args, s.cuda_stream)
+            for rep, q in enumerate([q1, q2, q1, q2]):
+                qd.copy_(H.to_torch(q, dtype, DEV)[None])      # eager work between replays
+                out.zero_(); idx.zero_()
+                s.synchronize()
+                g.replay()
+                s.synchronize()
+                ref = c_oracle.topk_attention(q, K2, V, dtype, k)
+                H.check_against_oracle(out[0].cpu().numpy(), idx[0].cpu().numpy(), vals[0].cpu().numpy(),
+                                       lse[0].cpu().numpy(), ref, H.score_margin(q, K2, dtype), k,
+                                       H.out_tolerance(dtype), float(np.abs(wl.widen(V, dtype)).max()), f"replay {rep}")
+                eager = cache.decode(0, qd, k)
+                s.synchronize()
+                assert torch.equal(eager[0], out) and torch.equal(eager[1], idx)
+    finally:
+        cache.close()
