@@ -94,7 +94,7 @@ def check_index_result(res, q, K, V, dtype, k, window=0, label=""):
     S = c_oracle.scores(q, K, dtype)
     recalls = [i8.recall_at_k(idx[h, :k_eff], ref[1][h, :k_eff]) for h in range(Hq)]
     assert min(recalls) >= 0.999, f"{label}: recall {min(recalls)}"
-    for h in range(Hq):
+    for h in range(Hq if k_eff > 0 else 0):
         got = idx[h, :k_eff].astype(np.int64)
         assert len(set(got.tolist())) == k_eff and got.min() >= 0 and got.max() < N - window, f"{label}: bad positions"
         # every returned position carries its exact score
