@@ -222,7 +222,8 @@ int topk_attn_set_scan_timing(topk_attn_t* h, int enable);
 int topk_attn_scan_time(topk_attn_t* h, double* total_ms, int* n_calls);
 
 /* Measurement aid: stream `bytes` (multiple of 16) from `src` (device) with 128-bit
- * loads and write one checksum word per workgroup to `sink` (device, >= 64 KiB).
+ * loads in the access shape of the key scan (16 KiB tiles per wave, sixteen loads in flight)
+ * and write one checksum word per workgroup to `sink` (device, >= 64 KiB).
  * Gives the read-bandwidth ceiling the key scan is compared against. */
 int topk_attn_read_probe(const void* src, size_t bytes, void* sink, void* hip_stream);
 

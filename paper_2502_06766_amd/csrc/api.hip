@@ -118,15 +118,23 @@ __global__ void append_kernel(const char* __restrict__ ksrc, const char* __restr
 
 __global__ void set_len_kernel(int32_t* len_slot, int32_t v) { *len_slot = v; }
 
+// Streaming read of n_vec 16-byte vectors: every wave walks 16 KiB tiles (16 independent
+// 1 KiB-per-instruction loads in flight), the access shape of the key scan without its work.
 __global__ void __launch_bounds__(256) read_probe_kernel(const u32x4* __restrict__ src, size_t n_vec, uint32_t* sink) {
     uint32_t acc = 0;
-    const size_t stride = (size_t)gridDim.x * blockDim.x;
-    size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
-    for (; i + 3 * stride < n_vec; i += 4 * stride) {
-        const u32x4 a = src[i], b = src[i + stride], c = src[i + 2 * stride], d = src[i + 3 * stride];
-        acc ^= a.x ^ a.y ^ a.z ^ a.w ^ b.x ^ b.y ^ b.z ^ b.w ^ c.x ^ c.y ^ c.z ^ c.w ^ d.x ^ d.y ^ d.z ^ d.w;
+    const size_t lane = threadIdx.x & 63;
+    const size_t wave = (size_t)blockIdx.x * 4 + (threadIdx.x >> 6), n_waves = (size_t)gridDim.x * 4;
+    const size_t n_tiles = n_vec / 1024;
+    for (size_t t = wave; t < n_tiles; t += n_waves) {
+        const u32x4* p = src + t * 1024 + lane;
+        u32x4 v[16];
+#pragma unroll
+        for (int u = 0; u < 16; ++u) v[u] = p[u * 64];
+#pragma unroll
+        for (int u = 0; u < 16; ++u) acc ^= v[u].x ^ v[u].y ^ v[u].z ^ v[u].w;
     }
-    for (; i < n_vec; i += stride) {
+    for (size_t i = n_tiles * 1024 + (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n_vec;
+         i += (size_t)gridDim.x * blockDim.x) {
         const u32x4 a = src[i];
         acc ^= a.x ^ a.y ^ a.z ^ a.w;
     }
@@ -571,8 +579,8 @@ int topk_attn_scan_time(topk_attn_t* h, double* total_ms, int* n_calls) {
 int topk_attn_read_probe(const void* src, size_t bytes, void* sink, void* hip_stream) {
     if (!src || !sink || bytes == 0 || (bytes & 15) || ((uintptr_t)src & 15)) return TOPK_ATTN_EINVAL;
     const size_t n_vec = bytes / 16;
-    size_t blocks = (n_vec + 256 * 4 - 1) / (256 * 4);
-    if (blocks > 16384) blocks = 16384;
+    size_t blocks = (n_vec + 4095) / 4096;      // one tile per wave at least
+    if (blocks > 512) blocks = 512;             // two workgroups per compute unit, like the key scan
     if (const char* e = getenv("TOPK_ATTN_PROBE_BLOCKS")) blocks = (size_t)atoi(e);
     if (blocks < 1) blocks = 1;
     hipLaunchKernelGGL(read_probe_kernel, dim3((unsigned)blocks), dim3(256), 0, (hipStream_t)hip_stream,
