@@ -289,6 +289,7 @@ static void fill_call(topk_attn_t* h, int layer, const void* q, int k, int n_que
     s->cand_cap = h->ws.cand_cap; s->n_seg = 4; s->seg_cap = (h->ws.cand_cap / 4) & ~(kCandChunk - 1); s->samp_cap = kSampMax; s->n_chunk_cap = h->ws.n_chunk_cap;
     s->Ncap = c.max_tokens;
     s->indexed = 0;
+    s->cand_est = 0;
     char* ws = static_cast<char*>(c.workspace);
     const size_t layer_b = (size_t)c.n_seqs * c.n_kv_heads * (size_t)c.max_tokens * c.head_dim * e;
     b->K = static_cast<char*>(c.kv_storage) + (size_t)layer * layer_b;
@@ -403,6 +404,7 @@ static int decode_impl(topk_attn_t* h, int layer, const void* q, int n_queries, 
             c_hi = pl.c_hi > c_hi ? pl.c_hi : c_hi;
         }
         if (fast) fast = choose_segments(h, s, nmax, c_hi, &s.n_seg, &s.seg_cap);
+        s.cand_est = (int)(c_hi < INT32_MAX ? c_hi : INT32_MAX);
     }
     if (!fast) s.indexed = 0;      // no filtered scan: exact path
     hipError_t e = hipSuccess;
@@ -410,7 +412,7 @@ static int decode_impl(topk_attn_t* h, int layer, const void* q, int n_queries, 
     if (fast && s.indexed) {
         e = launch_quantize_rows(s.dtype, s.D, q, (int64_t)s.B * s.Hq, 0, 1, b.q8, b.qscale, 0, st);
         if (e == hipSuccess) e = launch_scan8_sample(s, b, nmax, st);
-        if (e == hipSuccess) e = launch_threshold(s, b, st);
+        if (e == hipSuccess) e = launch_threshold(s, b, nmax, st);
         if (e == hipSuccess && timed) e = hipEventRecord(h->ev[2 * h->ev_used], st);
         if (e == hipSuccess) e = launch_scan8_filter(s, b, st);
         if (e == hipSuccess && timed) e = hipEventRecord(h->ev[2 * h->ev_used + 1], st);
@@ -420,7 +422,7 @@ static int decode_impl(topk_attn_t* h, int layer, const void* q, int n_queries, 
         if (e == hipSuccess) e = launch_select_full(s, b, true, st);
     } else if (fast) {
         e = launch_scan_sample(s, b, nmax, st);
-        if (e == hipSuccess) e = launch_threshold(s, b, st);
+        if (e == hipSuccess) e = launch_threshold(s, b, nmax, st);
         if (e == hipSuccess && timed) e = hipEventRecord(h->ev[2 * h->ev_used], st);
         if (e == hipSuccess) e = launch_scan_filter(s, b, nmax, st);
         if (e == hipSuccess && timed) e = hipEventRecord(h->ev[2 * h->ev_used + 1], st);

@@ -35,15 +35,32 @@ __device__ __forceinline__ void wg_weighted_rows(const Shape& sh, const Bufs& bf
 #pragma unroll
     for (int e = 0; e < EPL; ++e) acc[e] = 0.f;
     float lsum = 0.f;
-    for (int j = j0 + wave * rpw + rs; j < j1; j += 4 * rpw) {
-        const int64_t r = row(j);
-        const float w = weight(j);
-        const u32x4 raw = *reinterpret_cast<const u32x4*>(Vh + (r * D + c * EPL) * Elem<DT>::kBytes);
-        float vf[EPL];
-        Elem<DT>::widen(raw, vf);
+    // U independent rows per lane group at a time (a row's position, its weight,
+    // then the row itself are dependent loads: one at a time is latency-bound for small k)
+    constexpr int U = 4;
+    const int step = 4 * rpw;
+    for (int j = j0 + wave * rpw + rs; j < j1; j += U * step) {
+        int64_t r[U];
+        float w[U];
+        u32x4 raw[U];
 #pragma unroll
-        for (int e = 0; e < EPL; ++e) acc[e] = fmaf(w, vf[e], acc[e]);
-        lsum += w;
+        for (int u = 0; u < U; ++u) {
+            const int jj = j + u * step;
+            const bool ok = jj < j1;
+            r[u] = row(ok ? jj : j);
+            w[u] = ok ? weight(jj) : 0.f;
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+            raw[u] = *reinterpret_cast<const u32x4*>(Vh + (r[u] * D + c * EPL) * Elem<DT>::kBytes);
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            float vf[EPL];
+            Elem<DT>::widen(raw[u], vf);
+#pragma unroll
+            for (int e = 0; e < EPL; ++e) acc[e] = fmaf(w[u], vf[e], acc[e]);
+            lsum += w[u];
+        }
     }
     // add the row slots of the wave together
     for (int o = lpr; o < kWave; o <<= 1) {

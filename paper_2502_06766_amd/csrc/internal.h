@@ -28,6 +28,7 @@ struct Shape {
     int q_per_blk;    // row-tile scan: queries per block of <= 16 (query, head) rows
     int n_qblk;       // row-tile scan: blocks per cache sequence
     int indexed;      // the scan reads the int8 key index; candidates are re-scored exactly afterwards
+    int cand_est;     // candidates per head expected at most (sizes the selection's register cache)
     int k;            // requested k (k_eff = min(k, searched prefix of sequence b))
     int window;       // most recent tokens that are always attended and excluded from the search
     int max_k;
@@ -162,7 +163,7 @@ hipError_t launch_scan_filter(const Shape& s, const Bufs& b, int64_t Nmax, hipSt
 hipError_t launch_scan_full(const Shape& s, const Bufs& b, int64_t Nmax, float* dst, hipStream_t st);
 bool scan_mfma_supported(const Shape& s);
 
-hipError_t launch_threshold(const Shape& s, const Bufs& b, hipStream_t st);
+hipError_t launch_threshold(const Shape& s, const Bufs& b, int64_t Nmax, hipStream_t st);
 hipError_t launch_select_candidates(const Shape& s, const Bufs& b, hipStream_t st);
 hipError_t launch_select_full(const Shape& s, const Bufs& b, bool redo_flagged, hipStream_t st);
 

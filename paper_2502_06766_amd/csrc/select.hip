@@ -361,6 +361,7 @@ __device__ void wg_score_head(const Shape& sh, const Bufs& bf, int b, int h, int
 
 // Threshold estimate: the rank-th largest of the sample scores of each head (any value
 // with `rank` samples at or above it serves); also clears the head's fallback flag.
+template <int CPT>     // CPT * kSelThreads sample scores are kept in registers, the rest is streamed
 __global__ void __launch_bounds__(kSelThreads) threshold_kernel(Shape sh, Bufs bf) {
     __shared__ SelShared sm;
     const int b = blockIdx.y, h = blockIdx.x;
@@ -377,7 +378,7 @@ __global__ void __launch_bounds__(kSelThreads) threshold_kernel(Shape sh, Bufs b
     const int64_t N = prefix_len(bf.len[cache_seq(sh, b)], sh.window);
     const Plan pl = make_plan(N, sh.k < N ? sh.k : (int)N, sh.indexed);
     const SrcDense src{bf.samp + bh * sh.samp_cap, (int64_t)pl.n_samp};
-    const Items<(kSampMax + kSelThreads - 1) / kSelThreads, SrcDense> items(src);
+    const Items<CPT, SrcDense> items(src);
     const int rank = pl.rank < pl.n_samp ? pl.rank : pl.n_samp;
     // two digits (18 bits from the first bit in which the samples differ) are plenty: stopping
     // there lowers the threshold by at most the last bin's width, a handful of extra samples
@@ -392,9 +393,10 @@ __global__ void __launch_bounds__(kSelThreads) threshold_kernel(Shape sh, Bufs b
 
 // Exact selection among the candidates the filtered scan kept, read from the interleaved
 // per-wave segments.
+template <int CPT>     // CPT * kSelThreads candidate slots are kept on chip, the rest is streamed
 __global__ void __launch_bounds__(kSelThreads) select_candidates_kernel(Shape sh, Bufs bf) {
     __shared__ SelShared sm;
-    __shared__ uint32_t pos_lds[kCandSlots];
+    __shared__ uint32_t pos_lds[CPT * kSelThreads];
     const int b = blockIdx.y, h = blockIdx.x;
     const int tid = threadIdx.x, lane = lane_id(), wave = tid >> 6;
     const int64_t bh = (int64_t)b * sh.Hq + h;
@@ -440,7 +442,7 @@ __global__ void __launch_bounds__(kSelThreads) select_candidates_kernel(Shape sh
         return;
     }
     const SrcSeg src{bf.cand + bh * (int64_t)sh.cand_cap, sm.seg_len, pos_lds, 31 - __clz(sh.n_seg), (int)max_len};
-    const Items<kCandSlots / kSelThreads, SrcSeg> items(src);
+    const Items<CPT, SrcSeg> items(src);
     // every candidate is >= the head's threshold and the scan reported the largest score; not so
     // after an index scan, whose candidates were re-scored since
     const uint32_t kmax = wg_topk_emit(items, k_eff, sh.k, bf.sel_idx + bh * sh.k, bf.sel_val + bh * sh.k, sm,
@@ -475,12 +477,31 @@ __global__ void __launch_bounds__(kSelThreads) select_full_kernel(Shape sh, Bufs
     if (threadIdx.x == 0) bf.hmax[bh] = key_score(kmax);
 }
 
-hipError_t launch_threshold(const Shape& s, const Bufs& b, hipStream_t st) {
-    hipLaunchKernelGGL(threshold_kernel, dim3(s.Hq, s.B), dim3(kSelThreads), 0, st, s, b);
+// Both kernels are correct for any register-cache size (what does not fit is streamed); a
+// cache much larger than the data only costs loop trips over empty slots, which matters
+// when the whole step is a few tens of microseconds.
+hipError_t launch_threshold(const Shape& s, const Bufs& b, int64_t Nmax, hipStream_t st) {
+    const int n_samp = make_plan(Nmax, s.k < Nmax ? s.k : (int)Nmax, s.indexed).n_samp;
+    const dim3 grid(s.Hq, s.B), block(kSelThreads);
+    if (n_samp <= 2 * kSelThreads) hipLaunchKernelGGL(threshold_kernel<2>, grid, block, 0, st, s, b);
+    else if (n_samp <= 4 * kSelThreads) hipLaunchKernelGGL(threshold_kernel<4>, grid, block, 0, st, s, b);
+    else if (n_samp <= 8 * kSelThreads) hipLaunchKernelGGL(threshold_kernel<8>, grid, block, 0, st, s, b);
+    else hipLaunchKernelGGL((threshold_kernel<(kSampMax + kSelThreads - 1) / kSelThreads>), grid, block, 0, st, s, b);
     return hipGetLastError();
 }
 hipError_t launch_select_candidates(const Shape& s, const Bufs& b, hipStream_t st) {
-    hipLaunchKernelGGL(select_candidates_kernel, dim3(s.Hq, s.B), dim3(kSelThreads), 0, st, s, b);
+    // slots the filled part of the list is expected to span: the longest segment, a few
+    // standard deviations above the mean, times the segments
+    const double mean = (double)s.cand_est / (double)s.n_seg;
+    int64_t len = (int64_t)(mean + 4.0 * sqrt(mean) + 16.0);
+    len = (len + kCandChunk - 1) / kCandChunk * kCandChunk;
+    if (len > s.seg_cap) len = s.seg_cap;
+    const int64_t slots = len * s.n_seg;
+    const dim3 grid(s.Hq, s.B), block(kSelThreads);
+    if (slots <= 4 * kSelThreads) hipLaunchKernelGGL(select_candidates_kernel<4>, grid, block, 0, st, s, b);
+    else if (slots <= 8 * kSelThreads) hipLaunchKernelGGL(select_candidates_kernel<8>, grid, block, 0, st, s, b);
+    else if (slots <= 16 * kSelThreads) hipLaunchKernelGGL(select_candidates_kernel<16>, grid, block, 0, st, s, b);
+    else hipLaunchKernelGGL((select_candidates_kernel<kCandSlots / kSelThreads>), grid, block, 0, st, s, b);
     return hipGetLastError();
 }
 hipError_t launch_select_full(const Shape& s, const Bufs& b, bool redo_flagged, hipStream_t st) {
