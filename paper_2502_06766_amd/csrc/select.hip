@@ -298,9 +298,15 @@ __device__ __forceinline__ uint32_t wg_topk_emit(const It& items, int k_eff, int
         return present && (c > s.T || (c == s.T && (!ties || ip >= T2)));
     };
     uint32_t wave_total = 0;
-    items.visit([&](uint32_t c, uint32_t ip, bool p) {
-        wave_total += (uint32_t)__popcll(__ballot(wanted(c, ip, p)));
-    });
+    if (ties) {
+        items.visit([&](uint32_t c, uint32_t ip, bool p) {
+            wave_total += (uint32_t)__popcll(__ballot(wanted(c, ip, p)));
+        });
+    } else {       // the score alone decides: no need to fetch the positions for counting
+        items.visit([&](uint32_t c, uint32_t, bool p) {
+            wave_total += (uint32_t)__popcll(__ballot(p && c >= s.T));
+        });
+    }
     __syncthreads();
     if (lane == 0) sm.wave_tot[wave] = wave_total;
     __syncthreads();
