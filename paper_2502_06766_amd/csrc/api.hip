@@ -391,17 +391,20 @@ static int decode_impl(topk_attn_t* h, int layer, const void* q, int n_queries, 
     // the int8 index serves one query per sequence with the grouped scan layout
     const bool want_index = h->path == TOPK_ATTN_PATH_INDEX && n_queries == 1 && s.G <= 4;
     s.indexed = want_index ? 1 : 0;
+    // The batch takes the filtered scan if its longest sequence is worth it.  Shorter sequences
+    // ride along whenever their candidate list fits; the few that cannot be filtered at all (a
+    // handful of tokens, or k too dense) are recognised by the kernels themselves (same
+    // plan_is_fast) and go straight to the exact redo of the selection, which is cheap for them.
     bool fast = false;
     if (h->path != TOPK_ATTN_PATH_FULL && scan_mfma_supported(s) && nmax > 0) {
-        fast = true;
+        const Plan longest = make_plan(nmax, k < nmax ? k : (int)nmax, s.indexed);
+        fast = plan_is_fast(longest, nmax, s.cand_cap, h->path == TOPK_ATTN_PATH_FILTER);
         int64_t c_hi = 0;
         for (int i = 0; i < s.Bc && fast; ++i) {
             const int64_t n = prefix_len(h->len[(size_t)layer * s.Bc + i], window);
             if (n == 0) continue;            // this sequence lies entirely inside its window
-            const int ke = k < n ? k : (int)n;
-            const Plan pl = make_plan(n, ke, s.indexed);
-            fast = plan_is_fast(pl, n, s.cand_cap, h->path == TOPK_ATTN_PATH_FILTER);
-            c_hi = pl.c_hi > c_hi ? pl.c_hi : c_hi;
+            const Plan pl = make_plan(n, k < n ? k : (int)n, s.indexed);
+            if (plan_is_fast(pl, n, s.cand_cap, true)) c_hi = pl.c_hi > c_hi ? pl.c_hi : c_hi;
         }
         if (fast) fast = choose_segments(h, s, nmax, c_hi, &s.n_seg, &s.seg_cap);
         s.cand_est = (int)(c_hi < INT32_MAX ? c_hi : INT32_MAX);

@@ -383,6 +383,16 @@ __global__ void __launch_bounds__(kSelThreads) threshold_kernel(Shape sh, Bufs b
     // the sample was drawn by the plan of the cache sequence (shared by all its queries)
     const int64_t N = prefix_len(bf.len[cache_seq(sh, b)], sh.window);
     const Plan pl = make_plan(N, sh.k < N ? sh.k : (int)N, sh.indexed);
+    if (!plan_is_fast(pl, N, sh.cand_cap, true)) {
+        // a sequence of the batch that cannot be filtered (a few tokens only, or k too dense for
+        // the candidate list): nothing passes its scan and its heads go straight to the exact redo
+        if (threadIdx.x == 0) {
+            bf.thr[bh] = INFINITY;
+            bf.flags[bh] = 1;
+            if (bh == 0) *bf.fallback_total = 0;
+        }
+        return;
+    }
     const SrcDense src{bf.samp + bh * sh.samp_cap, (int64_t)pl.n_samp};
     const Items<CPT, SrcDense> items(src);
     const int rank = pl.rank < pl.n_samp ? pl.rank : pl.n_samp;
@@ -414,6 +424,7 @@ __global__ void __launch_bounds__(kSelThreads) select_candidates_kernel(Shape sh
         if (tid == 0) bf.hmax[bh] = -INFINITY;
         return;
     }
+    if (bf.flags[bh]) return;        // set by the threshold kernel: this sequence is not filtered at all
     // segment lengths: total, longest
     uint32_t sum = 0, mxl = 0, kmx = 0;      // kmx: largest score key any scanning wave saw
     for (int g = tid; g < sh.n_seg; g += kSelThreads) {

@@ -537,3 +537,41 @@ def test_decode_under_graph_capture_replays():
                 assert torch.equal(eager[0], out) and torch.equal(eager[1], idx)
     finally:
         cache.close()
+
+
+@pytest.mark.parametrize("path,lens,k", [
+    (ta.PATH_AUTO, [70000, 100, 40000, 255], 300),        # two sequences too short to be filtered
+    (ta.PATH_FILTER, [400000, 100, 40000], 39000),        # k too dense for the third one's sample
+    (ta.PATH_INDEX, [70000, 100, 40000, 255], 300),
+])
+def test_ragged_batch_keeps_the_filtered_scan(path, lens, k):
+    """A batch whose longest sequence is filtered while others cannot be (a few tokens, or k
+    almost the whole cache): those go through the exact redo inside the same call, are not
+    counted as fallbacks, and every sequence matches the oracle."""
+    dtype, Hq, Hkv, d = wl.F16, 8, 2, 128
+    B = len(lens)
+    cache = ta.TopkAttnCache(1, B, Hq, Hkv, d, max(lens), k, dtype,
+                             index_kind=ta.INDEX_INT8 if path == ta.PATH_INDEX else ta.INDEX_NONE)
+    try:
+        cache.set_path(path)
+        data = []
+        for b, n in enumerate(lens):
+            g = np.random.default_rng(800 + b)
+            q = wl.quantize(g.standard_normal((Hq, d)).astype(np.float32), dtype)
+            K = wl.quantize(g.standard_normal((Hkv, n, d)).astype(np.float32), dtype)
+            V = wl.quantize(g.standard_normal((Hkv, n, d)).astype(np.float32), dtype)
+            K, _, _ = H.enforce_margin(q, K, dtype, k, shrink=2.0 ** -9)
+            data.append((q, K, V))
+            cache.append(0, b, H.to_torch(K, dtype, DEV), H.to_torch(V, dtype, DEV), head_major=True)
+        qd = torch.stack([H.to_torch(x[0], dtype, DEV) for x in data]).contiguous()
+        out, idx, vals, lse = cache.decode(0, qd, k)
+        torch.cuda.synchronize()
+        assert cache.last_fallbacks() == 0
+        for b, n in enumerate(lens):
+            q, K, V = data[b]
+            ref = c_oracle.topk_attention(q, K, V, dtype, k)
+            H.check_against_oracle(out[b].cpu().numpy(), idx[b].cpu().numpy(), vals[b].cpu().numpy(),
+                                   lse[b].cpu().numpy(), ref, H.score_margin(q, K, dtype), min(k, n), 2e-3,
+                                   float(np.abs(wl.widen(V, dtype)).max()), f"ragged filtered seq {b} (N={n})")
+    finally:
+        cache.close()
