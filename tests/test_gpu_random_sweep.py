@@ -89,3 +89,67 @@ def test_random_shapes_and_entry_points(seed):
             if "margin enforcement did not converge" not in str(e):   # dense k with many rows per KV head
                 raise
     assert done >= 30
+
+
+@pytest.mark.parametrize("seed", [21, 22])
+def test_random_ragged_batches(seed):
+    """Two to four sequences of very different length in one call (a few tokens, a few thousand,
+    tens of thousands), a random layer of two (the other holds data of another length), every
+    entry point and pipeline; each sequence is judged against the oracle on its own."""
+    rng = np.random.default_rng(seed)
+    done = 0
+    for case in range(25):
+        dtype = int(rng.choice([wl.F16, wl.BF16, wl.F32], p=[0.45, 0.4, 0.15]))
+        d = int(rng.choice([64, 128]))
+        G = int(rng.choice([1, 2, 4, 8]))
+        Hkv = int(rng.integers(1, 3))
+        Hq = G * Hkv
+        B, layer = int(rng.integers(2, 5)), int(rng.integers(0, 2))
+        lens = [int(rng.choice([rng.integers(1, 300), rng.integers(300, 9000), rng.integers(33000, 70000)]))
+                for _ in range(B)]
+        M = int(rng.choice([1, 1, 2, 3]))
+        causal = bool(rng.random() < 0.7)
+        if causal:
+            lens = [max(n, M) for n in lens]
+        k = int(rng.integers(1, 600))
+        window = int(rng.choice([0, 0, 5, 200]))
+        use_index = dtype != wl.F32 and G <= 4 and M == 1 and rng.random() < 0.4
+        path = ta.PATH_INDEX if use_index else int(rng.choice([ta.PATH_AUTO, ta.PATH_FULL, ta.PATH_FILTER]))
+        sd = int(rng.integers(1 << 30))
+        label = f"ragged sweep seed {seed} case {case}: dtype={dtype} d={d} Hq={Hq} Hkv={Hkv} lens={lens} k={k} M={M} " \
+                f"causal={causal} window={window} path={path}"
+        try:
+            data = [TM.make_multi(M, Hq, Hkv, n, d, dtype, k, causal, window, seed=sd + b) for b, n in enumerate(lens)]
+        except AssertionError as e:
+            if "margin enforcement did not converge" not in str(e):
+                raise
+            continue
+        cache = ta.TopkAttnCache(2, B, Hq, Hkv, d, max(lens) + 7, k, dtype, max_window=window, max_queries=M,
+                                 index_kind=ta.INDEX_INT8 if use_index else ta.INDEX_NONE)
+        try:
+            cache.set_path(path)
+            for b, (q, K, V, delta) in enumerate(data):
+                half = max(1, lens[b] // 2)
+                cache.append(layer, b, H.to_torch(K, dtype, DEV), H.to_torch(V, dtype, DEV), head_major=True)
+                cache.append(1 - layer, b, H.to_torch(V[:, :half].copy(), dtype, DEV),
+                             H.to_torch(K[:, :half].copy(), dtype, DEV), head_major=True)
+            qd = torch.stack([H.to_torch(x[0], dtype, DEV) for x in data]).contiguous()          # [B, M, Hq, d]
+            if M == 1:
+                res = cache.decode(layer, qd[:, 0].contiguous(), k, window=window)
+            else:
+                res = cache.decode_multi(layer, qd, k, causal=causal, window=window)
+            torch.cuda.synchronize()
+            for b, (q, K, V, delta) in enumerate(data):
+                r = tuple(t[b].cpu().numpy() for t in res)
+                if M > 1:
+                    TM.check_multi(r, q, K, V, dtype, k, causal, window, delta, f"{label} seq {b}")
+                elif use_index:
+                    TI.check_index_result(r, q[0], K, V, dtype, k, window, f"{label} seq {b}")
+                else:
+                    ref = c_oracle.topk_attention_window(q[0], K, V, dtype, k, window)
+                    H.check_against_oracle(*r, ref, delta[0], min(k, max(0, lens[b] - window)), H.out_tolerance(dtype),
+                                           float(np.abs(wl.widen(V, dtype)).max()), f"{label} seq {b}")
+            done += 1
+        finally:
+            cache.close()
+    assert done >= 18
