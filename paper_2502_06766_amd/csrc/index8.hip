@@ -356,30 +356,29 @@ hipError_t launch_scan8_full(const Shape& s, const Bufs& b, int64_t Nmax, float*
 
 // ---------------------------------------------------------------------------------------
 // Exact refinement: the score of every candidate the index scan kept is replaced by the
-// fp32 dot product of the query with the 16-bit key row.  A workgroup takes 256 consecutive
-// slots of a head's candidate list,
-// D / 8 lanes per candidate.
+// fp32 dot product of the query with the 16-bit key row.  One wave per segment of a head's
+// candidate list (it knows the segment's length, so no slot is visited in vain), D / 8 lanes
+// per candidate, kRerankInFlight candidates in flight per lane group (an entry, then the row
+// it points to, are dependent loads).
 // ---------------------------------------------------------------------------------------
+#ifndef TKA_RERANK_U
+#define TKA_RERANK_U 4
+#endif
+constexpr int kRerankInFlight = TKA_RERANK_U;
+
 template <int DT>
 __global__ void __launch_bounds__(256) rerank_kernel(Shape sh, Bufs bf) {
     constexpr int EPL = Elem<DT>::kPerLoad;
-    constexpr int U = 8;                         // candidates in flight per lane group
+    constexpr int U = kRerankInFlight;
     __shared__ float qf[256];
     const int h = blockIdx.y, b = blockIdx.z;
     const int64_t bh = (int64_t)b * sh.Hq + h;
+    if (bf.flags[bh]) return;                            // not filtered: the exact redo scores this head itself
     const int D = sh.D;
-    const int lpr = D / EPL, groups = 256 / lpr;         // 16 lanes per candidate at D = 128: 16 groups
-    const int rs = threadIdx.x / lpr, c = threadIdx.x % lpr;
-    const int log2_seg = 31 - __clz(sh.n_seg);
-    const int64_t slot0 = (int64_t)blockIdx.x * 256;
-    const uint32_t* cnt = bf.seg_cnt + bh * sh.n_seg;
-    auto valid_slot = [&](int64_t s) {
-        uint32_t have = cnt[cand_slot_segment(s, log2_seg)];
-        if (have > (uint32_t)sh.seg_cap) have = (uint32_t)sh.seg_cap;
-        return (uint32_t)cand_slot_entry(s, log2_seg) < have;
-    };
-    // most blocks lie beyond the filled part of the list
-    if (!__syncthreads_or(valid_slot(slot0 + threadIdx.x) ? 1 : 0)) return;
+    const int lane = lane_id(), wave = threadIdx.x >> 6;
+    const int lpr = D / EPL, groups = kWave / lpr;       // 16 lanes per candidate at D = 128: 4 groups per wave
+    const int grp = lane / lpr, c = lane % lpr;
+    const int g = (int)blockIdx.x * 4 + wave;            // this wave's segment
     for (int i = threadIdx.x; i < D; i += 256) {
         const char* qp = static_cast<const char*>(bf.q) + (bh * D + i) * Elem<DT>::kBytes;
         qf[i] = DT == DT_F16 ? (float)*reinterpret_cast<const _Float16*>(qp)
@@ -389,19 +388,22 @@ __global__ void __launch_bounds__(256) rerank_kernel(Shape sh, Bufs bf) {
     float qr[EPL];
 #pragma unroll
     for (int e = 0; e < EPL; ++e) qr[e] = qf[c * EPL + e];
+    uint32_t have = bf.seg_cnt[bh * sh.n_seg + g];
+    if (have > (uint32_t)sh.seg_cap) have = (uint32_t)sh.seg_cap;
     const char* Kh = static_cast<const char*>(bf.K) +
                      ((int64_t)cache_seq(sh, b) * sh.Hkv + h / sh.G) * sh.Ncap * D * Elem<DT>::kBytes;
     uint64_t* list = bf.cand + bh * (int64_t)sh.cand_cap;
-    // lane group rs takes the slots slot0 + rs + groups * i; U of them are in flight at a time
-    for (int p = 0; p < 256; p += groups * U) {
+    for (uint32_t e0 = 0; e0 < have; e0 += groups * U) {          // `have` is uniform over the wave
         bool ok[U];
+        int64_t slot[U];
         uint64_t ent[U];
         u32x4 raw[U];
 #pragma unroll
         for (int u = 0; u < U; ++u) {
-            const int64_t s = slot0 + p + groups * u + rs;
-            ok[u] = p + groups * u + rs < 256 && valid_slot(s);
-            ent[u] = ok[u] ? list[s] : 0;
+            const uint32_t e = e0 + groups * u + grp;
+            ok[u] = e < have;
+            slot[u] = cand_slot(ok[u] ? e : 0, g, sh.n_seg);
+            ent[u] = ok[u] ? list[slot[u]] : 0;
         }
 #pragma unroll
         for (int u = 0; u < U; ++u)
@@ -414,15 +416,13 @@ __global__ void __launch_bounds__(256) rerank_kernel(Shape sh, Bufs bf) {
 #pragma unroll
             for (int i = 0; i < EPL; ++i) acc = fmaf(kf[i], qr[i], acc);
             for (int o = 1; o < lpr; o <<= 1) acc += wave_xor(acc, o);
-            if (ok[u] && c == 0)
-                list[slot0 + p + groups * u + rs] = ((uint64_t)__float_as_uint(acc + 0.0f) << 32) | (ent[u] & 0xFFFFFFFFull);
+            if (ok[u] && c == 0) list[slot[u]] = ((uint64_t)__float_as_uint(acc + 0.0f) << 32) | (ent[u] & 0xFFFFFFFFull);
         }
     }
 }
 
 hipError_t launch_rerank(const Shape& s, const Bufs& b, hipStream_t st) {
-    const int64_t slots = (int64_t)s.n_seg * s.seg_cap;
-    dim3 grid((unsigned)((slots + 255) / 256), (unsigned)s.Hq, (unsigned)s.B);
+    dim3 grid((unsigned)(s.n_seg / 4), (unsigned)s.Hq, (unsigned)s.B);      // n_seg is a multiple of 4
     if (s.dtype == DT_F16) hipLaunchKernelGGL((rerank_kernel<DT_F16>), grid, dim3(256), 0, st, s, b);
     else if (s.dtype == DT_BF16) hipLaunchKernelGGL((rerank_kernel<DT_BF16>), grid, dim3(256), 0, st, s, b);
     else return hipErrorInvalidValue;
