@@ -124,7 +124,8 @@ def main() -> int:
     e = 2
     alg_bytes = Hkv * N * d * e + M * (Hq * k * d * e + Hq * d * (e + 4) + Hq * k * 4)
     keys_per_s = Hkv * N / (ms_per_step * 1e-3)
-    n_qblk = 1 if M == 1 else -(-M // (16 // (Hq // Hkv)))     # passes over the keys: one per block of 16 rows
+    G = Hq // Hkv
+    n_qblk = 1 if M == 1 else -(-M // ((32 if M * G > 16 else 16) // G))     # passes over the keys: one per block of 16 or 32 rows
     scan_bytes = k_bytes * n_qblk
     if args.index and M == 1:
         scan_bytes = Hkv * N * (d + 4)                          # int8 codes and one fp32 scale per key

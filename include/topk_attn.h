@@ -147,7 +147,7 @@ int topk_attn_decode_window(topk_attn_t* h, int layer, const void* q, int k, int
  * cache construction time" of the section on million-token cache generation -- or in
  * verifying drafted tokens): each of the M queries of a sequence gets its own exact
  * top-k search, softmax and weighted value sum, exactly as if topk_attn_decode_window had
- * been called once per query, but the keys are read once per block of up to 16
+ * been called once per query, but the keys are read once per block of up to 32
  * (query, head) rows of a KV head instead of once per query.
  *   q     device [B, M, Hq, d];  out [B, M, Hq, d];  idx / vals [B, M, Hq, k];  lse [B, M, Hq]
  *   causal != 0: the M queries are the last M cached tokens' queries, query m attends only

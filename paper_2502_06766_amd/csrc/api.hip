@@ -283,7 +283,8 @@ static void fill_call(topk_attn_t* h, int layer, const void* q, int k, int n_que
     const int e = elem_bytes(c.dtype);
     s->Bc = c.n_seqs; s->M = n_queries; s->causal = 0; s->B = c.n_seqs * n_queries;
     s->Hq = c.n_q_heads; s->Hkv = c.n_kv_heads; s->G = c.n_q_heads / c.n_kv_heads;
-    s->q_per_blk = 16 / s->G < n_queries ? 16 / s->G : n_queries;     // G <= 16
+    s->row_tiles = n_queries * s->G > 16 ? 2 : 1;
+    s->q_per_blk = 16 * s->row_tiles / s->G < n_queries ? 16 * s->row_tiles / s->G : n_queries;     // G <= 16
     s->n_qblk = (n_queries + s->q_per_blk - 1) / s->q_per_blk;
     s->D = c.head_dim; s->dtype = c.dtype; s->k = k; s->window = 0; s->max_k = c.max_k;
     s->cand_cap = h->ws.cand_cap; s->n_seg = 4; s->seg_cap = (h->ws.cand_cap / 4) & ~(kCandChunk - 1); s->samp_cap = kSampMax; s->n_chunk_cap = h->ws.n_chunk_cap;

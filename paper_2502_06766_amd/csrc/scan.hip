@@ -344,7 +344,7 @@ scan_mfma_kernel(Shape sh, Bufs bf, int tiles_per_wave, float* dst) {
 }
 
 // ---------------------------------------------------------------------------------------
-// Row-tile variant: up to 16 (query, head) rows against one KV head in a single pass over
+// Row-tile variant: up to 16 (32 with two row tiles) (query, head) rows against one KV head in a single pass over
 // its keys -- head groups of 5..16, and several queries per sequence (a chunk of M
 // queries, the cache-construction use the paper mentions for top-k attention).  Operand A
 // holds 16 distinct rows, so the four accumulators of a 64-key tile give lane (j, n) the
@@ -360,21 +360,22 @@ scan_mfma_kernel(Shape sh, Bufs bf, int tiles_per_wave, float* dst) {
 constexpr int kStageRow = TKA_STAGE_ROW;
 static_assert(kCandChunk <= 16 && kStageRow >= 64 + kCandChunk, "row stage too small for an aligned flush");
 
-#ifndef TKA_ROWS_WAVES_PER_SIMD
-#define TKA_ROWS_WAVES_PER_SIMD 2
-#endif
-template <int DT, int D, int MODE>
+// NT row tiles (16 rows each) share every key tile: NT = 2 halves the passes over the keys for
+// 17..32 rows at the price of one wave per SIMD (512 registers) and 128 KiB of LDS stages,
+// which costs this kernel nothing measurable.
+template <int DT, int D, int MODE, int NT>
 __global__ void __launch_bounds__(kScanWaves* kWave)
-__attribute__((amdgpu_waves_per_eu(TKA_ROWS_WAVES_PER_SIMD, TKA_ROWS_WAVES_PER_SIMD)))
+__attribute__((amdgpu_waves_per_eu(NT == 1 ? 2 : 1, NT == 1 ? 2 : 1)))
 scan_rows_kernel(Shape sh, Bufs bf, int tiles_per_wave, float* dst) {
     using v8 = typename Mfma<DT>::v8;
     constexpr int KS = D / 32;
+    constexpr int X = 4 * NT;          // rows a lane owns: row 16 t + 4 j + i at x = 4 t + i
     const int G = sh.G, M = sh.M;
     const int bc = (int)blockIdx.z / sh.n_qblk, blk = (int)blockIdx.z % sh.n_qblk;   // cache sequence, row block
     const int kvh = blockIdx.y;
     const int m0 = blk * sh.q_per_blk;                                // first query of the block
     const int mq = sh.q_per_blk < M - m0 ? sh.q_per_blk : M - m0;     // its queries
-    const int R = mq * G;                                             // its rows, <= 16
+    const int R = mq * G;                                             // its rows, <= 16 NT
     const int lane = lane_id();
     const int j = lane >> 4, n = lane & 15;
     const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
@@ -415,45 +416,48 @@ scan_rows_kernel(Shape sh, Bufs bf, int tiles_per_wave, float* dst) {
         if (tile_end > n_tiles_all) tile_end = n_tiles_all;
     }
 
-    // operand A: lane (j, m) holds channels 32 s + 8 j .. +7 of row m
-    v8 qa[KS];
-    {
-        const v8* p = reinterpret_cast<const v8*>(static_cast<const char*>(bf.q) + head_of(n < R ? n : 0) * (D * 2)) + j;
+    // operand A of row tile t: lane (j, m) holds channels 32 s + 8 j .. +7 of row 16 t + m
+    v8 qa[NT][KS];
+#pragma unroll
+    for (int t = 0; t < NT; ++t) {
+        const int rr = 16 * t + n;
+        const v8* p = reinterpret_cast<const v8*>(static_cast<const char*>(bf.q) + head_of(rr < R ? rr : 0) * (D * 2)) + j;
 #pragma unroll
         for (int s = 0; s < KS; ++s) {
             v8 v = p[4 * s];
-            if (n >= R) v = v8{};
-            qa[s] = v;
+            if (rr >= R) v = v8{};
+            qa[t][s] = v;
         }
     }
     const char* Kh = static_cast<const char*>(bf.K) + ((int64_t)bc * sh.Hkv + kvh) * sh.Ncap * (D * 2);
 
-    // the four rows 4 j + i this lane owns
-    int64_t vh[4];
-    int P[4];
-    float thr[4], top[4];
-    int nl[4], ng[4];       // staged / already appended candidates (uniform over the 16 lanes of the row)
+    // the rows this lane owns
+    auto row_at = [&](int x) { return 16 * (x >> 2) + 4 * j + (x & 3); };
+    int64_t vh[X];
+    int P[X];
+    float thr[X], top[X];
+    int nl[X], ng[X];       // staged / already appended candidates (uniform over the 16 lanes of the row)
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        const int rr = 4 * j + i;
-        vh[i] = head_of(rr < R ? rr : 0);
-        P[i] = prefix_of(rr);
-        thr[i] = (MODE == MODE_FILTER && rr < R) ? bf.thr[vh[i]] : INFINITY;
-        top[i] = -INFINITY;
-        nl[i] = 0;
-        ng[i] = 0;
+    for (int x = 0; x < X; ++x) {
+        const int rr = row_at(x);
+        vh[x] = head_of(rr < R ? rr : 0);
+        P[x] = prefix_of(rr);
+        thr[x] = (MODE == MODE_FILTER && rr < R) ? bf.thr[vh[x]] : INFINITY;
+        top[x] = -INFINITY;
+        nl[x] = 0;
+        ng[x] = 0;
     }
     const int seg_cap = sh.seg_cap, n_seg = sh.n_seg;
     const int sid = (int)blockIdx.x * kScanWaves + wave;
-    __shared__ uint64_t stage_lds[MODE == MODE_FILTER ? kScanWaves * 16 * kStageRow : 1];
-    uint64_t* const st0 = stage_lds + (MODE == MODE_FILTER ? wave * 16 * kStageRow : 0);
+    __shared__ uint64_t stage_lds[MODE == MODE_FILTER ? kScanWaves * 16 * NT * kStageRow : 1];
+    uint64_t* const st0 = stage_lds + (MODE == MODE_FILTER ? wave * 16 * NT * kStageRow : 0);
 
-    // append the staged candidates of rows 4 j' + i (all j') to their segments, up to the last
-    // whole run of kCandChunk entries unless `final` (see stage_flush)
-    auto flush = [&](int i, int& nl_i, int& ng_i, int64_t vh_i, bool final) {
+    // append the staged candidates of the rows at x (one per lane group) to their segments, up to
+    // the last whole run of kCandChunk entries unless `final` (see stage_flush)
+    auto flush = [&](int x, int& nl_i, int& ng_i, int64_t vh_i, bool final) {
         wave_sync();
         uint64_t* list = bf.cand + vh_i * (int64_t)sh.cand_cap;
-        uint64_t* src = st0 + (4 * j + i) * kStageRow;
+        uint64_t* src = st0 + row_at(x) * kStageRow;
         const int total = ng_i + nl_i;
         const int f = (final ? total : (total & ~(kCandChunk - 1))) - ng_i;
         for (int e = n; e < f; e += 16) {
@@ -478,7 +482,7 @@ scan_rows_kernel(Shape sh, Bufs bf, int tiles_per_wave, float* dst) {
         }
         return p < N ? p : N - 1;
     };
-    auto consume = [&](const f32x4 (&c)[4], int64_t item0) {
+    auto consume = [&](const f32x4 (&c)[NT][4], int64_t item0) {
         if (MODE == MODE_SAMPLE) {
 #pragma unroll
             for (int g = 0; g < 4; ++g) {
@@ -486,8 +490,9 @@ scan_rows_kernel(Shape sh, Bufs bf, int tiles_per_wave, float* dst) {
                 if (item < n_items) {
                     const int64_t pos = sample_pos((int)item, stride);
 #pragma unroll
-                    for (int i = 0; i < 4; ++i)   // a sample past the row's own prefix does not count
-                        if (4 * j + i < R) bf.samp[vh[i] * sh.samp_cap + item] = pos < P[i] ? c[g][i] : -INFINITY;
+                    for (int x = 0; x < X; ++x)   // a sample past the row's own prefix does not count
+                        if (row_at(x) < R)
+                            bf.samp[vh[x] * sh.samp_cap + item] = pos < P[x] ? c[x >> 2][g][x & 3] : -INFINITY;
                 }
             }
         } else if (MODE == MODE_FULL) {
@@ -495,19 +500,19 @@ scan_rows_kernel(Shape sh, Bufs bf, int tiles_per_wave, float* dst) {
             for (int g = 0; g < 4; ++g) {
                 const int64_t item = item0 + 16 * g + n;
 #pragma unroll
-                for (int i = 0; i < 4; ++i)
-                    if (item < P[i]) dst[vh[i] * sh.Ncap + item] = c[g][i];
+                for (int x = 0; x < X; ++x)
+                    if (item < P[x]) dst[vh[x] * sh.Ncap + item] = c[x >> 2][g][x & 3];
             }
         } else {
             const uint32_t below = (1u << n) - 1u;
 #pragma unroll
-            for (int i = 0; i < 4; ++i) {
+            for (int i = 0; i < X; ++i) {
                 float sc[4];
                 bool ps[4];
                 uint64_t mg[4], any = 0;
 #pragma unroll
                 for (int g = 0; g < 4; ++g) {
-                    sc[g] = c[g][i] + 0.0f;
+                    sc[g] = c[i >> 2][g][i & 3] + 0.0f;
                     const bool valid = item0 + 16 * g + n < P[i];
                     if (valid) top[i] = fmaxf(top[i], sc[g]);
                     ps[g] = valid && sc[g] >= thr[i];
@@ -523,7 +528,7 @@ scan_rows_kernel(Shape sh, Bufs bf, int tiles_per_wave, float* dst) {
                         add += __popc(gm[g]);
                     }
                     if (__ballot(nl[i] + add > kStageRow)) flush(i, nl[i], ng[i], vh[i], false);
-                    uint64_t* row_st = st0 + (4 * j + i) * kStageRow;
+                    uint64_t* row_st = st0 + row_at(i) * kStageRow;
                     int off = nl[i];
 #pragma unroll
                     for (int g = 0; g < 4; ++g) {
@@ -537,19 +542,22 @@ scan_rows_kernel(Shape sh, Bufs bf, int tiles_per_wave, float* dst) {
             }
         }
     };
-    auto mac = [&](const v8 (&b)[4][KS], f32x4 (&c)[4]) {
+    auto mac = [&](const v8 (&b)[4][KS], f32x4 (&c)[NT][4]) {
 #pragma unroll
-        for (int g = 0; g < 4; ++g) {
-            c[g] = f32x4{0.f, 0.f, 0.f, 0.f};
+        for (int t = 0; t < NT; ++t) {
 #pragma unroll
-            for (int s = 0; s < KS; ++s) c[g] = Mfma<DT>::mac(qa[s], b[g][s], c[g]);
+            for (int g = 0; g < 4; ++g) {
+                c[t][g] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int s = 0; s < KS; ++s) c[t][g] = Mfma<DT>::mac(qa[t][s], b[g][s], c[t][g]);
+            }
         }
     };
 
     struct TileB { v8 b[4][KS]; } ba, bb;
     auto load_rows = [&](TileB& t, int64_t ti) { tile_load<DT, D>(Kh, [&](int slot) { return row_of(ti * 64, slot); }, t.b); };
     auto use = [&](TileB& t, int64_t ti) {
-        f32x4 c[4];
+        f32x4 c[NT][4];
         mac(t.b, c);
         consume(c, ti * 64);
     };
@@ -567,10 +575,10 @@ scan_rows_kernel(Shape sh, Bufs bf, int tiles_per_wave, float* dst) {
     }
     if (MODE == MODE_FILTER) {
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
+        for (int i = 0; i < X; ++i) {
             flush(i, nl[i], ng[i], vh[i], true);
             for (int o = 8; o > 0; o >>= 1) top[i] = fmaxf(top[i], wave_xor(top[i], o));
-            if (n == 0 && 4 * j + i < R) {
+            if (n == 0 && row_at(i) < R) {
                 bf.seg_cnt[vh[i] * (int64_t)n_seg + sid] = (uint32_t)ng[i];
                 bf.seg_max[vh[i] * (int64_t)n_seg + sid] = top[i];
             }
@@ -652,7 +660,10 @@ static hipError_t launch_mfma(const Shape& s, const Bufs& b, int64_t n_items, fl
     dim3 block(kScanWaves * kWave);
 #define TKA_LAUNCH(DT_, D_)                                                                                 \
     do {                                                                                                    \
-        if (rows) hipLaunchKernelGGL((scan_rows_kernel<DT_, D_, MODE>), grid, block, 0, st, s, b, tpw, dst); \
+        if (rows && s.row_tiles == 2)                                                                       \
+            hipLaunchKernelGGL((scan_rows_kernel<DT_, D_, MODE, 2>), grid, block, 0, st, s, b, tpw, dst);   \
+        else if (rows)                                                                                      \
+            hipLaunchKernelGGL((scan_rows_kernel<DT_, D_, MODE, 1>), grid, block, 0, st, s, b, tpw, dst);   \
         else hipLaunchKernelGGL((scan_mfma_kernel<DT_, D_, MODE>), grid, block, 0, st, s, b, tpw, dst);     \
     } while (0)
     if (s.dtype == DT_F16 && s.D == 128) TKA_LAUNCH(DT_F16, 128);
@@ -677,8 +688,11 @@ hipError_t launch_scan_filter(const Shape& s, const Bufs& b, int64_t Nmax, hipSt
     dim3 block(kScanWaves * kWave);
 #define TKA_LAUNCH(DT_, D_)                                                                                  \
     do {                                                                                                     \
-        if (rows)                                                                                            \
-            hipLaunchKernelGGL((scan_rows_kernel<DT_, D_, MODE_FILTER>), grid, block, 0, st, s, b, 0,        \
+        if (rows && s.row_tiles == 2)                                                                        \
+            hipLaunchKernelGGL((scan_rows_kernel<DT_, D_, MODE_FILTER, 2>), grid, block, 0, st, s, b, 0,     \
+                               (float*)nullptr);                                                             \
+        else if (rows)                                                                                       \
+            hipLaunchKernelGGL((scan_rows_kernel<DT_, D_, MODE_FILTER, 1>), grid, block, 0, st, s, b, 0,     \
                                (float*)nullptr);                                                             \
         else                                                                                                 \
             hipLaunchKernelGGL((scan_mfma_kernel<DT_, D_, MODE_FILTER>), grid, block, 0, st, s, b, 0,        \
