@@ -109,10 +109,10 @@ __device__ __forceinline__ void tile_load_full(const char* tile_base, uint32_t l
 // prefetch is unconditional (past the end it re-reads a tile the wave already had, a cache
 // hit) so that the wait before the MFMAs only covers the tile they consume.  Returns the
 // first tile of the sequence at or past `end`.
-template <class Buf, class Load, class Use>
+template <bool PIPELINED, class Buf, class Load, class Use>
 __device__ __forceinline__ int64_t walk_tiles(int64_t tile, int64_t end, int64_t step, Buf& ba, Buf& bb, Load load,
                                               Use use) {
-#if TKA_SCAN_PIPELINE
+  if (PIPELINED) {
     if (tile < end) {
         load(ba, tile);
         while (true) {
@@ -129,15 +129,19 @@ __device__ __forceinline__ int64_t walk_tiles(int64_t tile, int64_t end, int64_t
             tile = t2;
         }
     }
-#else
+  } else {       // one buffer: the other waves of the compute unit cover the latency
     for (; tile < end; tile += step) {
         load(ba, tile);
         __builtin_amdgcn_sched_barrier(0);
         use(ba, tile);
     }
-#endif
+  }
     return tile;
 }
+
+// head_dim 256 makes a 64-key tile 32 KiB: two register buffers of it do not fit, and
+// with 8 waves per compute unit 256 KiB are in flight anyway.
+template <int D> struct ScanPipelined { static constexpr bool value = TKA_SCAN_PIPELINE && D <= 128; };
 
 // Scores of the tile: lane l gets res[r] = q_{head0 + r} . K[row(l)].
 template <int DT, int D>
@@ -310,12 +314,12 @@ scan_mfma_kernel(Shape sh, Bufs bf, int tiles_per_wave, float* dst) {
     auto load_rows = [&](TileB& t, int64_t ti) { tile_load<DT, D>(Kh, [&](int slot) { return row_of(ti * 64, slot); }, t.b); };
     auto use = [&](TileB& t, int64_t ti) { consume(tile_mac<DT, D>(t.b, qa), ti * 64); };
     if (MODE == MODE_SAMPLE || !TKA_SCAN_SADDR) {
-        walk_tiles(tile, tile_end, tile_step, ba, bb, load_rows, use);
+        walk_tiles<ScanPipelined<D>::value>(tile, tile_end, tile_step, ba, bb, load_rows, use);
     } else {
         // whole tiles first, then the one tile (if any) that the end of the cache cuts short
         const int64_t n_whole = N / 64;
         const uint32_t lane_off = (uint32_t)(((lane & 15) * D + (lane >> 4) * 8) * 2);
-        tile = walk_tiles(tile, tile_end < n_whole ? tile_end : n_whole, tile_step, ba, bb,
+        tile = walk_tiles<ScanPipelined<D>::value>(tile, tile_end < n_whole ? tile_end : n_whole, tile_step, ba, bb,
                           [&](TileB& t, int64_t ti) { tile_load_full<DT, D>(Kh + ti * (64 * D * 2), lane_off, t.b); }, use);
         for (; tile < tile_end; tile += tile_step) {
             load_rows(ba, tile);
@@ -562,11 +566,11 @@ scan_rows_kernel(Shape sh, Bufs bf, int tiles_per_wave, float* dst) {
         consume(c, ti * 64);
     };
     if (MODE == MODE_SAMPLE || !TKA_SCAN_SADDR) {
-        walk_tiles(tile, tile_end, tile_step, ba, bb, load_rows, use);
+        walk_tiles<ScanPipelined<D>::value>(tile, tile_end, tile_step, ba, bb, load_rows, use);
     } else {
         const int64_t n_whole = N / 64;
         const uint32_t lane_off = (uint32_t)((n * D + j * 8) * 2);
-        tile = walk_tiles(tile, tile_end < n_whole ? tile_end : n_whole, tile_step, ba, bb,
+        tile = walk_tiles<ScanPipelined<D>::value>(tile, tile_end < n_whole ? tile_end : n_whole, tile_step, ba, bb,
                           [&](TileB& t, int64_t ti) { tile_load_full<DT, D>(Kh + ti * (64 * D * 2), lane_off, t.b); }, use);
         for (; tile < tile_end; tile += tile_step) {
             load_rows(ba, tile);
@@ -636,7 +640,7 @@ scan_generic_kernel(Shape sh, Bufs bf, int rows_per_block, float* dst) {
 }
 
 bool scan_mfma_supported(const Shape& s) {
-    return (s.dtype == DT_F16 || s.dtype == DT_BF16) && (s.D == 64 || s.D == 128) && s.G >= 1 && s.G <= 16;
+    return (s.dtype == DT_F16 || s.dtype == DT_BF16) && (s.D == 64 || s.D == 128 || s.D == 256) && s.G >= 1 && s.G <= 16;
 }
 
 static int tiles_per_wave_for(int64_t n_items, int B, int Hkv) {
@@ -670,6 +674,8 @@ static hipError_t launch_mfma(const Shape& s, const Bufs& b, int64_t n_items, fl
     else if (s.dtype == DT_F16 && s.D == 64) TKA_LAUNCH(DT_F16, 64);
     else if (s.dtype == DT_BF16 && s.D == 128) TKA_LAUNCH(DT_BF16, 128);
     else if (s.dtype == DT_BF16 && s.D == 64) TKA_LAUNCH(DT_BF16, 64);
+    else if (s.dtype == DT_F16 && s.D == 256) TKA_LAUNCH(DT_F16, 256);
+    else if (s.dtype == DT_BF16 && s.D == 256) TKA_LAUNCH(DT_BF16, 256);
     else return hipErrorInvalidValue;
 #undef TKA_LAUNCH
     return hipGetLastError();
@@ -702,6 +708,8 @@ hipError_t launch_scan_filter(const Shape& s, const Bufs& b, int64_t Nmax, hipSt
     else if (s.dtype == DT_F16 && s.D == 64) TKA_LAUNCH(DT_F16, 64);
     else if (s.dtype == DT_BF16 && s.D == 128) TKA_LAUNCH(DT_BF16, 128);
     else if (s.dtype == DT_BF16 && s.D == 64) TKA_LAUNCH(DT_BF16, 64);
+    else if (s.dtype == DT_F16 && s.D == 256) TKA_LAUNCH(DT_F16, 256);
+    else if (s.dtype == DT_BF16 && s.D == 256) TKA_LAUNCH(DT_BF16, 256);
     else return hipErrorInvalidValue;
 #undef TKA_LAUNCH
     return hipGetLastError();

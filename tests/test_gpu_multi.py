@@ -84,6 +84,8 @@ def run_multi_case(q, K, V, delta, dtype, k, causal, window=0, path=ta.PATH_AUTO
     (wl.F16, 4, 4, 1, 700, 128, 60, True, 0, ta.PATH_FULL),         # all scores stored, row-tile kernel
     (wl.F32, 3, 4, 2, 3000, 64, 50, True, 0, ta.PATH_AUTO),         # fp32: plain-FMA scorer per query
     (wl.F16, 16, 2, 2, 34000, 128, 150, True, 0, ta.PATH_AUTO),     # MQA-like: 16 queries x 1 head
+    (wl.F16, 3, 16, 2, 36000, 256, 100, True, 0, ta.PATH_AUTO),     # d = 256, G = 8: 24 rows in two row tiles
+    (wl.BF16, 2, 8, 2, 40000, 256, 300, False, 50, ta.PATH_AUTO),   # d = 256, 8 rows, window
     (wl.F16, 33, 4, 1, 33500, 64, 100, True, 16, ta.PATH_AUTO),     # 9 row blocks, the last with one query
 ])
 def test_multi_query_decode(dtype, M, Hq, Hkv, N, d, k, causal, window, path):
