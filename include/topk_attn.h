@@ -64,7 +64,7 @@ enum {
     TOPK_ATTN_INDEX_INT8 = 1    /* plus a compressed copy of every key row: int8 codes
                                    rint(x * 127 / amax) and one fp32 scale amax / 127 per row
                                    (amax = largest magnitude of the row; rows below 2^-100 are coded
-                                   as zero).  16-bit dtypes, head_dim 64 or 128, Hq/Hkv <= 4. */
+                                   as zero).  16-bit dtypes, head_dim 64, 128 or 256, Hq/Hkv <= 4. */
 };
 
 typedef struct {

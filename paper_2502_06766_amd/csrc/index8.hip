@@ -31,7 +31,7 @@ quantize_rows_kernel(const char* __restrict__ src, int64_t rows_per_head, int64_
                      int64_t n_rows, int D, int8_t* __restrict__ dst, float* __restrict__ scale,
                      int64_t dst_head_stride_rows) {
     constexpr int EPL = Elem<DT>::kPerLoad;          // 8 for 16-bit storage
-    const int lpr = D / EPL;                         // lanes per row: 8 or 16
+    const int lpr = D / EPL;                         // lanes per row: 8, 16 or 32
     const int rows_per_pass = 256 / lpr;
     const int rs = threadIdx.x / lpr, c = threadIdx.x % lpr;
     for (int64_t base = (int64_t)blockIdx.x * rows_per_pass; base < n_rows; base += (int64_t)gridDim.x * rows_per_pass) {
@@ -71,7 +71,7 @@ quantize_rows_kernel(const char* __restrict__ src, int64_t rows_per_head, int64_
 }
 
 bool index8_supported(int dtype, int D, int G) {
-    return (dtype == DT_F16 || dtype == DT_BF16) && (D == 64 || D == 128) && G >= 1 && G <= 4;
+    return (dtype == DT_F16 || dtype == DT_BF16) && (D == 64 || D == 128 || D == 256) && G >= 1 && G <= 4;
 }
 
 hipError_t launch_quantize_rows(int dtype, int D, const void* src, int64_t rows_per_head, int64_t src_head_stride_bytes,
@@ -339,6 +339,7 @@ static hipError_t launch_scan8(const Shape& s, const Bufs& b, int64_t n_items, f
     }
     if (s.D == 128) hipLaunchKernelGGL((scan8_kernel<128, MODE>), grid, block, 0, st, s, b, tpw, dst);
     else if (s.D == 64) hipLaunchKernelGGL((scan8_kernel<64, MODE>), grid, block, 0, st, s, b, tpw, dst);
+    else if (s.D == 256) hipLaunchKernelGGL((scan8_kernel<256, MODE>), grid, block, 0, st, s, b, tpw, dst);
     else return hipErrorInvalidValue;
     return hipGetLastError();
 }

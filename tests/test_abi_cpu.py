@@ -89,8 +89,8 @@ def test_int8_index_storage_and_supported_shapes():
     up = lambda x: (x + 255) // 256 * 256
     assert plain == 2 * up(rows * 128 * 2)
     assert with_index == plain + up(rows * 128) + up(rows * 4)        # codes, then one fp32 scale per row
-    # fp32 caches, head_dim 256 and head groups above 4 have no int8 index
-    for kw in (dict(dtype=ta.F32), dict(dtype=ta.F16, head_dim=256), dict(dtype=ta.F16, n_q_heads=16)):
+    # fp32 caches, head_dim 32 and head groups above 4 have no int8 index
+    for kw in (dict(dtype=ta.F32), dict(dtype=ta.F16, head_dim=32), dict(dtype=ta.F16, n_q_heads=16)):
         cfg = ta.make_config(**{**base, **kw, "index_kind": ta.INDEX_INT8})
         assert ta.topk_attn_kv_bytes(cfg) == 0
         h = ctypes.c_void_p()

@@ -38,7 +38,7 @@ def index_views(cache, L, B, Hkv, Ncap, d):
     return codes, scales
 
 
-@pytest.mark.parametrize("dtype,d", [(wl.F16, 128), (wl.BF16, 64), (wl.BF16, 128)])
+@pytest.mark.parametrize("dtype,d", [(wl.F16, 128), (wl.BF16, 64), (wl.BF16, 128), (wl.F16, 256)])
 def test_index_codes_and_scales_bit_exact(dtype, d):
     g = np.random.default_rng(d + dtype)
     L, B, Hq, Hkv, Ncap = 2, 2, 4, 2, 700
@@ -65,7 +65,8 @@ def test_index_codes_and_scales_bit_exact(dtype, d):
         cache.close()
 
 
-@pytest.mark.parametrize("dtype,Hq,Hkv,N,d", [(wl.F16, 8, 2, 3001, 128), (wl.BF16, 3, 3, 777, 64), (wl.F16, 4, 2, 64, 64)])
+@pytest.mark.parametrize("dtype,Hq,Hkv,N,d", [(wl.F16, 8, 2, 3001, 128), (wl.BF16, 3, 3, 777, 64), (wl.F16, 4, 2, 64, 64),
+                                                 (wl.BF16, 4, 1, 1000, 256)])
 def test_index_approximate_scores_bit_exact(dtype, Hq, Hkv, N, d):
     q, K, V = rand_case(Hq, Hkv, N, d, dtype, N, seed=N)
     cache = ta.TopkAttnCache(1, 1, Hq, Hkv, d, N + 50, 8, dtype, index_kind=ta.INDEX_INT8)
@@ -138,6 +139,7 @@ def run_index_case(q, K, V, dtype, k, window=0, label="", expect_fallbacks=0):
     (wl.BF16, 3, 3, 33333, 128, 500, 0),       # G = 1
     (wl.F16, 12, 4, 70001, 128, 1, 0),         # G = 3, k = 1
     (wl.F16, 8, 2, 40000, 128, 400, 1000),     # with the recent-token window
+    (wl.BF16, 4, 2, 45000, 256, 500, 0),       # d = 256
 ])
 def test_index_decode_recall(dtype, Hq, Hkv, N, d, k, window):
     g = np.random.default_rng(N + k)

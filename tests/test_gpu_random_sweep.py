@@ -36,7 +36,7 @@ def draw_case(rng):
     if causal and N < M:
         M = 1
     window = min(int(rng.choice([0, 0, 0, 1, 17, 300, N, N + 3])) if rng.random() < 0.4 else 0, 2000)
-    use_index = dtype != wl.F32 and d in (64, 128) and G <= 4 and M == 1 and rng.random() < 0.35
+    use_index = dtype != wl.F32 and d in (64, 128, 256) and G <= 4 and M == 1 and rng.random() < 0.35
     path = ta.PATH_INDEX if use_index else int(rng.choice([ta.PATH_AUTO, ta.PATH_FULL, ta.PATH_FILTER]))
     if M > 1 and N >= 64:
         k = max(1, min(k, N // 8))       # many rows per KV head: keep the margin enforcement convergent
