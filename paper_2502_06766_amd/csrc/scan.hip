@@ -15,7 +15,7 @@
 //            wave appends to a private segment of the head's candidate list (plain stores,
 //            no atomics, so the list order is fixed by the launch geometry alone)
 //   full   : score every key and store the fp32 scores
-// Other dtypes / head groupings go through a plain FMA kernel (full only).
+// fp32 caches go through a plain FMA kernel (full only).
 #include "device_utils.h"
 #include "internal.h"
 
@@ -590,8 +590,7 @@ scan_rows_kernel(Shape sh, Bufs bf, int tiles_per_wave, float* dst) {
     }
 }
 
-// Plain FMA scoring for every shape the MFMA kernel does not take (fp32 caches, other
-// head groupings): a row of D elements is spread over D*e/16 lanes, 16 bytes each.
+// Plain FMA scoring for what the MFMA kernels do not take (fp32 caches): a row of D elements is spread over D*e/16 lanes, 16 bytes each.
 template <int DT>
 __global__ void __launch_bounds__(256)
 scan_generic_kernel(Shape sh, Bufs bf, int rows_per_block, float* dst) {
@@ -640,7 +639,7 @@ scan_generic_kernel(Shape sh, Bufs bf, int rows_per_block, float* dst) {
 }
 
 bool scan_mfma_supported(const Shape& s) {
-    return (s.dtype == DT_F16 || s.dtype == DT_BF16) && (s.D == 64 || s.D == 128 || s.D == 256) && s.G >= 1 && s.G <= 16;
+    return (s.dtype == DT_F16 || s.dtype == DT_BF16) && (s.D == 32 || s.D == 64 || s.D == 128 || s.D == 256) && s.G >= 1 && s.G <= 16;
 }
 
 static int tiles_per_wave_for(int64_t n_items, int B, int Hkv) {
@@ -676,6 +675,8 @@ static hipError_t launch_mfma(const Shape& s, const Bufs& b, int64_t n_items, fl
     else if (s.dtype == DT_BF16 && s.D == 64) TKA_LAUNCH(DT_BF16, 64);
     else if (s.dtype == DT_F16 && s.D == 256) TKA_LAUNCH(DT_F16, 256);
     else if (s.dtype == DT_BF16 && s.D == 256) TKA_LAUNCH(DT_BF16, 256);
+    else if (s.dtype == DT_F16 && s.D == 32) TKA_LAUNCH(DT_F16, 32);
+    else if (s.dtype == DT_BF16 && s.D == 32) TKA_LAUNCH(DT_BF16, 32);
     else return hipErrorInvalidValue;
 #undef TKA_LAUNCH
     return hipGetLastError();
@@ -710,6 +711,8 @@ hipError_t launch_scan_filter(const Shape& s, const Bufs& b, int64_t Nmax, hipSt
     else if (s.dtype == DT_BF16 && s.D == 64) TKA_LAUNCH(DT_BF16, 64);
     else if (s.dtype == DT_F16 && s.D == 256) TKA_LAUNCH(DT_F16, 256);
     else if (s.dtype == DT_BF16 && s.D == 256) TKA_LAUNCH(DT_BF16, 256);
+    else if (s.dtype == DT_F16 && s.D == 32) TKA_LAUNCH(DT_F16, 32);
+    else if (s.dtype == DT_BF16 && s.D == 32) TKA_LAUNCH(DT_BF16, 32);
     else return hipErrorInvalidValue;
 #undef TKA_LAUNCH
     return hipGetLastError();

@@ -86,6 +86,7 @@ def run_multi_case(q, K, V, delta, dtype, k, causal, window=0, path=ta.PATH_AUTO
     (wl.F16, 16, 2, 2, 34000, 128, 150, True, 0, ta.PATH_AUTO),     # MQA-like: 16 queries x 1 head
     (wl.F16, 3, 16, 2, 36000, 256, 100, True, 0, ta.PATH_AUTO),     # d = 256, G = 8: 24 rows in two row tiles
     (wl.BF16, 2, 8, 2, 40000, 256, 300, False, 50, ta.PATH_AUTO),   # d = 256, 8 rows, window
+    (wl.F16, 5, 8, 2, 35000, 32, 120, True, 0, ta.PATH_AUTO),       # d = 32, 20 rows
     (wl.F16, 33, 4, 1, 33500, 64, 100, True, 16, ta.PATH_AUTO),     # 9 row blocks, the last with one query
 ])
 def test_multi_query_decode(dtype, M, Hq, Hkv, N, d, k, causal, window, path):

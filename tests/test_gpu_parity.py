@@ -107,6 +107,7 @@ def test_k_larger_than_n_pads():
     (wl.F16, 12, 4, 70001, 128, 1),      # G = 3, k = 1
     (wl.BF16, 8, 2, 50003, 256, 700),    # d = 256: one tile buffer per wave
     (wl.F16, 2, 2, 33000, 256, 64),      # d = 256, G = 1
+    (wl.BF16, 8, 2, 60001, 32, 200),     # d = 32: 4 KiB tiles
 ])
 def test_filter_path_sweep(dtype, Hq, Hkv, N, d, k):
     q, K, V = rand_case(Hq, Hkv, N, d, dtype, k, seed=N + k)
