@@ -125,7 +125,7 @@ def main() -> int:
     alg_bytes = Hkv * N * d * e + M * (Hq * k * d * e + Hq * d * (e + 4) + Hq * k * 4)
     keys_per_s = Hkv * N / (ms_per_step * 1e-3)
     G = Hq // Hkv
-    n_qblk = 1 if M == 1 else -(-M // ((32 if M * G > 16 else 16) // G))     # passes over the keys: one per block of 16 or 32 rows
+    n_qblk = 1 if M == 1 else -(-M * G // (32 if M * G > 16 else 16))     # passes over the keys: one per block of 16 or 32 rows
     scan_bytes = k_bytes * n_qblk
     if args.index and M == 1:
         scan_bytes = Hkv * N * (d + 4)                          # int8 codes and one fp32 scale per key

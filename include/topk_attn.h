@@ -72,7 +72,7 @@ typedef struct {
     int32_t n_layers;       /* L: independent caches, one per transformer layer */
     int32_t n_seqs;         /* B: sequences decoded together in one call */
     int32_t n_q_heads;      /* Hq */
-    int32_t n_kv_heads;     /* Hkv, must divide Hq; Hq/Hkv <= 16 */
+    int32_t n_kv_heads;     /* Hkv, must divide Hq; Hq/Hkv <= 128 (<= 16 for fp32 caches) */
     int32_t head_dim;       /* d in {32, 64, 128, 256} */
     int64_t max_tokens;     /* capacity N_cap per (layer, sequence) */
     int32_t max_k;          /* largest k decode will be called with; sizes the workspace */

@@ -41,7 +41,8 @@ bool config_ok(const topk_attn_config* c, int* why) {
     if (c->dtype != TOPK_ATTN_F32 && c->dtype != TOPK_ATTN_F16 && c->dtype != TOPK_ATTN_BF16) return false;
     if (c->head_dim != 32 && c->head_dim != 64 && c->head_dim != 128 && c->head_dim != 256) return false;
     if (c->n_q_heads % c->n_kv_heads) return false;
-    if (c->n_q_heads / c->n_kv_heads > 16) return false;
+    if (c->n_q_heads / c->n_kv_heads > 128) return false;
+    if (c->dtype == TOPK_ATTN_F32 && c->n_q_heads / c->n_kv_heads > 16) return false;   // plain-FMA scorer
     if (c->index_kind == TOPK_ATTN_INDEX_INT8 &&
         !index8_supported(c->dtype, c->head_dim, c->n_q_heads / c->n_kv_heads))
         return false;
@@ -284,8 +285,7 @@ static void fill_call(topk_attn_t* h, int layer, const void* q, int k, int n_que
     s->Bc = c.n_seqs; s->M = n_queries; s->causal = 0; s->B = c.n_seqs * n_queries;
     s->Hq = c.n_q_heads; s->Hkv = c.n_kv_heads; s->G = c.n_q_heads / c.n_kv_heads;
     s->row_tiles = n_queries * s->G > 16 ? 2 : 1;
-    s->q_per_blk = 16 * s->row_tiles / s->G < n_queries ? 16 * s->row_tiles / s->G : n_queries;     // G <= 16
-    s->n_qblk = (n_queries + s->q_per_blk - 1) / s->q_per_blk;
+    s->n_qblk = (n_queries * s->G + 16 * s->row_tiles - 1) / (16 * s->row_tiles);
     s->D = c.head_dim; s->dtype = c.dtype; s->k = k; s->window = 0; s->max_k = c.max_k;
     s->cand_cap = h->ws.cand_cap; s->n_seg = 4; s->seg_cap = (h->ws.cand_cap / 4) & ~(kCandChunk - 1); s->samp_cap = kSampMax; s->n_chunk_cap = h->ws.n_chunk_cap;
     s->Ncap = c.max_tokens;

@@ -26,8 +26,7 @@ struct Shape {
     int M;            // queries per cache sequence in this call (1 for plain decode)
     int causal;       // query m of M sees only the first len - (M - 1 - m) tokens
     int row_tiles;    // row-tile scan: 16-row tiles per pass over the keys (1 or 2)
-    int q_per_blk;    // row-tile scan: queries per block of <= 16 * row_tiles (query, head) rows
-    int n_qblk;       // row-tile scan: blocks per cache sequence
+    int n_qblk;       // row-tile scan: blocks of 16 * row_tiles (query, head) rows per KV head
     int indexed;      // the scan reads the int8 key index; candidates are re-scored exactly afterwards
     int cand_est;     // candidates per head expected at most (sizes the selection's register cache)
     int k;            // requested k (k_eff = min(k, searched prefix of sequence b))

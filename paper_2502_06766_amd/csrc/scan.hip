@@ -377,22 +377,22 @@ scan_rows_kernel(Shape sh, Bufs bf, int tiles_per_wave, float* dst) {
     const int G = sh.G, M = sh.M;
     const int bc = (int)blockIdx.z / sh.n_qblk, blk = (int)blockIdx.z % sh.n_qblk;   // cache sequence, row block
     const int kvh = blockIdx.y;
-    const int m0 = blk * sh.q_per_blk;                                // first query of the block
-    const int mq = sh.q_per_blk < M - m0 ? sh.q_per_blk : M - m0;     // its queries
-    const int R = mq * G;                                             // its rows, <= 16 NT
+    // the M * G (query, head) rows of the KV head, query-major, are cut into blocks of 16 NT rows
+    const int row0 = blk * 16 * NT;                                   // first row of the block
+    const int R = M * G - row0 < 16 * NT ? M * G - row0 : 16 * NT;    // its rows
     const int lane = lane_id();
     const int j = lane >> 4, n = lane & 15;
     const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
     const int64_t Nc = bf.len[bc];
     const int64_t N = prefix_len(Nc, sh.window);      // longest searched prefix of the sequence's queries
 
-    // row rr of the block is head kvh * G + rr % G of query m0 + rr / G
+    // row rr of the block is head kvh * G + (row0 + rr) % G of query (row0 + rr) / G
     auto head_of = [&](int rr) -> int64_t {
-        return ((int64_t)bc * M + m0 + rr / G) * sh.Hq + (int64_t)kvh * G + rr % G;
+        return ((int64_t)bc * M + (row0 + rr) / G) * sh.Hq + (int64_t)kvh * G + (row0 + rr) % G;
     };
     auto prefix_of = [&](int rr) -> int {   // keys row rr searches (0 for rows the block does not have)
         if (rr >= R) return 0;
-        const int m = m0 + rr / G;
+        const int m = (row0 + rr) / G;
         return (int)prefix_len(Nc - (sh.causal ? M - 1 - m : 0), sh.window);
     };
 
@@ -639,7 +639,7 @@ scan_generic_kernel(Shape sh, Bufs bf, int rows_per_block, float* dst) {
 }
 
 bool scan_mfma_supported(const Shape& s) {
-    return (s.dtype == DT_F16 || s.dtype == DT_BF16) && (s.D == 32 || s.D == 64 || s.D == 128 || s.D == 256) && s.G >= 1 && s.G <= 16;
+    return (s.dtype == DT_F16 || s.dtype == DT_BF16) && (s.D == 32 || s.D == 64 || s.D == 128 || s.D == 256) && s.G >= 1;
 }
 
 static int tiles_per_wave_for(int64_t n_items, int B, int Hkv) {

@@ -50,7 +50,8 @@ def test_kv_bytes_is_2ndl():
     (dict(head_dim=96), ta.EUNSUPPORTED),
     (dict(dtype=7), ta.EUNSUPPORTED),
     (dict(n_q_heads=30), ta.EUNSUPPORTED),          # 30 % 8 != 0
-    (dict(n_q_heads=8 * 32), ta.EUNSUPPORTED),       # group of 32 > 16
+    (dict(n_q_heads=8 * 129), ta.EUNSUPPORTED),      # group of 129 > 128
+    (dict(n_q_heads=8 * 32, dtype=ta.F32), ta.EUNSUPPORTED),   # fp32 caches: groups up to 16
     (dict(n_layers=0), ta.EINVAL),
     (dict(max_k=0), ta.EINVAL),
     (dict(max_tokens=1 << 31), ta.EINVAL),

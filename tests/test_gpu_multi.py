@@ -24,6 +24,9 @@ DEV = torch.device("cuda", 0) if torch.cuda.is_available() else None
     (wl.BF16, 24, 2, 70001, 128, 1, ta.PATH_AUTO),       # G = 12, k = 1
     (wl.F16, 14, 2, 4097, 64, 130, ta.PATH_FULL),        # G = 7, all scores stored
     (wl.F16, 16, 2, 3000, 128, 200, ta.PATH_FILTER),     # short cache forced through the filter
+    (wl.BF16, 64, 2, 36000, 128, 100, ta.PATH_AUTO),     # G = 32: one block of two row tiles per KV head
+    (wl.F16, 48, 1, 40001, 64, 50, ta.PATH_AUTO),        # multi-query attention, 48 heads on one KV head: two blocks
+    (wl.F16, 40, 1, 2000, 128, 30, ta.PATH_FULL),        # G = 40, all scores stored
 ])
 def test_wide_head_groups(dtype, Hq, Hkv, N, d, k, path):
     q, K, V = rand_case(Hq, Hkv, N, d, dtype, k, seed=N + k)
@@ -87,6 +90,7 @@ def run_multi_case(q, K, V, delta, dtype, k, causal, window=0, path=ta.PATH_AUTO
     (wl.F16, 3, 16, 2, 36000, 256, 100, True, 0, ta.PATH_AUTO),     # d = 256, G = 8: 24 rows in two row tiles
     (wl.BF16, 2, 8, 2, 40000, 256, 300, False, 50, ta.PATH_AUTO),   # d = 256, 8 rows, window
     (wl.F16, 5, 8, 2, 35000, 32, 120, True, 0, ta.PATH_AUTO),       # d = 32, 20 rows
+    (wl.F16, 3, 20, 1, 36000, 128, 64, True, 0, ta.PATH_AUTO),      # G = 20, 60 rows: blocks cut across queries
     (wl.F16, 33, 4, 1, 33500, 64, 100, True, 16, ta.PATH_AUTO),     # 9 row blocks, the last with one query
 ])
 def test_multi_query_decode(dtype, M, Hq, Hkv, N, d, k, causal, window, path):
