@@ -21,7 +21,9 @@ DEV = torch.device("cuda", 0) if torch.cuda.is_available() else None
 def draw_case(rng):
     dtype = int(rng.choice([wl.F16, wl.BF16, wl.F32], p=[0.45, 0.4, 0.15]))
     d = int(rng.choice([32, 64, 128, 256], p=[0.1, 0.3, 0.5, 0.1]))
-    G = int(rng.choice([1, 2, 3, 4, 5, 8, 12, 16]))
+    G = int(rng.choice([1, 2, 3, 4, 5, 8, 12, 16, 20, 32, 64]))
+    if dtype == wl.F32:
+        G = min(G, 16)            # fp32 caches: groups up to 16
     Hkv = int(rng.integers(1, 4))
     kind = rng.choice(["tiny", "small", "mid", "big"], p=[0.2, 0.3, 0.3, 0.2])
     N = int({"tiny": rng.integers(1, 200), "small": rng.integers(200, 5000), "mid": rng.integers(5000, 40000),
