@@ -116,6 +116,14 @@ int topk_attn_create(const topk_attn_config* cfg, topk_attn_t** out);
 int topk_attn_append_kv(topk_attn_t* h, int layer, int seq, const void* k_new, const void* v_new,
                         int64_t n_new, int64_t token_stride, int64_t head_stride, void* hip_stream);
 
+/* The per-step concat of Algorithm 1 for a whole batch: append n_new tokens to EVERY
+ * sequence of `layer` in one call (two small launches whatever B is; topk_attn_append_kv
+ * costs one per sequence).  k_new / v_new: device [B, n_new, Hkv, d], contiguous, 16-byte
+ * aligned.  Errors: EINVAL, ECAPACITY if any sequence would exceed max_tokens (nothing is
+ * enqueued then).  n_new == 0 is a no-op. */
+int topk_attn_append_step(topk_attn_t* h, int layer, const void* k_new, const void* v_new, int64_t n_new,
+                          void* hip_stream);
+
 /* One decode step of `layer` for all B sequences: steps 1-3 above over all tokens
  * currently cached for (layer, b).  k_eff = min(k, N_b).
  *   q     device [B, Hq, d] in the cache dtype

@@ -119,6 +119,27 @@ __global__ void append_kernel(const char* __restrict__ ksrc, const char* __restr
 
 __global__ void set_len_kernel(int32_t* len_slot, int32_t v) { *len_slot = v; }
 
+// n_new tokens for every sequence of a layer: source [B][n_new][Hkv][row], destination row
+// len[b] + t of (b, h).  The lengths are bumped by a second kernel once every block has read them.
+__global__ void append_step_kernel(const char* __restrict__ ksrc, const char* __restrict__ vsrc, char* __restrict__ kdst,
+                                   char* __restrict__ vdst, const int32_t* __restrict__ len, int64_t total, int64_t n_new,
+                                   int Hkv, int chunks_per_row, int64_t head_b) {
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (int64_t)gridDim.x * blockDim.x) {
+        const int c = (int)(i % chunks_per_row);
+        const int64_t th = i / chunks_per_row;
+        const int h = (int)(th % Hkv);
+        const int64_t bt = th / Hkv;
+        const int64_t t = bt % n_new, b = bt / n_new;
+        const int64_t d_o = (b * Hkv + h) * head_b + (((int64_t)len[b] + t) * chunks_per_row + c) * 16;
+        *reinterpret_cast<u32x4*>(kdst + d_o) = *reinterpret_cast<const u32x4*>(ksrc + i * 16);
+        *reinterpret_cast<u32x4*>(vdst + d_o) = *reinterpret_cast<const u32x4*>(vsrc + i * 16);
+    }
+}
+__global__ void bump_len_kernel(int32_t* len, int B, int32_t n_new) {
+    const int b = blockIdx.x * blockDim.x + threadIdx.x;
+    if (b < B) len[b] += n_new;
+}
+
 // Streaming read of n_vec 16-byte vectors: every wave walks 16 KiB tiles (16 independent
 // 1 KiB-per-instruction loads in flight), the access shape of the key scan without its work.
 __global__ void __launch_bounds__(256) read_probe_kernel(const u32x4* __restrict__ src, size_t n_vec, uint32_t* sink) {
@@ -276,6 +297,44 @@ int topk_attn_append_kv(topk_attn_t* h, int layer, int seq, const void* k_new, c
             return TOPK_ATTN_EDEVICE;
     }
     h->len[slot] = cur + n_new;
+    return TOPK_ATTN_OK;
+}
+
+int topk_attn_append_step(topk_attn_t* h, int layer, const void* k_new, const void* v_new, int64_t n_new,
+                          void* hip_stream) {
+    if (!h || layer < 0 || layer >= h->cfg.n_layers || n_new < 0) return TOPK_ATTN_EINVAL;
+    if (n_new == 0) return TOPK_ATTN_OK;
+    if (!k_new || !v_new || (((uintptr_t)k_new | (uintptr_t)v_new) & 15)) return TOPK_ATTN_EINVAL;
+    const topk_attn_config& c = h->cfg;
+    const int B = c.n_seqs;
+    for (int b = 0; b < B; ++b)
+        if (h->len[(size_t)layer * B + b] + n_new > c.max_tokens) return TOPK_ATTN_ECAPACITY;
+    hipStream_t st = (hipStream_t)hip_stream;
+    const int e = elem_bytes(c.dtype);
+    const int64_t row_b = (int64_t)c.head_dim * e, head_b = c.max_tokens * row_b;
+    const int64_t layer_off = (int64_t)layer * B * c.n_kv_heads * head_b;
+    char* kdst = static_cast<char*>(c.kv_storage) + layer_off;
+    char* vdst = static_cast<char*>(c.kv_storage) + h->kv_half + layer_off;
+    int32_t* len_dev = reinterpret_cast<int32_t*>(static_cast<char*>(c.workspace) + h->ws.len) + (size_t)layer * B;
+    const int chunks = (int)(row_b / 16);
+    const int64_t total = (int64_t)B * n_new * c.n_kv_heads * chunks;
+    int64_t blocks = (total + 255) / 256;
+    if (blocks > 65536) blocks = 65536;
+    hipLaunchKernelGGL(append_step_kernel, dim3((unsigned)blocks), dim3(256), 0, st, static_cast<const char*>(k_new),
+                       static_cast<const char*>(v_new), kdst, vdst, len_dev, total, n_new, c.n_kv_heads, chunks, head_b);
+    if (hipGetLastError() != hipSuccess) return TOPK_ATTN_EDEVICE;
+    if (c.index_kind == TOPK_ATTN_INDEX_INT8) {
+        char* base = static_cast<char*>(c.kv_storage) + 2 * h->kv_half;
+        const int64_t layer_rows = (int64_t)layer * B * c.n_kv_heads * c.max_tokens;
+        int8_t* codes = reinterpret_cast<int8_t*>(base) + layer_rows * c.head_dim;
+        float* scales = reinterpret_cast<float*>(base + index_codes_bytes(&c)) + layer_rows;
+        if (launch_quantize_step(c.dtype, c.head_dim, k_new, B, n_new, c.n_kv_heads, c.max_tokens, len_dev, codes, scales,
+                                 st) != hipSuccess)
+            return TOPK_ATTN_EDEVICE;
+    }
+    hipLaunchKernelGGL(bump_len_kernel, dim3((unsigned)((B + 255) / 256)), dim3(256), 0, st, len_dev, B, (int32_t)n_new);
+    if (hipGetLastError() != hipSuccess) return TOPK_ATTN_EDEVICE;
+    for (int b = 0; b < B; ++b) h->len[(size_t)layer * B + b] += n_new;
     return TOPK_ATTN_OK;
 }
 

@@ -70,6 +70,70 @@ quantize_rows_kernel(const char* __restrict__ src, int64_t rows_per_head, int64_
     }
 }
 
+// Row coding of the tokens a batched append adds: source rows [B][n_new][Hkv] (contiguous),
+// row (b, t, h) is coded into row len[b] + t of (b, h) of the layer's index.
+template <int DT>
+__global__ void __launch_bounds__(256)
+quantize_step_kernel(const char* __restrict__ src, int64_t n_rows, int64_t n_new, int Hkv, int64_t Ncap, int D,
+                     const int32_t* __restrict__ len, int8_t* __restrict__ dst, float* __restrict__ scale) {
+    constexpr int EPL = Elem<DT>::kPerLoad;
+    const int lpr = D / EPL;
+    const int rows_per_pass = 256 / lpr;
+    const int rs = threadIdx.x / lpr, c = threadIdx.x % lpr;
+    for (int64_t base = (int64_t)blockIdx.x * rows_per_pass; base < n_rows; base += (int64_t)gridDim.x * rows_per_pass) {
+        const int64_t r = base + rs;
+        const bool valid = r < n_rows;
+        const int64_t rr = valid ? r : n_rows - 1;
+        const int h = (int)(rr % Hkv);
+        const int64_t bt = rr / Hkv, t = bt % n_new, b = bt / n_new;
+        const u32x4 raw = *reinterpret_cast<const u32x4*>(src + (rr * D + c * EPL) * Elem<DT>::kBytes);
+        float x[EPL];
+        Elem<DT>::widen(raw, x);
+        float amax = 0.f;
+#pragma unroll
+        for (int e = 0; e < EPL; ++e) amax = fmaxf(amax, fabsf(x[e]));
+        for (int o = 1; o < lpr; o <<= 1) amax = fmaxf(amax, wave_xor(amax, o));
+        const bool live = amax >= kTinyRow;
+        const float inv = live ? 127.0f / amax : 0.f;
+        uint32_t w[EPL / 4];
+#pragma unroll
+        for (int i = 0; i < EPL / 4; ++i) {
+            uint32_t p = 0;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const int code = (int)rintf(x[4 * i + e] * inv);
+                p |= ((uint32_t)code & 0xFFu) << (8 * e);
+            }
+            w[i] = p;
+        }
+        if (valid) {
+            const int64_t drow = (b * Hkv + h) * Ncap + (int64_t)len[b] + t;
+            uint32_t* d = reinterpret_cast<uint32_t*>(dst + drow * D + c * EPL);
+#pragma unroll
+            for (int i = 0; i < EPL / 4; ++i) d[i] = w[i];
+            if (c == 0) scale[drow] = live ? amax / 127.0f : 0.f;
+        }
+    }
+}
+
+hipError_t launch_quantize_step(int dtype, int D, const void* src, int B, int64_t n_new, int Hkv, int64_t Ncap,
+                                const int32_t* len, int8_t* codes, float* scale, hipStream_t st) {
+    const int64_t n_rows = (int64_t)B * n_new * Hkv;
+    if (n_rows <= 0) return hipSuccess;
+    const int rows_per_pass = 256 / (D / 8);
+    int64_t blocks = (n_rows + rows_per_pass - 1) / rows_per_pass;
+    if (blocks > 65536) blocks = 65536;
+    if (dtype == DT_F16)
+        hipLaunchKernelGGL((quantize_step_kernel<DT_F16>), dim3((unsigned)blocks), dim3(256), 0, st,
+                           static_cast<const char*>(src), n_rows, n_new, Hkv, Ncap, D, len, codes, scale);
+    else if (dtype == DT_BF16)
+        hipLaunchKernelGGL((quantize_step_kernel<DT_BF16>), dim3((unsigned)blocks), dim3(256), 0, st,
+                           static_cast<const char*>(src), n_rows, n_new, Hkv, Ncap, D, len, codes, scale);
+    else
+        return hipErrorInvalidValue;
+    return hipGetLastError();
+}
+
 bool index8_supported(int dtype, int D, int G) {
     return (dtype == DT_F16 || dtype == DT_BF16) && (D == 64 || D == 128 || D == 256) && G >= 1 && G <= 4;
 }

@@ -174,6 +174,8 @@ hipError_t launch_gather(const Shape& s, const Bufs& b, hipStream_t st);
 bool index8_supported(int dtype, int D, int G);
 hipError_t launch_quantize_rows(int dtype, int D, const void* src, int64_t rows_per_head, int64_t src_head_stride_bytes,
                                 int n_heads, int8_t* dst, float* scale, int64_t dst_head_stride_rows, hipStream_t st);
+hipError_t launch_quantize_step(int dtype, int D, const void* src, int B, int64_t n_new, int Hkv, int64_t Ncap,
+                                const int32_t* len, int8_t* codes, float* scale, hipStream_t st);
 hipError_t launch_scan8_sample(const Shape& s, const Bufs& b, int64_t Nmax, hipStream_t st);
 hipError_t launch_scan8_filter(const Shape& s, const Bufs& b, hipStream_t st);
 hipError_t launch_scan8_full(const Shape& s, const Bufs& b, int64_t Nmax, float* dst, hipStream_t st);

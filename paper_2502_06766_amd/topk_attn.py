@@ -21,7 +21,7 @@ PATH_AUTO, PATH_FULL, PATH_FILTER, PATH_INDEX = 0, 1, 2, 3
 INDEX_NONE, INDEX_INT8 = 0, 1
 
 EXPORTS = [
-    "topk_attn_kv_bytes", "topk_attn_workspace_bytes", "topk_attn_create", "topk_attn_append_kv",
+    "topk_attn_kv_bytes", "topk_attn_workspace_bytes", "topk_attn_create", "topk_attn_append_kv", "topk_attn_append_step",
     "topk_attn_decode", "topk_attn_decode_window", "topk_attn_decode_multi", "topk_attn_decode_layers", "topk_attn_k_schedule", "topk_attn_scores", "topk_attn_length", "topk_attn_reset", "topk_attn_set_path",
     "topk_attn_last_fallbacks", "topk_attn_set_scan_timing", "topk_attn_scan_time", "topk_attn_read_probe", "topk_attn_strerror", "topk_attn_destroy",
 ]
@@ -75,6 +75,8 @@ def lib() -> ctypes.CDLL:
         L.topk_attn_create.restype = i32
         L.topk_attn_append_kv.argtypes = [vp, i32, i32, vp, vp, i64, i64, i64, vp]
         L.topk_attn_append_kv.restype = i32
+        L.topk_attn_append_step.argtypes = [vp, i32, vp, vp, i64, vp]
+        L.topk_attn_append_step.restype = i32
         L.topk_attn_decode.argtypes = [vp, i32, vp, i32, vp, vp, vp, vp, vp]
         L.topk_attn_decode.restype = i32
         L.topk_attn_decode_window.argtypes = [vp, i32, vp, i32, i32, vp, vp, vp, vp, vp]
@@ -154,6 +156,10 @@ def topk_attn_destroy(h: int) -> None:
 def topk_attn_append_kv(h, layer, seq, k_new_ptr, v_new_ptr, n_new, token_stride, head_stride, stream=0):
     _check(lib().topk_attn_append_kv(h, layer, seq, k_new_ptr, v_new_ptr, n_new, token_stride, head_stride,
                                      stream), "topk_attn_append_kv")
+
+
+def topk_attn_append_step(h, layer, k_new_ptr, v_new_ptr, n_new, stream=0):
+    _check(lib().topk_attn_append_step(h, layer, k_new_ptr, v_new_ptr, n_new, stream), "topk_attn_append_step")
 
 
 def topk_attn_decode(h, layer, q_ptr, k, out_ptr, idx_ptr=0, vals_ptr=0, lse_ptr=0, stream=0):
@@ -270,6 +276,12 @@ class TopkAttnCache:
             n = k_new.shape[0]
             ts, hs = k_new.shape[1] * d, d
         topk_attn_append_kv(self.h, layer, seq, k_new.data_ptr(), v_new.data_ptr(), n, ts, hs, self._stream())
+
+    def append_step(self, layer, k_new, v_new):
+        """k_new/v_new: [B, n, Hkv, d] device tensors: n tokens for every sequence of the layer."""
+        assert k_new.is_cuda and v_new.is_cuda and k_new.dtype == self.torch_dtype()
+        assert k_new.is_contiguous() and v_new.is_contiguous() and k_new.shape == v_new.shape
+        topk_attn_append_step(self.h, layer, k_new.data_ptr(), v_new.data_ptr(), k_new.shape[1], self._stream())
 
     def decode(self, layer, q, k, want_idx=True, want_vals=True, want_lse=True, window=0):
         """q [B, Hq, d] device tensor -> (out, idx, vals, lse) device tensors (None if not wanted)."""
