@@ -481,8 +481,7 @@ static int decode_impl(topk_attn_t* h, int layer, const void* q, int n_queries, 
         if (e == hipSuccess && timed) e = hipEventRecord(h->ev[2 * h->ev_used + 1], st);
         if (e == hipSuccess && timed) h->ev_used++;
         if (e == hipSuccess) e = launch_rerank(s, b, st);
-        if (e == hipSuccess) e = launch_select_candidates(s, b, st);
-        if (e == hipSuccess) e = launch_select_full(s, b, true, st);
+        if (e == hipSuccess) e = launch_select_candidates(s, b, st);   // redoes unusable heads itself
     } else if (fast) {
         e = launch_scan_sample(s, b, nmax, st);
         if (e == hipSuccess) e = launch_threshold(s, b, nmax, st);
@@ -490,8 +489,7 @@ static int decode_impl(topk_attn_t* h, int layer, const void* q, int n_queries, 
         if (e == hipSuccess) e = launch_scan_filter(s, b, nmax, st);
         if (e == hipSuccess && timed) e = hipEventRecord(h->ev[2 * h->ev_used + 1], st);
         if (e == hipSuccess && timed) h->ev_used++;
-        if (e == hipSuccess) e = launch_select_candidates(s, b, st);
-        if (e == hipSuccess) e = launch_select_full(s, b, true, st);   // redoes flagged heads only, else exits at once
+        if (e == hipSuccess) e = launch_select_candidates(s, b, st);   // redoes unusable heads itself
     } else {
         if (nmax > 0) {
             if (timed) e = hipEventRecord(h->ev[2 * h->ev_used], st);
@@ -499,7 +497,7 @@ static int decode_impl(topk_attn_t* h, int layer, const void* q, int n_queries, 
             if (e == hipSuccess && timed) e = hipEventRecord(h->ev[2 * h->ev_used + 1], st);
             if (e == hipSuccess && timed) h->ev_used++;
         }
-        if (e == hipSuccess) e = launch_select_full(s, b, false, st);   // with nothing to search it only pads
+        if (e == hipSuccess) e = launch_select_full(s, b, st);   // with nothing to search it only pads
     }
     if (e == hipSuccess) e = launch_gather(s, b, st);
     h->last_fast = fast;

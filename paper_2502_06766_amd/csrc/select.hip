@@ -407,8 +407,30 @@ __global__ void __launch_bounds__(kSelThreads) threshold_kernel(Shape sh, Bufs b
     }
 }
 
+// Exact selection of one head over its full score row (the general path's selection).
+__device__ __forceinline__ void wg_select_dense(const Shape& sh, const Bufs& bf, int64_t bh, int64_t N, int k_eff,
+                                                SelShared& sm) {
+    const SrcDense src{bf.scores + bh * sh.Ncap, N};
+    const Items<(8192 + kSelThreads - 1) / kSelThreads, SrcDense> items(src);
+    const uint32_t kmax = wg_topk_emit(items, k_eff, sh.k, bf.sel_idx + bh * sh.k, bf.sel_val + bh * sh.k, sm);
+    if (threadIdx.x == 0) bf.hmax[bh] = key_score(kmax);
+}
+
+// The exact redo of a head whose candidate list is unusable (its sequence cannot be filtered,
+// a segment overflowed, or the sampled threshold came out above the k-th score): the
+// workgroup rescores the whole head itself, then selects from the full row -- slow, rare, exact.
+__device__ __forceinline__ void wg_redo_head(const Shape& sh, const Bufs& bf, int b, int h, int64_t N, int k_eff,
+                                          SelShared& sm) {
+    const int64_t bh = (int64_t)b * sh.Hq + h;
+    float* row = bf.scores + bh * sh.Ncap;
+    if (sh.dtype == DT_F16) wg_score_head<DT_F16>(sh, bf, b, h, N, row, sm);
+    else if (sh.dtype == DT_BF16) wg_score_head<DT_BF16>(sh, bf, b, h, N, row, sm);
+    else wg_score_head<DT_F32>(sh, bf, b, h, N, row, sm);
+    wg_select_dense(sh, bf, bh, N, k_eff, sm);
+}
+
 // Exact selection among the candidates the filtered scan kept, read from the interleaved
-// per-wave segments.
+// per-wave segments.  A head without a usable list is redone exactly by the same workgroup.
 template <int CPT>     // CPT * kSelThreads candidate slots are kept on chip, the rest is streamed
 __global__ void __launch_bounds__(kSelThreads) select_candidates_kernel(Shape sh, Bufs bf) {
     __shared__ SelShared sm;
@@ -424,38 +446,45 @@ __global__ void __launch_bounds__(kSelThreads) select_candidates_kernel(Shape sh
         if (tid == 0) bf.hmax[bh] = -INFINITY;
         return;
     }
-    if (bf.flags[bh]) return;        // set by the threshold kernel: this sequence is not filtered at all
-    // segment lengths: total, longest
-    uint32_t sum = 0, mxl = 0, kmx = 0;      // kmx: largest score key any scanning wave saw
-    for (int g = tid; g < sh.n_seg; g += kSelThreads) {
-        const uint32_t c = bf.seg_cnt[bh * sh.n_seg + g];
-        sm.seg_len[g] = c;
-        sum += c;
-        mxl = c > mxl ? c : mxl;
-        const uint32_t km = score_key(bf.seg_max[bh * sh.n_seg + g]);
-        kmx = km > kmx ? km : kmx;
-    }
-    for (int o = 32; o > 0; o >>= 1) {
-        sum += __shfl_xor(sum, o, kWave);
-        const uint32_t t = __shfl_xor(mxl, o, kWave), u = __shfl_xor(kmx, o, kWave);
-        mxl = t > mxl ? t : mxl;
-        kmx = u > kmx ? u : kmx;
-    }
-    if (lane == 0) { sm.wave_tot[wave] = sum; sm.red_max[wave] = mxl; sm.red_min[wave] = kmx; }
-    __syncthreads();
-    uint32_t total = 0, max_len = 0;
-    kmx = 0;
-    for (int w = 0; w < kSelWaves; ++w) {
-        total += sm.wave_tot[w];
-        max_len = sm.red_max[w] > max_len ? sm.red_max[w] : max_len;
-        kmx = sm.red_min[w] > kmx ? sm.red_min[w] : kmx;
-    }
-    __syncthreads();
-    if (max_len > (uint32_t)sh.seg_cap || total < (uint32_t)k_eff) {   // uniform: a segment overflowed, or
-        if (tid == 0) {                                                // the threshold was too high
-            bf.flags[bh] = 1;
-            atomicAdd(bf.fallback_total, 1u);
+    // (uniform) flagged by the threshold kernel: this sequence is not filtered at all
+    bool redo = bf.flags[bh] != 0;
+    uint32_t max_len = 0, kmx = 0;           // longest segment; largest score key any scanning wave saw
+    if (!redo) {
+        uint32_t sum = 0, mxl = 0;
+        for (int g = tid; g < sh.n_seg; g += kSelThreads) {
+            const uint32_t c = bf.seg_cnt[bh * sh.n_seg + g];
+            sm.seg_len[g] = c;
+            sum += c;
+            mxl = c > mxl ? c : mxl;
+            const uint32_t km = score_key(bf.seg_max[bh * sh.n_seg + g]);
+            kmx = km > kmx ? km : kmx;
         }
+        for (int o = 32; o > 0; o >>= 1) {
+            sum += __shfl_xor(sum, o, kWave);
+            const uint32_t t = __shfl_xor(mxl, o, kWave), u = __shfl_xor(kmx, o, kWave);
+            mxl = t > mxl ? t : mxl;
+            kmx = u > kmx ? u : kmx;
+        }
+        if (lane == 0) { sm.wave_tot[wave] = sum; sm.red_max[wave] = mxl; sm.red_min[wave] = kmx; }
+        __syncthreads();
+        uint32_t total = 0;
+        kmx = 0;
+        for (int w = 0; w < kSelWaves; ++w) {
+            total += sm.wave_tot[w];
+            max_len = sm.red_max[w] > max_len ? sm.red_max[w] : max_len;
+            kmx = sm.red_min[w] > kmx ? sm.red_min[w] : kmx;
+        }
+        __syncthreads();
+        if (max_len > (uint32_t)sh.seg_cap || total < (uint32_t)k_eff) {   // a segment overflowed, or the
+            if (tid == 0) {                                                // threshold was too high
+                bf.flags[bh] = 1;
+                atomicAdd(bf.fallback_total, 1u);
+            }
+            redo = true;
+        }
+    }
+    if (redo) {
+        wg_redo_head(sh, bf, b, h, N, k_eff, sm);
         return;
     }
     const SrcSeg src{bf.cand + bh * (int64_t)sh.cand_cap, sm.seg_len, pos_lds, 31 - __clz(sh.n_seg), (int)max_len};
@@ -467,14 +496,11 @@ __global__ void __launch_bounds__(kSelThreads) select_candidates_kernel(Shape sh
     if (tid == 0) bf.hmax[bh] = key_score(kmax);
 }
 
-// Exact selection over the full score row.  General path: the scores are already in the
-// score buffer.  After a filtered scan (`redo_flagged`): only the heads whose candidate
-// list was unusable run, and each rescores its whole head itself first -- slow, rare, exact.
-__global__ void __launch_bounds__(kSelThreads) select_full_kernel(Shape sh, Bufs bf, int redo_flagged) {
+// Exact selection over the full score row, already in the score buffer (general path).
+__global__ void __launch_bounds__(kSelThreads) select_full_kernel(Shape sh, Bufs bf) {
     __shared__ SelShared sm;
     const int b = blockIdx.y, h = blockIdx.x;
     const int64_t bh = (int64_t)b * sh.Hq + h;
-    if (redo_flagged && !bf.flags[bh]) return;
     const int64_t N = prefix_len(visible_len(sh, bf, b), sh.window);
     const int k_eff = sh.k < N ? sh.k : (int)N;
     if (k_eff == 0) {
@@ -482,16 +508,7 @@ __global__ void __launch_bounds__(kSelThreads) select_full_kernel(Shape sh, Bufs
         if (threadIdx.x == 0) bf.hmax[bh] = -INFINITY;
         return;
     }
-    if (redo_flagged) {
-        float* row = bf.scores + bh * sh.Ncap;
-        if (sh.dtype == DT_F16) wg_score_head<DT_F16>(sh, bf, b, h, N, row, sm);
-        else if (sh.dtype == DT_BF16) wg_score_head<DT_BF16>(sh, bf, b, h, N, row, sm);
-        else wg_score_head<DT_F32>(sh, bf, b, h, N, row, sm);
-    }
-    const SrcDense src{bf.scores + bh * sh.Ncap, N};
-    const Items<(8192 + kSelThreads - 1) / kSelThreads, SrcDense> items(src);
-    const uint32_t kmax = wg_topk_emit(items, k_eff, sh.k, bf.sel_idx + bh * sh.k, bf.sel_val + bh * sh.k, sm);
-    if (threadIdx.x == 0) bf.hmax[bh] = key_score(kmax);
+    wg_select_dense(sh, bf, bh, N, k_eff, sm);
 }
 
 // Both kernels are correct for any register-cache size (what does not fit is streamed); a
@@ -521,8 +538,8 @@ hipError_t launch_select_candidates(const Shape& s, const Bufs& b, hipStream_t s
     else hipLaunchKernelGGL((select_candidates_kernel<kCandSlots / kSelThreads>), grid, block, 0, st, s, b);
     return hipGetLastError();
 }
-hipError_t launch_select_full(const Shape& s, const Bufs& b, bool redo_flagged, hipStream_t st) {
-    hipLaunchKernelGGL(select_full_kernel, dim3(s.Hq, s.B), dim3(kSelThreads), 0, st, s, b, redo_flagged ? 1 : 0);
+hipError_t launch_select_full(const Shape& s, const Bufs& b, hipStream_t st) {
+    hipLaunchKernelGGL(select_full_kernel, dim3(s.Hq, s.B), dim3(kSelThreads), 0, st, s, b);
     return hipGetLastError();
 }
 
