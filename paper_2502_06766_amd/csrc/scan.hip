@@ -16,6 +16,8 @@
 //            no atomics, so the list order is fixed by the launch geometry alone)
 //   full   : score every key and store the fp32 scores
 // fp32 caches go through a plain FMA kernel (full only).
+#include <type_traits>
+
 #include "device_utils.h"
 #include "internal.h"
 
@@ -375,8 +377,24 @@ scan_rows_kernel(Shape sh, Bufs bf, int tiles_per_wave, float* dst) {
     constexpr int KS = D / 32;
     constexpr int X = 4 * NT;          // rows a lane owns: row 16 t + 4 j + i at x = 4 t + i
     const int G = sh.G, M = sh.M;
-    const int bc = (int)blockIdx.z / sh.n_qblk, blk = (int)blockIdx.z % sh.n_qblk;   // cache sequence, row block
-    const int kvh = blockIdx.y;
+    // Workgroup -> (key stream bx of kv head kvh of cache sequence bc, row block blk).  With several
+    // row blocks the blocks of one key stream take neighbouring slots of one XCD (workgroups go
+    // to the XCDs round-robin by linear id), so they walk the same key tiles at the same time
+    // and all but the first read of a tile are served by that XCD's L2.
+    int bx = blockIdx.x, kvh = blockIdx.y, bc = (int)blockIdx.z / sh.n_qblk, blk = (int)blockIdx.z % sh.n_qblk;
+#ifndef TKA_NO_XCD_REMAP
+    {
+        const int gx = gridDim.x, gy = gridDim.y, streams = gx * gy * sh.Bc;
+        if (sh.n_qblk > 1 && streams % 8 == 0) {
+            const int lin = bx + gx * (kvh + gy * (int)blockIdx.z);
+            const int slot = lin >> 3, stream = (slot / sh.n_qblk) * 8 + (lin & 7);
+            blk = slot % sh.n_qblk;
+            bx = stream % gx;
+            kvh = (stream / gx) % gy;
+            bc = stream / (gx * gy);
+        }
+    }
+#endif
     // the M * G (query, head) rows of the KV head, query-major, are cut into blocks of 16 NT rows
     const int row0 = blk * 16 * NT;                                   // first row of the block
     const int R = M * G - row0 < 16 * NT ? M * G - row0 : 16 * NT;    // its rows
@@ -408,11 +426,11 @@ scan_rows_kernel(Shape sh, Bufs bf, int tiles_per_wave, float* dst) {
     const int64_t n_tiles_all = (n_items + 63) / 64;
     int64_t tile, tile_end, tile_step;
     if (MODE == MODE_FILTER) {
-        tile = (int64_t)blockIdx.x * kScanWaves + wave;
+        tile = (int64_t)bx * kScanWaves + wave;
         tile_step = (int64_t)gridDim.x * kScanWaves;
         tile_end = n_tiles_all;
     } else {
-        const int64_t tile0 = (int64_t)blockIdx.x * tiles_per_wave * kScanWaves;
+        const int64_t tile0 = (int64_t)bx * tiles_per_wave * kScanWaves;
         if (tile0 >= n_tiles_all) return;
         tile = tile0 + wave;
         tile_step = kScanWaves;
@@ -452,7 +470,7 @@ scan_rows_kernel(Shape sh, Bufs bf, int tiles_per_wave, float* dst) {
         ng[x] = 0;
     }
     const int seg_cap = sh.seg_cap, n_seg = sh.n_seg;
-    const int sid = (int)blockIdx.x * kScanWaves + wave;
+    const int sid = bx * kScanWaves + wave;
     __shared__ uint64_t stage_lds[MODE == MODE_FILTER ? kScanWaves * 16 * NT * kStageRow : 1];
     uint64_t* const st0 = stage_lds + (MODE == MODE_FILTER ? wave * 16 * NT * kStageRow : 0);
 
@@ -486,6 +504,77 @@ scan_rows_kernel(Shape sh, Bufs bf, int tiles_per_wave, float* dst) {
         }
         return p < N ? p : N - 1;
     };
+    // Filter step of a tile.  A lane counts its own passing keys of each row slot (at most 4,
+    // one per sub-tile), the counts of four row slots share a register (a byte each: a row has
+    // at most 64 passing keys per tile), and one inclusive scan over the 16 lanes of the row
+    // group (four DPP row shifts) ranks all of them at once: no per-row ballots, no scalar
+    // round trips.  Staged order within a row: by lane, then sub-tile (the selection does not
+    // depend on it).  A lane that has nothing to store for a (row slot, sub-tile) writes to a
+    // scratch slot of its own instead, so the stores need no branches.  WHOLE: the tile lies
+    // inside every row's searched prefix.
+    const int Pmin = prefix_of(0);      // rows of a block search prefixes that grow with the row
+    __shared__ uint64_t dummy_lds[MODE == MODE_FILTER ? kScanWaves * kWave : 1];
+    uint64_t* const dummy = dummy_lds + (MODE == MODE_FILTER ? threadIdx.x : 0);
+    auto filter = [&](auto whole_tag, const f32x4 (&c)[NT][4], int64_t item0) {
+        constexpr bool WHOLE = decltype(whole_tag)::value;
+        const int item_n = (int)item0 + n;              // positions fit 31 bits
+        bool ps[X][4];
+        uint32_t pk[NT];
+#pragma unroll
+        for (int t = 0; t < NT; ++t) pk[t] = 0;
+#pragma unroll
+        for (int x = 0; x < X; ++x) {
+            uint32_t cnt = 0;
+            float mx = top[x];
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                const float sc = c[x >> 2][g][x & 3];
+                const bool valid = WHOLE || item_n + 16 * g < P[x];
+                if (valid) mx = fmaxf(mx, sc);
+                ps[x][g] = valid && sc >= thr[x];
+                cnt += ps[x][g] ? 1u : 0u;
+            }
+            top[x] = mx;
+            pk[x >> 2] |= cnt << (8 * (x & 3));
+        }
+        uint32_t anyp = pk[0];
+#pragma unroll
+        for (int t = 1; t < NT; ++t) anyp |= pk[t];
+        if (!__ballot(anyp != 0u)) return;              // (uniform) nothing passes anywhere in the tile
+        uint32_t incl[NT], tot[NT];
+#pragma unroll
+        for (int t = 0; t < NT; ++t) {
+            uint32_t v = pk[t];
+            v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x111, 0xF, 0xF, true);   // row_shr:1
+            v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x112, 0xF, 0xF, true);   // row_shr:2
+            v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x114, 0xF, 0xF, true);   // row_shr:4
+            v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x118, 0xF, 0xF, true);   // row_shr:8
+            incl[t] = v;
+            tot[t] = (uint32_t)__builtin_amdgcn_ds_bpermute((lane | 15) << 2, (int)v);      // the group's last lane
+        }
+        bool full = false;
+#pragma unroll
+        for (int x = 0; x < X; ++x) full |= nl[x] + (int)((tot[x >> 2] >> (8 * (x & 3))) & 0xFFu) > kStageRow;
+        if (__ballot(full)) {
+#pragma unroll
+            for (int x = 0; x < X; ++x)
+                if (__ballot(nl[x] + (int)((tot[x >> 2] >> (8 * (x & 3))) & 0xFFu) > kStageRow))
+                    flush(x, nl[x], ng[x], vh[x], false);
+        }
+#pragma unroll
+        for (int x = 0; x < X; ++x) {
+            // bytes of incl are >= those of pk: the packed subtraction has no borrows
+            int off = nl[x] + (int)(((incl[x >> 2] - pk[x >> 2]) >> (8 * (x & 3))) & 0xFFu);
+            uint64_t* row_st = st0 + row_at(x) * kStageRow;
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                uint64_t* where = ps[x][g] ? row_st + off : dummy;
+                *where = ((uint64_t)__float_as_uint(c[x >> 2][g][x & 3] + 0.0f) << 32) | (uint64_t)(uint32_t)(item_n + 16 * g);
+                off += ps[x][g] ? 1 : 0;
+            }
+            nl[x] += (int)((tot[x >> 2] >> (8 * (x & 3))) & 0xFFu);
+        }
+    };
     auto consume = [&](const f32x4 (&c)[NT][4], int64_t item0) {
         if (MODE == MODE_SAMPLE) {
 #pragma unroll
@@ -508,42 +597,8 @@ scan_rows_kernel(Shape sh, Bufs bf, int tiles_per_wave, float* dst) {
                     if (item < P[x]) dst[vh[x] * sh.Ncap + item] = c[x >> 2][g][x & 3];
             }
         } else {
-            const uint32_t below = (1u << n) - 1u;
-#pragma unroll
-            for (int i = 0; i < X; ++i) {
-                float sc[4];
-                bool ps[4];
-                uint64_t mg[4], any = 0;
-#pragma unroll
-                for (int g = 0; g < 4; ++g) {
-                    sc[g] = c[i >> 2][g][i & 3] + 0.0f;
-                    const bool valid = item0 + 16 * g + n < P[i];
-                    if (valid) top[i] = fmaxf(top[i], sc[g]);
-                    ps[g] = valid && sc[g] >= thr[i];
-                    mg[g] = __ballot(ps[g]);
-                    any |= mg[g];
-                }
-                if (any) {
-                    uint32_t gm[4];
-                    int add = 0;
-#pragma unroll
-                    for (int g = 0; g < 4; ++g) {
-                        gm[g] = (uint32_t)(mg[g] >> (16 * j)) & 0xFFFFu;
-                        add += __popc(gm[g]);
-                    }
-                    if (__ballot(nl[i] + add > kStageRow)) flush(i, nl[i], ng[i], vh[i], false);
-                    uint64_t* row_st = st0 + row_at(i) * kStageRow;
-                    int off = nl[i];
-#pragma unroll
-                    for (int g = 0; g < 4; ++g) {
-                        if (ps[g])
-                            row_st[off + __popc(gm[g] & below)] =
-                                ((uint64_t)__float_as_uint(sc[g]) << 32) | (uint64_t)(uint32_t)(item0 + 16 * g + n);
-                        off += __popc(gm[g]);
-                    }
-                    nl[i] = off;
-                }
-            }
+            if (item0 + 64 <= Pmin) filter(std::true_type{}, c, item0);
+            else filter(std::false_type{}, c, item0);
         }
     };
     auto mac = [&](const v8 (&b)[4][KS], f32x4 (&c)[NT][4]) {
