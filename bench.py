@@ -5,6 +5,11 @@ A step is one topk_attn_decode call (key scan -> exact top-k -> softmax-weighted
 over one layer of the N = 1M configuration (32 query heads, 8 KV heads, d = 128, fp16,
 k = 16384).  The cache is resident in HBM before timing starts; steps rotate over
 several layers so every scan reads HBM-cold keys.  Prints one JSON line.
+
+--workload c2 | c4 | c5 times the other configurations the same way (they are parity-test
+cases, not the metric's workload): c2 one 128k-token layer, c4 sixteen sequences of 256k
+tokens per step, c5 one layer of the 32-layer 512k-token cache (all 32 resident, a step is
+one layer's decode).
 """
 from __future__ import annotations
 
@@ -35,6 +40,9 @@ def main() -> int:
                     help="queries per step (a causal chunk through topk_attn_decode_multi); 1 is the metric's workload")
     ap.add_argument("--index", action="store_true",
                     help="approximate search through the int8 key index (exact refinement); not the metric's workload")
+    ap.add_argument("--workload", default="c3", choices=["c2", "c3", "c4", "c5"],
+                    help="c3 is the metric's workload; the others are timed the same way for reference")
+    ap.add_argument("--k", type=int, default=0, help="override k (c4 is swept over 256, 1024, 4096 in the tests)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--seed", type=int, default=0)
     args = ap.parse_args()
@@ -52,32 +60,40 @@ def main() -> int:
         print("bench.py: no GPU visible", file=sys.stderr)
         return 1
     dev = torch.device("cuda", 0)
-    w = wl.C3 if not args.tokens else wl.C3.scaled(args.tokens)
-    N, k, d, Hq, Hkv = w.n_tokens, w.k, w.head_dim, w.n_q_heads, w.n_kv_heads
-    L = max(1, args.layers)
+    w = {"c2": wl.C2, "c3": wl.C3, "c4": wl.C4, "c5": wl.C5}[args.workload]
+    default = args.workload == "c3" and not args.tokens and not args.k     # the metric's workload as it stands
+    if args.tokens:
+        w = w.scaled(args.tokens)
+    N, k, d, Hq, Hkv, B = w.n_tokens, args.k or w.k, w.head_dim, w.n_q_heads, w.n_kv_heads, w.n_seqs
+    # layers resident at once: enough distinct key bytes that no scan finds its keys in a cache
+    L = max(1, {"c2": 8, "c3": args.layers, "c4": 1, "c5": 32}[args.workload])
 
     t0 = time.time()
     q, K, V = wl.make_quantized(w, args.seed, threads=16)
     gen_s = time.time() - t0
 
     M = max(1, args.queries)
-    cache = ta.TopkAttnCache(L, 1, Hq, Hkv, d, N, k, w.dtype, max_queries=M,
+    cache = ta.TopkAttnCache(L, B, Hq, Hkv, d, N, k, w.dtype, max_queries=M,
                              index_kind=ta.INDEX_INT8 if args.index else ta.INDEX_NONE)
     if args.index:
         cache.set_path(ta.PATH_INDEX)
-    Kd, Vd = torch.from_numpy(K).to(dev), torch.from_numpy(V).to(dev)
+
+    def to_dev(a):
+        return torch.from_numpy(a.view(np.int16)).to(dev).view(torch.bfloat16) if w.dtype == wl.BF16 else \
+            torch.from_numpy(a).to(dev)
+
+    Kd, Vd = to_dev(K), to_dev(V)
     for layer in range(L):
-        if layer == 0:
-            cache.append(0, 0, Kd, Vd, head_major=True)
-        else:   # same distribution, different addresses and row order
-            sh = 7919 * layer
-            cache.append(layer, 0, torch.roll(Kd, sh, 1), torch.roll(Vd, sh, 1), head_major=True)
+        for b in range(B):   # same distribution, different addresses and row order
+            sh = 7919 * (layer * B + b)
+            cache.append(layer, b, torch.roll(Kd, sh, 1) if sh else Kd, torch.roll(Vd, sh, 1) if sh else Vd,
+                         head_major=True)
     del Kd, Vd
     if M > 1:
         q = wl.make_query_chunk(q, w.dtype, M, args.seed)
-    qd = torch.from_numpy(q).to(dev)[None].contiguous()
-    out = torch.empty((1, M, Hq, d), dtype=torch.float32, device=dev)
-    idx = torch.empty((1, M, Hq, k), dtype=torch.int32, device=dev)
+    qd = to_dev(q)[None].expand(B, *q.shape).contiguous()
+    out = torch.empty((B, M, Hq, d), dtype=torch.float32, device=dev)
+    idx = torch.empty((B, M, Hq, k), dtype=torch.int32, device=dev)
     stream = torch.cuda.current_stream(dev).cuda_stream
     torch.cuda.synchronize()
 
@@ -110,7 +126,7 @@ def main() -> int:
 
     # streaming-read ceiling over the same key bytes (128-bit loads, nothing else)
     sink = torch.zeros(16384, dtype=torch.int32, device=dev)
-    k_bytes = Hkv * N * d * 2
+    k_bytes = B * Hkv * N * d * 2          # the key bytes of one layer
     probe_ms = []
     for i in range(L * 3):
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
@@ -119,20 +135,19 @@ def main() -> int:
         e1.record()
         torch.cuda.synchronize()
         probe_ms.append(e0.elapsed_time(e1))
-    probe_gbps = k_bytes / (min(probe_ms[L:]) * 1e-3) / 1e9
+    probe_gbps = k_bytes / (min(probe_ms[min(L, len(probe_ms) - 1):]) * 1e-3) / 1e9
 
     e = 2
-    alg_bytes = Hkv * N * d * e + M * (Hq * k * d * e + Hq * d * (e + 4) + Hq * k * 4)
-    keys_per_s = Hkv * N / (ms_per_step * 1e-3)
-    G = Hq // Hkv
-    n_qblk = 1 if M == 1 else -(-M * G // (32 if M * G > 16 else 16))     # passes over the keys: one per block of 16 or 32 rows
-    scan_bytes = k_bytes * n_qblk
+    alg_bytes = k_bytes + B * M * (Hq * k * d * e + Hq * d * (e + 4) + Hq * k * 4)
+    keys_per_s = B * Hkv * N / (ms_per_step * 1e-3)
+    # every key is needed once per launch, however many blocks of (query, head) rows walk over it
+    scan_bytes = k_bytes
     if args.index and M == 1:
-        scan_bytes = Hkv * N * (d + 4)                          # int8 codes and one fp32 scale per key
+        scan_bytes = B * Hkv * N * (d + 4)                      # int8 codes and one fp32 scale per key
     scan_gbps = scan_bytes / (scan_ms * 1e-3) / 1e9
 
     cpu = None
-    if not args.no_cpu_baseline and M == 1 and not args.index:
+    if not args.no_cpu_baseline and M == 1 and not args.index and args.workload == "c3":
         from oracle import c_oracle
         reps = 3
         t0 = time.perf_counter()
@@ -144,7 +159,8 @@ def main() -> int:
                          f"({reps * cpu_s * c_oracle.num_threads():.0f} core-seconds)"}
 
     res = {
-        "metric": "kv_keys_scored_per_sec_per_decode_step_N1M",
+        "metric": "kv_keys_scored_per_sec_per_decode_step_N1M" if args.workload == "c3"
+        else "kv_keys_scored_per_sec_per_decode_step_" + args.workload,
         "value": keys_per_s,
         "unit": "keys/s",
         "n_gpus": 1,
@@ -154,12 +170,12 @@ def main() -> int:
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
-        "dtype": "f16",
+        "dtype": "bf16" if w.dtype == wl.BF16 else "f16",
         "data": "synthetic",
         "config": {"workload": w.name, "n_q_heads": Hq, "n_kv_heads": Hkv, "head_dim": d, "n_tokens": N,
-                   "k": k, "layers_rotated": L, "n_seqs": 1, "queries_per_step": M,
+                   "k": k, "layers_rotated": L, "n_seqs": B, "queries_per_step": M,
                    "search": "int8 index + exact refinement" if args.index else "exact"},
-        "scores_per_sec": M * Hq * N / (ms_per_step * 1e-3),
+        "scores_per_sec": B * M * Hq * N / (ms_per_step * 1e-3),
         "step_hbm_gbps": alg_bytes / (ms_per_step * 1e-3) / 1e9,
         "step_pct_of_hbm_peak": 100.0 * alg_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBPS,
         "step_ms_gpu_events": ev0.elapsed_time(ev1) / args.steps,
@@ -167,7 +183,7 @@ def main() -> int:
         "filter_fallback_heads": fallbacks,
         "roofline": {"bound": "hbm", "kernel": ("scan8_kernel (filter)" if args.index else "scan_mfma_kernel (filter)") if M == 1 else "scan_rows_kernel (filter)", "achieved": scan_gbps,
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": scan_gbps / HBM_PEAK_GBPS,
-                     "traffic": SCAN_TRAFFIC_BYTES_C3 if not args.tokens and M == 1 and not args.index else None, "ms_per_launch": scan_ms,
+                     "traffic": SCAN_TRAFFIC_BYTES_C3 if default and M == 1 and not args.index else None, "ms_per_launch": scan_ms,
                      "bytes_per_launch": scan_bytes,
                      "frac_of_read_probe": scan_gbps / probe_gbps},
         "cpu_baseline": cpu,
