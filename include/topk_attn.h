@@ -49,8 +49,8 @@ enum {
     TOPK_ATTN_PATH_AUTO = 0,    /* filtered scan when the shape allows it, else full */
     TOPK_ATTN_PATH_FULL = 1,    /* always materialise all N scores and radix-select over them */
     TOPK_ATTN_PATH_FILTER = 2,  /* sampled-threshold scan whenever its candidate list fits the
-                                   workspace, also for short caches (the full path still redoes
-                                   heads whose candidate list under- or overflows) */
+                                   workspace, also for short caches (heads whose candidate list
+                                   under- or overflows are still redone exactly) */
     TOPK_ATTN_PATH_INDEX = 3    /* approximate search over the int8 key index with exact refinement
                                    (needs index_kind = TOPK_ATTN_INDEX_INT8); where the filtered scan
                                    does not apply (short caches, dense k, several queries) the exact
@@ -117,8 +117,8 @@ int topk_attn_append_kv(topk_attn_t* h, int layer, int seq, const void* k_new, c
                         int64_t n_new, int64_t token_stride, int64_t head_stride, void* hip_stream);
 
 /* The per-step concat of Algorithm 1 for a whole batch: append n_new tokens to EVERY
- * sequence of `layer` in one call (two small launches whatever B is; topk_attn_append_kv
- * costs one per sequence).  k_new / v_new: device [B, n_new, Hkv, d], contiguous, 16-byte
+ * sequence of `layer` in one call (two launches whatever B is, three with an int8 index;
+ * topk_attn_append_kv costs one per sequence).  k_new / v_new: device [B, n_new, Hkv, d], contiguous, 16-byte
  * aligned.  Errors: EINVAL, ECAPACITY if any sequence would exceed max_tokens (nothing is
  * enqueued then).  n_new == 0 is a no-op. */
 int topk_attn_append_step(topk_attn_t* h, int layer, const void* k_new, const void* v_new, int64_t n_new,
