@@ -438,6 +438,15 @@ __global__ void __launch_bounds__(kSelThreads) select_candidates_kernel(Shape sh
     const int b = blockIdx.y, h = blockIdx.x;
     const int tid = threadIdx.x, lane = lane_id(), wave = tid >> 6;
     const int64_t bh = (int64_t)b * sh.Hq + h;
+    // Everything the prologue needs from memory is asked for at once: this kernel runs on a
+    // few dozen compute units at the end of a dependent chain of kernels, and every load it
+    // waits for on its own costs a full trip to memory (n_seg <= kMaxSeg <= kSelThreads).
+    static_assert(kMaxSeg <= kSelThreads, "one segment per thread");
+    const uint32_t flagged = bf.flags[bh];
+    const float thr_h = bf.thr[bh];
+    const bool has_seg = tid < sh.n_seg;
+    const uint32_t my_cnt = has_seg ? bf.seg_cnt[bh * sh.n_seg + tid] : 0u;
+    const float my_max = has_seg ? bf.seg_max[bh * sh.n_seg + tid] : -INFINITY;
     const int64_t N = prefix_len(visible_len(sh, bf, b), sh.window);
     const int k_eff = sh.k < N ? sh.k : (int)N;
 
@@ -447,17 +456,13 @@ __global__ void __launch_bounds__(kSelThreads) select_candidates_kernel(Shape sh
         return;
     }
     // (uniform) flagged by the threshold kernel: this sequence is not filtered at all
-    bool redo = bf.flags[bh] != 0;
+    bool redo = flagged != 0;
     uint32_t max_len = 0, kmx = 0;           // longest segment; largest score key any scanning wave saw
     if (!redo) {
-        uint32_t sum = 0, mxl = 0;
-        for (int g = tid; g < sh.n_seg; g += kSelThreads) {
-            const uint32_t c = bf.seg_cnt[bh * sh.n_seg + g];
-            sm.seg_len[g] = c;
-            sum += c;
-            mxl = c > mxl ? c : mxl;
-            const uint32_t km = score_key(bf.seg_max[bh * sh.n_seg + g]);
-            kmx = km > kmx ? km : kmx;
+        uint32_t sum = my_cnt, mxl = my_cnt;
+        if (has_seg) {
+            sm.seg_len[tid] = my_cnt;
+            kmx = score_key(my_max);
         }
         for (int o = 32; o > 0; o >>= 1) {
             sum += __shfl_xor(sum, o, kWave);
@@ -492,7 +497,7 @@ __global__ void __launch_bounds__(kSelThreads) select_candidates_kernel(Shape sh
     // every candidate is >= the head's threshold and the scan reported the largest score; not so
     // after an index scan, whose candidates were re-scored since
     const uint32_t kmax = wg_topk_emit(items, k_eff, sh.k, bf.sel_idx + bh * sh.k, bf.sel_val + bh * sh.k, sm,
-                                       !sh.indexed, score_key(bf.thr[bh]), kmx);
+                                       !sh.indexed, score_key(thr_h), kmx);
     if (tid == 0) bf.hmax[bh] = key_score(kmax);
 }
 
