@@ -388,8 +388,7 @@ static void fill_call(topk_attn_t* h, int layer, const void* q, int k, int n_que
 // eight standard deviations.  False if no split fits (the caller takes the full path).
 static bool choose_segments(const topk_attn_t* h, const Shape& s, int64_t nmax, int64_t c_hi, int* n_seg,
                             int* seg_cap) {
-    int64_t target_wgs = 2 * (int64_t)h->n_cu;
-    if (const char* e = getenv("TOPK_ATTN_SCAN_WGS")) target_wgs = atoll(e);
+    const int64_t target_wgs = 2 * (int64_t)h->n_cu;
     int64_t P = target_wgs / ((int64_t)scan_grid_z(s) * s.Hkv);
     const int64_t tiles = (nmax + 63) / 64;
     if (P * 4 > tiles) P = tiles / 4;
@@ -644,7 +643,6 @@ int topk_attn_read_probe(const void* src, size_t bytes, void* sink, void* hip_st
     const size_t n_vec = bytes / 16;
     size_t blocks = (n_vec + 4095) / 4096;      // one tile per wave at least
     if (blocks > 512) blocks = 512;             // two workgroups per compute unit, like the key scan
-    if (const char* e = getenv("TOPK_ATTN_PROBE_BLOCKS")) blocks = (size_t)atoi(e);
     if (blocks < 1) blocks = 1;
     hipLaunchKernelGGL(read_probe_kernel, dim3((unsigned)blocks), dim3(256), 0, (hipStream_t)hip_stream,
                        static_cast<const u32x4*>(src), n_vec, static_cast<uint32_t*>(sink));

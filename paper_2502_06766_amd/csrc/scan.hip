@@ -702,7 +702,6 @@ static int tiles_per_wave_for(int64_t n_items, int B, int Hkv) {
     const int64_t tiles = (n_items + 63) / 64;
     const int64_t want_wgs = 4096 / ((int64_t)B * Hkv > 0 ? (int64_t)B * Hkv : 1);
     int64_t tpw = tiles / (kScanWaves * (want_wgs > 0 ? want_wgs : 1));
-    if (const char* e = getenv("TOPK_ATTN_TILES_PER_WAVE")) tpw = atoi(e);
     if (tpw < 1) tpw = 1;
     if (tpw > 64) tpw = 64;
     return (int)tpw;
