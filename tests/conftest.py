@@ -12,6 +12,14 @@ def pytest_configure(config):
     config.addinivalue_line("markers", "gpu: needs a real MI355X (run with -m gpu on the GPU box)")
 
 
+def pytest_sessionstart(session):
+    """The tests load the library that is built; only when none is there do they build it."""
+    from paper_2502_06766_amd import topk_attn
+    if not os.path.exists(topk_attn.LIB_PATH):
+        from paper_2502_06766_amd import build
+        build.build()
+
+
 def _have_gpu() -> bool:
     try:
         import torch
