@@ -124,6 +124,16 @@ def main() -> int:
     ta.topk_attn_set_scan_timing(cache.h, False)
     scan_ms = scan_ms_total / max(1, n_scan)
 
+    # spread of the single steps, from a second pass with an event between steps (the events
+    # cost a little, so this pass is not the one the metric is taken from)
+    marks = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]
+    marks[0].record()
+    for i in range(args.steps):
+        step(i)
+        marks[i + 1].record()
+    torch.cuda.synchronize()
+    per_step = sorted(marks[i].elapsed_time(marks[i + 1]) for i in range(args.steps))
+
     # streaming-read ceiling over the same key bytes (128-bit loads, nothing else)
     sink = torch.zeros(16384, dtype=torch.int32, device=dev)
     k_bytes = B * Hkv * N * d * 2          # the key bytes of one layer
@@ -147,15 +157,16 @@ def main() -> int:
     scan_gbps = scan_bytes / (scan_ms * 1e-3) / 1e9
 
     cpu = None
-    if not args.no_cpu_baseline and M == 1 and not args.index and args.workload == "c3":
+    if not args.no_cpu_baseline and M == 1 and not args.index:
         from oracle import c_oracle
         reps = 3
         t0 = time.perf_counter()
         for _ in range(reps):
             c_oracle.topk_attention(q, K, V, w.dtype, k)
         cpu_s = (time.perf_counter() - t0) / reps
+        what = "full decode steps of the same workload" if B == 1 else f"decode steps of one of the {B} sequences"
         cpu = {"value": Hkv * N / cpu_s, "unit": "keys/s", "cores": c_oracle.num_threads(), "kind": "oracle",
-               "sample": f"{reps} full decode steps of the same workload ({Hq} heads x {N} keys), {cpu_s:.2f} s each "
+               "sample": f"{reps} {what} ({Hq} heads x {N} keys), {cpu_s:.2f} s each "
                          f"({reps * cpu_s * c_oracle.num_threads():.0f} core-seconds)"}
 
     res = {
@@ -179,6 +190,8 @@ def main() -> int:
         "step_hbm_gbps": alg_bytes / (ms_per_step * 1e-3) / 1e9,
         "step_pct_of_hbm_peak": 100.0 * alg_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBPS,
         "step_ms_gpu_events": ev0.elapsed_time(ev1) / args.steps,
+        "step_ms_median": per_step[len(per_step) // 2],
+        "step_ms_min": per_step[0],
         "read_probe_gbps": probe_gbps,
         "filter_fallback_heads": fallbacks,
         "roofline": {"bound": "hbm", "kernel": ("scan8_kernel (filter)" if args.index else "scan_mfma_kernel (filter)") if M == 1 else "scan_rows_kernel (filter)", "achieved": scan_gbps,
