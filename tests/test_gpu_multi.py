@@ -27,6 +27,7 @@ DEV = torch.device("cuda", 0) if torch.cuda.is_available() else None
     (wl.BF16, 64, 2, 36000, 128, 100, ta.PATH_AUTO),     # G = 32: one block of two row tiles per KV head
     (wl.F16, 48, 1, 40001, 64, 50, ta.PATH_AUTO),        # multi-query attention, 48 heads on one KV head: two blocks
     (wl.F16, 40, 1, 2000, 128, 30, ta.PATH_FULL),        # G = 40, all scores stored
+    (wl.F16, 16, 2, 40000, 128, 14000, ta.PATH_FILTER),  # G = 8, a third of the keys selected
 ])
 def test_wide_head_groups(dtype, Hq, Hkv, N, d, k, path):
     q, K, V = rand_case(Hq, Hkv, N, d, dtype, k, seed=N + k)
@@ -92,6 +93,8 @@ def run_multi_case(q, K, V, delta, dtype, k, causal, window=0, path=ta.PATH_AUTO
     (wl.F16, 5, 8, 2, 35000, 32, 120, True, 0, ta.PATH_AUTO),       # d = 32, 20 rows
     (wl.F16, 3, 20, 1, 36000, 128, 64, True, 0, ta.PATH_AUTO),      # G = 20, 60 rows: blocks cut across queries
     (wl.F16, 33, 4, 1, 33500, 64, 100, True, 16, ta.PATH_AUTO),     # 9 row blocks, the last with one query
+    (wl.F16, 3, 8, 2, 36000, 128, 9000, True, 0, ta.PATH_FILTER),   # a quarter of the keys selected: the per-row
+    (wl.BF16, 6, 8, 2, 34000, 64, 12000, True, 0, ta.PATH_FILTER),  # stages flush every few tiles (12 and 24 rows)
 ])
 def test_multi_query_decode(dtype, M, Hq, Hkv, N, d, k, causal, window, path):
     q, K, V, delta = make_multi(M, Hq, Hkv, N, d, dtype, k, causal, window, seed=N + k + M)
