@@ -83,3 +83,60 @@ def test_append_step_capacity_and_arguments():
         assert ta.lib().topk_attn_append_step(c.h, 1, kn.data_ptr(), kn.data_ptr(), 1, None) == ta.EINVAL
     finally:
         c.close()
+
+
+def test_serving_batch_of_many_short_sequences():
+    """1500 sequences of 1..400 tokens in one call, grown by batched appends: the grid dimensions
+    that carry the sequence index, ragged lengths inside one launch, k above and below the lengths."""
+    dtype, Hq, Hkv, d, k, B = wl.F16, 8, 2, 64, 24, 1500
+    g = np.random.default_rng(77)
+    lens = g.integers(1, 401, size=B)
+    lens[:4] = [1, 400, 24, 25]
+    Nmax = int(lens.max())
+    K = wl.quantize(g.standard_normal((B, Hkv, Nmax, d)).astype(np.float32), dtype)
+    V = wl.quantize(g.standard_normal((B, Hkv, Nmax, d)).astype(np.float32), dtype)
+    q = wl.quantize(g.standard_normal((B, Hq, d)).astype(np.float32), dtype)
+    check = list(range(8)) + g.choice(B, size=40, replace=False).tolist() + [B - 1]
+    for s in check:                                     # a score margin where the result is compared
+        n = int(lens[s])
+        K[s, :, :n] = H.enforce_margin(q[s], np.ascontiguousarray(K[s, :, :n]), dtype, k)[0]
+    cache = ta.TopkAttnCache(1, B, Hq, Hkv, d, Nmax + 2, k, dtype)
+    try:
+        Kd, Vd = H.to_torch(K, dtype, DEV), H.to_torch(V, dtype, DEV)
+        # every sequence starts with its first token, then batched steps add a token to all of them;
+        # sequences that are already complete receive a copy of their last token, removed again below
+        # by resetting and re-importing them
+        for s in range(B):
+            n = int(lens[s])
+            cache.append(0, s, Kd[s, :, :max(1, n - 2)].contiguous(), Vd[s, :, :max(1, n - 2)].contiguous(),
+                         head_major=True)
+        for step in range(2):
+            pos = torch.tensor(np.clip(np.maximum(1, lens - 2) + step, 0, Nmax - 1), device=DEV)
+            kn = Kd[torch.arange(B, device=DEV), :, pos][:, None].contiguous()     # [B, 1, Hkv, d]
+            vn = Vd[torch.arange(B, device=DEV), :, pos][:, None].contiguous()
+            cache.append_step(0, kn, vn)
+        short = [s for s in range(B) if lens[s] < 3]    # these got more tokens than they have
+        for s in short:
+            cache.reset(0, s)
+            n = int(lens[s])
+            cache.append(0, s, Kd[s, :, :n].contiguous(), Vd[s, :, :n].contiguous(), head_major=True)
+        assert [cache.length(0, s) for s in range(B)] == lens.tolist()
+        out, idx, vals, lse = cache.decode(0, H.to_torch(q, dtype, DEV), k)
+        torch.cuda.synchronize()
+        out, idx, vals, lse = (t.cpu().numpy() for t in (out, idx, vals, lse))
+        for s in check:
+            n = int(lens[s])
+            Ks, Vs = np.ascontiguousarray(K[s, :, :n]), np.ascontiguousarray(V[s, :, :n])
+            ref = c_oracle.topk_attention(q[s], Ks, Vs, dtype, k)
+            H.check_against_oracle(out[s], idx[s], vals[s], lse[s], ref, H.score_margin(q[s], Ks, dtype), min(k, n),
+                                   H.out_tolerance(dtype), float(np.abs(wl.widen(Vs, dtype)).max()), f"seq {s}")
+        # the sequences not compared one by one: valid positions, no duplicates, padding where k > length
+        for s in range(B):
+            n, ke = int(lens[s]), min(k, int(lens[s]))
+            for h in range(Hq):
+                sel = idx[s, h, :ke]
+                assert sel.min() >= 0 and sel.max() < n and np.unique(sel).size == ke, f"seq {s} head {h}"
+                assert (idx[s, h, ke:] == -1).all()
+            assert np.isfinite(out[s]).all()
+    finally:
+        cache.close()
