@@ -496,7 +496,7 @@ static int decode_impl(topk_attn_t* h, int layer, const void* q, int n_queries, 
             if (e == hipSuccess && timed) e = hipEventRecord(h->ev[2 * h->ev_used + 1], st);
             if (e == hipSuccess && timed) h->ev_used++;
         }
-        if (e == hipSuccess) e = launch_select_full(s, b, st);   // with nothing to search it only pads
+        if (e == hipSuccess) e = launch_select_full(s, b, nmax, st);   // with nothing to search it only pads
     }
     if (e == hipSuccess) e = launch_gather(s, b, st);
     h->last_fast = fast;

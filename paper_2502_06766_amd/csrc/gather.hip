@@ -21,10 +21,12 @@ struct GatherShared {
 
 // Weighted sum of value rows j in [j0, j1): row(j) gives the cache position, weight(j) its
 // softmax numerator.  Leaves the partial of this workgroup in slot `slot` of the head.
+// With `direct` (the head has this one partial only) the normalised result goes straight to
+// `out` / `lse` and no merge kernel follows.
 template <int DT, class RowFn, class WeightFn>
 __device__ __forceinline__ void wg_weighted_rows(const Shape& sh, const Bufs& bf, int64_t bh, const char* Vh, int j0,
                                                  int j1, RowFn row, WeightFn weight, float m_ref, int slot,
-                                                 GatherShared& sm) {
+                                                 GatherShared& sm, bool direct = false, float scale = 0.f) {
     constexpr int EPL = Elem<DT>::kPerLoad;
     const int D = sh.D;
     const int lane = lane_id(), wave = threadIdx.x >> 6;
@@ -77,6 +79,13 @@ __device__ __forceinline__ void wg_weighted_rows(const Shape& sh, const Bufs& bf
         if (c == 0) sm.red[wave][256] = lsum;
     }
     __syncthreads();
+    if (direct) {
+        const float l = (sm.red[0][256] + sm.red[1][256]) + (sm.red[2][256] + sm.red[3][256]);
+        for (int t = threadIdx.x; t < D; t += blockDim.x)
+            bf.out[bh * D + t] = ((sm.red[0][t] + sm.red[1][t]) + (sm.red[2][t] + sm.red[3][t])) / l;
+        if (threadIdx.x == 0 && bf.lse) bf.lse[bh] = m_ref * scale + logf(l);
+        return;
+    }
     float* pa = bf.part_acc + (bh * sh.n_chunk_cap + slot) * D;
     for (int t = threadIdx.x; t < D; t += blockDim.x)
         pa[t] = (sm.red[0][t] + sm.red[1][t]) + (sm.red[2][t] + sm.red[3][t]);
@@ -96,7 +105,8 @@ __device__ __forceinline__ void mark_empty(const Shape& sh, const Bufs& bf, int6
 
 // slots [0, ceil(k / kGatherRows)): the retrieved rows
 template <int DT>
-__global__ void __launch_bounds__(256) gather_partial_kernel(Shape sh, Bufs bf, float scale_log2e) {
+__global__ void __launch_bounds__(256) gather_partial_kernel(Shape sh, Bufs bf, float scale_log2e, float scale,
+                                                             int direct) {
     __shared__ GatherShared sm;
     const int chunk_id = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
     const int64_t bh = (int64_t)b * sh.Hq + h;
@@ -111,7 +121,7 @@ __global__ void __launch_bounds__(256) gather_partial_kernel(Shape sh, Bufs bf, 
     const float* val = bf.sel_val + bh * sh.k;
     const float m = bf.hmax[bh];
     wg_weighted_rows<DT>(sh, bf, bh, Vh, j0, j1, [&](int j) { return (int64_t)idx[j]; },
-                         [&](int j) { return exp2f((val[j] - m) * scale_log2e); }, m, chunk_id, sm);
+                         [&](int j) { return exp2f((val[j] - m) * scale_log2e); }, m, chunk_id, sm, direct != 0, scale);
 }
 
 // slots [slot0, slot0 + ceil(window / kGatherRows)): the always-attended recent tokens,
@@ -262,12 +272,14 @@ hipError_t launch_gather(const Shape& s, const Bufs& b, hipStream_t st) {
     const int nch = (s.k + kGatherRows - 1) / kGatherRows;
     const int nwin = (s.window + kGatherRows - 1) / kGatherRows;
     dim3 grid((unsigned)nch, (unsigned)s.Hq, (unsigned)s.B);
+    // one chunk per head and no window: the gather writes the result itself (k_eff >= 1 for every sequence)
+    const int direct = nch == 1 && nwin == 0 ? 1 : 0;
     if (s.dtype == DT_F32)
-        hipLaunchKernelGGL((gather_partial_kernel<DT_F32>), grid, dim3(256), 0, st, s, b, scale_log2e);
+        hipLaunchKernelGGL((gather_partial_kernel<DT_F32>), grid, dim3(256), 0, st, s, b, scale_log2e, scale, direct);
     else if (s.dtype == DT_F16)
-        hipLaunchKernelGGL((gather_partial_kernel<DT_F16>), grid, dim3(256), 0, st, s, b, scale_log2e);
+        hipLaunchKernelGGL((gather_partial_kernel<DT_F16>), grid, dim3(256), 0, st, s, b, scale_log2e, scale, direct);
     else
-        hipLaunchKernelGGL((gather_partial_kernel<DT_BF16>), grid, dim3(256), 0, st, s, b, scale_log2e);
+        hipLaunchKernelGGL((gather_partial_kernel<DT_BF16>), grid, dim3(256), 0, st, s, b, scale_log2e, scale, direct);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     if (nwin > 0) {
@@ -284,7 +296,7 @@ hipError_t launch_gather(const Shape& s, const Bufs& b, hipStream_t st) {
     if (nwin > 0)
         hipLaunchKernelGGL(gather_combine_kernel, dim3(s.Hq, s.B), dim3(256), 0, st, s, b, scale, scale_log2e,
                            nch + nwin);
-    else
+    else if (!direct)
         hipLaunchKernelGGL(gather_sum_kernel, dim3(s.Hq, s.B), dim3(256), 0, st, s, b, scale);
     return hipGetLastError();
 }

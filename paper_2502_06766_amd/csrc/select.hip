@@ -43,7 +43,9 @@ __device__ __forceinline__ float key_score(uint32_t o) { return __uint_as_float(
 // ---------------------------------------------------------------------------------------
 // Sources: slot i of a head either holds an item (score, position) or is empty.
 // ---------------------------------------------------------------------------------------
-struct SrcDense {            // scores[i] at position i, i < n
+template <int NT>            // NT: threads of the workgroup
+struct SrcDenseT {           // scores[i] at position i, i < n
+    static constexpr int kThreads = NT;
     const float* s;
     int64_t n;
     typedef float raw_t;
@@ -55,10 +57,12 @@ struct SrcDense {            // scores[i] at position i, i < n
     // the position of a cached slot is implied by the slot
     __device__ __forceinline__ void stash(int, float) const {}
     __device__ __forceinline__ uint32_t cached_ipos(int j) const {
-        return 0xFFFFFFFFu - (uint32_t)(j * kSelThreads + (int)threadIdx.x);
+        return 0xFFFFFFFFu - (uint32_t)(j * NT + (int)threadIdx.x);
     }
 };
+typedef SrcDenseT<kSelThreads> SrcDense;
 struct SrcSeg {              // candidate list of n_seg interleaved segments: entry e of segment g
+    static constexpr int kThreads = kSelThreads;
     const uint64_t* segs;    // sits in slot cand_slot(e, g, n_seg); entries are (score bits << 32 | position)
     const uint32_t* seg_len; // LDS: entries per segment
     uint32_t* pos_lds;       // LDS: inverted positions of the cached slots, [slot j][thread]
@@ -88,6 +92,7 @@ struct SrcSeg {              // candidate list of n_seg interleaved segments: en
 // may use wave-wide ballots.
 template <int CPT, class Src>
 struct Items {
+    static constexpr int kThreads = Src::kThreads;
     uint32_t kc[CPT > 0 ? CPT : 1];
     const Src src;      // by value: keeps the LDS pointers inside visible to the compiler as LDS
     __device__ __forceinline__ Items(const Src& s) : src(s) {
@@ -100,7 +105,7 @@ struct Items {
 #pragma unroll
             for (int u = 0; u < B; ++u) {
                 if (j0 + u < CPT) {          // CPT need not be a multiple of the batch
-                    const int64_t i = (int64_t)(j0 + u) * kSelThreads + threadIdx.x;
+                    const int64_t i = (int64_t)(j0 + u) * kThreads + threadIdx.x;
                     ok[u] = src.valid(i);
                     r[u] = *src.where(ok[u] ? i : 0);
                 }
@@ -121,18 +126,18 @@ struct Items {
         for (int j = 0; j < CPT; ++j) f(kc[j], src.cached_ipos(j), kc[j] != 0u);
         constexpr int U = 8;
         const int64_t n_slots = src.slots();
-        for (int64_t base = (int64_t)CPT * kSelThreads; base < n_slots; base += (int64_t)U * kSelThreads) {
+        for (int64_t base = (int64_t)CPT * kThreads; base < n_slots; base += (int64_t)U * kThreads) {
             typename Src::raw_t r[U];
             bool ok[U];
 #pragma unroll
             for (int u = 0; u < U; ++u) {
-                const int64_t i = base + (int64_t)u * kSelThreads + threadIdx.x;
+                const int64_t i = base + (int64_t)u * kThreads + threadIdx.x;
                 ok[u] = src.valid(i);
                 r[u] = *src.where(ok[u] ? i : 0);
             }
 #pragma unroll
             for (int u = 0; u < U; ++u) {
-                const int64_t i = base + (int64_t)u * kSelThreads + threadIdx.x;
+                const int64_t i = base + (int64_t)u * kThreads + threadIdx.x;
                 f(ok[u] ? src.key(r[u]) : 0u, src.ipos(r[u], i), ok[u]);
             }
         }
@@ -154,7 +159,7 @@ struct Sel32 {
 // all keys, and the pass that would find them is skipped.  `max_passes` > 0 stops the
 // refinement early: the result then has need <= have and T is only a lower bound of the
 // k-th key (for callers that can live with a few extra keys at or above T).
-template <class Keys>
+template <int NT, class Keys>     // NT: threads of the workgroup
 __device__ __forceinline__ Sel32 wg_select32(Keys keys, int64_t k, SelShared& sm, bool bounded = false,
                                              uint32_t lo = 0u, uint32_t hi = 0u, int max_passes = 0) {
     const int tid = threadIdx.x, lane = lane_id(), wave = tid >> 6;
@@ -175,12 +180,12 @@ __device__ __forceinline__ Sel32 wg_select32(Keys keys, int64_t k, SelShared& sm
     }
     __syncthreads();                  // the shared scratch may still be read by a previous select
     if (!bounded && lane == 0) { sm.red_max[wave] = mx; sm.red_min[wave] = mn; }
-    for (int i = tid; i < kBins; i += kSelThreads) sm.hist[i] = 0;
+    for (int i = tid; i < kBins; i += NT) sm.hist[i] = 0;
     __syncthreads();
     if (!bounded) {
         if (wave == 0) {
-            mx = lane < kSelWaves ? sm.red_max[lane] : 0u;
-            mn = lane < kSelWaves ? sm.red_min[lane] : ~0u;
+            mx = lane < (NT / kWave) ? sm.red_max[lane] : 0u;
+            mn = lane < (NT / kWave) ? sm.red_min[lane] : ~0u;
             for (int o = 32; o > 0; o >>= 1) {
                 const uint32_t a = __shfl_xor(mx, o, kWave), b = __shfl_xor(mn, o, kWave);
                 mx = a > mx ? a : mx;
@@ -200,7 +205,7 @@ __device__ __forceinline__ Sel32 wg_select32(Keys keys, int64_t k, SelShared& sm
         if (lane == 0) sm.wave_tot[wave] = cnt;
         __syncthreads();
         uint32_t total = 0;
-        for (int w = 0; w < kSelWaves; ++w) total += sm.wave_tot[w];
+        for (int w = 0; w < (NT / kWave); ++w) total += sm.wave_tot[w];
         res.T = mx; res.need = (uint32_t)k; res.have = total; res.exact = true;
         return res;
     }
@@ -250,7 +255,7 @@ __device__ __forceinline__ Sel32 wg_select32(Keys keys, int64_t k, SelShared& sm
         const uint32_t bin = sm.bin, above = sm.above;
         cb = sm.cb;
         __syncthreads();
-        for (int i = tid; i < kBins; i += kSelThreads) sm.hist[i] = 0;
+        for (int i = tid; i < kBins; i += NT) sm.hist[i] = 0;
         prefix |= bin << shift;
         k_rem -= above;
         rb = shift;
@@ -269,7 +274,7 @@ __device__ __forceinline__ Sel32 wg_select32(Keys keys, int64_t k, SelShared& sm
 
 // Slots the selection does not fill: position -1, score -inf.
 __device__ __forceinline__ void pad_outputs(int k_eff, int k, int32_t* idx, float* vals) {
-    for (int j = k_eff + (int)threadIdx.x; j < k; j += kSelThreads) {
+    for (int j = k_eff + (int)threadIdx.x; j < k; j += (int)blockDim.x) {
         idx[j] = -1;
         vals[j] = -INFINITY;
     }
@@ -283,13 +288,13 @@ __device__ __forceinline__ uint32_t wg_topk_emit(const It& items, int k_eff, int
                                                  SelShared& sm, bool bounded = false, uint32_t lo = 0u,
                                                  uint32_t hi = 0u) {
     const int lane = lane_id(), wave = threadIdx.x >> 6;
-    const Sel32 s = wg_select32([&](auto f) { items.visit([&](uint32_t c, uint32_t, bool p) { f(c, p); }); },
+    const Sel32 s = wg_select32<It::kThreads>([&](auto f) { items.visit([&](uint32_t c, uint32_t, bool p) { f(c, p); }); },
                                 (int64_t)k_eff, sm, bounded, lo, hi);
     const bool ties = s.need < s.have;    // (uniform) more items share the k-th score than fit
     uint32_t T2 = 0u;                     // then: inverted-position threshold inside the class key == T
     if (ties) {
         // positions are unique, so this select always ends with need == have: ipos >= T2 is exact
-        const Sel32 t = wg_select32(
+        const Sel32 t = wg_select32<It::kThreads>(
             [&](auto f) { items.visit([&](uint32_t c, uint32_t ip, bool p) { f(ip, p && c == s.T); }); },
             (int64_t)s.need, sm);
         T2 = t.T;
@@ -398,7 +403,7 @@ __global__ void __launch_bounds__(kSelThreads) threshold_kernel(Shape sh, Bufs b
     const int rank = pl.rank < pl.n_samp ? pl.rank : pl.n_samp;
     // two digits (18 bits from the first bit in which the samples differ) are plenty: stopping
     // there lowers the threshold by at most the last bin's width, a handful of extra samples
-    const Sel32 s = wg_select32([&](auto f) { items.visit([&](uint32_t c, uint32_t, bool p) { f(c, p); }); },
+    const Sel32 s = wg_select32<kSelThreads>([&](auto f) { items.visit([&](uint32_t c, uint32_t, bool p) { f(c, p); }); },
                                 (int64_t)rank, sm, false, 0u, 0u, 2);
     if (threadIdx.x == 0) {
         bf.thr[bh] = key_score(s.T);
@@ -408,10 +413,11 @@ __global__ void __launch_bounds__(kSelThreads) threshold_kernel(Shape sh, Bufs b
 }
 
 // Exact selection of one head over its full score row (the general path's selection).
+template <int NT, int CPT>     // the first CPT * NT scores stay in registers, the rest is streamed
 __device__ __forceinline__ void wg_select_dense(const Shape& sh, const Bufs& bf, int64_t bh, int64_t N, int k_eff,
                                                 SelShared& sm) {
-    const SrcDense src{bf.scores + bh * sh.Ncap, N};
-    const Items<(8192 + kSelThreads - 1) / kSelThreads, SrcDense> items(src);
+    const SrcDenseT<NT> src{bf.scores + bh * sh.Ncap, N};
+    const Items<CPT, SrcDenseT<NT>> items(src);
     const uint32_t kmax = wg_topk_emit(items, k_eff, sh.k, bf.sel_idx + bh * sh.k, bf.sel_val + bh * sh.k, sm);
     if (threadIdx.x == 0) bf.hmax[bh] = key_score(kmax);
 }
@@ -426,7 +432,7 @@ __device__ __forceinline__ void wg_redo_head(const Shape& sh, const Bufs& bf, in
     if (sh.dtype == DT_F16) wg_score_head<DT_F16>(sh, bf, b, h, N, row, sm);
     else if (sh.dtype == DT_BF16) wg_score_head<DT_BF16>(sh, bf, b, h, N, row, sm);
     else wg_score_head<DT_F32>(sh, bf, b, h, N, row, sm);
-    wg_select_dense(sh, bf, bh, N, k_eff, sm);
+    wg_select_dense<kSelThreads, 8>(sh, bf, bh, N, k_eff, sm);
 }
 
 // Exact selection among the candidates the filtered scan kept, read from the interleaved
@@ -502,7 +508,11 @@ __global__ void __launch_bounds__(kSelThreads) select_candidates_kernel(Shape sh
 }
 
 // Exact selection over the full score row, already in the score buffer (general path).
-__global__ void __launch_bounds__(kSelThreads) select_full_kernel(Shape sh, Bufs bf) {
+// NT threads per head: a batch of many short sequences is thousands of heads of a few
+// thousand scores each, and a workgroup no larger than the row needs keeps more heads in
+// flight per compute unit and makes every barrier of the select cheaper.
+template <int NT, int CPT>
+__global__ void __launch_bounds__(NT) select_full_kernel(Shape sh, Bufs bf) {
     __shared__ SelShared sm;
     const int b = blockIdx.y, h = blockIdx.x;
     const int64_t bh = (int64_t)b * sh.Hq + h;
@@ -513,7 +523,7 @@ __global__ void __launch_bounds__(kSelThreads) select_full_kernel(Shape sh, Bufs
         if (threadIdx.x == 0) bf.hmax[bh] = -INFINITY;
         return;
     }
-    wg_select_dense(sh, bf, bh, N, k_eff, sm);
+    wg_select_dense<NT, CPT>(sh, bf, bh, N, k_eff, sm);
 }
 
 // Both kernels are correct for any register-cache size (what does not fit is streamed); a
@@ -543,8 +553,18 @@ hipError_t launch_select_candidates(const Shape& s, const Bufs& b, hipStream_t s
     else hipLaunchKernelGGL((select_candidates_kernel<kCandSlots / kSelThreads>), grid, block, 0, st, s, b);
     return hipGetLastError();
 }
-hipError_t launch_select_full(const Shape& s, const Bufs& b, hipStream_t st) {
-    hipLaunchKernelGGL(select_full_kernel, dim3(s.Hq, s.B), dim3(kSelThreads), 0, st, s, b);
+hipError_t launch_select_full(const Shape& s, const Bufs& b, int64_t Nmax, hipStream_t st) {
+    const dim3 grid(s.Hq, s.B);
+#define TKA_SF(NT_, CPT_) hipLaunchKernelGGL((select_full_kernel<NT_, CPT_>), grid, dim3(NT_), 0, st, s, b)
+    // workgroup size and register-cached scores per thread by the longest row of the call
+    // (measured on batches of 256..4096 short sequences; any choice is correct)
+    if (Nmax <= 512) TKA_SF(64, 8);
+    else if (Nmax <= 1024) TKA_SF(64, 16);
+    else if (Nmax <= 2048) TKA_SF(128, 16);
+    else if (Nmax <= 4096) TKA_SF(256, 16);
+    else if (Nmax <= 8192) TKA_SF(256, 32);
+    else TKA_SF(kSelThreads, 8);
+#undef TKA_SF
     return hipGetLastError();
 }
 
