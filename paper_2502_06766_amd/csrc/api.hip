@@ -395,6 +395,12 @@ static bool choose_segments(const topk_attn_t* h, const Shape& s, int64_t nmax, 
     if (P * 4 > kMaxSeg) P = kMaxSeg / 4;
     if (P < 1) P = 1;
     while (P & (P - 1)) P &= P - 1;          // power of two: the selection indexes segments by mask
+    {   // rounding down may leave the chip a quarter empty: take the next power of two if it stays within 1.5 x
+        const int64_t streams = (int64_t)scan_grid_z(s) * s.Hkv;
+        if (streams * P * 8 < target_wgs * 7 && streams * P * 2 * 2 <= target_wgs * 3 && P * 2 * 4 <= tiles &&
+            P * 2 * 4 <= kMaxSeg)
+            P *= 2;
+    }
     for (; P >= 1; P /= 2) {
         const int64_t ns = P * 4;
         const int64_t cap = (s.cand_cap / ns) & ~(int64_t)(kCandChunk - 1);

@@ -60,9 +60,9 @@ struct SrcDenseT {           // scores[i] at position i, i < n
         return 0xFFFFFFFFu - (uint32_t)(j * NT + (int)threadIdx.x);
     }
 };
-typedef SrcDenseT<kSelThreads> SrcDense;
-struct SrcSeg {              // candidate list of n_seg interleaved segments: entry e of segment g
-    static constexpr int kThreads = kSelThreads;
+template <int NT>
+struct SrcSegT {             // candidate list of n_seg interleaved segments: entry e of segment g
+    static constexpr int kThreads = NT;
     const uint64_t* segs;    // sits in slot cand_slot(e, g, n_seg); entries are (score bits << 32 | position)
     const uint32_t* seg_len; // LDS: entries per segment
     uint32_t* pos_lds;       // LDS: inverted positions of the cached slots, [slot j][thread]
@@ -81,9 +81,9 @@ struct SrcSeg {              // candidate list of n_seg interleaved segments: en
     }
     __device__ __forceinline__ uint32_t ipos(uint64_t e, int64_t) const { return 0xFFFFFFFFu - (uint32_t)e; }
     __device__ __forceinline__ void stash(int j, uint64_t e) const {
-        pos_lds[j * kSelThreads + (int)threadIdx.x] = 0xFFFFFFFFu - (uint32_t)e;
+        pos_lds[j * NT + (int)threadIdx.x] = 0xFFFFFFFFu - (uint32_t)e;
     }
-    __device__ __forceinline__ uint32_t cached_ipos(int j) const { return pos_lds[j * kSelThreads + (int)threadIdx.x]; }
+    __device__ __forceinline__ uint32_t cached_ipos(int j) const { return pos_lds[j * NT + (int)threadIdx.x]; }
 };
 
 // The items of one head as seen by one thread: register slot j holds the score key of
@@ -341,7 +341,7 @@ __device__ void wg_score_head(const Shape& sh, const Bufs& bf, int b, int h, int
     constexpr int EPL = Elem<DT>::kPerLoad;
     const int D = sh.D;
     const int64_t bh = (int64_t)b * sh.Hq + h;
-    for (int i = threadIdx.x; i < D; i += kSelThreads) {
+    for (int i = threadIdx.x; i < D; i += (int)blockDim.x) {
         const char* qp = static_cast<const char*>(bf.q) + (bh * D + i) * Elem<DT>::kBytes;
         float v;
         if (DT == DT_F32) v = *reinterpret_cast<const float*>(qp);
@@ -350,7 +350,7 @@ __device__ void wg_score_head(const Shape& sh, const Bufs& bf, int b, int h, int
         sm.qrow[i] = v;
     }
     __syncthreads();
-    const int lpr = D / EPL, rows_per_pass = kSelThreads / lpr;
+    const int lpr = D / EPL, rows_per_pass = (int)blockDim.x / lpr;
     const int rs = threadIdx.x / lpr, chunk = threadIdx.x % lpr;
     const char* Kh = static_cast<const char*>(bf.K) +
                      ((int64_t)cache_seq(sh, b) * sh.Hkv + h / sh.G) * sh.Ncap * D * Elem<DT>::kBytes;
@@ -372,8 +372,8 @@ __device__ void wg_score_head(const Shape& sh, const Bufs& bf, int b, int h, int
 
 // Threshold estimate: the rank-th largest of the sample scores of each head (any value
 // with `rank` samples at or above it serves); also clears the head's fallback flag.
-template <int CPT>     // CPT * kSelThreads sample scores are kept in registers, the rest is streamed
-__global__ void __launch_bounds__(kSelThreads) threshold_kernel(Shape sh, Bufs bf) {
+template <int CPT, int NT>     // NT threads; CPT * NT sample scores are kept in registers, the rest is streamed
+__global__ void __launch_bounds__(NT) threshold_kernel(Shape sh, Bufs bf) {
     __shared__ SelShared sm;
     const int b = blockIdx.y, h = blockIdx.x;
     const int64_t bh = (int64_t)b * sh.Hq + h;
@@ -398,12 +398,12 @@ __global__ void __launch_bounds__(kSelThreads) threshold_kernel(Shape sh, Bufs b
         }
         return;
     }
-    const SrcDense src{bf.samp + bh * sh.samp_cap, (int64_t)pl.n_samp};
-    const Items<CPT, SrcDense> items(src);
+    const SrcDenseT<NT> src{bf.samp + bh * sh.samp_cap, (int64_t)pl.n_samp};
+    const Items<CPT, SrcDenseT<NT>> items(src);
     const int rank = pl.rank < pl.n_samp ? pl.rank : pl.n_samp;
     // two digits (18 bits from the first bit in which the samples differ) are plenty: stopping
     // there lowers the threshold by at most the last bin's width, a handful of extra samples
-    const Sel32 s = wg_select32<kSelThreads>([&](auto f) { items.visit([&](uint32_t c, uint32_t, bool p) { f(c, p); }); },
+    const Sel32 s = wg_select32<NT>([&](auto f) { items.visit([&](uint32_t c, uint32_t, bool p) { f(c, p); }); },
                                 (int64_t)rank, sm, false, 0u, 0u, 2);
     if (threadIdx.x == 0) {
         bf.thr[bh] = key_score(s.T);
@@ -425,6 +425,7 @@ __device__ __forceinline__ void wg_select_dense(const Shape& sh, const Bufs& bf,
 // The exact redo of a head whose candidate list is unusable (its sequence cannot be filtered,
 // a segment overflowed, or the sampled threshold came out above the k-th score): the
 // workgroup rescores the whole head itself, then selects from the full row -- slow, rare, exact.
+template <int NT>
 __device__ __forceinline__ void wg_redo_head(const Shape& sh, const Bufs& bf, int b, int h, int64_t N, int k_eff,
                                           SelShared& sm) {
     const int64_t bh = (int64_t)b * sh.Hq + h;
@@ -432,22 +433,21 @@ __device__ __forceinline__ void wg_redo_head(const Shape& sh, const Bufs& bf, in
     if (sh.dtype == DT_F16) wg_score_head<DT_F16>(sh, bf, b, h, N, row, sm);
     else if (sh.dtype == DT_BF16) wg_score_head<DT_BF16>(sh, bf, b, h, N, row, sm);
     else wg_score_head<DT_F32>(sh, bf, b, h, N, row, sm);
-    wg_select_dense<kSelThreads, 8>(sh, bf, bh, N, k_eff, sm);
+    wg_select_dense<NT, 8>(sh, bf, bh, N, k_eff, sm);
 }
 
 // Exact selection among the candidates the filtered scan kept, read from the interleaved
 // per-wave segments.  A head without a usable list is redone exactly by the same workgroup.
-template <int CPT>     // CPT * kSelThreads candidate slots are kept on chip, the rest is streamed
-__global__ void __launch_bounds__(kSelThreads) select_candidates_kernel(Shape sh, Bufs bf) {
+template <int CPT, int NT>     // NT threads (>= n_seg); CPT * NT candidate slots are kept on chip, the rest is streamed
+__global__ void __launch_bounds__(NT) select_candidates_kernel(Shape sh, Bufs bf) {
     __shared__ SelShared sm;
-    __shared__ uint32_t pos_lds[CPT * kSelThreads];
+    __shared__ uint32_t pos_lds[CPT * NT];
     const int b = blockIdx.y, h = blockIdx.x;
     const int tid = threadIdx.x, lane = lane_id(), wave = tid >> 6;
     const int64_t bh = (int64_t)b * sh.Hq + h;
     // Everything the prologue needs from memory is asked for at once: this kernel runs on a
     // few dozen compute units at the end of a dependent chain of kernels, and every load it
-    // waits for on its own costs a full trip to memory (n_seg <= kMaxSeg <= kSelThreads).
-    static_assert(kMaxSeg <= kSelThreads, "one segment per thread");
+    // waits for on its own costs a full trip to memory (the host launches at least n_seg threads).
     const uint32_t flagged = bf.flags[bh];
     const float thr_h = bf.thr[bh];
     const bool has_seg = tid < sh.n_seg;
@@ -480,7 +480,7 @@ __global__ void __launch_bounds__(kSelThreads) select_candidates_kernel(Shape sh
         __syncthreads();
         uint32_t total = 0;
         kmx = 0;
-        for (int w = 0; w < kSelWaves; ++w) {
+        for (int w = 0; w < NT / kWave; ++w) {
             total += sm.wave_tot[w];
             max_len = sm.red_max[w] > max_len ? sm.red_max[w] : max_len;
             kmx = sm.red_min[w] > kmx ? sm.red_min[w] : kmx;
@@ -495,11 +495,11 @@ __global__ void __launch_bounds__(kSelThreads) select_candidates_kernel(Shape sh
         }
     }
     if (redo) {
-        wg_redo_head(sh, bf, b, h, N, k_eff, sm);
+        wg_redo_head<NT>(sh, bf, b, h, N, k_eff, sm);
         return;
     }
-    const SrcSeg src{bf.cand + bh * (int64_t)sh.cand_cap, sm.seg_len, pos_lds, 31 - __clz(sh.n_seg), (int)max_len};
-    const Items<CPT, SrcSeg> items(src);
+    const SrcSegT<NT> src{bf.cand + bh * (int64_t)sh.cand_cap, sm.seg_len, pos_lds, 31 - __clz(sh.n_seg), (int)max_len};
+    const Items<CPT, SrcSegT<NT>> items(src);
     // every candidate is >= the head's threshold and the scan reported the largest score; not so
     // after an index scan, whose candidates were re-scored since
     const uint32_t kmax = wg_topk_emit(items, k_eff, sh.k, bf.sel_idx + bh * sh.k, bf.sel_val + bh * sh.k, sm,
@@ -529,13 +529,24 @@ __global__ void __launch_bounds__(NT) select_full_kernel(Shape sh, Bufs bf) {
 // Both kernels are correct for any register-cache size (what does not fit is streamed); a
 // cache much larger than the data only costs loop trips over empty slots, which matters
 // when the whole step is a few tens of microseconds.
+// A call with many heads (a batch) whose rows are small takes 256-thread workgroups: several
+// fit a compute unit at once and every barrier of the select is cheaper; one head alone is
+// served faster by 1024 threads.
+static bool many_small_heads(const Shape& s) { return (int64_t)s.Hq * s.B >= 1024; }
+
 hipError_t launch_threshold(const Shape& s, const Bufs& b, int64_t Nmax, hipStream_t st) {
     const int n_samp = make_plan(Nmax, s.k < Nmax ? s.k : (int)Nmax, s.indexed).n_samp;
-    const dim3 grid(s.Hq, s.B), block(kSelThreads);
-    if (n_samp <= 2 * kSelThreads) hipLaunchKernelGGL(threshold_kernel<2>, grid, block, 0, st, s, b);
-    else if (n_samp <= 4 * kSelThreads) hipLaunchKernelGGL(threshold_kernel<4>, grid, block, 0, st, s, b);
-    else if (n_samp <= 8 * kSelThreads) hipLaunchKernelGGL(threshold_kernel<8>, grid, block, 0, st, s, b);
-    else hipLaunchKernelGGL((threshold_kernel<(kSampMax + kSelThreads - 1) / kSelThreads>), grid, block, 0, st, s, b);
+    const dim3 grid(s.Hq, s.B);
+#define TKA_TH(CPT_, NT_) hipLaunchKernelGGL((threshold_kernel<CPT_, NT_>), grid, dim3(NT_), 0, st, s, b)
+    if (many_small_heads(s) && n_samp <= 4096) {
+        if (n_samp <= 1024) TKA_TH(4, 256);
+        else if (n_samp <= 2048) TKA_TH(8, 256);
+        else TKA_TH(16, 256);
+    } else if (n_samp <= 2 * kSelThreads) TKA_TH(2, kSelThreads);
+    else if (n_samp <= 4 * kSelThreads) TKA_TH(4, kSelThreads);
+    else if (n_samp <= 8 * kSelThreads) TKA_TH(8, kSelThreads);
+    else TKA_TH((kSampMax + kSelThreads - 1) / kSelThreads, kSelThreads);
+#undef TKA_TH
     return hipGetLastError();
 }
 hipError_t launch_select_candidates(const Shape& s, const Bufs& b, hipStream_t st) {
@@ -546,11 +557,18 @@ hipError_t launch_select_candidates(const Shape& s, const Bufs& b, hipStream_t s
     len = (len + kCandChunk - 1) / kCandChunk * kCandChunk;
     if (len > s.seg_cap) len = s.seg_cap;
     const int64_t slots = len * s.n_seg;
-    const dim3 grid(s.Hq, s.B), block(kSelThreads);
-    if (slots <= 4 * kSelThreads) hipLaunchKernelGGL(select_candidates_kernel<4>, grid, block, 0, st, s, b);
-    else if (slots <= 8 * kSelThreads) hipLaunchKernelGGL(select_candidates_kernel<8>, grid, block, 0, st, s, b);
-    else if (slots <= 16 * kSelThreads) hipLaunchKernelGGL(select_candidates_kernel<16>, grid, block, 0, st, s, b);
-    else hipLaunchKernelGGL((select_candidates_kernel<kCandSlots / kSelThreads>), grid, block, 0, st, s, b);
+    const dim3 grid(s.Hq, s.B);
+    static_assert(kMaxSeg <= kSelThreads, "one candidate segment per thread in the selection's prologue");
+#define TKA_SC(CPT_, NT_) hipLaunchKernelGGL((select_candidates_kernel<CPT_, NT_>), grid, dim3(NT_), 0, st, s, b)
+    if (many_small_heads(s) && slots <= 8192 && s.n_seg <= 256) {
+        if (slots <= 2048) TKA_SC(8, 256);
+        else if (slots <= 4096) TKA_SC(16, 256);
+        else TKA_SC(32, 256);
+    } else if (slots <= 4 * kSelThreads) TKA_SC(4, kSelThreads);
+    else if (slots <= 8 * kSelThreads) TKA_SC(8, kSelThreads);
+    else if (slots <= 16 * kSelThreads) TKA_SC(16, kSelThreads);
+    else TKA_SC(kCandSlots / kSelThreads, kSelThreads);
+#undef TKA_SC
     return hipGetLastError();
 }
 hipError_t launch_select_full(const Shape& s, const Bufs& b, int64_t Nmax, hipStream_t st) {
