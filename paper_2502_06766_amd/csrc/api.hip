@@ -72,7 +72,13 @@ WsLayout ws_layout(const topk_attn_config* c) {
     WsLayout w;
     const size_t BH = (size_t)c->n_seqs * (c->max_queries > 1 ? c->max_queries : 1) * c->n_q_heads;
     const int64_t max_k = c->max_k < c->max_tokens ? c->max_k : c->max_tokens;
-    w.cand_cap = (int)(4 * max_k + 16384);
+    // candidate list per head: room for the expected candidates (about 2 k at most) and for the
+    // slack of its segments.  A call with few KV-head streams splits each stream into many
+    // wave segments (up to about 1024 waves over the chip, doubled where the split is rounded
+    // up), and every segment needs its own few dozen spare entries.
+    int64_t seg_max = 8 * ((512 + (int64_t)c->n_seqs * c->n_kv_heads - 1) / ((int64_t)c->n_seqs * c->n_kv_heads));
+    if (seg_max > kMaxSeg) seg_max = kMaxSeg;
+    w.cand_cap = (int)(4 * max_k + 16384 + 48 * seg_max);
     const int64_t max_w = c->max_window < c->max_tokens ? c->max_window : c->max_tokens;
     w.n_chunk_cap = (int)((c->max_k + kGatherRows - 1) / kGatherRows + (max_w + kGatherRows - 1) / kGatherRows);
     size_t o = 0;

@@ -108,6 +108,9 @@ def test_k_larger_than_n_pads():
     (wl.BF16, 8, 2, 50003, 256, 700),    # d = 256: one tile buffer per wave
     (wl.F16, 2, 2, 33000, 256, 64),      # d = 256, G = 1
     (wl.BF16, 8, 2, 60001, 32, 200),     # d = 32: 4 KiB tiles
+    (wl.F16, 4, 1, 300001, 128, 3000),   # one KV head (a head-sharded layer): 1024 wave segments per head
+    (wl.BF16, 8, 1, 200000, 128, 2000),  # the same with a group of 8 (row-tile scan)
+    (wl.F16, 12, 3, 150000, 64, 900),    # three KV heads: the segment split is rounded up
 ])
 def test_filter_path_sweep(dtype, Hq, Hkv, N, d, k):
     q, K, V = rand_case(Hq, Hkv, N, d, dtype, k, seed=N + k)
