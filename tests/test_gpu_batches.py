@@ -1,6 +1,7 @@
-"""GPU tests of the batched per-step append (Algorithm 1's concat for every sequence of a layer
-in one call): the cache bytes, the int8 index and the lengths it leaves must equal what
-per-sequence appends leave, and a decode over the result must match the oracle."""
+"""GPU tests of batched use: the per-step append for a whole batch (Algorithm 1's concat for every
+sequence of a layer in one call) must leave the cache bytes, the int8 index and the lengths that
+per-sequence appends leave, and decodes over batches of many sequences (short ones on the general
+path, long ones on the filtered path) must match the oracle."""
 import numpy as np
 import pytest
 import torch
@@ -138,5 +139,38 @@ def test_serving_batch_of_many_short_sequences():
                 assert sel.min() >= 0 and sel.max() < n and np.unique(sel).size == ke, f"seq {s} head {h}"
                 assert (idx[s, h, ke:] == -1).all()
             assert np.isfinite(out[s]).all()
+    finally:
+        cache.close()
+
+
+def test_batch_of_40_sequences_on_the_filtered_path():
+    """1280 heads in one call, ragged lengths of 33k..41k tokens: the filtered scan with the small
+    workgroups the threshold and candidate selections take when a call has many heads."""
+    dtype, Hq, Hkv, d, k, B = wl.BF16, 32, 8, 64, 300, 40
+    g = np.random.default_rng(5)
+    lens = g.integers(33000, 41000, size=B)
+    Nmax = int(lens.max())
+    q = wl.quantize(g.standard_normal((B, Hq, d)).astype(np.float32), dtype)
+    base_K = wl.quantize(g.standard_normal((Hkv, Nmax + 4096, d)).astype(np.float32), dtype)
+    base_V = wl.quantize(g.standard_normal((Hkv, Nmax + 4096, d)).astype(np.float32), dtype)
+    cache = ta.TopkAttnCache(1, B, Hq, Hkv, d, Nmax, k, dtype)
+    try:
+        host = []
+        for s in range(B):                          # every sequence: its own window of the base arrays
+            n, o = int(lens[s]), 97 * s
+            Ks = np.ascontiguousarray(base_K[:, o:o + n])
+            Ks = H.enforce_margin(q[s], Ks, dtype, k)[0]
+            Vs = np.ascontiguousarray(base_V[:, o:o + n])
+            host.append((Ks, Vs))
+            cache.append(0, s, H.to_torch(Ks, dtype, DEV), H.to_torch(Vs, dtype, DEV), head_major=True)
+        out, idx, vals, lse = cache.decode(0, H.to_torch(q, dtype, DEV), k)
+        torch.cuda.synchronize()
+        assert cache.last_fallbacks() == 0
+        out, idx, vals, lse = (t.cpu().numpy() for t in (out, idx, vals, lse))
+        for s in range(B):
+            Ks, Vs = host[s]
+            ref = c_oracle.topk_attention(q[s], Ks, Vs, dtype, k)
+            H.check_against_oracle(out[s], idx[s], vals[s], lse[s], ref, H.score_margin(q[s], Ks, dtype), k,
+                                   H.out_tolerance(dtype), float(np.abs(wl.widen(Vs, dtype)).max()), f"seq {s}")
     finally:
         cache.close()
