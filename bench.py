@@ -26,7 +26,7 @@ if ROOT not in sys.path:
 HBM_PEAK_GBPS = 8000.0   # MI355X HBM3E, published
 # HBM bytes one key-scan launch moves at the default workload, from rocprofv3 FETCH_SIZE + WRITE_SIZE
 # (profiles/decode_c3_hbm_counters.md, counters calibrated against copy kernels of known size).
-SCAN_TRAFFIC_BYTES_C3 = 2.1713e9
+SCAN_TRAFFIC_BYTES_C3 = 2.1714e9
 
 
 def main() -> int:
