@@ -469,7 +469,10 @@ static int decode_impl(topk_attn_t* h, int layer, const void* q, int n_queries, 
     bool fast = false;
     if (h->path != TOPK_ATTN_PATH_FULL && scan_mfma_supported(s) && nmax > 0) {
         const Plan longest = make_plan(nmax, k < nmax ? k : (int)nmax, s.indexed);
-        fast = plan_is_fast(longest, nmax, s.cand_cap, h->path == TOPK_ATTN_PATH_FILTER);
+        int64_t total = 0;               // searched tokens of the whole call
+        for (int i = 0; i < s.Bc; ++i) total += prefix_len(h->len[(size_t)layer * s.Bc + i], window);
+        fast = plan_is_fast(longest, nmax, s.cand_cap, h->path == TOPK_ATTN_PATH_FILTER,
+                            total >= kFilterBatchTokens ? kFilterMinNBatch : kFilterMinN);
         int64_t c_hi = 0;
         for (int i = 0; i < s.Bc && fast; ++i) {
             const int64_t n = prefix_len(h->len[(size_t)layer * s.Bc + i], window);

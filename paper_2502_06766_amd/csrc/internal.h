@@ -15,7 +15,13 @@ constexpr int kSelThreads = TKA_SEL_THREADS;   // workgroup size of the selectio
 constexpr int kGatherRows = 256;    // value rows handled by one gather workgroup
 constexpr int kSampMax = 16384;     // most sample scores per head in the threshold estimate
 constexpr int kSampMin = 1024;
-constexpr int kFilterMinN = 32768;  // below this the full path is faster (measured crossover)
+// Shortest cache the filtered scan is used for unless forced: below, writing all scores and
+// selecting over them is faster (measured crossovers: one sequence 16k tokens 46 against 56 us,
+// 30k tokens 72 against 65 us; in a batch the small kernels of the filtered path are shared by
+// more work and it wins from 8k tokens on once the call holds 128k tokens in all).
+constexpr int kFilterMinN = 24576;
+constexpr int kFilterMinNBatch = 8192;
+constexpr int64_t kFilterBatchTokens = 131072;
 constexpr int kMaxSeg = 1024;       // most candidate segments per head
 
 // Geometry of one decode call, passed by value to every kernel.
@@ -146,9 +152,10 @@ __host__ __device__ inline Plan make_plan(int64_t N, int k_eff, int indexed = 0)
 // The filtered scan needs the candidate list to fit; unless forced it is also skipped
 // for short caches and for selections so dense that nearly every key would be a candidate
 // (measured at 512k tokens: it wins up to k = 60 % of the cache, loses from 75 % on).
-__host__ __device__ inline bool plan_is_fast(const Plan& p, int64_t N, int cand_cap, bool force) {
+__host__ __device__ inline bool plan_is_fast(const Plan& p, int64_t N, int cand_cap, bool force,
+                                             int64_t min_n = kFilterMinN) {
     if (N < 256 || p.rank > p.n_samp || p.c_hi > cand_cap) return false;
-    return force || (N >= kFilterMinN && p.c_hi * 5 <= N * 4);
+    return force || (N >= min_n && p.c_hi * 5 <= N * 4);
 }
 
 // Position of sample s: one jittered position inside each stride-long stratum.
