@@ -529,10 +529,10 @@ __global__ void __launch_bounds__(NT) select_full_kernel(Shape sh, Bufs bf) {
 // Both kernels are correct for any register-cache size (what does not fit is streamed); a
 // cache much larger than the data only costs loop trips over empty slots, which matters
 // when the whole step is a few tens of microseconds.
-// A call with many heads (a batch) whose rows are small takes 256-thread workgroups: several
+// A call with many heads (a batch, 512 heads or more) whose rows are small takes 256-thread workgroups: several
 // fit a compute unit at once and every barrier of the select is cheaper; one head alone is
 // served faster by 1024 threads.
-static bool many_small_heads(const Shape& s) { return (int64_t)s.Hq * s.B >= 1024; }
+static bool many_small_heads(const Shape& s) { return (int64_t)s.Hq * s.B >= 512; }
 
 hipError_t launch_threshold(const Shape& s, const Bufs& b, int64_t Nmax, hipStream_t st) {
     const int n_samp = make_plan(Nmax, s.k < Nmax ? s.k : (int)Nmax, s.indexed).n_samp;
