@@ -112,7 +112,9 @@ int topk_attn_create(const topk_attn_config* cfg, topk_attn_t** out);
  * head-major [Hkv, n_new, d]: token_stride = d, head_stride = n_new*d).  Rows must be
  * 16-byte aligned.  The data is copied on `hip_stream` (a hipStream_t, may be NULL for
  * the default stream); the source may be reused once the stream has passed the call.
- * Errors: EINVAL (null, range, n_new < 0, misaligned), ECAPACITY. n_new == 0 is a no-op. */
+ * Errors: EINVAL (null, range, n_new < 0, misaligned), ECAPACITY. n_new == 0 is a no-op.
+ * The handle keeps a host copy of every length (argument checks, launch shapes) that advances
+ * once per call: an append recorded into a HIP graph must not be replayed (decode calls may). */
 int topk_attn_append_kv(topk_attn_t* h, int layer, int seq, const void* k_new, const void* v_new,
                         int64_t n_new, int64_t token_stride, int64_t head_stride, void* hip_stream);
 
