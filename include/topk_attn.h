@@ -138,7 +138,9 @@ int topk_attn_append_step(topk_attn_t* h, int layer, const void* k_new, const vo
  *         (lets a caller merge with attention over further keys, e.g. a recent window)
  * Ties between equal scores go to the lower position.  Scores are accumulated in fp32.
  * Asynchronous on `hip_stream`.  Errors: EINVAL (null h/q/out, layer range, k < 1,
- * k > max_k, a sequence with no tokens), EDEVICE. */
+ * k > max_k, a sequence with no tokens), EDEVICE.
+ * The launch shapes are chosen from the cached lengths at call time: a decode recorded into a
+ * HIP graph may be replayed as long as no sequence of the layer has grown since. */
 int topk_attn_decode(topk_attn_t* h, int layer, const void* q, int k, float* out, int32_t* idx,
                      float* vals, float* lse, void* hip_stream);
 
