@@ -245,6 +245,26 @@ def test_c2_llama_layer_128k_bf16():
     run_case(q, K, V, w.dtype, w.k, label="c2", expect_fallbacks=0)
 
 
+@pytest.mark.parametrize("w", [wl.C2, wl.C3.scaled(300000)], ids=["c2", "c3_300k"])
+def test_generator_output_as_it_comes_differs_only_inside_the_rounding_band(w):
+    """No margin enforced: the selected sets may differ from the float64 oracle's, but only among keys
+    whose score lies within delta of the k-th score, and the output keeps its tolerance."""
+    q, K, V = wl.make_quantized(w, 4)
+    ref = c_oracle.topk_attention(q, K, V, w.dtype, w.k)
+    S = c_oracle.scores(q, K, w.dtype)
+    delta = H.score_margin(q, K, w.dtype)
+    cache = ta.TopkAttnCache(1, 1, w.n_q_heads, w.n_kv_heads, w.head_dim, w.n_tokens, w.k, w.dtype)
+    try:
+        cache.append(0, 0, H.to_torch(K, w.dtype, DEV), H.to_torch(V, w.dtype, DEV), head_major=True)
+        out, idx, _, _ = cache.decode(0, H.to_torch(q, w.dtype, DEV)[None].contiguous(), w.k)
+        torch.cuda.synchronize()
+        frac = H.check_band_tolerant(out[0].cpu().numpy(), idx[0].cpu().numpy(), ref, S, delta, w.k,
+                                     H.out_tolerance(w.dtype), float(np.abs(wl.widen(V, w.dtype)).max()), w.name)
+        print(f"{w.name}: {frac:.3f} of the heads select exactly the oracle's set without a margin")
+    finally:
+        cache.close()
+
+
 def test_c3_llama_layer_1m_fp16():
     w = wl.C3
     q, K, V = wl.make_quantized(w, 0)
