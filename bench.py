@@ -6,8 +6,8 @@ over one layer of the N = 1M configuration (32 query heads, 8 KV heads, d = 128,
 k = 16384).  The cache is resident in HBM before timing starts; steps rotate over
 several layers so every scan reads HBM-cold keys.  Prints one JSON line.
 
---workload c2 | c4 | c5 times the other configurations the same way (they are parity-test
-cases, not the metric's workload): c2 one 128k-token layer, c4 sixteen sequences of 256k
+--workload c1 | c2 | c4 | c5 times the other configurations the same way (they are parity-test
+cases, not the metric's workload): c1 the small fp32 case (launch-bound), c2 one 128k-token layer, c4 sixteen sequences of 256k
 tokens per step, c5 one layer of the 32-layer 512k-token cache (all 32 resident, a step is
 one layer's decode).
 """
@@ -40,7 +40,7 @@ def main() -> int:
                     help="queries per step (a causal chunk through topk_attn_decode_multi); 1 is the metric's workload")
     ap.add_argument("--index", action="store_true",
                     help="approximate search through the int8 key index (exact refinement); not the metric's workload")
-    ap.add_argument("--workload", default="c3", choices=["c2", "c3", "c4", "c5"],
+    ap.add_argument("--workload", default="c3", choices=["c1", "c2", "c3", "c4", "c5"],
                     help="c3 is the metric's workload; the others are timed the same way for reference")
     ap.add_argument("--k", type=int, default=0, help="override k (c4 is swept over 256, 1024, 4096 in the tests)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -60,13 +60,13 @@ def main() -> int:
         print("bench.py: no GPU visible", file=sys.stderr)
         return 1
     dev = torch.device("cuda", 0)
-    w = {"c2": wl.C2, "c3": wl.C3, "c4": wl.C4, "c5": wl.C5}[args.workload]
+    w = {"c1": wl.C1, "c2": wl.C2, "c3": wl.C3, "c4": wl.C4, "c5": wl.C5}[args.workload]
     default = args.workload == "c3" and not args.tokens and not args.k     # the metric's workload as it stands
     if args.tokens:
         w = w.scaled(args.tokens)
     N, k, d, Hq, Hkv, B = w.n_tokens, args.k or w.k, w.head_dim, w.n_q_heads, w.n_kv_heads, w.n_seqs
     # layers resident at once: enough distinct key bytes that no scan finds its keys in a cache
-    L = max(1, {"c2": 8, "c3": args.layers, "c4": 1, "c5": 32}[args.workload])
+    L = max(1, {"c1": 8, "c2": 8, "c3": args.layers, "c4": 1, "c5": 32}[args.workload])
 
     t0 = time.time()
     q, K, V = wl.make_quantized(w, args.seed, threads=16)
@@ -136,7 +136,8 @@ def main() -> int:
 
     # streaming-read ceiling over the same key bytes (128-bit loads, nothing else)
     sink = torch.zeros(16384, dtype=torch.int32, device=dev)
-    k_bytes = B * Hkv * N * d * 2          # the key bytes of one layer
+    e = 4 if w.dtype == wl.F32 else 2
+    k_bytes = B * Hkv * N * d * e          # the key bytes of one layer
     probe_ms = []
     for i in range(L * 3):
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
@@ -147,7 +148,6 @@ def main() -> int:
         probe_ms.append(e0.elapsed_time(e1))
     probe_gbps = k_bytes / (min(probe_ms[min(L, len(probe_ms) - 1):]) * 1e-3) / 1e9
 
-    e = 2
     alg_bytes = k_bytes + B * M * (Hq * k * d * e + Hq * d * (e + 4) + Hq * k * 4)
     keys_per_s = B * Hkv * N / (ms_per_step * 1e-3)
     # every key is needed once per launch, however many blocks of (query, head) rows walk over it
@@ -181,7 +181,7 @@ def main() -> int:
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
-        "dtype": "bf16" if w.dtype == wl.BF16 else "f16",
+        "dtype": {wl.F32: "f32", wl.F16: "f16", wl.BF16: "bf16"}[w.dtype],
         "data": "synthetic",
         "config": {"workload": w.name, "n_q_heads": Hq, "n_kv_heads": Hkv, "head_dim": d, "n_tokens": N,
                    "k": k, "layers_rotated": L, "n_seqs": B, "queries_per_step": M,
@@ -194,7 +194,7 @@ def main() -> int:
         "step_ms_min": per_step[0],
         "read_probe_gbps": probe_gbps,
         "filter_fallback_heads": fallbacks,
-        "roofline": {"bound": "hbm", "kernel": ("scan8_kernel (filter)" if args.index else "scan_mfma_kernel (filter)") if M == 1 else "scan_rows_kernel (filter)", "achieved": scan_gbps,
+        "roofline": {"bound": "hbm", "kernel": "scan_generic_kernel (full)" if w.dtype == wl.F32 else ("scan8_kernel (filter)" if args.index else "scan_mfma_kernel (filter)") if M == 1 else "scan_rows_kernel (filter)", "achieved": scan_gbps,
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": scan_gbps / HBM_PEAK_GBPS,
                      "traffic": SCAN_TRAFFIC_BYTES_C3 if default and M == 1 and not args.index else None, "ms_per_launch": scan_ms,
                      "bytes_per_launch": scan_bytes,
