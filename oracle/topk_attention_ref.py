@@ -25,7 +25,10 @@ dominant keys, truncation-error bound; for the window variant: window 0 equals t
 plain step, full coverage equals library dense attention, brute force on tiny N, and
 the log-sum-exp merge of a top-k prefix with library attention over the window;
 for the multi-query variant: k >= N with a causal chunk equals library causal dense
-attention, the last causal query equals the plain step, and brute force on tiny N).
+attention, the last causal query equals the plain step, and brute force on tiny N;
+for k_schedule: hand-computed shares including ties in the fractional parts, closed forms
+(uniform split, two-layer ratio, arithmetic progression), sum = budget, every layer >= 1,
+the quota rule and monotonicity in the ratio).
 No function is "parity unpinned".
 """
 from __future__ import annotations

@@ -135,7 +135,12 @@ def test_k_schedule_closed_forms_and_invariants():
     assert ta.topk_attn_k_schedule(4000, 2, 3.0) == [1000, 3000]
     # arithmetic progression when it divides: L = 5, ratio 3 -> weights 1, 1.5, 2, 2.5, 3 (sum 10)
     assert ta.topk_attn_k_schedule(1000, 5, 3.0) == [100, 150, 200, 250, 300]
-    for total, L, r in [(262144, 32, 4.0), (1000, 7, 2.5), (33, 32, 8.0), (5000, 3, 0.5), (77, 1, 9.0)]:
+    # ties in the fractional parts go to the later layer (the oracle's own pins fix these values)
+    assert ta.topk_attn_k_schedule(10, 4, 1.0) == [2, 2, 3, 3] == ref.k_schedule(10, 4, 1.0)
+    assert ta.topk_attn_k_schedule(6, 2, 3.0) == [1, 5] == ref.k_schedule(6, 2, 3.0)
+    assert ta.topk_attn_k_schedule(100, 8, 1.0) == ref.k_schedule(100, 8, 1.0)
+    for total, L, r in [(262144, 32, 4.0), (1000, 7, 2.5), (33, 32, 8.0), (5000, 3, 0.5), (77, 1, 9.0),
+                        (7, 3, 3.0), (11, 3, 2.0), (9, 3, 0.5), (12345, 17, 1.0), (999, 10, 10.0)]:
         ks = ta.topk_attn_k_schedule(total, L, r)
         assert sum(ks) == total and min(ks) >= 1 and len(ks) == L
         assert ks == ref.k_schedule(total, L, r)

@@ -559,3 +559,68 @@ def test_rerank_with_all_candidates_is_the_exact_step_and_recall_grows():
             np.testing.assert_allclose(got[2][h], (K[h // 2][got[1][h]] @ q[h]), rtol=1e-12)
     assert prev == 1.0            # 3x over-fetch recovers everything at this noise level
     assert i8.recall_at_k(np.array([1, 2, -1]), np.array([2, 3, -1, -1])) == 0.5
+
+
+# ---------------------------------------------------------------- layer-wise k ("Layer-Wise Settings for k")
+# Pins of ref.k_schedule that do not pass through the HIP library: hand-computed shares,
+# closed forms and invariants of a fixed-budget largest-remainder split.
+def test_k_schedule_hand_computed_cases():
+    # uniform budget that divides: every layer the same
+    assert ref.k_schedule(32 * 8192, 32, 1.0) == [8192] * 32
+    assert ref.k_schedule(77, 1, 9.0) == [77]
+    # two layers, last/first = 3: shares 1/4 and 3/4
+    assert ref.k_schedule(4000, 2, 3.0) == [1000, 3000]
+    # five layers, ratio 3: weights 1, 1.5, 2, 2.5, 3 (sum 10) -> an arithmetic progression
+    assert ref.k_schedule(1000, 5, 3.0) == [100, 150, 200, 250, 300]
+    # three layers, ratio 3, budget 7: shares 7/6, 14/6, 21/6 -> floors 1, 2, 3; the one key left goes
+    # to the largest fractional part (0.5, the last layer)
+    assert ref.k_schedule(7, 3, 3.0) == [1, 2, 4]
+    # three layers, ratio 2, budget 11: weights 1, 1.5, 2 (sum 4.5) -> shares 2.444, 3.667, 4.889 ->
+    # floors 2, 3, 4; two keys left go to fractions 0.889 and 0.667
+    assert ref.k_schedule(11, 3, 2.0) == [2, 4, 5]
+    # decreasing schedule (ratio 1/2), budget 9, three layers: weights 1, 0.75, 0.5 (sum 2.25) ->
+    # shares 4, 3, 2 exactly
+    assert ref.k_schedule(9, 3, 0.5) == [4, 3, 2]
+
+
+def test_k_schedule_ties_go_to_the_later_layer():
+    # all fractional parts equal (2.5 each): the two keys left go to the last two layers
+    assert ref.k_schedule(10, 4, 1.0) == [2, 2, 3, 3]
+    # 100 over 8 layers: 12.5 each, four keys left -> the last four layers
+    assert ref.k_schedule(100, 8, 1.0) == [12, 12, 12, 12, 13, 13, 13, 13]
+    # ratio 3, two layers, budget 6: shares 1.5 and 4.5 tie at 0.5 -> the later layer is rounded up
+    assert ref.k_schedule(6, 2, 3.0) == [1, 5]
+
+
+@pytest.mark.parametrize("total,L,r", [(262144, 32, 4.0), (1000, 7, 2.5), (33, 32, 8.0), (5000, 3, 0.5),
+                                        (32, 32, 5.0), (12345, 17, 1.0), (999, 10, 10.0)])
+def test_k_schedule_invariants(total, L, r):
+    ks = ref.k_schedule(total, L, r)
+    assert len(ks) == L and sum(ks) == total and min(ks) >= 1
+    assert all(isinstance(x, int) for x in ks)
+    # quota rule of a largest-remainder split: every layer within one key of its exact share
+    # (shares below one key are lifted to one, which can only push the others down, never up)
+    w = np.array([1.0 + (r - 1.0) * l / (L - 1) if L > 1 else 1.0 for l in range(L)])
+    share = total * w / w.sum()
+    if share.min() >= 1.0:
+        assert (np.abs(np.array(ks) - share) < 1.0 + 1e-9).all()
+    else:
+        assert (np.array(ks) <= np.maximum(share, 1.0) + 1.0 + 1e-9).all()
+    # linear in the layer up to rounding, in the direction the ratio says
+    d = np.diff(ks)
+    if total >= 8 * L:
+        assert (np.abs(np.diff(d)) <= 2).all()
+    assert (d >= -1).all() if r >= 1 else (d <= 1).all()
+
+
+def test_k_schedule_is_monotone_in_the_ratio():
+    # a larger last/first ratio moves budget from the first layer to the last
+    first, last = [], []
+    for r in (1.0, 1.5, 2.0, 3.0, 5.0, 9.0):
+        ks = ref.k_schedule(64000, 16, r)
+        first.append(ks[0]); last.append(ks[-1])
+        assert abs(ks[-1] / ks[0] - r) < 0.01 * r       # the ratio asked for, up to rounding
+    assert first == sorted(first, reverse=True) and last == sorted(last)
+    # ratio r and 1/r mirror each other (up to which side of a tie is rounded up)
+    a, b = ref.k_schedule(64000, 16, 4.0), ref.k_schedule(64000, 16, 0.25)
+    assert max(abs(x - y) for x, y in zip(a, b[::-1])) <= 1
