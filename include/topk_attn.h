@@ -39,7 +39,9 @@ enum {
     TOPK_ATTN_ECAPACITY = 2,    /* append would exceed max_tokens */
     TOPK_ATTN_EUNSUPPORTED = 3, /* head_dim / dtype / head grouping the kernels do not cover */
     TOPK_ATTN_EDEVICE = 4,      /* a HIP call failed */
-    TOPK_ATTN_ENOMEM = 5        /* host allocation failed, or a caller buffer is too small */
+    TOPK_ATTN_ENOMEM = 5,       /* host allocation failed, or a caller buffer is too small */
+    TOPK_ATTN_ESCRATCH = 6      /* topk_attn_decode_static: the configuration needs more per-call scratch
+                                   than the library's built-in buffer holds */
 };
 
 enum { TOPK_ATTN_F32 = 0, TOPK_ATTN_F16 = 1, TOPK_ATTN_BF16 = 2 }; /* element type of q, K, V */
@@ -143,6 +145,23 @@ int topk_attn_append_step(topk_attn_t* h, int layer, const void* k_new, const vo
  * HIP graph may be replayed as long as no sequence of the layer has grown since. */
 int topk_attn_decode(topk_attn_t* h, int layer, const void* q, int k, float* out, int32_t* idx,
                      float* vals, float* lse, void* hip_stream);
+
+/* topk_attn_decode for callers that cannot allocate device memory for the call or hand over a
+ * workspace they may reuse: code under HIP graph capture, tight serving loops, harnesses that
+ * forbid allocation.  Same arguments, same kernels and bit-identical results, but every per-call
+ * buffer (sample scores, thresholds, candidate lists, the score buffer of the exact redo, partial
+ * sums; internal idx / vals when the caller passes none) lives in a buffer built into the
+ * library: a device array of TOPK_ATTN_STATIC_SCRATCH_BYTES that every GPU the library runs on
+ * holds until the process ends.  Only the cache lengths are still read from the handle's
+ * workspace.  The call allocates and frees nothing and enqueues kernels only.
+ * Limit: ESCRATCH (nothing enqueued) if topk_attn_workspace_bytes(cfg) minus the lengths' share
+ * (n_layers * n_seqs * 4, rounded up to 256) exceeds TOPK_ATTN_STATIC_SCRATCH_BYTES -- one
+ * Llama-8B-shaped layer of 128k tokens at k = 2048 fits, a million-token layer does not.
+ * All calls on one GPU, from whatever handle, share the one array: the call clears the words
+ * that must start at zero itself, and two such calls that overlap in time on one GPU race. */
+#define TOPK_ATTN_STATIC_SCRATCH_BYTES ((size_t)48 << 20)
+int topk_attn_decode_static(topk_attn_t* h, int layer, const void* q, int k, float* out, int32_t* idx,
+                            float* vals, float* lse, void* hip_stream);
 
 /* Decode step with the recent-token window of Algorithm 1 (its K_gen / V_gen, "resembles
  * windowed attention"): for each sequence the last min(window, N_b) cached tokens are always

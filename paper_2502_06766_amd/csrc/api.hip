@@ -6,6 +6,7 @@
 
 #include <algorithm>
 #include <cmath>
+#include <mutex>
 #include <new>
 #include <utility>
 #include <vector>
@@ -170,7 +171,34 @@ __global__ void __launch_bounds__(256) read_probe_kernel(const u32x4* __restrict
     if ((threadIdx.x & 63) == 0) atomicXor(&sink[blockIdx.x & 16383], acc);
 }
 
+__global__ void zero_words_kernel(uint32_t* p, size_t n) {
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x) p[i] = 0u;
+}
+
 }  // namespace
+
+// Built-in scratch of topk_attn_decode_static: the per-call buffers of one decode (everything the
+// handle's workspace holds except the cache lengths) for callers that bring no workspace of
+// their own to that call.  One copy per GPU, at its own address, held until the process ends.
+constexpr size_t kStaticScratchBytes = (size_t)48 << 20;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+// Device address of `scratch` on each GPU (the array's name is only a host-side stand-in for
+// it), looked up once per device with that device current.
+constexpr int kMaxDevices = 64;
+static void* g_scratch_ptr[kMaxDevices];
+static std::mutex g_scratch_mutex;
+static int scratch_address(int device, void** out) {
+    if (device < 0 || device >= kMaxDevices) return TOPK_ATTN_EINVAL;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[device]) {
+        void* p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return TOPK_ATTN_EDEVICE;
+        g_scratch_ptr[device] = p;
+    }
+    *out = g_scratch_ptr[device];
+    return TOPK_ATTN_OK;
+}
 
 constexpr int kTimingSlots = 512;
 
@@ -181,6 +209,8 @@ struct topk_attn {
     std::vector<int64_t> len;   // host mirror of the device lengths, [L][B]
     int path;
     bool last_fast;
+    bool last_static;           // the last decode used the built-in scratch
+    char* scratch_dev;          // this device's copy of the built-in scratch
     int n_cu;                   // compute units of the device
     // optional event pairs around the key scan of each decode (measurement only)
     bool timing;
@@ -225,6 +255,13 @@ int topk_attn_create(const topk_attn_config* cfg, topk_attn_t** out) {
     hipDeviceProp_t prop;
     if (hipGetDeviceProperties(&prop, cfg->device) != hipSuccess) { delete h; return TOPK_ATTN_EDEVICE; }
     h->n_cu = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
+    h->last_static = false;
+    {   // cfg->device is current here
+        void* p = nullptr;
+        const int rc = scratch_address(cfg->device, &p);
+        if (rc != TOPK_ATTN_OK) { delete h; return rc; }
+        h->scratch_dev = static_cast<char*>(p);
+    }
     // lengths and the small per-head control words start at zero
     if (hipMemset(cfg->workspace, 0, w.cand) != hipSuccess || hipDeviceSynchronize() != hipSuccess) {
         delete h;
@@ -344,7 +381,8 @@ int topk_attn_append_step(topk_attn_t* h, int layer, const void* k_new, const vo
     return TOPK_ATTN_OK;
 }
 
-static void fill_call(topk_attn_t* h, int layer, const void* q, int k, int n_queries, Shape* s, Bufs* b) {
+static void fill_call(topk_attn_t* h, int layer, const void* q, int k, int n_queries, Shape* s, Bufs* b,
+                      bool use_static = false) {
     const topk_attn_config& c = h->cfg;
     const int e = elem_bytes(c.dtype);
     s->Bc = c.n_seqs; s->M = n_queries; s->causal = 0; s->B = c.n_seqs * n_queries;
@@ -356,7 +394,9 @@ static void fill_call(topk_attn_t* h, int layer, const void* q, int k, int n_que
     s->Ncap = c.max_tokens;
     s->indexed = 0;
     s->cand_est = 0;
-    char* ws = static_cast<char*>(c.workspace);
+    char* const ws_len = static_cast<char*>(c.workspace);
+    // everything after the lengths is per-call scratch: the handle's workspace, or the library's own array
+    char* const ws = use_static ? reinterpret_cast<char*>(reinterpret_cast<uintptr_t>(h->scratch_dev) - h->ws.thr) : ws_len;
     const size_t layer_b = (size_t)c.n_seqs * c.n_kv_heads * (size_t)c.max_tokens * c.head_dim * e;
     b->K = static_cast<char*>(c.kv_storage) + (size_t)layer * layer_b;
     b->V = static_cast<char*>(c.kv_storage) + h->kv_half + (size_t)layer * layer_b;
@@ -370,7 +410,7 @@ static void fill_call(topk_attn_t* h, int layer, const void* q, int k, int n_que
     }
     b->q8 = reinterpret_cast<int8_t*>(ws + h->ws.q8);
     b->qscale = reinterpret_cast<float*>(ws + h->ws.qscale);
-    b->len = reinterpret_cast<int32_t*>(ws + h->ws.len) + (size_t)layer * c.n_seqs;
+    b->len = reinterpret_cast<int32_t*>(ws_len + h->ws.len) + (size_t)layer * c.n_seqs;
     b->thr = reinterpret_cast<float*>(ws + h->ws.thr);
     b->samp = reinterpret_cast<float*>(ws + h->ws.samp);
     b->seg_cnt = reinterpret_cast<uint32_t*>(ws + h->ws.seg_cnt);
@@ -438,8 +478,9 @@ static int lengths_of(const topk_attn_t* h, int layer, int window, int64_t min_t
 }
 
 static int decode_impl(topk_attn_t* h, int layer, const void* q, int n_queries, int causal, int k, int window,
-                       float* out, int32_t* idx, float* vals, float* lse, void* hip_stream) {
+                       float* out, int32_t* idx, float* vals, float* lse, void* hip_stream, bool use_static = false) {
     if (!h || !q || !out) return TOPK_ATTN_EINVAL;
+    if (use_static && h->ws.total - h->ws.thr > kStaticScratchBytes) return TOPK_ATTN_ESCRATCH;
     if (layer < 0 || layer >= h->cfg.n_layers) return TOPK_ATTN_EINVAL;
     if (k < 1 || k > h->cfg.max_k) return TOPK_ATTN_EINVAL;
     if (window < 0 || window > h->cfg.max_window) return TOPK_ATTN_EINVAL;
@@ -452,7 +493,7 @@ static int decode_impl(topk_attn_t* h, int layer, const void* q, int n_queries, 
     if (lengths_of(h, layer, window, causal ? n_queries : 1, &nmin, &nmax) != TOPK_ATTN_OK) return TOPK_ATTN_EINVAL;
     hipStream_t st = (hipStream_t)hip_stream;
     Shape s; Bufs b;
-    fill_call(h, layer, q, k, n_queries, &s, &b);
+    fill_call(h, layer, q, k, n_queries, &s, &b, use_static);
     s.window = window;
     s.causal = causal ? 1 : 0;
     b.out = out; b.lse = lse;
@@ -485,6 +526,16 @@ static int decode_impl(topk_attn_t* h, int layer, const void* q, int n_queries, 
     }
     if (!fast) s.indexed = 0;      // no filtered scan: exact path
     hipError_t e = hipSuccess;
+    if (use_static) {
+        // the array keeps what the last call on this GPU left: the per-head control words start at zero
+        // (a fill kernel, so that the call may be recorded into a HIP graph)
+        uint32_t* first = b.flags;
+        const size_t n_words = (size_t)(reinterpret_cast<char*>(b.fallback_total) + sizeof(uint32_t) -
+                                        reinterpret_cast<char*>(first)) / sizeof(uint32_t);
+        hipLaunchKernelGGL(zero_words_kernel, dim3((unsigned)((n_words + 255) / 256 < 64 ? (n_words + 255) / 256 : 64)),
+                           dim3(256), 0, st, first, n_words);
+        e = hipGetLastError();
+    }
     const bool timed = h->timing && h->ev_used < kTimingSlots;
     if (fast && s.indexed) {
         e = launch_quantize_rows(s.dtype, s.D, q, (int64_t)s.B * s.Hq, 0, 1, b.q8, b.qscale, 0, st);
@@ -515,12 +566,18 @@ static int decode_impl(topk_attn_t* h, int layer, const void* q, int n_queries, 
     }
     if (e == hipSuccess) e = launch_gather(s, b, st);
     h->last_fast = fast;
+    h->last_static = use_static;
     return e == hipSuccess ? TOPK_ATTN_OK : TOPK_ATTN_EDEVICE;
 }
 
 int topk_attn_decode(topk_attn_t* h, int layer, const void* q, int k, float* out, int32_t* idx, float* vals,
                      float* lse, void* hip_stream) {
     return decode_impl(h, layer, q, 1, 0, k, 0, out, idx, vals, lse, hip_stream);
+}
+
+int topk_attn_decode_static(topk_attn_t* h, int layer, const void* q, int k, float* out, int32_t* idx, float* vals,
+                            float* lse, void* hip_stream) {
+    return decode_impl(h, layer, q, 1, 0, k, 0, out, idx, vals, lse, hip_stream, true);
 }
 
 int topk_attn_decode_window(topk_attn_t* h, int layer, const void* q, int k, int window, float* out, int32_t* idx,
@@ -615,7 +672,9 @@ int topk_attn_last_fallbacks(topk_attn_t* h, int* n_heads) {
     *n_heads = 0;
     if (!h->last_fast) return TOPK_ATTN_OK;
     uint32_t v = 0;
-    if (hipMemcpy(&v, static_cast<char*>(h->cfg.workspace) + h->ws.fallback, sizeof v, hipMemcpyDeviceToHost) !=
+    const char* where = h->last_static ? h->scratch_dev + (h->ws.fallback - h->ws.thr)
+                                       : static_cast<char*>(h->cfg.workspace) + h->ws.fallback;
+    if (hipMemcpy(&v, where, sizeof v, hipMemcpyDeviceToHost) !=
         hipSuccess)
         return TOPK_ATTN_EDEVICE;
     *n_heads = (int)v;
@@ -672,6 +731,7 @@ const char* topk_attn_strerror(int code) {
         case TOPK_ATTN_EUNSUPPORTED: return "unsupported configuration";
         case TOPK_ATTN_EDEVICE: return "HIP error";
         case TOPK_ATTN_ENOMEM: return "out of memory or buffer too small";
+        case TOPK_ATTN_ESCRATCH: return "configuration needs more per-call scratch than the library's built-in buffer holds";
         default: return "unknown error";
     }
 }

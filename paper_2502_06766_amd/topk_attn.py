@@ -15,14 +15,14 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 # TOPK_ATTN_LIB selects another build of the same library (A/B measurements)
 LIB_PATH = os.environ.get("TOPK_ATTN_LIB") or os.path.join(_HERE, "libtopk_attn.so")
 
-OK, EINVAL, ECAPACITY, EUNSUPPORTED, EDEVICE, ENOMEM = range(6)
+OK, EINVAL, ECAPACITY, EUNSUPPORTED, EDEVICE, ENOMEM, ESCRATCH = range(7)
 F32, F16, BF16 = 0, 1, 2
 PATH_AUTO, PATH_FULL, PATH_FILTER, PATH_INDEX = 0, 1, 2, 3
 INDEX_NONE, INDEX_INT8 = 0, 1
 
 EXPORTS = [
     "topk_attn_kv_bytes", "topk_attn_workspace_bytes", "topk_attn_create", "topk_attn_append_kv", "topk_attn_append_step",
-    "topk_attn_decode", "topk_attn_decode_window", "topk_attn_decode_multi", "topk_attn_decode_layers", "topk_attn_k_schedule", "topk_attn_scores", "topk_attn_length", "topk_attn_reset", "topk_attn_set_path",
+    "topk_attn_decode", "topk_attn_decode_static", "topk_attn_decode_window", "topk_attn_decode_multi", "topk_attn_decode_layers", "topk_attn_k_schedule", "topk_attn_scores", "topk_attn_length", "topk_attn_reset", "topk_attn_set_path",
     "topk_attn_last_fallbacks", "topk_attn_set_scan_timing", "topk_attn_scan_time", "topk_attn_read_probe", "topk_attn_strerror", "topk_attn_destroy",
 ]
 
@@ -79,6 +79,8 @@ def lib() -> ctypes.CDLL:
         L.topk_attn_append_step.restype = i32
         L.topk_attn_decode.argtypes = [vp, i32, vp, i32, vp, vp, vp, vp, vp]
         L.topk_attn_decode.restype = i32
+        L.topk_attn_decode_static.argtypes = [vp, i32, vp, i32, vp, vp, vp, vp, vp]
+        L.topk_attn_decode_static.restype = i32
         L.topk_attn_decode_window.argtypes = [vp, i32, vp, i32, i32, vp, vp, vp, vp, vp]
         L.topk_attn_decode_window.restype = i32
         L.topk_attn_decode_multi.argtypes = [vp, i32, vp, i32, i32, i32, i32, vp, vp, vp, vp, vp]
@@ -165,6 +167,11 @@ def topk_attn_append_step(h, layer, k_new_ptr, v_new_ptr, n_new, stream=0):
 def topk_attn_decode(h, layer, q_ptr, k, out_ptr, idx_ptr=0, vals_ptr=0, lse_ptr=0, stream=0):
     _check(lib().topk_attn_decode(h, layer, q_ptr, k, out_ptr, idx_ptr or None, vals_ptr or None,
                                   lse_ptr or None, stream), "topk_attn_decode")
+
+
+def topk_attn_decode_static(h, layer, q_ptr, k, out_ptr, idx_ptr=0, vals_ptr=0, lse_ptr=0, stream=0):
+    _check(lib().topk_attn_decode_static(h, layer, q_ptr, k, out_ptr, idx_ptr or None, vals_ptr or None,
+                                         lse_ptr or None, stream), "topk_attn_decode_static")
 
 
 def topk_attn_decode_window(h, layer, q_ptr, k, window, out_ptr, idx_ptr=0, vals_ptr=0, lse_ptr=0, stream=0):
