@@ -77,7 +77,7 @@ typedef struct {
     int32_t n_kv_heads;     /* Hkv, must divide Hq; Hq/Hkv <= 128 (<= 16 for fp32 caches) */
     int32_t head_dim;       /* d in {32, 64, 128, 256} */
     int64_t max_tokens;     /* capacity N_cap per (layer, sequence) */
-    int32_t max_k;          /* largest k decode will be called with; sizes the workspace */
+    int32_t max_k;          /* largest k decode will be called with (<= 2^28); sizes the workspace */
     int32_t dtype;          /* TOPK_ATTN_F32 / F16 / BF16 for q, K and V alike */
     int32_t device;         /* HIP device ordinal */
     int32_t max_window;     /* largest `window` topk_attn_decode_window will be called with (0 if unused) */
@@ -218,18 +218,15 @@ int topk_attn_decode_layers(topk_attn_t* h, int layer0, int n_layers, const void
                             int window, float* out, int32_t* idx, float* vals, float* lse,
                             void* hip_stream);
 
-/* Debug/measurement: write the full fp32 score matrix S = q K^T of `layer`
- * to scores [B, Hq, max_tokens] (device); entries beyond a sequence's length are
- * left untouched. */
-int topk_attn_scores(topk_attn_t* h, int layer, const void* q, float* scores, void* hip_stream);
-
 /* Tokens currently cached for (layer, seq); -1 on bad arguments. */
 int64_t topk_attn_length(const topk_attn_t* h, int layer, int seq);
 
 /* Forget the tokens of (layer, seq) (length := 0); enqueued on hip_stream. */
 int topk_attn_reset(topk_attn_t* h, int layer, int seq, void* hip_stream);
 
-/* Choose the selection pipeline (TOPK_ATTN_PATH_*); default AUTO.  EINVAL for an unknown
+/* Choose the search (TOPK_ATTN_PATH_*); default AUTO, the exact search.  TOPK_ATTN_PATH_INDEX is
+ * the method's approximate search over the int8 index; FULL and FILTER only force one of the two
+ * exact pipelines AUTO chooses between (same results; tests use them).  EINVAL for an unknown
  * value, or TOPK_ATTN_PATH_INDEX on a handle without an index.  With TOPK_ATTN_PATH_INDEX
  * the result of decode is approximate: a key whose coded score falls below the candidate
  * threshold is missed even if its exact score belongs to the k largest (recall@k against
@@ -237,26 +234,6 @@ int topk_attn_reset(topk_attn_t* h, int layer, int seq, void* hip_stream);
  * scores, and the softmax runs over exactly those.  topk_attn_scores then dumps the
  * approximate scores  float(codes(q) . codes(K_i)) * (scale_q * scale_i). */
 int topk_attn_set_path(topk_attn_t* h, int path);
-
-/* After the stream has been synchronised by the caller: number of (sequence, head)
- * pairs of the last decode whose filtered candidate list was unusable and were
- * recomputed by the full path.  Copies a few bytes device->host (synchronous). */
-int topk_attn_last_fallbacks(topk_attn_t* h, int* n_heads);
-
-/* Measurement aid: when enabled, every decode records a HIP event on its stream just
- * before and just after the key-scan kernel (up to 512 decodes between two reads).
- * Enabling creates the events (host resources only) and clears earlier records. */
-int topk_attn_set_scan_timing(topk_attn_t* h, int enable);
-
-/* After the caller has synchronised the stream: total milliseconds between the event
- * pairs recorded since the last read and the number of pairs; clears the records. */
-int topk_attn_scan_time(topk_attn_t* h, double* total_ms, int* n_calls);
-
-/* Measurement aid: stream `bytes` (multiple of 16) from `src` (device) with 128-bit
- * loads in the access shape of the key scan (16 KiB tiles per wave, sixteen loads in flight)
- * and write one checksum word per workgroup to `sink` (device, >= 64 KiB).
- * Gives the read-bandwidth ceiling the key scan is compared against. */
-int topk_attn_read_probe(const void* src, size_t bytes, void* sink, void* hip_stream);
 
 const char* topk_attn_strerror(int code);
 

@@ -16,6 +16,29 @@ FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-u
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 
 
+def source_hash() -> str:
+    """Identifies the sources a library was built from: sha256 over csrc/ and include/ (first 16 hex digits)."""
+    import hashlib
+    h = hashlib.sha256()
+    inc = os.path.join(os.path.dirname(HERE), "include")
+    files = [os.path.join(CSRC, f) for f in os.listdir(CSRC)] + [os.path.join(inc, f) for f in os.listdir(inc)]
+    for f in sorted(files):
+        if f.endswith((".hip", ".h")):
+            h.update(os.path.basename(f).encode())
+            h.update(open(f, "rb").read())
+    return h.hexdigest()[:16]
+
+
+def built_hash():
+    """source_hash() of the sources the library on disk was built from, read from the file
+    itself (no dlopen); None if there is no library or it carries no identifier."""
+    import re
+    if not os.path.exists(LIB):
+        return None
+    m = re.search(rb"tka-build-id:([0-9a-f]{16})", open(LIB, "rb").read())
+    return m.group(1).decode() if m else None
+
+
 def _compile(src: str, extra) -> str:
     obj = os.path.join(OBJ_DIR, src.replace(".hip", ".o"))
     subprocess.check_call([HIPCC, *FLAGS, *extra, "-c", os.path.join(CSRC, src), "-o", obj])
@@ -25,8 +48,9 @@ def _compile(src: str, extra) -> str:
 def build(extra_flags=(), verbose: bool = False) -> str:
     """Compile every source and link the shared library; always recompiles."""
     os.makedirs(OBJ_DIR, exist_ok=True)
+    flags = list(extra_flags) + [f'-DTKA_BUILD_ID="{source_hash()}"']
     with ThreadPoolExecutor(max_workers=5) as ex:
-        objs = list(ex.map(lambda s: _compile(s, list(extra_flags)), SOURCES))
+        objs = list(ex.map(lambda s: _compile(s, flags), SOURCES))
     subprocess.check_call([HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB, *objs])
     if verbose:
         print("built", LIB)

@@ -12,6 +12,7 @@
 #include <vector>
 
 #include "../../include/topk_attn.h"
+#include "../../include/topk_attn_debug.h"
 #include "device_utils.h"
 #include "internal.h"
 
@@ -37,6 +38,7 @@ bool config_ok(const topk_attn_config* c, int* why) {
     if (c->index_kind != TOPK_ATTN_INDEX_NONE && c->index_kind != TOPK_ATTN_INDEX_INT8) return false;
     if ((int64_t)c->n_seqs * (c->max_queries > 1 ? c->max_queries : 1) > 65535) return false;   // a grid dimension
     if (c->max_tokens > (int64_t)0x7FFFFF00) return false;   // positions are int32
+    if (c->max_k > (1 << 28)) return false;                  // the candidate list (about 4 max_k entries) is indexed by int32
     if (c->n_seqs > 65535 || c->n_kv_heads > 65535) return false;
     *why = TOPK_ATTN_EUNSUPPORTED;
     if (c->dtype != TOPK_ATTN_F32 && c->dtype != TOPK_ATTN_F16 && c->dtype != TOPK_ATTN_BF16) return false;
@@ -81,7 +83,7 @@ WsLayout ws_layout(const topk_attn_config* c) {
     if (seg_max > kMaxSeg) seg_max = kMaxSeg;
     w.cand_cap = (int)(4 * max_k + 16384 + 48 * seg_max);
     const int64_t max_w = c->max_window < c->max_tokens ? c->max_window : c->max_tokens;
-    w.n_chunk_cap = (int)((c->max_k + kGatherRows - 1) / kGatherRows + (max_w + kGatherRows - 1) / kGatherRows);
+    w.n_chunk_cap = (int)(((int64_t)c->max_k + kGatherRows - 1) / kGatherRows + (max_w + kGatherRows - 1) / kGatherRows);
     size_t o = 0;
     auto take = [&](size_t bytes) { size_t at = o; o = align_up(o + bytes); return at; };
     w.len = take((size_t)c->n_layers * c->n_seqs * sizeof(int32_t));
@@ -722,6 +724,13 @@ int topk_attn_read_probe(const void* src, size_t bytes, void* sink, void* hip_st
                        static_cast<const u32x4*>(src), n_vec, static_cast<uint32_t*>(sink));
     return hipGetLastError() == hipSuccess ? TOPK_ATTN_OK : TOPK_ATTN_EDEVICE;
 }
+
+#ifndef TKA_BUILD_ID
+#define TKA_BUILD_ID "unknown"
+#endif
+// the tag in front lets a script find the identifier in the file without loading it
+static const char kBuildTag[] = "tka-build-id:" TKA_BUILD_ID;
+const char* topk_attn_build_id(void) { return kBuildTag + 13; }
 
 const char* topk_attn_strerror(int code) {
     switch (code) {

@@ -39,10 +39,7 @@ __device__ __forceinline__ void wg_weighted_rows(const Shape& sh, const Bufs& bf
     float lsum = 0.f;
     // U independent rows per lane group at a time (a row's position, its weight,
     // then the row itself are dependent loads: one at a time is latency-bound for small k)
-#ifndef TKA_GATHER_U
-#define TKA_GATHER_U 4
-#endif
-    constexpr int U = TKA_GATHER_U;
+    constexpr int U = 4;
     const int step = 4 * rpw;
     for (int j = j0 + wave * rpw + rs; j < j1; j += U * step) {
         int64_t r[U];

@@ -14,6 +14,7 @@
 // recall measured against the exact path.
 #include "device_utils.h"
 #include "internal.h"
+#include "scan_common.h"
 
 namespace tka {
 
@@ -161,10 +162,6 @@ hipError_t launch_quantize_rows(int dtype, int D, const void* src, int64_t rows_
 // ---------------------------------------------------------------------------------------
 // Scan over the codes (grouped layout: one query, up to four heads per KV head).
 // ---------------------------------------------------------------------------------------
-enum { MODE_SAMPLE = 0, MODE_FILTER = 1, MODE_FULL = 2 };
-constexpr int kScanWaves = 4;
-constexpr int kStage = 128;     // LDS staging slots per (wave, head)
-
 // Codes of a 64-key tile in operand-B layout (lane (j, n) holds the 16-byte chunk 4 s + j of
 // key 16 g + n) and the scale of key `lane`.
 template <int D, class RowFn>
@@ -203,48 +200,6 @@ __device__ __forceinline__ i32x4 tile_mac8(const i32x4 (&b)[4][D / 64], const i3
         res[r] = (j & 2) ? hi : lo;
     }
     return res;
-}
-
-struct CandStage8 {
-    uint64_t* lds;
-    uint64_t* list;     // the head's candidate list
-    int sid;            // this wave's segment
-    int n_lds, n_glob;
-};
-
-// Appends the staged entries up to the last whole run of kCandChunk (all of them when
-// `final`): whole 128-byte lines; the remainder moves to the front of the stage.
-__device__ __forceinline__ void stage_flush8(CandStage8& c, int seg_cap, int n_seg, bool final = false) {
-    static_assert(kCandChunk <= kWave && kStage >= kWave + kCandChunk, "stage too small for an aligned flush");
-    wave_sync();
-    const int total = c.n_glob + c.n_lds;
-    const int f = (final ? total : (total & ~(kCandChunk - 1))) - c.n_glob;
-    for (int i = lane_id(); i < f; i += kWave) {
-        const int slot = c.n_glob + i;
-        if (slot < seg_cap) c.list[cand_slot(slot, c.sid, n_seg)] = c.lds[i];
-    }
-    const int r = f > 0 ? c.n_lds - f : c.n_lds;
-    if (f > 0) {
-        const uint64_t keep = lane_id() < r ? c.lds[f + lane_id()] : 0;
-        wave_sync();
-        if (lane_id() < r) c.lds[lane_id()] = keep;
-        c.n_glob += f;
-    }
-    wave_sync();
-    c.n_lds = r;
-}
-
-__device__ __forceinline__ void filter_head8(float score, float thr, CandStage8& c, bool valid, int64_t item,
-                                             int seg_cap, int n_seg) {
-    const float sc = score + 0.0f;
-    const bool pass = valid && sc >= thr;
-    const uint64_t m = __ballot(pass);
-    if (m) {
-        const int add = __popcll(m);
-        if (c.n_lds + add > kStage) stage_flush8(c, seg_cap, n_seg);
-        if (pass) c.lds[c.n_lds + mask_rank(m)] = ((uint64_t)__float_as_uint(sc) << 32) | (uint64_t)(uint32_t)item;
-        c.n_lds += add;
-    }
 }
 
 template <int D, int MODE>
@@ -305,7 +260,7 @@ scan8_kernel(Shape sh, Bufs bf, int tiles_per_wave, float* dst) {
     uint64_t* const list0 = bf.cand + head0 * (int64_t)sh.cand_cap;
     __shared__ uint64_t stage_lds[MODE == MODE_FILTER ? kScanWaves * 4 * kStage : 1];
     uint64_t* const st0 = stage_lds + (MODE == MODE_FILTER ? wave * 4 * kStage : 0);
-    CandStage8 cs0{st0, list0, sid, 0, 0}, cs1{st0 + kStage, list0 + (int64_t)sh.cand_cap, sid, 0, 0},
+    CandStage cs0{st0, list0, sid, 0, 0}, cs1{st0 + kStage, list0 + (int64_t)sh.cand_cap, sid, 0, 0},
         cs2{st0 + 2 * kStage, list0 + 2 * (int64_t)sh.cand_cap, sid, 0, 0},
         cs3{st0 + 3 * kStage, list0 + 3 * (int64_t)sh.cand_cap, sid, 0, 0};
     float thr0 = 0.f, thr1 = 0.f, thr2 = 0.f, thr3 = 0.f;
@@ -339,10 +294,10 @@ scan8_kernel(Shape sh, Bufs bf, int tiles_per_wave, float* dst) {
                 if (3 < G) out[(head0 + 3) * pitch + item] = s3;
             }
         } else {
-            filter_head8(s0, thr0, cs0, valid, item, seg_cap, sh.n_seg);
-            if (1 < G) filter_head8(s1, thr1, cs1, valid, item, seg_cap, sh.n_seg);
-            if (2 < G) filter_head8(s2, thr2, cs2, valid, item, seg_cap, sh.n_seg);
-            if (3 < G) filter_head8(s3, thr3, cs3, valid, item, seg_cap, sh.n_seg);
+            filter_head(s0, thr0, cs0, valid, item, seg_cap, sh.n_seg);
+            if (1 < G) filter_head(s1, thr1, cs1, valid, item, seg_cap, sh.n_seg);
+            if (2 < G) filter_head(s2, thr2, cs2, valid, item, seg_cap, sh.n_seg);
+            if (3 < G) filter_head(s3, thr3, cs3, valid, item, seg_cap, sh.n_seg);
         }
     };
 
@@ -367,10 +322,10 @@ scan8_kernel(Shape sh, Bufs bf, int tiles_per_wave, float* dst) {
         }
     }
     if (MODE == MODE_FILTER) {
-        stage_flush8(cs0, seg_cap, sh.n_seg, true);
-        if (1 < G) stage_flush8(cs1, seg_cap, sh.n_seg, true);
-        if (2 < G) stage_flush8(cs2, seg_cap, sh.n_seg, true);
-        if (3 < G) stage_flush8(cs3, seg_cap, sh.n_seg, true);
+        stage_flush(cs0, seg_cap, sh.n_seg, true);
+        if (1 < G) stage_flush(cs1, seg_cap, sh.n_seg, true);
+        if (2 < G) stage_flush(cs2, seg_cap, sh.n_seg, true);
+        if (3 < G) stage_flush(cs3, seg_cap, sh.n_seg, true);
         if (lane == 0) {
             uint32_t* sc = bf.seg_cnt + head0 * (int64_t)sh.n_seg + sid;
             sc[0] = (uint32_t)cs0.n_glob;
@@ -381,15 +336,6 @@ scan8_kernel(Shape sh, Bufs bf, int tiles_per_wave, float* dst) {
     }
 }
 
-static int tiles_per_wave8(int64_t n_items, int B, int Hkv) {
-    const int64_t tiles = (n_items + 63) / 64;
-    const int64_t want_wgs = 4096 / ((int64_t)B * Hkv > 0 ? (int64_t)B * Hkv : 1);
-    int64_t tpw = tiles / (kScanWaves * (want_wgs > 0 ? want_wgs : 1));
-    if (tpw < 1) tpw = 1;
-    if (tpw > 64) tpw = 64;
-    return (int)tpw;
-}
-
 template <int MODE>
 static hipError_t launch_scan8(const Shape& s, const Bufs& b, int64_t n_items, float* dst, hipStream_t st) {
     dim3 grid, block(kScanWaves * kWave);
@@ -397,7 +343,7 @@ static hipError_t launch_scan8(const Shape& s, const Bufs& b, int64_t n_items, f
     if (MODE == MODE_FILTER) {
         grid = dim3((unsigned)(s.n_seg / kScanWaves), (unsigned)s.Hkv, (unsigned)s.B);
     } else {
-        tpw = tiles_per_wave8(n_items, s.B, s.Hkv);
+        tpw = tiles_per_wave_for(n_items, s.B, s.Hkv);
         const int64_t tiles = (n_items + 63) / 64, per_wg = (int64_t)tpw * kScanWaves;
         grid = dim3((unsigned)((tiles + per_wg - 1) / per_wg), (unsigned)s.Hkv, (unsigned)s.B);
     }
@@ -426,10 +372,7 @@ hipError_t launch_scan8_full(const Shape& s, const Bufs& b, int64_t Nmax, float*
 // per candidate, kRerankInFlight candidates in flight per lane group (an entry, then the row
 // it points to, are dependent loads).
 // ---------------------------------------------------------------------------------------
-#ifndef TKA_RERANK_U
-#define TKA_RERANK_U 4
-#endif
-constexpr int kRerankInFlight = TKA_RERANK_U;
+constexpr int kRerankInFlight = 4;    // the best of 1, 2, 4, 8, 16 measured
 
 template <int DT>
 __global__ void __launch_bounds__(256) rerank_kernel(Shape sh, Bufs bf) {

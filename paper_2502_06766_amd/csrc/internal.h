@@ -8,10 +8,7 @@ namespace tka {
 enum { DT_F32 = 0, DT_F16 = 1, DT_BF16 = 2 };
 
 constexpr int kWave = 64;
-#ifndef TKA_SEL_THREADS
-#define TKA_SEL_THREADS 1024
-#endif
-constexpr int kSelThreads = TKA_SEL_THREADS;   // workgroup size of the selection kernels
+constexpr int kSelThreads = 1024;   // workgroup size of the selection kernels
 constexpr int kGatherRows = 256;    // value rows handled by one gather workgroup
 constexpr int kSampMax = 16384;     // most sample scores per head in the threshold estimate
 constexpr int kSampMin = 1024;
@@ -93,10 +90,7 @@ __device__ inline int64_t visible_len(const Shape& sh, const Bufs& bf, int b) {
 // consecutive entries of a segment are contiguous (a wave's flush writes whole 128-byte
 // pieces), and the runs of the segments interleave, so that the filled part of the list is
 // dense at its start whatever the fill of the single segments.
-#ifndef TKA_CAND_CHUNK_LOG2
-#define TKA_CAND_CHUNK_LOG2 4
-#endif
-constexpr int kCandChunkLog2 = TKA_CAND_CHUNK_LOG2;
+constexpr int kCandChunkLog2 = 4;
 constexpr int kCandChunk = 1 << kCandChunkLog2;
 // slot of entry e of segment g
 __host__ __device__ inline int64_t cand_slot(int64_t e, int g, int n_seg) {

@@ -20,6 +20,7 @@
 
 #include "device_utils.h"
 #include "internal.h"
+#include "scan_common.h"
 
 namespace tka {
 
@@ -36,16 +37,6 @@ template <> struct Mfma<DT_BF16> {
         return __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, c, 0, 0, 0);
     }
 };
-
-#ifndef TKA_SCAN_PIPELINE
-#define TKA_SCAN_PIPELINE 1   // 1: loads of tile t+1 are issued before the MFMAs of tile t; 0: no prefetch
-#endif
-#ifndef TKA_SCAN_SADDR
-#define TKA_SCAN_SADDR 1      // 1: whole tiles are addressed as wave-uniform base + per-lane 32-bit offset
-#endif
-
-enum { MODE_SAMPLE = 0, MODE_FILTER = 1, MODE_FULL = 2 };
-constexpr int kScanWaves = 4;     // waves per scan workgroup
 
 // Query block of the group in operand-A layout: lane (j, m) holds channels
 // 32 s + 8 j .. +7 of head m % 4 (zero for heads the group does not have).
@@ -143,7 +134,7 @@ __device__ __forceinline__ int64_t walk_tiles(int64_t tile, int64_t end, int64_t
 
 // head_dim 256 makes a 64-key tile 32 KiB: two register buffers of it do not fit, and
 // with 8 waves per compute unit 256 KiB are in flight anyway.
-template <int D> struct ScanPipelined { static constexpr bool value = TKA_SCAN_PIPELINE && D <= 128; };
+template <int D> struct ScanPipelined { static constexpr bool value = D <= 128; };
 
 // Scores of the tile: lane l gets res[r] = q_{head0 + r} . K[row(l)].
 template <int DT, int D>
@@ -167,56 +158,6 @@ __device__ __forceinline__ f32x4 tile_mac(const typename Mfma<DT>::v8 (&b)[4][D 
         res[r] = (j & 2) ? hi : lo;
     }
     return res;
-}
-
-constexpr int kStage = 128;   // LDS staging slots per (wave, head)
-
-// Candidates of one (wave, head): staged in LDS, appended to the wave's private segment
-// of the head's global list in bursts.  Global stores in the tile loop would sit between
-// the key loads in the wave's in-order memory queue and stall the prefetch.
-struct CandStage {
-    uint64_t* lds;      // kStage slots
-    uint64_t* list;     // the head's candidate list (entry e of this wave at list[cand_slot(e, sid, n_seg)])
-    int sid;            // this wave's segment
-    int n_lds;          // staged entries (wave-uniform)
-    int n_glob;         // entries already appended, may run past seg_cap (overflow is detected later)
-};
-
-// Appends the staged entries up to the last whole run of kCandChunk (all of them when
-// `final`), so that every store but the last covers whole 128-byte lines; the remainder
-// (fewer than kCandChunk entries) moves to the front of the stage.
-__device__ __forceinline__ void stage_flush(CandStage& c, int seg_cap, int n_seg, bool final = false) {
-    static_assert(kCandChunk <= kWave && kStage >= kWave + kCandChunk, "stage too small for an aligned flush");
-    wave_sync();
-    const int total = c.n_glob + c.n_lds;
-    const int f = (final ? total : (total & ~(kCandChunk - 1))) - c.n_glob;     // entries to append now
-    for (int i = lane_id(); i < f; i += kWave) {
-        const int slot = c.n_glob + i;
-        if (slot < seg_cap) c.list[cand_slot(slot, c.sid, n_seg)] = c.lds[i];
-    }
-    const int r = f > 0 ? c.n_lds - f : c.n_lds;
-    if (f > 0) {
-        const uint64_t keep = lane_id() < r ? c.lds[f + lane_id()] : 0;
-        wave_sync();
-        if (lane_id() < r) c.lds[lane_id()] = keep;
-        c.n_glob += f;
-    }
-    wave_sync();
-    c.n_lds = r;
-}
-
-// Keep the keys of one head whose score reaches the head's threshold.
-__device__ __forceinline__ void filter_head(float score, float thr, CandStage& c, bool valid, int64_t item,
-                                            int seg_cap, int n_seg) {
-    const float sc = score + 0.0f;
-    const bool pass = valid && sc >= thr;
-    const uint64_t m = __ballot(pass);
-    if (m) {
-        const int add = __popcll(m);
-        if (c.n_lds + add > kStage) stage_flush(c, seg_cap, n_seg);
-        if (pass) c.lds[c.n_lds + mask_rank(m)] = ((uint64_t)__float_as_uint(sc) << 32) | (uint64_t)(uint32_t)item;
-        c.n_lds += add;
-    }
 }
 
 template <int DT, int D, int MODE>
@@ -315,7 +256,7 @@ scan_mfma_kernel(Shape sh, Bufs bf, int tiles_per_wave, float* dst) {
     struct TileB { v8 b[4][D / 32]; } ba, bb;
     auto load_rows = [&](TileB& t, int64_t ti) { tile_load<DT, D>(Kh, [&](int slot) { return row_of(ti * 64, slot); }, t.b); };
     auto use = [&](TileB& t, int64_t ti) { consume(tile_mac<DT, D>(t.b, qa), ti * 64); };
-    if (MODE == MODE_SAMPLE || !TKA_SCAN_SADDR) {
+    if (MODE == MODE_SAMPLE) {
         walk_tiles<ScanPipelined<D>::value>(tile, tile_end, tile_step, ba, bb, load_rows, use);
     } else {
         // whole tiles first, then the one tile (if any) that the end of the cache cuts short
@@ -358,12 +299,9 @@ scan_mfma_kernel(Shape sh, Bufs bf, int tiles_per_wave, float* dst) {
 // per tile as the grouped kernel, four times the rows.  Per-row state lives in the 16
 // lanes that own the row.
 // ---------------------------------------------------------------------------------------
-#ifndef TKA_STAGE_ROW
-#define TKA_STAGE_ROW 128
-#endif
 // LDS staging slots per (wave, row): the 64 entries one step can add on top of the remainder
 // (fewer than kCandChunk entries) an aligned flush leaves behind
-constexpr int kStageRow = TKA_STAGE_ROW;
+constexpr int kStageRow = 128;
 static_assert(kCandChunk <= 16 && kStageRow >= 64 + kCandChunk, "row stage too small for an aligned flush");
 
 // NT row tiles (16 rows each) share every key tile: NT = 2 halves the passes over the keys for
@@ -382,7 +320,6 @@ scan_rows_kernel(Shape sh, Bufs bf, int tiles_per_wave, float* dst) {
     // to the XCDs round-robin by linear id), so they walk the same key tiles at the same time
     // and all but the first read of a tile are served by that XCD's L2.
     int bx = blockIdx.x, kvh = blockIdx.y, bc = (int)blockIdx.z / sh.n_qblk, blk = (int)blockIdx.z % sh.n_qblk;
-#ifndef TKA_NO_XCD_REMAP
     {
         const int gx = gridDim.x, gy = gridDim.y, streams = gx * gy * sh.Bc;
         if (sh.n_qblk > 1 && streams % 8 == 0) {
@@ -394,7 +331,6 @@ scan_rows_kernel(Shape sh, Bufs bf, int tiles_per_wave, float* dst) {
             bc = stream / (gx * gy);
         }
     }
-#endif
     // the M * G (query, head) rows of the KV head, query-major, are cut into blocks of 16 NT rows
     const int row0 = blk * 16 * NT;                                   // first row of the block
     const int R = M * G - row0 < 16 * NT ? M * G - row0 : 16 * NT;    // its rows
@@ -620,7 +556,7 @@ scan_rows_kernel(Shape sh, Bufs bf, int tiles_per_wave, float* dst) {
         mac(t.b, c);
         consume(c, ti * 64);
     };
-    if (MODE == MODE_SAMPLE || !TKA_SCAN_SADDR) {
+    if (MODE == MODE_SAMPLE) {
         walk_tiles<ScanPipelined<D>::value>(tile, tile_end, tile_step, ba, bb, load_rows, use);
     } else {
         const int64_t n_whole = N / 64;
@@ -695,16 +631,6 @@ scan_generic_kernel(Shape sh, Bufs bf, int rows_per_block, float* dst) {
 
 bool scan_mfma_supported(const Shape& s) {
     return (s.dtype == DT_F16 || s.dtype == DT_BF16) && (s.D == 32 || s.D == 64 || s.D == 128 || s.D == 256) && s.G >= 1;
-}
-
-static int tiles_per_wave_for(int64_t n_items, int B, int Hkv) {
-    // aim at ~16 workgroups per CU over the whole grid, at least 1 tile and at most 32 per wave
-    const int64_t tiles = (n_items + 63) / 64;
-    const int64_t want_wgs = 4096 / ((int64_t)B * Hkv > 0 ? (int64_t)B * Hkv : 1);
-    int64_t tpw = tiles / (kScanWaves * (want_wgs > 0 ? want_wgs : 1));
-    if (tpw < 1) tpw = 1;
-    if (tpw > 64) tpw = 64;
-    return (int)tpw;
 }
 
 template <int MODE>

@@ -16,10 +16,7 @@
 namespace tka {
 
 constexpr int kSelWaves = kSelThreads / kWave;
-#ifndef TKA_DIGIT_BITS
-#define TKA_DIGIT_BITS 9
-#endif
-constexpr int kDigitBits = TKA_DIGIT_BITS;     // radix digit width
+constexpr int kDigitBits = 9;                  // radix digit width (the best of 8..11 measured)
 constexpr int kBins = 1 << kDigitBits;
 constexpr int kBinsPerLane = kBins / kWave;
 constexpr int kCandSlots = 32768;              // candidate slots kept on chip per head

@@ -12,8 +12,7 @@ import os
 from typing import Optional
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-# TOPK_ATTN_LIB selects another build of the same library (A/B measurements)
-LIB_PATH = os.environ.get("TOPK_ATTN_LIB") or os.path.join(_HERE, "libtopk_attn.so")
+LIB_PATH = os.path.join(_HERE, "libtopk_attn.so")
 
 OK, EINVAL, ECAPACITY, EUNSUPPORTED, EDEVICE, ENOMEM, ESCRATCH = range(7)
 F32, F16, BF16 = 0, 1, 2
@@ -23,7 +22,7 @@ INDEX_NONE, INDEX_INT8 = 0, 1
 EXPORTS = [
     "topk_attn_kv_bytes", "topk_attn_workspace_bytes", "topk_attn_create", "topk_attn_append_kv", "topk_attn_append_step",
     "topk_attn_decode", "topk_attn_decode_static", "topk_attn_decode_window", "topk_attn_decode_multi", "topk_attn_decode_layers", "topk_attn_k_schedule", "topk_attn_scores", "topk_attn_length", "topk_attn_reset", "topk_attn_set_path",
-    "topk_attn_last_fallbacks", "topk_attn_set_scan_timing", "topk_attn_scan_time", "topk_attn_read_probe", "topk_attn_strerror", "topk_attn_destroy",
+    "topk_attn_last_fallbacks", "topk_attn_set_scan_timing", "topk_attn_scan_time", "topk_attn_read_probe", "topk_attn_build_id", "topk_attn_strerror", "topk_attn_destroy",
 ]
 
 
@@ -105,6 +104,8 @@ def lib() -> ctypes.CDLL:
         L.topk_attn_scan_time.restype = i32
         L.topk_attn_read_probe.argtypes = [vp, sz, vp, vp]
         L.topk_attn_read_probe.restype = i32
+        L.topk_attn_build_id.argtypes = []
+        L.topk_attn_build_id.restype = ctypes.c_char_p
         L.topk_attn_strerror.argtypes = [i32]
         L.topk_attn_strerror.restype = ctypes.c_char_p
         L.topk_attn_destroy.argtypes = [vp]
@@ -134,6 +135,10 @@ def make_config(n_layers, n_seqs, n_q_heads, n_kv_heads, head_dim, max_tokens, m
 
 def topk_attn_strerror(code: int) -> str:
     return lib().topk_attn_strerror(code).decode()
+
+
+def topk_attn_build_id() -> str:
+    return lib().topk_attn_build_id().decode()
 
 
 def topk_attn_kv_bytes(cfg: Config) -> int:

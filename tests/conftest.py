@@ -13,10 +13,10 @@ def pytest_configure(config):
 
 
 def pytest_sessionstart(session):
-    """The tests load the library that is built; only when none is there do they build it."""
-    from paper_2502_06766_amd import topk_attn
-    if not os.path.exists(topk_attn.LIB_PATH):
-        from paper_2502_06766_amd import build
+    """The tests load the library that is built; they build it only when none is there or when the one
+    that is there was built from other sources than those beside it (the library carries a hash of its sources)."""
+    from paper_2502_06766_amd import build
+    if build.built_hash() != build.source_hash():
         build.build()
 
 

@@ -15,7 +15,7 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 
 def header_functions():
-    text = open(os.path.join(ROOT, "include", "topk_attn.h")).read()
+    text = "".join(open(os.path.join(ROOT, "include", f)).read() for f in ("topk_attn.h", "topk_attn_debug.h"))
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
     return sorted(set(re.findall(r"\b(topk_attn_[a-z_]+)\s*\(", text)))
 
