@@ -36,13 +36,20 @@ def test_wide_head_groups(dtype, Hq, Hkv, N, d, k, path):
 
 
 # ------------------------------------------------------------------ several queries per sequence
-def make_multi(M, Hq, Hkv, N, d, dtype, k, causal, window, seed):
+def make_multi(M, Hq, Hkv, N, d, dtype, k, causal, window, seed, allow_unmargined=False):
+    """delta is None when `allow_unmargined` and the margin could not be enforced (the keys are then
+    whatever the last round left, as good an input as any; check_multi judges it without a margin)."""
     g = np.random.default_rng(seed)
     q0 = wl.quantize(g.standard_normal((Hq, d)).astype(np.float32), dtype)
     q = wl.make_query_chunk(q0, dtype, M, seed)
     K = wl.quantize(g.standard_normal((Hkv, N, d)).astype(np.float32), dtype)
     V = wl.quantize(g.standard_normal((Hkv, N, d)).astype(np.float32), dtype)
-    K, delta = H.enforce_margin_multi(q, K, dtype, k, causal, window)
+    try:
+        K, delta = H.enforce_margin_multi(q, K, dtype, k, causal, window)
+    except H.MarginNotReached:
+        if not allow_unmargined:
+            raise
+        delta = None
     return q, K, V, delta
 
 
@@ -50,6 +57,12 @@ def check_multi(res, q, K, V, dtype, k, causal, window, delta, label):
     """res = (out, idx, vals, lse) numpy arrays [M, Hq, ...] of one sequence."""
     M, Hq, d = q.shape
     N = K.shape[1]
+    if delta is None:           # no margin on these inputs: every query is judged on its own visible part
+        for m in range(M):
+            n_vis = N - (M - 1 - m) if causal else N
+            H.check_unmargined(tuple(r[m] for r in res), q[m], np.ascontiguousarray(K[:, :n_vis]),
+                               np.ascontiguousarray(V[:, :n_vis]), dtype, k, window, f"{label} query {m} (no margin)")
+        return
     ref = c_oracle.topk_attention_multi(q, K, V, dtype, k, causal, window)
     vmax = float(np.abs(wl.widen(V, dtype)).max())
     for m in range(M):

@@ -93,6 +93,13 @@ def test_general_path_sweep(dtype, Hq, Hkv, N, d, k):
     run_case(q, K, V, dtype, k, path=ta.PATH_FULL, chunks=3, label=f"full N={N} k={k}")
 
 
+def test_fp32_cache_200k_tokens():
+    """A long fp32 cache by name (the sweeps reach such sizes only by chance): 200003 tokens,
+    4 heads on 2 KV heads, d = 64, k = 1000; index sets exact, out within 1e-5."""
+    q, K, V = rand_case(4, 2, 200003, 64, wl.F32, 1000, seed=2026)
+    run_case(q, K, V, wl.F32, 1000, chunks=2, label="fp32 N=200003")
+
+
 def test_k_larger_than_n_pads():
     q, K, V = rand_case(4, 2, 50, 64, wl.F16, 50, seed=5)
     run_case(q, K, V, wl.F16, 80, path=ta.PATH_FULL, label="k>N")
@@ -274,9 +281,11 @@ def test_c3_llama_layer_1m_fp16():
 
 def test_c4_batched_16_sequences_k_sweep():
     """Config 4 at full size: 16 sequences x 262144 tokens, bf16, k in {256, 1024, 4096}, one
-    batched decode per k.  The oracle checks sampled sequences; the others are checked
-    against properties that need no oracle (selected scores are the largest of the score
-    dump, vals belong to idx)."""
+    batched decode per k.  Every sequence is judged against the oracle for every k: sequences
+    0, 7 and 15 get an enforced margin at all three boundaries (index sets exact), the other
+    13 are taken as the generator made them and judged by helpers.check_unmargined (sets may
+    differ from the oracle's only inside the rounding band; vals, out and lse against the oracle's
+    arithmetic over the selected positions)."""
     w = wl.C4
     B, Hq, Hkv, d, N = w.n_seqs, w.n_q_heads, w.n_kv_heads, w.head_dim, w.n_tokens
     ks = list(wl.C4_K_SWEEP)
@@ -293,24 +302,31 @@ def test_c4_batched_16_sequences_k_sweep():
             qs.append(H.to_torch(q, w.dtype, DEV))
             print(f"c4: sequence {b} resident", flush=True)
         qd = torch.stack(qs).contiguous()
-        S = cache.scores(0, qd)                       # [B, Hq, N] fp32 dump (same arithmetic as the scan)
+        res = {}
         for k in ks:
             out, idx, vals, lse = cache.decode(0, qd, k)
             torch.cuda.synchronize()
             assert cache.last_fallbacks() == 0
-            for b in sampled:
+            res[k] = tuple(t.cpu().numpy() for t in (out, idx, vals, lse))
+        exact_heads = total_heads = 0
+        for b in range(B):
+            if b in sampled:
                 q, K, V = host[b]
-                ref = c_oracle.topk_attention(q, K, V, w.dtype, k)
-                H.check_against_oracle(out[b].cpu().numpy(), idx[b].cpu().numpy(), vals[b].cpu().numpy(),
-                                       lse[b].cpu().numpy(), ref, H.score_margin(q, K, w.dtype), k, 2e-3,
-                                       float(np.abs(wl.widen(V, w.dtype)).max()), f"c4 k={k} seq {b}")
-            # every sequence: vals are the dumped scores at idx, and nothing unselected is larger
-            got = torch.gather(S, 2, idx.long())
-            assert torch.equal(got, vals)
-            kth = torch.topk(S, k, dim=2).values[:, :, -1]
-            assert torch.equal(vals.min(dim=2).values, kth)
-            assert (torch.sort(idx, dim=2).values[:, :, 1:] != torch.sort(idx, dim=2).values[:, :, :-1]).all()
-            print(f"c4: k={k} ok", flush=True)
+                delta = H.score_margin(q, K, w.dtype)
+                vmax = float(np.abs(wl.widen(V, w.dtype)).max())
+                for k in ks:
+                    ref = c_oracle.topk_attention(q, K, V, w.dtype, k)
+                    H.check_against_oracle(*(r[b] for r in res[k]), ref, delta, k, 2e-3, vmax, f"c4 k={k} seq {b}")
+            else:
+                q, K, V = wl.make_quantized(w, seed=3, seq=b, threads=16)      # the same arrays the cache holds
+                S = c_oracle.scores(q, K, w.dtype)
+                for k in ks:
+                    frac = H.check_unmargined(tuple(r[b] for r in res[k]), q, K, V, w.dtype, k, 0,
+                                              f"c4 k={k} seq {b} (no margin)", S=S)
+                    exact_heads += round(frac * Hq)
+                    total_heads += Hq
+            print(f"c4: sequence {b} judged against the oracle", flush=True)
+        print(f"c4: {exact_heads} of {total_heads} heads without a margin select exactly the oracle's set", flush=True)
     finally:
         cache.close()
 

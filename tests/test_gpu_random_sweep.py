@@ -48,49 +48,57 @@ def draw_case(rng):
 
 def run_drawn(c, label):
     dtype, d, Hq, Hkv, N, k, M, window, path = (c[x] for x in ("dtype", "d", "Hq", "Hkv", "N", "k", "M", "window", "path"))
+    """Returns True if the case was judged with an enforced margin (exact sets), False if the margin could
+    not be enforced and the case was judged by helpers.check_unmargined."""
     if M > 1:
-        q, K, V, delta = TM.make_multi(M, Hq, Hkv, N, d, dtype, k, c["causal"], window, seed=c["data_seed"])
+        q, K, V, delta = TM.make_multi(M, Hq, Hkv, N, d, dtype, k, c["causal"], window, seed=c["data_seed"],
+                                       allow_unmargined=True)
         TM.run_multi_case(q, K, V, delta, dtype, k, c["causal"], window, path, label=label)
-        return
+        return delta is not None
     g = np.random.default_rng(c["data_seed"])
     q = wl.quantize(g.standard_normal((Hq, d)).astype(np.float32), dtype)
     K = wl.quantize(g.standard_normal((Hkv, N, d)).astype(np.float32), dtype)
     V = wl.quantize(g.standard_normal((Hkv, N, d)).astype(np.float32), dtype)
     P = max(0, N - window)
+    margin_ok = True
     if 0 < k < P:
         Kp = np.ascontiguousarray(K[:, :P])
-        Kp, _, _ = H.enforce_margin(q, Kp, dtype, k)
+        try:
+            Kp, _, _ = H.enforce_margin(q, Kp, dtype, k)
+        except H.MarginNotReached:       # Kp is what the last round left: as good an input as any
+            margin_ok = False
         K[:, :P] = Kp
     if path == ta.PATH_INDEX:
-        TI.run_index_case(q, K, V, dtype, k, window, label=label, expect_fallbacks=None)
-        return
-    ref = c_oracle.topk_attention_window(q, K, V, dtype, k, window)
+        TI.run_index_case(q, K, V, dtype, k, window, label=label, expect_fallbacks=None, margin_ok=margin_ok)
+        return margin_ok
     cache = ta.TopkAttnCache(1, 1, Hq, Hkv, d, N + c["slack"], k, dtype, max_window=window)
     try:
         cache.set_path(path)
         cache.append(0, 0, H.to_torch(K, dtype, DEV), H.to_torch(V, dtype, DEV), head_major=True)
-        out, idx, vals, lse = cache.decode(0, H.to_torch(q, dtype, DEV)[None].contiguous(), k, window=window)
+        res = cache.decode(0, H.to_torch(q, dtype, DEV)[None].contiguous(), k, window=window)
         torch.cuda.synchronize()
-        H.check_against_oracle(out[0].cpu().numpy(), idx[0].cpu().numpy(), vals[0].cpu().numpy(), lse[0].cpu().numpy(),
-                               ref, H.score_margin(q, K, dtype), min(k, P), H.out_tolerance(dtype),
-                               float(np.abs(wl.widen(V, dtype)).max()), label)
+        res = tuple(t[0].cpu().numpy() for t in res)
+        if margin_ok:
+            ref = c_oracle.topk_attention_window(q, K, V, dtype, k, window)
+            H.check_against_oracle(*res, ref, H.score_margin(q, K, dtype), min(k, P), H.out_tolerance(dtype),
+                                   float(np.abs(wl.widen(V, dtype)).max()), label)
+        else:
+            H.check_unmargined(res, q, K, V, dtype, k, window, label + " (no margin)")
     finally:
         cache.close()
+    return margin_ok
 
 
 @pytest.mark.parametrize("seed", [11, 12, 13])
 def test_random_shapes_and_entry_points(seed):
     rng = np.random.default_rng(seed)
-    done = 0
+    done = margined = 0
     for i in range(40):
         c = draw_case(rng)
-        try:
-            run_drawn(c, f"sweep seed {seed} case {i} {c}")
-            done += 1
-        except AssertionError as e:
-            if "margin enforcement did not converge" not in str(e):   # dense k with many rows per KV head
-                raise
-    assert done >= 30
+        margined += run_drawn(c, f"sweep seed {seed} case {i} {c}")     # every draw reaches the GPU and the oracle
+        done += 1
+    print(f"sweep seed {seed}: {done} cases judged, {margined} of them with an enforced margin", flush=True)
+    assert done == 40 and margined >= 30
 
 
 @pytest.mark.parametrize("seed", [21, 22])
@@ -120,12 +128,8 @@ def test_random_ragged_batches(seed):
         sd = int(rng.integers(1 << 30))
         label = f"ragged sweep seed {seed} case {case}: dtype={dtype} d={d} Hq={Hq} Hkv={Hkv} lens={lens} k={k} M={M} " \
                 f"causal={causal} window={window} path={path}"
-        try:
-            data = [TM.make_multi(M, Hq, Hkv, n, d, dtype, k, causal, window, seed=sd + b) for b, n in enumerate(lens)]
-        except AssertionError as e:
-            if "margin enforcement did not converge" not in str(e):
-                raise
-            continue
+        data = [TM.make_multi(M, Hq, Hkv, n, d, dtype, k, causal, window, seed=sd + b, allow_unmargined=True)
+                for b, n in enumerate(lens)]
         cache = ta.TopkAttnCache(2, B, Hq, Hkv, d, max(lens) + 7, k, dtype, max_window=window, max_queries=M,
                                  index_kind=ta.INDEX_INT8 if use_index else ta.INDEX_NONE)
         try:
@@ -146,7 +150,9 @@ def test_random_ragged_batches(seed):
                 if M > 1:
                     TM.check_multi(r, q, K, V, dtype, k, causal, window, delta, f"{label} seq {b}")
                 elif use_index:
-                    TI.check_index_result(r, q[0], K, V, dtype, k, window, f"{label} seq {b}")
+                    TI.check_index_result(r, q[0], K, V, dtype, k, window, f"{label} seq {b}", margin_ok=delta is not None)
+                elif delta is None:
+                    H.check_unmargined(r, q[0], K, V, dtype, k, window, f"{label} seq {b} (no margin)")
                 else:
                     ref = c_oracle.topk_attention_window(q[0], K, V, dtype, k, window)
                     H.check_against_oracle(*r, ref, delta[0], min(k, max(0, lens[b] - window)), H.out_tolerance(dtype),
@@ -154,4 +160,4 @@ def test_random_ragged_batches(seed):
             done += 1
         finally:
             cache.close()
-    assert done >= 18
+    assert done == 25          # every drawn batch reaches the GPU and the oracle
