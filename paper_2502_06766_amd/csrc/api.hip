@@ -25,8 +25,8 @@ inline size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
 inline int elem_bytes(int dtype) { return dtype == TOPK_ATTN_F32 ? 4 : 2; }
 
 struct WsLayout {
-    size_t len, thr, samp, seg_cnt, seg_max, flags, hmax, fallback, qscale, q8, cand, scores, sel_idx, sel_val, part_acc, part_l, part_m, total;
-    int cand_cap, n_chunk_cap;
+    size_t len, thr, bins, samp, seg_cnt, seg_max, flags, hmax, fallback, tailrec, qscale, q8, hist, cand, bnd, scores, sel_idx, sel_val, part_acc, part_l, part_m, total;
+    int cand_cap, n_chunk_cap, hist_cap;
 };
 
 bool config_ok(const topk_attn_config* c, int* why) {
@@ -83,20 +83,27 @@ WsLayout ws_layout(const topk_attn_config* c) {
     if (seg_max > kMaxSeg) seg_max = kMaxSeg;
     w.cand_cap = (int)(4 * max_k + 16384 + 48 * seg_max);
     const int64_t max_w = c->max_window < c->max_tokens ? c->max_window : c->max_tokens;
-    w.n_chunk_cap = (int)(((int64_t)c->max_k + kGatherRows - 1) / kGatherRows + (max_w + kGatherRows - 1) / kGatherRows);
+    // partial sums per head: the tail of the filtered path makes up to one per 128 selected rows (and never
+    // more than scan workgroups fed the head), the gather one per 256; the window adds one per 256 tokens
+    w.n_chunk_cap = (int)(((int64_t)c->max_k + 127) / 128 + (max_w + kGatherRows - 1) / kGatherRows);
+    w.hist_cap = (int)(seg_max / 4);            // scan workgroups per head (four wave segments each)
     size_t o = 0;
     auto take = [&](size_t bytes) { size_t at = o; o = align_up(o + bytes); return at; };
     w.len = take((size_t)c->n_layers * c->n_seqs * sizeof(int32_t));
     w.thr = take(BH * sizeof(float));
+    w.bins = take(BH * 2 * sizeof(float));
     w.samp = take(BH * kSampMax * sizeof(float));
     w.seg_cnt = take(BH * kMaxSeg * sizeof(uint32_t));
     w.seg_max = take(BH * kMaxSeg * sizeof(float));
     w.flags = take(BH * sizeof(uint32_t));
     w.hmax = take(BH * sizeof(float));
     w.fallback = take(sizeof(uint32_t));
+    w.tailrec = take(BH * 4 * sizeof(uint32_t));
     w.qscale = take(BH * sizeof(float));
     w.q8 = take(BH * (size_t)c->head_dim);
+    w.hist = take(BH * (size_t)w.hist_cap * kTailBins * sizeof(uint32_t));
     w.cand = take(BH * (size_t)w.cand_cap * sizeof(uint64_t));
+    w.bnd = take(BH * (size_t)w.cand_cap * sizeof(uint64_t));
     w.scores = take(BH * (size_t)c->max_tokens * sizeof(float));
     w.sel_idx = take(BH * (size_t)c->max_k * sizeof(int32_t));   // stride is the requested k, up to max_k
     w.sel_val = take(BH * (size_t)c->max_k * sizeof(float));
@@ -265,7 +272,7 @@ int topk_attn_create(const topk_attn_config* cfg, topk_attn_t** out) {
         h->scratch_dev = static_cast<char*>(p);
     }
     // lengths and the small per-head control words start at zero
-    if (hipMemset(cfg->workspace, 0, w.cand) != hipSuccess || hipDeviceSynchronize() != hipSuccess) {
+    if (hipMemset(cfg->workspace, 0, w.hist) != hipSuccess || hipDeviceSynchronize() != hipSuccess) {
         delete h;
         return TOPK_ATTN_EDEVICE;
     }
@@ -392,6 +399,7 @@ static void fill_call(topk_attn_t* h, int layer, const void* q, int k, int n_que
     s->row_tiles = n_queries * s->G > 16 ? 2 : 1;
     s->n_qblk = (n_queries * s->G + 16 * s->row_tiles - 1) / (16 * s->row_tiles);
     s->D = c.head_dim; s->dtype = c.dtype; s->k = k; s->window = 0; s->max_k = c.max_k;
+    s->hist_cap = h->ws.hist_cap; s->tail_spw = 1; s->tail_wgs = 1;
     s->cand_cap = h->ws.cand_cap; s->n_seg = 4; s->seg_cap = (h->ws.cand_cap / 4) & ~(kCandChunk - 1); s->samp_cap = kSampMax; s->n_chunk_cap = h->ws.n_chunk_cap;
     s->Ncap = c.max_tokens;
     s->indexed = 0;
@@ -414,6 +422,10 @@ static void fill_call(topk_attn_t* h, int layer, const void* q, int k, int n_que
     b->qscale = reinterpret_cast<float*>(ws + h->ws.qscale);
     b->len = reinterpret_cast<int32_t*>(ws_len + h->ws.len) + (size_t)layer * c.n_seqs;
     b->thr = reinterpret_cast<float*>(ws + h->ws.thr);
+    b->bins = reinterpret_cast<float*>(ws + h->ws.bins);
+    b->hist = reinterpret_cast<uint32_t*>(ws + h->ws.hist);
+    b->bnd = reinterpret_cast<uint64_t*>(ws + h->ws.bnd);
+    b->tailrec = reinterpret_cast<uint32_t*>(ws + h->ws.tailrec);
     b->samp = reinterpret_cast<float*>(ws + h->ws.samp);
     b->seg_cnt = reinterpret_cast<uint32_t*>(ws + h->ws.seg_cnt);
     b->seg_max = reinterpret_cast<float*>(ws + h->ws.seg_max);
@@ -441,12 +453,13 @@ static bool choose_segments(const topk_attn_t* h, const Shape& s, int64_t nmax, 
     const int64_t tiles = (nmax + 63) / 64;
     if (P * 4 > tiles) P = tiles / 4;
     if (P * 4 > kMaxSeg) P = kMaxSeg / 4;
+    if (P > s.hist_cap) P = s.hist_cap;     // every scan workgroup leaves its per-bin candidate counts
     if (P < 1) P = 1;
     while (P & (P - 1)) P &= P - 1;          // power of two: the selection indexes segments by mask
     {   // rounding down may leave the chip a quarter empty: take the next power of two if it stays within 1.5 x
         const int64_t streams = (int64_t)scan_grid_z(s) * s.Hkv;
         if (streams * P * 8 < target_wgs * 7 && streams * P * 2 * 2 <= target_wgs * 3 && P * 2 * 4 <= tiles &&
-            P * 2 * 4 <= kMaxSeg)
+            P * 2 * 4 <= kMaxSeg && P * 2 <= s.hist_cap)
             P *= 2;
     }
     for (; P >= 1; P /= 2) {
@@ -525,9 +538,17 @@ static int decode_impl(topk_attn_t* h, int layer, const void* q, int n_queries, 
         }
         if (fast) fast = choose_segments(h, s, nmax, c_hi, &s.n_seg, &s.seg_cap);
         s.cand_est = (int)(c_hi < INT32_MAX ? c_hi : INT32_MAX);
+        if (fast) {     // tail: about 128 selected rows per workgroup, whole scan workgroups each
+            const int n_wg = s.n_seg / 4;
+            int want = (k + 127) / 128;
+            want = want < 1 ? 1 : (want > n_wg ? n_wg : want);
+            s.tail_spw = (n_wg + want - 1) / want;
+            s.tail_wgs = (n_wg + s.tail_spw - 1) / s.tail_spw;
+        }
     }
     if (!fast) s.indexed = 0;      // no filtered scan: exact path
     hipError_t e = hipSuccess;
+    bool tail_done = false;
     if (use_static) {
         // the array keeps what the last call on this GPU left: the per-head control words start at zero
         // (a fill kernel, so that the call may be recorded into a HIP graph)
@@ -556,7 +577,12 @@ static int decode_impl(topk_attn_t* h, int layer, const void* q, int n_queries, 
         if (e == hipSuccess) e = launch_scan_filter(s, b, nmax, st);
         if (e == hipSuccess && timed) e = hipEventRecord(h->ev[2 * h->ev_used + 1], st);
         if (e == hipSuccess && timed) h->ev_used++;
-        if (e == hipSuccess) e = launch_select_candidates(s, b, st);   // redoes unusable heads itself
+        if (tail_supported(s)) {
+            if (e == hipSuccess) e = launch_tail(s, b, st);            // selection and gather; redoes unusable heads itself
+            tail_done = true;
+        } else if (e == hipSuccess) {
+            e = launch_select_candidates(s, b, st);                    // redoes unusable heads itself
+        }
     } else {
         if (nmax > 0) {
             if (timed) e = hipEventRecord(h->ev[2 * h->ev_used], st);
@@ -566,7 +592,7 @@ static int decode_impl(topk_attn_t* h, int layer, const void* q, int n_queries, 
         }
         if (e == hipSuccess) e = launch_select_full(s, b, nmax, st);   // with nothing to search it only pads
     }
-    if (e == hipSuccess) e = launch_gather(s, b, st);
+    if (e == hipSuccess && !tail_done) e = launch_gather(s, b, st);
     h->last_fast = fast;
     h->last_static = use_static;
     return e == hipSuccess ? TOPK_ATTN_OK : TOPK_ATTN_EDEVICE;

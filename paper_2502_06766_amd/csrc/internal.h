@@ -10,7 +10,10 @@ enum { DT_F32 = 0, DT_F16 = 1, DT_BF16 = 2 };
 constexpr int kWave = 64;
 constexpr int kSelThreads = 1024;   // workgroup size of the selection kernels
 constexpr int kGatherRows = 256;    // value rows handled by one gather workgroup
-constexpr int kSampMax = 16384;     // most sample scores per head in the threshold estimate
+// Most sample scores per head in the threshold estimate.  The sample rows are random 256-byte reads
+// (4.8 TB/s at best): 16384 per KV head cost 13 us at one million tokens, 8192 cost 9, for a sixth more
+// candidates (the rank rule keeps the threshold six standard deviations below the expected k-th score).
+constexpr int kSampMax = 8192;
 constexpr int kSampMin = 1024;
 // Shortest cache the filtered scan is used for unless forced: below, writing all scores and
 // selecting over them is faster (measured crossovers: one sequence 16k tokens 46 against 56 us,
@@ -40,6 +43,9 @@ struct Shape {
     int seg_cap;      // entries per segment (n_seg * seg_cap <= cand_cap), a multiple of kCandChunk
     int samp_cap;     // entries per (b, head) sample-score row
     int n_chunk_cap;  // partial-sum slots per (b, head)
+    int hist_cap;     // scan workgroups per head the per-bin candidate counts have room for
+    int tail_spw;     // tail: scan workgroups whose candidates one tail workgroup takes
+    int tail_wgs;     // tail: workgroups per head = ceil((n_seg / 4) / tail_spw)
     int64_t Ncap;     // row capacity per (layer, seq, kv head)
 };
 
@@ -54,6 +60,7 @@ struct Bufs {
     float* qscale;          // [B*Hq]
     const int32_t* len;     // [Bc] tokens cached per cache sequence (this layer)
     float* thr;             // [B*Hq] candidate threshold
+    float* bins;            // [B*Hq][2] lower end and bins per unit of score of tail_bin()
     float* samp;            // [B*Hq][samp_cap]
     uint32_t* seg_cnt;      // [B*Hq][n_seg] candidates each scanning wave found (may exceed seg_cap)
     float* seg_max;         // [B*Hq][n_seg] largest score each scanning wave saw (-inf if it saw none)
@@ -61,6 +68,9 @@ struct Bufs {
     float* hmax;            // [B*Hq] largest selected score
     uint64_t* cand;         // [B*Hq][cand_cap] (score bits << 32 | position); entry e of segment g
                             // at [cand_slot(e, g, n_seg)]
+    uint32_t* hist;         // [B*Hq][hist_cap][kTailBins] candidates per score bin found by each scan workgroup
+    uint64_t* bnd;          // [B*Hq][cand_cap] candidates of the bin the k-th score falls in
+    uint32_t* tailrec;      // [B*Hq][4] what the tail's second kernel needs to know of a head (TailRec)
     float* scores;          // [B*Hq][Ncap] full score buffer
     int32_t* sel_idx;       // [B*Hq][k]
     float* sel_val;         // [B*Hq][k]
@@ -104,6 +114,19 @@ __host__ __device__ inline int64_t cand_slot_entry(int64_t i, int log2_n_seg) {
     return (((i >> kCandChunkLog2) >> log2_n_seg) << kCandChunkLog2) | (i & (kCandChunk - 1));
 }
 
+// Coarse order of the candidates of a head by score, for the tail of the filtered path:
+// bin 0 takes everything below `lo`, bins 1 .. kTailBins - 2 are 1 / inv_d wide from `lo`
+// up, the last one is open-ended.  The threshold kernel lays the fine bins over the band of
+// scores in which the sample puts the k-th largest score, so that the bin it falls in holds
+// few candidates.  Monotone in the score; the scan (which counts candidates per bin) and the
+// tail (which sorts them by bin) evaluate exactly this sequence of roundings.
+constexpr int kTailBins = 64;
+__device__ __forceinline__ int tail_bin(float score, float lo, float inv_d) {
+    const float t = __fmul_rn(__fsub_rn(score, lo), inv_d);
+    const int b = 1 + (int)fminf(t, (float)(kTailBins - 2));     // NaN (inf * 0) counts as the last bin
+    return score < lo ? 0 : b;
+}
+
 // Tokens of a sequence the search runs over: everything but the always-attended window.
 __host__ __device__ inline int64_t prefix_len(int64_t n_tokens, int window) {
     return n_tokens - (window < n_tokens ? (int64_t)window : n_tokens);
@@ -114,6 +137,9 @@ struct Plan {
     int n_samp;      // sample keys per KV head (multiple of 64)
     int stride;      // one sample per `stride` consecutive positions
     int rank;        // threshold = rank-th largest sample score
+    int rank_k;      // sample scores expected at or above the true k-th score (rounded up)
+    int rank_lo;     // the k-th score lies between the sample scores of these two ranks
+    int rank_hi;     // (rank_hi <= rank_k <= rank_lo <= rank) unless a four-sigma sampling event happens
     int64_t c_hi;    // candidates expected at most (z-sigma above the mean)
 };
 
@@ -139,6 +165,11 @@ __host__ __device__ inline Plan make_plan(int64_t N, int k_eff, int indexed = 0)
     double sr = 0.5 * (z + sqrt(z * z + 4.0 * r0));
     double r = sr * sr;
     p.rank = (int)r + 2;
+    p.rank_k = (int)r0 + 1;
+    p.rank_lo = (int)(r0 + 4.0 * sqrt(r0)) + 2;
+    if (p.rank_lo > p.rank) p.rank_lo = p.rank;
+    p.rank_hi = (int)(r0 - 4.0 * sqrt(r0));
+    if (p.rank_hi < 1) p.rank_hi = 1;
     p.c_hi = (int64_t)((double)N * (r + z * sr + 2.0) / (double)ns) + 64;
     return p;
 }
@@ -170,6 +201,10 @@ hipError_t launch_select_candidates(const Shape& s, const Bufs& b, hipStream_t s
 hipError_t launch_select_full(const Shape& s, const Bufs& b, int64_t Nmax, hipStream_t st);
 
 hipError_t launch_gather(const Shape& s, const Bufs& b, hipStream_t st);
+
+// fused selection + gather after a filtered scan that counted its candidates per score bin
+bool tail_supported(const Shape& s);
+hipError_t launch_tail(const Shape& s, const Bufs& b, hipStream_t st);
 
 // int8 key index
 bool index8_supported(int dtype, int D, int G);

@@ -21,144 +21,9 @@
 #include "device_utils.h"
 #include "internal.h"
 #include "scan_common.h"
+#include "scan_tiles.h"
 
 namespace tka {
-
-template <int DT> struct Mfma;
-template <> struct Mfma<DT_F16> {
-    using v8 = f16x8;
-    static __device__ __forceinline__ f32x4 mac(v8 a, v8 b, f32x4 c) {
-        return __builtin_amdgcn_mfma_f32_16x16x32_f16(a, b, c, 0, 0, 0);
-    }
-};
-template <> struct Mfma<DT_BF16> {
-    using v8 = bf16x8;
-    static __device__ __forceinline__ f32x4 mac(v8 a, v8 b, f32x4 c) {
-        return __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, c, 0, 0, 0);
-    }
-};
-
-// Query block of the group in operand-A layout: lane (j, m) holds channels
-// 32 s + 8 j .. +7 of head m % 4 (zero for heads the group does not have).
-template <int DT, int D>
-__device__ __forceinline__ void load_query_a(const void* q, int64_t head0, int G,
-                                             typename Mfma<DT>::v8 (&qa)[D / 32]) {
-    using v8 = typename Mfma<DT>::v8;
-    const int lane = lane_id();
-    const int j = lane >> 4, r = lane & 3;
-    const v8* p = reinterpret_cast<const v8*>(static_cast<const char*>(q) + (head0 + (r < G ? r : 0)) * D * 2) + j;
-#pragma unroll
-    for (int s = 0; s < D / 32; ++s) {
-        v8 v = p[4 * s];
-        if (r >= G) v = v8{};
-        qa[s] = v;
-    }
-}
-
-// Operand B of a 64-key tile: for each 16-key sub-tile g, lane (j, n) loads the 16-byte
-// chunks 4 s + j (s = 0 .. D/32-1) of the row rowfn(16 g + n).  All loads are issued
-// before anything consumes them.
-template <int DT, int D, class RowFn>
-__device__ __forceinline__ void tile_load(const char* Kh, RowFn rowfn, typename Mfma<DT>::v8 (&b)[4][D / 32]) {
-    using v8 = typename Mfma<DT>::v8;
-    constexpr int KS = D / 32;
-    const int lane = lane_id();
-    const int j = lane >> 4, n = lane & 15;
-#pragma unroll
-    for (int g = 0; g < 4; ++g) {
-        const int64_t row = rowfn(16 * g + n);
-        const v8* p = reinterpret_cast<const v8*>(Kh + row * (D * 2)) + j;
-#pragma unroll
-        for (int s = 0; s < KS; ++s) b[g][s] = p[4 * s];
-    }
-}
-
-// The same for a tile whose 64 rows all exist, through buffer loads: the tile's address
-// (wave-uniform) sits in a scalar buffer descriptor, the 16-row sub-tile is a scalar offset
-// and lane_off = (n * D + 8 j) * 2 the lane's loop-invariant byte offset, so the loop holds
-// no per-lane address arithmetic at all.  (With per-lane 64-bit addresses the compiler
-// builds them in registers of the buffer it is about to refill and then waits for every
-// outstanding load before it may overwrite them, which serialises every other prefetch.)
-template <int DT, int D>
-__device__ __forceinline__ void tile_load_full(const char* tile_base, uint32_t lane_off,
-                                               typename Mfma<DT>::v8 (&b)[4][D / 32]) {
-    using v8 = typename Mfma<DT>::v8;
-    constexpr int KS = D / 32;
-    // raw buffer (stride 0), 64 * D * 2 bytes long, 32-bit data format
-    const __amdgpu_buffer_rsrc_t rsrc =
-        __builtin_amdgcn_make_buffer_rsrc(const_cast<char*>(tile_base), 0, 64 * D * 2, 0x00020000);
-#pragma unroll
-    for (int g = 0; g < 4; ++g) {
-#pragma unroll
-        for (int s = 0; s < KS; ++s) {
-            const u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(rsrc, (int)lane_off + 64 * s, g * 16 * D * 2, 0);
-            b[g][s] = __builtin_bit_cast(v8, v);
-        }
-    }
-}
-
-// A wave's walk over the tiles tile, tile + step, ... < end with two register buffers: the
-// next tile's loads are in flight while the current one is multiplied and filtered.  The
-// prefetch is unconditional (past the end it re-reads a tile the wave already had, a cache
-// hit) so that the wait before the MFMAs only covers the tile they consume.  Returns the
-// first tile of the sequence at or past `end`.
-template <bool PIPELINED, class Buf, class Load, class Use>
-__device__ __forceinline__ int64_t walk_tiles(int64_t tile, int64_t end, int64_t step, Buf& ba, Buf& bb, Load load,
-                                              Use use) {
-  if (PIPELINED) {
-    if (tile < end) {
-        load(ba, tile);
-        while (true) {
-            const int64_t t1 = tile + step;
-            load(bb, t1 < end ? t1 : tile);
-            __builtin_amdgcn_sched_barrier(0);
-            use(ba, tile);
-            if (t1 >= end) { tile = t1; break; }
-            const int64_t t2 = t1 + step;
-            load(ba, t2 < end ? t2 : t1);
-            __builtin_amdgcn_sched_barrier(0);
-            use(bb, t1);
-            if (t2 >= end) { tile = t2; break; }
-            tile = t2;
-        }
-    }
-  } else {       // one buffer: the other waves of the compute unit cover the latency
-    for (; tile < end; tile += step) {
-        load(ba, tile);
-        __builtin_amdgcn_sched_barrier(0);
-        use(ba, tile);
-    }
-  }
-    return tile;
-}
-
-// head_dim 256 makes a 64-key tile 32 KiB: two register buffers of it do not fit, and
-// with 8 waves per compute unit 256 KiB are in flight anyway.
-template <int D> struct ScanPipelined { static constexpr bool value = D <= 128; };
-
-// Scores of the tile: lane l gets res[r] = q_{head0 + r} . K[row(l)].
-template <int DT, int D>
-__device__ __forceinline__ f32x4 tile_mac(const typename Mfma<DT>::v8 (&b)[4][D / 32],
-                                          const typename Mfma<DT>::v8 (&qa)[D / 32]) {
-    constexpr int KS = D / 32;
-    const int j = lane_id() >> 4;
-    f32x4 c[4];
-#pragma unroll
-    for (int g = 0; g < 4; ++g) {
-        c[g] = f32x4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-        for (int s = 0; s < KS; ++s) c[g] = Mfma<DT>::mac(qa[s], b[g][s], c[g]);
-    }
-    // rows 4 jj .. 4 jj + 3 of every accumulator hold heads 0..3; lane group jj keeps sub-tile jj
-    f32x4 res;
-#pragma unroll
-    for (int r = 0; r < 4; ++r) {
-        const float lo = (j & 1) ? c[1][r] : c[0][r];
-        const float hi = (j & 1) ? c[3][r] : c[2][r];
-        res[r] = (j & 2) ? hi : lo;
-    }
-    return res;
-}
 
 template <int DT, int D, int MODE>
 __global__ void __launch_bounds__(kScanWaves* kWave)
@@ -213,12 +78,18 @@ scan_mfma_kernel(Shape sh, Bufs bf, int tiles_per_wave, float* dst) {
         cs2{st0 + 2 * kStage, list0 + 2 * (int64_t)sh.cand_cap, sid, 0, 0},
         cs3{st0 + 3 * kStage, list0 + 3 * (int64_t)sh.cand_cap, sid, 0, 0};
     float thr0 = 0.f, thr1 = 0.f, thr2 = 0.f, thr3 = 0.f;
+    float lo0 = 0.f, lo1 = 0.f, lo2 = 0.f, lo3 = 0.f, iw0 = 0.f, iw1 = 0.f, iw2 = 0.f, iw3 = 0.f;   // tail_bin() of each head
     float top0 = -INFINITY, top1 = -INFINITY, top2 = -INFINITY, top3 = -INFINITY;   // largest score seen per head
+    // candidates of this workgroup per score bin and head (the tail sorts them by bin)
+    __shared__ uint32_t hist_lds[MODE == MODE_FILTER ? 4 * kTailBins : 1];
     if (MODE == MODE_FILTER) {
-        thr0 = bf.thr[head0];
-        if (1 < G) thr1 = bf.thr[head0 + 1];
-        if (2 < G) thr2 = bf.thr[head0 + 2];
-        if (3 < G) thr3 = bf.thr[head0 + 3];
+        const float* bins = bf.bins + 2 * head0;
+        thr0 = bf.thr[head0]; lo0 = bins[0]; iw0 = bins[1];
+        if (1 < G) { thr1 = bf.thr[head0 + 1]; lo1 = bins[2]; iw1 = bins[3]; }
+        if (2 < G) { thr2 = bf.thr[head0 + 2]; lo2 = bins[4]; iw2 = bins[5]; }
+        if (3 < G) { thr3 = bf.thr[head0 + 3]; lo3 = bins[6]; iw3 = bins[7]; }
+        for (int i = threadIdx.x; i < 4 * kTailBins; i += kScanWaves * kWave) hist_lds[i] = 0;
+        __syncthreads();
     }
 
     // row of tile slot `slot` for the tile starting at item `item0`
@@ -246,10 +117,10 @@ scan_mfma_kernel(Shape sh, Bufs bf, int tiles_per_wave, float* dst) {
                 top0 = fmaxf(top0, res[0]); top1 = fmaxf(top1, res[1]);
                 top2 = fmaxf(top2, res[2]); top3 = fmaxf(top3, res[3]);
             }
-            if (0 < G) filter_head(res[0], thr0, cs0, valid, item, seg_cap, sh.n_seg);
-            if (1 < G) filter_head(res[1], thr1, cs1, valid, item, seg_cap, sh.n_seg);
-            if (2 < G) filter_head(res[2], thr2, cs2, valid, item, seg_cap, sh.n_seg);
-            if (3 < G) filter_head(res[3], thr3, cs3, valid, item, seg_cap, sh.n_seg);
+            if (0 < G) filter_head(res[0], thr0, cs0, valid, item, seg_cap, sh.n_seg, hist_lds, lo0, iw0);
+            if (1 < G) filter_head(res[1], thr1, cs1, valid, item, seg_cap, sh.n_seg, hist_lds + kTailBins, lo1, iw1);
+            if (2 < G) filter_head(res[2], thr2, cs2, valid, item, seg_cap, sh.n_seg, hist_lds + 2 * kTailBins, lo2, iw2);
+            if (3 < G) filter_head(res[3], thr3, cs3, valid, item, seg_cap, sh.n_seg, hist_lds + 3 * kTailBins, lo3, iw3);
         }
     };
 
@@ -287,6 +158,9 @@ scan_mfma_kernel(Shape sh, Bufs bf, int tiles_per_wave, float* dst) {
             if (2 < G) { sc[2 * (int64_t)sh.n_seg] = (uint32_t)cs2.n_glob; sx[2 * (int64_t)sh.n_seg] = top2; }
             if (3 < G) { sc[3 * (int64_t)sh.n_seg] = (uint32_t)cs3.n_glob; sx[3 * (int64_t)sh.n_seg] = top3; }
         }
+        __syncthreads();
+        for (int i = threadIdx.x; i < G * kTailBins; i += kScanWaves * kWave)
+            bf.hist[((head0 + i / kTailBins) * sh.hist_cap + blockIdx.x) * kTailBins + i % kTailBins] = hist_lds[i];
     }
 }
 

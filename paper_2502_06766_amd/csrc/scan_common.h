@@ -45,16 +45,20 @@ __device__ __forceinline__ void stage_flush(CandStage& c, int seg_cap, int n_seg
     c.n_lds = r;
 }
 
-// Keep the keys of one head whose score reaches the head's threshold.
+// Keep the keys of one head whose score reaches the head's threshold.  `hist` (LDS, kTailBins
+// counters of this head, or null) counts the kept keys per score bin.
 __device__ __forceinline__ void filter_head(float score, float thr, CandStage& c, bool valid, int64_t item,
-                                            int seg_cap, int n_seg) {
+                                            int seg_cap, int n_seg, uint32_t* hist = nullptr, float bin_lo = 0.f, float bin_inv = 0.f) {
     const float sc = score + 0.0f;
     const bool pass = valid && sc >= thr;
     const uint64_t m = __ballot(pass);
     if (m) {
         const int add = __popcll(m);
         if (c.n_lds + add > kStage) stage_flush(c, seg_cap, n_seg);
-        if (pass) c.lds[c.n_lds + mask_rank(m)] = ((uint64_t)__float_as_uint(sc) << 32) | (uint64_t)(uint32_t)item;
+        if (pass) {
+            c.lds[c.n_lds + mask_rank(m)] = ((uint64_t)__float_as_uint(sc) << 32) | (uint64_t)(uint32_t)item;
+            if (hist) atomicAdd(&hist[tail_bin(sc, bin_lo, bin_inv)], 1u);
+        }
         c.n_lds += add;
     }
 }

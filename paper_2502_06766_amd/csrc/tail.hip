@@ -1,0 +1,600 @@
+// Tail of the filtered path: exact top-k among the candidates the key scan kept, softmax
+// over the k selected scores and weighted sum of their value rows (the knn_search result
+// and the attention step of Algorithm 1 of arXiv 2502.06766), in two kernels that use the
+// whole chip instead of one workgroup per head.
+//
+// The scan leaves, beside every head's candidate list, the number of candidates each of
+// its workgroups found per score bin (64 bins above the head's threshold, monotone in the
+// score).  From these counts every workgroup of the first kernel derives, on its own and
+// without any exchange, the bin B the k-th largest score falls in: candidates in higher
+// bins are selected for certain, candidates in lower bins are not, and only those of bin B
+// (a few hundred) still have to be ranked exactly.
+//
+//   tail_gather_kernel  many workgroups per head, each over the candidates of a few scan
+//                       workgroups: writes the certain winners to idx / vals at offsets known
+//                       from the counts, copies bin B's candidates to the head's boundary
+//                       list, and accumulates the softmax-weighted value rows of its winners
+//                       (weights relative to the head's largest score, which the scan reported).
+//   tail_finish_kernel  one workgroup per head: exact selection (radix select, lower
+//                       position wins ties) of the missing winners among the boundary list,
+//                       their value rows, the sum of all partials in a fixed order,
+//                       normalisation, padding of idx / vals.
+//
+// A head whose candidate list is unusable (a segment overflowed, the sampled threshold came
+// out above the k-th score, or its sequence cannot be filtered at all) is redone exactly
+// inside the same two launches: the workgroups of the first kernel rescore all keys of the
+// head's KV head with the MFMA tile routine of the scan (once per group of up to four heads
+// that share the keys) into the score buffer, and the second kernel selects over the full
+// score row and gathers the k rows itself.  Nothing is launched for the common case.
+#include "device_utils.h"
+#include "internal.h"
+#include "scan_common.h"
+#include "scan_tiles.h"
+#include "select_common.h"
+
+namespace tka {
+
+enum { TAIL_NORMAL = 0, TAIL_REDO = 1, TAIL_EMPTY = 2 };
+struct TailRec { uint32_t state, above, need, have; };   // what tail_finish_kernel needs to know of a head
+
+constexpr int kTailThreads = 256;
+constexpr int kTailWaves = kTailThreads / kWave;
+constexpr int kTailStage = 128;      // winners a wave stages before it fetches their value rows
+static_assert(kTailWaves == kScanWaves && kTailBins == kWave, "wave w of a tail workgroup takes the segments of wave w of the scan");
+
+// What the scan left for head bh: candidates in all segments, longest segment, largest score
+// key any scanning wave saw.  All threads of the workgroup call it and get the same values.
+__device__ __forceinline__ void seg_summary(const Shape& sh, const Bufs& bf, int64_t bh, uint32_t (&red)[3][kTailWaves],
+                                            uint32_t& total, uint32_t& max_len, uint32_t& kmx) {
+    uint32_t sum = 0, mxl = 0, km = 0;
+    for (int g = threadIdx.x; g < sh.n_seg; g += kTailThreads) {
+        const uint32_t c = bf.seg_cnt[bh * sh.n_seg + g];
+        const uint32_t m = score_key(bf.seg_max[bh * sh.n_seg + g]);
+        sum += c;
+        mxl = c > mxl ? c : mxl;
+        km = m > km ? m : km;
+    }
+    for (int o = 32; o > 0; o >>= 1) {
+        sum += __shfl_xor(sum, o, kWave);
+        const uint32_t t = __shfl_xor(mxl, o, kWave), u = __shfl_xor(km, o, kWave);
+        mxl = t > mxl ? t : mxl;
+        km = u > km ? u : km;
+    }
+    __syncthreads();                 // the scratch may still be read from a previous call
+    if (lane_id() == 0) {
+        const int w = threadIdx.x >> 6;
+        red[0][w] = sum; red[1][w] = mxl; red[2][w] = km;
+    }
+    __syncthreads();
+    total = 0; max_len = 0; kmx = 0;
+#pragma unroll
+    for (int w = 0; w < kTailWaves; ++w) {
+        total += red[0][w];
+        max_len = red[1][w] > max_len ? red[1][w] : max_len;
+        kmx = red[2][w] > kmx ? red[2][w] : kmx;
+    }
+}
+
+// Is the candidate list of head bh unusable?  (uniform over the workgroup)
+__device__ __forceinline__ bool head_needs_redo(const Shape& sh, const Bufs& bf, int64_t bh, int k_eff,
+                                                uint32_t (&red)[3][kTailWaves], uint32_t& kmx) {
+    if (bf.flags[bh]) { kmx = 0; return true; }          // its sequence was not filtered at all
+    uint32_t total, max_len;
+    seg_summary(sh, bf, bh, red, total, max_len, kmx);
+    return max_len > (uint32_t)sh.seg_cap || total < (uint32_t)k_eff;
+}
+
+template <int DT, int D>
+__global__ void __launch_bounds__(kTailThreads) tail_gather_kernel(Shape sh, Bufs bf, float scale_log2e) {
+    using v8 = typename Mfma<DT>::v8;
+    constexpr int EPL = 8;                 // elements per 16-byte load
+    constexpr int LPR = D / EPL;           // lanes per value row
+    constexpr int RPW = kWave / LPR;       // rows a wave fetches per load instruction
+    constexpr int U = 4;                   // independent rows in flight per lane group
+    constexpr int R = 2;                   // batches of 64 candidates a wave keeps in registers between its two passes
+    __shared__ uint32_t s_red[3][kTailWaves];
+    __shared__ uint32_t s_part[2][kTailWaves][kTailBins];
+    __shared__ uint32_t s_sel[6];
+    __shared__ uint32_t s_cnt[kTailWaves][2];
+    __shared__ int32_t st_pos[kTailWaves][kTailStage];
+    __shared__ float st_w[kTailWaves][kTailStage];
+    __shared__ float s_acc[kTailWaves][D + 1];
+
+    const int awg = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
+    const int tid = threadIdx.x, lane = lane_id();
+    const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+    const int64_t bh = (int64_t)b * sh.Hq + h;
+    TailRec* rec = reinterpret_cast<TailRec*>(bf.tailrec) + bh;
+
+    // Everything the prologue needs from memory is asked for before anything is waited for: this
+    // kernel is a chain of dependent steps per workgroup, and every load it waits for on its own
+    // costs a full trip to memory (what the scan wrote is in no cache of this compute unit).
+    const int n_wg = sh.n_seg / kScanWaves;                          // scan workgroups that fed this head
+    const int j0 = awg * sh.tail_spw;
+    const int j1 = j0 + sh.tail_spw < n_wg ? j0 + sh.tail_spw : n_wg;
+    const float bin_lo = bf.bins[2 * bh], bin_inv = bf.bins[2 * bh + 1];
+    const uint64_t* list = bf.cand + bh * (int64_t)sh.cand_cap;
+    const uint32_t* scnt = bf.seg_cnt + bh * sh.n_seg;
+    uint32_t h_all = 0, h_before = 0;
+    {
+        const uint32_t* hp = bf.hist + bh * (int64_t)sh.hist_cap * kTailBins;
+        const int bin = tid & (kTailBins - 1), part = tid >> 6;      // kTailBins == kWave: one wave per part
+#pragma unroll 8
+        for (int j = part; j < n_wg; j += kTailWaves) {
+            const uint32_t c = hp[j * kTailBins + bin];
+            h_all += c;
+            h_before += j < j0 ? c : 0u;
+        }
+    }
+    // the first candidates of this wave's first segment, before their number is known (any slot of
+    // the list may be read; what lies beyond the segment's length is ignored below)
+    const int g_first = j0 * kScanWaves + wave;
+    uint64_t saved[R];
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+        const int64_t slot = cand_slot(r * kWave + lane, g_first, sh.n_seg);
+        saved[r] = list[slot < sh.cand_cap ? slot : 0];
+    }
+
+    const int64_t N = prefix_len(visible_len(sh, bf, b), sh.window);
+    const int k_eff = sh.k < N ? sh.k : (int)N;
+    if (k_eff == 0) {                      // nothing to search for this sequence
+        if (awg == 0 && tid == 0) *rec = TailRec{TAIL_EMPTY, 0u, 0u, 0u};
+        return;
+    }
+    uint32_t kmx;
+    if (head_needs_redo(sh, bf, bh, k_eff, s_red, kmx)) {
+        if (awg == 0 && tid == 0) {
+            *rec = TailRec{TAIL_REDO, 0u, 0u, 0u};
+            if (!bf.flags[bh]) atomicAdd(bf.fallback_total, 1u);     // a list that should have been usable
+        }
+        // Exact scores of every key for the heads of this group that need them, computed once: by the
+        // workgroups of the lowest such head among the (up to four) heads that share an operand block.
+        const int r_full = h % sh.G, sub0 = r_full & ~3, r_me = r_full - sub0;
+        const int Gs = sh.G - sub0 < 4 ? sh.G - sub0 : 4;
+        const int64_t head0 = bh - r_me;
+        uint32_t mask = 0;
+        for (int r = 0; r < Gs; ++r) {
+            uint32_t dummy;
+            if (r == r_me || head_needs_redo(sh, bf, head0 + r, k_eff, s_red, dummy)) mask |= 1u << r;
+        }
+        if ((mask & ((1u << r_me) - 1u)) != 0u) return;              // a lower head of the group leads
+        v8 qa[D / 32];
+        load_query_a<DT, D>(bf.q, head0, Gs, qa);
+        const int kvh = h / sh.G;
+        const char* Kh = static_cast<const char*>(bf.K) + ((int64_t)cache_seq(sh, b) * sh.Hkv + kvh) * sh.Ncap * (D * 2);
+        // 16 keys per step (one MFMA column block; a quarter of the scan's tile keeps this rarely used
+        // branch from setting the register budget of the kernel): lane (j, n) loads the chunks 4 s + j of
+        // key n, every group of four accumulator rows holds the heads of the block for key n
+        const int jj = lane >> 4, n = lane & 15;
+        const int64_t n_blk = (N + 15) / 16;
+        for (int64_t blk = (int64_t)awg * kTailWaves + wave; blk < n_blk; blk += (int64_t)gridDim.x * kTailWaves) {
+            const int64_t key = blk * 16 + n;
+            const v8* p = reinterpret_cast<const v8*>(Kh + (key < N ? key : N - 1) * (D * 2)) + jj;
+            v8 kb[D / 32];
+#pragma unroll
+            for (int s = 0; s < D / 32; ++s) kb[s] = p[4 * s];
+            f32x4 acc4 = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int s = 0; s < D / 32; ++s) acc4 = Mfma<DT>::mac(qa[s], kb[s], acc4);
+            if (jj == 0 && key < N) {
+#pragma unroll
+                for (int r = 0; r < 4; ++r)
+                    if (mask & (1u << r)) bf.scores[(head0 + r) * sh.Ncap + key] = acc4[r];
+            }
+        }
+        return;
+    }
+
+    // ---- the bin of the k-th score and this workgroup's output offsets, from the scan's counts
+    s_part[0][tid >> 6][tid & (kTailBins - 1)] = h_all;
+    s_part[1][tid >> 6][tid & (kTailBins - 1)] = h_before;
+    __syncthreads();
+    if (wave == 0) {
+        // lane l looks at bin kTailBins - 1 - l: prefix sums run from the highest bin down
+        const int bin = kTailBins - 1 - lane;
+        uint32_t all = 0, before = 0;
+#pragma unroll
+        for (int p = 0; p < kTailWaves; ++p) { all += s_part[0][p][bin]; before += s_part[1][p][bin]; }
+        uint32_t ia = all, ib = before;
+        for (int o = 1; o < kWave; o <<= 1) {
+            const uint32_t va = __shfl_up(ia, o, kWave), vb = __shfl_up(ib, o, kWave);
+            if (lane >= o) { ia += va; ib += vb; }
+        }
+        const uint32_t run = ia - all;
+        if (run < (uint32_t)k_eff && (uint32_t)k_eff <= ia) {        // exactly one lane: total >= k_eff
+            s_sel[0] = (uint32_t)bin;            // B: the bin the k-th score falls in
+            s_sel[1] = run;                      // candidates in higher bins: selected for certain
+            s_sel[2] = all;                      // candidates in bin B
+            s_sel[3] = ib - before;              // certain winners of the scan workgroups before mine
+            s_sel[4] = before;                   // bin-B candidates of the scan workgroups before mine
+        }
+    }
+    __syncthreads();
+    const int binB = (int)s_sel[0];
+    const uint32_t above = s_sel[1], have = s_sel[2];
+    const float hmax = key_score(kmx);
+    if (awg == 0 && tid == 0) {
+        *rec = TailRec{TAIL_NORMAL, above, (uint32_t)k_eff - above, have};
+        bf.hmax[bh] = hmax;
+    }
+
+    // ---- first pass over my candidates: how many certain winners / bin-B candidates each wave has.
+    // Wave w takes segment 4 j + w of every scan workgroup j of mine, 64 candidates at a time; the
+    // first R batches stay in registers for the second pass.
+    uint32_t nw = 0, nb = 0;
+    {
+        int bi = 0;
+        for (int j = j0; j < j1; ++j) {
+            const int g = j * kScanWaves + wave;
+            const uint32_t cnt = scnt[g];
+            for (uint32_t e0 = 0; e0 < cnt; e0 += kWave, ++bi) {
+                const uint32_t e = e0 + lane;
+                uint64_t ent;
+                if (j == j0 && bi < R) ent = bi == 0 ? saved[0] : saved[1];
+                else {
+                    ent = list[cand_slot(e < cnt ? e : 0, g, sh.n_seg)];
+                    if (bi < R) { if (bi == 0) saved[0] = ent; else saved[1] = ent; }
+                }
+                const int bin = tail_bin(__uint_as_float((uint32_t)(ent >> 32)), bin_lo, bin_inv);
+                nw += (e < cnt && bin > binB) ? 1u : 0u;
+                nb += (e < cnt && bin == binB) ? 1u : 0u;
+            }
+        }
+    }
+    static_assert(R == 2, "the register cache of candidate batches is written out for two batches");
+    for (int o = 32; o > 0; o >>= 1) { nw += __shfl_xor(nw, o, kWave); nb += __shfl_xor(nb, o, kWave); }
+    if (lane == 0) { s_cnt[wave][0] = nw; s_cnt[wave][1] = nb; }
+    __syncthreads();
+    uint32_t emit_at = s_sel[3], bnd_at = s_sel[4];
+    for (int w = 0; w < wave; ++w) { emit_at += s_cnt[w][0]; bnd_at += s_cnt[w][1]; }
+
+    // ---- second pass: write winners and boundary candidates, fetch the winners' value rows
+    int32_t* idx = bf.sel_idx + bh * sh.k;
+    float* vals = bf.sel_val + bh * sh.k;
+    uint64_t* bnd = bf.bnd + bh * (int64_t)sh.cand_cap;
+    const char* Vh = static_cast<const char*>(bf.V) +
+                     ((int64_t)cache_seq(sh, b) * sh.Hkv + h / sh.G) * sh.Ncap * (D * 2);
+    const int rs = lane / LPR, c = lane % LPR;
+    float acc[EPL];
+#pragma unroll
+    for (int e = 0; e < EPL; ++e) acc[e] = 0.f;
+    float lsum = 0.f;
+    int n_st = 0;                                                    // staged winners (uniform over the wave)
+    auto fetch_staged = [&]() {
+        wave_sync();
+        for (int r0 = 0; r0 < n_st; r0 += RPW * U) {
+            float w[U];
+            u32x4 raw[U];
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const int r = r0 + u * RPW + rs;
+                const bool ok = r < n_st;
+                const int64_t pos = st_pos[wave][ok ? r : 0];
+                w[u] = ok ? st_w[wave][r] : 0.f;
+                raw[u] = *reinterpret_cast<const u32x4*>(Vh + (pos * D + c * EPL) * 2);
+            }
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                float vf[EPL];
+                Elem<DT>::widen(raw[u], vf);
+#pragma unroll
+                for (int e = 0; e < EPL; ++e) acc[e] = fmaf(w[u], vf[e], acc[e]);
+                lsum += w[u];
+            }
+        }
+        wave_sync();
+        n_st = 0;
+    };
+    {
+        int bi = 0;
+        for (int j = j0; j < j1; ++j) {
+            const int g = j * kScanWaves + wave;
+            const uint32_t cnt = scnt[g];
+            for (uint32_t e0 = 0; e0 < cnt; e0 += kWave, ++bi) {
+                const uint32_t e = e0 + lane;
+                const bool valid = e < cnt;
+                uint64_t ent;
+                if (bi < R) ent = bi == 0 ? saved[0] : saved[1];
+                else ent = list[cand_slot(valid ? e : 0, g, sh.n_seg)];
+                const float sc = __uint_as_float((uint32_t)(ent >> 32));
+                const int bin = tail_bin(sc, bin_lo, bin_inv);
+                const bool win = valid && bin > binB, edge = valid && bin == binB;
+                const uint64_t mw = __ballot(win), me = __ballot(edge);
+                if (n_st > kTailStage - kWave) fetch_staged();
+                if (win) {
+                    const int r = mask_rank(mw);
+                    const uint32_t o = emit_at + (uint32_t)r;
+                    if (o < (uint32_t)k_eff) {            // always true; guards the output buffers
+                        idx[o] = (int32_t)(uint32_t)ent;
+                        vals[o] = sc;
+                    }
+                    st_pos[wave][n_st + r] = (int32_t)(uint32_t)ent;
+                    st_w[wave][n_st + r] = exp2f((sc - hmax) * scale_log2e);
+                }
+                if (edge) {
+                    const uint32_t o = bnd_at + (uint32_t)mask_rank(me);
+                    if (o < (uint32_t)sh.cand_cap) bnd[o] = ent;
+                }
+                const int addw = __popcll(mw);
+                emit_at += (uint32_t)addw;
+                bnd_at += (uint32_t)__popcll(me);
+                n_st += addw;
+            }
+        }
+    }
+    fetch_staged();
+
+    // ---- this workgroup's partial sum (weights relative to the head's largest score)
+    for (int o = LPR; o < kWave; o <<= 1) {
+#pragma unroll
+        for (int e = 0; e < EPL; ++e) acc[e] += wave_xor(acc[e], o);
+        lsum += wave_xor(lsum, o);
+    }
+    if (rs == 0) {
+#pragma unroll
+        for (int e = 0; e < EPL; ++e) s_acc[wave][c * EPL + e] = acc[e];
+        if (c == 0) s_acc[wave][D] = lsum;
+    }
+    __syncthreads();
+    float* pacc = bf.part_acc + (bh * sh.n_chunk_cap + awg) * D;
+    for (int t = tid; t < D; t += kTailThreads) pacc[t] = (s_acc[0][t] + s_acc[1][t]) + (s_acc[2][t] + s_acc[3][t]);
+    if (tid == 0) {
+        bf.part_l[bh * sh.n_chunk_cap + awg] = (s_acc[0][D] + s_acc[1][D]) + (s_acc[2][D] + s_acc[3][D]);
+        bf.part_m[bh * sh.n_chunk_cap + awg] = hmax;
+    }
+}
+
+// Candidates of the boundary bin: a dense list of (score bits << 32 | position) entries.
+template <int NT>
+struct SrcListT {
+    static constexpr int kThreads = NT;
+    const uint64_t* ent;
+    int64_t n;
+    uint32_t* pos_lds;       // LDS: inverted positions of the cached slots, [slot j][thread]
+    typedef uint64_t raw_t;
+    __device__ __forceinline__ int64_t slots() const { return n; }
+    __device__ __forceinline__ bool valid(int64_t i) const { return i < n; }
+    __device__ __forceinline__ const uint64_t* where(int64_t i) const { return ent + i; }
+    __device__ __forceinline__ uint32_t key(uint64_t e) const { return score_key(__uint_as_float((uint32_t)(e >> 32))); }
+    __device__ __forceinline__ uint32_t ipos(uint64_t e, int64_t) const { return 0xFFFFFFFFu - (uint32_t)e; }
+    __device__ __forceinline__ void stash(int j, uint64_t e) const { pos_lds[j * NT + (int)threadIdx.x] = 0xFFFFFFFFu - (uint32_t)e; }
+    __device__ __forceinline__ uint32_t cached_ipos(int j) const { return pos_lds[j * NT + (int)threadIdx.x]; }
+};
+
+constexpr int kFinishSmall = 2048;     // boundary candidates ranked by direct comparison; more go through the radix select
+
+// Rank of each of this thread's CI items among the composite keys in LDS (number of keys that
+// beat it), by comparing with every key: all lanes read the same key at a time (an LDS
+// broadcast), eight reads in flight.  `n8` is the list length rounded up to a multiple of eight,
+// the padding holds keys that beat nothing.
+template <int CI>
+__device__ __forceinline__ void rank_by_comparison(const uint64_t* keys, int n8, const uint64_t (&mine)[CI], uint32_t (&rank)[CI]) {
+#pragma unroll
+    for (int i = 0; i < CI; ++i) rank[i] = 0;
+    for (int base = 0; base < n8; base += 8) {
+        uint64_t o[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) o[u] = keys[base + u];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+#pragma unroll
+            for (int i = 0; i < CI; ++i) rank[i] += o[u] > mine[i] ? 1u : 0u;
+        }
+    }
+}
+
+template <int DT, int NT>
+__global__ void __launch_bounds__(NT) tail_finish_kernel(Shape sh, Bufs bf, float scale, float scale_log2e) {
+    constexpr int EPL = 8, NW = NT / kWave, CPT = 4, U = 4;
+    constexpr int CIMAX = kFinishSmall / NT;       // boundary candidates per thread on the small path
+    __shared__ SelShared sm;
+    __shared__ uint32_t pos_lds[CPT * NT];
+    __shared__ __align__(16) uint64_t s_keys[kFinishSmall + 8];
+    __shared__ int32_t s_pos[kFinishSmall];
+    __shared__ float s_w[kFinishSmall];
+    __shared__ float s_acc[NW][256 + 1];
+    __shared__ float s_red[NT];
+    const int h = blockIdx.x, b = blockIdx.y;
+    const int tid = threadIdx.x, lane = lane_id(), wave = tid >> 6;
+    const int64_t bh = (int64_t)b * sh.Hq + h;
+    const int D = sh.D;
+    const int64_t N = prefix_len(visible_len(sh, bf, b), sh.window);
+    const int k_eff = sh.k < N ? sh.k : (int)N;
+    const TailRec rec = reinterpret_cast<const TailRec*>(bf.tailrec)[bh];
+    float hmax = bf.hmax[bh];                 // the first kernel's, unless the head is redone
+    int32_t* idx = bf.sel_idx + bh * sh.k;
+    float* vals = bf.sel_val + bh * sh.k;
+    if (rec.state == TAIL_EMPTY || k_eff == 0) {
+        pad_outputs(0, sh.k, idx, vals);
+        for (int t = tid; t < D; t += NT) bf.out[bh * D + t] = 0.f;
+        if (tid == 0) {
+            bf.hmax[bh] = -INFINITY;
+            if (bf.lse) bf.lse[bh] = -INFINITY;
+        }
+        return;
+    }
+    // the partial sums of the first kernel's workgroups, NT / D threads per output element (asked for
+    // first: nothing below depends on them until the end)
+    const int n_parts = rec.state == TAIL_NORMAL ? sh.tail_wgs : 0;
+    const int parts = NT / D, e_out = tid % D, part = tid / D;
+    constexpr int PV = 32;                    // partials per thread whose loads stay in flight until the end
+    float pv[PV], a_parts = 0.f, l_parts = 0.f;
+    {
+        const float* pa = bf.part_acc + bh * sh.n_chunk_cap * (int64_t)D + e_out;
+#pragma unroll
+        for (int u = 0; u < PV; ++u) {
+            const int s = part + u * parts;
+            pv[u] = s < n_parts ? pa[(int64_t)s * D] : 0.f;
+        }
+        for (int s = part + PV * parts; s < n_parts; s += parts) a_parts += pa[(int64_t)s * D];
+        for (int s = tid; s < n_parts; s += NT) l_parts += bf.part_l[bh * sh.n_chunk_cap + s];
+    }
+    const int lpr = D / EPL, rpw = kWave / lpr;
+    const int rs = lane / lpr, c = lane % lpr;
+    const char* Vh = static_cast<const char*>(bf.V) + ((int64_t)cache_seq(sh, b) * sh.Hkv + h / sh.G) * sh.Ncap * D * 2;
+    float acc[EPL];
+#pragma unroll
+    for (int e = 0; e < EPL; ++e) acc[e] = 0.f;
+    float lsum = 0.f;
+    // weighted value rows j0 .. j1 of a list of (position, weight) pairs
+    auto gather_rows = [&](int j0, int j1, auto pos_of, auto weight_of) {
+        const int step = NW * rpw;
+        for (int j = j0 + wave * rpw + rs; j < j1; j += U * step) {
+            int64_t r[U];
+            float w[U];
+            u32x4 raw[U];
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const int jj = j + u * step;
+                const bool ok = jj < j1;
+                r[u] = pos_of(ok ? jj : j);
+                w[u] = ok ? weight_of(jj) : 0.f;
+            }
+#pragma unroll
+            for (int u = 0; u < U; ++u) raw[u] = *reinterpret_cast<const u32x4*>(Vh + (r[u] * D + c * EPL) * 2);
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                float vf[EPL];
+                Elem<DT>::widen(raw[u], vf);
+#pragma unroll
+                for (int e = 0; e < EPL; ++e) acc[e] = fmaf(w[u], vf[e], acc[e]);
+                lsum += w[u];
+            }
+        }
+    };
+
+    if (rec.state == TAIL_REDO) {
+        // every score of the head is in the score buffer: exact selection over the full row
+        hmax = key_score(wg_select_dense<NT, 8>(sh, bf, bh, N, k_eff, sm));     // writes idx, vals, padding, hmax
+        __syncthreads();                      // idx / vals written above are read below
+        gather_rows(0, k_eff, [&](int j) { return (int64_t)idx[j]; },
+                    [&](int j) { return exp2f((vals[j] - hmax) * scale_log2e); });
+    } else if ((int)rec.have > kFinishSmall) {
+        // a boundary bin this full (massive ties, or a sample that misjudged the k-th score): radix select
+        const SrcListT<NT> src{bf.bnd + bh * (int64_t)sh.cand_cap, (int64_t)rec.have, pos_lds};
+        const Items<CPT, SrcListT<NT>> items(src);
+        wg_topk_emit(items, (int)rec.need, sh.k - (int)rec.above, idx + rec.above, vals + rec.above, sm);
+        __syncthreads();
+        gather_rows((int)rec.above, k_eff, [&](int j) { return (int64_t)idx[j]; },
+                    [&](int j) { return exp2f((vals[j] - hmax) * scale_log2e); });
+    } else {
+        // The usual case, a few hundred boundary candidates: each is ranked against all others by its
+        // composite key (score key, then inverted position: larger beats smaller, equal scores go to
+        // the lower position, no two keys are equal), and the `need` best are the missing winners.
+        const uint64_t* bnd = bf.bnd + bh * (int64_t)sh.cand_cap;
+        const int have = (int)rec.have, need = (int)rec.need;
+        uint64_t mine[CIMAX], ent[CIMAX];
+#pragma unroll
+        for (int i = 0; i < CIMAX; ++i) {
+            const int s = i * NT + tid;
+            ent[i] = s < have ? bnd[s] : 0ull;
+            mine[i] = s < have ? ((uint64_t)score_key(__uint_as_float((uint32_t)(ent[i] >> 32))) << 32) |
+                                     (uint64_t)(0xFFFFFFFFu - (uint32_t)ent[i])
+                               : ~0ull;                                   // nothing beats an empty slot's key
+            if (s < have) s_keys[s] = mine[i];
+        }
+        const int have8 = (have + 7) & ~7;
+        if (tid < have8 - have) s_keys[have + tid] = 0ull;               // padding: beats nothing
+        __syncthreads();
+        uint32_t rank[CIMAX];
+        const int ci = (have + NT - 1) / NT;                              // slots per thread in use (uniform)
+        if (ci <= 1) { uint64_t m1[1] = {mine[0]}; uint32_t r1[1]; rank_by_comparison<1>(s_keys, have8, m1, r1); rank[0] = r1[0]; }
+        else if (ci <= 2 && CIMAX >= 2) {
+            uint64_t m2[2] = {mine[0], mine[CIMAX >= 2 ? 1 : 0]}; uint32_t r2[2];
+            rank_by_comparison<2>(s_keys, have8, m2, r2); rank[0] = r2[0]; rank[CIMAX >= 2 ? 1 : 0] = r2[1];
+        } else rank_by_comparison<CIMAX>(s_keys, have8, mine, rank);
+        // winners in a fixed order: slot-major, then thread
+        uint32_t wave_total = 0;
+#pragma unroll
+        for (int i = 0; i < CIMAX; ++i) {
+            const bool win = i < ci && i * NT + tid < have && rank[i] < (uint32_t)need;
+            wave_total += (uint32_t)__popcll(__ballot(win));
+        }
+        if (lane == 0) sm.wave_tot[wave] = wave_total;
+        __syncthreads();
+        uint32_t run = 0;
+        for (int w = 0; w < wave; ++w) run += sm.wave_tot[w];
+#pragma unroll
+        for (int i = 0; i < CIMAX; ++i) {
+            const bool win = i < ci && i * NT + tid < have && rank[i] < (uint32_t)need;
+            const uint64_t m = __ballot(win);
+            if (win) {
+                const uint32_t o = run + (uint32_t)mask_rank(m);
+                if (o < (uint32_t)need) {         // always true; guards the buffers
+                    const float sc = __uint_as_float((uint32_t)(ent[i] >> 32));
+                    idx[rec.above + o] = (int32_t)(uint32_t)ent[i];
+                    vals[rec.above + o] = sc;
+                    s_pos[o] = (int32_t)(uint32_t)ent[i];
+                    s_w[o] = exp2f((sc - hmax) * scale_log2e);
+                }
+            }
+            run += (uint32_t)__popcll(m);
+        }
+        pad_outputs(k_eff, sh.k, idx, vals);
+        __syncthreads();
+        gather_rows(0, need, [&](int j) { return (int64_t)s_pos[j]; }, [&](int j) { return s_w[j]; });
+    }
+
+    for (int o = lpr; o < kWave; o <<= 1) {
+#pragma unroll
+        for (int e = 0; e < EPL; ++e) acc[e] += wave_xor(acc[e], o);
+        lsum += wave_xor(lsum, o);
+    }
+    __syncthreads();                          // sm.wave_tot is reused below
+    if (rs == 0) {
+#pragma unroll
+        for (int e = 0; e < EPL; ++e) s_acc[wave][c * EPL + e] = acc[e];
+        if (c == 0) s_acc[wave][256] = lsum;
+    }
+    for (int o = 32; o > 0; o >>= 1) l_parts += wave_xor(l_parts, o);          // fixed tree: same result every run
+#pragma unroll
+    for (int u = 0; u < PV; ++u) a_parts += pv[u];                             // fixed order
+    s_red[tid] = a_parts;
+    if (lane == 0) sm.wave_tot[wave] = __float_as_uint(l_parts);
+    __syncthreads();
+    if (tid < D) {
+        float lt = 0.f, at = 0.f;
+        for (int w = 0; w < NW; ++w) lt += __uint_as_float(sm.wave_tot[w]) + s_acc[w][256];
+        for (int w = 0; w < NW; ++w) at += s_acc[w][e_out];
+        for (int p = 0; p < parts; ++p) at += s_red[p * D + e_out];
+        bf.out[bh * D + e_out] = at / lt;
+        if (tid == 0 && bf.lse) bf.lse[bh] = hmax * scale + logf(lt);
+    }
+}
+
+bool tail_supported(const Shape& s) {
+    return !scan_row_tiles(s) && !s.indexed && s.window == 0 && (s.dtype == DT_F16 || s.dtype == DT_BF16) &&
+           s.n_seg % kScanWaves == 0 && s.n_seg / kScanWaves <= s.hist_cap && s.tail_wgs <= s.n_chunk_cap;
+}
+
+hipError_t launch_tail(const Shape& s, const Bufs& b, hipStream_t st) {
+    const float scale = 1.0f / sqrtf((float)s.D);
+    const float scale_log2e = scale * 1.4426950408889634f;
+    const dim3 grid_a((unsigned)s.tail_wgs, (unsigned)s.Hq, (unsigned)s.B);
+#define TKA_TAIL_A(DT_, D_) hipLaunchKernelGGL((tail_gather_kernel<DT_, D_>), grid_a, dim3(kTailThreads), 0, st, s, b, scale_log2e)
+    if (s.dtype == DT_F16 && s.D == 128) TKA_TAIL_A(DT_F16, 128);
+    else if (s.dtype == DT_BF16 && s.D == 128) TKA_TAIL_A(DT_BF16, 128);
+    else if (s.dtype == DT_F16 && s.D == 64) TKA_TAIL_A(DT_F16, 64);
+    else if (s.dtype == DT_BF16 && s.D == 64) TKA_TAIL_A(DT_BF16, 64);
+    else if (s.dtype == DT_F16 && s.D == 256) TKA_TAIL_A(DT_F16, 256);
+    else if (s.dtype == DT_BF16 && s.D == 256) TKA_TAIL_A(DT_BF16, 256);
+    else if (s.dtype == DT_F16 && s.D == 32) TKA_TAIL_A(DT_F16, 32);
+    else if (s.dtype == DT_BF16 && s.D == 32) TKA_TAIL_A(DT_BF16, 32);
+    else return hipErrorInvalidValue;
+#undef TKA_TAIL_A
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    const dim3 grid_b((unsigned)s.Hq, (unsigned)s.B);
+    const bool small = true;
+    if (s.dtype == DT_F16) {
+        if (small) hipLaunchKernelGGL((tail_finish_kernel<DT_F16, 256>), grid_b, dim3(256), 0, st, s, b, scale, scale_log2e);
+        else hipLaunchKernelGGL((tail_finish_kernel<DT_F16, 1024>), grid_b, dim3(1024), 0, st, s, b, scale, scale_log2e);
+    } else {
+        if (small) hipLaunchKernelGGL((tail_finish_kernel<DT_BF16, 256>), grid_b, dim3(256), 0, st, s, b, scale, scale_log2e);
+        else hipLaunchKernelGGL((tail_finish_kernel<DT_BF16, 1024>), grid_b, dim3(1024), 0, st, s, b, scale, scale_log2e);
+    }
+    return hipGetLastError();
+}
+
+}  // namespace tka

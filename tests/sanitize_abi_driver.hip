@@ -22,6 +22,8 @@ hipError_t launch_threshold(const Shape&, const Bufs&, int64_t, hipStream_t) { r
 hipError_t launch_select_candidates(const Shape&, const Bufs&, hipStream_t) { return hipErrorUnknown; }
 hipError_t launch_select_full(const Shape&, const Bufs&, int64_t, hipStream_t) { return hipErrorUnknown; }
 hipError_t launch_gather(const Shape&, const Bufs&, hipStream_t) { return hipErrorUnknown; }
+bool tail_supported(const Shape&) { return false; }
+hipError_t launch_tail(const Shape&, const Bufs&, hipStream_t) { return hipErrorUnknown; }
 bool index8_supported(int dtype, int D, int G) { return dtype != 0 && D >= 64 && G <= 4; }
 hipError_t launch_quantize_rows(int, int, const void*, int64_t, int64_t, int, int8_t*, float*, int64_t, hipStream_t) {
     return hipErrorUnknown;
