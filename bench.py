@@ -43,6 +43,8 @@ def main() -> int:
     ap.add_argument("--workload", default="c3", choices=["c1", "c2", "c3", "c4", "c5"],
                     help="c3 is the metric's workload; the others are timed the same way for reference")
     ap.add_argument("--k", type=int, default=0, help="override k (c4 is swept over 256, 1024, 4096 in the tests)")
+    ap.add_argument("--force-redo", action="store_true",
+                    help="worst case of the filtered path: every head is redone exactly (not the metric's workload)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--seed", type=int, default=0)
     args = ap.parse_args()
@@ -61,7 +63,7 @@ def main() -> int:
         return 1
     dev = torch.device("cuda", 0)
     w = {"c1": wl.C1, "c2": wl.C2, "c3": wl.C3, "c4": wl.C4, "c5": wl.C5}[args.workload]
-    default = args.workload == "c3" and not args.tokens and not args.k     # the metric's workload as it stands
+    default = args.workload == "c3" and not args.tokens and not args.k and not args.force_redo     # the metric's workload as it stands
     if args.tokens:
         w = w.scaled(args.tokens)
     N, k, d, Hq, Hkv, B = w.n_tokens, args.k or w.k, w.head_dim, w.n_q_heads, w.n_kv_heads, w.n_seqs
@@ -77,6 +79,8 @@ def main() -> int:
                              index_kind=ta.INDEX_INT8 if args.index else ta.INDEX_NONE)
     if args.index:
         cache.set_path(ta.PATH_INDEX)
+    if args.force_redo:
+        ta.topk_attn_debug_force_redo(cache.h, True)
 
     def to_dev(a):
         return torch.from_numpy(a.view(np.int16)).to(dev).view(torch.bfloat16) if w.dtype == wl.BF16 else \
@@ -185,7 +189,8 @@ def main() -> int:
         "data": "synthetic",
         "config": {"workload": w.name, "n_q_heads": Hq, "n_kv_heads": Hkv, "head_dim": d, "n_tokens": N,
                    "k": k, "layers_rotated": L, "n_seqs": B, "queries_per_step": M,
-                   "search": "int8 index + exact refinement" if args.index else "exact"},
+                   "search": "int8 index + exact refinement" if args.index else "exact",
+                   **({"forced": "every head redone exactly (worst case of the filtered path)"} if args.force_redo else {})},
         "scores_per_sec": B * M * Hq * N / (ms_per_step * 1e-3),
         "step_hbm_gbps": alg_bytes / (ms_per_step * 1e-3) / 1e9,
         "step_pct_of_hbm_peak": 100.0 * alg_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBPS,

@@ -17,9 +17,19 @@ extern "C" {
 int topk_attn_scores(topk_attn_t* h, int layer, const void* q, float* scores, void* hip_stream);
 
 /* After the stream has been synchronised by the caller: number of (sequence, head)
- * pairs of the last decode whose filtered candidate list was unusable and were
- * recomputed by the full path.  Copies a few bytes device->host (synchronous). */
+ * pairs of the last decode whose filtered candidate list turned out unusable (a segment
+ * overflowed, or fewer than k keys reached the sampled threshold) and were recomputed
+ * exactly.  Heads of sequences that cannot be filtered at all (a few tokens only, or k too
+ * dense) are recomputed the same way by design and are not counted.  Copies a few bytes
+ * device->host (synchronous). */
 int topk_attn_last_fallbacks(topk_attn_t* h, int* n_heads);
+
+/* Measurement aid for the worst case of the filtered path: when enabled, every head of a decode
+ * that takes the filtered path is treated like a head whose candidate list turned out unusable
+ * (nothing passes its scan; all its keys are rescored exactly and selected from the full score
+ * row).  Results are unchanged; such heads are not counted by topk_attn_last_fallbacks, which
+ * counts lists that should have been usable. */
+int topk_attn_debug_force_redo(topk_attn_t* h, int enable);
 
 /* Measurement aid: when enabled, every decode records a HIP event on its stream just
  * before and just after the key-scan kernel (up to 512 decodes between two reads).

@@ -25,7 +25,7 @@ inline size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
 inline int elem_bytes(int dtype) { return dtype == TOPK_ATTN_F32 ? 4 : 2; }
 
 struct WsLayout {
-    size_t len, thr, bins, samp, seg_cnt, seg_max, flags, hmax, fallback, tailrec, qscale, q8, hist, cand, bnd, scores, sel_idx, sel_val, part_acc, part_l, part_m, total;
+    size_t len, thr, bins, samp, seg_cnt, seg_max, seg_cnt2, flags, hmax, fallback, tailrec, qscale, q8, hist, cand, bnd, scores, sel_idx, sel_val, part_acc, part_l, part_m, total;
     int cand_cap, n_chunk_cap, hist_cap;
 };
 
@@ -95,6 +95,7 @@ WsLayout ws_layout(const topk_attn_config* c) {
     w.samp = take(BH * kSampMax * sizeof(float));
     w.seg_cnt = take(BH * kMaxSeg * sizeof(uint32_t));
     w.seg_max = take(BH * kMaxSeg * sizeof(float));
+    w.seg_cnt2 = take(BH * kMaxSeg * sizeof(uint32_t));
     w.flags = take(BH * sizeof(uint32_t));
     w.hmax = take(BH * sizeof(float));
     w.fallback = take(sizeof(uint32_t));
@@ -219,6 +220,7 @@ struct topk_attn {
     int path;
     bool last_fast;
     bool last_static;           // the last decode used the built-in scratch
+    bool force_redo;            // measurement aid, see topk_attn_debug_force_redo
     char* scratch_dev;          // this device's copy of the built-in scratch
     int n_cu;                   // compute units of the device
     // optional event pairs around the key scan of each decode (measurement only)
@@ -265,6 +267,7 @@ int topk_attn_create(const topk_attn_config* cfg, topk_attn_t** out) {
     if (hipGetDeviceProperties(&prop, cfg->device) != hipSuccess) { delete h; return TOPK_ATTN_EDEVICE; }
     h->n_cu = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
     h->last_static = false;
+    h->force_redo = false;
     {   // cfg->device is current here
         void* p = nullptr;
         const int rc = scratch_address(cfg->device, &p);
@@ -403,6 +406,7 @@ static void fill_call(topk_attn_t* h, int layer, const void* q, int k, int n_que
     s->cand_cap = h->ws.cand_cap; s->n_seg = 4; s->seg_cap = (h->ws.cand_cap / 4) & ~(kCandChunk - 1); s->samp_cap = kSampMax; s->n_chunk_cap = h->ws.n_chunk_cap;
     s->Ncap = c.max_tokens;
     s->indexed = 0;
+    s->force_redo = h->force_redo ? 1 : 0;
     s->cand_est = 0;
     char* const ws_len = static_cast<char*>(c.workspace);
     // everything after the lengths is per-call scratch: the handle's workspace, or the library's own array
@@ -429,6 +433,7 @@ static void fill_call(topk_attn_t* h, int layer, const void* q, int k, int n_que
     b->samp = reinterpret_cast<float*>(ws + h->ws.samp);
     b->seg_cnt = reinterpret_cast<uint32_t*>(ws + h->ws.seg_cnt);
     b->seg_max = reinterpret_cast<float*>(ws + h->ws.seg_max);
+    b->seg_cnt2 = reinterpret_cast<uint32_t*>(ws + h->ws.seg_cnt2);
     b->flags = reinterpret_cast<uint32_t*>(ws + h->ws.flags);
     b->hmax = reinterpret_cast<float*>(ws + h->ws.hmax);
     b->cand = reinterpret_cast<uint64_t*>(ws + h->ws.cand);
@@ -706,6 +711,12 @@ int topk_attn_last_fallbacks(topk_attn_t* h, int* n_heads) {
         hipSuccess)
         return TOPK_ATTN_EDEVICE;
     *n_heads = (int)v;
+    return TOPK_ATTN_OK;
+}
+
+int topk_attn_debug_force_redo(topk_attn_t* h, int enable) {
+    if (!h) return TOPK_ATTN_EINVAL;
+    h->force_redo = enable != 0;
     return TOPK_ATTN_OK;
 }
 

@@ -218,7 +218,6 @@ scan8_kernel(Shape sh, Bufs bf, int tiles_per_wave, float* dst) {
     if (MODE == MODE_SAMPLE) {
         if (N == 0) return;
         Plan pl = make_plan(N, sh.k < N ? sh.k : (int)N, 1);
-        if (!plan_is_fast(pl, N, sh.cand_cap, true)) return;   // not filtered: no threshold needed
         n_items = pl.n_samp;
         stride = pl.stride;
     }

@@ -34,6 +34,7 @@ struct Shape {
     int row_tiles;    // row-tile scan: 16-row tiles per pass over the keys (1 or 2)
     int n_qblk;       // row-tile scan: blocks of 16 * row_tiles (query, head) rows per KV head
     int indexed;      // the scan reads the int8 key index; candidates are re-scored exactly afterwards
+    int force_redo;   // measurement aid: treat every head as not filterable (exact redo of all heads)
     int cand_est;     // candidates per head expected at most (sizes the selection's register cache)
     int k;            // requested k (k_eff = min(k, searched prefix of sequence b))
     int window;       // most recent tokens that are always attended and excluded from the search
@@ -64,7 +65,9 @@ struct Bufs {
     float* samp;            // [B*Hq][samp_cap]
     uint32_t* seg_cnt;      // [B*Hq][n_seg] candidates each scanning wave found (may exceed seg_cap)
     float* seg_max;         // [B*Hq][n_seg] largest score each scanning wave saw (-inf if it saw none)
-    uint32_t* flags;        // [B*Hq] 1 = candidate list unusable, use the full path
+    uint32_t* seg_cnt2;     // [B*Hq][n_seg] lengths of the segments the tail fills again for a head whose list was unusable
+    uint32_t* flags;        // [B*Hq] bit 0: the filter is not expected to work for the head's sequence (not a fallback if it does not);
+                            // bit 1: set by the tail when keys sorted again did not fit their segments; bit 2: ignore a usable list
     float* hmax;            // [B*Hq] largest selected score
     uint64_t* cand;         // [B*Hq][cand_cap] (score bits << 32 | position); entry e of segment g
                             // at [cand_slot(e, g, n_seg)]

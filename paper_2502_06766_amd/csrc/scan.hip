@@ -41,7 +41,6 @@ scan_mfma_kernel(Shape sh, Bufs bf, int tiles_per_wave, float* dst) {
     if (MODE == MODE_SAMPLE) {
         if (N == 0) return;          // nothing to search: the whole sequence is inside the window
         Plan pl = make_plan(N, sh.k < N ? sh.k : (int)N);
-        if (!plan_is_fast(pl, N, sh.cand_cap, true)) return;   // not filtered: no threshold needed
         n_items = pl.n_samp;
         stride = pl.stride;
     }
@@ -229,7 +228,6 @@ scan_rows_kernel(Shape sh, Bufs bf, int tiles_per_wave, float* dst) {
     if (MODE == MODE_SAMPLE) {
         if (N == 0) return;
         Plan pl = make_plan(N, sh.k < N ? sh.k : (int)N);
-        if (!plan_is_fast(pl, N, sh.cand_cap, true)) return;
         n_items = pl.n_samp;
         stride = pl.stride;
     }

@@ -58,12 +58,12 @@ __global__ void __launch_bounds__(NT) threshold_kernel(Shape sh, Bufs bf) {
     // the sample was drawn by the plan of the cache sequence (shared by all its queries)
     const int64_t N = prefix_len(bf.len[cache_seq(sh, b)], sh.window);
     const Plan pl = make_plan(N, sh.k < N ? sh.k : (int)N, sh.indexed);
-    if (!plan_is_fast(pl, N, sh.cand_cap, true)) {
-        // a sequence of the batch that cannot be filtered (a few tokens only, or k too dense for
-        // the candidate list): nothing passes its scan and its heads are redone exactly
-        leave(INFINITY, 1u, 0.f, 0.f);
-        return;
-    }
+    // A sequence of the batch for which the filter is not worth it (a few tokens only, or k so dense that the
+    // candidate list cannot hold what passes) gets its threshold like any other: the scan still counts what
+    // reaches it per bin even where the list overflows, and the tail sorts the keys by those counts.  Its
+    // heads are marked so that they are not reported as fallbacks (bit 0); bit 2 makes the tail ignore a
+    // usable list (measurement aid).
+    const uint32_t mark = (plan_is_fast(pl, N, sh.cand_cap, true) ? 0u : 1u) | (sh.force_redo ? 4u : 0u);
     const int n_samp = pl.n_samp;
     const uint32_t rank = (uint32_t)(pl.rank < n_samp ? pl.rank : n_samp);
     const uint32_t rank_lo = (uint32_t)(pl.rank_lo < (int)rank ? pl.rank_lo : (int)rank);
@@ -146,7 +146,7 @@ __global__ void __launch_bounds__(NT) threshold_kernel(Shape sh, Bufs bf) {
     }
     // (a bin-0 threshold must let -inf samples through when the rank reaches that deep: no finite sample is left out)
     if (b1 == 0 && mn == INFINITY) thr = -INFINITY;
-    leave(thr, 0u, bin_lo, bin_inv);
+    leave(thr, mark, bin_lo, bin_inv);
 }
 
 // Exact selection among the candidates the filtered scan kept, read from the interleaved

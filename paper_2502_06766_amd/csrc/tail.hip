@@ -42,9 +42,34 @@ constexpr int kTailWaves = kTailThreads / kWave;
 constexpr int kTailStage = 128;      // winners a wave stages before it fetches their value rows
 static_assert(kTailWaves == kScanWaves && kTailBins == kWave, "wave w of a tail workgroup takes the segments of wave w of the scan");
 
+// How a head's selection is obtained (uniform over the workgroups of the head):
+//   LIST    from its candidate list (the usual case);
+//   RESCAN  the list is unusable (a segment overflowed) but the scan's per-bin counts, which go on where
+//           the list stops, cover at least k keys: every workgroup scores the keys of its scan
+//           workgroups again, keeps those from the k-th score's bin up in the segments the scan
+//           would have put them in, and sorts them as it would have sorted list entries;
+//   DENSE   neither (fewer than k keys reached the threshold, or too many share the k-th score's bin):
+//           all scores go to the score buffer and the second kernel selects over the full row.
+enum { MODE_LIST = 0, MODE_RESCAN = 1, MODE_DENSE = 2 };
+
+struct HeadSel {          // what a workgroup needs to sort a head's candidates (uniform over the workgroup)
+    int mode, binB;
+    uint32_t above, have, emit_at, bnd_at;   // certain winners, bin-B candidates; this workgroup's first output slots
+    float hmax;
+};
+
+struct TailShared {
+    uint32_t red[3][kTailWaves];
+    uint32_t part[2][kTailWaves][kTailBins];
+    uint32_t sel[6];
+    uint32_t cnt[kTailWaves][2];
+    int32_t st_pos[kTailWaves][kTailStage];
+    float st_w[kTailWaves][kTailStage];
+};
+
 // What the scan left for head bh: candidates in all segments, longest segment, largest score
 // key any scanning wave saw.  All threads of the workgroup call it and get the same values.
-__device__ __forceinline__ void seg_summary(const Shape& sh, const Bufs& bf, int64_t bh, uint32_t (&red)[3][kTailWaves],
+__device__ __forceinline__ void seg_summary(const Shape& sh, const Bufs& bf, int64_t bh, TailShared& sm,
                                             uint32_t& total, uint32_t& max_len, uint32_t& kmx) {
     uint32_t sum = 0, mxl = 0, km = 0;
     for (int g = threadIdx.x; g < sh.n_seg; g += kTailThreads) {
@@ -60,28 +85,62 @@ __device__ __forceinline__ void seg_summary(const Shape& sh, const Bufs& bf, int
         mxl = t > mxl ? t : mxl;
         km = u > km ? u : km;
     }
-    __syncthreads();                 // the scratch may still be read from a previous call
     if (lane_id() == 0) {
         const int w = threadIdx.x >> 6;
-        red[0][w] = sum; red[1][w] = mxl; red[2][w] = km;
+        sm.red[0][w] = sum; sm.red[1][w] = mxl; sm.red[2][w] = km;
     }
     __syncthreads();
     total = 0; max_len = 0; kmx = 0;
 #pragma unroll
     for (int w = 0; w < kTailWaves; ++w) {
-        total += red[0][w];
-        max_len = red[1][w] > max_len ? red[1][w] : max_len;
-        kmx = red[2][w] > kmx ? red[2][w] : kmx;
+        total += sm.red[0][w];
+        max_len = sm.red[1][w] > max_len ? sm.red[1][w] : max_len;
+        kmx = sm.red[2][w] > kmx ? sm.red[2][w] : kmx;
     }
 }
 
-// Is the candidate list of head bh unusable?  (uniform over the workgroup)
-__device__ __forceinline__ bool head_needs_redo(const Shape& sh, const Bufs& bf, int64_t bh, int k_eff,
-                                                uint32_t (&red)[3][kTailWaves], uint32_t& kmx) {
-    if (bf.flags[bh]) { kmx = 0; return true; }          // its sequence was not filtered at all
-    uint32_t total, max_len;
-    seg_summary(sh, bf, bh, red, total, max_len, kmx);
-    return max_len > (uint32_t)sh.seg_cap || total < (uint32_t)k_eff;
+// Everything a workgroup whose first scan workgroup is j0 needs to know of head bh.  `h_all` / `h_before`
+// are this thread's share of the head's per-bin candidate counts (bin tid % 64, a quarter of the scan
+// workgroups; all of them, and those before j0).  All threads call it once and get the same result.
+__device__ __forceinline__ HeadSel analyse_head(const Shape& sh, const Bufs& bf, int64_t bh, int k_eff, uint32_t h_all,
+                                                uint32_t h_before, TailShared& sm) {
+    const int lane = lane_id(), wave = threadIdx.x >> 6;
+    sm.part[0][wave][threadIdx.x & (kTailBins - 1)] = h_all;
+    sm.part[1][wave][threadIdx.x & (kTailBins - 1)] = h_before;
+    if (threadIdx.x == 0) sm.sel[5] = 0u;
+    uint32_t total, max_len, kmx;
+    seg_summary(sh, bf, bh, sm, total, max_len, kmx);      // (its barrier also covers the stores above)
+    if (wave == 0) {
+        // lane l looks at bin kTailBins - 1 - l: prefix sums run from the highest bin down
+        const int bin = kTailBins - 1 - lane;
+        uint32_t all = 0, before = 0;
+#pragma unroll
+        for (int p = 0; p < kTailWaves; ++p) { all += sm.part[0][p][bin]; before += sm.part[1][p][bin]; }
+        uint32_t ia = all, ib = before;
+        for (int o = 1; o < kWave; o <<= 1) {
+            const uint32_t va = __shfl_up(ia, o, kWave), vb = __shfl_up(ib, o, kWave);
+            if (lane >= o) { ia += va; ib += vb; }
+        }
+        const uint32_t run = ia - all;
+        if (run < (uint32_t)k_eff && (uint32_t)k_eff <= ia) {        // at most one lane
+            sm.sel[0] = (uint32_t)bin;           // B: the bin the k-th score falls in
+            sm.sel[1] = run;                     // candidates in higher bins: selected for certain
+            sm.sel[2] = all;                     // candidates in bin B
+            sm.sel[3] = ib - before;             // certain winners of the scan workgroups before j0
+            sm.sel[4] = before;                  // bin-B candidates of the scan workgroups before j0
+            sm.sel[5] = 1u;                      // the counts cover k_eff keys
+        }
+    }
+    __syncthreads();
+    HeadSel hs;
+    hs.binB = (int)sm.sel[0]; hs.above = sm.sel[1]; hs.have = sm.sel[2]; hs.emit_at = sm.sel[3]; hs.bnd_at = sm.sel[4];
+    const bool counted = sm.sel[5] != 0u;
+    hs.hmax = key_score(kmx);
+    const bool list_ok = !(bf.flags[bh] & 4u) && max_len <= (uint32_t)sh.seg_cap && total >= (uint32_t)k_eff;
+    // (the boundary list has room for cand_cap entries, and so does the list the keys are sorted into again)
+    hs.mode = list_ok ? MODE_LIST
+                      : (counted && (uint64_t)hs.above + hs.have <= (uint64_t)sh.cand_cap ? MODE_RESCAN : MODE_DENSE);
+    return hs;
 }
 
 template <int DT, int D>
@@ -92,12 +151,7 @@ __global__ void __launch_bounds__(kTailThreads) tail_gather_kernel(Shape sh, Buf
     constexpr int RPW = kWave / LPR;       // rows a wave fetches per load instruction
     constexpr int U = 4;                   // independent rows in flight per lane group
     constexpr int R = 2;                   // batches of 64 candidates a wave keeps in registers between its two passes
-    __shared__ uint32_t s_red[3][kTailWaves];
-    __shared__ uint32_t s_part[2][kTailWaves][kTailBins];
-    __shared__ uint32_t s_sel[6];
-    __shared__ uint32_t s_cnt[kTailWaves][2];
-    __shared__ int32_t st_pos[kTailWaves][kTailStage];
-    __shared__ float st_w[kTailWaves][kTailStage];
+    __shared__ TailShared sm;
     __shared__ float s_acc[kTailWaves][D + 1];
 
     const int awg = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
@@ -113,8 +167,7 @@ __global__ void __launch_bounds__(kTailThreads) tail_gather_kernel(Shape sh, Buf
     const int j0 = awg * sh.tail_spw;
     const int j1 = j0 + sh.tail_spw < n_wg ? j0 + sh.tail_spw : n_wg;
     const float bin_lo = bf.bins[2 * bh], bin_inv = bf.bins[2 * bh + 1];
-    const uint64_t* list = bf.cand + bh * (int64_t)sh.cand_cap;
-    const uint32_t* scnt = bf.seg_cnt + bh * sh.n_seg;
+    uint64_t* const list = bf.cand + bh * (int64_t)sh.cand_cap;
     uint32_t h_all = 0, h_before = 0;
     {
         const uint32_t* hp = bf.hist + bh * (int64_t)sh.hist_cap * kTailBins;
@@ -128,96 +181,89 @@ __global__ void __launch_bounds__(kTailThreads) tail_gather_kernel(Shape sh, Buf
     }
     // the first candidates of this wave's first segment, before their number is known (any slot of
     // the list may be read; what lies beyond the segment's length is ignored below)
-    const int g_first = j0 * kScanWaves + wave;
     uint64_t saved[R];
+    {
+        const int g_first = j0 * kScanWaves + wave;
 #pragma unroll
-    for (int r = 0; r < R; ++r) {
-        const int64_t slot = cand_slot(r * kWave + lane, g_first, sh.n_seg);
-        saved[r] = list[slot < sh.cand_cap ? slot : 0];
+        for (int r = 0; r < R; ++r) {
+            const int64_t slot = cand_slot(r * kWave + lane, g_first, sh.n_seg);
+            saved[r] = list[slot < sh.cand_cap ? slot : 0];
+        }
     }
-
     const int64_t N = prefix_len(visible_len(sh, bf, b), sh.window);
     const int k_eff = sh.k < N ? sh.k : (int)N;
     if (k_eff == 0) {                      // nothing to search for this sequence
         if (awg == 0 && tid == 0) *rec = TailRec{TAIL_EMPTY, 0u, 0u, 0u};
         return;
     }
-    uint32_t kmx;
-    if (head_needs_redo(sh, bf, bh, k_eff, s_red, kmx)) {
-        if (awg == 0 && tid == 0) {
-            *rec = TailRec{TAIL_REDO, 0u, 0u, 0u};
-            if (!bf.flags[bh]) atomicAdd(bf.fallback_total, 1u);     // a list that should have been usable
-        }
-        // Exact scores of every key for the heads of this group that need them, computed once: by the
-        // workgroups of the lowest such head among the (up to four) heads that share an operand block.
-        const int r_full = h % sh.G, sub0 = r_full & ~3, r_me = r_full - sub0;
-        const int Gs = sh.G - sub0 < 4 ? sh.G - sub0 : 4;
-        const int64_t head0 = bh - r_me;
-        uint32_t mask = 0;
-        for (int r = 0; r < Gs; ++r) {
-            uint32_t dummy;
-            if (r == r_me || head_needs_redo(sh, bf, head0 + r, k_eff, s_red, dummy)) mask |= 1u << r;
-        }
-        if ((mask & ((1u << r_me) - 1u)) != 0u) return;              // a lower head of the group leads
-        v8 qa[D / 32];
-        load_query_a<DT, D>(bf.q, head0, Gs, qa);
-        const int kvh = h / sh.G;
-        const char* Kh = static_cast<const char*>(bf.K) + ((int64_t)cache_seq(sh, b) * sh.Hkv + kvh) * sh.Ncap * (D * 2);
-        // 16 keys per step (one MFMA column block; a quarter of the scan's tile keeps this rarely used
-        // branch from setting the register budget of the kernel): lane (j, n) loads the chunks 4 s + j of
-        // key n, every group of four accumulator rows holds the heads of the block for key n
-        const int jj = lane >> 4, n = lane & 15;
-        const int64_t n_blk = (N + 15) / 16;
-        for (int64_t blk = (int64_t)awg * kTailWaves + wave; blk < n_blk; blk += (int64_t)gridDim.x * kTailWaves) {
-            const int64_t key = blk * 16 + n;
-            const v8* p = reinterpret_cast<const v8*>(Kh + (key < N ? key : N - 1) * (D * 2)) + jj;
-            v8 kb[D / 32];
-#pragma unroll
-            for (int s = 0; s < D / 32; ++s) kb[s] = p[4 * s];
-            f32x4 acc4 = f32x4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-            for (int s = 0; s < D / 32; ++s) acc4 = Mfma<DT>::mac(qa[s], kb[s], acc4);
-            if (jj == 0 && key < N) {
-#pragma unroll
-                for (int r = 0; r < 4; ++r)
-                    if (mask & (1u << r)) bf.scores[(head0 + r) * sh.Ncap + key] = acc4[r];
-            }
-        }
-        return;
+    const HeadSel hs = analyse_head(sh, bf, bh, k_eff, h_all, h_before, sm);
+    if (awg == 0 && tid == 0) {
+        const bool dense = hs.mode == MODE_DENSE;
+        rec->state = dense ? (uint32_t)TAIL_REDO : (uint32_t)TAIL_NORMAL;
+        rec->above = dense ? 0u : hs.above;
+        rec->need = dense ? 0u : (uint32_t)k_eff - hs.above;
+        rec->have = dense ? 0u : hs.have;
+        bf.hmax[bh] = hs.hmax;
+        if (hs.mode != MODE_LIST && !(bf.flags[bh] & 5u)) atomicAdd(bf.fallback_total, 1u);   // a list that should have been usable
     }
 
-    // ---- the bin of the k-th score and this workgroup's output offsets, from the scan's counts
-    s_part[0][tid >> 6][tid & (kTailBins - 1)] = h_all;
-    s_part[1][tid >> 6][tid & (kTailBins - 1)] = h_before;
-    __syncthreads();
-    if (wave == 0) {
-        // lane l looks at bin kTailBins - 1 - l: prefix sums run from the highest bin down
-        const int bin = kTailBins - 1 - lane;
-        uint32_t all = 0, before = 0;
+    const uint32_t* scnt = bf.seg_cnt + bh * sh.n_seg;
+    if (hs.mode != MODE_LIST) {
+        // ---- The list is unusable: the keys of my scan workgroups' tiles are scored again with the scan's
+        // own arithmetic, 16 keys at a time (a quarter of the scan's tile keeps this rarely used branch from
+        // setting the register budget of the kernel): lane (jj, n) loads the chunks 4 s + jj of key n, and
+        // every group of four accumulator rows holds the scores of key n for the heads of the operand block.
+        // DENSE: every score goes to the score buffer.  RESCAN: keys from bin B up go to the head's candidate
+        // list again, into the segment the scan would have put them in; the segments' new lengths are kept
+        // apart from the scan's (other workgroups may still be judging the head by those).
+        const int r_full = h % sh.G, sub0 = r_full & ~3, r_me = r_full - sub0;
+        const int Gs = sh.G - sub0 < 4 ? sh.G - sub0 : 4;
+        v8 qa[D / 32];
+        load_query_a<DT, D>(bf.q, bh - r_me, Gs, qa);
+        const char* Kh = static_cast<const char*>(bf.K) + ((int64_t)cache_seq(sh, b) * sh.Hkv + h / sh.G) * sh.Ncap * (D * 2);
+        const int jj = lane >> 4, n = lane & 15;
+        const bool rescan = hs.mode == MODE_RESCAN;
+        const int64_t n_tiles = (N + 63) / 64;
+        for (int j = j0; j < j1; ++j) {
+            const int sid = j * kScanWaves + wave;
+            uint32_t cnt = 0;                                           // entries written to segment sid (uniform over the wave)
+            for (int64_t tile = sid; tile < n_tiles; tile += sh.n_seg) {
 #pragma unroll
-        for (int p = 0; p < kTailWaves; ++p) { all += s_part[0][p][bin]; before += s_part[1][p][bin]; }
-        uint32_t ia = all, ib = before;
-        for (int o = 1; o < kWave; o <<= 1) {
-            const uint32_t va = __shfl_up(ia, o, kWave), vb = __shfl_up(ib, o, kWave);
-            if (lane >= o) { ia += va; ib += vb; }
+                for (int sub = 0; sub < 4; ++sub) {
+                    const int64_t key = tile * 64 + sub * 16 + n;
+                    const v8* p = reinterpret_cast<const v8*>(Kh + (key < N ? key : N - 1) * (D * 2)) + jj;
+                    v8 kb[D / 32];
+#pragma unroll
+                    for (int s = 0; s < D / 32; ++s) kb[s] = p[4 * s];
+                    f32x4 acc4 = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                    for (int s = 0; s < D / 32; ++s) acc4 = Mfma<DT>::mac(qa[s], kb[s], acc4);
+                    const float sc = (r_me == 0 ? acc4[0] : r_me == 1 ? acc4[1] : r_me == 2 ? acc4[2] : acc4[3]) + 0.0f;
+                    const bool mine = jj == 0 && key < N;               // every lane group holds the same scores: the first one writes
+                    if (mine && !rescan) bf.scores[bh * sh.Ncap + key] = sc;
+                    const bool keep = mine && rescan && tail_bin(sc, bin_lo, bin_inv) >= hs.binB;
+                    const uint64_t m = __ballot(keep);
+                    if (keep) {
+                        const uint32_t e = cnt + (uint32_t)mask_rank(m);
+                        if (e < (uint32_t)sh.seg_cap)
+                            list[cand_slot(e, sid, sh.n_seg)] = ((uint64_t)__float_as_uint(sc) << 32) | (uint64_t)(uint32_t)key;
+                    }
+                    cnt += (uint32_t)__popcll(m);
+                }
+            }
+            if (lane == 0 && rescan) {
+                bf.seg_cnt2[bh * sh.n_seg + sid] = cnt < (uint32_t)sh.seg_cap ? cnt : (uint32_t)sh.seg_cap;
+                if (cnt > (uint32_t)sh.seg_cap) atomicOr(&bf.flags[bh], 2u);           // does not fit: the second kernel selects densely
+            }
         }
-        const uint32_t run = ia - all;
-        if (run < (uint32_t)k_eff && (uint32_t)k_eff <= ia) {        // exactly one lane: total >= k_eff
-            s_sel[0] = (uint32_t)bin;            // B: the bin the k-th score falls in
-            s_sel[1] = run;                      // candidates in higher bins: selected for certain
-            s_sel[2] = all;                      // candidates in bin B
-            s_sel[3] = ib - before;              // certain winners of the scan workgroups before mine
-            s_sel[4] = before;                   // bin-B candidates of the scan workgroups before mine
-        }
+        if (!rescan) return;
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+        __syncthreads();                      // the segments written above are read below by other lanes; a line of the
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");   // old list may sit in this compute unit's cache (it was read early on)
+        scnt = bf.seg_cnt2 + bh * sh.n_seg;
+        saved[0] = saved[1] = 0ull;           // (not carried through this branch: nothing is cached for a list written again)
     }
-    __syncthreads();
-    const int binB = (int)s_sel[0];
-    const uint32_t above = s_sel[1], have = s_sel[2];
-    const float hmax = key_score(kmx);
-    if (awg == 0 && tid == 0) {
-        *rec = TailRec{TAIL_NORMAL, above, (uint32_t)k_eff - above, have};
-        bf.hmax[bh] = hmax;
-    }
+    const bool cached = hs.mode == MODE_LIST;     // the first R batches of this wave's first segment are in saved[]
 
     // ---- first pass over my candidates: how many certain winners / bin-B candidates each wave has.
     // Wave w takes segment 4 j + w of every scan workgroup j of mine, 64 candidates at a time; the
@@ -231,23 +277,23 @@ __global__ void __launch_bounds__(kTailThreads) tail_gather_kernel(Shape sh, Buf
             for (uint32_t e0 = 0; e0 < cnt; e0 += kWave, ++bi) {
                 const uint32_t e = e0 + lane;
                 uint64_t ent;
-                if (j == j0 && bi < R) ent = bi == 0 ? saved[0] : saved[1];
+                if (cached && j == j0 && bi < R) ent = bi == 0 ? saved[0] : saved[1];
                 else {
                     ent = list[cand_slot(e < cnt ? e : 0, g, sh.n_seg)];
                     if (bi < R) { if (bi == 0) saved[0] = ent; else saved[1] = ent; }
                 }
                 const int bin = tail_bin(__uint_as_float((uint32_t)(ent >> 32)), bin_lo, bin_inv);
-                nw += (e < cnt && bin > binB) ? 1u : 0u;
-                nb += (e < cnt && bin == binB) ? 1u : 0u;
+                nw += (e < cnt && bin > hs.binB) ? 1u : 0u;
+                nb += (e < cnt && bin == hs.binB) ? 1u : 0u;
             }
         }
     }
     static_assert(R == 2, "the register cache of candidate batches is written out for two batches");
     for (int o = 32; o > 0; o >>= 1) { nw += __shfl_xor(nw, o, kWave); nb += __shfl_xor(nb, o, kWave); }
-    if (lane == 0) { s_cnt[wave][0] = nw; s_cnt[wave][1] = nb; }
+    if (lane == 0) { sm.cnt[wave][0] = nw; sm.cnt[wave][1] = nb; }
     __syncthreads();
-    uint32_t emit_at = s_sel[3], bnd_at = s_sel[4];
-    for (int w = 0; w < wave; ++w) { emit_at += s_cnt[w][0]; bnd_at += s_cnt[w][1]; }
+    uint32_t emit_at = hs.emit_at, bnd_at = hs.bnd_at;
+    for (int w = 0; w < wave; ++w) { emit_at += sm.cnt[w][0]; bnd_at += sm.cnt[w][1]; }
 
     // ---- second pass: write winners and boundary candidates, fetch the winners' value rows
     int32_t* idx = bf.sel_idx + bh * sh.k;
@@ -270,8 +316,8 @@ __global__ void __launch_bounds__(kTailThreads) tail_gather_kernel(Shape sh, Buf
             for (int u = 0; u < U; ++u) {
                 const int r = r0 + u * RPW + rs;
                 const bool ok = r < n_st;
-                const int64_t pos = st_pos[wave][ok ? r : 0];
-                w[u] = ok ? st_w[wave][r] : 0.f;
+                const int64_t pos = sm.st_pos[wave][ok ? r : 0];
+                w[u] = ok ? sm.st_w[wave][r] : 0.f;
                 raw[u] = *reinterpret_cast<const u32x4*>(Vh + (pos * D + c * EPL) * 2);
             }
 #pragma unroll
@@ -299,18 +345,18 @@ __global__ void __launch_bounds__(kTailThreads) tail_gather_kernel(Shape sh, Buf
                 else ent = list[cand_slot(valid ? e : 0, g, sh.n_seg)];
                 const float sc = __uint_as_float((uint32_t)(ent >> 32));
                 const int bin = tail_bin(sc, bin_lo, bin_inv);
-                const bool win = valid && bin > binB, edge = valid && bin == binB;
+                const bool win = valid && bin > hs.binB, edge = valid && bin == hs.binB;
                 const uint64_t mw = __ballot(win), me = __ballot(edge);
                 if (n_st > kTailStage - kWave) fetch_staged();
                 if (win) {
                     const int r = mask_rank(mw);
                     const uint32_t o = emit_at + (uint32_t)r;
-                    if (o < (uint32_t)k_eff) {            // always true; guards the output buffers
+                    if (o < (uint32_t)k_eff) {            // always true for a consistent list; guards the output buffers
                         idx[o] = (int32_t)(uint32_t)ent;
                         vals[o] = sc;
                     }
-                    st_pos[wave][n_st + r] = (int32_t)(uint32_t)ent;
-                    st_w[wave][n_st + r] = exp2f((sc - hmax) * scale_log2e);
+                    sm.st_pos[wave][n_st + r] = (int32_t)(uint32_t)ent;
+                    sm.st_w[wave][n_st + r] = exp2f((sc - hs.hmax) * scale_log2e);
                 }
                 if (edge) {
                     const uint32_t o = bnd_at + (uint32_t)mask_rank(me);
@@ -341,7 +387,7 @@ __global__ void __launch_bounds__(kTailThreads) tail_gather_kernel(Shape sh, Buf
     for (int t = tid; t < D; t += kTailThreads) pacc[t] = (s_acc[0][t] + s_acc[1][t]) + (s_acc[2][t] + s_acc[3][t]);
     if (tid == 0) {
         bf.part_l[bh * sh.n_chunk_cap + awg] = (s_acc[0][D] + s_acc[1][D]) + (s_acc[2][D] + s_acc[3][D]);
-        bf.part_m[bh * sh.n_chunk_cap + awg] = hmax;
+        bf.part_m[bh * sh.n_chunk_cap + awg] = hs.hmax;
     }
 }
 
@@ -401,8 +447,14 @@ __global__ void __launch_bounds__(NT) tail_finish_kernel(Shape sh, Bufs bf, floa
     const int D = sh.D;
     const int64_t N = prefix_len(visible_len(sh, bf, b), sh.window);
     const int k_eff = sh.k < N ? sh.k : (int)N;
-    const TailRec rec = reinterpret_cast<const TailRec*>(bf.tailrec)[bh];
+    TailRec rec = reinterpret_cast<const TailRec*>(bf.tailrec)[bh];
+    if (bf.flags[bh] & 2u) rec.state = TAIL_REDO;     // the keys sorted again did not fit their segments
     float hmax = bf.hmax[bh];                 // the first kernel's, unless the head is redone
+    // the first boundary candidates are asked for before their number is known (any slot of the
+    // list may be read; what lies beyond `have` is ignored below)
+    uint64_t ent[CIMAX];
+#pragma unroll
+    for (int i = 0; i < CIMAX; ++i) ent[i] = (i * NT + tid < sh.cand_cap) ? bf.bnd[bh * (int64_t)sh.cand_cap + i * NT + tid] : 0ull;
     int32_t* idx = bf.sel_idx + bh * sh.k;
     float* vals = bf.sel_val + bh * sh.k;
     if (rec.state == TAIL_EMPTY || k_eff == 0) {
@@ -482,13 +534,11 @@ __global__ void __launch_bounds__(NT) tail_finish_kernel(Shape sh, Bufs bf, floa
         // The usual case, a few hundred boundary candidates: each is ranked against all others by its
         // composite key (score key, then inverted position: larger beats smaller, equal scores go to
         // the lower position, no two keys are equal), and the `need` best are the missing winners.
-        const uint64_t* bnd = bf.bnd + bh * (int64_t)sh.cand_cap;
         const int have = (int)rec.have, need = (int)rec.need;
-        uint64_t mine[CIMAX], ent[CIMAX];
+        uint64_t mine[CIMAX];
 #pragma unroll
         for (int i = 0; i < CIMAX; ++i) {
             const int s = i * NT + tid;
-            ent[i] = s < have ? bnd[s] : 0ull;
             mine[i] = s < have ? ((uint64_t)score_key(__uint_as_float((uint32_t)(ent[i] >> 32))) << 32) |
                                      (uint64_t)(0xFFFFFFFFu - (uint32_t)ent[i])
                                : ~0ull;                                   // nothing beats an empty slot's key

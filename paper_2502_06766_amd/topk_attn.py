@@ -22,7 +22,7 @@ INDEX_NONE, INDEX_INT8 = 0, 1
 EXPORTS = [
     "topk_attn_kv_bytes", "topk_attn_workspace_bytes", "topk_attn_create", "topk_attn_append_kv", "topk_attn_append_step",
     "topk_attn_decode", "topk_attn_decode_static", "topk_attn_decode_window", "topk_attn_decode_multi", "topk_attn_decode_layers", "topk_attn_k_schedule", "topk_attn_scores", "topk_attn_length", "topk_attn_reset", "topk_attn_set_path",
-    "topk_attn_last_fallbacks", "topk_attn_set_scan_timing", "topk_attn_scan_time", "topk_attn_read_probe", "topk_attn_build_id", "topk_attn_strerror", "topk_attn_destroy",
+    "topk_attn_last_fallbacks", "topk_attn_debug_force_redo", "topk_attn_set_scan_timing", "topk_attn_scan_time", "topk_attn_read_probe", "topk_attn_build_id", "topk_attn_strerror", "topk_attn_destroy",
 ]
 
 
@@ -98,6 +98,8 @@ def lib() -> ctypes.CDLL:
         L.topk_attn_set_path.restype = i32
         L.topk_attn_last_fallbacks.argtypes = [vp, ctypes.POINTER(i32)]
         L.topk_attn_last_fallbacks.restype = i32
+        L.topk_attn_debug_force_redo.argtypes = [vp, i32]
+        L.topk_attn_debug_force_redo.restype = i32
         L.topk_attn_set_scan_timing.argtypes = [vp, i32]
         L.topk_attn_set_scan_timing.restype = i32
         L.topk_attn_scan_time.argtypes = [vp, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(i32)]
@@ -225,6 +227,10 @@ def topk_attn_last_fallbacks(h) -> int:
     n = ctypes.c_int(0)
     _check(lib().topk_attn_last_fallbacks(h, ctypes.byref(n)), "topk_attn_last_fallbacks")
     return n.value
+
+
+def topk_attn_debug_force_redo(h, enable: bool):
+    _check(lib().topk_attn_debug_force_redo(h, 1 if enable else 0), "topk_attn_debug_force_redo")
 
 
 def topk_attn_set_scan_timing(h, enable: bool):

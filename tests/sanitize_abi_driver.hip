@@ -132,6 +132,7 @@ int main() {
     CHECK(topk_attn_scores(nullptr, 0, &f, &f, nullptr) == TOPK_ATTN_EINVAL);
     CHECK(topk_attn_last_fallbacks(nullptr, &n) == TOPK_ATTN_EINVAL);
     CHECK(topk_attn_set_scan_timing(nullptr, 1) == TOPK_ATTN_EINVAL);
+    CHECK(topk_attn_debug_force_redo(nullptr, 1) == TOPK_ATTN_EINVAL);
     CHECK(topk_attn_scan_time(nullptr, &ms, &n) == TOPK_ATTN_EINVAL);
     CHECK(topk_attn_read_probe(nullptr, 16, nullptr, nullptr) == TOPK_ATTN_EINVAL);
     CHECK(topk_attn_destroy(nullptr) == TOPK_ATTN_EINVAL);

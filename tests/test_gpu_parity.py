@@ -170,6 +170,51 @@ def test_all_keys_identical(N, redone):
     assert fb == (Hq if redone else 0)
 
 
+def test_every_head_redone_exactly_matches_the_oracle():
+    """The worst case of the filtered path, forced: every head is treated as not filterable, all keys
+    are rescored by the tail's workgroups (once per group of heads that share them) and selected from
+    the full score row.  Same bars as the normal path."""
+    dtype, Hq, Hkv, N, d, k = wl.BF16, 8, 2, 70001, 128, 900
+    q, K, V = rand_case(Hq, Hkv, N, d, dtype, k, seed=4711)
+    ref = c_oracle.topk_attention(q, K, V, dtype, k)
+    cache = ta.TopkAttnCache(1, 1, Hq, Hkv, d, N, k, dtype)
+    try:
+        cache.append(0, 0, H.to_torch(K, dtype, DEV), H.to_torch(V, dtype, DEV), head_major=True)
+        qd = H.to_torch(q, dtype, DEV)[None].contiguous()
+        ta.topk_attn_debug_force_redo(cache.h, True)
+        out, idx, vals, lse = cache.decode(0, qd, k)
+        torch.cuda.synchronize()
+        assert cache.last_fallbacks() == 0          # forced, not counted
+        H.check_against_oracle(out[0].cpu().numpy(), idx[0].cpu().numpy(), vals[0].cpu().numpy(), lse[0].cpu().numpy(),
+                               ref, H.score_margin(q, K, dtype), k, 2e-3, float(np.abs(wl.widen(V, dtype)).max()),
+                               "forced redo")
+        ta.topk_attn_debug_force_redo(cache.h, False)
+        out2, idx2, _, _ = cache.decode(0, qd, k)
+        torch.cuda.synchronize()
+        assert torch.equal(torch.sort(idx2, dim=2).values, torch.sort(idx, dim=2).values)
+        np.testing.assert_allclose(out2.cpu().numpy(), out.cpu().numpy(), rtol=2e-5, atol=1e-6)
+    finally:
+        cache.close()
+
+
+def test_one_head_of_a_group_overflows_and_is_redone():
+    """Every key scores the same for head 0 (one constant channel, a query that reads only it), so all keys
+    reach its threshold, its candidate segments overflow and it alone is redone exactly (ties go to the
+    lowest positions); the other three heads of the group keep their candidate lists."""
+    g = np.random.default_rng(99)
+    dtype, Hq, Hkv, N, d, k = wl.F16, 4, 1, 120000, 128, 500
+    K = g.standard_normal((Hkv, N, d)).astype(np.float32)
+    K[:, :, 0] = 1.5
+    q = g.standard_normal((Hq, d)).astype(np.float32)
+    q[0] = 0.0
+    q[0, 0] = 2.0
+    V = g.standard_normal((Hkv, N, d)).astype(np.float32)
+    q, K, V = (wl.quantize(a, dtype) for a in (q, K, V))
+    Kn, _, _ = H.enforce_margin(np.ascontiguousarray(q[1:]), K, dtype, k)      # margins for heads 1..3 (seen as a group of 3)
+    fb = run_case(q, Kn, V, dtype, k, path=ta.PATH_FILTER, label="one head overflows")
+    assert fb == 1
+
+
 # ------------------------------------------------------------------ debug score dump
 @pytest.mark.parametrize("dtype,G,d", [(wl.F16, 4, 128), (wl.BF16, 2, 64), (wl.F32, 4, 64), (wl.F16, 8, 128)])
 def test_scores_within_fp32_bound(dtype, G, d):
