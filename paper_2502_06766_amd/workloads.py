@@ -39,7 +39,7 @@ class Workload:
     n_tokens: int
     k: int
     dtype: int
-    recipe: str          # "planted_sum" | "planted_cos" | "score_shaped"
+    recipe: str          # "planted_sum" | "planted_cos" | "score_shaped" | "clustered"
     n_planted: int = 0   # per query head (planted_cos) or in total (planted_sum)
     n_outlier_channels: int = 0
 
@@ -66,6 +66,9 @@ C4 = Workload("c4_batched16_256k_bf16", 4, 1, 16, 32, 8, 128, 262144, 1024, BF16
               "planted_cos", n_planted=64, n_outlier_channels=4)
 C5 = Workload("c5_32layer_512k_fp16", 5, 32, 1, 32, 8, 128, 524288, 8192, F16,
               "score_shaped")
+# Not one of the five: a cache with the structure that lets a coarse index rule out whole pages (see
+# make_clustered), for the sub-linear search.
+C6 = Workload("c6_clustered_1m_fp16", 6, 1, 1, 32, 8, 128, 1048576, 16384, F16, "clustered")
 CONFIGS = {w.config_id: w for w in (C1, C2, C3, C4, C5)}
 C4_K_SWEEP = (256, 1024, 4096)
 
@@ -179,12 +182,69 @@ def _fill_head_score_shaped(w, seed, layer, seq, h_kv, q, K, V):
         K[h_kv][s:e] = (t @ Qp.T + n @ P.T).astype(np.float32)
 
 
+# c6: topical runs.  Every KV head draws N_CENTROIDS centroids ~ N(0, 1); the sequence is a chain of runs of
+# CLUSTER_RUN[0] .. CLUSTER_RUN[1] consecutive tokens, each run around one centroid (picked at random), its
+# keys the centroid plus N(0, sigma^2) noise.  A query head is Gaussian plus CLUSTER_PULL times the sum of
+# CLUSTER_HOT centroids of its KV head, so the keys it attends to sit in the runs of a few centroids, while
+# the other runs score like unrelated text.  `sigma` is how tight a run is: the page index can rule a page
+# out only if its keys are close together.
+N_CENTROIDS = 256
+CLUSTER_RUN = (128, 2048)
+CLUSTER_HOT = 3
+CLUSTER_PULL = 0.25
+CLUSTER_SIGMA = 0.05
+
+
+def _cluster_rng(w, seed, layer, seq, h_kv):
+    return _rng(seed, w.config_id, layer * w.n_seqs + seq, 0x10000 + h_kv)
+
+
+def _cluster_centroids(w, seed, layer, seq, h_kv):
+    g = _rng(seed, w.config_id, layer * w.n_seqs + seq, 0x20000 + h_kv)
+    return g.standard_normal((N_CENTROIDS, w.head_dim), dtype=np.float32)
+
+
+def _fill_head_clustered(w, seed, layer, seq, h_kv, q, K, V, sigma):
+    g = _cluster_rng(w, seed, layer, seq, h_kv)
+    N, d = w.n_tokens, w.head_dim
+    C = _cluster_centroids(w, seed, layer, seq, h_kv)
+    g.standard_normal(out=K[h_kv], dtype=np.float32)
+    g.standard_normal(out=V[h_kv], dtype=np.float32)
+    K[h_kv] *= np.float32(sigma)
+    pos = 0
+    while pos < N:
+        run = int(g.integers(CLUSTER_RUN[0], CLUSTER_RUN[1] + 1))
+        K[h_kv][pos:pos + run] += C[int(g.integers(N_CENTROIDS))]
+        pos += run
+
+
+def make_clustered(w: Workload, seed: int, sigma: float = CLUSTER_SIGMA, layer: int = 0, seq: int = 0, threads: int = 8):
+    """(q, K, V) float32 of the clustered recipe (see above), before rounding to the storage dtype."""
+    N, d, G = w.n_tokens, w.head_dim, w.group
+    K = np.empty((w.n_kv_heads, N, d), dtype=np.float32)
+    V = np.empty((w.n_kv_heads, N, d), dtype=np.float32)
+    q = make_query(w, seed, layer, seq)
+    for h in range(w.n_q_heads):
+        gq = _rng(seed, w.config_id, layer * w.n_seqs + seq, 0x30000 + h)
+        hot = gq.choice(N_CENTROIDS, size=CLUSTER_HOT, replace=False)
+        q[h] += np.float32(CLUSTER_PULL) * _cluster_centroids(w, seed, layer, seq, h // G)[hot].sum(axis=0)
+    if threads > 1 and w.n_kv_heads > 1 and N * d >= (1 << 22):
+        with ThreadPoolExecutor(max_workers=min(threads, w.n_kv_heads)) as ex:
+            list(ex.map(lambda h: _fill_head_clustered(w, seed, layer, seq, h, q, K, V, sigma), range(w.n_kv_heads)))
+    else:
+        for h in range(w.n_kv_heads):
+            _fill_head_clustered(w, seed, layer, seq, h, q, K, V, sigma)
+    return q, K, V
+
+
 def make_cache(w: Workload, seed: int, layer: int = 0, seq: int = 0, threads: int = 8):
     """Returns (q [Hq,d], K [Hkv,N,d], V [Hkv,N,d]) as float32, before rounding
     to the storage dtype."""
     N, d = w.n_tokens, w.head_dim
     K = np.empty((w.n_kv_heads, N, d), dtype=np.float32)
     V = np.empty((w.n_kv_heads, N, d), dtype=np.float32)
+    if w.recipe == "clustered":
+        return make_clustered(w, seed, CLUSTER_SIGMA, layer, seq, threads)
     if w.recipe == "planted_sum":
         assert w.n_q_heads == 1 and w.n_kv_heads == 1
         g = _rng(seed, w.config_id, layer * w.n_seqs + seq, 0)

@@ -624,3 +624,100 @@ def test_k_schedule_is_monotone_in_the_ratio():
     # ratio r and 1/r mirror each other (up to which side of a tie is rounded up)
     a, b = ref.k_schedule(64000, 16, 4.0), ref.k_schedule(64000, 16, 0.25)
     assert max(abs(x - y) for x, y in zip(a, b[::-1])) <= 1
+
+
+# ---------------------------------------------------------------- coarse page index (sub-linear search)
+from oracle import page_index_ref as pg
+
+
+def _pages_case(seed, Hq=4, Hkv=2, N=300, d=16, page=16):
+    g = np.random.default_rng(seed)
+    q = g.standard_normal((Hq, d))
+    K = g.standard_normal((Hkv, N, d)) * g.uniform(0.2, 3.0, (Hkv, N, 1))
+    return q, K, page
+
+
+def test_page_bound_is_never_below_a_key_of_the_page():
+    q, K, page = _pages_case(1)
+    c, r = pg.page_balls(K, page)
+    ub = pg.page_upper_bound(q, c, r)
+    S = ref.scores(q, K)
+    N = K.shape[1]
+    for h in range(q.shape[0]):
+        per_key = np.repeat(ub[h], page)[:N]
+        assert (S[h] <= per_key + 1e-9).all()
+    assert (pg.ball_slack(K, page, c, r) >= -1e-12).all() and np.abs(pg.ball_slack(K, page, c, r)).min() < 1e-12
+    assert c.shape == (2, 19, 16) and r.shape == (2, 19)        # 300 tokens: 18 full pages and one of 12
+
+
+def test_page_bound_is_attained_on_the_sphere_and_is_what_a_minimiser_finds():
+    """max of q . x over the ball |x - c| <= r: closed form q . c + |q| r, reached at x = c + r q / |q|; a
+    library constrained minimiser (SLSQP on -q . x) finds the same value."""
+    from scipy.optimize import minimize
+    g = np.random.default_rng(2)
+    d = 6
+    for _ in range(5):
+        q, c, r = g.standard_normal(d), g.standard_normal(d), float(g.uniform(0.1, 2.0))
+        ub = pg.page_upper_bound(q[None], c[None, None], np.array([[r]]))[0, 0]
+        x_star = c + r * q / np.linalg.norm(q)
+        assert abs(q @ x_star - ub) < 1e-12
+        res = minimize(lambda x: -(q @ x), c, constraints=[{"type": "ineq", "fun": lambda x: r * r - (x - c) @ (x - c)}],
+                       method="SLSQP", options={"ftol": 1e-12, "maxiter": 500})
+        assert abs(-res.fun - ub) < 1e-5
+    # a key placed on that point makes the bound tight for its page
+    K = np.stack([c + 0.1 * g.standard_normal(d) for _ in range(7)] )[None]
+    cc, rr = pg.page_balls(K, 8)
+    far = cc[0, 0] + rr[0, 0] * q / np.linalg.norm(q)
+    assert abs(pg.page_upper_bound(q[None], cc, rr)[0, 0] - q @ far) < 1e-12
+
+
+def test_page_bound_special_cases():
+    g = np.random.default_rng(3)
+    q = g.standard_normal((2, 8))
+    row = g.standard_normal(8)
+    K = np.tile(row, (1, 32, 1))                              # identical keys: radius 0, bound = the score
+    c, r = pg.page_balls(K, 8)
+    assert np.abs(r).max() < 1e-12
+    np.testing.assert_allclose(pg.page_upper_bound(q, c, r), np.tile((q @ row)[:, None], (1, 4)), rtol=1e-12)
+    # two keys: the centre is their midpoint, the radius half their distance
+    K2 = np.stack([row, row + 2.0])[None]
+    c2, r2 = pg.page_balls(K2, 2)
+    np.testing.assert_allclose(c2[0, 0], row + 1.0)
+    assert abs(r2[0, 0] - np.sqrt(8.0)) < 1e-12
+    # linear in beta between the centre's score and the full bound
+    q3, K3, page = _pages_case(4)
+    c3, r3 = pg.page_balls(K3, page)
+    b0, b1, bh = (pg.page_upper_bound(q3, c3, r3, b) for b in (0.0, 1.0, 0.5))
+    np.testing.assert_allclose(bh, 0.5 * (b0 + b1), rtol=1e-12)
+    np.testing.assert_allclose(b0[1], c3[0] @ q3[1], rtol=1e-12)     # head 1 reads KV head 0 (G = 2)
+    np.testing.assert_allclose(b0[2], c3[1] @ q3[2], rtol=1e-12)     # head 2 reads KV head 1
+    assert (b1 >= b0).all()
+
+
+def test_pages_an_exact_search_must_read_and_restricted_search():
+    q, K, page = _pages_case(5, N=257)
+    S = ref.scores(q, K)
+    k, G = 20, 2
+    c, r = pg.page_balls(K, page)
+    ub = pg.page_upper_bound(q, c, r)
+    idx = np.stack([ref.select_topk(S[h], k)[0] for h in range(4)])
+    need = pg.pages_holding_topk(idx, c.shape[1], page, G)
+    # brute force: a page is needed iff removing it changes some head's selection
+    for g_ in range(2):
+        for p in range(c.shape[1]):
+            hit = any(((idx[h] // page) == p).any() for h in (2 * g_, 2 * g_ + 1))
+            assert need[g_, p] == hit
+    s_k = np.array([np.sort(S[h])[::-1][k - 1] for h in range(4)])
+    for level in (s_k, s_k - 0.5, np.full(4, -np.inf)):
+        keep = pg.pages_above(ub, level, G)
+        assert (keep | ~need).all()                           # every needed page is kept at a cut-off <= the k-th score
+        got = pg.search_in_pages(S, keep, k, page, G)
+        for h in range(4):
+            np.testing.assert_array_equal(got[h], idx[h])     # and the restricted search is the exact one
+    assert pg.pages_above(ub, np.full(4, -np.inf), G).all()
+    # a cut-off above the k-th score may lose keys: then the restricted search differs (the approximate regime)
+    keep_hi = pg.pages_above(ub, ub.max(axis=1) - 1e-9, G)   # only each head's best-looking page survives
+    assert keep_hi.sum() <= 4 and not (keep_hi | ~need).all()
+    # pages_above takes the union over the heads of a group
+    solo = ub >= s_k[:, None]
+    np.testing.assert_array_equal(pg.pages_above(ub, s_k, G), solo[0::2] | solo[1::2])

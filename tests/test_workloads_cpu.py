@@ -116,3 +116,29 @@ def test_bf16_rounds_to_nearest_even():
     x = np.array([1.0 + 2.0 ** -8, 1.0 + 3 * 2.0 ** -8, 1.0 + 2.0 ** -8 + 2.0 ** -20], dtype=np.float32)
     got = wl.bf16_bits_to_f32(wl.to_bf16_bits(x))
     assert got.tolist() == [1.0, 1.0 + 2.0 ** -6, 1.0 + 2.0 ** -7]
+
+
+def test_clustered_recipe_has_runs_a_page_index_can_rule_out():
+    """c6: keys in runs around a few hundred centroids.  Seeded and repeatable; the tighter the runs the
+    fewer pages hold a score bound that reaches the k-th score (figures from the float64 oracle)."""
+    from oracle import page_index_ref as pg
+    from oracle import topk_attention_ref as ref
+    w = wl.C6.scaled(32768)
+    a = wl.make_clustered(w, 3, 0.05)
+    b = wl.make_clustered(w, 3, 0.05)
+    for x, y in zip(a, b):
+        np.testing.assert_array_equal(x, y)
+    assert not np.array_equal(wl.make_clustered(w, 4, 0.05)[1], a[1])
+    q0, K0, _ = wl.make_cache(w, 3)                               # the recipe's default tightness
+    np.testing.assert_array_equal(K0, wl.make_clustered(w, 3, wl.CLUSTER_SIGMA)[1])
+    kept = []
+    for sigma in (0.02, 0.1, 0.4):
+        q, K, V = wl.make_clustered(w, 3, sigma)
+        qd, Kd = wl.widen(wl.quantize(q, w.dtype), w.dtype), wl.widen(wl.quantize(K, w.dtype), w.dtype)
+        S = ref.scores(qd, Kd)
+        c, r = pg.page_balls(Kd, 64)
+        s_k = np.sort(S, axis=1)[:, -w.k]
+        kept.append(pg.pages_above(pg.page_upper_bound(qd, c, r), s_k, w.group).mean())
+        # within a run the keys stay close to their centroid: the median page radius is about sigma sqrt(d)
+        assert 0.7 * sigma * np.sqrt(w.head_dim) < np.median(r) < 1.6 * sigma * np.sqrt(w.head_dim)
+    assert kept[0] < 0.35 and kept[0] < kept[1] < kept[2] and kept[2] > 0.95
