@@ -9,13 +9,15 @@ several layers so every scan reads HBM-cold keys.  Prints one JSON line.
 --workload c1 | c2 | c4 | c5 times the other configurations the same way (they are parity-test
 cases, not the metric's workload): c1 the small fp32 case (launch-bound), c2 one 128k-token layer, c4 sixteen sequences of 256k
 tokens per step, c5 one layer of the 32-layer 512k-token cache (all 32 resident, a step is
-one layer's decode).
+one layer's decode).  --workload c6 --pages times the sub-linear search through the page index
+on the cache with topical runs (the scan reads only the pages whose bound reaches the threshold).
 """
 from __future__ import annotations
 
 import argparse
 import json
 import os
+import re
 import sys
 import time
 
@@ -24,9 +26,22 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBPS = 8000.0   # MI355X HBM3E, published
-# HBM bytes one key-scan launch moves at the default workload, from rocprofv3 FETCH_SIZE + WRITE_SIZE
-# (profiles/decode_c3_hbm_counters.md, counters calibrated against copy kernels of known size).
-SCAN_TRAFFIC_BYTES_C3 = 2.1714e9
+
+
+def measured_traffic(kernel: str, workload: str):
+    """HBM bytes one launch of `kernel` moves at `workload`, as the committed rocprofv3 counter summary
+    states it (FETCH_SIZE + WRITE_SIZE, calibrated against copy kernels of known size); None when the
+    summary does not cover that kernel and workload."""
+    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "profiles", "decode_c3_hbm_counters.md")
+    try:
+        with open(path) as f:
+            for line in f:
+                m = re.match(r"traffic: kernel=(\S+) workload=(\S+) bytes_per_launch=(\S+)", line.strip())
+                if m and m.group(1) == kernel and m.group(2) == workload:
+                    return float(m.group(3))
+    except OSError:
+        pass
+    return None
 
 
 def main() -> int:
@@ -40,7 +55,11 @@ def main() -> int:
                     help="queries per step (a causal chunk through topk_attn_decode_multi); 1 is the metric's workload")
     ap.add_argument("--index", action="store_true",
                     help="approximate search through the int8 key index (exact refinement); not the metric's workload")
-    ap.add_argument("--workload", default="c3", choices=["c1", "c2", "c3", "c4", "c5"],
+    ap.add_argument("--pages", action="store_true",
+                    help="sub-linear search through the page index (exact with --beta 1); not the metric's workload")
+    ap.add_argument("--beta", type=float, default=1.0, help="scale of the page radius in the page bound (--pages)")
+    ap.add_argument("--sigma", type=float, default=0.0, help="spread of the keys of a run around its centroid (c6; 0 = the recipe's)")
+    ap.add_argument("--workload", default="c3", choices=["c1", "c2", "c3", "c4", "c5", "c6"],
                     help="c3 is the metric's workload; the others are timed the same way for reference")
     ap.add_argument("--k", type=int, default=0, help="override k (c4 is swept over 256, 1024, 4096 in the tests)")
     ap.add_argument("--force-redo", action="store_true",
@@ -62,23 +81,30 @@ def main() -> int:
         print("bench.py: no GPU visible", file=sys.stderr)
         return 1
     dev = torch.device("cuda", 0)
-    w = {"c1": wl.C1, "c2": wl.C2, "c3": wl.C3, "c4": wl.C4, "c5": wl.C5}[args.workload]
-    default = args.workload == "c3" and not args.tokens and not args.k and not args.force_redo     # the metric's workload as it stands
+    w = {"c1": wl.C1, "c2": wl.C2, "c3": wl.C3, "c4": wl.C4, "c5": wl.C5, "c6": wl.C6}[args.workload]
+    default = args.workload == "c3" and not args.tokens and not args.k and not args.force_redo and not args.pages   # the metric's workload as it stands
     if args.tokens:
         w = w.scaled(args.tokens)
     N, k, d, Hq, Hkv, B = w.n_tokens, args.k or w.k, w.head_dim, w.n_q_heads, w.n_kv_heads, w.n_seqs
     # layers resident at once: enough distinct key bytes that no scan finds its keys in a cache
-    L = max(1, {"c1": 8, "c2": 8, "c3": args.layers, "c4": 1, "c5": 32}[args.workload])
+    L = max(1, {"c1": 8, "c2": 8, "c3": args.layers, "c4": 1, "c5": 32, "c6": args.layers}[args.workload])
 
     t0 = time.time()
-    q, K, V = wl.make_quantized(w, args.seed, threads=16)
+    if args.workload == "c6":
+        sigma = args.sigma or wl.CLUSTER_SIGMA
+        q, K, V = (wl.quantize(a, w.dtype) for a in wl.make_clustered(w, args.seed, sigma, threads=16))
+    else:
+        q, K, V = wl.make_quantized(w, args.seed, threads=16)
     gen_s = time.time() - t0
 
     M = max(1, args.queries)
     cache = ta.TopkAttnCache(L, B, Hq, Hkv, d, N, k, w.dtype, max_queries=M,
-                             index_kind=ta.INDEX_INT8 if args.index else ta.INDEX_NONE)
+                             index_kind=ta.INDEX_INT8 if args.index else ta.INDEX_PAGES if args.pages else ta.INDEX_NONE)
     if args.index:
         cache.set_path(ta.PATH_INDEX)
+    if args.pages:
+        cache.set_path(ta.PATH_PAGES)
+        ta.topk_attn_set_page_bound_scale(cache.h, args.beta)
     if args.force_redo:
         ta.topk_attn_debug_force_redo(cache.h, True)
 
@@ -112,6 +138,7 @@ def main() -> int:
         step(i)
     torch.cuda.synchronize()
     fallbacks = cache.last_fallbacks()
+    pages_read, pages_total = ta.topk_attn_last_pages_read(cache.h)
 
     ta.topk_attn_set_scan_timing(cache.h, True)
     ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
@@ -158,7 +185,11 @@ def main() -> int:
     scan_bytes = k_bytes
     if args.index and M == 1:
         scan_bytes = B * Hkv * N * (d + 4)                      # int8 codes and one fp32 scale per key
+    if args.pages and M == 1:                                   # the pages kept, and one mask bit per page
+        scan_bytes = pages_read * 64 * d * e + pages_total // 8
     scan_gbps = scan_bytes / (scan_ms * 1e-3) / 1e9
+    scan_kernel = "scan_generic_kernel<full>" if w.dtype == wl.F32 else "scan_rows_kernel<filter>" if M > 1 else \
+        "scan8_kernel<filter>" if args.index else "scan_mfma_kernel<filter,paged>" if args.pages else "scan_mfma_kernel<filter>"
 
     cpu = None
     if not args.no_cpu_baseline and M == 1 and not args.index:
@@ -189,7 +220,10 @@ def main() -> int:
         "data": "synthetic",
         "config": {"workload": w.name, "n_q_heads": Hq, "n_kv_heads": Hkv, "head_dim": d, "n_tokens": N,
                    "k": k, "layers_rotated": L, "n_seqs": B, "queries_per_step": M,
-                   "search": "int8 index + exact refinement" if args.index else "exact",
+                   "search": "int8 index + exact refinement" if args.index else
+                   (f"page index, bound scale {args.beta:g}" + (" (exact)" if args.beta == 1.0 else " (approximate)")) if args.pages else "exact",
+                   **({"pages_read": pages_read, "pages_total": pages_total} if args.pages else {}),
+                   **({"sigma": args.sigma or wl.CLUSTER_SIGMA} if args.workload == "c6" else {}),
                    **({"forced": "every head redone exactly (worst case of the filtered path)"} if args.force_redo else {})},
         "scores_per_sec": B * M * Hq * N / (ms_per_step * 1e-3),
         "step_hbm_gbps": alg_bytes / (ms_per_step * 1e-3) / 1e9,
@@ -199,9 +233,9 @@ def main() -> int:
         "step_ms_min": per_step[0],
         "read_probe_gbps": probe_gbps,
         "filter_fallback_heads": fallbacks,
-        "roofline": {"bound": "hbm", "kernel": "scan_generic_kernel (full)" if w.dtype == wl.F32 else ("scan8_kernel (filter)" if args.index else "scan_mfma_kernel (filter)") if M == 1 else "scan_rows_kernel (filter)", "achieved": scan_gbps,
+        "roofline": {"bound": "hbm", "kernel": scan_kernel, "achieved": scan_gbps,
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": scan_gbps / HBM_PEAK_GBPS,
-                     "traffic": SCAN_TRAFFIC_BYTES_C3 if default and M == 1 and not args.index else None, "ms_per_launch": scan_ms,
+                     "traffic": measured_traffic(scan_kernel, w.name) if default and M == 1 and not args.index else None, "ms_per_launch": scan_ms,
                      "bytes_per_launch": scan_bytes,
                      "frac_of_read_probe": scan_gbps / probe_gbps},
         "cpu_baseline": cpu,

@@ -53,20 +53,31 @@ enum {
     TOPK_ATTN_PATH_FILTER = 2,  /* sampled-threshold scan whenever its candidate list fits the
                                    workspace, also for short caches (heads whose candidate list
                                    under- or overflows are still redone exactly) */
-    TOPK_ATTN_PATH_INDEX = 3    /* approximate search over the int8 key index with exact refinement
+    TOPK_ATTN_PATH_INDEX = 3,   /* approximate search over the int8 key index with exact refinement
                                    (needs index_kind = TOPK_ATTN_INDEX_INT8); where the filtered scan
                                    does not apply (short caches, dense k, several queries) the exact
                                    path runs instead */
+    TOPK_ATTN_PATH_PAGES = 4    /* sub-linear search: the key scan skips the pages the coarse page index
+                                   rules out (needs index_kind = TOPK_ATTN_INDEX_PAGES).  Exact: same
+                                   result as the plain scan, unless topk_attn_set_page_bound_scale has
+                                   shrunk the bound.  Where the filtered scan does not apply (short
+                                   caches, dense k, several queries, a window) the exact path runs */
 };
 
 /* Search index kept beside the keys (Algorithm 1's build_index; the paper leaves the kind of
  * index open, from a plain list to approximate structures). */
 enum {
     TOPK_ATTN_INDEX_NONE = 0,   /* the key array itself: exact search */
-    TOPK_ATTN_INDEX_INT8 = 1    /* plus a compressed copy of every key row: int8 codes
+    TOPK_ATTN_INDEX_INT8 = 1,   /* plus a compressed copy of every key row: int8 codes
                                    rint(x * 127 / amax) and one fp32 scale amax / 127 per row
                                    (amax = largest magnitude of the row; rows below 2^-100 are coded
                                    as zero).  16-bit dtypes, head_dim 64, 128 or 256, Hq/Hkv <= 4. */
+    TOPK_ATTN_INDEX_PAGES = 2   /* plus a coarse index over pages of 64 consecutive tokens (the paper's
+                                   sub-linear retrieval; the kind of index is left open there): per page
+                                   a centre c (mean of its keys, in the cache dtype) and two fp32 numbers,
+                                   a radius r >= |k - c| for every key k of the page and |c|.  A page
+                                   cannot hold a key that scores more than q . c + |q| r (Cauchy-Schwarz).
+                                   16-bit dtypes, Hq/Hkv <= 4. */
 };
 
 typedef struct {
@@ -95,7 +106,9 @@ typedef struct {
  * the paper's 2NDL cache of the Introduction with D = Hkv*d), each rounded up to 256 bytes.
  * With TOPK_ATTN_INDEX_INT8 the codes [layer][seq][kv_head][max_tokens][head_dim] int8 and
  * then the scales [layer][seq][kv_head][max_tokens] fp32 follow (each rounded up to 256
- * bytes).  0 on invalid config. */
+ * bytes).  With TOPK_ATTN_INDEX_PAGES the page centres [layer][seq][kv_head][P][head_dim] in
+ * `dtype` and then [layer][seq][kv_head][P][2] fp32 (radius, centre norm) follow, P =
+ * ceil(max_tokens / 64): 1.6 % of K at head_dim 128.  0 on invalid config. */
 size_t topk_attn_kv_bytes(const topk_attn_config* cfg);
 
 /* Bytes of scratch the kernels need (score buffer, candidate lists, partial sums,
@@ -217,6 +230,13 @@ int topk_attn_k_schedule(int64_t total_k, int n_layers, double last_over_first, 
 int topk_attn_decode_layers(topk_attn_t* h, int layer0, int n_layers, const void* q, const int32_t* k,
                             int window, float* out, int32_t* idx, float* vals, float* lse,
                             void* hip_stream);
+
+/* Scale beta in (0, 1] of the page radius in the bound q . c + beta |q| r that decides which pages the
+ * key scan of TOPK_ATTN_PATH_PAGES reads.  1 (the default) is exact.  Below 1 fewer pages are read and a
+ * key whose page was skipped is missed even if its score belongs to the k largest: approximate search,
+ * recall@k against the exact path is the figure of merit; what is returned carries exact scores.
+ * EINVAL without a page index or for beta outside (0, 1]. */
+int topk_attn_set_page_bound_scale(topk_attn_t* h, float beta);
 
 /* Tokens currently cached for (layer, seq); -1 on bad arguments. */
 int64_t topk_attn_length(const topk_attn_t* h, int layer, int seq);

@@ -24,6 +24,11 @@ int topk_attn_scores(topk_attn_t* h, int layer, const void* q, float* scores, vo
  * device->host (synchronous). */
 int topk_attn_last_fallbacks(topk_attn_t* h, int* n_heads);
 
+/* After the caller has synchronised the stream: how many pages (64 tokens of one KV head) the key scan
+ * of the last decode read, and how many the layer's caches hold.  Equal unless the decode went through
+ * TOPK_ATTN_PATH_PAGES.  Copies the page mask device->host (synchronous). */
+int topk_attn_last_pages_read(topk_attn_t* h, int64_t* pages_read, int64_t* pages_total);
+
 /* Measurement aid for the worst case of the filtered path: when enabled, every head of a decode
  * that takes the filtered path is treated like a head whose candidate list turned out unusable
  * (nothing passes its scan; all its keys are rescored exactly and selected from the full score

@@ -9,7 +9,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OBJ_DIR = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libtopk_attn.so")
-SOURCES = ["api.hip", "scan.hip", "select.hip", "gather.hip", "index8.hip", "tail.hip"]
+SOURCES = ["api.hip", "scan.hip", "select.hip", "gather.hip", "index8.hip", "tail.hip", "pages.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
          # packed-fp32 VALU forms are kept off on the test machines
@@ -49,7 +49,7 @@ def build(extra_flags=(), verbose: bool = False) -> str:
     """Compile every source and link the shared library; always recompiles."""
     os.makedirs(OBJ_DIR, exist_ok=True)
     flags = list(extra_flags) + [f'-DTKA_BUILD_ID="{source_hash()}"']
-    with ThreadPoolExecutor(max_workers=6) as ex:
+    with ThreadPoolExecutor(max_workers=7) as ex:
         objs = list(ex.map(lambda s: _compile(s, flags), SOURCES))
     subprocess.check_call([HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB, *objs])
     if verbose:

@@ -25,8 +25,8 @@ inline size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
 inline int elem_bytes(int dtype) { return dtype == TOPK_ATTN_F32 ? 4 : 2; }
 
 struct WsLayout {
-    size_t len, thr, bins, samp, seg_cnt, seg_max, seg_cnt2, flags, hmax, fallback, tailrec, qscale, q8, hist, cand, bnd, scores, sel_idx, sel_val, part_acc, part_l, part_m, total;
-    int cand_cap, n_chunk_cap, hist_cap;
+    size_t len, thr, bins, samp, seg_cnt, seg_max, seg_cnt2, flags, hmax, fallback, tailrec, qscale, q8, page_mask, hist, cand, bnd, scores, sel_idx, sel_val, part_acc, part_l, part_m, total;
+    int cand_cap, bnd_cap, n_chunk_cap, hist_cap, page_words;
 };
 
 bool config_ok(const topk_attn_config* c, int* why) {
@@ -35,7 +35,9 @@ bool config_ok(const topk_attn_config* c, int* why) {
     if (c->n_layers < 1 || c->n_seqs < 1 || c->n_q_heads < 1 || c->n_kv_heads < 1) return false;
     if (c->max_tokens < 1 || c->max_k < 1 || c->device < 0 || c->max_window < 0) return false;
     if (c->max_queries < 0 || c->max_queries > 4096) return false;
-    if (c->index_kind != TOPK_ATTN_INDEX_NONE && c->index_kind != TOPK_ATTN_INDEX_INT8) return false;
+    if (c->index_kind != TOPK_ATTN_INDEX_NONE && c->index_kind != TOPK_ATTN_INDEX_INT8 &&
+        c->index_kind != TOPK_ATTN_INDEX_PAGES)
+        return false;
     if ((int64_t)c->n_seqs * (c->max_queries > 1 ? c->max_queries : 1) > 65535) return false;   // a grid dimension
     if (c->max_tokens > (int64_t)0x7FFFFF00) return false;   // positions are int32
     if (c->max_k > (1 << 28)) return false;                  // the candidate list (about 4 max_k entries) is indexed by int32
@@ -48,6 +50,9 @@ bool config_ok(const topk_attn_config* c, int* why) {
     if (c->dtype == TOPK_ATTN_F32 && c->n_q_heads / c->n_kv_heads > 16) return false;   // plain-FMA scorer
     if (c->index_kind == TOPK_ATTN_INDEX_INT8 &&
         !index8_supported(c->dtype, c->head_dim, c->n_q_heads / c->n_kv_heads))
+        return false;
+    if (c->index_kind == TOPK_ATTN_INDEX_PAGES &&
+        !pages_supported(c->dtype, c->head_dim, c->n_q_heads / c->n_kv_heads))
         return false;
     *why = TOPK_ATTN_OK;
     return true;
@@ -67,21 +72,41 @@ size_t index_scales_bytes(const topk_attn_config* c) {
     if (c->index_kind != TOPK_ATTN_INDEX_INT8) return 0;
     return align_up((size_t)c->n_layers * c->n_seqs * c->n_kv_heads * (size_t)c->max_tokens * sizeof(float));
 }
+// page index behind K and V: centres, then (radius, centre norm) pairs
+int64_t page_cap_of(const topk_attn_config* c) { return (c->max_tokens + 63) / 64; }
+size_t page_centres_bytes(const topk_attn_config* c) {
+    if (c->index_kind != TOPK_ATTN_INDEX_PAGES) return 0;
+    return align_up((size_t)c->n_layers * c->n_seqs * c->n_kv_heads * (size_t)page_cap_of(c) * c->head_dim * elem_bytes(c->dtype));
+}
+size_t page_balls_bytes(const topk_attn_config* c) {
+    if (c->index_kind != TOPK_ATTN_INDEX_PAGES) return 0;
+    return align_up((size_t)c->n_layers * c->n_seqs * c->n_kv_heads * (size_t)page_cap_of(c) * 2 * sizeof(float));
+}
 size_t kv_total_bytes(const topk_attn_config* c) {
-    return 2 * kv_half_bytes(c) + index_codes_bytes(c) + index_scales_bytes(c);
+    return 2 * kv_half_bytes(c) + index_codes_bytes(c) + index_scales_bytes(c) + page_centres_bytes(c) + page_balls_bytes(c);
 }
 
 WsLayout ws_layout(const topk_attn_config* c) {
     WsLayout w;
     const size_t BH = (size_t)c->n_seqs * (c->max_queries > 1 ? c->max_queries : 1) * c->n_q_heads;
     const int64_t max_k = c->max_k < c->max_tokens ? c->max_k : c->max_tokens;
-    // candidate list per head: room for the expected candidates (about 2 k at most) and for the
-    // slack of its segments.  A call with few KV-head streams splits each stream into many
-    // wave segments (up to about 1024 waves over the chip, doubled where the split is rounded
-    // up), and every segment needs its own few dozen spare entries.
+    // candidate list per head.  A call with few KV-head streams splits each stream into many wave
+    // segments (up to about 1024 waves over the chip, doubled where the split is rounded up).
     int64_t seg_max = 8 * ((512 + (int64_t)c->n_seqs * c->n_kv_heads - 1) / ((int64_t)c->n_seqs * c->n_kv_heads));
     if (seg_max > kMaxSeg) seg_max = kMaxSeg;
-    w.cand_cap = (int)(4 * max_k + 16384 + 48 * seg_max);
+    // The boundary list takes the expected candidates (about 2 k at most) and a few dozen spare entries
+    // per segment.  The segments of the candidate list are sized for keys whose scores come in runs
+    // along the sequence (a passage the query attends to): a whole 64-key tile of candidates lands in
+    // one segment at a time, so a segment that expects m such tiles gets room for m + 5 sqrt(m) + 4.
+    w.bnd_cap = (int)(4 * max_k + 16384 + 48 * seg_max);
+    {
+        const Plan top = make_plan(c->max_tokens, (int)max_k);
+        const double m = (double)top.c_hi / (64.0 * (double)seg_max);
+        const int64_t lumpy = (int64_t)((double)seg_max * 64.0 * (m + 5.0 * sqrt(m) + 4.0));
+        w.cand_cap = (int)(lumpy > w.bnd_cap ? lumpy : w.bnd_cap);
+        // whole 128-byte lines per head and whole runs of kCandChunk per segment, however the list is split
+        w.cand_cap = (int)(((int64_t)w.cand_cap + kMaxSeg * kCandChunk - 1) / (kMaxSeg * kCandChunk) * (kMaxSeg * kCandChunk));
+    }
     const int64_t max_w = c->max_window < c->max_tokens ? c->max_window : c->max_tokens;
     // partial sums per head: the tail of the filtered path makes up to one per 128 selected rows (and never
     // more than scan workgroups fed the head), the gather one per 256; the window adds one per 256 tokens
@@ -102,9 +127,12 @@ WsLayout ws_layout(const topk_attn_config* c) {
     w.tailrec = take(BH * 4 * sizeof(uint32_t));
     w.qscale = take(BH * sizeof(float));
     w.q8 = take(BH * (size_t)c->head_dim);
+    w.page_words = (int)((page_cap_of(c) + 63) / 64);
+    w.page_mask = take(c->index_kind == TOPK_ATTN_INDEX_PAGES
+                           ? (size_t)c->n_seqs * c->n_kv_heads * (size_t)w.page_words * sizeof(uint64_t) : 0);
     w.hist = take(BH * (size_t)w.hist_cap * kTailBins * sizeof(uint32_t));
     w.cand = take(BH * (size_t)w.cand_cap * sizeof(uint64_t));
-    w.bnd = take(BH * (size_t)w.cand_cap * sizeof(uint64_t));
+    w.bnd = take(BH * (size_t)w.bnd_cap * sizeof(uint64_t));
     w.scores = take(BH * (size_t)c->max_tokens * sizeof(float));
     w.sel_idx = take(BH * (size_t)c->max_k * sizeof(int32_t));   // stride is the requested k, up to max_k
     w.sel_val = take(BH * (size_t)c->max_k * sizeof(float));
@@ -221,6 +249,9 @@ struct topk_attn {
     bool last_fast;
     bool last_static;           // the last decode used the built-in scratch
     bool force_redo;            // measurement aid, see topk_attn_debug_force_redo
+    float page_beta;            // scale of the page radius in the page bound (1 = exact)
+    bool last_paged;            // the last decode went through the page index
+    int last_layer;
     char* scratch_dev;          // this device's copy of the built-in scratch
     int n_cu;                   // compute units of the device
     // optional event pairs around the key scan of each decode (measurement only)
@@ -268,6 +299,9 @@ int topk_attn_create(const topk_attn_config* cfg, topk_attn_t** out) {
     h->n_cu = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
     h->last_static = false;
     h->force_redo = false;
+    h->page_beta = 1.0f;
+    h->last_paged = false;
+    h->last_layer = 0;
     {   // cfg->device is current here
         void* p = nullptr;
         const int rc = scratch_address(cfg->device, &p);
@@ -296,8 +330,9 @@ int64_t topk_attn_length(const topk_attn_t* h, int layer, int seq) {
 }
 
 int topk_attn_set_path(topk_attn_t* h, int path) {
-    if (!h || path < TOPK_ATTN_PATH_AUTO || path > TOPK_ATTN_PATH_INDEX) return TOPK_ATTN_EINVAL;
+    if (!h || path < TOPK_ATTN_PATH_AUTO || path > TOPK_ATTN_PATH_PAGES) return TOPK_ATTN_EINVAL;
     if (path == TOPK_ATTN_PATH_INDEX && h->cfg.index_kind != TOPK_ATTN_INDEX_INT8) return TOPK_ATTN_EINVAL;
+    if (path == TOPK_ATTN_PATH_PAGES && h->cfg.index_kind != TOPK_ATTN_INDEX_PAGES) return TOPK_ATTN_EINVAL;
     h->path = path;
     return TOPK_ATTN_OK;
 }
@@ -351,6 +386,17 @@ int topk_attn_append_kv(topk_attn_t* h, int layer, int seq, const void* k_new, c
                                  (hipStream_t)hip_stream) != hipSuccess)
             return TOPK_ATTN_EDEVICE;
     }
+    if (c.index_kind == TOPK_ATTN_INDEX_PAGES) {   // balls of the pages just touched (stream order: after the copy)
+        char* base = static_cast<char*>(c.kv_storage) + 2 * h->kv_half;
+        const int64_t pcap = page_cap_of(&c);
+        const int64_t stream0 = (int64_t)slot * c.n_kv_heads;
+        char* centres = base + stream0 * pcap * row_b;
+        float* balls = reinterpret_cast<float*>(base + page_centres_bytes(&c)) + stream0 * pcap * 2;
+        const char* kseq = static_cast<const char*>(c.kv_storage) + stream0 * head_b;
+        if (launch_page_balls(c.dtype, c.head_dim, kseq, c.max_tokens, pcap, c.n_kv_heads, 1, nullptr, cur, n_new, centres,
+                              balls, (hipStream_t)hip_stream) != hipSuccess)
+            return TOPK_ATTN_EDEVICE;
+    }
     h->len[slot] = cur + n_new;
     return TOPK_ATTN_OK;
 }
@@ -387,6 +433,16 @@ int topk_attn_append_step(topk_attn_t* h, int layer, const void* k_new, const vo
                                  st) != hipSuccess)
             return TOPK_ATTN_EDEVICE;
     }
+    if (c.index_kind == TOPK_ATTN_INDEX_PAGES) {
+        char* base = static_cast<char*>(c.kv_storage) + 2 * h->kv_half;
+        const int64_t pcap = page_cap_of(&c);
+        const int64_t stream0 = (int64_t)layer * B * c.n_kv_heads;
+        char* centres = base + stream0 * pcap * row_b;
+        float* balls = reinterpret_cast<float*>(base + page_centres_bytes(&c)) + stream0 * pcap * 2;
+        if (launch_page_balls(c.dtype, c.head_dim, kdst, c.max_tokens, pcap, c.n_kv_heads, B, len_dev, 0, n_new, centres, balls,
+                              st) != hipSuccess)
+            return TOPK_ATTN_EDEVICE;
+    }
     hipLaunchKernelGGL(bump_len_kernel, dim3((unsigned)((B + 255) / 256)), dim3(256), 0, st, len_dev, B, (int32_t)n_new);
     if (hipGetLastError() != hipSuccess) return TOPK_ATTN_EDEVICE;
     for (int b = 0; b < B; ++b) h->len[(size_t)layer * B + b] += n_new;
@@ -403,9 +459,11 @@ static void fill_call(topk_attn_t* h, int layer, const void* q, int k, int n_que
     s->n_qblk = (n_queries * s->G + 16 * s->row_tiles - 1) / (16 * s->row_tiles);
     s->D = c.head_dim; s->dtype = c.dtype; s->k = k; s->window = 0; s->max_k = c.max_k;
     s->hist_cap = h->ws.hist_cap; s->tail_spw = 1; s->tail_wgs = 1;
-    s->cand_cap = h->ws.cand_cap; s->n_seg = 4; s->seg_cap = (h->ws.cand_cap / 4) & ~(kCandChunk - 1); s->samp_cap = kSampMax; s->n_chunk_cap = h->ws.n_chunk_cap;
+    s->cand_cap = h->ws.cand_cap; s->bnd_cap = h->ws.bnd_cap; s->n_seg = 4; s->seg_cap = (h->ws.cand_cap / 4) & ~(kCandChunk - 1); s->samp_cap = kSampMax; s->n_chunk_cap = h->ws.n_chunk_cap;
     s->Ncap = c.max_tokens;
     s->indexed = 0;
+    s->paged = 0; s->no_rescan = 0;
+    s->page_cap = (int)page_cap_of(&c); s->page_words = h->ws.page_words;
     s->force_redo = h->force_redo ? 1 : 0;
     s->cand_est = 0;
     char* const ws_len = static_cast<char*>(c.workspace);
@@ -422,6 +480,14 @@ static void fill_call(topk_attn_t* h, int layer, const void* q, int k, int n_que
         b->K8 = reinterpret_cast<const int8_t*>(base) + layer_rows * c.head_dim;
         b->Kscale = reinterpret_cast<const float*>(base + index_codes_bytes(&c)) + layer_rows;
     }
+    b->page_centres = nullptr; b->page_balls = nullptr;
+    if (c.index_kind == TOPK_ATTN_INDEX_PAGES) {
+        const char* base = static_cast<const char*>(c.kv_storage) + 2 * h->kv_half;
+        const size_t layer_streams = (size_t)layer * c.n_seqs * c.n_kv_heads;
+        b->page_centres = base + layer_streams * (size_t)page_cap_of(&c) * c.head_dim * e;
+        b->page_balls = reinterpret_cast<const float*>(base + page_centres_bytes(&c)) + layer_streams * (size_t)page_cap_of(&c) * 2;
+    }
+    b->page_mask = reinterpret_cast<uint64_t*>(ws + h->ws.page_mask);
     b->q8 = reinterpret_cast<int8_t*>(ws + h->ws.q8);
     b->qscale = reinterpret_cast<float*>(ws + h->ws.qscale);
     b->len = reinterpret_cast<int32_t*>(ws_len + h->ws.len) + (size_t)layer * c.n_seqs;
@@ -523,6 +589,8 @@ static int decode_impl(topk_attn_t* h, int layer, const void* q, int n_queries, 
     // the int8 index serves one query per sequence with the grouped scan layout
     const bool want_index = h->path == TOPK_ATTN_PATH_INDEX && n_queries == 1 && s.G <= 4;
     s.indexed = want_index ? 1 : 0;
+    // the page index serves the grouped scan without a window (what its tail covers)
+    const bool want_pages = h->path == TOPK_ATTN_PATH_PAGES && n_queries == 1 && s.G <= 4 && window == 0;
     // The batch takes the filtered scan if its longest sequence is worth it.  Shorter sequences
     // ride along whenever their candidate list fits; the few that cannot be filtered at all (a
     // handful of tokens, or k too dense) are recognised by the kernels themselves (same
@@ -576,10 +644,13 @@ static int decode_impl(topk_attn_t* h, int layer, const void* q, int n_queries, 
         if (e == hipSuccess) e = launch_rerank(s, b, st);
         if (e == hipSuccess) e = launch_select_candidates(s, b, st);   // redoes unusable heads itself
     } else if (fast) {
+        s.paged = want_pages && tail_supported(s) ? 1 : 0;
+        s.no_rescan = s.paged && h->page_beta < 1.0f ? 1 : 0;
         e = launch_scan_sample(s, b, nmax, st);
         if (e == hipSuccess) e = launch_threshold(s, b, nmax, st);
+        if (e == hipSuccess && s.paged) e = launch_page_filter(s, b, h->page_beta, st);
         if (e == hipSuccess && timed) e = hipEventRecord(h->ev[2 * h->ev_used], st);
-        if (e == hipSuccess) e = launch_scan_filter(s, b, nmax, st);
+        if (e == hipSuccess) e = s.paged ? launch_scan_filter_paged(s, b, st) : launch_scan_filter(s, b, nmax, st);
         if (e == hipSuccess && timed) e = hipEventRecord(h->ev[2 * h->ev_used + 1], st);
         if (e == hipSuccess && timed) h->ev_used++;
         if (tail_supported(s)) {
@@ -599,6 +670,8 @@ static int decode_impl(topk_attn_t* h, int layer, const void* q, int n_queries, 
     }
     if (e == hipSuccess && !tail_done) e = launch_gather(s, b, st);
     h->last_fast = fast;
+    h->last_paged = fast && s.paged;
+    h->last_layer = layer;
     h->last_static = use_static;
     return e == hipSuccess ? TOPK_ATTN_OK : TOPK_ATTN_EDEVICE;
 }
@@ -711,6 +784,31 @@ int topk_attn_last_fallbacks(topk_attn_t* h, int* n_heads) {
         hipSuccess)
         return TOPK_ATTN_EDEVICE;
     *n_heads = (int)v;
+    return TOPK_ATTN_OK;
+}
+
+int topk_attn_set_page_bound_scale(topk_attn_t* h, float beta) {
+    if (!h || h->cfg.index_kind != TOPK_ATTN_INDEX_PAGES || !(beta > 0.0f) || beta > 1.0f) return TOPK_ATTN_EINVAL;
+    h->page_beta = beta;
+    return TOPK_ATTN_OK;
+}
+
+int topk_attn_last_pages_read(topk_attn_t* h, int64_t* pages_read, int64_t* pages_total) {
+    if (!h || !pages_read || !pages_total) return TOPK_ATTN_EINVAL;
+    const topk_attn_config& c = h->cfg;
+    int64_t total = 0;
+    for (int b = 0; b < c.n_seqs; ++b) total += (h->len[(size_t)h->last_layer * c.n_seqs + b] + 63) / 64 * c.n_kv_heads;
+    *pages_total = total;
+    *pages_read = total;                       // every page, unless the last decode went through the page index
+    if (!h->last_paged || h->last_static) return TOPK_ATTN_OK;
+    const size_t words = (size_t)c.n_seqs * c.n_kv_heads * h->ws.page_words;
+    std::vector<uint64_t> mask(words);
+    if (hipMemcpy(mask.data(), static_cast<char*>(c.workspace) + h->ws.page_mask, words * sizeof(uint64_t),
+                  hipMemcpyDeviceToHost) != hipSuccess)
+        return TOPK_ATTN_EDEVICE;
+    int64_t read = 0;
+    for (uint64_t w : mask) read += __builtin_popcountll(w);
+    *pages_read = read;
     return TOPK_ATTN_OK;
 }
 

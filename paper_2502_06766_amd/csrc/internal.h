@@ -35,11 +35,16 @@ struct Shape {
     int n_qblk;       // row-tile scan: blocks of 16 * row_tiles (query, head) rows per KV head
     int indexed;      // the scan reads the int8 key index; candidates are re-scored exactly afterwards
     int force_redo;   // measurement aid: treat every head as not filterable (exact redo of all heads)
+    int paged;        // the scan skips the pages the coarse page index rules out
+    int no_rescan;    // the pages skipped may hold candidates (approximate page bound): an unusable list is redone densely
+    int page_cap;     // pages per key stream the page index has room for (ceil(Ncap / 64))
+    int page_words;   // 64-bit words of the page mask per key stream
     int cand_est;     // candidates per head expected at most (sizes the selection's register cache)
     int k;            // requested k (k_eff = min(k, searched prefix of sequence b))
     int window;       // most recent tokens that are always attended and excluded from the search
     int max_k;
     int cand_cap;     // entries per (b, head) candidate list
+    int bnd_cap;      // entries per (b, head) boundary list
     int n_seg;        // segments the candidate list is split in (one per scanning wave), power of 2
     int seg_cap;      // entries per segment (n_seg * seg_cap <= cand_cap), a multiple of kCandChunk
     int samp_cap;     // entries per (b, head) sample-score row
@@ -72,8 +77,11 @@ struct Bufs {
     uint64_t* cand;         // [B*Hq][cand_cap] (score bits << 32 | position); entry e of segment g
                             // at [cand_slot(e, g, n_seg)]
     uint32_t* hist;         // [B*Hq][hist_cap][kTailBins] candidates per score bin found by each scan workgroup
-    uint64_t* bnd;          // [B*Hq][cand_cap] candidates of the bin the k-th score falls in
+    uint64_t* bnd;          // [B*Hq][bnd_cap] candidates of the bin the k-th score falls in
     uint32_t* tailrec;      // [B*Hq][4] what the tail's second kernel needs to know of a head (TailRec)
+    const void* page_centres;  // this layer's page centres [Bc][Hkv][page_cap][D] (cache dtype), or null
+    const float* page_balls;   // this layer's [Bc][Hkv][page_cap][2]: radius of the page's ball, norm of its centre
+    uint64_t* page_mask;       // [B][Hkv][page_words] one bit per page: 1 = the scan reads it
     float* scores;          // [B*Hq][Ncap] full score buffer
     int32_t* sel_idx;       // [B*Hq][k]
     float* sel_val;         // [B*Hq][k]
@@ -208,6 +216,13 @@ hipError_t launch_gather(const Shape& s, const Bufs& b, hipStream_t st);
 // fused selection + gather after a filtered scan that counted its candidates per score bin
 bool tail_supported(const Shape& s);
 hipError_t launch_tail(const Shape& s, const Bufs& b, hipStream_t st);
+
+// coarse page index
+bool pages_supported(int dtype, int D, int G);
+hipError_t launch_page_balls(int dtype, int D, const void* K, int64_t Ncap, int64_t Pcap, int Hkv, int B,
+                             const int32_t* len_dev, int64_t row0, int64_t n_new, void* centres, float* balls, hipStream_t st);
+hipError_t launch_page_filter(const Shape& s, const Bufs& b, float beta, hipStream_t st);
+hipError_t launch_scan_filter_paged(const Shape& s, const Bufs& b, hipStream_t st);
 
 // int8 key index
 bool index8_supported(int dtype, int D, int G);

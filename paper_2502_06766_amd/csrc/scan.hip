@@ -25,7 +25,9 @@
 
 namespace tka {
 
-template <int DT, int D, int MODE>
+// PAGED (filter mode only): the wave skips the tiles whose bit in the page mask is clear (pages of 64 keys
+// that the coarse page index has ruled out for every head of the group).
+template <int DT, int D, int MODE, bool PAGED = false>
 __global__ void __launch_bounds__(kScanWaves* kWave)
 scan_mfma_kernel(Shape sh, Bufs bf, int tiles_per_wave, float* dst) {
     using v8 = typename Mfma<DT>::v8;
@@ -128,6 +130,25 @@ scan_mfma_kernel(Shape sh, Bufs bf, int tiles_per_wave, float* dst) {
     auto use = [&](TileB& t, int64_t ti) { consume(tile_mac<DT, D>(t.b, qa), ti * 64); };
     if (MODE == MODE_SAMPLE) {
         walk_tiles<ScanPipelined<D>::value>(tile, tile_end, tile_step, ba, bb, load_rows, use);
+    } else if (MODE == MODE_FILTER && PAGED) {
+        // 64 of my tiles at a time: lane i looks up the bit of tile `tile + i * tile_step`; the tiles that
+        // are left are scored one after the other (the other waves of the compute unit cover the latency)
+        const uint64_t* pm = bf.page_mask + ((int64_t)b * sh.Hkv + kvh) * sh.page_words;
+        const int64_t n_whole = N / 64;
+        const uint32_t lane_off = (uint32_t)(((lane & 15) * D + (lane >> 4) * 8) * 2);
+        for (; tile < tile_end; tile += 64 * tile_step) {
+            const int64_t mine = tile + lane * tile_step;
+            const bool alive = mine < tile_end && ((pm[mine >> 6] >> (mine & 63)) & 1ull) != 0ull;
+            uint64_t m = __ballot(alive);
+            while (m) {
+                const int bit = __builtin_ctzll(m);
+                m &= m - 1ull;
+                const int64_t ti = tile + bit * tile_step;
+                if (ti < n_whole) tile_load_full<DT, D>(Kh + ti * (64 * D * 2), lane_off, ba.b);
+                else load_rows(ba, ti);
+                use(ba, ti);
+            }
+        }
     } else {
         // whole tiles first, then the one tile (if any) that the end of the cache cuts short
         const int64_t n_whole = N / 64;
@@ -537,6 +558,25 @@ static hipError_t launch_mfma(const Shape& s, const Bufs& b, int64_t n_items, fl
 hipError_t launch_scan_sample(const Shape& s, const Bufs& b, int64_t Nmax, hipStream_t st) {
     Plan pl = make_plan(Nmax, s.k);
     return launch_mfma<MODE_SAMPLE>(s, b, pl.n_samp, nullptr, st);
+}
+
+hipError_t launch_scan_filter_paged(const Shape& s, const Bufs& b, hipStream_t st) {
+    if (scan_row_tiles(s)) return hipErrorInvalidValue;      // grouped scan only
+    dim3 grid((unsigned)(s.n_seg / kScanWaves), (unsigned)s.Hkv, (unsigned)s.B);
+    dim3 block(kScanWaves * kWave);
+#define TKA_LAUNCH(DT_, D_) \
+    hipLaunchKernelGGL((scan_mfma_kernel<DT_, D_, MODE_FILTER, true>), grid, block, 0, st, s, b, 0, (float*)nullptr)
+    if (s.dtype == DT_F16 && s.D == 128) TKA_LAUNCH(DT_F16, 128);
+    else if (s.dtype == DT_F16 && s.D == 64) TKA_LAUNCH(DT_F16, 64);
+    else if (s.dtype == DT_BF16 && s.D == 128) TKA_LAUNCH(DT_BF16, 128);
+    else if (s.dtype == DT_BF16 && s.D == 64) TKA_LAUNCH(DT_BF16, 64);
+    else if (s.dtype == DT_F16 && s.D == 256) TKA_LAUNCH(DT_F16, 256);
+    else if (s.dtype == DT_BF16 && s.D == 256) TKA_LAUNCH(DT_BF16, 256);
+    else if (s.dtype == DT_F16 && s.D == 32) TKA_LAUNCH(DT_F16, 32);
+    else if (s.dtype == DT_BF16 && s.D == 32) TKA_LAUNCH(DT_BF16, 32);
+    else return hipErrorInvalidValue;
+#undef TKA_LAUNCH
+    return hipGetLastError();
 }
 
 hipError_t launch_scan_filter(const Shape& s, const Bufs& b, int64_t Nmax, hipStream_t st) {

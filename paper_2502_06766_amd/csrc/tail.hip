@@ -136,10 +136,11 @@ __device__ __forceinline__ HeadSel analyse_head(const Shape& sh, const Bufs& bf,
     hs.binB = (int)sm.sel[0]; hs.above = sm.sel[1]; hs.have = sm.sel[2]; hs.emit_at = sm.sel[3]; hs.bnd_at = sm.sel[4];
     const bool counted = sm.sel[5] != 0u;
     hs.hmax = key_score(kmx);
-    const bool list_ok = !(bf.flags[bh] & 4u) && max_len <= (uint32_t)sh.seg_cap && total >= (uint32_t)k_eff;
-    // (the boundary list has room for cand_cap entries, and so does the list the keys are sorted into again)
+    // the bin of the k-th score has to fit the boundary list, and the keys sorted again their list
+    const bool bnd_ok = counted && hs.have <= (uint32_t)sh.bnd_cap;
+    const bool list_ok = !(bf.flags[bh] & 4u) && max_len <= (uint32_t)sh.seg_cap && total >= (uint32_t)k_eff && bnd_ok;
     hs.mode = list_ok ? MODE_LIST
-                      : (counted && (uint64_t)hs.above + hs.have <= (uint64_t)sh.cand_cap ? MODE_RESCAN : MODE_DENSE);
+                      : (bnd_ok && !sh.no_rescan && (uint64_t)hs.above + hs.have <= (uint64_t)sh.cand_cap ? MODE_RESCAN : MODE_DENSE);
     return hs;
 }
 
@@ -298,7 +299,7 @@ __global__ void __launch_bounds__(kTailThreads) tail_gather_kernel(Shape sh, Buf
     // ---- second pass: write winners and boundary candidates, fetch the winners' value rows
     int32_t* idx = bf.sel_idx + bh * sh.k;
     float* vals = bf.sel_val + bh * sh.k;
-    uint64_t* bnd = bf.bnd + bh * (int64_t)sh.cand_cap;
+    uint64_t* bnd = bf.bnd + bh * (int64_t)sh.bnd_cap;
     const char* Vh = static_cast<const char*>(bf.V) +
                      ((int64_t)cache_seq(sh, b) * sh.Hkv + h / sh.G) * sh.Ncap * (D * 2);
     const int rs = lane / LPR, c = lane % LPR;
@@ -360,7 +361,7 @@ __global__ void __launch_bounds__(kTailThreads) tail_gather_kernel(Shape sh, Buf
                 }
                 if (edge) {
                     const uint32_t o = bnd_at + (uint32_t)mask_rank(me);
-                    if (o < (uint32_t)sh.cand_cap) bnd[o] = ent;
+                    if (o < (uint32_t)sh.bnd_cap) bnd[o] = ent;
                 }
                 const int addw = __popcll(mw);
                 emit_at += (uint32_t)addw;
@@ -454,7 +455,7 @@ __global__ void __launch_bounds__(NT) tail_finish_kernel(Shape sh, Bufs bf, floa
     // list may be read; what lies beyond `have` is ignored below)
     uint64_t ent[CIMAX];
 #pragma unroll
-    for (int i = 0; i < CIMAX; ++i) ent[i] = (i * NT + tid < sh.cand_cap) ? bf.bnd[bh * (int64_t)sh.cand_cap + i * NT + tid] : 0ull;
+    for (int i = 0; i < CIMAX; ++i) ent[i] = (i * NT + tid < sh.bnd_cap) ? bf.bnd[bh * (int64_t)sh.bnd_cap + i * NT + tid] : 0ull;
     int32_t* idx = bf.sel_idx + bh * sh.k;
     float* vals = bf.sel_val + bh * sh.k;
     if (rec.state == TAIL_EMPTY || k_eff == 0) {
@@ -524,7 +525,7 @@ __global__ void __launch_bounds__(NT) tail_finish_kernel(Shape sh, Bufs bf, floa
                     [&](int j) { return exp2f((vals[j] - hmax) * scale_log2e); });
     } else if ((int)rec.have > kFinishSmall) {
         // a boundary bin this full (massive ties, or a sample that misjudged the k-th score): radix select
-        const SrcListT<NT> src{bf.bnd + bh * (int64_t)sh.cand_cap, (int64_t)rec.have, pos_lds};
+        const SrcListT<NT> src{bf.bnd + bh * (int64_t)sh.bnd_cap, (int64_t)rec.have, pos_lds};
         const Items<CPT, SrcListT<NT>> items(src);
         wg_topk_emit(items, (int)rec.need, sh.k - (int)rec.above, idx + rec.above, vals + rec.above, sm);
         __syncthreads();

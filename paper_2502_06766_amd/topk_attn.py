@@ -16,13 +16,13 @@ LIB_PATH = os.path.join(_HERE, "libtopk_attn.so")
 
 OK, EINVAL, ECAPACITY, EUNSUPPORTED, EDEVICE, ENOMEM, ESCRATCH = range(7)
 F32, F16, BF16 = 0, 1, 2
-PATH_AUTO, PATH_FULL, PATH_FILTER, PATH_INDEX = 0, 1, 2, 3
-INDEX_NONE, INDEX_INT8 = 0, 1
+PATH_AUTO, PATH_FULL, PATH_FILTER, PATH_INDEX, PATH_PAGES = 0, 1, 2, 3, 4
+INDEX_NONE, INDEX_INT8, INDEX_PAGES = 0, 1, 2
 
 EXPORTS = [
     "topk_attn_kv_bytes", "topk_attn_workspace_bytes", "topk_attn_create", "topk_attn_append_kv", "topk_attn_append_step",
     "topk_attn_decode", "topk_attn_decode_static", "topk_attn_decode_window", "topk_attn_decode_multi", "topk_attn_decode_layers", "topk_attn_k_schedule", "topk_attn_scores", "topk_attn_length", "topk_attn_reset", "topk_attn_set_path",
-    "topk_attn_last_fallbacks", "topk_attn_debug_force_redo", "topk_attn_set_scan_timing", "topk_attn_scan_time", "topk_attn_read_probe", "topk_attn_build_id", "topk_attn_strerror", "topk_attn_destroy",
+    "topk_attn_last_fallbacks", "topk_attn_set_page_bound_scale", "topk_attn_last_pages_read", "topk_attn_debug_force_redo", "topk_attn_set_scan_timing", "topk_attn_scan_time", "topk_attn_read_probe", "topk_attn_build_id", "topk_attn_strerror", "topk_attn_destroy",
 ]
 
 
@@ -98,6 +98,10 @@ def lib() -> ctypes.CDLL:
         L.topk_attn_set_path.restype = i32
         L.topk_attn_last_fallbacks.argtypes = [vp, ctypes.POINTER(i32)]
         L.topk_attn_last_fallbacks.restype = i32
+        L.topk_attn_set_page_bound_scale.argtypes = [vp, ctypes.c_float]
+        L.topk_attn_set_page_bound_scale.restype = i32
+        L.topk_attn_last_pages_read.argtypes = [vp, ctypes.POINTER(i64), ctypes.POINTER(i64)]
+        L.topk_attn_last_pages_read.restype = i32
         L.topk_attn_debug_force_redo.argtypes = [vp, i32]
         L.topk_attn_debug_force_redo.restype = i32
         L.topk_attn_set_scan_timing.argtypes = [vp, i32]
@@ -227,6 +231,17 @@ def topk_attn_last_fallbacks(h) -> int:
     n = ctypes.c_int(0)
     _check(lib().topk_attn_last_fallbacks(h, ctypes.byref(n)), "topk_attn_last_fallbacks")
     return n.value
+
+
+def topk_attn_set_page_bound_scale(h, beta: float):
+    _check(lib().topk_attn_set_page_bound_scale(h, beta), "topk_attn_set_page_bound_scale")
+
+
+def topk_attn_last_pages_read(h):
+    """(pages read by the last decode's key scan, pages cached); sync the stream first."""
+    a, b = ctypes.c_int64(0), ctypes.c_int64(0)
+    _check(lib().topk_attn_last_pages_read(h, ctypes.byref(a), ctypes.byref(b)), "topk_attn_last_pages_read")
+    return a.value, b.value
 
 
 def topk_attn_debug_force_redo(h, enable: bool):

@@ -25,6 +25,13 @@ hipError_t launch_gather(const Shape&, const Bufs&, hipStream_t) { return hipErr
 bool tail_supported(const Shape&) { return false; }
 hipError_t launch_tail(const Shape&, const Bufs&, hipStream_t) { return hipErrorUnknown; }
 bool index8_supported(int dtype, int D, int G) { return dtype != 0 && D >= 64 && G <= 4; }
+bool pages_supported(int dtype, int, int G) { return dtype != 0 && G <= 4; }
+hipError_t launch_page_balls(int, int, const void*, int64_t, int64_t, int, int, const int32_t*, int64_t, int64_t, void*, float*,
+                             hipStream_t) {
+    return hipErrorUnknown;
+}
+hipError_t launch_page_filter(const Shape&, const Bufs&, float, hipStream_t) { return hipErrorUnknown; }
+hipError_t launch_scan_filter_paged(const Shape&, const Bufs&, hipStream_t) { return hipErrorUnknown; }
 hipError_t launch_quantize_rows(int, int, const void*, int64_t, int64_t, int, int8_t*, float*, int64_t, hipStream_t) {
     return hipErrorUnknown;
 }
@@ -133,6 +140,14 @@ int main() {
     CHECK(topk_attn_last_fallbacks(nullptr, &n) == TOPK_ATTN_EINVAL);
     CHECK(topk_attn_set_scan_timing(nullptr, 1) == TOPK_ATTN_EINVAL);
     CHECK(topk_attn_debug_force_redo(nullptr, 1) == TOPK_ATTN_EINVAL);
+    CHECK(topk_attn_set_page_bound_scale(nullptr, 1.0f) == TOPK_ATTN_EINVAL);
+    { int64_t a = 0, bb = 0; CHECK(topk_attn_last_pages_read(nullptr, &a, &bb) == TOPK_ATTN_EINVAL); }
+    c = base_config();
+    c.index_kind = TOPK_ATTN_INDEX_PAGES;
+    {   // centres and (radius, centre norm) pairs of ceil(100000 / 64) pages per key stream, each region rounded up to 256 bytes
+        const unsigned long long pages = 2ull * 3 * 8 * ((100000 + 63) / 64);
+        CHECK(topk_attn_kv_bytes(&c) == kv + (pages * 128 * 2 + 255) / 256 * 256 + (pages * 8 + 255) / 256 * 256);
+    }
     CHECK(topk_attn_scan_time(nullptr, &ms, &n) == TOPK_ATTN_EINVAL);
     CHECK(topk_attn_read_probe(nullptr, 16, nullptr, nullptr) == TOPK_ATTN_EINVAL);
     CHECK(topk_attn_destroy(nullptr) == TOPK_ATTN_EINVAL);

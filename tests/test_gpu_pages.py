@@ -1,0 +1,239 @@
+"""GPU tests of the coarse page index (TOPK_ATTN_INDEX_PAGES / TOPK_ATTN_PATH_PAGES), the sub-linear search.
+
+* Index contents: every page's ball (centre, radius) encloses the page's keys and is about as tight
+  as the ball around the mean that oracle/page_index_ref.py computes, after appends in pieces.
+* The search is exact: index sets, vals, out, lse judged against the exact oracle like the plain
+  path, and bit-identical to the plain path on the same handle; the pages read include every page
+  that holds a selected key (oracle) and, on a cache with topical runs, are a fraction of the cache.
+* With a shrunk bound the search is approximate: recall@k against the exact oracle.
+"""
+import numpy as np
+import pytest
+import torch
+
+import helpers as H
+from oracle import c_oracle
+from oracle import int8_index_ref as i8
+from oracle import page_index_ref as pg
+from paper_2502_06766_amd import topk_attn as ta
+from paper_2502_06766_amd import workloads as wl
+
+pytestmark = pytest.mark.gpu
+DEV = torch.device("cuda", 0) if torch.cuda.is_available() else None
+PAGE = 64
+
+
+def page_views(cache, L, B, Hkv, Ncap, d, dtype):
+    """Centres [L, B, Hkv, P, d] (storage dtype) and balls [L, B, Hkv, P, 2] fp32 as laid out behind K and V."""
+    up = lambda x: (x + 255) // 256 * 256
+    P = (Ncap + PAGE - 1) // PAGE
+    half = up(L * B * Hkv * Ncap * d * 2)
+    nc = L * B * Hkv * P * d * 2
+    tdt = torch.bfloat16 if dtype == wl.BF16 else torch.float16
+    centres = cache.kv[2 * half: 2 * half + nc].view(tdt).view(L, B, Hkv, P, d)
+    off = 2 * half + up(nc)
+    balls = cache.kv[off: off + L * B * Hkv * P * 8].view(torch.float32).view(L, B, Hkv, P, 2)
+    return centres, balls
+
+
+def clustered(N, k, seed, sigma, dtype=wl.F16, Hq=8, Hkv=2, d=128):
+    w = wl.Workload("clustered_test", 6, 1, 1, Hq, Hkv, d, N, k, dtype, "clustered")
+    q, K, V = wl.make_clustered(w, seed, sigma, threads=8)
+    return wl.quantize(q, dtype), wl.quantize(K, dtype), wl.quantize(V, dtype)
+
+
+@pytest.mark.parametrize("dtype,d", [(wl.F16, 128), (wl.BF16, 64), (wl.BF16, 256), (wl.F16, 32)])
+def test_page_balls_enclose_their_pages_after_piecewise_appends(dtype, d):
+    g = np.random.default_rng(d + dtype)
+    L, B, Hq, Hkv, Ncap, N = 2, 2, 4, 2, 1000, 903
+    K = (g.standard_normal((Hkv, N, d)) * g.uniform(0.05, 4.0, (Hkv, N, 1))).astype(np.float32)
+    K[0, 128:192] = K[0, 128]                                  # page 2 of KV head 0: 64 identical keys
+    Ks = wl.quantize(K, dtype)
+    Vs = wl.quantize(g.standard_normal((Hkv, N, d)).astype(np.float32), dtype)
+    cache = ta.TopkAttnCache(L, B, Hq, Hkv, d, Ncap, 16, dtype, index_kind=ta.INDEX_PAGES)
+    try:
+        Kd, Vd = H.to_torch(Ks, dtype, DEV), H.to_torch(Vs, dtype, DEV)
+        # layer 1, sequence 1: a bulk import that ends inside a page, single tokens across a page boundary
+        # (token-major), then the rest; layer 0 through the batched per-step append
+        cache.append(1, 1, Kd[:, :100].contiguous(), Vd[:, :100].contiguous(), head_major=True)
+        for t in range(100, 131):
+            cache.append(1, 1, Kd[:, t:t + 1].permute(1, 0, 2).contiguous(), Vd[:, t:t + 1].permute(1, 0, 2).contiguous())
+        cache.append(1, 1, Kd[:, 131:].contiguous(), Vd[:, 131:].contiguous(), head_major=True)
+        cache.append(0, 0, Kd[:, :70].contiguous(), Vd[:, :70].contiguous(), head_major=True)
+        cache.append(0, 1, Kd[:, :5].contiguous(), Vd[:, :5].contiguous(), head_major=True)
+        steps = [(200, 203), (203, 264), (264, 334)]           # every sequence of layer 0 grows by the same tokens
+        for a, z in steps:
+            kn = Kd[:, a:z].permute(1, 0, 2)[None].expand(B, -1, -1, -1).contiguous()
+            cache.append_step(0, kn, kn.clone())
+        torch.cuda.synchronize()
+        centres, balls = page_views(cache, L, B, Hkv, Ncap, d, dtype)
+        Kw = wl.widen(Ks, dtype)
+
+        def judge(c_dev, b_dev, rows, label):
+            P = (rows.shape[1] + PAGE - 1) // PAGE
+            c = c_dev[:, :P].float().cpu().numpy().astype(np.float64)
+            r = b_dev[:, :P, 0].cpu().numpy().astype(np.float64)
+            cn = b_dev[:, :P, 1].cpu().numpy().astype(np.float64)
+            slack = pg.ball_slack(rows, PAGE, c, r)
+            assert (slack >= 0).all(), f"{label}: a key lies outside its page's ball"
+            c_ref, r_ref = pg.page_balls(rows, PAGE)
+            # the stored centre is the mean rounded to the storage type: the radius grows by at most that rounding
+            step = (2.0 ** -8 if dtype == wl.BF16 else 2.0 ** -11) * np.abs(c_ref).max(axis=2) * np.sqrt(d)
+            assert (r <= r_ref * 1.001 + step + 1e-6).all(), f"{label}: radius looser than the ball around the mean"
+            assert (cn >= np.sqrt((c ** 2).sum(axis=2)) * (1 - 1e-6)).all() and (cn <= np.sqrt((c ** 2).sum(axis=2)) * 1.001 + 1e-30).all()
+            return r
+
+        r = judge(centres[1, 1], balls[1, 1], Kw, "layer 1")
+        assert r[0, 2] <= 1e-20 and r[1, 2] > 1e-3              # identical keys: the centre is the key, the radius nothing
+        grown = np.concatenate([Kw[:, :70], Kw[:, 200:203], Kw[:, 203:264], Kw[:, 264:334]], axis=1)
+        judge(centres[0, 0], balls[0, 0], grown, "layer 0 seq 0")
+        grown1 = np.concatenate([Kw[:, :5], Kw[:, 200:203], Kw[:, 203:264], Kw[:, 264:334]], axis=1)
+        judge(centres[0, 1], balls[0, 1], grown1, "layer 0 seq 1")
+    finally:
+        cache.close()
+
+
+def run_pages_case(q, K, V, dtype, k, beta=1.0, label="", margin=True):
+    """One sequence through the page index and through the plain scan of the same handle.  Returns
+    (fraction of pages read, recalls per head)."""
+    Hq, d = q.shape
+    Hkv, N, _ = K.shape
+    G = Hq // Hkv
+    if margin:
+        try:      # a nudge of several ulps of the storage type
+            K, _, _ = H.enforce_margin(q, K, dtype, k, shrink=2.0 ** -9 if dtype == wl.F16 else 2.0 ** -6)
+        except H.MarginNotReached:
+            margin = False
+    ref = c_oracle.topk_attention(q, K, V, dtype, k)
+    cache = ta.TopkAttnCache(1, 1, Hq, Hkv, d, N, k, dtype, index_kind=ta.INDEX_PAGES)
+    try:
+        cache.append(0, 0, H.to_torch(K, dtype, DEV), H.to_torch(V, dtype, DEV), head_major=True)
+        qd = H.to_torch(q, dtype, DEV)[None].contiguous()
+        plain = cache.decode(0, qd, k)
+        plain_fallbacks = cache.last_fallbacks()
+        assert ta.topk_attn_last_pages_read(cache.h)[0] == ta.topk_attn_last_pages_read(cache.h)[1]
+        cache.set_path(ta.PATH_PAGES)
+        if beta != 1.0:
+            ta.topk_attn_set_page_bound_scale(cache.h, beta)
+        res = cache.decode(0, qd, k)
+        torch.cuda.synchronize()
+        read, total = ta.topk_attn_last_pages_read(cache.h)
+        assert total == Hkv * ((N + PAGE - 1) // PAGE) and 0 < read <= total
+        out, idx, vals, lse = (t[0].cpu().numpy() for t in res)
+        delta = H.score_margin(q, K, dtype)
+        vmax = float(np.abs(wl.widen(V, dtype)).max())
+        k_eff = min(k, N)
+        recalls = [i8.recall_at_k(idx[h, :k_eff], ref[1][h, :k_eff]) for h in range(Hq)]
+        if beta == 1.0:
+            assert cache.last_fallbacks() == plain_fallbacks       # same candidates, same lists
+            if margin:
+                H.check_against_oracle(out, idx, vals, lse, ref, delta, k_eff, H.out_tolerance(dtype), vmax, label)
+            else:
+                H.check_unmargined((out, idx, vals, lse), q, K, V, dtype, k, 0, label)
+            # same candidates as the plain scan: bit-identical selection and output
+            assert torch.equal(torch.sort(res[1], dim=2).values, torch.sort(plain[1], dim=2).values), f"{label}: index sets differ from the plain scan's"
+            assert torch.equal(res[0], plain[0]) and torch.equal(res[3], plain[3]), f"{label}: out differs from the plain scan's"
+            # no page that holds a selected key was skipped: at least those pages were read
+            need = pg.pages_holding_topk(ref[1], (N + PAGE - 1) // PAGE, PAGE, G)
+            assert read >= need.sum(), f"{label}: fewer pages read than hold selected keys"
+        else:
+            S = c_oracle.scores(q, K, dtype)
+            for h in range(Hq):        # whatever is returned is a valid position with its exact score
+                got = idx[h, :k_eff].astype(np.int64)
+                assert np.unique(got).size == k_eff and got.min() >= 0 and got.max() < N
+                assert np.abs(vals[h, :k_eff].astype(np.float64) - S[h, got]).max() <= delta[h] / 8
+        return read / total, recalls
+    finally:
+        cache.close()
+
+
+@pytest.mark.parametrize("dtype,Hq,Hkv,N,d,k,sigma", [
+    (wl.F16, 8, 2, 70001, 128, 700, 0.02),
+    (wl.BF16, 8, 2, 65536, 128, 1024, 0.05),
+    (wl.F16, 4, 2, 50003, 64, 300, 0.03),        # G = 2, d = 64
+    (wl.BF16, 3, 3, 40000, 256, 500, 0.02),      # G = 1, d = 256
+    (wl.F16, 4, 1, 300001, 128, 3000, 0.02),     # one KV head: 1024 wave segments
+])
+def test_pages_path_is_exact_on_clustered_caches(dtype, Hq, Hkv, N, d, k, sigma):
+    q, K, V = clustered(N, k, seed=N + k, sigma=sigma, dtype=dtype, Hq=Hq, Hkv=Hkv, d=d)
+    frac, _ = run_pages_case(q, K, V, dtype, k, label=f"pages N={N} k={k} sigma={sigma}")
+    print(f"pages N={N} k={k} sigma={sigma}: {frac:.3f} of the pages read", flush=True)
+    assert frac < 0.6          # runs this tight leave a good part of the cache unread
+
+
+def test_pages_path_on_unstructured_keys_reads_everything_and_stays_exact():
+    g = np.random.default_rng(8)
+    Hq, Hkv, N, d, k = 8, 2, 40001, 128, 300
+    q = wl.quantize(g.standard_normal((Hq, d)).astype(np.float32), wl.F16)
+    K = wl.quantize(g.standard_normal((Hkv, N, d)).astype(np.float32), wl.F16)
+    V = wl.quantize(g.standard_normal((Hkv, N, d)).astype(np.float32), wl.F16)
+    frac, _ = run_pages_case(q, K, V, wl.F16, k, label="pages gaussian")
+    assert frac > 0.99         # Gaussian rows: no page can be ruled out
+
+
+def test_shrunk_page_bound_trades_recall_for_pages():
+    N, k, sigma = 131072, 2048, 0.1
+    q, K, V = clustered(N, k, seed=17, sigma=sigma)
+    fracs, recs = [], []
+    for beta in (1.0, 0.5, 0.1):
+        frac, recalls = run_pages_case(q, K, V, wl.F16, k, beta=beta, label=f"beta {beta}", margin=False)
+        fracs.append(frac)
+        recs.append(min(recalls))
+        print(f"beta {beta}: {frac:.3f} of the pages read, recall@k {min(recalls):.4f} .. {max(recalls):.4f}", flush=True)
+    assert recs[0] == 1.0
+    assert fracs[0] > fracs[1] > fracs[2]
+    assert recs[1] >= 0.9 and recs[2] >= 0.3          # a shrunk bound misses keys, the more the smaller it is
+
+
+def test_pages_ragged_batch_windows_and_queries_fall_back_to_the_exact_path():
+    dtype, Hq, Hkv, d, k = wl.F16, 8, 2, 128, 200
+    lens = [60000, 130, 33000]
+    cache = ta.TopkAttnCache(1, 3, Hq, Hkv, d, max(lens), k, dtype, index_kind=ta.INDEX_PAGES, max_window=64)
+    try:
+        cache.set_path(ta.PATH_PAGES)
+        data = []
+        for b, n in enumerate(lens):
+            q, K, V = clustered(n, k, seed=300 + b, sigma=0.03)
+            K, _, _ = H.enforce_margin(q, K, dtype, k, shrink=2.0 ** -9)
+            data.append((q, K, V))
+            cache.append(0, b, H.to_torch(K, dtype, DEV), H.to_torch(V, dtype, DEV), head_major=True)
+        qd = torch.stack([H.to_torch(x[0], dtype, DEV) for x in data]).contiguous()
+        out, idx, vals, lse = cache.decode(0, qd, k)
+        torch.cuda.synchronize()
+        read, total = ta.topk_attn_last_pages_read(cache.h)
+        assert read < total
+        for b, n in enumerate(lens):
+            q, K, V = data[b]
+            ref = c_oracle.topk_attention(q, K, V, dtype, k)
+            H.check_against_oracle(out[b].cpu().numpy(), idx[b].cpu().numpy(), vals[b].cpu().numpy(), lse[b].cpu().numpy(),
+                                   ref, H.score_margin(q, K, dtype), min(k, n), 2e-3, float(np.abs(wl.widen(V, dtype)).max()),
+                                   f"pages ragged seq {b}")
+        # with a window the call takes the plain path (every page read), and is still right
+        outw, idxw, valsw, lsew = cache.decode(0, qd, k, window=64)
+        torch.cuda.synchronize()
+        read, total = ta.topk_attn_last_pages_read(cache.h)
+        assert read == total
+        q, K, V = data[0]
+        refw = c_oracle.topk_attention_window(q, K, V, dtype, k, 64)
+        H.check_unmargined(tuple(t[0].cpu().numpy() for t in (outw, idxw, valsw, lsew)), q, K, V, dtype, k, 64, "pages + window")
+        assert ta.lib().topk_attn_set_page_bound_scale(cache.h, 0.0) == ta.EINVAL
+        assert ta.lib().topk_attn_set_page_bound_scale(cache.h, 1.5) == ta.EINVAL
+    finally:
+        cache.close()
+    plain = ta.TopkAttnCache(1, 1, Hq, Hkv, d, 1000, k, dtype)
+    try:
+        assert ta.lib().topk_attn_set_path(plain.h, ta.PATH_PAGES) == ta.EINVAL
+        assert ta.lib().topk_attn_set_page_bound_scale(plain.h, 0.5) == ta.EINVAL
+    finally:
+        plain.close()
+
+
+def test_c6_clustered_1m_tokens_sublinear_and_exact():
+    """The clustered workload at full size (one million tokens, k = 16384, fp16): the page index reads a
+    fraction of the pages and returns exactly the oracle's selection."""
+    w = wl.C6
+    q, K, V = wl.make_clustered(w, 0, 0.02, threads=16)
+    q, K, V = wl.quantize(q, w.dtype), wl.quantize(K, w.dtype), wl.quantize(V, w.dtype)
+    frac, _ = run_pages_case(q, K, V, w.dtype, w.k, label="c6")
+    print(f"c6: {frac:.3f} of the pages read", flush=True)
+    assert frac < 0.35
