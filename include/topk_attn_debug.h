@@ -29,6 +29,14 @@ int topk_attn_last_fallbacks(topk_attn_t* h, int* n_heads);
  * TOPK_ATTN_PATH_PAGES.  Copies the page mask device->host (synchronous). */
 int topk_attn_last_pages_read(topk_attn_t* h, int64_t* pages_read, int64_t* pages_total);
 
+/* After the caller has synchronised the stream: what the selection of the last decode found for each
+ * (sequence, head) pair that took the filtered path with the chip-wide selection: records[4 i + 0] = 0 if
+ * the head's candidate list was used, 1 / 2 if its keys were sorted or selected again; [4 i + 1] = keys
+ * selected for certain (score bins above the one the k-th score falls in); [4 i + 2] = keys still to pick
+ * from that bin; [4 i + 3] = candidates in that bin.  `records` is a host array of 4 * n_seqs * n_q_heads
+ * words.  TOPK_ATTN_EINVAL if the last decode took another path.  Copies device->host (synchronous). */
+int topk_attn_last_selection_records(topk_attn_t* h, uint32_t* records);
+
 /* Measurement aid for the worst case of the filtered path: when enabled, every head of a decode
  * that takes the filtered path is treated like a head whose candidate list turned out unusable
  * (nothing passes its scan; all its keys are rescored exactly and selected from the full score

@@ -251,6 +251,7 @@ struct topk_attn {
     bool force_redo;            // measurement aid, see topk_attn_debug_force_redo
     float page_beta;            // scale of the page radius in the page bound (1 = exact)
     bool last_paged;            // the last decode went through the page index
+    bool last_tail;             // the last decode used the chip-wide selection (its per-head records are in the workspace)
     int last_layer;
     char* scratch_dev;          // this device's copy of the built-in scratch
     int n_cu;                   // compute units of the device
@@ -301,6 +302,7 @@ int topk_attn_create(const topk_attn_config* cfg, topk_attn_t** out) {
     h->force_redo = false;
     h->page_beta = 1.0f;
     h->last_paged = false;
+    h->last_tail = false;
     h->last_layer = 0;
     {   // cfg->device is current here
         void* p = nullptr;
@@ -671,6 +673,7 @@ static int decode_impl(topk_attn_t* h, int layer, const void* q, int n_queries, 
     if (e == hipSuccess && !tail_done) e = launch_gather(s, b, st);
     h->last_fast = fast;
     h->last_paged = fast && s.paged;
+    h->last_tail = tail_done;
     h->last_layer = layer;
     h->last_static = use_static;
     return e == hipSuccess ? TOPK_ATTN_OK : TOPK_ATTN_EDEVICE;
@@ -809,6 +812,15 @@ int topk_attn_last_pages_read(topk_attn_t* h, int64_t* pages_read, int64_t* page
     int64_t read = 0;
     for (uint64_t w : mask) read += __builtin_popcountll(w);
     *pages_read = read;
+    return TOPK_ATTN_OK;
+}
+
+int topk_attn_last_selection_records(topk_attn_t* h, uint32_t* records) {
+    if (!h || !records || !h->last_tail || h->last_static) return TOPK_ATTN_EINVAL;
+    const topk_attn_config& c = h->cfg;
+    if (hipMemcpy(records, static_cast<char*>(c.workspace) + h->ws.tailrec, (size_t)c.n_seqs * c.n_q_heads * 4 * sizeof(uint32_t),
+                  hipMemcpyDeviceToHost) != hipSuccess)
+        return TOPK_ATTN_EDEVICE;
     return TOPK_ATTN_OK;
 }
 

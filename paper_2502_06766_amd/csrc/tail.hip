@@ -409,7 +409,8 @@ struct SrcListT {
     __device__ __forceinline__ uint32_t cached_ipos(int j) const { return pos_lds[j * NT + (int)threadIdx.x]; }
 };
 
-constexpr int kFinishSmall = 2048;     // boundary candidates ranked by direct comparison; more go through the radix select
+constexpr int kFinishInner = 2048;     // candidates the finishing workgroup ranks by direct comparison at most
+constexpr int kFinishSmall = 4096;     // boundary candidates the finishing workgroup holds in registers; more go through the radix select
 
 // Rank of each of this thread's CI items among the composite keys in LDS (number of keys that
 // beat it), by comparing with every key: all lanes read the same key at a time (an LDS
@@ -433,15 +434,16 @@ __device__ __forceinline__ void rank_by_comparison(const uint64_t* keys, int n8,
 
 template <int DT, int NT>
 __global__ void __launch_bounds__(NT) tail_finish_kernel(Shape sh, Bufs bf, float scale, float scale_log2e) {
-    constexpr int EPL = 8, NW = NT / kWave, CPT = 4, U = 4;
+    constexpr int EPL = 8, NW = NT / kWave, CPT = 4, U = 8;       // U: value rows in flight per lane group
     constexpr int CIMAX = kFinishSmall / NT;       // boundary candidates per thread on the small path
     __shared__ SelShared sm;
     __shared__ uint32_t pos_lds[CPT * NT];
-    __shared__ __align__(16) uint64_t s_keys[kFinishSmall + 8];
+    __shared__ __align__(16) uint64_t s_keys[kFinishInner + 8];
     __shared__ int32_t s_pos[kFinishSmall];
     __shared__ float s_w[kFinishSmall];
     __shared__ float s_acc[NW][256 + 1];
     __shared__ float s_red[NT];
+    __shared__ uint32_t s_cnt[2][NW];
     const int h = blockIdx.x, b = blockIdx.y;
     const int tid = threadIdx.x, lane = lane_id(), wave = tid >> 6;
     const int64_t bh = (int64_t)b * sh.Hq + h;
@@ -517,13 +519,64 @@ __global__ void __launch_bounds__(NT) tail_finish_kernel(Shape sh, Bufs bf, floa
         }
     };
 
-    if (rec.state == TAIL_REDO) {
+    // How the winners among the boundary candidates are found (uniform over the workgroup).
+    enum { BY_REDO, BY_RADIX, BY_SUBBINS, BY_RANKING };
+    const int have = (int)rec.have, need = (int)rec.need;
+    int how = rec.state == TAIL_REDO ? BY_REDO : have > kFinishSmall ? BY_RADIX : have > NT ? BY_SUBBINS : BY_RANKING;
+    int sb[CIMAX], sbin = 0, sure = 0, m = 0;
+    if (how == BY_SUBBINS) {
+        // Many boundary candidates (scores that come in clusters put a whole cluster into the bin of the
+        // k-th score): sort them once more into kBins sub-bins over their own score range, take the
+        // sub-bins above the one the need-th best falls in as they are, and rank only that one.
+        float lo = INFINITY, hi = -INFINITY;
+#pragma unroll
+        for (int i = 0; i < CIMAX; ++i) {
+            const float sc = __uint_as_float((uint32_t)(ent[i] >> 32));
+            if (i * NT + tid < have) { lo = fminf(lo, sc); hi = fmaxf(hi, sc); }
+        }
+        for (int o = 32; o > 0; o >>= 1) { lo = fminf(lo, wave_xor(lo, o)); hi = fmaxf(hi, wave_xor(hi, o)); }
+        if (lane == 0) { s_red[wave] = lo; s_red[NW + wave] = hi; }
+        for (int i = tid; i < kBins; i += NT) sm.hist[i] = 0;
+        if (tid == 0) { sm.bin = 0u; sm.above = 0u; sm.cb = (uint32_t)have; }     // (overwritten below: 1 <= need <= have)
+        __syncthreads();
+#pragma unroll
+        for (int w = 0; w < NW; ++w) { lo = fminf(lo, s_red[w]); hi = fmaxf(hi, s_red[NW + w]); }
+        const float sub_inv = hi > lo ? (float)(kBins - 1) / (hi - lo) : 0.f;
+#pragma unroll
+        for (int i = 0; i < CIMAX; ++i) {
+            const float sc = __uint_as_float((uint32_t)(ent[i] >> 32));
+            sb[i] = i * NT + tid < have ? (int)fminf((sc - lo) * sub_inv, (float)(kBins - 1)) : -1;   // monotone in the score
+            if (sb[i] >= 0) atomicAdd(&sm.hist[sb[i]], 1u);
+        }
+        __syncthreads();
+        {   // the sub-bin in which the counts, summed from the top, reach `need`: thread t looks at the two bins 2t, 2t+1 from the top
+            static_assert(kBins == 2 * NT, "two sub-bins per thread");
+            const uint32_t c0 = sm.hist[kBins - 1 - 2 * tid], c1 = sm.hist[kBins - 2 - 2 * tid];
+            uint32_t inc = c0 + c1;
+            for (int o = 1; o < kWave; o <<= 1) {
+                const uint32_t v = __shfl_up(inc, o, kWave);
+                if (lane >= o) inc += v;
+            }
+            if (lane == kWave - 1) s_cnt[0][wave] = inc;
+            __syncthreads();
+            uint32_t before = inc - (c0 + c1);
+            for (int w = 0; w < wave; ++w) before += s_cnt[0][w];
+            if (before < (uint32_t)need && (uint32_t)need <= before + c0) { sm.bin = (uint32_t)(kBins - 1 - 2 * tid); sm.above = before; sm.cb = c0; }
+            else if (before + c0 < (uint32_t)need && (uint32_t)need <= before + c0 + c1) {
+                sm.bin = (uint32_t)(kBins - 2 - 2 * tid); sm.above = before + c0; sm.cb = c1;
+            }
+            __syncthreads();
+        }
+        sbin = (int)sm.bin; sure = (int)sm.above; m = (int)sm.cb;
+        if (m > kFinishInner) how = BY_RADIX;      // (nearly) all of them tie: the radix select breaks ties by position
+    }
+    if (how == BY_REDO) {
         // every score of the head is in the score buffer: exact selection over the full row
         hmax = key_score(wg_select_dense<NT, 8>(sh, bf, bh, N, k_eff, sm));     // writes idx, vals, padding, hmax
         __syncthreads();                      // idx / vals written above are read below
         gather_rows(0, k_eff, [&](int j) { return (int64_t)idx[j]; },
                     [&](int j) { return exp2f((vals[j] - hmax) * scale_log2e); });
-    } else if ((int)rec.have > kFinishSmall) {
+    } else if (how == BY_RADIX) {
         // a boundary bin this full (massive ties, or a sample that misjudged the k-th score): radix select
         const SrcListT<NT> src{bf.bnd + bh * (int64_t)sh.bnd_cap, (int64_t)rec.have, pos_lds};
         const Items<CPT, SrcListT<NT>> items(src);
@@ -532,55 +585,87 @@ __global__ void __launch_bounds__(NT) tail_finish_kernel(Shape sh, Bufs bf, floa
         gather_rows((int)rec.above, k_eff, [&](int j) { return (int64_t)idx[j]; },
                     [&](int j) { return exp2f((vals[j] - hmax) * scale_log2e); });
     } else {
-        // The usual case, a few hundred boundary candidates: each is ranked against all others by its
-        // composite key (score key, then inverted position: larger beats smaller, equal scores go to
-        // the lower position, no two keys are equal), and the `need` best are the missing winners.
-        const int have = (int)rec.have, need = (int)rec.need;
-        uint64_t mine[CIMAX];
+        if (how == BY_SUBBINS) {
+            // fixed order (wave, slot, lane) for both the certain winners and the entries still to rank
+            uint32_t tot_w = 0, tot_e = 0;
 #pragma unroll
-        for (int i = 0; i < CIMAX; ++i) {
-            const int s = i * NT + tid;
-            mine[i] = s < have ? ((uint64_t)score_key(__uint_as_float((uint32_t)(ent[i] >> 32))) << 32) |
-                                     (uint64_t)(0xFFFFFFFFu - (uint32_t)ent[i])
-                               : ~0ull;                                   // nothing beats an empty slot's key
-            if (s < have) s_keys[s] = mine[i];
-        }
-        const int have8 = (have + 7) & ~7;
-        if (tid < have8 - have) s_keys[have + tid] = 0ull;               // padding: beats nothing
-        __syncthreads();
-        uint32_t rank[CIMAX];
-        const int ci = (have + NT - 1) / NT;                              // slots per thread in use (uniform)
-        if (ci <= 1) { uint64_t m1[1] = {mine[0]}; uint32_t r1[1]; rank_by_comparison<1>(s_keys, have8, m1, r1); rank[0] = r1[0]; }
-        else if (ci <= 2 && CIMAX >= 2) {
-            uint64_t m2[2] = {mine[0], mine[CIMAX >= 2 ? 1 : 0]}; uint32_t r2[2];
-            rank_by_comparison<2>(s_keys, have8, m2, r2); rank[0] = r2[0]; rank[CIMAX >= 2 ? 1 : 0] = r2[1];
-        } else rank_by_comparison<CIMAX>(s_keys, have8, mine, rank);
-        // winners in a fixed order: slot-major, then thread
-        uint32_t wave_total = 0;
+            for (int i = 0; i < CIMAX; ++i) {
+                tot_w += (uint32_t)__popcll(__ballot(sb[i] > sbin));
+                tot_e += (uint32_t)__popcll(__ballot(sb[i] == sbin));
+            }
+            if (lane == 0) { s_cnt[0][wave] = tot_w; s_cnt[1][wave] = tot_e; }
+            __syncthreads();
+            uint32_t run_w = 0, run_e = 0;
+            for (int w = 0; w < wave; ++w) { run_w += s_cnt[0][w]; run_e += s_cnt[1][w]; }
 #pragma unroll
-        for (int i = 0; i < CIMAX; ++i) {
-            const bool win = i < ci && i * NT + tid < have && rank[i] < (uint32_t)need;
-            wave_total += (uint32_t)__popcll(__ballot(win));
-        }
-        if (lane == 0) sm.wave_tot[wave] = wave_total;
-        __syncthreads();
-        uint32_t run = 0;
-        for (int w = 0; w < wave; ++w) run += sm.wave_tot[w];
-#pragma unroll
-        for (int i = 0; i < CIMAX; ++i) {
-            const bool win = i < ci && i * NT + tid < have && rank[i] < (uint32_t)need;
-            const uint64_t m = __ballot(win);
-            if (win) {
-                const uint32_t o = run + (uint32_t)mask_rank(m);
-                if (o < (uint32_t)need) {         // always true; guards the buffers
-                    const float sc = __uint_as_float((uint32_t)(ent[i] >> 32));
-                    idx[rec.above + o] = (int32_t)(uint32_t)ent[i];
+            for (int i = 0; i < CIMAX; ++i) {
+                const bool win = sb[i] > sbin, edge = sb[i] == sbin;
+                const uint64_t mw = __ballot(win), me = __ballot(edge);
+                const float sc = __uint_as_float((uint32_t)(ent[i] >> 32));
+                if (win) {
+                    const uint32_t o = run_w + (uint32_t)mask_rank(mw);
+                    if (o < (uint32_t)need) {         // always true; guards the buffers
+                        idx[rec.above + o] = (int32_t)(uint32_t)ent[i];
+                        vals[rec.above + o] = sc;
+                        s_pos[o] = (int32_t)(uint32_t)ent[i];
+                        s_w[o] = exp2f((sc - hmax) * scale_log2e);
+                    }
+                }
+                if (edge) {
+                    const uint32_t o = run_e + (uint32_t)mask_rank(me);
+                    if (o < (uint32_t)kFinishInner) s_keys[o] = ((uint64_t)score_key(sc) << 32) | (uint64_t)(0xFFFFFFFFu - (uint32_t)ent[i]);
+                }
+                run_w += (uint32_t)__popcll(mw);
+                run_e += (uint32_t)__popcll(me);
+            }
+            const int m8 = (m + 7) & ~7;
+            if (tid < m8 - m) s_keys[m + tid] = 0ull;                     // padding: beats nothing
+            __syncthreads();
+            const uint32_t need2 = (uint32_t)(need - sure);               // 1 .. m of the ranked entries win
+            for (int j = tid; j < m; j += NT) {
+                const uint64_t m1[1] = {s_keys[j]};
+                uint32_t r1[1];
+                rank_by_comparison<1>(s_keys, m8, m1, r1);
+                if (r1[0] < need2) {
+                    const uint32_t o = (uint32_t)sure + r1[0];
+                    const float sc = key_score((uint32_t)(m1[0] >> 32));
+                    const int32_t pos = (int32_t)(0xFFFFFFFFu - (uint32_t)m1[0]);
+                    idx[rec.above + o] = pos;
                     vals[rec.above + o] = sc;
-                    s_pos[o] = (int32_t)(uint32_t)ent[i];
+                    s_pos[o] = pos;
                     s_w[o] = exp2f((sc - hmax) * scale_log2e);
                 }
             }
-            run += (uint32_t)__popcll(m);
+        } else {
+            // The usual case, at most one boundary candidate per thread: each is ranked against all others
+            // by its composite key (score key, then inverted position: larger beats smaller, equal scores go
+            // to the lower position, no two keys are equal), and the `need` best are the missing winners.
+            const uint64_t mine[1] = {tid < have ? ((uint64_t)score_key(__uint_as_float((uint32_t)(ent[0] >> 32))) << 32) |
+                                                       (uint64_t)(0xFFFFFFFFu - (uint32_t)ent[0])
+                                                 : ~0ull};                    // nothing beats an empty slot's key
+            if (tid < have) s_keys[tid] = mine[0];
+            const int have8 = (have + 7) & ~7;
+            if (tid < have8 - have) s_keys[have + tid] = 0ull;               // padding: beats nothing
+            __syncthreads();
+            uint32_t rank[1];
+            rank_by_comparison<1>(s_keys, have8, mine, rank);
+            // winners in thread order
+            const bool win = tid < have && rank[0] < (uint32_t)need;
+            const uint64_t mw = __ballot(win);
+            if (lane == 0) sm.wave_tot[wave] = (uint32_t)__popcll(mw);
+            __syncthreads();
+            uint32_t run = 0;
+            for (int w = 0; w < wave; ++w) run += sm.wave_tot[w];
+            if (win) {
+                const uint32_t o = run + (uint32_t)mask_rank(mw);
+                if (o < (uint32_t)need) {         // always true; guards the buffers
+                    const float sc = __uint_as_float((uint32_t)(ent[0] >> 32));
+                    idx[rec.above + o] = (int32_t)(uint32_t)ent[0];
+                    vals[rec.above + o] = sc;
+                    s_pos[o] = (int32_t)(uint32_t)ent[0];
+                    s_w[o] = exp2f((sc - hmax) * scale_log2e);
+                }
+            }
         }
         pad_outputs(k_eff, sh.k, idx, vals);
         __syncthreads();
@@ -637,14 +722,8 @@ hipError_t launch_tail(const Shape& s, const Bufs& b, hipStream_t st) {
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     const dim3 grid_b((unsigned)s.Hq, (unsigned)s.B);
-    const bool small = true;
-    if (s.dtype == DT_F16) {
-        if (small) hipLaunchKernelGGL((tail_finish_kernel<DT_F16, 256>), grid_b, dim3(256), 0, st, s, b, scale, scale_log2e);
-        else hipLaunchKernelGGL((tail_finish_kernel<DT_F16, 1024>), grid_b, dim3(1024), 0, st, s, b, scale, scale_log2e);
-    } else {
-        if (small) hipLaunchKernelGGL((tail_finish_kernel<DT_BF16, 256>), grid_b, dim3(256), 0, st, s, b, scale, scale_log2e);
-        else hipLaunchKernelGGL((tail_finish_kernel<DT_BF16, 1024>), grid_b, dim3(1024), 0, st, s, b, scale, scale_log2e);
-    }
+    if (s.dtype == DT_F16) hipLaunchKernelGGL((tail_finish_kernel<DT_F16, 256>), grid_b, dim3(256), 0, st, s, b, scale, scale_log2e);
+    else hipLaunchKernelGGL((tail_finish_kernel<DT_BF16, 256>), grid_b, dim3(256), 0, st, s, b, scale, scale_log2e);
     return hipGetLastError();
 }
 

@@ -22,7 +22,7 @@ INDEX_NONE, INDEX_INT8, INDEX_PAGES = 0, 1, 2
 EXPORTS = [
     "topk_attn_kv_bytes", "topk_attn_workspace_bytes", "topk_attn_create", "topk_attn_append_kv", "topk_attn_append_step",
     "topk_attn_decode", "topk_attn_decode_static", "topk_attn_decode_window", "topk_attn_decode_multi", "topk_attn_decode_layers", "topk_attn_k_schedule", "topk_attn_scores", "topk_attn_length", "topk_attn_reset", "topk_attn_set_path",
-    "topk_attn_last_fallbacks", "topk_attn_set_page_bound_scale", "topk_attn_last_pages_read", "topk_attn_debug_force_redo", "topk_attn_set_scan_timing", "topk_attn_scan_time", "topk_attn_read_probe", "topk_attn_build_id", "topk_attn_strerror", "topk_attn_destroy",
+    "topk_attn_last_fallbacks", "topk_attn_set_page_bound_scale", "topk_attn_last_pages_read", "topk_attn_last_selection_records", "topk_attn_debug_force_redo", "topk_attn_set_scan_timing", "topk_attn_scan_time", "topk_attn_read_probe", "topk_attn_build_id", "topk_attn_strerror", "topk_attn_destroy",
 ]
 
 
@@ -102,6 +102,8 @@ def lib() -> ctypes.CDLL:
         L.topk_attn_set_page_bound_scale.restype = i32
         L.topk_attn_last_pages_read.argtypes = [vp, ctypes.POINTER(i64), ctypes.POINTER(i64)]
         L.topk_attn_last_pages_read.restype = i32
+        L.topk_attn_last_selection_records.argtypes = [vp, ctypes.POINTER(ctypes.c_uint32)]
+        L.topk_attn_last_selection_records.restype = i32
         L.topk_attn_debug_force_redo.argtypes = [vp, i32]
         L.topk_attn_debug_force_redo.restype = i32
         L.topk_attn_set_scan_timing.argtypes = [vp, i32]
@@ -242,6 +244,13 @@ def topk_attn_last_pages_read(h):
     a, b = ctypes.c_int64(0), ctypes.c_int64(0)
     _check(lib().topk_attn_last_pages_read(h, ctypes.byref(a), ctypes.byref(b)), "topk_attn_last_pages_read")
     return a.value, b.value
+
+
+def topk_attn_last_selection_records(h, n_heads_total: int):
+    """[n_heads_total][4] (state, certain, to pick, in the boundary bin) of the last decode; sync the stream first."""
+    buf = (ctypes.c_uint32 * (4 * n_heads_total))()
+    _check(lib().topk_attn_last_selection_records(h, buf), "topk_attn_last_selection_records")
+    return [tuple(buf[4 * i:4 * i + 4]) for i in range(n_heads_total)]
 
 
 def topk_attn_debug_force_redo(h, enable: bool):

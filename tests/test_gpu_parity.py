@@ -156,6 +156,35 @@ def test_ties_lower_position_wins(path, N, k, dtype):
     run_case(q, K, V, dtype, k, path=path, label="ties", exact_inputs=True)
 
 
+@pytest.mark.parametrize("dtype,N,k,spread", [(wl.F16, 200000, 5000, 1), (wl.BF16, 150001, 2000, 1), (wl.F16, 60000, 6000, 1), (wl.F16, 300000, 9000, 1), (wl.BF16, 400000, 3000, 1)])
+def test_many_ties_around_the_kth_score(dtype, N, k, spread):
+    """Integer scores: hundreds to thousands of keys share the k-th score and its neighbours, so the bin
+    of the k-th score holds far more candidates than one per thread of the finishing workgroup (they are
+    sorted into sub-bins first, and the sub-bin of the k-th score is ranked with the position tie-break).
+    The scores are exact in fp32: the selection must equal the oracle's, ties to the lower position."""
+    g = np.random.default_rng(N + k)
+    Hq, Hkv, d = 8, 2, 128
+    q = wl.quantize(g.integers(-spread, spread + 1, (Hq, d)).astype(np.float32), dtype)
+    K = wl.quantize(g.integers(-spread, spread + 1, (Hkv, N, d)).astype(np.float32), dtype)
+    V = wl.quantize(g.standard_normal((Hkv, N, d)).astype(np.float32), dtype)
+    ref = c_oracle.topk_attention(q, K, V, dtype, k)
+    cache = ta.TopkAttnCache(1, 1, Hq, Hkv, d, N, k, dtype)
+    try:
+        cache.set_path(ta.PATH_FILTER)
+        cache.append(0, 0, H.to_torch(K, dtype, DEV), H.to_torch(V, dtype, DEV), head_major=True)
+        qd = H.to_torch(q, dtype, DEV)[None].contiguous()
+        out, idx, vals, lse = cache.decode(0, qd, k)
+        torch.cuda.synchronize()
+        rec = ta.topk_attn_last_selection_records(cache.h, Hq)
+        assert any(r[0] == 0 and r[3] > 256 for r in rec), f"no head with a crowded boundary bin: {rec}"
+        H.check_against_oracle(out[0].cpu().numpy(), idx[0].cpu().numpy(), vals[0].cpu().numpy(), lse[0].cpu().numpy(),
+                               ref, np.full(Hq, 1e-30), k, H.out_tolerance(dtype), float(np.abs(wl.widen(V, dtype)).max()),
+                               "ties around the k-th score")
+        print("boundary bins:", sorted(r[3] for r in rec), "states", sorted(r[0] for r in rec), flush=True)
+    finally:
+        cache.close()
+
+
 @pytest.mark.parametrize("N,redone", [(30000, False), (150000, True)])
 def test_all_keys_identical(N, redone):
     """Every score equal: positions 0..k-1 win and out is their mean.  Every key is a candidate: the
