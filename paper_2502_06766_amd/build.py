@@ -10,6 +10,9 @@ CSRC = os.path.join(HERE, "csrc")
 OBJ_DIR = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libtopk_attn.so")
 SOURCES = ["api.hip", "scan.hip", "select.hip", "gather.hip", "index8.hip", "tail.hip", "pages.hip"]
+# measurement program of its own (streaming-read ceiling over launch shapes), built beside the library
+PROBE_SRC = "read_probe_sweep.hip"
+PROBE = os.path.join(OBJ_DIR, "read_probe_sweep")
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
          # packed-fp32 VALU forms are kept off on the test machines
@@ -23,7 +26,7 @@ def source_hash() -> str:
     inc = os.path.join(os.path.dirname(HERE), "include")
     files = [os.path.join(CSRC, f) for f in os.listdir(CSRC)] + [os.path.join(inc, f) for f in os.listdir(inc)]
     for f in sorted(files):
-        if f.endswith((".hip", ".h")):
+        if f.endswith((".hip", ".h")) and os.path.basename(f) != PROBE_SRC:
             h.update(os.path.basename(f).encode())
             h.update(open(f, "rb").read())
     return h.hexdigest()[:16]
@@ -52,6 +55,7 @@ def build(extra_flags=(), verbose: bool = False) -> str:
     with ThreadPoolExecutor(max_workers=7) as ex:
         objs = list(ex.map(lambda s: _compile(s, flags), SOURCES))
     subprocess.check_call([HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB, *objs])
+    subprocess.check_call([HIPCC, *FLAGS, os.path.join(CSRC, PROBE_SRC), "-o", PROBE])
     if verbose:
         print("built", LIB)
     return LIB
