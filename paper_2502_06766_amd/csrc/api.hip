@@ -108,10 +108,14 @@ WsLayout ws_layout(const topk_attn_config* c) {
         w.cand_cap = (int)(((int64_t)w.cand_cap + kMaxSeg * kCandChunk - 1) / (kMaxSeg * kCandChunk) * (kMaxSeg * kCandChunk));
     }
     const int64_t max_w = c->max_window < c->max_tokens ? c->max_window : c->max_tokens;
-    // partial sums per head: the tail of the filtered path makes up to one per 128 selected rows (and never
-    // more than scan workgroups fed the head), the gather one per 256; the window adds one per 256 tokens
-    w.n_chunk_cap = (int)(((int64_t)c->max_k + 127) / 128 + (max_w + kGatherRows - 1) / kGatherRows);
     w.hist_cap = (int)(seg_max / 4);            // scan workgroups per head (four wave segments each)
+    // partial sums per head: the tail of the filtered path makes up to one per 128 selected rows, at least one per
+    // four scan workgroups (and never more than scan workgroups fed the head), the gather one per 256; the window
+    // adds one per 256 tokens
+    {
+        const int64_t by_k = ((int64_t)c->max_k + 127) / 128, by_wg = (w.hist_cap + 3) / 4;
+        w.n_chunk_cap = (int)((by_k > by_wg ? by_k : by_wg) + (max_w + kGatherRows - 1) / kGatherRows);
+    }
     size_t o = 0;
     auto take = [&](size_t bytes) { size_t at = o; o = align_up(o + bytes); return at; };
     w.len = take((size_t)c->n_layers * c->n_seqs * sizeof(int32_t));
@@ -613,9 +617,11 @@ static int decode_impl(topk_attn_t* h, int layer, const void* q, int n_queries, 
         }
         if (fast) fast = choose_segments(h, s, nmax, c_hi, &s.n_seg, &s.seg_cap);
         s.cand_est = (int)(c_hi < INT32_MAX ? c_hi : INT32_MAX);
-        if (fast) {     // tail: about 128 selected rows per workgroup, whole scan workgroups each
+        if (fast) {     // tail: about 128 selected rows per workgroup and at most four scan workgroups each
+            // (a tail workgroup walks its scan workgroups one after the other: dependent loads each time)
             const int n_wg = s.n_seg / 4;
             int want = (k + 127) / 128;
+            if (want < (n_wg + 3) / 4) want = (n_wg + 3) / 4;
             want = want < 1 ? 1 : (want > n_wg ? n_wg : want);
             s.tail_spw = (n_wg + want - 1) / want;
             s.tail_wgs = (n_wg + s.tail_spw - 1) / s.tail_spw;

@@ -15,17 +15,20 @@
 //                       from the counts, copies bin B's candidates to the head's boundary
 //                       list, and accumulates the softmax-weighted value rows of its winners
 //                       (weights relative to the head's largest score, which the scan reported).
-//   tail_finish_kernel  one workgroup per head: exact selection (radix select, lower
-//                       position wins ties) of the missing winners among the boundary list,
-//                       their value rows, the sum of all partials in a fixed order,
-//                       normalisation, padding of idx / vals.
+//   tail_finish_kernel  one workgroup per head: the missing winners among the boundary list (ranked
+//                       by direct comparison of composite keys, lower position wins ties; a
+//                       crowded list is first sorted into sub-bins over its own score range, a
+//                       list of mostly tied scores goes through the radix select), their value
+//                       rows, the sum of all partials in a fixed order, normalisation, padding
+//                       of idx / vals.
 //
 // A head whose candidate list is unusable (a segment overflowed, the sampled threshold came
 // out above the k-th score, or its sequence cannot be filtered at all) is redone exactly
-// inside the same two launches: the workgroups of the first kernel rescore all keys of the
-// head's KV head with the MFMA tile routine of the scan (once per group of up to four heads
-// that share the keys) into the score buffer, and the second kernel selects over the full
-// score row and gathers the k rows itself.  Nothing is launched for the common case.
+// inside the same two launches (modes RESCAN and DENSE below): the workgroups of the first
+// kernel score the keys of their scan workgroups again with the MFMA tile routine of the scan,
+// and either sort them from the k-th score's bin up (known from the scan's counts) into the
+// head's segments and go on as with a list, or write all scores to the score buffer, over
+// which the second kernel selects densely.  Nothing is launched for the common case.
 #include "device_utils.h"
 #include "internal.h"
 #include "scan_common.h"
