@@ -172,7 +172,7 @@ int topk_attn_decode(topk_attn_t* h, int layer, const void* q, int k, float* out
  * Llama-8B-shaped layer of 128k tokens at k = 2048 fits, a million-token layer does not.
  * All calls on one GPU, from whatever handle, share the one array: the call clears the words
  * that must start at zero itself, and two such calls that overlap in time on one GPU race. */
-#define TOPK_ATTN_STATIC_SCRATCH_BYTES ((size_t)48 << 20)
+#define TOPK_ATTN_STATIC_SCRATCH_BYTES ((size_t)96 << 20)
 int topk_attn_decode_static(topk_attn_t* h, int layer, const void* q, int k, float* out, int32_t* idx,
                             float* vals, float* lse, void* hip_stream);
 

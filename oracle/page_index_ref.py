@@ -1,8 +1,8 @@
 """CPU oracle for the coarse page index of the sub-linear search (NumPy, float64).  TEST INFRASTRUCTURE.
 
 The methodology section of the paper leaves the search index open; the point of the method is that
-the k best keys of a query can be found without reading every key ("sublinear time" in its
-introduction).  The index here is a plain one that lets whole groups of keys be ruled out exactly:
+the k best keys of a query can be found without reading every key (the sub-linear search its
+introduction aims at).  The index here is a plain one that lets whole groups of keys be ruled out exactly:
 the cache is cut into pages of `page` consecutive tokens, and each page keeps a centre c (the mean of
 its keys) and a radius r (the largest Euclidean distance of one of its keys from the centre).  By the
 Cauchy-Schwarz inequality no key of the page can score more than

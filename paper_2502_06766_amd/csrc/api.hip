@@ -222,7 +222,7 @@ __global__ void zero_words_kernel(uint32_t* p, size_t n) {
 // Built-in scratch of topk_attn_decode_static: the per-call buffers of one decode (everything the
 // handle's workspace holds except the cache lengths) for callers that bring no workspace of
 // their own to that call.  One copy per GPU, at its own address, held until the process ends.
-constexpr size_t kStaticScratchBytes = (size_t)48 << 20;
+constexpr size_t kStaticScratchBytes = (size_t)96 << 20;
 static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
 
 // Device address of `scratch` on each GPU (the array's name is only a host-side stand-in for

@@ -1,8 +1,8 @@
 // Coarse page index for the sub-linear search (the paper's methodology section leaves the kind of
-// search index open; its introduction promises retrieval "in sublinear time"): the cache is cut into
-// pages of 64 consecutive tokens (one tile of the key scan), and each page keeps a centre c (the
-// mean of its keys, rounded to the storage type) and a radius r >= |k - c| for every key k of the
-// page.  By the Cauchy-Schwarz inequality no key of the page scores more than q . c + |q| r, so a
+// search index open; its introduction states the aim of finding the k best keys without reading all of
+// them): the cache is cut into pages of 64 consecutive tokens (one tile of the key scan), and each
+// page keeps a centre c (the mean of its keys, rounded to the storage type) and a radius
+// r >= |k - c| for every key k of the page.  By the Cauchy-Schwarz inequality no key of the page scores more than q . c + |q| r, so a
 // page whose bound stays below a head's candidate threshold cannot hold a candidate of that head,
 // and the key scan skips the pages that no head of the KV group needs.  The result is exactly that
 // of the plain scan.  With a bound scale beta < 1 the radius is shrunk: fewer pages are read and
