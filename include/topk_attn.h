@@ -176,8 +176,8 @@ int topk_attn_decode(topk_attn_t* h, int layer, const void* q, int k, float* out
 int topk_attn_decode_static(topk_attn_t* h, int layer, const void* q, int k, float* out, int32_t* idx,
                             float* vals, float* lse, void* hip_stream);
 
-/* Decode step with the recent-token window of Algorithm 1 (its K_gen / V_gen, "resembles
- * windowed attention"): for each sequence the last min(window, N_b) cached tokens are always
+/* Decode step with the recent-token window of Algorithm 1 (its K_gen / V_gen, which the
+ * paper likens to windowed attention): for each sequence the last min(window, N_b) cached tokens are always
  * attended, the k-nearest-neighbour search runs over the older prefix only
  * (k_eff = min(k, N_b - window)), and one softmax spans the retrieved and the window scores
  * (the algorithm's window line is read as a joint softmax over both parts applied to
@@ -187,8 +187,8 @@ int topk_attn_decode_window(topk_attn_t* h, int layer, const void* q, int k, int
                             int32_t* idx, float* vals, float* lse, void* hip_stream);
 
 /* Several queries per sequence against the cache in one pass over the keys (a chunk of M
- * consecutive queries, as in building the cache chunk by chunk -- the paper's "top-k at
- * cache construction time" of the section on million-token cache generation -- or in
+ * consecutive queries, as in building the cache chunk by chunk -- the paper's suggestion to use top-k
+ * attention when the cache is built, in the section on million-token cache generation -- or in
  * verifying drafted tokens): each of the M queries of a sequence gets its own exact
  * top-k search, softmax and weighted value sum, exactly as if topk_attn_decode_window had
  * been called once per query, but the keys are read once per block of up to 32

@@ -1,8 +1,7 @@
 """CPU oracle for the compressed (int8) key index.  TEST INFRASTRUCTURE.
 
-The paper's search index "can be as simple as a list (for exact nearest neighbors)" or an
-approximate structure (methodology section, the paragraph on converting the key tensors
-into a search index).  The index checked here is the usual compressed-list kind of vector
+The paper's search index may be a plain list (exact search) or an approximate structure
+(methodology section, the paragraph on converting the key tensors into a search index).  The index checked here is the usual compressed-list kind of vector
 databases: every key row is stored a second time as int8 codes with one fp32 scale per
 row, the query is coded the same way, approximate scores come from the integer dot
 product, and a candidate set chosen by approximate score is re-scored exactly before the
