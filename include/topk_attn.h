@@ -58,9 +58,10 @@ enum {
                                    does not apply (short caches, dense k, several queries) the exact
                                    path runs instead */
     TOPK_ATTN_PATH_PAGES = 4    /* sub-linear search: the key scan skips the pages the coarse page index
-                                   rules out (needs index_kind = TOPK_ATTN_INDEX_PAGES).  Exact: same
-                                   result as the plain scan, unless topk_attn_set_page_bound_scale has
-                                   shrunk the bound.  Where the filtered scan does not apply (short
+                                   rules out (needs index_kind = TOPK_ATTN_INDEX_PAGES).  Exact: the
+                                   selection of the plain scan (out may differ in the last bits: the
+                                   partial sums are added in another order), unless
+                                   topk_attn_set_page_bound_scale has shrunk the bound.  Where the filtered scan does not apply (short
                                    caches, dense k, several queries, a window) the exact path runs */
 };
 

@@ -25,7 +25,7 @@ inline size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
 inline int elem_bytes(int dtype) { return dtype == TOPK_ATTN_F32 ? 4 : 2; }
 
 struct WsLayout {
-    size_t len, thr, bins, samp, seg_cnt, seg_max, seg_cnt2, flags, hmax, fallback, tailrec, qscale, q8, page_mask, hist, cand, bnd, scores, sel_idx, sel_val, part_acc, part_l, part_m, total;
+    size_t len, thr, bins, samp, seg_cnt, seg_max, seg_cnt2, flags, hmax, fallback, tailrec, qscale, q8, page_mask, page_cnt, page_list, hist, cand, bnd, scores, sel_idx, sel_val, part_acc, part_l, part_m, total;
     int cand_cap, bnd_cap, n_chunk_cap, hist_cap, page_words;
 };
 
@@ -132,8 +132,10 @@ WsLayout ws_layout(const topk_attn_config* c) {
     w.qscale = take(BH * sizeof(float));
     w.q8 = take(BH * (size_t)c->head_dim);
     w.page_words = (int)((page_cap_of(c) + 63) / 64);
-    w.page_mask = take(c->index_kind == TOPK_ATTN_INDEX_PAGES
-                           ? (size_t)c->n_seqs * c->n_kv_heads * (size_t)w.page_words * sizeof(uint64_t) : 0);
+    const size_t page_streams = c->index_kind == TOPK_ATTN_INDEX_PAGES ? (size_t)c->n_seqs * c->n_kv_heads : 0;
+    w.page_mask = take(page_streams * (size_t)w.page_words * sizeof(uint64_t));
+    w.page_cnt = take(page_streams * sizeof(uint32_t));
+    w.page_list = take(page_streams * (size_t)w.page_words * 64 * sizeof(int32_t));
     w.hist = take(BH * (size_t)w.hist_cap * kTailBins * sizeof(uint32_t));
     w.cand = take(BH * (size_t)w.cand_cap * sizeof(uint64_t));
     w.bnd = take(BH * (size_t)w.bnd_cap * sizeof(uint64_t));
@@ -494,6 +496,8 @@ static void fill_call(topk_attn_t* h, int layer, const void* q, int k, int n_que
         b->page_balls = reinterpret_cast<const float*>(base + page_centres_bytes(&c)) + layer_streams * (size_t)page_cap_of(&c) * 2;
     }
     b->page_mask = reinterpret_cast<uint64_t*>(ws + h->ws.page_mask);
+    b->page_cnt = reinterpret_cast<uint32_t*>(ws + h->ws.page_cnt);
+    b->page_list = reinterpret_cast<int32_t*>(ws + h->ws.page_list);
     b->q8 = reinterpret_cast<int8_t*>(ws + h->ws.q8);
     b->qscale = reinterpret_cast<float*>(ws + h->ws.qscale);
     b->len = reinterpret_cast<int32_t*>(ws_len + h->ws.len) + (size_t)layer * c.n_seqs;
@@ -653,7 +657,7 @@ static int decode_impl(topk_attn_t* h, int layer, const void* q, int n_queries, 
         if (e == hipSuccess) e = launch_select_candidates(s, b, st);   // redoes unusable heads itself
     } else if (fast) {
         s.paged = want_pages && tail_supported(s) ? 1 : 0;
-        s.no_rescan = s.paged && h->page_beta < 1.0f ? 1 : 0;
+        s.no_rescan = s.paged;      // the paged scan deals its tiles to the waves by rank among the pages kept
         e = launch_scan_sample(s, b, nmax, st);
         if (e == hipSuccess) e = launch_threshold(s, b, nmax, st);
         if (e == hipSuccess && s.paged) e = launch_page_filter(s, b, h->page_beta, st);

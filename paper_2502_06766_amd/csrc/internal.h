@@ -36,7 +36,7 @@ struct Shape {
     int indexed;      // the scan reads the int8 key index; candidates are re-scored exactly afterwards
     int force_redo;   // measurement aid: treat every head as not filterable (exact redo of all heads)
     int paged;        // the scan skips the pages the coarse page index rules out
-    int no_rescan;    // the pages skipped may hold candidates (approximate page bound): an unusable list is redone densely
+    int no_rescan;    // an unusable list is redone densely (the per-bin counts of a paged scan are not those of the plain tile order)
     int page_cap;     // pages per key stream the page index has room for (ceil(Ncap / 64))
     int page_words;   // 64-bit words of the page mask per key stream
     int cand_est;     // candidates per head expected at most (sizes the selection's register cache)
@@ -82,6 +82,8 @@ struct Bufs {
     const void* page_centres;  // this layer's page centres [Bc][Hkv][page_cap][D] (cache dtype), or null
     const float* page_balls;   // this layer's [Bc][Hkv][page_cap][2]: radius of the page's ball, norm of its centre
     uint64_t* page_mask;       // [B][Hkv][page_words] one bit per page: 1 = the scan reads it
+    uint32_t* page_cnt;        // [B][Hkv] pages the scan reads
+    int32_t* page_list;        // [B][Hkv][64 * page_words] their numbers, ascending
     float* scores;          // [B*Hq][Ncap] full score buffer
     int32_t* sel_idx;       // [B*Hq][k]
     float* sel_val;         // [B*Hq][k]

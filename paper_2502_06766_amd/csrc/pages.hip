@@ -11,6 +11,9 @@
 //   page_ball_kernel    index build: centre, radius and |c| of the pages an append touched
 //   page_filter_kernel  per decode: one bit per page and KV head (1 = scan it), 64 pages per wave
 //                       scored against the group's queries with the MFMA tile routine of the scan
+//   page_list_kernel    the numbers of the pages kept, ascending, and their count per key stream: the
+//                       scan deals them to its waves by rank, so that every wave reads as many pages
+//                       as any other whatever the pattern of the pages kept
 #include "device_utils.h"
 #include "internal.h"
 #include "scan_tiles.h"
@@ -153,6 +156,41 @@ __global__ void __launch_bounds__(256) page_filter_kernel(Shape sh, Bufs bf, flo
     if (lane == 0) *out = m;
 }
 
+// One workgroup per key stream: compacts the mask into the ascending list of the pages kept.
+constexpr int kListThreads = 1024;
+__global__ void __launch_bounds__(kListThreads) page_list_kernel(Shape sh, Bufs bf) {
+    __shared__ uint32_t wave_tot[kListThreads / kWave];
+    __shared__ uint32_t carry;
+    const int tid = threadIdx.x, lane = lane_id(), wave = tid >> 6;
+    const int64_t stream = (int64_t)blockIdx.y * sh.Hkv + blockIdx.x;
+    const uint64_t* pm = bf.page_mask + stream * sh.page_words;
+    int32_t* list = bf.page_list + stream * (int64_t)sh.page_words * 64;
+    if (tid == 0) carry = 0u;
+    __syncthreads();
+    for (int w0 = 0; w0 < sh.page_words; w0 += kListThreads) {       // (uniform trip count)
+        const int w = w0 + tid;
+        uint64_t m = w < sh.page_words ? pm[w] : 0ull;
+        const uint32_t c = (uint32_t)__popcll(m);
+        uint32_t inc = c;
+        for (int o = 1; o < kWave; o <<= 1) {
+            const uint32_t v = __shfl_up(inc, o, kWave);
+            if (lane >= o) inc += v;
+        }
+        if (lane == kWave - 1) wave_tot[wave] = inc;
+        __syncthreads();
+        uint32_t at = carry + inc - c;
+        for (int i = 0; i < wave; ++i) at += wave_tot[i];
+        while (m) {
+            list[at++] = (int32_t)(w * 64 + __builtin_ctzll(m));
+            m &= m - 1ull;
+        }
+        __syncthreads();
+        if (tid == kListThreads - 1) carry = at;                      // the last thread's end = all pages so far
+        __syncthreads();
+    }
+    if (tid == 0) bf.page_cnt[stream] = carry;
+}
+
 hipError_t launch_page_balls(int dtype, int D, const void* K, int64_t Ncap, int64_t Pcap, int Hkv, int B,
                              const int32_t* len_dev, int64_t row0, int64_t n_new, void* centres, float* balls, hipStream_t st) {
     if (n_new <= 0) return hipSuccess;
@@ -186,6 +224,9 @@ hipError_t launch_page_filter(const Shape& s, const Bufs& b, float beta, hipStre
     else if (s.dtype == DT_BF16 && s.D == 32) TKA_PF(DT_BF16, 32);
     else return hipErrorInvalidValue;
 #undef TKA_PF
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(page_list_kernel, dim3((unsigned)s.Hkv, (unsigned)s.B), dim3(kListThreads), 0, st, s, b);
     return hipGetLastError();
 }
 

@@ -131,22 +131,63 @@ scan_mfma_kernel(Shape sh, Bufs bf, int tiles_per_wave, float* dst) {
     if (MODE == MODE_SAMPLE) {
         walk_tiles<ScanPipelined<D>::value>(tile, tile_end, tile_step, ba, bb, load_rows, use);
     } else if (MODE == MODE_FILTER && PAGED) {
-        // 64 of my tiles at a time: lane i looks up the bit of tile `tile + i * tile_step`; the tiles that
-        // are left are scored one after the other (the other waves of the compute unit cover the latency)
-        const uint64_t* pm = bf.page_mask + ((int64_t)b * sh.Hkv + kvh) * sh.page_words;
+        // The pages kept, ascending, are dealt to the wave segments by rank: segment sid takes the pages of
+        // ranks sid, sid + n_seg, ... (64 of them looked up at a time, one per lane), so every wave reads as
+        // many tiles as any other.  They are walked like the plain sequence (next tile's loads in flight
+        // while the current one is multiplied and filtered; one buffer at head_dim 256).
+        const int64_t stream = (int64_t)b * sh.Hkv + kvh;
+        const int32_t* plist = bf.page_list + stream * (int64_t)sh.page_words * 64;
+        const int64_t n_kept = (int64_t)bf.page_cnt[stream];
         const int64_t n_whole = N / 64;
         const uint32_t lane_off = (uint32_t)(((lane & 15) * D + (lane >> 4) * 8) * 2);
-        for (; tile < tile_end; tile += 64 * tile_step) {
-            const int64_t mine = tile + lane * tile_step;
-            const bool alive = mine < tile_end && ((pm[mine >> 6] >> (mine & 63)) & 1ull) != 0ull;
-            uint64_t m = __ballot(alive);
-            while (m) {
-                const int bit = __builtin_ctzll(m);
-                m &= m - 1ull;
-                const int64_t ti = tile + bit * tile_step;
-                if (ti < n_whole) tile_load_full<DT, D>(Kh + ti * (64 * D * 2), lane_off, ba.b);
-                else load_rows(ba, ti);
-                use(ba, ti);
+        int64_t base = tile;                     // rank of the first page of the current group of 64
+        int32_t mine = 0;                        // lane i: page of rank base + i * tile_step
+        int have = 0, at = 0;                    // pages in the group, pages of it already taken
+        auto look_up = [&]() {
+            const int64_t r = base + lane * tile_step;
+            mine = r < n_kept ? plist[r] : 0;
+            const int64_t left = (n_kept - base + tile_step - 1) / tile_step;
+            have = (int)(left < 64 ? left : 64);
+            at = 0;
+        };
+        if (base < n_kept) look_up();
+        auto next = [&]() -> int64_t {           // the wave's next tile to read, or -1 (wave-uniform)
+            if (at == have) {
+                base += 64 * tile_step;
+                if (have < 64 || base >= n_kept) return -1;
+                look_up();
+            }
+            return (int64_t)__builtin_amdgcn_readlane(mine, at++);
+        };
+        auto load_any = [&](TileB& t, int64_t ti) {
+            if (ti < n_whole) tile_load_full<DT, D>(Kh + ti * (64 * D * 2), lane_off, t.b);
+            else load_rows(t, ti);
+        };
+        if (base < n_kept) {
+            int64_t t0 = next();
+            if (ScanPipelined<D>::value) {
+                if (t0 >= 0) {
+                    load_any(ba, t0);
+                    while (true) {
+                        const int64_t t1 = next();
+                        load_any(bb, t1 >= 0 ? t1 : t0);       // past the end: a tile the wave already had
+                        __builtin_amdgcn_sched_barrier(0);
+                        use(ba, t0);
+                        if (t1 < 0) break;
+                        const int64_t t2 = next();
+                        load_any(ba, t2 >= 0 ? t2 : t1);
+                        __builtin_amdgcn_sched_barrier(0);
+                        use(bb, t1);
+                        if (t2 < 0) break;
+                        t0 = t2;
+                    }
+                }
+            } else {
+                for (; t0 >= 0; t0 = next()) {
+                    load_any(ba, t0);
+                    __builtin_amdgcn_sched_barrier(0);
+                    use(ba, t0);
+                }
             }
         }
     } else {

@@ -3,7 +3,7 @@
 * Index contents: every page's ball (centre, radius) encloses the page's keys and is about as tight
   as the ball around the mean that oracle/page_index_ref.py computes, after appends in pieces.
 * The search is exact: index sets, vals, out, lse judged against the exact oracle like the plain
-  path, and bit-identical to the plain path on the same handle; the pages read include every page
+  path, and the same selection as the plain path on the same handle; the pages read include every page
   that holds a selected key (oracle) and, on a cache with topical runs, are a fraction of the cache.
 * With a shrunk bound the search is approximate: recall@k against the exact oracle.
 """
@@ -130,9 +130,15 @@ def run_pages_case(q, K, V, dtype, k, beta=1.0, label="", margin=True):
                 H.check_against_oracle(out, idx, vals, lse, ref, delta, k_eff, H.out_tolerance(dtype), vmax, label)
             else:
                 H.check_unmargined((out, idx, vals, lse), q, K, V, dtype, k, 0, label)
-            # same candidates as the plain scan: bit-identical selection and output
+            # same candidates as the plain scan: the same selection; the pages kept are dealt to the waves in
+            # another order than the tiles of the plain scan, so the fp32 sums may differ in their last bits
             assert torch.equal(torch.sort(res[1], dim=2).values, torch.sort(plain[1], dim=2).values), f"{label}: index sets differ from the plain scan's"
-            assert torch.equal(res[0], plain[0]) and torch.equal(res[3], plain[3]), f"{label}: out differs from the plain scan's"
+            assert torch.equal(torch.sort(res[2], dim=2).values, torch.sort(plain[2], dim=2).values), f"{label}: vals differ from the plain scan's"
+            np.testing.assert_allclose(res[0].cpu().numpy(), plain[0].cpu().numpy(), rtol=2e-5, atol=1e-6, err_msg=label)
+            np.testing.assert_allclose(res[3].cpu().numpy(), plain[3].cpu().numpy(), rtol=1e-6, err_msg=label)
+            again = cache.decode(0, qd, k)                      # and the same bits every time
+            torch.cuda.synchronize()
+            assert all(torch.equal(a, b) for a, b in zip(again, res)), f"{label}: two runs differ"
             # no page that holds a selected key was skipped: at least those pages were read
             need = pg.pages_holding_topk(ref[1], (N + PAGE - 1) // PAGE, PAGE, G)
             assert read >= need.sum(), f"{label}: fewer pages read than hold selected keys"
