@@ -55,6 +55,8 @@ def main() -> int:
                     help="queries per step (a causal chunk through topk_attn_decode_multi); 1 is the metric's workload")
     ap.add_argument("--index", action="store_true",
                     help="approximate search through the int8 key index (exact refinement); not the metric's workload")
+    ap.add_argument("--window", type=int, default=0,
+                    help="recent tokens always attended and left out of the search (topk_attn_decode_window); not the metric's workload")
     ap.add_argument("--pages", action="store_true",
                     help="sub-linear search through the page index (exact with --beta 1); not the metric's workload")
     ap.add_argument("--beta", type=float, default=1.0, help="scale of the page radius in the page bound (--pages)")
@@ -82,7 +84,7 @@ def main() -> int:
         return 1
     dev = torch.device("cuda", 0)
     w = {"c1": wl.C1, "c2": wl.C2, "c3": wl.C3, "c4": wl.C4, "c5": wl.C5, "c6": wl.C6}[args.workload]
-    default = args.workload == "c3" and not args.tokens and not args.k and not args.force_redo and not args.pages   # the metric's workload as it stands
+    default = args.workload == "c3" and not args.tokens and not args.k and not args.force_redo and not args.pages and not args.window   # the metric's workload as it stands
     if args.tokens:
         w = w.scaled(args.tokens)
     N, k, d, Hq, Hkv, B = w.n_tokens, args.k or w.k, w.head_dim, w.n_q_heads, w.n_kv_heads, w.n_seqs
@@ -98,7 +100,7 @@ def main() -> int:
     gen_s = time.time() - t0
 
     M = max(1, args.queries)
-    cache = ta.TopkAttnCache(L, B, Hq, Hkv, d, N, k, w.dtype, max_queries=M,
+    cache = ta.TopkAttnCache(L, B, Hq, Hkv, d, N, k, w.dtype, max_queries=M, max_window=args.window,
                              index_kind=ta.INDEX_INT8 if args.index else ta.INDEX_PAGES if args.pages else ta.INDEX_NONE)
     if args.index:
         cache.set_path(ta.PATH_INDEX)
@@ -128,10 +130,12 @@ def main() -> int:
     torch.cuda.synchronize()
 
     def step(i):
-        if M == 1:
+        if M == 1 and args.window:
+            ta.topk_attn_decode_window(cache.h, i % L, qd.data_ptr(), k, args.window, out.data_ptr(), idx.data_ptr(), 0, 0, stream)
+        elif M == 1:
             ta.topk_attn_decode(cache.h, i % L, qd.data_ptr(), k, out.data_ptr(), idx.data_ptr(), 0, 0, stream)
         else:
-            ta.topk_attn_decode_multi(cache.h, i % L, qd.data_ptr(), M, True, k, 0, out.data_ptr(), idx.data_ptr(),
+            ta.topk_attn_decode_multi(cache.h, i % L, qd.data_ptr(), M, True, k, args.window, out.data_ptr(), idx.data_ptr(),
                                       0, 0, stream)
 
     for i in range(args.warmup):
@@ -227,6 +231,7 @@ def main() -> int:
                    (f"page index, bound scale {args.beta:g}" + (" (exact)" if args.beta == 1.0 else " (approximate)")) if args.pages else "exact",
                    **({"pages_read": pages_read, "pages_total": pages_total} if args.pages else {}),
                    **({"sigma": args.sigma or wl.CLUSTER_SIGMA} if args.workload == "c6" else {}),
+                   **({"window": args.window} if args.window else {}),
                    **({"forced": "every head redone exactly (worst case of the filtered path)"} if args.force_redo else {})},
         "scores_per_sec": B * M * Hq * N / (ms_per_step * 1e-3),
         "step_hbm_gbps": alg_bytes / (ms_per_step * 1e-3) / 1e9,

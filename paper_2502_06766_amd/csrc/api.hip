@@ -666,6 +666,7 @@ static int decode_impl(topk_attn_t* h, int layer, const void* q, int n_queries, 
         if (e == hipSuccess && timed) e = hipEventRecord(h->ev[2 * h->ev_used + 1], st);
         if (e == hipSuccess && timed) h->ev_used++;
         if (tail_supported(s)) {
+            if (e == hipSuccess && window > 0) e = launch_window_partials(s, b, s.tail_wgs, st);   // merged by the tail's finish
             if (e == hipSuccess) e = launch_tail(s, b, st);            // selection and gather; redoes unusable heads itself
             tail_done = true;
         } else if (e == hipSuccess) {

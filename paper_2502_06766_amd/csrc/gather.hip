@@ -263,6 +263,22 @@ __global__ void __launch_bounds__(256) gather_combine_kernel(Shape sh, Bufs bf, 
     }
 }
 
+// Partial sums over the recent-token window of every head into the slots slot0, slot0 + 1, ... (one per
+// kGatherRows tokens), each relative to its own largest score.
+hipError_t launch_window_partials(const Shape& s, const Bufs& b, int slot0, hipStream_t st) {
+    const float scale_log2e = (1.0f / sqrtf((float)s.D)) * 1.4426950408889634f;
+    const int nwin = (s.window + kGatherRows - 1) / kGatherRows;
+    if (nwin == 0) return hipSuccess;
+    dim3 wgrid((unsigned)nwin, (unsigned)s.Hq, (unsigned)s.B);
+    if (s.dtype == DT_F32)
+        hipLaunchKernelGGL((window_partial_kernel<DT_F32>), wgrid, dim3(256), 0, st, s, b, scale_log2e, slot0);
+    else if (s.dtype == DT_F16)
+        hipLaunchKernelGGL((window_partial_kernel<DT_F16>), wgrid, dim3(256), 0, st, s, b, scale_log2e, slot0);
+    else
+        hipLaunchKernelGGL((window_partial_kernel<DT_BF16>), wgrid, dim3(256), 0, st, s, b, scale_log2e, slot0);
+    return hipGetLastError();
+}
+
 hipError_t launch_gather(const Shape& s, const Bufs& b, hipStream_t st) {
     const float scale = 1.0f / sqrtf((float)s.D);
     const float scale_log2e = scale * 1.4426950408889634f;
@@ -280,14 +296,7 @@ hipError_t launch_gather(const Shape& s, const Bufs& b, hipStream_t st) {
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     if (nwin > 0) {
-        dim3 wgrid((unsigned)nwin, (unsigned)s.Hq, (unsigned)s.B);
-        if (s.dtype == DT_F32)
-            hipLaunchKernelGGL((window_partial_kernel<DT_F32>), wgrid, dim3(256), 0, st, s, b, scale_log2e, nch);
-        else if (s.dtype == DT_F16)
-            hipLaunchKernelGGL((window_partial_kernel<DT_F16>), wgrid, dim3(256), 0, st, s, b, scale_log2e, nch);
-        else
-            hipLaunchKernelGGL((window_partial_kernel<DT_BF16>), wgrid, dim3(256), 0, st, s, b, scale_log2e, nch);
-        e = hipGetLastError();
+        e = launch_window_partials(s, b, nch, st);
         if (e != hipSuccess) return e;
     }
     if (nwin > 0)

@@ -463,13 +463,39 @@ __global__ void __launch_bounds__(NT) tail_finish_kernel(Shape sh, Bufs bf, floa
     for (int i = 0; i < CIMAX; ++i) ent[i] = (i * NT + tid < sh.bnd_cap) ? bf.bnd[bh * (int64_t)sh.bnd_cap + i * NT + tid] : 0ull;
     int32_t* idx = bf.sel_idx + bh * sh.k;
     float* vals = bf.sel_val + bh * sh.k;
-    if (rec.state == TAIL_EMPTY || k_eff == 0) {
-        pad_outputs(0, sh.k, idx, vals);
-        for (int t = tid; t < D; t += NT) bf.out[bh * D + t] = 0.f;
-        if (tid == 0) {
-            bf.hmax[bh] = -INFINITY;
-            if (bf.lse) bf.lse[bh] = -INFINITY;
+    // With a recent-token window (always attended, outside the search) the window's partial sums, each
+    // relative to its own largest score, sit in the slots behind the first kernel's: one softmax over both
+    // parts by the usual rescaling.  `at`, `lt`: this thread's output element and the weight total of the
+    // retrieved part relative to `m_top` (lt == 0: nothing retrieved).
+    const int n_win = (sh.window + kGatherRows - 1) / kGatherRows;
+    auto write_out = [&](float at, float lt, float m_top) {
+        const int e = tid % D;
+        float M = lt > 0.f ? m_top : -INFINITY;
+        const float* pl = bf.part_l + bh * sh.n_chunk_cap + sh.tail_wgs;
+        const float* pm = bf.part_m + bh * sh.n_chunk_cap + sh.tail_wgs;
+        const float* pa = bf.part_acc + (bh * sh.n_chunk_cap + sh.tail_wgs) * (int64_t)D + e;
+        for (int s = 0; s < n_win; ++s)
+            if (pl[s] > 0.f) M = fmaxf(M, pm[s]);
+        if (n_win > 0 && M > -INFINITY) {
+            const float f0 = lt > 0.f ? exp2f((m_top - M) * scale_log2e) : 0.f;
+            at *= f0; lt *= f0;
+            for (int s = 0; s < n_win; ++s) {
+                const float ls = pl[s];
+                if (ls > 0.f) {
+                    const float f = exp2f((pm[s] - M) * scale_log2e);
+                    lt = fmaf(ls, f, lt);
+                    at = fmaf(pa[(int64_t)s * D], f, at);
+                }
+            }
         }
+        const bool any = lt > 0.f;
+        bf.out[bh * D + e] = any ? at / lt : 0.f;
+        if (tid == 0 && bf.lse) bf.lse[bh] = any ? M * scale + logf(lt) : -INFINITY;
+    };
+    if (rec.state == TAIL_EMPTY || k_eff == 0) {      // nothing to search for this sequence
+        pad_outputs(0, sh.k, idx, vals);
+        if (tid == 0) bf.hmax[bh] = -INFINITY;
+        if (tid < D) write_out(0.f, 0.f, -INFINITY);
         return;
     }
     // the partial sums of the first kernel's workgroups, NT / D threads per output element (asked for
@@ -697,14 +723,14 @@ __global__ void __launch_bounds__(NT) tail_finish_kernel(Shape sh, Bufs bf, floa
         for (int w = 0; w < NW; ++w) lt += __uint_as_float(sm.wave_tot[w]) + s_acc[w][256];
         for (int w = 0; w < NW; ++w) at += s_acc[w][e_out];
         for (int p = 0; p < parts; ++p) at += s_red[p * D + e_out];
-        bf.out[bh * D + e_out] = at / lt;
-        if (tid == 0 && bf.lse) bf.lse[bh] = hmax * scale + logf(lt);
+        write_out(at, lt, hmax);
     }
 }
 
 bool tail_supported(const Shape& s) {
-    return !scan_row_tiles(s) && !s.indexed && s.window == 0 && (s.dtype == DT_F16 || s.dtype == DT_BF16) &&
-           s.n_seg % kScanWaves == 0 && s.n_seg / kScanWaves <= s.hist_cap && s.tail_wgs <= s.n_chunk_cap;
+    const int n_win = (s.window + kGatherRows - 1) / kGatherRows;     // the window's partial sums follow the tail's
+    return !scan_row_tiles(s) && !s.indexed && (s.dtype == DT_F16 || s.dtype == DT_BF16) &&
+           s.n_seg % kScanWaves == 0 && s.n_seg / kScanWaves <= s.hist_cap && s.tail_wgs + n_win <= s.n_chunk_cap;
 }
 
 hipError_t launch_tail(const Shape& s, const Bufs& b, hipStream_t st) {
