@@ -653,8 +653,15 @@ static int decode_impl(topk_attn_t* h, int layer, const void* q, int n_queries, 
         if (e == hipSuccess) e = launch_scan8_filter(s, b, st);
         if (e == hipSuccess && timed) e = hipEventRecord(h->ev[2 * h->ev_used + 1], st);
         if (e == hipSuccess && timed) h->ev_used++;
-        if (e == hipSuccess) e = launch_rerank(s, b, st);
-        if (e == hipSuccess) e = launch_select_candidates(s, b, st);   // redoes unusable heads itself
+        s.no_rescan = 1;       // the per-bin counts cover the listed candidates only: an unusable list is redone densely
+        if (e == hipSuccess) e = launch_rerank(s, b, st);              // exact scores, and their per-bin counts for the tail
+        if (tail_supported(s)) {
+            if (e == hipSuccess && window > 0) e = launch_window_partials(s, b, s.tail_wgs, st);
+            if (e == hipSuccess) e = launch_tail(s, b, st);
+            tail_done = true;
+        } else if (e == hipSuccess) {
+            e = launch_select_candidates(s, b, st);                    // redoes unusable heads itself
+        }
     } else if (fast) {
         s.paged = want_pages && tail_supported(s) ? 1 : 0;
         s.no_rescan = s.paged;      // the paged scan deals its tiles to the waves by rank among the pages kept

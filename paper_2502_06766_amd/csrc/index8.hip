@@ -378,19 +378,28 @@ __global__ void __launch_bounds__(256) rerank_kernel(Shape sh, Bufs bf) {
     constexpr int EPL = Elem<DT>::kPerLoad;
     constexpr int U = kRerankInFlight;
     __shared__ float qf[256];
+    __shared__ uint32_t hist_lds[kTailBins];             // this workgroup's candidates per score bin (exact scores)
     const int h = blockIdx.y, b = blockIdx.z;
     const int64_t bh = (int64_t)b * sh.Hq + h;
-    if (bf.flags[bh]) return;                            // not filtered: the exact redo scores this head itself
-    const int D = sh.D;
     const int lane = lane_id(), wave = threadIdx.x >> 6;
+    const int g = (int)blockIdx.x * 4 + wave;            // this wave's segment
+    uint32_t* hist_out = bf.hist + (bh * sh.hist_cap + blockIdx.x) * kTailBins;
+    const bool counts = (int)blockIdx.x < sh.hist_cap;   // (always, when the tail is going to read them)
+    if (bf.flags[bh]) {                                  // not filtered: the exact redo scores this head itself
+        if (counts && threadIdx.x < kTailBins) hist_out[threadIdx.x] = 0u;
+        if (lane == 0) bf.seg_max[bh * sh.n_seg + g] = -INFINITY;
+        return;
+    }
+    const int D = sh.D;
     const int lpr = D / EPL, groups = kWave / lpr;       // 16 lanes per candidate at D = 128: 4 groups per wave
     const int grp = lane / lpr, c = lane % lpr;
-    const int g = (int)blockIdx.x * 4 + wave;            // this wave's segment
+    const float bin_lo = bf.bins[2 * bh], bin_inv = bf.bins[2 * bh + 1];
     for (int i = threadIdx.x; i < D; i += 256) {
         const char* qp = static_cast<const char*>(bf.q) + (bh * D + i) * Elem<DT>::kBytes;
         qf[i] = DT == DT_F16 ? (float)*reinterpret_cast<const _Float16*>(qp)
                              : __uint_as_float((uint32_t)*reinterpret_cast<const uint16_t*>(qp) << 16);
     }
+    if (threadIdx.x < kTailBins) hist_lds[threadIdx.x] = 0u;
     __syncthreads();
     float qr[EPL];
 #pragma unroll
@@ -400,6 +409,7 @@ __global__ void __launch_bounds__(256) rerank_kernel(Shape sh, Bufs bf) {
     const char* Kh = static_cast<const char*>(bf.K) +
                      ((int64_t)cache_seq(sh, b) * sh.Hkv + h / sh.G) * sh.Ncap * D * Elem<DT>::kBytes;
     uint64_t* list = bf.cand + bh * (int64_t)sh.cand_cap;
+    float top = -INFINITY;                               // largest exact score of the segment
     for (uint32_t e0 = 0; e0 < have; e0 += groups * U) {          // `have` is uniform over the wave
         bool ok[U];
         int64_t slot[U];
@@ -423,9 +433,18 @@ __global__ void __launch_bounds__(256) rerank_kernel(Shape sh, Bufs bf) {
 #pragma unroll
             for (int i = 0; i < EPL; ++i) acc = fmaf(kf[i], qr[i], acc);
             for (int o = 1; o < lpr; o <<= 1) acc += wave_xor(acc, o);
-            if (ok[u] && c == 0) list[slot[u]] = ((uint64_t)__float_as_uint(acc + 0.0f) << 32) | (ent[u] & 0xFFFFFFFFull);
+            if (ok[u] && c == 0) {
+                const float sc = acc + 0.0f;
+                list[slot[u]] = ((uint64_t)__float_as_uint(sc) << 32) | (ent[u] & 0xFFFFFFFFull);
+                atomicAdd(&hist_lds[tail_bin(sc, bin_lo, bin_inv)], 1u);
+                top = fmaxf(top, sc);
+            }
         }
     }
+    for (int o = 32; o > 0; o >>= 1) top = fmaxf(top, wave_xor(top, o));
+    if (lane == 0) bf.seg_max[bh * sh.n_seg + g] = top;
+    __syncthreads();
+    if (counts && threadIdx.x < kTailBins) hist_out[threadIdx.x] = hist_lds[threadIdx.x];
 }
 
 hipError_t launch_rerank(const Shape& s, const Bufs& b, hipStream_t st) {

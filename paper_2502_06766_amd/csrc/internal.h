@@ -173,15 +173,16 @@ __host__ __device__ inline Plan make_plan(int64_t N, int k_eff, int indexed = 0)
     // r - z sqrt(r) = r0 so that the threshold is below the k-th score unless a
     // z-sigma event happens; the candidate list then holds about N r / n_samp entries.
     const double z = 6.0;
-    double r0 = (double)k_eff * (double)ns / (double)N;
-    if (indexed) r0 = 1.25 * r0 + 4.0;
+    const double r_true = (double)k_eff * (double)ns / (double)N;
+    double r0 = r_true;
+    if (indexed) r0 = 1.25 * r0 + 4.0;      // approximate scores: more candidates, so that coding noise loses none
     double sr = 0.5 * (z + sqrt(z * z + 4.0 * r0));
     double r = sr * sr;
     p.rank = (int)r + 2;
     p.rank_k = (int)r0 + 1;
     p.rank_lo = (int)(r0 + 4.0 * sqrt(r0)) + 2;
     if (p.rank_lo > p.rank) p.rank_lo = p.rank;
-    p.rank_hi = (int)(r0 - 4.0 * sqrt(r0));
+    p.rank_hi = (int)(r_true - 4.0 * sqrt(r_true));     // (the band of the k-th score itself, also with an index)
     if (p.rank_hi < 1) p.rank_hi = 1;
     p.c_hi = (int64_t)((double)N * (r + z * sr + 2.0) / (double)ns) + 64;
     return p;
