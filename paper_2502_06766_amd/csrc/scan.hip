@@ -47,9 +47,9 @@ scan_mfma_kernel(Shape sh, Bufs bf, int tiles_per_wave, float* dst) {
         stride = pl.stride;
     }
     // tiles of this wave.  sample/full: a workgroup owns a contiguous run of tiles and its
-    // waves take them round-robin.  filter: wave-segment sid = 4 blockIdx.x + wave takes the
-    // tiles sid, sid + n_seg, ... so that any clustering of high scores along the sequence
-    // spreads evenly over the segments.
+    // waves take them round-robin.  filter: wave-segment sid = 4 blockIdx.x + wave takes one tile
+    // of every row of n_seg tiles (seg_tile()), so that any clustering of high scores along the
+    // sequence spreads evenly over the segments.
     const int64_t n_tiles_all = (n_items + 63) / 64;
     int64_t tile, tile_end, tile_step;
     if (MODE == MODE_FILTER) {
@@ -131,39 +131,43 @@ scan_mfma_kernel(Shape sh, Bufs bf, int tiles_per_wave, float* dst) {
     if (MODE == MODE_SAMPLE) {
         walk_tiles<ScanPipelined<D>::value>(tile, tile_end, tile_step, ba, bb, load_rows, use);
     } else if (MODE == MODE_FILTER && PAGED) {
-        // The pages kept, ascending, are dealt to the wave segments by rank: segment sid takes the pages of
-        // ranks sid, sid + n_seg, ... (64 of them looked up at a time, one per lane), so every wave reads as
-        // many tiles as any other.  They are walked like the plain sequence (next tile's loads in flight
+        // The pages kept, ascending, are dealt to the wave segments by rank like the tiles of the plain scan
+        // (seg_tile() over ranks; 64 rows looked up at a time, one per lane), so every wave reads as many
+        // tiles as any other.  They are walked like the plain sequence (next tile's loads in flight
         // while the current one is multiplied and filtered; one buffer at head_dim 256).
         const int64_t stream = (int64_t)b * sh.Hkv + kvh;
         const int32_t* plist = bf.page_list + stream * (int64_t)sh.page_words * 64;
         const int64_t n_kept = (int64_t)bf.page_cnt[stream];
         const int64_t n_whole = N / 64;
         const uint32_t lane_off = (uint32_t)(((lane & 15) * D + (lane >> 4) * 8) * 2);
-        int64_t base = tile;                     // rank of the first page of the current group of 64
-        int32_t mine = 0;                        // lane i: page of rank base + i * tile_step
-        int have = 0, at = 0;                    // pages in the group, pages of it already taken
+        const int n_seg = (int)tile_step;
+        const int64_t rows = (n_kept + n_seg - 1) / n_seg;      // rows of n_seg ranks; the last one may be short
+        int64_t base = 0;                        // first row of the current group of 64
+        int32_t mine = 0;                        // lane i: page whose rank is this segment's in row base + i
+        uint64_t m = 0ull;                       // rows of the group that hold a page for this segment, not yet taken
         auto look_up = [&]() {
-            const int64_t r = base + lane * tile_step;
-            mine = r < n_kept ? plist[r] : 0;
-            const int64_t left = (n_kept - base + tile_step - 1) / tile_step;
-            have = (int)(left < 64 ? left : 64);
-            at = 0;
+            const int64_t i = base + lane;
+            const int64_t r = seg_tile(i, sid, n_seg);
+            const bool ok = i < rows && r < n_kept;
+            mine = ok ? plist[r] : 0;
+            m = __ballot(ok);
         };
-        if (base < n_kept) look_up();
+        if (rows > 0) look_up();
         auto next = [&]() -> int64_t {           // the wave's next tile to read, or -1 (wave-uniform)
-            if (at == have) {
-                base += 64 * tile_step;
-                if (have < 64 || base >= n_kept) return -1;
+            while (m == 0ull) {
+                base += 64;
+                if (base >= rows) return -1;
                 look_up();
             }
-            return (int64_t)__builtin_amdgcn_readlane(mine, at++);
+            const int bit = __builtin_ctzll(m);
+            m &= m - 1ull;
+            return (int64_t)__builtin_amdgcn_readlane(mine, bit);
         };
         auto load_any = [&](TileB& t, int64_t ti) {
             if (ti < n_whole) tile_load_full<DT, D>(Kh + ti * (64 * D * 2), lane_off, t.b);
             else load_rows(t, ti);
         };
-        if (base < n_kept) {
+        if (rows > 0) {
             int64_t t0 = next();
             if (ScanPipelined<D>::value) {
                 if (t0 >= 0) {
@@ -191,14 +195,33 @@ scan_mfma_kernel(Shape sh, Bufs bf, int tiles_per_wave, float* dst) {
             }
         }
     } else {
-        // whole tiles first, then the one tile (if any) that the end of the cache cuts short
-        const int64_t n_whole = N / 64;
-        const uint32_t lane_off = (uint32_t)(((lane & 15) * D + (lane >> 4) * 8) * 2);
-        tile = walk_tiles<ScanPipelined<D>::value>(tile, tile_end < n_whole ? tile_end : n_whole, tile_step, ba, bb,
-                          [&](TileB& t, int64_t ti) { tile_load_full<DT, D>(Kh + ti * (64 * D * 2), lane_off, t.b); }, use);
-        for (; tile < tile_end; tile += tile_step) {
-            load_rows(ba, tile);
-            use(ba, tile);
+        if (MODE == MODE_FILTER) {
+            // one tile per row of n_seg tiles: the rows made of whole tiles only first, then the last one or two
+            // (tiles beyond the cache are skipped, the one its end cuts short is loaded row by row)
+            const int n_seg = (int)tile_step;
+            const int64_t n_whole = N / 64;
+            const int64_t rows_whole = n_whole / n_seg, rows = (n_tiles_all + n_seg - 1) / n_seg;
+            const uint32_t lane_off = (uint32_t)(((lane & 15) * D + (lane >> 4) * 8) * 2);
+            walk_tiles<ScanPipelined<D>::value>(0, rows_whole, 1, ba, bb,
+                [&](TileB& t, int64_t i) { tile_load_full<DT, D>(Kh + seg_tile(i, sid, n_seg) * (64 * D * 2), lane_off, t.b); },
+                [&](TileB& t, int64_t i) { use(t, seg_tile(i, sid, n_seg)); });
+            for (int64_t i = rows_whole; i < rows; ++i) {
+                const int64_t ti = seg_tile(i, sid, n_seg);
+                if (ti < n_tiles_all) {
+                    load_rows(ba, ti);
+                    use(ba, ti);
+                }
+            }
+        } else {
+            // whole tiles first, then the one tile (if any) that the end of the cache cuts short
+            const int64_t n_whole = N / 64;
+            const uint32_t lane_off = (uint32_t)(((lane & 15) * D + (lane >> 4) * 8) * 2);
+            tile = walk_tiles<ScanPipelined<D>::value>(tile, tile_end < n_whole ? tile_end : n_whole, tile_step, ba, bb,
+                              [&](TileB& t, int64_t ti) { tile_load_full<DT, D>(Kh + ti * (64 * D * 2), lane_off, t.b); }, use);
+            for (; tile < tile_end; tile += tile_step) {
+                load_rows(ba, tile);
+                use(ba, tile);
+            }
         }
     }
     if (MODE == MODE_FILTER) {

@@ -63,6 +63,17 @@ __device__ __forceinline__ void filter_head(float score, float thr, CandStage& c
     }
 }
 
+// Tile that wave segment `sid` takes in row i of the filter scan.  The tiles of a key stream form rows of
+// n_seg consecutive tiles (n_seg a power of two), one tile per segment and row; each row is dealt to the
+// segments rotated by a pseudo-random amount.  Consecutive tiles still go to consecutive segments, so a run
+// of high scores spreads over neighbouring segments, and a pattern that repeats along the sequence (equally
+// long documents with their hot tokens at the same place, say) does not put all its tiles into the same few
+// segments, as the plain dealing sid, sid + n_seg, ... would.
+__host__ __device__ inline int64_t seg_tile(int64_t i, int sid, int n_seg) {
+    const uint32_t rot = ((uint32_t)i * 0x9E3779B1u) >> 12;
+    return i * n_seg + (int64_t)(((uint32_t)sid + rot) & (uint32_t)(n_seg - 1));
+}
+
 inline int tiles_per_wave_for(int64_t n_items, int B, int Hkv) {
     // aim at ~16 workgroups per CU over the whole grid, at least 1 tile and at most 32 per wave
     const int64_t tiles = (n_items + 63) / 64;

@@ -231,7 +231,9 @@ __global__ void __launch_bounds__(kTailThreads) tail_gather_kernel(Shape sh, Buf
         for (int j = j0; j < j1; ++j) {
             const int sid = j * kScanWaves + wave;
             uint32_t cnt = 0;                                           // entries written to segment sid (uniform over the wave)
-            for (int64_t tile = sid; tile < n_tiles; tile += sh.n_seg) {
+            for (int64_t row = 0; row * sh.n_seg < n_tiles; ++row) {    // the tiles the scan dealt to segment sid
+                const int64_t tile = seg_tile(row, sid, sh.n_seg);
+                if (tile >= n_tiles) continue;
 #pragma unroll
                 for (int sub = 0; sub < 4; ++sub) {
                     const int64_t key = tile * 64 + sub * 16 + n;

@@ -185,6 +185,37 @@ def test_many_ties_around_the_kth_score(dtype, N, k, spread):
         cache.close()
 
 
+def test_hot_tokens_at_a_fixed_place_of_equally_long_documents():
+    """256 documents of 4096 tokens whose first 64 tokens all score high for one head: a pattern with a
+    period that divides the scan's tile stride.  Dealing the tiles sid, sid + n_seg, ... would put all
+    256 hot tiles (16384 candidates) into 16 of the 1024 wave segments and overflow them on every step;
+    the rotated dealing spreads them, and the candidate list stays usable: exact result, no head redone."""
+    g = np.random.default_rng(77)
+    dtype, Hq, Hkv, d, doc, n_docs, k = wl.F16, 4, 1, 128, 4096, 256, 10000
+    N = doc * n_docs
+    q = g.standard_normal((Hq, d)).astype(np.float32)
+    K = g.standard_normal((Hkv, N, d)).astype(np.float32)
+    hot = (np.arange(N) % doc) < 64
+    K[0, hot] += 0.5 * q[0]                                     # about +64 on head 0's score: above every other key
+    V = g.standard_normal((Hkv, N, d)).astype(np.float32)
+    q, K, V = wl.quantize(q, dtype), wl.quantize(K, dtype), wl.quantize(V, dtype)
+    cache = ta.TopkAttnCache(1, 1, Hq, Hkv, d, N, k, dtype)
+    try:
+        cache.append(0, 0, H.to_torch(K, dtype, DEV), H.to_torch(V, dtype, DEV), head_major=True)
+        qd = H.to_torch(q, dtype, DEV)[None].contiguous()
+        res = cache.decode(0, qd, k)
+        torch.cuda.synchronize()
+        assert cache.last_fallbacks() == 0
+        rec = ta.topk_attn_last_selection_records(cache.h, Hq)
+        assert all(r[0] == 0 for r in rec), rec
+        same = H.check_unmargined(tuple(t[0].cpu().numpy() for t in res), q, K, V, dtype, k, 0, "periodic hot tokens")
+        idx0 = res[1][0, 0].cpu().numpy()
+        assert hot[idx0].all()                                  # head 0 selects hot tokens only
+        assert same >= 0.75
+    finally:
+        cache.close()
+
+
 @pytest.mark.parametrize("N,redone", [(30000, False), (150000, True)])
 def test_all_keys_identical(N, redone):
     """Every score equal: positions 0..k-1 win and out is their mean.  Every key is a candidate: the
