@@ -302,20 +302,29 @@ scan8_kernel(Shape sh, Bufs bf, int tiles_per_wave, float* dst) {
 
     i32x4 ba[4][KS], bb[4][KS];
     float ksa, ksb;
+    // filter: the wave takes one tile of every row of n_seg tiles (seg_tile()); the walk then counts rows, and a
+    // tile of the last row that lies beyond the cache re-reads the last key rows and keeps nothing
+    const int n_seg_w = (int)tile_step, sid_w = (int)tile;
+    if (MODE == MODE_FILTER) {
+        tile = 0;
+        tile_step = 1;
+        tile_end = (n_tiles_all + n_seg_w - 1) / n_seg_w;
+    }
+    auto tile_of = [&](int64_t t) -> int64_t { return MODE == MODE_FILTER ? seg_tile(t, sid_w, n_seg_w) : t; };
     if (tile < tile_end) {
-        tile_load8<D>(Kh, Sh, [&](int slot) { return row_of(tile * 64, slot); }, ba, ksa);
+        tile_load8<D>(Kh, Sh, [&](int slot) { return row_of(tile_of(tile) * 64, slot); }, ba, ksa);
         while (true) {
             const int64_t t1 = tile + tile_step;
             const int64_t p1 = t1 < tile_end ? t1 : tile;
-            tile_load8<D>(Kh, Sh, [&](int slot) { return row_of(p1 * 64, slot); }, bb, ksb);
+            tile_load8<D>(Kh, Sh, [&](int slot) { return row_of(tile_of(p1) * 64, slot); }, bb, ksb);
             __builtin_amdgcn_sched_barrier(0);
-            consume(tile_mac8<D>(ba, qa), ksa, tile * 64);
+            consume(tile_mac8<D>(ba, qa), ksa, tile_of(tile) * 64);
             if (t1 >= tile_end) break;
             const int64_t t2 = t1 + tile_step;
             const int64_t p2 = t2 < tile_end ? t2 : t1;
-            tile_load8<D>(Kh, Sh, [&](int slot) { return row_of(p2 * 64, slot); }, ba, ksa);
+            tile_load8<D>(Kh, Sh, [&](int slot) { return row_of(tile_of(p2) * 64, slot); }, ba, ksa);
             __builtin_amdgcn_sched_barrier(0);
-            consume(tile_mac8<D>(bb, qa), ksb, t1 * 64);
+            consume(tile_mac8<D>(bb, qa), ksb, tile_of(t1) * 64);
             if (t2 >= tile_end) break;
             tile = t2;
         }

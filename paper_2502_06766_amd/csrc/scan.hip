@@ -515,6 +515,24 @@ scan_rows_kernel(Shape sh, Bufs bf, int tiles_per_wave, float* dst) {
     };
     if (MODE == MODE_SAMPLE) {
         walk_tiles<ScanPipelined<D>::value>(tile, tile_end, tile_step, ba, bb, load_rows, use);
+    } else if (MODE == MODE_FILTER) {
+        // one tile per row of n_seg tiles (seg_tile()): the rows made of whole tiles only first, then the
+        // last one or two (tiles beyond the cache are skipped, the one its end cuts short is loaded row by row)
+        const int n_seg = (int)tile_step;
+        const int sid_w = (int)tile;                            // this wave's segment
+        const int64_t n_whole = N / 64;
+        const int64_t rows_whole = n_whole / n_seg, rows_all = (n_tiles_all + n_seg - 1) / n_seg;
+        const uint32_t lane_off = (uint32_t)((n * D + j * 8) * 2);
+        walk_tiles<ScanPipelined<D>::value>(0, rows_whole, 1, ba, bb,
+            [&](TileB& t, int64_t i) { tile_load_full<DT, D>(Kh + seg_tile(i, sid_w, n_seg) * (64 * D * 2), lane_off, t.b); },
+            [&](TileB& t, int64_t i) { use(t, seg_tile(i, sid_w, n_seg)); });
+        for (int64_t i = rows_whole; i < rows_all; ++i) {
+            const int64_t ti = seg_tile(i, sid_w, n_seg);
+            if (ti < n_tiles_all) {
+                load_rows(ba, ti);
+                use(ba, ti);
+            }
+        }
     } else {
         const int64_t n_whole = N / 64;
         const uint32_t lane_off = (uint32_t)((n * D + j * 8) * 2);
