@@ -243,3 +243,43 @@ def test_c6_clustered_1m_tokens_sublinear_and_exact():
     frac, _ = run_pages_case(q, K, V, w.dtype, w.k, label="c6")
     print(f"c6: {frac:.3f} of the pages read", flush=True)
     assert frac < 0.35
+
+
+def test_pages_edge_cases_tiny_caches_reset_and_static_scratch():
+    """Caches too short for the filtered scan, k beyond the cache, a sequence reset and filled again (its
+    old balls must not survive), and the no-allocation entry point on a handle with a page index."""
+    dtype, Hq, Hkv, d = wl.F16, 8, 2, 128
+    cache = ta.TopkAttnCache(1, 1, Hq, Hkv, d, 70000, 900, dtype, index_kind=ta.INDEX_PAGES)
+    try:
+        cache.set_path(ta.PATH_PAGES)
+        for N, k in ((100, 16), (70, 900), (3000, 64)):         # general path: every page read, result exact
+            q, K, V = clustered(N, min(k, N), seed=N, sigma=0.05)
+            cache.reset(0, 0)
+            cache.append(0, 0, H.to_torch(K, dtype, DEV), H.to_torch(V, dtype, DEV), head_major=True)
+            qd = H.to_torch(q, dtype, DEV)[None].contiguous()
+            res = cache.decode(0, qd, k)
+            torch.cuda.synchronize()
+            read, total = ta.topk_attn_last_pages_read(cache.h)
+            assert read == total == Hkv * ((N + PAGE - 1) // PAGE)
+            H.check_unmargined(tuple(t[0].cpu().numpy() for t in res), q, K, V, dtype, k, 0, f"pages tiny N={N} k={k}")
+        # a long sequence after the short ones, appended in two pieces that split a page
+        N, k = 69999, 700
+        q, K, V = clustered(N, k, seed=5, sigma=0.02)
+        cache.reset(0, 0)
+        Kd, Vd = H.to_torch(K, dtype, DEV), H.to_torch(V, dtype, DEV)
+        cache.append(0, 0, Kd[:, :33333].contiguous(), Vd[:, :33333].contiguous(), head_major=True)
+        cache.append(0, 0, Kd[:, 33333:].contiguous(), Vd[:, 33333:].contiguous(), head_major=True)
+        qd = H.to_torch(q, dtype, DEV)[None].contiguous()
+        res = cache.decode(0, qd, k)
+        torch.cuda.synchronize()
+        read, total = ta.topk_attn_last_pages_read(cache.h)
+        assert 0 < read < total
+        H.check_unmargined(tuple(t[0].cpu().numpy() for t in res), q, K, V, dtype, k, 0, "pages after reset")
+        # the entry point that allocates nothing: same kernels on the library's own scratch array
+        out = torch.empty_like(res[0]); idx = torch.empty_like(res[1]); vals = torch.empty_like(res[2]); lse = torch.empty_like(res[3])
+        st = torch.cuda.current_stream(DEV).cuda_stream
+        ta.topk_attn_decode_static(cache.h, 0, qd.data_ptr(), k, out.data_ptr(), idx.data_ptr(), vals.data_ptr(), lse.data_ptr(), st)
+        torch.cuda.synchronize()
+        assert torch.equal(out, res[0]) and torch.equal(idx, res[1]) and torch.equal(vals, res[2]) and torch.equal(lse, res[3])
+    finally:
+        cache.close()
