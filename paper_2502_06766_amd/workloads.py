@@ -192,7 +192,7 @@ N_CENTROIDS = 256
 CLUSTER_RUN = (128, 2048)
 CLUSTER_HOT = 3
 CLUSTER_PULL = 0.25
-CLUSTER_SIGMA = 0.05
+CLUSTER_SIGMA = 0.02
 
 
 def _cluster_rng(w, seed, layer, seq, h_kv):
