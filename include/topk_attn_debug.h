@@ -31,11 +31,23 @@ int topk_attn_last_pages_read(topk_attn_t* h, int64_t* pages_read, int64_t* page
 
 /* After the caller has synchronised the stream: what the selection of the last decode found for each
  * (sequence, head) pair that took the filtered path with the chip-wide selection: records[4 i + 0] = 0 if
- * the head's candidate list was used, 1 / 2 if its keys were sorted or selected again; [4 i + 1] = keys
+ * the head's candidate list was used or its keys were sorted again, 1 if it was selected from its full
+ * score row, 2 if there was nothing to search, with the head's flag word in bits 8 and up (bit 8: its
+ * sequence cannot be filtered, bit 9: the keys sorted again did not fit either, bit 10: forced redo); [4 i + 1] = keys
  * selected for certain (score bins above the one the k-th score falls in); [4 i + 2] = keys still to pick
  * from that bin; [4 i + 3] = candidates in that bin.  `records` is a host array of 4 * n_seqs * n_q_heads
  * words.  TOPK_ATTN_EINVAL if the last decode took another path.  Copies device->host (synchronous). */
 int topk_attn_last_selection_records(topk_attn_t* h, uint32_t* records);
+
+/* After the caller has synchronised the stream: copies the first `bytes` bytes of one of the per-call arrays of
+ * the handle's workspace to the host array `dst` (for tests that look at what a decode left behind).  Names:
+ * "thr", "bins", "samp", "seg_cnt", "seg_max", "seg_cnt2", "flags", "tailrec", "page_mask", "page_cnt",
+ * "page_list", "hist", "cand", "bnd".  EINVAL for another name or more bytes than the array holds.  The second call
+ * reports dims[0..5] = entries per candidate list, entries per boundary list, scan workgroups the per-bin counts
+ * have room for, most wave segments per head, and the wave segments and entries per segment of the last
+ * filtered decode (0, 0 if the last decode was not filtered). */
+int topk_attn_debug_read_workspace(topk_attn_t* h, const char* name, void* dst, size_t bytes);
+int topk_attn_debug_read_workspace_dims(topk_attn_t* h, int32_t* dims);
 
 /* Measurement aid for the worst case of the filtered path: when enabled, every head of a decode
  * that takes the filtered path is treated like a head whose candidate list turned out unusable

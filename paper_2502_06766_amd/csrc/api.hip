@@ -258,6 +258,7 @@ struct topk_attn {
     float page_beta;            // scale of the page radius in the page bound (1 = exact)
     bool last_paged;            // the last decode went through the page index
     bool last_tail;             // the last decode used the chip-wide selection (its per-head records are in the workspace)
+    int last_n_seg, last_seg_cap;   // the split of the last filtered decode's candidate lists (0: not filtered)
     int last_layer;
     char* scratch_dev;          // this device's copy of the built-in scratch
     int n_cu;                   // compute units of the device
@@ -309,6 +310,7 @@ int topk_attn_create(const topk_attn_config* cfg, topk_attn_t** out) {
     h->page_beta = 1.0f;
     h->last_paged = false;
     h->last_tail = false;
+    h->last_n_seg = h->last_seg_cap = 0;
     h->last_layer = 0;
     {   // cfg->device is current here
         void* p = nullptr;
@@ -692,6 +694,8 @@ static int decode_impl(topk_attn_t* h, int layer, const void* q, int n_queries, 
     h->last_fast = fast;
     h->last_paged = fast && s.paged;
     h->last_tail = tail_done;
+    h->last_n_seg = fast ? s.n_seg : 0;
+    h->last_seg_cap = fast ? s.seg_cap : 0;
     h->last_layer = layer;
     h->last_static = use_static;
     return e == hipSuccess ? TOPK_ATTN_OK : TOPK_ATTN_EDEVICE;
@@ -836,9 +840,39 @@ int topk_attn_last_pages_read(topk_attn_t* h, int64_t* pages_read, int64_t* page
 int topk_attn_last_selection_records(topk_attn_t* h, uint32_t* records) {
     if (!h || !records || !h->last_tail || h->last_static) return TOPK_ATTN_EINVAL;
     const topk_attn_config& c = h->cfg;
-    if (hipMemcpy(records, static_cast<char*>(c.workspace) + h->ws.tailrec, (size_t)c.n_seqs * c.n_q_heads * 4 * sizeof(uint32_t),
-                  hipMemcpyDeviceToHost) != hipSuccess)
+    const size_t n = (size_t)c.n_seqs * c.n_q_heads;
+    if (hipMemcpy(records, static_cast<char*>(c.workspace) + h->ws.tailrec, n * 4 * sizeof(uint32_t), hipMemcpyDeviceToHost) !=
+        hipSuccess)
         return TOPK_ATTN_EDEVICE;
+    std::vector<uint32_t> flags(n);
+    if (hipMemcpy(flags.data(), static_cast<char*>(c.workspace) + h->ws.flags, n * sizeof(uint32_t), hipMemcpyDeviceToHost) !=
+        hipSuccess)
+        return TOPK_ATTN_EDEVICE;
+    for (size_t i = 0; i < n; ++i) records[4 * i] |= flags[i] << 8;      // the head's flag word above the state
+    return TOPK_ATTN_OK;
+}
+
+int topk_attn_debug_read_workspace(topk_attn_t* h, const char* name, void* dst, size_t bytes) {
+    if (!h || !name || !dst) return TOPK_ATTN_EINVAL;
+    const WsLayout& w = h->ws;
+    const struct { const char* name; size_t at, end; } arrays[] = {
+        {"thr", w.thr, w.bins}, {"bins", w.bins, w.samp}, {"samp", w.samp, w.seg_cnt}, {"seg_cnt", w.seg_cnt, w.seg_max},
+        {"seg_max", w.seg_max, w.seg_cnt2}, {"seg_cnt2", w.seg_cnt2, w.flags}, {"flags", w.flags, w.hmax},
+        {"tailrec", w.tailrec, w.qscale}, {"page_mask", w.page_mask, w.page_cnt}, {"page_cnt", w.page_cnt, w.page_list},
+        {"page_list", w.page_list, w.hist}, {"hist", w.hist, w.cand}, {"cand", w.cand, w.bnd}, {"bnd", w.bnd, w.scores}};
+    for (const auto& a : arrays) {
+        if (strcmp(a.name, name) != 0) continue;
+        if (bytes > a.end - a.at) return TOPK_ATTN_EINVAL;
+        return hipMemcpy(dst, static_cast<char*>(h->cfg.workspace) + a.at, bytes, hipMemcpyDeviceToHost) == hipSuccess
+                   ? TOPK_ATTN_OK : TOPK_ATTN_EDEVICE;
+    }
+    return TOPK_ATTN_EINVAL;
+}
+
+int topk_attn_debug_read_workspace_dims(topk_attn_t* h, int32_t* dims) {
+    if (!h || !dims) return TOPK_ATTN_EINVAL;
+    dims[0] = h->ws.cand_cap; dims[1] = h->ws.bnd_cap; dims[2] = h->ws.hist_cap; dims[3] = kMaxSeg;
+    dims[4] = h->last_n_seg; dims[5] = h->last_seg_cap;
     return TOPK_ATTN_OK;
 }
 

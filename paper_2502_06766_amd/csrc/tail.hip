@@ -216,14 +216,17 @@ __global__ void __launch_bounds__(kTailThreads) tail_gather_kernel(Shape sh, Buf
         // ---- The list is unusable: the keys of my scan workgroups' tiles are scored again with the scan's
         // own arithmetic, 16 keys at a time (a quarter of the scan's tile keeps this rarely used branch from
         // setting the register budget of the kernel): lane (jj, n) loads the chunks 4 s + jj of key n, and
-        // every group of four accumulator rows holds the scores of key n for the heads of the operand block.
-        // DENSE: every score goes to the score buffer.  RESCAN: keys from bin B up go to the head's candidate
+        // every group of four accumulator rows holds the score of key n in its first row.
+        // Every score goes to the score buffer.  RESCAN: keys from bin B up also go to the head's candidate
         // list again, into the segment the scan would have put them in; the segments' new lengths are kept
         // apart from the scan's (other workgroups may still be judging the head by those).
-        const int r_full = h % sh.G, sub0 = r_full & ~3, r_me = r_full - sub0;
-        const int Gs = sh.G - sub0 < 4 ? sh.G - sub0 : 4;
+        // Operand A holds this head alone (rows 0, 4, 8, 12; the others zero), so that accumulator element 0 is
+        // its score in every lane: no choice among the four elements by the head's place in its group between
+        // the MFMAs and the read of their result.  (A wave-uniform choice compiles to a branch there, and the
+        // read behind that branch came too early after the last MFMA: the scores of a group's first head were
+        // those of half-finished accumulators.)
         v8 qa[D / 32];
-        load_query_a<DT, D>(bf.q, bh - r_me, Gs, qa);
+        load_query_a<DT, D>(bf.q, bh, 1, qa);
         const char* Kh = static_cast<const char*>(bf.K) + ((int64_t)cache_seq(sh, b) * sh.Hkv + h / sh.G) * sh.Ncap * (D * 2);
         const int jj = lane >> 4, n = lane & 15;
         const bool rescan = hs.mode == MODE_RESCAN;
@@ -244,9 +247,9 @@ __global__ void __launch_bounds__(kTailThreads) tail_gather_kernel(Shape sh, Buf
                     f32x4 acc4 = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
                     for (int s = 0; s < D / 32; ++s) acc4 = Mfma<DT>::mac(qa[s], kb[s], acc4);
-                    const float sc = (r_me == 0 ? acc4[0] : r_me == 1 ? acc4[1] : r_me == 2 ? acc4[2] : acc4[3]) + 0.0f;
+                    const float sc = acc4[0] + 0.0f;
                     const bool mine = jj == 0 && key < N;               // every lane group holds the same scores: the first one writes
-                    if (mine && !rescan) bf.scores[bh * sh.Ncap + key] = sc;
+                    if (mine) bf.scores[bh * sh.Ncap + key] = sc;        // (also when sorting again: should a segment overflow once more, the second kernel selects over this row)
                     const bool keep = mine && rescan && tail_bin(sc, bin_lo, bin_inv) >= hs.binB;
                     const uint64_t m = __ballot(keep);
                     if (keep) {
@@ -322,7 +325,8 @@ __global__ void __launch_bounds__(kTailThreads) tail_gather_kernel(Shape sh, Buf
             for (int u = 0; u < U; ++u) {
                 const int r = r0 + u * RPW + rs;
                 const bool ok = r < n_st;
-                const int64_t pos = sm.st_pos[wave][ok ? r : 0];
+                int64_t pos = (int64_t)(uint32_t)sm.st_pos[wave][ok ? r : 0];
+                pos = pos < N ? pos : N - 1;                         // (entries are positions below N; never read beyond the cache)
                 w[u] = ok ? sm.st_w[wave][r] : 0.f;
                 raw[u] = *reinterpret_cast<const u32x4*>(Vh + (pos * D + c * EPL) * 2);
             }
@@ -534,7 +538,8 @@ __global__ void __launch_bounds__(NT) tail_finish_kernel(Shape sh, Bufs bf, floa
             for (int u = 0; u < U; ++u) {
                 const int jj = j + u * step;
                 const bool ok = jj < j1;
-                r[u] = pos_of(ok ? jj : j);
+                const int64_t pos = (int64_t)(uint32_t)pos_of(ok ? jj : j);
+                r[u] = pos < N ? pos : N - 1;                        // (never read beyond the cache, whatever an entry holds)
                 w[u] = ok ? weight_of(jj) : 0.f;
             }
 #pragma unroll

@@ -22,7 +22,7 @@ INDEX_NONE, INDEX_INT8, INDEX_PAGES = 0, 1, 2
 EXPORTS = [
     "topk_attn_kv_bytes", "topk_attn_workspace_bytes", "topk_attn_create", "topk_attn_append_kv", "topk_attn_append_step",
     "topk_attn_decode", "topk_attn_decode_static", "topk_attn_decode_window", "topk_attn_decode_multi", "topk_attn_decode_layers", "topk_attn_k_schedule", "topk_attn_scores", "topk_attn_length", "topk_attn_reset", "topk_attn_set_path",
-    "topk_attn_last_fallbacks", "topk_attn_set_page_bound_scale", "topk_attn_last_pages_read", "topk_attn_last_selection_records", "topk_attn_debug_force_redo", "topk_attn_set_scan_timing", "topk_attn_scan_time", "topk_attn_read_probe", "topk_attn_build_id", "topk_attn_strerror", "topk_attn_destroy",
+    "topk_attn_last_fallbacks", "topk_attn_set_page_bound_scale", "topk_attn_last_pages_read", "topk_attn_last_selection_records", "topk_attn_debug_read_workspace", "topk_attn_debug_read_workspace_dims", "topk_attn_debug_force_redo", "topk_attn_set_scan_timing", "topk_attn_scan_time", "topk_attn_read_probe", "topk_attn_build_id", "topk_attn_strerror", "topk_attn_destroy",
 ]
 
 
@@ -104,6 +104,10 @@ def lib() -> ctypes.CDLL:
         L.topk_attn_last_pages_read.restype = i32
         L.topk_attn_last_selection_records.argtypes = [vp, ctypes.POINTER(ctypes.c_uint32)]
         L.topk_attn_last_selection_records.restype = i32
+        L.topk_attn_debug_read_workspace.argtypes = [vp, ctypes.c_char_p, vp, ctypes.c_size_t]
+        L.topk_attn_debug_read_workspace.restype = i32
+        L.topk_attn_debug_read_workspace_dims.argtypes = [vp, ctypes.POINTER(i32)]
+        L.topk_attn_debug_read_workspace_dims.restype = i32
         L.topk_attn_debug_force_redo.argtypes = [vp, i32]
         L.topk_attn_debug_force_redo.restype = i32
         L.topk_attn_set_scan_timing.argtypes = [vp, i32]
@@ -251,6 +255,21 @@ def topk_attn_last_selection_records(h, n_heads_total: int):
     buf = (ctypes.c_uint32 * (4 * n_heads_total))()
     _check(lib().topk_attn_last_selection_records(h, buf), "topk_attn_last_selection_records")
     return [tuple(buf[4 * i:4 * i + 4]) for i in range(n_heads_total)]
+
+
+def topk_attn_debug_read_workspace(h, name: str, dtype, count: int):
+    """The first `count` elements (numpy `dtype`) of a named per-call array of the workspace; sync the stream first."""
+    import numpy as np
+    a = np.empty(count, dtype=dtype)
+    _check(lib().topk_attn_debug_read_workspace(h, name.encode(), a.ctypes.data, a.nbytes), "topk_attn_debug_read_workspace")
+    return a
+
+
+def topk_attn_debug_read_workspace_dims(h):
+    """(cand_cap, bnd_cap, hist_cap, most segments, segments and entries per segment of the last filtered decode)."""
+    d = (ctypes.c_int32 * 6)()
+    _check(lib().topk_attn_debug_read_workspace_dims(h, d), "topk_attn_debug_read_workspace_dims")
+    return tuple(d)
 
 
 def topk_attn_debug_force_redo(h, enable: bool):

@@ -216,6 +216,39 @@ def test_hot_tokens_at_a_fixed_place_of_equally_long_documents():
         cache.close()
 
 
+def test_winners_that_all_meet_in_one_wave_segment():
+    """The worst case for the candidate segments, built with the scan's own dealing of tiles: the k best
+    keys of one head all lie in the 32 tiles that go to one wave segment.  The segment overflows in the
+    scan, and again when the keys are sorted a second time from the k-th score's bin up, so the head is
+    selected from its full score row: the result must still be the oracle's."""
+    g = np.random.default_rng(5)
+    dtype, Hq, Hkv, d, N, k = wl.F16, 2, 1, 64, 1 << 21, 1500
+    n_seg, sid = 1024, 517                                      # one KV head: the stream is cut into 1024 wave segments
+    rows = N // 64 // n_seg
+    tiles = [i * n_seg + ((sid + (((i * 0x9E3779B1) & 0xFFFFFFFF) >> 12)) & (n_seg - 1)) for i in range(rows)]
+    q = g.standard_normal((Hq, d)).astype(np.float32)
+    K = g.standard_normal((Hkv, N, d)).astype(np.float32)
+    hot = np.zeros(N, dtype=bool)
+    for t in tiles:
+        hot[t * 64:(t + 1) * 64] = True
+    K[0, hot] += 0.8 * q[0]                                     # head 0: 2048 keys far above all others
+    V = g.standard_normal((Hkv, N, d)).astype(np.float32)
+    q, K, V = wl.quantize(q, dtype), wl.quantize(K, dtype), wl.quantize(V, dtype)
+    cache = ta.TopkAttnCache(1, 1, Hq, Hkv, d, N, k, dtype)
+    try:
+        cache.append(0, 0, H.to_torch(K, dtype, DEV), H.to_torch(V, dtype, DEV), head_major=True)
+        qd = H.to_torch(q, dtype, DEV)[None].contiguous()
+        res = cache.decode(0, qd, k)
+        torch.cuda.synchronize()
+        rec = ta.topk_attn_last_selection_records(cache.h, Hq)
+        print("selection records:", rec, "fallbacks", cache.last_fallbacks(), flush=True)
+        assert cache.last_fallbacks() >= 1                      # head 0 was redone
+        H.check_unmargined(tuple(t[0].cpu().numpy() for t in res), q, K, V, dtype, k, 0, "one hot segment")
+        assert hot[res[1][0, 0].cpu().numpy()].all()
+    finally:
+        cache.close()
+
+
 @pytest.mark.parametrize("N,redone", [(30000, False), (150000, True)])
 def test_all_keys_identical(N, redone):
     """Every score equal: positions 0..k-1 win and out is their mean.  Every key is a candidate: the
@@ -253,6 +286,38 @@ def test_every_head_redone_exactly_matches_the_oracle():
         torch.cuda.synchronize()
         assert torch.equal(torch.sort(idx2, dim=2).values, torch.sort(idx, dim=2).values)
         np.testing.assert_allclose(out2.cpu().numpy(), out.cpu().numpy(), rtol=2e-5, atol=1e-6)
+    finally:
+        cache.close()
+
+
+@pytest.mark.parametrize("dtype,Hq,Hkv,d,N,k", [
+    (wl.F16, 2, 1, 64, 1 << 21, 1500),       # one KV head: 1024 wave segments, 32 tiles each; head_dim 64, groups of 2
+    (wl.F16, 2, 1, 128, 300000, 1500),
+    (wl.BF16, 8, 2, 64, 300000, 800),
+    (wl.BF16, 3, 1, 32, 200000, 500),        # groups of 3, head_dim 32
+    (wl.F16, 4, 4, 256, 150000, 700),        # groups of 1, head_dim 256
+])
+def test_every_head_sorted_again_over_shapes(dtype, Hq, Hkv, d, N, k):
+    """Forced redo (every head's keys are scored and sorted again by the tail) over head dims and group
+    sizes: what the second scoring keeps must be what the scan counted, or output slots stay unwritten."""
+    g = np.random.default_rng(N + d)
+    q = wl.quantize(g.standard_normal((Hq, d)).astype(np.float32), dtype)
+    K = wl.quantize(g.standard_normal((Hkv, N, d)).astype(np.float32), dtype)
+    V = wl.quantize(g.standard_normal((Hkv, N, d)).astype(np.float32), dtype)
+    cache = ta.TopkAttnCache(1, 1, Hq, Hkv, d, N, k, dtype)
+    try:
+        cache.append(0, 0, H.to_torch(K, dtype, DEV), H.to_torch(V, dtype, DEV), head_major=True)
+        qd = H.to_torch(q, dtype, DEV)[None].contiguous()
+        ta.topk_attn_debug_force_redo(cache.h, True)
+        res = cache.decode(0, qd, k)
+        torch.cuda.synchronize()
+        rec = ta.topk_attn_last_selection_records(cache.h, Hq)
+        dims = ta.topk_attn_debug_read_workspace_dims(cache.h)
+        kept = ta.topk_attn_debug_read_workspace(cache.h, "seg_cnt2", np.uint32, dims[4] * Hq).reshape(Hq, dims[4])     # [head][wave segment]
+        for h in range(Hq):
+            assert rec[h][0] >> 8 == 4 and rec[h][0] & 0xFF == 0        # forced, sorted again, no dense selection
+            assert kept[h].sum() == rec[h][1] + rec[h][3], f"head {h}: kept {kept[h].sum()}, counted {rec[h][1]} + {rec[h][3]}"
+        H.check_unmargined(tuple(t[0].cpu().numpy() for t in res), q, K, V, dtype, k, 0, f"forced redo d={d} G={Hq // Hkv}")
     finally:
         cache.close()
 
