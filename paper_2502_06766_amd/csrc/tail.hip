@@ -316,6 +316,7 @@ __global__ void __launch_bounds__(kTailThreads) tail_gather_kernel(Shape sh, Buf
     for (int e = 0; e < EPL; ++e) acc[e] = 0.f;
     float lsum = 0.f;
     int n_st = 0;                                                    // staged winners (uniform over the wave)
+    const uint32_t n_last = (uint32_t)(N - 1);                       // (N >= 1 here, and below 2^31)
     auto fetch_staged = [&]() {
         wave_sync();
         for (int r0 = 0; r0 < n_st; r0 += RPW * U) {
@@ -325,8 +326,8 @@ __global__ void __launch_bounds__(kTailThreads) tail_gather_kernel(Shape sh, Buf
             for (int u = 0; u < U; ++u) {
                 const int r = r0 + u * RPW + rs;
                 const bool ok = r < n_st;
-                int64_t pos = (int64_t)(uint32_t)sm.st_pos[wave][ok ? r : 0];
-                pos = pos < N ? pos : N - 1;                         // (entries are positions below N; never read beyond the cache)
+                const uint32_t p32 = (uint32_t)sm.st_pos[wave][ok ? r : 0];
+                const int64_t pos = (int64_t)(p32 < n_last ? p32 : n_last);   // (entries are positions below N; never read beyond the cache)
                 w[u] = ok ? sm.st_w[wave][r] : 0.f;
                 raw[u] = *reinterpret_cast<const u32x4*>(Vh + (pos * D + c * EPL) * 2);
             }
@@ -527,6 +528,7 @@ __global__ void __launch_bounds__(NT) tail_finish_kernel(Shape sh, Bufs bf, floa
 #pragma unroll
     for (int e = 0; e < EPL; ++e) acc[e] = 0.f;
     float lsum = 0.f;
+    const uint32_t n_last = (uint32_t)(N > 0 ? N - 1 : 0);
     // weighted value rows j0 .. j1 of a list of (position, weight) pairs
     auto gather_rows = [&](int j0, int j1, auto pos_of, auto weight_of) {
         const int step = NW * rpw;
@@ -538,8 +540,8 @@ __global__ void __launch_bounds__(NT) tail_finish_kernel(Shape sh, Bufs bf, floa
             for (int u = 0; u < U; ++u) {
                 const int jj = j + u * step;
                 const bool ok = jj < j1;
-                const int64_t pos = (int64_t)(uint32_t)pos_of(ok ? jj : j);
-                r[u] = pos < N ? pos : N - 1;                        // (never read beyond the cache, whatever an entry holds)
+                const uint32_t p32 = (uint32_t)pos_of(ok ? jj : j);
+                r[u] = (int64_t)(p32 < n_last ? p32 : n_last);       // (never read beyond the cache, whatever an entry holds)
                 w[u] = ok ? weight_of(jj) : 0.f;
             }
 #pragma unroll
