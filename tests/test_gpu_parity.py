@@ -754,6 +754,46 @@ def test_decode_under_graph_capture_replays():
         cache.close()
 
 
+def test_window_decode_under_graph_capture_replays():
+    """The same for a decode with a recent-token window, whose partial sums the library computes on a side
+    stream of its own (forked from and joined to the caller's stream by events): the fork and the join are
+    captured with the rest, and every replay gives the eager result."""
+    dtype, Hq, Hkv, d, N, k, W = wl.BF16, 8, 2, 128, 50000, 300, 700
+    g0 = np.random.default_rng(702)
+    K = wl.quantize(g0.standard_normal((Hkv, N, d)).astype(np.float32), dtype)
+    V = wl.quantize(g0.standard_normal((Hkv, N, d)).astype(np.float32), dtype)
+    qs = [wl.quantize(g0.standard_normal((Hq, d)).astype(np.float32), dtype) for _ in range(2)]
+    cache = ta.TopkAttnCache(1, 1, Hq, Hkv, d, N, k, dtype, max_window=W)
+    try:
+        cache.append(0, 0, H.to_torch(K, dtype, DEV), H.to_torch(V, dtype, DEV), head_major=True)
+        qd = H.to_torch(qs[0], dtype, DEV)[None].contiguous()
+        out = torch.empty((1, Hq, d), dtype=torch.float32, device=DEV)
+        idx = torch.empty((1, Hq, k), dtype=torch.int32, device=DEV)
+        vals = torch.empty((1, Hq, k), dtype=torch.float32, device=DEV)
+        lse = torch.empty((1, Hq), dtype=torch.float32, device=DEV)
+        s = torch.cuda.Stream()
+        with torch.cuda.stream(s):
+            args = (cache.h, 0, qd.data_ptr(), k, W, out.data_ptr(), idx.data_ptr(), vals.data_ptr(), lse.data_ptr())
+            ta.topk_attn_decode_window(*args, s.cuda_stream)   # warm-up outside the capture
+            s.synchronize()
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g, stream=s):
+                ta.topk_attn_decode_window(*args, s.cuda_stream)
+            for rep, q in enumerate([qs[0], qs[1], qs[0], qs[1]]):
+                qd.copy_(H.to_torch(q, dtype, DEV)[None])      # eager work between replays
+                out.zero_(); idx.zero_(); lse.zero_()
+                s.synchronize()
+                g.replay()
+                s.synchronize()
+                H.check_unmargined((out[0].cpu().numpy(), idx[0].cpu().numpy(), vals[0].cpu().numpy(), lse[0].cpu().numpy()),
+                                   q, K, V, dtype, k, W, f"window replay {rep}")
+                eager = cache.decode(0, qd, k, window=W)
+                s.synchronize()
+                assert torch.equal(eager[0], out) and torch.equal(eager[1], idx) and torch.equal(eager[3], lse)
+    finally:
+        cache.close()
+
+
 @pytest.mark.parametrize("path,lens,k", [
     (ta.PATH_AUTO, [70000, 100, 40000, 255], 300),        # two sequences too short to be filtered
     (ta.PATH_FILTER, [400000, 100, 40000], 39000),        # k too dense for the third one's sample
