@@ -13,7 +13,9 @@
 //   sample : score a strided, jittered sample of positions (threshold estimate)
 //   filter : score every key, keep (score, position) pairs >= a per-head threshold; every
 //            wave appends to a private segment of the head's candidate list (plain stores,
-//            no atomics, so the list order is fixed by the launch geometry alone)
+//            no atomics, so the list order is fixed by the launch geometry alone) and the
+//            workgroup counts what it kept per score bin for the selection that follows; with
+//            a page index the wave reads only the tiles (pages) the index could not rule out
 //   full   : score every key and store the fp32 scores
 // fp32 caches go through a plain FMA kernel (full only).
 #include <type_traits>
