@@ -30,13 +30,13 @@ int topk_attn_last_fallbacks(topk_attn_t* h, int* n_heads);
 int topk_attn_last_pages_read(topk_attn_t* h, int64_t* pages_read, int64_t* pages_total);
 
 /* After the caller has synchronised the stream: what the selection of the last decode found for each
- * (sequence, head) pair that took the filtered path with the chip-wide selection: records[4 i + 0] = 0 if
+ * (sequence, query, head) row that took the filtered path with the chip-wide selection: records[4 i + 0] = 0 if
  * the head's candidate list was used or its keys were sorted again, 1 if it was selected from its full
  * score row, 2 if there was nothing to search, with the head's flag word in bits 8 and up (bit 8: its
  * sequence cannot be filtered, bit 9: the keys sorted again did not fit either, bit 10: forced redo); [4 i + 1] = keys
  * selected for certain (score bins above the one the k-th score falls in); [4 i + 2] = keys still to pick
  * from that bin; [4 i + 3] = candidates in that bin.  `records` is a host array of 4 * n_seqs * n_q_heads
- * words.  TOPK_ATTN_EINVAL if the last decode took another path.  Copies device->host (synchronous). */
+ * words, times the queries per sequence of that decode.  TOPK_ATTN_EINVAL if the last decode took another path.  Copies device->host (synchronous). */
 int topk_attn_last_selection_records(topk_attn_t* h, uint32_t* records);
 
 /* After the caller has synchronised the stream: copies the first `bytes` bytes of one of the per-call arrays of

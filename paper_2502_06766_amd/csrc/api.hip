@@ -258,6 +258,7 @@ struct topk_attn {
     float page_beta;            // scale of the page radius in the page bound (1 = exact)
     bool last_paged;            // the last decode went through the page index
     bool last_tail;             // the last decode used the chip-wide selection (its per-head records are in the workspace)
+    int last_queries;           // queries per sequence of the last decode
     int last_n_seg, last_seg_cap;   // the split of the last filtered decode's candidate lists (0: not filtered)
     int last_layer;
     char* scratch_dev;          // this device's copy of the built-in scratch
@@ -314,6 +315,7 @@ int topk_attn_create(const topk_attn_config* cfg, topk_attn_t** out) {
     h->page_beta = 1.0f;
     h->last_paged = false;
     h->last_tail = false;
+    h->last_queries = 1;
     h->last_n_seg = h->last_seg_cap = 0;
     h->last_layer = 0;
     {   // cfg->device is current here
@@ -724,6 +726,7 @@ static int decode_impl(topk_attn_t* h, int layer, const void* q, int n_queries, 
     h->last_fast = fast;
     h->last_paged = fast && s.paged;
     h->last_tail = tail_done;
+    h->last_queries = n_queries;
     h->last_n_seg = fast ? s.n_seg : 0;
     h->last_seg_cap = fast ? s.seg_cap : 0;
     h->last_layer = layer;
@@ -870,7 +873,7 @@ int topk_attn_last_pages_read(topk_attn_t* h, int64_t* pages_read, int64_t* page
 int topk_attn_last_selection_records(topk_attn_t* h, uint32_t* records) {
     if (!h || !records || !h->last_tail || h->last_static) return TOPK_ATTN_EINVAL;
     const topk_attn_config& c = h->cfg;
-    const size_t n = (size_t)c.n_seqs * c.n_q_heads;
+    const size_t n = (size_t)c.n_seqs * h->last_queries * c.n_q_heads;
     if (hipMemcpy(records, static_cast<char*>(c.workspace) + h->ws.tailrec, n * 4 * sizeof(uint32_t), hipMemcpyDeviceToHost) !=
         hipSuccess)
         return TOPK_ATTN_EDEVICE;

@@ -257,7 +257,8 @@ scan_mfma_kernel(Shape sh, Bufs bf, int tiles_per_wave, float* dst) {
 // holds 16 distinct rows, so the four accumulators of a 64-key tile give lane (j, n) the
 // scores of rows 4 j + i (i = 0..3) for keys n, 16 + n, 32 + n, 48 + n: the same 16 MFMAs
 // per tile as the grouped kernel, four times the rows.  Per-row state lives in the 16
-// lanes that own the row.
+// lanes that own the row.  A row's candidates are counted per score bin when they leave
+// the row's LDS stage for its segment (the same counts the grouped kernel leaves).
 // ---------------------------------------------------------------------------------------
 // LDS staging slots per (wave, row): the 64 entries one step can add on top of the remainder
 // (fewer than kCandChunk entries) an aligned flush leaves behind
@@ -304,6 +305,12 @@ scan_rows_kernel(Shape sh, Bufs bf, int tiles_per_wave, float* dst) {
     auto head_of = [&](int rr) -> int64_t {
         return ((int64_t)bc * M + (row0 + rr) / G) * sh.Hq + (int64_t)kvh * G + (row0 + rr) % G;
     };
+    // candidates per score bin (tail_bin()) of each row, counted as they leave the stage
+    __shared__ uint32_t hist_lds[MODE == MODE_FILTER ? 16 * NT * kTailBins : 1];
+    if (MODE == MODE_FILTER) {
+        for (int i = threadIdx.x; i < 16 * NT * kTailBins; i += kScanWaves * kWave) hist_lds[i] = 0;
+        __syncthreads();
+    }
     auto prefix_of = [&](int rr) -> int {   // keys row rr searches (0 for rows the block does not have)
         if (rr >= R) return 0;
         const int m = (row0 + rr) / G;
@@ -350,14 +357,15 @@ scan_rows_kernel(Shape sh, Bufs bf, int tiles_per_wave, float* dst) {
 
     // the rows this lane owns
     auto row_at = [&](int x) { return 16 * (x >> 2) + 4 * j + (x & 3); };
-    int64_t vh[X];
+    int vh[X];              // head of each row (a 32-bit index: heads are few)
     int P[X];
     float thr[X], top[X];
     int nl[X], ng[X];       // staged / already appended candidates (uniform over the 16 lanes of the row)
 #pragma unroll
     for (int x = 0; x < X; ++x) {
-        const int rr = row_at(x);
-        vh[x] = head_of(rr < R ? rr : 0);
+        int rr = row_at(x);
+        asm volatile("" : "+v"(rr));     // the row's bins are read here, not kept in registers across the tile loop
+        vh[x] = (int)head_of(rr < R ? rr : 0);
         P[x] = prefix_of(rr);
         thr[x] = (MODE == MODE_FILTER && rr < R) ? bf.thr[vh[x]] : INFINITY;
         top[x] = -INFINITY;
@@ -366,6 +374,16 @@ scan_rows_kernel(Shape sh, Bufs bf, int tiles_per_wave, float* dst) {
     }
     const int seg_cap = sh.seg_cap, n_seg = sh.n_seg;
     const int sid = bx * kScanWaves + wave;
+    // tail_bin() parameters of each row, a copy per wave (read when the wave's staged candidates are counted)
+    __shared__ float rows_all_lds[MODE == MODE_FILTER ? kScanWaves * 16 * NT * 2 : 1];
+    float* const rows_lds = rows_all_lds + (MODE == MODE_FILTER ? wave * 16 * NT * 2 : 0);
+    if (MODE == MODE_FILTER) {
+#pragma unroll
+        for (int x = 0; x < X; ++x) {
+            const float2 lw = *reinterpret_cast<const float2*>(bf.bins + 2 * vh[x]);
+            if (n == 0) *reinterpret_cast<float2*>(rows_lds + 2 * row_at(x)) = lw;
+        }
+    }
     __shared__ uint64_t stage_lds[MODE == MODE_FILTER ? kScanWaves * 16 * NT * kStageRow : 1];
     uint64_t* const st0 = stage_lds + (MODE == MODE_FILTER ? wave * 16 * NT * kStageRow : 0);
 
@@ -377,9 +395,15 @@ scan_rows_kernel(Shape sh, Bufs bf, int tiles_per_wave, float* dst) {
         uint64_t* src = st0 + row_at(x) * kStageRow;
         const int total = ng_i + nl_i;
         const int f = (final ? total : (total & ~(kCandChunk - 1))) - ng_i;
+        int rr = row_at(x);
+        asm volatile("" : "+v"(rr));     // the row's bins are read here, not kept in registers across the tile loop
+        const float bin_lo = rows_lds[2 * rr], bin_inv = rows_lds[2 * rr + 1];
+        uint32_t* const hist = hist_lds + rr * kTailBins;
         for (int e = n; e < f; e += 16) {
             const int slot = ng_i + e;
-            if (slot < seg_cap) list[cand_slot(slot, sid, n_seg)] = src[e];
+            const uint64_t ent = src[e];
+            if (slot < seg_cap) list[cand_slot(slot, sid, n_seg)] = ent;
+            atomicAdd(&hist[tail_bin(__uint_as_float((uint32_t)(ent >> 32)), bin_lo, bin_inv)], 1u);   // also past a full segment
         }
         const int r = f > 0 ? nl_i - f : nl_i;          // < kCandChunk <= 16 after a flush
         const bool mv = f > 0 && n < r;
@@ -421,10 +445,11 @@ scan_rows_kernel(Shape sh, Bufs bf, int tiles_per_wave, float* dst) {
         for (int x = 0; x < X; ++x) {
             uint32_t cnt = 0;
             float mx = top[x];
+            const int Px = WHOLE ? 0 : prefix_of(row_at(x));    // (worked out again for the few tiles at the end: a register less per row)
 #pragma unroll
             for (int g = 0; g < 4; ++g) {
                 const float sc = c[x >> 2][g][x & 3];
-                const bool valid = WHOLE || item_n + 16 * g < P[x];
+                const bool valid = WHOLE || item_n + 16 * g < Px;
                 if (valid) mx = fmaxf(mx, sc);
                 ps[x][g] = valid && sc >= thr[x];
                 cnt += ps[x][g] ? 1u : 0u;
@@ -450,7 +475,7 @@ scan_rows_kernel(Shape sh, Bufs bf, int tiles_per_wave, float* dst) {
         bool full = false;
 #pragma unroll
         for (int x = 0; x < X; ++x) full |= nl[x] + (int)((tot[x >> 2] >> (8 * (x & 3))) & 0xFFu) > kStageRow;
-        if (__ballot(full)) {
+        if (__builtin_expect(__ballot(full) != 0, 0)) {
 #pragma unroll
             for (int x = 0; x < X; ++x)
                 if (__ballot(nl[x] + (int)((tot[x >> 2] >> (8 * (x & 3))) & 0xFFu) > kStageRow))
@@ -480,7 +505,7 @@ scan_rows_kernel(Shape sh, Bufs bf, int tiles_per_wave, float* dst) {
 #pragma unroll
                     for (int x = 0; x < X; ++x)   // a sample past the row's own prefix does not count
                         if (row_at(x) < R)
-                            bf.samp[vh[x] * sh.samp_cap + item] = pos < P[x] ? c[x >> 2][g][x & 3] : -INFINITY;
+                            bf.samp[(int64_t)vh[x] * sh.samp_cap + item] = pos < P[x] ? c[x >> 2][g][x & 3] : -INFINITY;
                 }
             }
         } else if (MODE == MODE_FULL) {
@@ -489,7 +514,7 @@ scan_rows_kernel(Shape sh, Bufs bf, int tiles_per_wave, float* dst) {
                 const int64_t item = item0 + 16 * g + n;
 #pragma unroll
                 for (int x = 0; x < X; ++x)
-                    if (item < P[x]) dst[vh[x] * sh.Ncap + item] = c[x >> 2][g][x & 3];
+                    if (item < P[x]) dst[(int64_t)vh[x] * sh.Ncap + item] = c[x >> 2][g][x & 3];
             }
         } else {
             if (item0 + 64 <= Pmin) filter(std::true_type{}, c, item0);
@@ -551,10 +576,13 @@ scan_rows_kernel(Shape sh, Bufs bf, int tiles_per_wave, float* dst) {
             flush(i, nl[i], ng[i], vh[i], true);
             for (int o = 8; o > 0; o >>= 1) top[i] = fmaxf(top[i], wave_xor(top[i], o));
             if (n == 0 && row_at(i) < R) {
-                bf.seg_cnt[vh[i] * (int64_t)n_seg + sid] = (uint32_t)ng[i];
-                bf.seg_max[vh[i] * (int64_t)n_seg + sid] = top[i];
+                bf.seg_cnt[(int64_t)vh[i] * n_seg + sid] = (uint32_t)ng[i];
+                bf.seg_max[(int64_t)vh[i] * n_seg + sid] = top[i];
             }
         }
+        __syncthreads();
+        for (int i = threadIdx.x; i < R * kTailBins; i += kScanWaves * kWave)
+            bf.hist[(head_of(i / kTailBins) * sh.hist_cap + bx) * kTailBins + i % kTailBins] = hist_lds[i];
     }
 }
 

@@ -738,7 +738,7 @@ __global__ void __launch_bounds__(NT) tail_finish_kernel(Shape sh, Bufs bf, floa
 
 bool tail_supported(const Shape& s) {
     const int n_win = (s.window + kGatherRows - 1) / kGatherRows;     // the window's partial sums follow the tail's
-    return !scan_row_tiles(s) && (!s.indexed || s.no_rescan) && (s.dtype == DT_F16 || s.dtype == DT_BF16) &&
+    return (!s.indexed || s.no_rescan) && (s.dtype == DT_F16 || s.dtype == DT_BF16) &&
            s.n_seg % kScanWaves == 0 && s.n_seg / kScanWaves <= s.hist_cap && s.tail_wgs + n_win <= s.n_chunk_cap;
 }
 

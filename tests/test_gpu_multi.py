@@ -224,3 +224,35 @@ def test_multi_batched_wide_groups_ragged():
             check_multi(tuple(t[b].cpu().numpy() for t in res), q, K, V, dtype, k, True, W, delta, f"wide ragged seq {b}")
     finally:
         cache.close()
+
+
+@pytest.mark.parametrize("dtype,M,Hq,Hkv,N,d,k,causal,window", [
+    (wl.F16, 4, 8, 2, 200000, 128, 700, True, 0),
+    (wl.BF16, 3, 16, 2, 150000, 64, 400, True, 64),      # G = 8, a window beside the search
+    (wl.F16, 9, 4, 1, 120000, 128, 300, False, 0),       # three row blocks
+])
+def test_multi_every_row_sorted_again(dtype, M, Hq, Hkv, N, d, k, causal, window):
+    """Forced redo of a chunk of queries: the tail scores every row's keys again (each query over its own
+    visible prefix) and must keep exactly what the row-tile scan counted; then the same call unforced."""
+    q, K, V, delta = make_multi(M, Hq, Hkv, N, d, dtype, k, causal, window, seed=N + M, allow_unmargined=True)
+    cache = ta.TopkAttnCache(1, 1, Hq, Hkv, d, N, k, dtype, max_window=window, max_queries=M)
+    try:
+        cache.append(0, 0, H.to_torch(K, dtype, DEV), H.to_torch(V, dtype, DEV), head_major=True)
+        qd = H.to_torch(q, dtype, DEV)[None].contiguous()
+        ta.topk_attn_debug_force_redo(cache.h, True)
+        res = cache.decode_multi(0, qd, k, causal=causal, window=window)
+        torch.cuda.synchronize()
+        rec = ta.topk_attn_last_selection_records(cache.h, M * Hq)
+        dims = ta.topk_attn_debug_read_workspace_dims(cache.h)
+        kept = ta.topk_attn_debug_read_workspace(cache.h, "seg_cnt2", np.uint32, dims[4] * M * Hq).reshape(M * Hq, dims[4])
+        for r in range(M * Hq):
+            assert rec[r][0] >> 8 == 4 and rec[r][0] & 0xFF == 0, f"row {r}: record {rec[r]}"   # forced, sorted again, not dense
+            assert kept[r].sum() == rec[r][1] + rec[r][3], f"row {r}: kept {kept[r].sum()}, counted {rec[r][1]} + {rec[r][3]}"
+        check_multi(tuple(t[0].cpu().numpy() for t in res), q, K, V, dtype, k, causal, window, delta, "forced redo of a chunk")
+        ta.topk_attn_debug_force_redo(cache.h, False)
+        res2 = cache.decode_multi(0, qd, k, causal=causal, window=window)
+        torch.cuda.synchronize()
+        assert torch.equal(torch.sort(res2[1], dim=-1).values, torch.sort(res[1], dim=-1).values)
+        np.testing.assert_allclose(res2[0].cpu().numpy(), res[0].cpu().numpy(), rtol=2e-5, atol=1e-6)
+    finally:
+        cache.close()

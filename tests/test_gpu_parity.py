@@ -296,6 +296,8 @@ def test_every_head_redone_exactly_matches_the_oracle():
     (wl.BF16, 8, 2, 64, 300000, 800),
     (wl.BF16, 3, 1, 32, 200000, 500),        # groups of 3, head_dim 32
     (wl.F16, 4, 4, 256, 150000, 700),        # groups of 1, head_dim 256
+    (wl.F16, 8, 1, 128, 300000, 1500),       # groups of 8: the row-tile scan (one tile of 16 rows)
+    (wl.BF16, 40, 2, 64, 200000, 600),       # groups of 20: two row tiles per block
 ])
 def test_every_head_sorted_again_over_shapes(dtype, Hq, Hkv, d, N, k):
     """Forced redo (every head's keys are scored and sorted again by the tail) over head dims and group
