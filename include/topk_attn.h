@@ -62,7 +62,7 @@ enum {
                                    selection of the plain scan (out may differ in the last bits: the
                                    partial sums are added in another order), unless
                                    topk_attn_set_page_bound_scale has shrunk the bound.  Where the filtered scan does not apply (short
-                                   caches, dense k, several queries, a window) the exact path runs */
+                                   caches, dense k, several queries, head groups above 4) the exact path runs */
 };
 
 /* Search index kept beside the keys (Algorithm 1's build_index; the paper leaves the kind of

@@ -619,8 +619,8 @@ static int decode_impl(topk_attn_t* h, int layer, const void* q, int n_queries, 
     // the int8 index serves one query per sequence with the grouped scan layout
     const bool want_index = h->path == TOPK_ATTN_PATH_INDEX && n_queries == 1 && s.G <= 4;
     s.indexed = want_index ? 1 : 0;
-    // the page index serves the grouped scan without a window (what its tail covers)
-    const bool want_pages = h->path == TOPK_ATTN_PATH_PAGES && n_queries == 1 && s.G <= 4 && window == 0;
+    // the page index serves the grouped scan (with a window: over the pages of the searched prefix)
+    const bool want_pages = h->path == TOPK_ATTN_PATH_PAGES && n_queries == 1 && s.G <= 4;
     // The batch takes the filtered scan if its longest sequence is worth it.  Shorter sequences
     // ride along whenever their candidate list fits; the few that cannot be filtered at all (a
     // handful of tokens, or k too dense) are recognised by the kernels themselves (same

@@ -191,7 +191,7 @@ def test_shrunk_page_bound_trades_recall_for_pages():
     assert recs[1] >= 0.9 and recs[2] >= 0.3          # a shrunk bound misses keys, the more the smaller it is
 
 
-def test_pages_ragged_batch_windows_and_queries_fall_back_to_the_exact_path():
+def test_pages_ragged_batch_and_windows():
     dtype, Hq, Hkv, d, k = wl.F16, 8, 2, 128, 200
     lens = [60000, 130, 33000]
     cache = ta.TopkAttnCache(1, 3, Hq, Hkv, d, max(lens), k, dtype, index_kind=ta.INDEX_PAGES, max_window=64)
@@ -214,14 +214,16 @@ def test_pages_ragged_batch_windows_and_queries_fall_back_to_the_exact_path():
             H.check_against_oracle(out[b].cpu().numpy(), idx[b].cpu().numpy(), vals[b].cpu().numpy(), lse[b].cpu().numpy(),
                                    ref, H.score_margin(q, K, dtype), min(k, n), 2e-3, float(np.abs(wl.widen(V, dtype)).max()),
                                    f"pages ragged seq {b}")
-        # with a window the call takes the plain path (every page read), and is still right
-        outw, idxw, valsw, lsew = cache.decode(0, qd, k, window=64)
-        torch.cuda.synchronize()
-        read, total = ta.topk_attn_last_pages_read(cache.h)
-        assert read == total
-        q, K, V = data[0]
-        refw = c_oracle.topk_attention_window(q, K, V, dtype, k, 64)
-        H.check_unmargined(tuple(t[0].cpu().numpy() for t in (outw, idxw, valsw, lsew)), q, K, V, dtype, k, 64, "pages + window")
+        # with a window the search covers the pages of each sequence's prefix (the last one cut short by the window)
+        for window in (64, 37):
+            outw, idxw, valsw, lsew = cache.decode(0, qd, k, window=window)
+            torch.cuda.synchronize()
+            read, total = ta.topk_attn_last_pages_read(cache.h)
+            assert read < total
+            for b in range(len(lens)):
+                q, K, V = data[b]
+                H.check_unmargined(tuple(t[b].cpu().numpy() for t in (outw, idxw, valsw, lsew)), q, K, V, dtype, k, window,
+                                   f"pages + window {window}, seq {b}")
         assert ta.lib().topk_attn_set_page_bound_scale(cache.h, 0.0) == ta.EINVAL
         assert ta.lib().topk_attn_set_page_bound_scale(cache.h, 1.5) == ta.EINVAL
     finally:
@@ -232,6 +234,31 @@ def test_pages_ragged_batch_windows_and_queries_fall_back_to_the_exact_path():
         assert ta.lib().topk_attn_set_page_bound_scale(plain.h, 0.5) == ta.EINVAL
     finally:
         plain.close()
+
+
+@pytest.mark.parametrize("dtype,N,d,k,window", [(wl.F16, 300000, 128, 2000, 1000), (wl.BF16, 150001, 64, 700, 4096)])
+def test_pages_with_a_window_match_the_plain_scan(dtype, N, d, k, window):
+    """Page index and recent-token window together: the search runs over the pages of the prefix before the
+    window (its last page cut short by the window), the window's tokens are always attended to."""
+    Hq, Hkv = 8, 2
+    q, K, V = clustered(N, k, seed=N + window, sigma=0.03, dtype=dtype, Hq=Hq, Hkv=Hkv, d=d)
+    cache = ta.TopkAttnCache(1, 1, Hq, Hkv, d, N, k, dtype, index_kind=ta.INDEX_PAGES, max_window=window)
+    try:
+        cache.append(0, 0, H.to_torch(K, dtype, DEV), H.to_torch(V, dtype, DEV), head_major=True)
+        qd = H.to_torch(q, dtype, DEV)[None].contiguous()
+        plain = cache.decode(0, qd, k, window=window)
+        cache.set_path(ta.PATH_PAGES)
+        res = cache.decode(0, qd, k, window=window)
+        torch.cuda.synchronize()
+        read, total = ta.topk_attn_last_pages_read(cache.h)
+        print(f"pages + window: {read} of {total} pages read", flush=True)
+        assert 0 < read < 0.7 * total
+        H.check_unmargined(tuple(t[0].cpu().numpy() for t in res), q, K, V, dtype, k, window, "pages + window")
+        assert torch.equal(torch.sort(res[1], dim=2).values, torch.sort(plain[1], dim=2).values)
+        np.testing.assert_allclose(res[0].cpu().numpy(), plain[0].cpu().numpy(), rtol=2e-5, atol=1e-6)
+        np.testing.assert_allclose(res[3].cpu().numpy(), plain[3].cpu().numpy(), rtol=1e-6)
+    finally:
+        cache.close()
 
 
 def test_c6_clustered_1m_tokens_sublinear_and_exact():
