@@ -184,9 +184,7 @@ int topk_attn_decode_static(topk_attn_t* h, int layer, const void* q, int k, flo
  * (the algorithm's window line is read as a joint softmax over both parts applied to
  * [V[I]; V_gen]).  idx / vals report the search result over the prefix; lse covers both parts.
  * window == 0 is topk_attn_decode.  Extra error: EINVAL if window < 0 or > max_window.
- * The sums over the window may run on a second stream that the handle owns (created by
- * topk_attn_create when max_window > 0, default priority), forked from hip_stream and joined to it by
- * events inside the call: for the caller the whole call is work on hip_stream, also under graph capture. */
+ * All work is enqueued on hip_stream. */
 int topk_attn_decode_window(topk_attn_t* h, int layer, const void* q, int k, int window, float* out,
                             int32_t* idx, float* vals, float* lse, void* hip_stream);
 

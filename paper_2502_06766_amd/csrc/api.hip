@@ -266,10 +266,6 @@ struct topk_attn {
     // optional event pairs around the key scan of each decode (measurement only)
     bool timing;
     std::vector<hipEvent_t> ev;  // 2 * kTimingSlots once enabled
-    // side stream for the recent-token window's partial sums, which depend on nothing the search computes: forked from
-    // the caller's stream at the start of a decode and joined before the kernel that merges them (null without a window)
-    hipStream_t aux = nullptr;
-    hipEvent_t ev_fork = nullptr, ev_join = nullptr;
     int ev_used;
 };
 
@@ -324,15 +320,6 @@ int topk_attn_create(const topk_attn_config* cfg, topk_attn_t** out) {
         if (rc != TOPK_ATTN_OK) { delete h; return rc; }
         h->scratch_dev = static_cast<char*>(p);
     }
-    if (cfg->max_window > 0 &&
-        (hipStreamCreateWithFlags(&h->aux, hipStreamNonBlocking) != hipSuccess ||
-         hipEventCreateWithFlags(&h->ev_fork, hipEventDisableTiming) != hipSuccess ||
-         hipEventCreateWithFlags(&h->ev_join, hipEventDisableTiming) != hipSuccess)) {
-        if (h->ev_fork) (void)hipEventDestroy(h->ev_fork);
-        if (h->aux) (void)hipStreamDestroy(h->aux);
-        delete h;
-        return TOPK_ATTN_EDEVICE;
-    }
     // lengths and the small per-head control words start at zero
     if (hipMemset(cfg->workspace, 0, w.hist) != hipSuccess || hipDeviceSynchronize() != hipSuccess) {
         delete h;
@@ -345,9 +332,6 @@ int topk_attn_create(const topk_attn_config* cfg, topk_attn_t** out) {
 int topk_attn_destroy(topk_attn_t* h) {
     if (!h) return TOPK_ATTN_EINVAL;
     for (hipEvent_t e : h->ev) (void)hipEventDestroy(e);
-    if (h->ev_fork) (void)hipEventDestroy(h->ev_fork);
-    if (h->ev_join) (void)hipEventDestroy(h->ev_join);
-    if (h->aux) (void)hipStreamDestroy(h->aux);
     delete h;
     return TOPK_ATTN_OK;
 }
@@ -666,20 +650,6 @@ static int decode_impl(topk_attn_t* h, int layer, const void* q, int n_queries, 
     }
     const bool timed = h->timing && h->ev_used < kTimingSlots;
     if (fast && s.indexed) s.no_rescan = 1;   // (the per-bin counts cover the listed candidates only: an unusable list is redone densely)
-    // The window's partial sums wait for nothing of the search: with the chip-wide tail, which merges them at the very
-    // end, they run on the side stream beside the key scan.
-    bool window_forked = false;
-    if (e == hipSuccess && fast && window > 0 && h->aux && tail_supported(s)) {
-        e = hipEventRecord(h->ev_fork, st);
-        if (e == hipSuccess) e = hipStreamWaitEvent(h->aux, h->ev_fork, 0);
-        if (e == hipSuccess) e = launch_window_partials(s, b, s.tail_wgs, h->aux);
-        if (e == hipSuccess) e = hipEventRecord(h->ev_join, h->aux);
-        window_forked = e == hipSuccess;
-    }
-    auto window_partials = [&]() -> hipError_t {          // before the tail: the partial sums are there, or under way
-        if (window == 0) return hipSuccess;
-        return window_forked ? hipStreamWaitEvent(st, h->ev_join, 0) : launch_window_partials(s, b, s.tail_wgs, st);
-    };
     if (fast && s.indexed) {
         e = launch_quantize_rows(s.dtype, s.D, q, (int64_t)s.B * s.Hq, 0, 1, b.q8, b.qscale, 0, st);
         if (e == hipSuccess) e = launch_scan8_sample(s, b, nmax, st);
@@ -690,8 +660,7 @@ static int decode_impl(topk_attn_t* h, int layer, const void* q, int n_queries, 
         if (e == hipSuccess && timed) h->ev_used++;
         if (e == hipSuccess) e = launch_rerank(s, b, st);              // exact scores, and their per-bin counts for the tail
         if (tail_supported(s)) {
-            if (e == hipSuccess) e = window_partials();
-            if (e == hipSuccess) e = launch_tail(s, b, st);
+            if (e == hipSuccess) e = launch_tail(s, b, st);            // (with a window: its partial sums too)
             tail_done = true;
         } else if (e == hipSuccess) {
             e = launch_select_candidates(s, b, st);                    // redoes unusable heads itself
@@ -707,8 +676,7 @@ static int decode_impl(topk_attn_t* h, int layer, const void* q, int n_queries, 
         if (e == hipSuccess && timed) e = hipEventRecord(h->ev[2 * h->ev_used + 1], st);
         if (e == hipSuccess && timed) h->ev_used++;
         if (tail_supported(s)) {
-            if (e == hipSuccess) e = window_partials();                // merged by the tail's finish
-            if (e == hipSuccess) e = launch_tail(s, b, st);            // selection and gather; redoes unusable heads itself
+            if (e == hipSuccess) e = launch_tail(s, b, st);            // selection and gather (with a window: its partial sums too); redoes unusable heads itself
             tail_done = true;
         } else if (e == hipSuccess) {
             e = launch_select_candidates(s, b, st);                    // redoes unusable heads itself

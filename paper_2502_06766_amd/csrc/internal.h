@@ -215,7 +215,6 @@ hipError_t launch_select_candidates(const Shape& s, const Bufs& b, hipStream_t s
 hipError_t launch_select_full(const Shape& s, const Bufs& b, int64_t Nmax, hipStream_t st);
 
 hipError_t launch_gather(const Shape& s, const Bufs& b, hipStream_t st);
-hipError_t launch_window_partials(const Shape& s, const Bufs& b, int slot0, hipStream_t st);
 
 // fused selection + gather after a filtered scan that counted its candidates per score bin
 bool tail_supported(const Shape& s);

@@ -30,6 +30,7 @@
 // head's segments and go on as with a list, or write all scores to the score buffer, over
 // which the second kernel selects densely.  Nothing is launched for the common case.
 #include "device_utils.h"
+#include "gather_common.h"
 #include "internal.h"
 #include "scan_common.h"
 #include "scan_tiles.h"
@@ -147,9 +148,18 @@ __device__ __forceinline__ HeadSel analyse_head(const Shape& sh, const Bufs& bf,
     return hs;
 }
 
-template <int DT, int D>
+template <int DT, int D, bool WIN>
 __global__ void __launch_bounds__(kTailThreads) tail_gather_kernel(Shape sh, Bufs bf, float scale_log2e) {
     using v8 = typename Mfma<DT>::v8;
+    if (WIN && (int)blockIdx.x >= sh.tail_wgs) {
+        // the recent-token window rides in the same launch: the workgroups behind the head's tail_wgs leave the
+        // partial sums of its chunks in the slots behind theirs (they wait for nothing of the search)
+        static_assert(kTailThreads == 256, "window_chunk() is written for workgroups of 256 threads");
+        __shared__ GatherShared win_sm;
+        const int chunk = (int)blockIdx.x - sh.tail_wgs;
+        window_chunk<DT>(sh, bf, scale_log2e, chunk, blockIdx.y, blockIdx.z, sh.tail_wgs + chunk, win_sm);
+        return;
+    }
     constexpr int EPL = 8;                 // elements per 16-byte load
     constexpr int LPR = D / EPL;           // lanes per value row
     constexpr int RPW = kWave / LPR;       // rows a wave fetches per load instruction
@@ -745,8 +755,13 @@ bool tail_supported(const Shape& s) {
 hipError_t launch_tail(const Shape& s, const Bufs& b, hipStream_t st) {
     const float scale = 1.0f / sqrtf((float)s.D);
     const float scale_log2e = scale * 1.4426950408889634f;
-    const dim3 grid_a((unsigned)s.tail_wgs, (unsigned)s.Hq, (unsigned)s.B);
-#define TKA_TAIL_A(DT_, D_) hipLaunchKernelGGL((tail_gather_kernel<DT_, D_>), grid_a, dim3(kTailThreads), 0, st, s, b, scale_log2e)
+    const int n_win = (s.window + kGatherRows - 1) / kGatherRows;     // chunks of the recent-token window, if any
+    const dim3 grid_a((unsigned)(s.tail_wgs + n_win), (unsigned)s.Hq, (unsigned)s.B);
+#define TKA_TAIL_A(DT_, D_)                                                                                              \
+    do {                                                                                                                 \
+        if (n_win) hipLaunchKernelGGL((tail_gather_kernel<DT_, D_, true>), grid_a, dim3(kTailThreads), 0, st, s, b, scale_log2e); \
+        else hipLaunchKernelGGL((tail_gather_kernel<DT_, D_, false>), grid_a, dim3(kTailThreads), 0, st, s, b, scale_log2e);      \
+    } while (0)
     if (s.dtype == DT_F16 && s.D == 128) TKA_TAIL_A(DT_F16, 128);
     else if (s.dtype == DT_BF16 && s.D == 128) TKA_TAIL_A(DT_BF16, 128);
     else if (s.dtype == DT_F16 && s.D == 64) TKA_TAIL_A(DT_F16, 64);

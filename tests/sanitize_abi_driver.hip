@@ -24,7 +24,6 @@ hipError_t launch_select_full(const Shape&, const Bufs&, int64_t, hipStream_t) {
 hipError_t launch_gather(const Shape&, const Bufs&, hipStream_t) { return hipErrorUnknown; }
 bool tail_supported(const Shape&) { return false; }
 hipError_t launch_tail(const Shape&, const Bufs&, hipStream_t) { return hipErrorUnknown; }
-hipError_t launch_window_partials(const Shape&, const Bufs&, int, hipStream_t) { return hipErrorUnknown; }
 bool index8_supported(int dtype, int D, int G) { return dtype != 0 && D >= 64 && G <= 4; }
 bool pages_supported(int dtype, int, int G) { return dtype != 0 && G <= 4; }
 hipError_t launch_page_balls(int, int, const void*, int64_t, int64_t, int, int, const int32_t*, int64_t, int64_t, void*, float*,
