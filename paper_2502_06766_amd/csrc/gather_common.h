@@ -128,20 +128,31 @@ __device__ __forceinline__ void window_chunk(const Shape& sh, const Bufs& bf, fl
     const int lpr = D / EPL, rows_per_pass = 256 / lpr;
     const int rs = threadIdx.x / lpr, c = threadIdx.x % lpr;
     float mx = -INFINITY;
-    for (int j = j0; j < j1; j += rows_per_pass) {
-        const int jj = j + rs;
-        const bool valid = jj < j1;
-        const int64_t r = P + (valid ? jj : j1 - 1);
-        const u32x4 raw = *reinterpret_cast<const u32x4*>(Kh + (r * D + c * EPL) * Elem<DT>::kBytes);
-        float kf[EPL];
-        Elem<DT>::widen(raw, kf);
-        float acc = 0.f;
+    float qf[EPL];
 #pragma unroll
-        for (int e = 0; e < EPL; ++e) acc = fmaf(kf[e], sm.q[c * EPL + e], acc);
-        for (int o = 1; o < lpr; o <<= 1) acc += wave_xor(acc, o);
-        if (valid) {
-            if (c == 0) sm.sc[jj - j0] = acc;
-            mx = fmaxf(mx, acc);
+    for (int e = 0; e < EPL; ++e) qf[e] = sm.q[c * EPL + e];
+    constexpr int UW = 4;          // key rows in flight per lane (one at a time is a chain of trips to memory)
+    for (int j = j0; j < j1; j += UW * rows_per_pass) {
+        u32x4 raw[UW];
+#pragma unroll
+        for (int u = 0; u < UW; ++u) {
+            const int jj = j + u * rows_per_pass + rs;
+            const int64_t r = P + (jj < j1 ? jj : j1 - 1);
+            raw[u] = *reinterpret_cast<const u32x4*>(Kh + (r * D + c * EPL) * Elem<DT>::kBytes);
+        }
+#pragma unroll
+        for (int u = 0; u < UW; ++u) {
+            const int jj = j + u * rows_per_pass + rs;
+            float kf[EPL];
+            Elem<DT>::widen(raw[u], kf);
+            float acc = 0.f;
+#pragma unroll
+            for (int e = 0; e < EPL; ++e) acc = fmaf(kf[e], qf[e], acc);
+            for (int o = 1; o < lpr; o <<= 1) acc += wave_xor(acc, o);
+            if (jj < j1) {
+                if (c == 0) sm.sc[jj - j0] = acc;
+                mx = fmaxf(mx, acc);
+            }
         }
     }
     for (int o = 32; o > 0; o >>= 1) mx = fmaxf(mx, wave_xor(mx, o));
