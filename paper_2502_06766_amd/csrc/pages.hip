@@ -120,6 +120,14 @@ __global__ void __launch_bounds__(256) page_filter_kernel(Shape sh, Bufs bf, flo
         if (lane == 0) *out = 0ull;
         return;
     }
+    // the centres and balls are asked for first: the query norms below wait for loads of their own
+    const int64_t stream = (int64_t)b * sh.Hkv + kvh;
+    const char* Ch = static_cast<const char*>(bf.page_centres) + stream * sh.page_cap * (D * 2);
+    v8 cb[4][D / 32];
+    tile_load<DT, D>(Ch, [&](int slot) { const int64_t p = tile * 64 + slot; return p < P ? p : P - 1; }, cb);
+    const int64_t page = tile * 64 + lane;
+    const float* ball = bf.page_balls + (stream * sh.page_cap + (page < P ? page : P - 1)) * 2;
+    const float rad = ball[0], cn = ball[1];
     v8 qa[D / 32];
     load_query_a<DT, D>(bf.q, head0, G, qa);
     // |q| of the group's heads
@@ -135,14 +143,7 @@ __global__ void __launch_bounds__(256) page_filter_kernel(Shape sh, Bufs bf, flo
         for (int o = 32; o > 0; o >>= 1) s2 += wave_xor(s2, o);
         qn[r] = sqrtf(s2) * 1.0001f;
     }
-    const int64_t stream = (int64_t)b * sh.Hkv + kvh;
-    const char* Ch = static_cast<const char*>(bf.page_centres) + stream * sh.page_cap * (D * 2);
-    v8 cb[4][D / 32];
-    tile_load<DT, D>(Ch, [&](int slot) { const int64_t p = tile * 64 + slot; return p < P ? p : P - 1; }, cb);
     const f32x4 res = tile_mac<DT, D>(cb, qa);                        // lane l: q_r . centre of page tile * 64 + l
-    const int64_t page = tile * 64 + lane;
-    const float* ball = bf.page_balls + (stream * sh.page_cap + (page < P ? page : P - 1)) * 2;
-    const float rad = ball[0], cn = ball[1];
     bool keep = false;
 #pragma unroll
     for (int r = 0; r < 4; ++r) {
