@@ -25,13 +25,16 @@ namespace tka {
 // first digit on sign and exponent, where a few bins take nearly all samples: thousands of
 // shared-memory atomics on half a dozen addresses.)  The same histogram gives the parameters of
 // tail_bin(), which the tail of the filtered path uses to sort candidates coarsely by score.
+// When the range of the samples is so wide that only a few bins lie between the threshold and the
+// top of the band the k-th score is expected in, the samples of those bins are binned once more.
 // Also clears the head's fallback flag.
+constexpr int kThrRefineBelow = 8;   // the bins between threshold and band top are binned again when fewer than this
 template <int CPT, int NT>     // NT threads; the launcher makes sure n_samp <= CPT * NT <= samp_cap
 __global__ void __launch_bounds__(NT) threshold_kernel(Shape sh, Bufs bf) {
     constexpr int NB = 512, NW = NT / kWave, BPL = NB / kWave;
     __shared__ uint32_t hist[NB];
     __shared__ float red_mx[NW], red_mn[NW];
-    __shared__ uint32_t s_bin[3];
+    __shared__ uint32_t s_bin[4];
     const int b = blockIdx.y, h = blockIdx.x;
     const int tid = threadIdx.x, lane = lane_id(), wave = tid >> 6;
     const int64_t bh = (int64_t)b * sh.Hq + h;
@@ -88,20 +91,21 @@ __global__ void __launch_bounds__(NT) threshold_kernel(Shape sh, Bufs bf) {
     // sc1 = 0 puts every sample into bin 0 (all samples equal, none finite, or a range beyond fp32)
     const float range = mx - mn;
     const float sc1 = (range > 0.f && range < INFINITY) ? (float)NB / range : 0.f;
-#pragma unroll
-    for (int j = 0; j < CPT; ++j) {
-        if (j * NT + tid < n_samp) {
-            int bb = 0;
-            if (sv[j] > -INFINITY) {
-                bb = (int)fminf((sv[j] - mn) * sc1, (float)(NB - 1));
-                bb = bb < 0 ? 0 : bb;
-            }
-            atomicAdd(&hist[bb], 1u);
+    auto coarse_bin = [&](float v) {
+        int bb = 0;
+        if (v > -INFINITY) {
+            bb = (int)fminf((v - mn) * sc1, (float)(NB - 1));
+            bb = bb < 0 ? 0 : bb;
         }
-    }
+        return bb;
+    };
+#pragma unroll
+    for (int j = 0; j < CPT; ++j)
+        if (j * NT + tid < n_samp) atomicAdd(&hist[coarse_bin(sv[j])], 1u);
     __syncthreads();
-    // wave 0 walks the bins from the top: the bins in which the count reaches each of the three ranks
-    if (wave == 0) {
+    // wave 0 walks the bins from the top: the bins in which the count (on top of `above` samples that lie
+    // beyond the last bin) reaches each of the three ranks; s_bin[3]: samples above the bin of the smallest rank
+    auto walk = [&](uint32_t above) {
         uint32_t c[BPL], local = 0;
 #pragma unroll
         for (int i = 0; i < BPL; ++i) {     // lane l owns bins NB - 1 - BPL l - i; rotated start: lanes hit different LDS banks
@@ -115,33 +119,67 @@ __global__ void __launch_bounds__(NT) threshold_kernel(Shape sh, Bufs bf) {
             const uint32_t v = __shfl_up(incl, o, kWave);
             if (lane >= o) incl += v;
         }
+        incl += above;
         const uint32_t want[3] = {rank, rank_lo, rank_hi};
 #pragma unroll
         for (int q = 0; q < 3; ++q) {
             if (incl - local < want[q] && want[q] <= incl) {   // exactly one lane
                 uint32_t run = incl - local;
                 int found = 0;
+                uint32_t before = run;
 #pragma unroll
                 for (int i = 0; i < BPL; ++i) {                // bins in descending order: c[] is rotated by the lane
                     uint32_t ci = 0;
 #pragma unroll
                     for (int r = 0; r < BPL; ++r) ci = ((r + lane) & (BPL - 1)) == i ? c[r] : ci;
-                    if (run < want[q] && want[q] <= run + ci) found = NB - 1 - (BPL * lane + i);
+                    if (run < want[q] && want[q] <= run + ci) { found = NB - 1 - (BPL * lane + i); before = run; }
                     run += ci;
                 }
                 s_bin[q] = (uint32_t)found;
+                if (q == 2) s_bin[3] = before;
             }
         }
-    }
+    };
+    if (wave == 0) walk(0u);
     __syncthreads();
-    const int b1 = (int)s_bin[0], b_lo = (int)s_bin[1], b_hi = (int)s_bin[2];
+    int b1 = (int)s_bin[0], b_lo = (int)s_bin[1], b_hi = (int)s_bin[2];
     // threshold: the lower edge of bin b1.  tail_bin(): fine bins over the band of scores the sample puts the
     // k-th score in, from the lower edge of the bin of sample rank_lo to the upper edge of that of sample rank_hi
+    float lo = mn, sc = sc1;
+    // A few samples far from the rest (keys every query attends to, say) stretch the range, and the whole band
+    // falls into a handful of wide bins: the threshold, a bin's lower edge, then lets several times the wanted
+    // candidates through.  The samples of those bins are then binned once more over the bins' own range.
+    if (sc1 > 0.f && b_hi - b1 < kThrRefineBelow) {
+        const float lo2 = mn + (float)b1 / sc1, hi2 = mn + (float)(b_hi + 1) / sc1;
+        const float range2 = hi2 - lo2;
+        const float sc2 = range2 > 0.f ? (float)NB / range2 : 0.f;
+        const uint32_t above = s_bin[3];                        // samples in the bins above b_hi
+        if (sc2 > 0.f && sc2 < INFINITY) {
+            __syncthreads();                                    // (everyone has read s_bin)
+            for (int i = tid; i < NB; i += NT) hist[i] = 0;
+            __syncthreads();
+#pragma unroll
+            for (int j = 0; j < CPT; ++j) {
+                if (j * NT + tid < n_samp) {
+                    const int bb = coarse_bin(sv[j]);            // which samples take part is decided as before, bin by bin
+                    if (bb >= b1 && bb <= b_hi) {
+                        int fb = (int)fminf((sv[j] - lo2) * sc2, (float)(NB - 1));
+                        atomicAdd(&hist[fb < 0 ? 0 : fb], 1u);
+                    }
+                }
+            }
+            __syncthreads();
+            if (wave == 0) walk(above);
+            __syncthreads();
+            b1 = (int)s_bin[0]; b_lo = (int)s_bin[1]; b_hi = (int)s_bin[2];
+            lo = lo2; sc = sc2;
+        }
+    }
     float thr = mn, bin_lo = mn, bin_inv = 0.f;
-    if (sc1 > 0.f) {
-        thr = b1 == 0 ? mn : mn + (float)b1 / sc1;
-        bin_lo = mn + (float)b_lo / sc1;
-        const float inv = (float)(kTailBins - 2) * sc1 / (float)(b_hi + 1 - b_lo);
+    if (sc > 0.f) {
+        thr = (b1 == 0 && lo == mn) ? mn : lo + (float)b1 / sc;
+        bin_lo = lo + (float)b_lo / sc;
+        const float inv = (float)(kTailBins - 2) * sc / (float)(b_hi + 1 - b_lo);
         bin_inv = inv < INFINITY ? inv : 0.f;
     }
     // (a bin-0 threshold must let -inf samples through when the rank reaches that deep: no finite sample is left out)

@@ -324,6 +324,40 @@ def test_every_head_sorted_again_over_shapes(dtype, Hq, Hkv, d, N, k):
         cache.close()
 
 
+@pytest.mark.parametrize("dtype,mag,frac", [(wl.F16, 3000.0, 0.0005), (wl.BF16, -3000.0, 0.001), (wl.F16, 300.0, 0.002)])
+def test_outlier_scores_do_not_inflate_the_candidate_lists(dtype, mag, frac):
+    """A few keys every query of the group scores far from the rest (what keys that all queries attend to look
+    like) stretch the range of the sampled scores a hundredfold.  The threshold estimate bins the samples around
+    the wanted rank a second time, so the lists stay about as long as without those keys; the result is exact
+    either way."""
+    g = np.random.default_rng(int(abs(mag)))
+    Hq, Hkv, N, d, k = 8, 2, 300000, 128, 3000
+    G = Hq // Hkv
+    q = g.standard_normal((Hq, d)).astype(np.float32)
+    K = g.standard_normal((Hkv, N, d)).astype(np.float32)
+    V = g.standard_normal((Hkv, N, d)).astype(np.float32)
+    Kp = K.copy()
+    pos = g.choice(N, int(N * frac), replace=False)
+    Kp[:, pos] += (mag / np.sqrt(d)) * q.reshape(Hkv, G, d).mean(axis=1)[:, None, :]
+    counts = []
+    for keys in (K, Kp):
+        qq, Kq, Vq = wl.quantize(q, dtype), wl.quantize(keys, dtype), wl.quantize(V, dtype)
+        cache = ta.TopkAttnCache(1, 1, Hq, Hkv, d, N, k, dtype)
+        try:
+            cache.append(0, 0, H.to_torch(Kq, dtype, DEV), H.to_torch(Vq, dtype, DEV), head_major=True)
+            res = cache.decode(0, H.to_torch(qq, dtype, DEV)[None].contiguous(), k)
+            torch.cuda.synchronize()
+            assert cache.last_fallbacks() == 0
+            dims = ta.topk_attn_debug_read_workspace_dims(cache.h)
+            sc = ta.topk_attn_debug_read_workspace(cache.h, "seg_cnt", np.uint32, dims[3] * Hq).reshape(Hq, dims[3])[:, :dims[4]]
+            counts.append(sc.sum(axis=1))
+            H.check_unmargined(tuple(t[0].cpu().numpy() for t in res), qq, Kq, Vq, dtype, k, 0, f"outliers {mag} x {frac}")
+        finally:
+            cache.close()
+    print(f"candidates per head: {counts[0].min()}..{counts[0].max()} without, {counts[1].min()}..{counts[1].max()} with the outliers", flush=True)
+    assert counts[1].max() <= 1.5 * counts[0].max() + N * frac
+
+
 def test_one_head_of_a_group_overflows_and_is_redone():
     """Every key scores the same for head 0 (one constant channel, a query that reads only it), so all keys
     reach its threshold, its candidate segments overflow and it alone is redone exactly (ties go to the
