@@ -2,6 +2,8 @@
 grouping, cache length (also at and around tile boundaries), k, queries per sequence, causal
 visibility, window and pipeline are drawn at random; every case is judged like the
 hand-picked ones (index sets exact on margin-enforced inputs; recall for the int8 index).
+Two further sweeps draw shapes for the forced redo of every row and for the page index over
+clustered caches.
 """
 import numpy as np
 import pytest
@@ -161,3 +163,87 @@ def test_random_ragged_batches(seed):
         finally:
             cache.close()
     assert done == 25          # every drawn batch reaches the GPU and the oracle
+
+
+@pytest.mark.parametrize("seed", [31, 32])
+def test_random_shapes_with_every_row_redone(seed):
+    """Forced redo (the tail scores every row's keys again and sorts them) over random 16-bit shapes, head
+    groups of both scan kernels, chunks of queries, windows; judged against the oracle without a margin."""
+    rng = np.random.default_rng(seed)
+    for case in range(14):
+        dtype = int(rng.choice([wl.F16, wl.BF16]))
+        d = int(rng.choice([32, 64, 128, 256], p=[0.1, 0.3, 0.5, 0.1]))
+        G = int(rng.choice([1, 2, 3, 4, 5, 8, 16, 20]))
+        Hkv = int(rng.integers(1, 3))
+        N = int(rng.integers(20000, 200000))
+        if rng.random() < 0.3:
+            N = (N // 64) * 64 + int(rng.integers(-1, 2))
+        k = int(rng.integers(1, 3000))
+        M = int(rng.choice([1, 1, 1, 2, 3, 5]))
+        causal = bool(rng.integers(0, 2))
+        window = int(rng.choice([0, 0, 100, 1000]))
+        sd = int(rng.integers(0, 2 ** 31))
+        label = f"redo sweep seed {seed} case {case}: dtype={dtype} d={d} G={G} Hkv={Hkv} N={N} k={k} M={M} causal={causal} window={window}"
+        print(label, flush=True)
+        g = np.random.default_rng(sd)
+        Hq = G * Hkv
+        q = wl.make_query_chunk(wl.quantize(g.standard_normal((Hq, d)).astype(np.float32), dtype), dtype, M, sd)
+        K = wl.quantize(g.standard_normal((Hkv, N, d)).astype(np.float32), dtype)
+        V = wl.quantize(g.standard_normal((Hkv, N, d)).astype(np.float32), dtype)
+        cache = ta.TopkAttnCache(1, 1, Hq, Hkv, d, N, k, dtype, max_window=window, max_queries=M)
+        try:
+            cache.append(0, 0, H.to_torch(K, dtype, DEV), H.to_torch(V, dtype, DEV), head_major=True)
+            ta.topk_attn_debug_force_redo(cache.h, True)
+            res = cache.decode_multi(0, H.to_torch(q, dtype, DEV)[None].contiguous(), k, causal=causal, window=window)
+            torch.cuda.synchronize()
+            TM.check_multi(tuple(t[0].cpu().numpy() for t in res), q, K, V, dtype, k, causal, window, None, label)
+        finally:
+            cache.close()
+
+
+@pytest.mark.parametrize("seed", [41, 42])
+def test_random_clustered_caches_through_the_page_index(seed):
+    """Page index over random clustered caches (ragged batches, caches appended in two pieces, windows,
+    tight and loose runs): the selection of the plain scan of the same handle, and the oracle's."""
+    rng = np.random.default_rng(seed)
+    for case in range(14):
+        dtype = int(rng.choice([wl.F16, wl.BF16]))
+        d = int(rng.choice([32, 64, 128, 256], p=[0.1, 0.3, 0.5, 0.1]))
+        G = int(rng.choice([1, 2, 3, 4]))
+        Hkv = int(rng.integers(1, 4))
+        Hq = G * Hkv
+        N = int(rng.integers(300, 150000))
+        if rng.random() < 0.3:
+            N = max(64, (N // 64) * 64 + int(rng.integers(-1, 2)))
+        k = int(rng.integers(1, min(N, 3000) + 1))
+        window = int(rng.choice([0, 0, 37, 64, 1000]))
+        sigma = float(rng.choice([0.01, 0.03, 0.1, 1.0]))
+        lens = [N] + [int(rng.integers(1, N + 1)) for _ in range(int(rng.choice([0, 0, 1, 2])))]
+        sd = int(rng.integers(0, 2 ** 31))
+        label = f"pages sweep seed {seed} case {case}: dtype={dtype} d={d} G={G} Hkv={Hkv} lens={lens} k={k} window={window} sigma={sigma}"
+        print(label, flush=True)
+        cache = ta.TopkAttnCache(1, len(lens), Hq, Hkv, d, N, k, dtype, index_kind=ta.INDEX_PAGES, max_window=window)
+        try:
+            data = []
+            for b, n in enumerate(lens):
+                w = wl.Workload("sweep", 6, 1, 1, Hq, Hkv, d, n, k, dtype, "clustered")
+                q, K, V = (wl.quantize(a, dtype) for a in wl.make_clustered(w, sd + b, sigma, threads=8))
+                data.append((q, K, V))
+                cut = int(rng.integers(0, n + 1))
+                Kd, Vd = H.to_torch(K, dtype, DEV), H.to_torch(V, dtype, DEV)
+                if cut > 0:
+                    cache.append(0, b, Kd[:, :cut].contiguous(), Vd[:, :cut].contiguous(), head_major=True)
+                if cut < n:
+                    cache.append(0, b, Kd[:, cut:].contiguous(), Vd[:, cut:].contiguous(), head_major=True)
+            qd = torch.stack([H.to_torch(x[0], dtype, DEV) for x in data]).contiguous()
+            plain = cache.decode(0, qd, k, window=window)
+            cache.set_path(ta.PATH_PAGES)
+            res = cache.decode(0, qd, k, window=window)
+            torch.cuda.synchronize()
+            assert torch.equal(torch.sort(res[1], dim=2).values, torch.sort(plain[1], dim=2).values), label
+            np.testing.assert_allclose(res[0].cpu().numpy(), plain[0].cpu().numpy(), rtol=3e-5, atol=2e-6, err_msg=label)
+            for b in range(len(lens)):
+                q, K, V = data[b]
+                H.check_unmargined(tuple(t[b].cpu().numpy() for t in res), q, K, V, dtype, k, window, f"{label} seq {b}")
+        finally:
+            cache.close()
