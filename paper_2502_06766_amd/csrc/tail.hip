@@ -14,7 +14,9 @@
 //                       workgroups: writes the certain winners to idx / vals at offsets known
 //                       from the counts, copies bin B's candidates to the head's boundary
 //                       list, and accumulates the softmax-weighted value rows of its winners
-//                       (weights relative to the head's largest score, which the scan reported).
+//                       (weights relative to the head's largest score, which the scan reported;
+//                       the rows are asked for as soon as the winners are known, before it is
+//                       known where they go in idx / vals).
 //   tail_finish_kernel  one workgroup per head: the missing winners among the boundary list (ranked
 //                       by direct comparison of composite keys, lower position wins ties; a
 //                       crowded list is first sorted into sub-bins over its own score range, a
@@ -284,40 +286,10 @@ __global__ void __launch_bounds__(kTailThreads) tail_gather_kernel(Shape sh, Buf
     }
     const bool cached = hs.mode == MODE_LIST;     // the first R batches of this wave's first segment are in saved[]
 
-    // ---- first pass over my candidates: how many certain winners / bin-B candidates each wave has.
-    // Wave w takes segment 4 j + w of every scan workgroup j of mine, 64 candidates at a time; the
-    // first R batches stay in registers for the second pass.
-    uint32_t nw = 0, nb = 0;
-    {
-        int bi = 0;
-        for (int j = j0; j < j1; ++j) {
-            const int g = j * kScanWaves + wave;
-            const uint32_t cnt = scnt[g];
-            for (uint32_t e0 = 0; e0 < cnt; e0 += kWave, ++bi) {
-                const uint32_t e = e0 + lane;
-                uint64_t ent;
-                if (cached && j == j0 && bi < R) ent = bi == 0 ? saved[0] : saved[1];
-                else {
-                    ent = list[cand_slot(e < cnt ? e : 0, g, sh.n_seg)];
-                    if (bi < R) { if (bi == 0) saved[0] = ent; else saved[1] = ent; }
-                }
-                const int bin = tail_bin(__uint_as_float((uint32_t)(ent >> 32)), bin_lo, bin_inv);
-                nw += (e < cnt && bin > hs.binB) ? 1u : 0u;
-                nb += (e < cnt && bin == hs.binB) ? 1u : 0u;
-            }
-        }
-    }
-    static_assert(R == 2, "the register cache of candidate batches is written out for two batches");
-    for (int o = 32; o > 0; o >>= 1) { nw += __shfl_xor(nw, o, kWave); nb += __shfl_xor(nb, o, kWave); }
-    if (lane == 0) { sm.cnt[wave][0] = nw; sm.cnt[wave][1] = nb; }
-    __syncthreads();
-    uint32_t emit_at = hs.emit_at, bnd_at = hs.bnd_at;
-    for (int w = 0; w < wave; ++w) { emit_at += sm.cnt[w][0]; bnd_at += sm.cnt[w][1]; }
-
-    // ---- second pass: write winners and boundary candidates, fetch the winners' value rows
-    int32_t* idx = bf.sel_idx + bh * sh.k;
-    float* vals = bf.sel_val + bh * sh.k;
-    uint64_t* bnd = bf.bnd + bh * (int64_t)sh.bnd_cap;
+    // ---- first pass over my candidates: how many certain winners / bin-B candidates each wave has, and the
+    // winners' positions and softmax weights into the wave's LDS stage (their value rows can be fetched
+    // before it is known where they go in idx / vals).  Wave w takes segment 4 j + w of every scan workgroup
+    // j of mine, 64 candidates at a time; the first R batches stay in registers for the second pass.
     const char* Vh = static_cast<const char*>(bf.V) +
                      ((int64_t)cache_seq(sh, b) * sh.Hkv + h / sh.G) * sh.Ncap * (D * 2);
     const int rs = lane / LPR, c = lane % LPR;
@@ -327,32 +299,89 @@ __global__ void __launch_bounds__(kTailThreads) tail_gather_kernel(Shape sh, Buf
     float lsum = 0.f;
     int n_st = 0;                                                    // staged winners (uniform over the wave)
     const uint32_t n_last = (uint32_t)(N - 1);                       // (N >= 1 here, and below 2^31)
-    auto fetch_staged = [&]() {
-        wave_sync();
-        for (int r0 = 0; r0 < n_st; r0 += RPW * U) {
+    // one round of staged rows: U per lane group, asked for by ask_round() and added up by add_round()
+    auto ask_round = [&](int r0, float (&w)[U], u32x4 (&raw)[U]) {
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int r = r0 + u * RPW + rs;
+            const bool ok = r < n_st;
+            const uint32_t p32 = (uint32_t)sm.st_pos[wave][ok ? r : 0];
+            const int64_t pos = (int64_t)(p32 < n_last ? p32 : n_last);   // (entries are positions below N; never read beyond the cache)
+            w[u] = ok ? sm.st_w[wave][r] : 0.f;
+            raw[u] = *reinterpret_cast<const u32x4*>(Vh + (pos * D + c * EPL) * 2);
+        }
+    };
+    auto add_round = [&](const float (&w)[U], const u32x4 (&raw)[U]) {
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            float vf[EPL];
+            Elem<DT>::widen(raw[u], vf);
+#pragma unroll
+            for (int e = 0; e < EPL; ++e) acc[e] = fmaf(w[u], vf[e], acc[e]);
+            lsum += w[u];
+        }
+    };
+    auto fetch_staged = [&](int r_first) {                           // rows r_first .. n_st - 1 of the stage
+        for (int r0 = r_first; r0 < n_st; r0 += RPW * U) {
             float w[U];
             u32x4 raw[U];
-#pragma unroll
-            for (int u = 0; u < U; ++u) {
-                const int r = r0 + u * RPW + rs;
-                const bool ok = r < n_st;
-                const uint32_t p32 = (uint32_t)sm.st_pos[wave][ok ? r : 0];
-                const int64_t pos = (int64_t)(p32 < n_last ? p32 : n_last);   // (entries are positions below N; never read beyond the cache)
-                w[u] = ok ? sm.st_w[wave][r] : 0.f;
-                raw[u] = *reinterpret_cast<const u32x4*>(Vh + (pos * D + c * EPL) * 2);
-            }
-#pragma unroll
-            for (int u = 0; u < U; ++u) {
-                float vf[EPL];
-                Elem<DT>::widen(raw[u], vf);
-#pragma unroll
-                for (int e = 0; e < EPL; ++e) acc[e] = fmaf(w[u], vf[e], acc[e]);
-                lsum += w[u];
+            ask_round(r0, w, raw);
+            add_round(w, raw);
+        }
+    };
+    uint32_t nw = 0, nb = 0;                                         // (uniform over the wave)
+    {
+        int bi = 0;
+        for (int j = j0; j < j1; ++j) {
+            const int g = j * kScanWaves + wave;
+            const uint32_t cnt = scnt[g];
+            for (uint32_t e0 = 0; e0 < cnt; e0 += kWave, ++bi) {
+                const uint32_t e = e0 + lane;
+                const bool valid = e < cnt;
+                uint64_t ent;
+                if (cached && j == j0 && bi < R) ent = bi == 0 ? saved[0] : saved[1];
+                else {
+                    ent = list[cand_slot(valid ? e : 0, g, sh.n_seg)];
+                    if (bi < R) { if (bi == 0) saved[0] = ent; else saved[1] = ent; }
+                }
+                const float sc = __uint_as_float((uint32_t)(ent >> 32));
+                const int bin = tail_bin(sc, bin_lo, bin_inv);
+                const bool win = valid && bin > hs.binB;
+                const uint64_t mw = __ballot(win), me = __ballot(valid && bin == hs.binB);
+                if (n_st > kTailStage - kWave) {                     // the stage is full: its rows are fetched now
+                    wave_sync();
+                    fetch_staged(0);
+                    wave_sync();
+                    n_st = 0;
+                }
+                if (win) {
+                    const int r = n_st + mask_rank(mw);
+                    sm.st_pos[wave][r] = (int32_t)(uint32_t)ent;
+                    sm.st_w[wave][r] = exp2f((sc - hs.hmax) * scale_log2e);
+                }
+                const int addw = __popcll(mw);
+                n_st += addw;
+                nw += (uint32_t)addw;
+                nb += (uint32_t)__popcll(me);
             }
         }
-        wave_sync();
-        n_st = 0;
-    };
+    }
+    static_assert(R == 2, "the register cache of candidate batches is written out for two batches");
+    // the first round of value rows is asked for now: it is under way while the waves exchange their counts and
+    // the second pass writes the selection
+    wave_sync();
+    float w_first[U];
+    u32x4 raw_first[U];
+    if (n_st > 0) ask_round(0, w_first, raw_first);                  // (uniform over the wave)
+    if (lane == 0) { sm.cnt[wave][0] = nw; sm.cnt[wave][1] = nb; }
+    __syncthreads();
+    uint32_t emit_at = hs.emit_at, bnd_at = hs.bnd_at;
+    for (int w = 0; w < wave; ++w) { emit_at += sm.cnt[w][0]; bnd_at += sm.cnt[w][1]; }
+
+    // ---- second pass: write winners and boundary candidates where the counts put them
+    int32_t* idx = bf.sel_idx + bh * sh.k;
+    float* vals = bf.sel_val + bh * sh.k;
+    uint64_t* bnd = bf.bnd + bh * (int64_t)sh.bnd_cap;
     {
         int bi = 0;
         for (int j = j0; j < j1; ++j) {
@@ -368,29 +397,24 @@ __global__ void __launch_bounds__(kTailThreads) tail_gather_kernel(Shape sh, Buf
                 const int bin = tail_bin(sc, bin_lo, bin_inv);
                 const bool win = valid && bin > hs.binB, edge = valid && bin == hs.binB;
                 const uint64_t mw = __ballot(win), me = __ballot(edge);
-                if (n_st > kTailStage - kWave) fetch_staged();
                 if (win) {
-                    const int r = mask_rank(mw);
-                    const uint32_t o = emit_at + (uint32_t)r;
+                    const uint32_t o = emit_at + (uint32_t)mask_rank(mw);
                     if (o < (uint32_t)k_eff) {            // always true for a consistent list; guards the output buffers
                         idx[o] = (int32_t)(uint32_t)ent;
                         vals[o] = sc;
                     }
-                    sm.st_pos[wave][n_st + r] = (int32_t)(uint32_t)ent;
-                    sm.st_w[wave][n_st + r] = exp2f((sc - hs.hmax) * scale_log2e);
                 }
                 if (edge) {
                     const uint32_t o = bnd_at + (uint32_t)mask_rank(me);
                     if (o < (uint32_t)sh.bnd_cap) bnd[o] = ent;
                 }
-                const int addw = __popcll(mw);
-                emit_at += (uint32_t)addw;
+                emit_at += (uint32_t)__popcll(mw);
                 bnd_at += (uint32_t)__popcll(me);
-                n_st += addw;
             }
         }
     }
-    fetch_staged();
+    if (n_st > 0) add_round(w_first, raw_first);
+    fetch_staged(RPW * U);
 
     // ---- this workgroup's partial sum (weights relative to the head's largest score)
     for (int o = LPR; o < kWave; o <<= 1) {
