@@ -261,6 +261,48 @@ def test_pages_with_a_window_match_the_plain_scan(dtype, N, d, k, window):
         cache.close()
 
 
+def test_page_index_decode_under_graph_capture_replays():
+    """A decode through the page index with a window, captured in a HIP graph (page filter, page list, paged
+    scan, tail: kernels only) and replayed with eager work in between: every replay gives the eager result,
+    also after the query has changed (another set of pages is kept)."""
+    dtype, Hq, Hkv, d, N, k, W = wl.F16, 8, 2, 128, 120000, 900, 300
+    q1, K, V = clustered(N, k, seed=77, sigma=0.03, dtype=dtype, Hq=Hq, Hkv=Hkv, d=d)
+    q2 = wl.quantize(np.random.default_rng(78).standard_normal((Hq, d)).astype(np.float32), dtype)
+    cache = ta.TopkAttnCache(1, 1, Hq, Hkv, d, N, k, dtype, index_kind=ta.INDEX_PAGES, max_window=W)
+    try:
+        cache.append(0, 0, H.to_torch(K, dtype, DEV), H.to_torch(V, dtype, DEV), head_major=True)
+        cache.set_path(ta.PATH_PAGES)
+        qd = H.to_torch(q1, dtype, DEV)[None].contiguous()
+        out = torch.empty((1, Hq, d), dtype=torch.float32, device=DEV)
+        idx = torch.empty((1, Hq, k), dtype=torch.int32, device=DEV)
+        vals = torch.empty((1, Hq, k), dtype=torch.float32, device=DEV)
+        lse = torch.empty((1, Hq), dtype=torch.float32, device=DEV)
+        s = torch.cuda.Stream()
+        with torch.cuda.stream(s):
+            args = (cache.h, 0, qd.data_ptr(), k, W, out.data_ptr(), idx.data_ptr(), vals.data_ptr(), lse.data_ptr())
+            ta.topk_attn_decode_window(*args, s.cuda_stream)   # warm-up outside the capture
+            s.synchronize()
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g, stream=s):
+                ta.topk_attn_decode_window(*args, s.cuda_stream)
+            reads = []
+            for rep, q in enumerate([q1, q2, q1, q2]):
+                qd.copy_(H.to_torch(q, dtype, DEV)[None])      # eager work between replays
+                out.zero_(); idx.zero_(); lse.zero_()
+                s.synchronize()
+                g.replay()
+                s.synchronize()
+                reads.append(ta.topk_attn_last_pages_read(cache.h)[0])
+                H.check_unmargined((out[0].cpu().numpy(), idx[0].cpu().numpy(), vals[0].cpu().numpy(), lse[0].cpu().numpy()),
+                                   q, K, V, dtype, k, W, f"pages replay {rep}")
+                eager = cache.decode(0, qd, k, window=W)
+                s.synchronize()
+                assert torch.equal(eager[0], out) and torch.equal(eager[1], idx) and torch.equal(eager[3], lse)
+            assert reads[0] == reads[2] and reads[1] == reads[3] and reads[0] != reads[1]
+    finally:
+        cache.close()
+
+
 def test_c6_clustered_1m_tokens_sublinear_and_exact():
     """The clustered workload at full size (one million tokens, k = 16384, fp16): the page index reads a
     fraction of the pages and returns exactly the oracle's selection."""

@@ -790,9 +790,8 @@ def test_decode_under_graph_capture_replays():
 
 
 def test_window_decode_under_graph_capture_replays():
-    """The same for a decode with a recent-token window, whose partial sums the library computes on a side
-    stream of its own (forked from and joined to the caller's stream by events): the fork and the join are
-    captured with the rest, and every replay gives the eager result."""
+    """The same for a decode with a recent-token window (its partial sums come from extra workgroups of the
+    tail's first kernel): every replay gives the eager result."""
     dtype, Hq, Hkv, d, N, k, W = wl.BF16, 8, 2, 128, 50000, 300, 700
     g0 = np.random.default_rng(702)
     K = wl.quantize(g0.standard_normal((Hkv, N, d)).astype(np.float32), dtype)
