@@ -256,3 +256,58 @@ def test_multi_every_row_sorted_again(dtype, M, Hq, Hkv, N, d, k, causal, window
         np.testing.assert_allclose(res2[0].cpu().numpy(), res[0].cpu().numpy(), rtol=2e-5, atol=1e-6)
     finally:
         cache.close()
+
+
+def test_other_entry_points_under_graph_capture_replays():
+    """A chunk of queries (row-tile scan), the int8 index and the entry point that allocates nothing, each
+    captured in a HIP graph and replayed with eager work in between: every replay equals the eager call on the
+    same inputs (the eager results are judged against the oracle by the other tests)."""
+    dtype, Hq, Hkv, d, N, k, M, W = wl.F16, 8, 2, 128, 60000, 400, 3, 200
+    g0 = np.random.default_rng(909)
+    K = wl.quantize(g0.standard_normal((Hkv, N, d)).astype(np.float32), dtype)
+    V = wl.quantize(g0.standard_normal((Hkv, N, d)).astype(np.float32), dtype)
+    qs = [wl.make_query_chunk(wl.quantize(g0.standard_normal((Hq, d)).astype(np.float32), dtype), dtype, M, 5 + i) for i in range(2)]
+    cache = ta.TopkAttnCache(1, 1, Hq, Hkv, d, N, k, dtype, max_window=W, max_queries=M, index_kind=ta.INDEX_INT8)
+    try:
+        cache.append(0, 0, H.to_torch(K, dtype, DEV), H.to_torch(V, dtype, DEV), head_major=True)
+        qd = H.to_torch(qs[0], dtype, DEV)[None].contiguous()                 # [1, M, Hq, d]
+        q1 = qd[:, 0].contiguous()                                            # one query per sequence
+        out = torch.empty((1, M, Hq, d), dtype=torch.float32, device=DEV)
+        idx = torch.empty((1, M, Hq, k), dtype=torch.int32, device=DEV)
+        vals = torch.empty((1, M, Hq, k), dtype=torch.float32, device=DEV)
+        lse = torch.empty((1, M, Hq), dtype=torch.float32, device=DEV)
+        ptrs = (out.data_ptr(), idx.data_ptr(), vals.data_ptr(), lse.data_ptr())
+        s = torch.cuda.Stream()
+        calls = {
+            "chunk": (lambda: ta.topk_attn_decode_multi(cache.h, 0, qd.data_ptr(), M, True, k, W, *ptrs, s.cuda_stream),
+                      lambda: cache.decode_multi(0, qd, k, causal=True, window=W), ta.PATH_AUTO, M),
+            "index": (lambda: ta.topk_attn_decode_window(cache.h, 0, q1.data_ptr(), k, W, *ptrs, s.cuda_stream),
+                      lambda: cache.decode(0, q1, k, window=W), ta.PATH_INDEX, 1),
+            "static": (lambda: ta.topk_attn_decode_static(cache.h, 0, q1.data_ptr(), k, *ptrs, s.cuda_stream),
+                       lambda: cache.decode(0, q1, k), ta.PATH_AUTO, 1),
+        }
+        with torch.cuda.stream(s):
+            for name, (raw_call, eager_call, path, m) in calls.items():
+                cache.set_path(path)
+                raw_call()                                                     # warm-up outside the capture
+                s.synchronize()
+                g = torch.cuda.CUDAGraph()
+                with torch.cuda.graph(g, stream=s):
+                    raw_call()
+                for rep, q in enumerate([qs[0], qs[1], qs[0]]):
+                    qd.copy_(H.to_torch(q, dtype, DEV)[None])                  # eager work between replays
+                    q1.copy_(qd[:, 0])
+                    out.zero_(); idx.zero_(); lse.zero_()
+                    s.synchronize()
+                    g.replay()
+                    s.synchronize()
+                    got = (out.clone(), idx.clone(), lse.clone())
+                    eager = eager_call()
+                    s.synchronize()
+                    flat = lambda t, n: t.reshape(-1)[:n]
+                    n_o, n_i, n_l = m * Hq * d, m * Hq * k, m * Hq
+                    assert torch.equal(flat(eager[0], n_o), flat(got[0], n_o)), f"{name} replay {rep}: out"
+                    assert torch.equal(flat(eager[1], n_i), flat(got[1], n_i)), f"{name} replay {rep}: idx"
+                    assert torch.equal(flat(eager[3], n_l), flat(got[2], n_l)), f"{name} replay {rep}: lse"
+    finally:
+        cache.close()
