@@ -552,7 +552,16 @@ __global__ void __launch_bounds__(NT) tail_finish_kernel(Shape sh, Bufs bf, floa
             const int s = part + u * parts;
             pv[u] = s < n_parts ? pa[(int64_t)s * D] : 0.f;
         }
-        for (int s = part + PV * parts; s < n_parts; s += parts) a_parts += pa[(int64_t)s * D];
+        for (int s0 = part + PV * parts; s0 < n_parts; s0 += 8 * parts) {      // (more than PV * parts partials: eight loads at a time, added in the same order)
+            float t[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const int s = s0 + u * parts;
+                t[u] = s < n_parts ? pa[(int64_t)s * D] : 0.f;
+            }
+#pragma unroll
+            for (int u = 0; u < 8; ++u) a_parts += t[u];
+        }
         for (int s = tid; s < n_parts; s += NT) l_parts += bf.part_l[bh * sh.n_chunk_cap + s];
     }
     const int lpr = D / EPL, rpw = kWave / lpr;
