@@ -636,6 +636,10 @@ static int decode_impl(topk_attn_t* h, int layer, const void* q, int n_queries, 
         }
     }
     if (!fast) s.indexed = 0;      // no filtered scan: exact path
+    if (fast && s.indexed) s.no_rescan = 1;   // (the per-bin counts cover the listed candidates only: an unusable list is redone densely)
+    // the selection that follows the filtered scan has limits of its own (count vectors, partial-sum slots); they hold
+    // for every shape the scan takes with this workspace, and a shape beyond them takes the exact path like any other
+    if (fast && !tail_supported(s)) { fast = false; s.indexed = 0; s.no_rescan = 0; }
     hipError_t e = hipSuccess;
     bool tail_done = false;
     if (use_static) {
@@ -649,7 +653,6 @@ static int decode_impl(topk_attn_t* h, int layer, const void* q, int n_queries, 
         e = hipGetLastError();
     }
     const bool timed = h->timing && h->ev_used < kTimingSlots;
-    if (fast && s.indexed) s.no_rescan = 1;   // (the per-bin counts cover the listed candidates only: an unusable list is redone densely)
     if (fast && s.indexed) {
         e = launch_quantize_rows(s.dtype, s.D, q, (int64_t)s.B * s.Hq, 0, 1, b.q8, b.qscale, 0, st);
         if (e == hipSuccess) e = launch_scan8_sample(s, b, nmax, st);
@@ -659,14 +662,10 @@ static int decode_impl(topk_attn_t* h, int layer, const void* q, int n_queries, 
         if (e == hipSuccess && timed) e = hipEventRecord(h->ev[2 * h->ev_used + 1], st);
         if (e == hipSuccess && timed) h->ev_used++;
         if (e == hipSuccess) e = launch_rerank(s, b, st);              // exact scores, and their per-bin counts for the tail
-        if (tail_supported(s)) {
-            if (e == hipSuccess) e = launch_tail(s, b, st);            // (with a window: its partial sums too)
-            tail_done = true;
-        } else if (e == hipSuccess) {
-            e = launch_select_candidates(s, b, st);                    // redoes unusable heads itself
-        }
+        if (e == hipSuccess) e = launch_tail(s, b, st);                // (with a window: its partial sums too)
+        tail_done = true;
     } else if (fast) {
-        s.paged = want_pages && tail_supported(s) ? 1 : 0;
+        s.paged = want_pages ? 1 : 0;
         s.no_rescan = s.paged;      // the paged scan deals its tiles to the waves by rank among the pages kept
         e = launch_scan_sample(s, b, nmax, st);
         if (e == hipSuccess) e = launch_threshold(s, b, nmax, st);
@@ -675,12 +674,8 @@ static int decode_impl(topk_attn_t* h, int layer, const void* q, int n_queries, 
         if (e == hipSuccess) e = s.paged ? launch_scan_filter_paged(s, b, st) : launch_scan_filter(s, b, nmax, st);
         if (e == hipSuccess && timed) e = hipEventRecord(h->ev[2 * h->ev_used + 1], st);
         if (e == hipSuccess && timed) h->ev_used++;
-        if (tail_supported(s)) {
-            if (e == hipSuccess) e = launch_tail(s, b, st);            // selection and gather (with a window: its partial sums too); redoes unusable heads itself
-            tail_done = true;
-        } else if (e == hipSuccess) {
-            e = launch_select_candidates(s, b, st);                    // redoes unusable heads itself
-        }
+        if (e == hipSuccess) e = launch_tail(s, b, st);                // selection and gather (with a window: its partial sums too); redoes unusable heads itself
+        tail_done = true;
     } else {
         if (nmax > 0) {
             if (timed) e = hipEventRecord(h->ev[2 * h->ev_used], st);

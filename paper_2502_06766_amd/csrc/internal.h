@@ -211,7 +211,6 @@ hipError_t launch_scan_full(const Shape& s, const Bufs& b, int64_t Nmax, float* 
 bool scan_mfma_supported(const Shape& s);
 
 hipError_t launch_threshold(const Shape& s, const Bufs& b, int64_t Nmax, hipStream_t st);
-hipError_t launch_select_candidates(const Shape& s, const Bufs& b, hipStream_t st);
 hipError_t launch_select_full(const Shape& s, const Bufs& b, int64_t Nmax, hipStream_t st);
 
 hipError_t launch_gather(const Shape& s, const Bufs& b, hipStream_t st);

@@ -187,77 +187,6 @@ __global__ void __launch_bounds__(NT) threshold_kernel(Shape sh, Bufs bf) {
     leave(thr, mark, bin_lo, bin_inv);
 }
 
-// Exact selection among the candidates the filtered scan kept, read from the interleaved
-// per-wave segments.  A head without a usable list is redone exactly by the same workgroup.
-template <int CPT, int NT>     // NT threads (>= n_seg); CPT * NT candidate slots are kept on chip, the rest is streamed
-__global__ void __launch_bounds__(NT) select_candidates_kernel(Shape sh, Bufs bf) {
-    __shared__ SelShared sm;
-    __shared__ uint32_t pos_lds[CPT * NT];
-    const int b = blockIdx.y, h = blockIdx.x;
-    const int tid = threadIdx.x, lane = lane_id(), wave = tid >> 6;
-    const int64_t bh = (int64_t)b * sh.Hq + h;
-    // Everything the prologue needs from memory is asked for at once: this kernel runs on a
-    // few dozen compute units at the end of a dependent chain of kernels, and every load it
-    // waits for on its own costs a full trip to memory (the host launches at least n_seg threads).
-    const uint32_t flagged = bf.flags[bh];
-    const float thr_h = bf.thr[bh];
-    const bool has_seg = tid < sh.n_seg;
-    const uint32_t my_cnt = has_seg ? bf.seg_cnt[bh * sh.n_seg + tid] : 0u;
-    const float my_max = has_seg ? bf.seg_max[bh * sh.n_seg + tid] : -INFINITY;
-    const int64_t N = prefix_len(visible_len(sh, bf, b), sh.window);
-    const int k_eff = sh.k < N ? sh.k : (int)N;
-
-    if (k_eff == 0) {                // nothing to search: only padding to write
-        pad_outputs(0, sh.k, bf.sel_idx + bh * sh.k, bf.sel_val + bh * sh.k);
-        if (tid == 0) bf.hmax[bh] = -INFINITY;
-        return;
-    }
-    // (uniform) flagged by the threshold kernel: this sequence is not filtered at all
-    bool redo = flagged != 0;
-    uint32_t max_len = 0, kmx = 0;           // longest segment; largest score key any scanning wave saw
-    if (!redo) {
-        uint32_t sum = my_cnt, mxl = my_cnt;
-        if (has_seg) {
-            sm.seg_len[tid] = my_cnt;
-            kmx = score_key(my_max);
-        }
-        for (int o = 32; o > 0; o >>= 1) {
-            sum += __shfl_xor(sum, o, kWave);
-            const uint32_t t = __shfl_xor(mxl, o, kWave), u = __shfl_xor(kmx, o, kWave);
-            mxl = t > mxl ? t : mxl;
-            kmx = u > kmx ? u : kmx;
-        }
-        if (lane == 0) { sm.wave_tot[wave] = sum; sm.red_max[wave] = mxl; sm.red_min[wave] = kmx; }
-        __syncthreads();
-        uint32_t total = 0;
-        kmx = 0;
-        for (int w = 0; w < NT / kWave; ++w) {
-            total += sm.wave_tot[w];
-            max_len = sm.red_max[w] > max_len ? sm.red_max[w] : max_len;
-            kmx = sm.red_min[w] > kmx ? sm.red_min[w] : kmx;
-        }
-        __syncthreads();
-        if (max_len > (uint32_t)sh.seg_cap || total < (uint32_t)k_eff) {   // a segment overflowed, or the
-            if (tid == 0) {                                                // threshold was too high
-                bf.flags[bh] = 1;
-                atomicAdd(bf.fallback_total, 1u);
-            }
-            redo = true;
-        }
-    }
-    if (redo) {
-        wg_redo_head<NT>(sh, bf, b, h, N, k_eff, sm);
-        return;
-    }
-    const SrcSegT<NT> src{bf.cand + bh * (int64_t)sh.cand_cap, sm.seg_len, pos_lds, 31 - __clz(sh.n_seg), (int)max_len};
-    const Items<CPT, SrcSegT<NT>> items(src);
-    // every candidate is >= the head's threshold and the scan reported the largest score; not so
-    // after an index scan, whose candidates were re-scored since
-    const uint32_t kmax = wg_topk_emit(items, k_eff, sh.k, bf.sel_idx + bh * sh.k, bf.sel_val + bh * sh.k, sm,
-                                       !sh.indexed, score_key(thr_h), kmx);
-    if (tid == 0) bf.hmax[bh] = key_score(kmax);
-}
-
 // Exact selection over the full score row, already in the score buffer (general path).
 // NT threads per head: a batch of many short sequences is thousands of heads of a few
 // thousand scores each, and a workgroup no larger than the row needs keeps more heads in
@@ -277,7 +206,8 @@ __global__ void __launch_bounds__(NT) select_full_kernel(Shape sh, Bufs bf) {
     wg_select_dense<NT, CPT>(sh, bf, bh, N, k_eff, sm);
 }
 
-// Both kernels are correct for any register-cache size (what does not fit is streamed); a
+
+// The kernel is correct for any register-cache size (what does not fit is streamed); a
 // cache much larger than the data only costs loop trips over empty slots, which matters
 // when the whole step is a few tens of microseconds.
 // A call with many heads (a batch, 512 heads or more) whose rows are small takes 256-thread workgroups: several
@@ -297,28 +227,6 @@ hipError_t launch_threshold(const Shape& s, const Bufs& b, int64_t Nmax, hipStre
     else if (n_samp <= 4096) TKA_TH(16, 256);
     else TKA_TH(32, 256);
 #undef TKA_TH
-    return hipGetLastError();
-}
-hipError_t launch_select_candidates(const Shape& s, const Bufs& b, hipStream_t st) {
-    // slots the filled part of the list is expected to span: the longest segment, a few
-    // standard deviations above the mean, times the segments
-    const double mean = (double)s.cand_est / (double)s.n_seg;
-    int64_t len = (int64_t)(mean + 4.0 * sqrt(mean) + 16.0);
-    len = (len + kCandChunk - 1) / kCandChunk * kCandChunk;
-    if (len > s.seg_cap) len = s.seg_cap;
-    const int64_t slots = len * s.n_seg;
-    const dim3 grid(s.Hq, s.B);
-    static_assert(kMaxSeg <= kSelThreads, "one candidate segment per thread in the selection's prologue");
-#define TKA_SC(CPT_, NT_) hipLaunchKernelGGL((select_candidates_kernel<CPT_, NT_>), grid, dim3(NT_), 0, st, s, b)
-    if (many_small_heads(s) && slots <= 8192 && s.n_seg <= 256) {
-        if (slots <= 2048) TKA_SC(8, 256);
-        else if (slots <= 4096) TKA_SC(16, 256);
-        else TKA_SC(32, 256);
-    } else if (slots <= 4 * kSelThreads) TKA_SC(4, kSelThreads);
-    else if (slots <= 8 * kSelThreads) TKA_SC(8, kSelThreads);
-    else if (slots <= 16 * kSelThreads) TKA_SC(16, kSelThreads);
-    else TKA_SC(kCandSlots / kSelThreads, kSelThreads);
-#undef TKA_SC
     return hipGetLastError();
 }
 hipError_t launch_select_full(const Shape& s, const Bufs& b, int64_t Nmax, hipStream_t st) {

@@ -11,7 +11,6 @@ constexpr int kSelWaves = kSelThreads / kWave;
 constexpr int kDigitBits = 9;                  // radix digit width (the best of 8..11 measured)
 constexpr int kBins = 1 << kDigitBits;
 constexpr int kBinsPerLane = kBins / kWave;
-constexpr int kCandSlots = 32768;              // candidate slots kept on chip per head
 
 struct SelShared {
     uint32_t hist[kBins];
@@ -20,8 +19,6 @@ struct SelShared {
     uint32_t bc_max, bc_min;
     uint32_t bin, above, cb;
     uint32_t wave_tot[kSelWaves];
-    uint32_t seg_len[kMaxSeg];
-    float qrow[256];
 };
 
 // Order-preserving key of a score (-0 counts as +0).  0 would need the bit pattern of a
@@ -49,32 +46,6 @@ struct SrcDenseT {           // scores[i] at position i, i < n
         return 0xFFFFFFFFu - (uint32_t)(j * NT + (int)threadIdx.x);
     }
 };
-template <int NT>
-struct SrcSegT {             // candidate list of n_seg interleaved segments: entry e of segment g
-    static constexpr int kThreads = NT;
-    const uint64_t* segs;    // sits in slot cand_slot(e, g, n_seg); entries are (score bits << 32 | position)
-    const uint32_t* seg_len; // LDS: entries per segment
-    uint32_t* pos_lds;       // LDS: inverted positions of the cached slots, [slot j][thread]
-    int log2_n_seg;          // n_seg is a power of two
-    int max_len;             // longest segment
-    typedef uint64_t raw_t;
-    __device__ __forceinline__ int64_t slots() const {
-        return (int64_t)((max_len + kCandChunk - 1) & ~(kCandChunk - 1)) << log2_n_seg;
-    }
-    __device__ __forceinline__ bool valid(int64_t i) const {
-        return i < slots() && (uint32_t)cand_slot_entry(i, log2_n_seg) < seg_len[cand_slot_segment(i, log2_n_seg)];
-    }
-    __device__ __forceinline__ const uint64_t* where(int64_t i) const { return segs + i; }
-    __device__ __forceinline__ uint32_t key(uint64_t e) const {
-        return score_key(__uint_as_float((uint32_t)(e >> 32)));
-    }
-    __device__ __forceinline__ uint32_t ipos(uint64_t e, int64_t) const { return 0xFFFFFFFFu - (uint32_t)e; }
-    __device__ __forceinline__ void stash(int j, uint64_t e) const {
-        pos_lds[j * NT + (int)threadIdx.x] = 0xFFFFFFFFu - (uint32_t)e;
-    }
-    __device__ __forceinline__ uint32_t cached_ipos(int j) const { return pos_lds[j * NT + (int)threadIdx.x]; }
-};
-
 // The items of one head as seen by one thread: register slot j holds the score key of
 // source slot j * kSelThreads + tid, later slots are streamed.  Every lane of a wave
 // visits the same slots in the same order (with a per-lane "present" flag), so visitors
@@ -322,43 +293,6 @@ __device__ __forceinline__ uint32_t wg_topk_emit(const It& items, int k_eff, int
     return s.kmax;
 }
 
-// Scores of all N keys against one query head, computed by this workgroup alone with plain
-// FMAs (rows of D elements spread over D*e/16 lanes).  Only used to redo a head whose
-// candidate list turned out unusable, so speed does not matter.
-template <int DT>
-__device__ void wg_score_head(const Shape& sh, const Bufs& bf, int b, int h, int64_t N, float* dst, SelShared& sm) {
-    constexpr int EPL = Elem<DT>::kPerLoad;
-    const int D = sh.D;
-    const int64_t bh = (int64_t)b * sh.Hq + h;
-    for (int i = threadIdx.x; i < D; i += (int)blockDim.x) {
-        const char* qp = static_cast<const char*>(bf.q) + (bh * D + i) * Elem<DT>::kBytes;
-        float v;
-        if (DT == DT_F32) v = *reinterpret_cast<const float*>(qp);
-        else if (DT == DT_F16) v = (float)*reinterpret_cast<const _Float16*>(qp);
-        else v = __uint_as_float((uint32_t)*reinterpret_cast<const uint16_t*>(qp) << 16);
-        sm.qrow[i] = v;
-    }
-    __syncthreads();
-    const int lpr = D / EPL, rows_per_pass = (int)blockDim.x / lpr;
-    const int rs = threadIdx.x / lpr, chunk = threadIdx.x % lpr;
-    const char* Kh = static_cast<const char*>(bf.K) +
-                     ((int64_t)cache_seq(sh, b) * sh.Hkv + h / sh.G) * sh.Ncap * D * Elem<DT>::kBytes;
-    for (int64_t base = 0; base < N; base += rows_per_pass) {
-        const int64_t row = base + rs;
-        const bool valid = row < N;
-        const u32x4 raw =
-            *reinterpret_cast<const u32x4*>(Kh + ((valid ? row : N - 1) * D + chunk * EPL) * Elem<DT>::kBytes);
-        float kf[EPL];
-        Elem<DT>::widen(raw, kf);
-        float acc = 0.f;
-#pragma unroll
-        for (int e = 0; e < EPL; ++e) acc = fmaf(kf[e], sm.qrow[chunk * EPL + e], acc);
-        for (int m = 1; m < lpr; m <<= 1) acc += wave_xor(acc, m);
-        if (valid && chunk == 0) dst[row] = acc;
-    }
-    __syncthreads();   // the scores are read back by other threads of this workgroup
-}
-
 // Exact selection of one head over its full score row (the general path's selection).
 template <int NT, int CPT>     // the first CPT * NT scores stay in registers, the rest is streamed
 __device__ __forceinline__ uint32_t wg_select_dense(const Shape& sh, const Bufs& bf, int64_t bh, int64_t N, int k_eff,
@@ -368,20 +302,6 @@ __device__ __forceinline__ uint32_t wg_select_dense(const Shape& sh, const Bufs&
     const uint32_t kmax = wg_topk_emit(items, k_eff, sh.k, bf.sel_idx + bh * sh.k, bf.sel_val + bh * sh.k, sm);
     if (threadIdx.x == 0) bf.hmax[bh] = key_score(kmax);
     return kmax;              // key of the largest score (uniform)
-}
-
-// The exact redo of a head whose candidate list is unusable (its sequence cannot be filtered,
-// a segment overflowed, or the sampled threshold came out above the k-th score): the
-// workgroup rescores the whole head itself, then selects from the full row -- slow, rare, exact.
-template <int NT>
-__device__ __forceinline__ void wg_redo_head(const Shape& sh, const Bufs& bf, int b, int h, int64_t N, int k_eff,
-                                          SelShared& sm) {
-    const int64_t bh = (int64_t)b * sh.Hq + h;
-    float* row = bf.scores + bh * sh.Ncap;
-    if (sh.dtype == DT_F16) wg_score_head<DT_F16>(sh, bf, b, h, N, row, sm);
-    else if (sh.dtype == DT_BF16) wg_score_head<DT_BF16>(sh, bf, b, h, N, row, sm);
-    else wg_score_head<DT_F32>(sh, bf, b, h, N, row, sm);
-    wg_select_dense<NT, 8>(sh, bf, bh, N, k_eff, sm);
 }
 
 }  // namespace tka

@@ -19,7 +19,6 @@ hipError_t launch_scan_filter(const Shape&, const Bufs&, int64_t, hipStream_t) {
 hipError_t launch_scan_full(const Shape&, const Bufs&, int64_t, float*, hipStream_t) { return hipErrorUnknown; }
 bool scan_mfma_supported(const Shape&) { return false; }
 hipError_t launch_threshold(const Shape&, const Bufs&, int64_t, hipStream_t) { return hipErrorUnknown; }
-hipError_t launch_select_candidates(const Shape&, const Bufs&, hipStream_t) { return hipErrorUnknown; }
 hipError_t launch_select_full(const Shape&, const Bufs&, int64_t, hipStream_t) { return hipErrorUnknown; }
 hipError_t launch_gather(const Shape&, const Bufs&, hipStream_t) { return hipErrorUnknown; }
 bool tail_supported(const Shape&) { return false; }
