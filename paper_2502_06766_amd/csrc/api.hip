@@ -477,7 +477,6 @@ static void fill_call(topk_attn_t* h, int layer, const void* q, int k, int n_que
     s->paged = 0; s->no_rescan = 0;
     s->page_cap = (int)page_cap_of(&c); s->page_words = h->ws.page_words;
     s->force_redo = h->force_redo ? 1 : 0;
-    s->cand_est = 0;
     char* const ws_len = static_cast<char*>(c.workspace);
     // everything after the lengths is per-call scratch: the handle's workspace, or the library's own array
     char* const ws = use_static ? reinterpret_cast<char*>(reinterpret_cast<uintptr_t>(h->scratch_dev) - h->ws.thr) : ws_len;
@@ -624,7 +623,6 @@ static int decode_impl(topk_attn_t* h, int layer, const void* q, int n_queries, 
             if (plan_is_fast(pl, n, s.cand_cap, true)) c_hi = pl.c_hi > c_hi ? pl.c_hi : c_hi;
         }
         if (fast) fast = choose_segments(h, s, nmax, c_hi, &s.n_seg, &s.seg_cap);
-        s.cand_est = (int)(c_hi < INT32_MAX ? c_hi : INT32_MAX);
         if (fast) {     // tail: about 128 selected rows per workgroup and at most four scan workgroups each
             // (a tail workgroup walks its scan workgroups one after the other: dependent loads each time)
             const int n_wg = s.n_seg / 4;

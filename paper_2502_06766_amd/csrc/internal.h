@@ -39,7 +39,6 @@ struct Shape {
     int no_rescan;    // an unusable list is redone densely (the per-bin counts of a paged scan are not those of the plain tile order)
     int page_cap;     // pages per key stream the page index has room for (ceil(Ncap / 64))
     int page_words;   // 64-bit words of the page mask per key stream
-    int cand_est;     // candidates per head expected at most (sizes the selection's register cache)
     int k;            // requested k (k_eff = min(k, searched prefix of sequence b))
     int window;       // most recent tokens that are always attended and excluded from the search
     int max_k;
