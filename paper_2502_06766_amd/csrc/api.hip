@@ -186,6 +186,27 @@ __global__ void append_step_kernel(const char* __restrict__ ksrc, const char* __
         *reinterpret_cast<u32x4*>(vdst + d_o) = *reinterpret_cast<const u32x4*>(vsrc + i * 16);
     }
 }
+// The same for a step small enough for one workgroup (a token or a few per sequence, no index to extend): the
+// workgroup bumps the lengths itself once all its threads have placed their pieces, one launch instead of two.
+constexpr int kAppendSmallThreads = 1024;
+constexpr int64_t kAppendSmallPieces = 4 * kAppendSmallThreads;       // 16-byte pieces of K (and of V) per call: 256 rows of 256 bytes
+__global__ void __launch_bounds__(kAppendSmallThreads)
+append_step_small_kernel(const char* __restrict__ ksrc, const char* __restrict__ vsrc, char* __restrict__ kdst,
+                         char* __restrict__ vdst, int32_t* len, int64_t total, int64_t n_new, int Hkv, int chunks_per_row,
+                         int64_t head_b, int B) {
+    for (int64_t i = threadIdx.x; i < total; i += kAppendSmallThreads) {
+        const int c = (int)(i % chunks_per_row);
+        const int64_t th = i / chunks_per_row;
+        const int h = (int)(th % Hkv);
+        const int64_t bt = th / Hkv;
+        const int64_t t = bt % n_new, b = bt / n_new;
+        const int64_t d_o = (b * Hkv + h) * head_b + (((int64_t)len[b] + t) * chunks_per_row + c) * 16;
+        *reinterpret_cast<u32x4*>(kdst + d_o) = *reinterpret_cast<const u32x4*>(ksrc + i * 16);
+        *reinterpret_cast<u32x4*>(vdst + d_o) = *reinterpret_cast<const u32x4*>(vsrc + i * 16);
+    }
+    __syncthreads();            // every thread has used the lengths it needed
+    for (int b = threadIdx.x; b < B; b += kAppendSmallThreads) len[b] += (int32_t)n_new;
+}
 __global__ void bump_len_kernel(int32_t* len, int B, int32_t n_new) {
     const int b = blockIdx.x * blockDim.x + threadIdx.x;
     if (b < B) len[b] += n_new;
@@ -431,6 +452,13 @@ int topk_attn_append_step(topk_attn_t* h, int layer, const void* k_new, const vo
     int32_t* len_dev = reinterpret_cast<int32_t*>(static_cast<char*>(c.workspace) + h->ws.len) + (size_t)layer * B;
     const int chunks = (int)(row_b / 16);
     const int64_t total = (int64_t)B * n_new * c.n_kv_heads * chunks;
+    if (c.index_kind == TOPK_ATTN_INDEX_NONE && total <= kAppendSmallPieces) {
+        hipLaunchKernelGGL(append_step_small_kernel, dim3(1), dim3(kAppendSmallThreads), 0, st, static_cast<const char*>(k_new),
+                           static_cast<const char*>(v_new), kdst, vdst, len_dev, total, n_new, c.n_kv_heads, chunks, head_b, B);
+        if (hipGetLastError() != hipSuccess) return TOPK_ATTN_EDEVICE;
+        for (int b = 0; b < B; ++b) h->len[(size_t)layer * B + b] += n_new;
+        return TOPK_ATTN_OK;
+    }
     int64_t blocks = (total + 255) / 256;
     if (blocks > 65536) blocks = 65536;
     hipLaunchKernelGGL(append_step_kernel, dim3((unsigned)blocks), dim3(256), 0, st, static_cast<const char*>(k_new),

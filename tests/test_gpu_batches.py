@@ -21,7 +21,7 @@ def test_append_step_equals_per_sequence_appends(dtype, d, index):
     g = np.random.default_rng(1000 + d + dtype)
     L, B, Hq, Hkv, Ncap = 2, 3, 8, 2, 900
     start = [300, 0, 517]                       # ragged lengths before the batched steps
-    steps = [1, 1, 3, 1, 17, 1]                 # tokens per batched append
+    steps = [1, 1, 3, 1, 17, 150, 1]            # tokens per batched append (one workgroup's worth, or many)
     total = [s + sum(steps) for s in start]
     k = 40
     q = wl.quantize(g.standard_normal((B, Hq, d)).astype(np.float32), dtype)
