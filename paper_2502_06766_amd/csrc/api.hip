@@ -459,6 +459,17 @@ int topk_attn_append_step(topk_attn_t* h, int layer, const void* k_new, const vo
         for (int b = 0; b < B; ++b) h->len[(size_t)layer * B + b] += n_new;
         return TOPK_ATTN_OK;
     }
+    if (c.index_kind == TOPK_ATTN_INDEX_INT8 && total <= kAppendSmallPieces) {      // the same with the rows' codes
+        char* base = static_cast<char*>(c.kv_storage) + 2 * h->kv_half;
+        const int64_t layer_rows = (int64_t)layer * B * c.n_kv_heads * c.max_tokens;
+        int8_t* codes = reinterpret_cast<int8_t*>(base) + layer_rows * c.head_dim;
+        float* scales = reinterpret_cast<float*>(base + index_codes_bytes(&c)) + layer_rows;
+        if (launch_append_step_small8(c.dtype, c.head_dim, k_new, v_new, kdst, vdst, head_b, B, n_new, c.n_kv_heads,
+                                      c.max_tokens, len_dev, codes, scales, st) != hipSuccess)
+            return TOPK_ATTN_EDEVICE;
+        for (int b = 0; b < B; ++b) h->len[(size_t)layer * B + b] += n_new;
+        return TOPK_ATTN_OK;
+    }
     int64_t blocks = (total + 255) / 256;
     if (blocks > 65536) blocks = 65536;
     hipLaunchKernelGGL(append_step_kernel, dim3((unsigned)blocks), dim3(256), 0, st, static_cast<const char*>(k_new),

@@ -135,6 +135,77 @@ hipError_t launch_quantize_step(int dtype, int D, const void* src, int B, int64_
     return hipGetLastError();
 }
 
+// A small batched append on a cache with the int8 index in one launch: one workgroup places the new key and
+// value rows, codes the key rows, and bumps the lengths once all its threads have used them.
+constexpr int kAppendSmall8Threads = 1024;
+template <int DT>
+__global__ void __launch_bounds__(kAppendSmall8Threads)
+append_step_small8_kernel(const char* __restrict__ ksrc, const char* __restrict__ vsrc, char* __restrict__ kdst,
+                          char* __restrict__ vdst, int64_t head_b, int64_t n_rows, int64_t n_new, int Hkv, int64_t Ncap,
+                          int D, int B, int32_t* len, int8_t* __restrict__ dst, float* __restrict__ scale) {
+    constexpr int EPL = Elem<DT>::kPerLoad;          // 8: the index codes 16-bit caches
+    const int lpr = D / EPL;
+    const int rows_per_pass = kAppendSmall8Threads / lpr;
+    const int rs = threadIdx.x / lpr, c = threadIdx.x % lpr;
+    for (int64_t base = 0; base < n_rows; base += rows_per_pass) {
+        const int64_t r = base + rs;
+        const bool valid = r < n_rows;
+        const int64_t rr = valid ? r : n_rows - 1;
+        const int h = (int)(rr % Hkv);
+        const int64_t bt = rr / Hkv, t = bt % n_new, b = bt / n_new;
+        const int64_t s_o = (rr * D + c * EPL) * Elem<DT>::kBytes;
+        const u32x4 raw = *reinterpret_cast<const u32x4*>(ksrc + s_o);
+        const u32x4 rawv = *reinterpret_cast<const u32x4*>(vsrc + s_o);
+        const int64_t row = (int64_t)len[b] + t;
+        float x[EPL];
+        Elem<DT>::widen(raw, x);
+        float amax = 0.f;
+#pragma unroll
+        for (int e = 0; e < EPL; ++e) amax = fmaxf(amax, fabsf(x[e]));
+        for (int o = 1; o < lpr; o <<= 1) amax = fmaxf(amax, wave_xor(amax, o));
+        const bool live = amax >= kTinyRow;
+        const float inv = live ? 127.0f / amax : 0.f;
+        uint32_t w[EPL / 4];
+#pragma unroll
+        for (int i = 0; i < EPL / 4; ++i) {
+            uint32_t p = 0;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const int code = (int)rintf(x[4 * i + e] * inv);
+                p |= ((uint32_t)code & 0xFFu) << (8 * e);
+            }
+            w[i] = p;
+        }
+        if (valid) {
+            const int64_t d_o = (b * Hkv + h) * head_b + (row * D + c * EPL) * Elem<DT>::kBytes;
+            *reinterpret_cast<u32x4*>(kdst + d_o) = raw;
+            *reinterpret_cast<u32x4*>(vdst + d_o) = rawv;
+            const int64_t drow = (b * Hkv + h) * Ncap + row;
+            uint32_t* d = reinterpret_cast<uint32_t*>(dst + drow * D + c * EPL);
+#pragma unroll
+            for (int i = 0; i < EPL / 4; ++i) d[i] = w[i];
+            if (c == 0) scale[drow] = live ? amax / 127.0f : 0.f;
+        }
+    }
+    __syncthreads();            // every thread has used the lengths it needed
+    for (int b = threadIdx.x; b < B; b += kAppendSmall8Threads) len[b] += (int32_t)n_new;
+}
+
+hipError_t launch_append_step_small8(int dtype, int D, const void* ksrc, const void* vsrc, void* kdst, void* vdst,
+                                     int64_t head_bytes, int B, int64_t n_new, int Hkv, int64_t Ncap, int32_t* len,
+                                     int8_t* codes, float* scale, hipStream_t st) {
+    const int64_t n_rows = (int64_t)B * n_new * Hkv;
+#define TKA_AS8(DT_)                                                                                                     \
+    hipLaunchKernelGGL((append_step_small8_kernel<DT_>), dim3(1), dim3(kAppendSmall8Threads), 0, st,                    \
+                       static_cast<const char*>(ksrc), static_cast<const char*>(vsrc), static_cast<char*>(kdst),        \
+                       static_cast<char*>(vdst), head_bytes, n_rows, n_new, Hkv, Ncap, D, B, len, codes, scale)
+    if (dtype == DT_F16) TKA_AS8(DT_F16);
+    else if (dtype == DT_BF16) TKA_AS8(DT_BF16);
+    else return hipErrorInvalidValue;
+#undef TKA_AS8
+    return hipGetLastError();
+}
+
 bool index8_supported(int dtype, int D, int G) {
     return (dtype == DT_F16 || dtype == DT_BF16) && (D == 64 || D == 128 || D == 256) && G >= 1 && G <= 4;
 }

@@ -229,6 +229,9 @@ hipError_t launch_scan_filter_paged(const Shape& s, const Bufs& b, hipStream_t s
 bool index8_supported(int dtype, int D, int G);
 hipError_t launch_quantize_rows(int dtype, int D, const void* src, int64_t rows_per_head, int64_t src_head_stride_bytes,
                                 int n_heads, int8_t* dst, float* scale, int64_t dst_head_stride_rows, hipStream_t st);
+hipError_t launch_append_step_small8(int dtype, int D, const void* ksrc, const void* vsrc, void* kdst, void* vdst,
+                                     int64_t head_bytes, int B, int64_t n_new, int Hkv, int64_t Ncap, int32_t* len,
+                                     int8_t* codes, float* scale, hipStream_t st);
 hipError_t launch_quantize_step(int dtype, int D, const void* src, int B, int64_t n_new, int Hkv, int64_t Ncap,
                                 const int32_t* len, int8_t* codes, float* scale, hipStream_t st);
 hipError_t launch_scan8_sample(const Shape& s, const Bufs& b, int64_t Nmax, hipStream_t st);

@@ -34,6 +34,8 @@ hipError_t launch_scan_filter_paged(const Shape&, const Bufs&, hipStream_t) { re
 hipError_t launch_quantize_rows(int, int, const void*, int64_t, int64_t, int, int8_t*, float*, int64_t, hipStream_t) {
     return hipErrorUnknown;
 }
+hipError_t launch_append_step_small8(int, int, const void*, const void*, void*, void*, int64_t, int, int64_t, int, int64_t,
+                                     int32_t*, int8_t*, float*, hipStream_t) { return hipErrorUnknown; }
 hipError_t launch_quantize_step(int, int, const void*, int, int64_t, int, int64_t, const int32_t*, int8_t*, float*,
                                 hipStream_t) {
     return hipErrorUnknown;
